@@ -1,0 +1,265 @@
+"""Pins for oracle/pgpe.py: invariants of ask, brute-force ranks, the PGPE estimator from
+its textbook definition on materialised samples, closed-form expectations, Adam closed
+forms, bf16 rounding against a library routine, and convergence on a sphere."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pgpe, philox
+
+
+def _state(P, mu=None, sigma=0.1, **kw):
+    st = pgpe.PGPEState.create(pgpe.PGPEConfig(P=P, sigma_init=sigma, **kw), mu)
+    return st
+
+
+# ---------------------------------------------------------------- ask
+def test_antithetic_pairs():
+    P, pop = 37, 10
+    st = _state(P)                                   # mu = 0: mirror images are exact negatives
+    th = pgpe.ask(st, 123, pop)
+    assert (th[0::2].view(np.uint32) ^ th[1::2].view(np.uint32) == 0x80000000).all()
+    mu = np.random.default_rng(0).standard_normal(P).astype(np.float32)
+    st = _state(P, mu)
+    th = pgpe.ask(st, 123, pop).astype(np.float64)
+    ulp = np.spacing(np.abs(2 * mu).astype(np.float32)).astype(np.float64)
+    assert (np.abs(th[0::2] + th[1::2] - 2.0 * mu) <= ulp).all()
+    # in exact (fp64) arithmetic the pair sums to 2 mu
+    z = philox.pair_noise(123, 1, np.arange(pop // 2), P)
+    plus = mu.astype(np.float64) + st.sigma.astype(np.float64) * z
+    minus = mu.astype(np.float64) - st.sigma.astype(np.float64) * z
+    np.testing.assert_allclose(plus + minus, np.broadcast_to(2.0 * mu, plus.shape), rtol=0, atol=1e-15)
+
+
+def test_zero_sigma_returns_mu_bit_exact():
+    mu = np.random.default_rng(1).standard_normal(50).astype(np.float32)
+    st = _state(50, mu, sigma=0.0)
+    th = pgpe.ask(st, 9, 6)
+    assert (th.view(np.uint32) == mu.view(np.uint32)[None, :]).all()
+
+
+def test_perturbation_is_sigma_times_noise():
+    P = 64
+    st = _state(P, sigma=0.25)
+    th = pgpe.ask(st, 5, 4)
+    z = philox.pair_noise(5, 1, [0, 1], P)
+    np.testing.assert_allclose(th[0::2], 0.25 * z, rtol=1e-6)
+    assert th.dtype == np.float32
+
+
+def test_ask_rejects_odd_population_and_uses_generation():
+    st = _state(8)
+    with pytest.raises(ValueError):
+        pgpe.ask(st, 1, 5)
+    a = pgpe.ask(st, 1, 4)
+    st.t = 2
+    b = pgpe.ask(st, 1, 4)
+    assert not np.array_equal(a, b)
+    rows = pgpe.ask_rows(st, 1, 4, members=[3], cols=[2, 7])
+    assert np.array_equal(rows[0], b[3, [2, 7]])
+
+
+def test_bf16_rounding_against_torch_and_midpoints():
+    # exhaustive: every finite bf16 value v and its successor w; the midpoint rounds to the even one
+    hi = np.arange(0x0000, 0x7F7F, dtype=np.uint32)
+    v = (hi << 16).view(np.float32)
+    mid_bits = (hi << 16) | np.uint32(0x8000)
+    mid = mid_bits.view(np.float32)
+    r = pgpe.round_to_bf16(mid).view(np.uint32) >> 16
+    expect = np.where(hi % 2 == 0, hi, hi + 1)
+    assert (r == expect).all()
+    assert (pgpe.round_to_bf16((mid_bits + 1).view(np.float32)).view(np.uint32) >> 16 == hi + 1).all()
+    assert (pgpe.round_to_bf16((mid_bits - 1).view(np.float32)).view(np.uint32) >> 16 == hi).all()
+    assert (pgpe.round_to_bf16(v).view(np.uint32) == v.view(np.uint32)).all()
+    x = (np.random.default_rng(2).standard_normal(200000) * 10).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(pgpe.round_to_bf16(x), want)
+    assert np.array_equal(pgpe.round_to_bf16(-x), -want)
+
+
+# ---------------------------------------------------------------- centered ranks
+def _brute_rank(f):
+    key = pgpe.orderable_key(f)
+    pop = len(f)
+    r = np.zeros(pop, dtype=np.uint32)
+    for m in range(pop):
+        for j in range(pop):
+            if (int(key[j]), j) < (int(key[m]), m):
+                r[m] += 1
+    return r
+
+
+@pytest.mark.parametrize("pop", [2, 3, 64, 257])
+def test_centered_rank_structure(pop):
+    f = np.random.default_rng(pop).standard_normal(pop).astype(np.float32)
+    rank, c = pgpe.centered_rank(f)
+    assert sorted(rank.tolist()) == list(range(pop))
+    lin = np.linspace(-0.5, 0.5, pop)
+    assert np.abs(np.sort(c).astype(np.float64) - lin).max() <= np.spacing(np.float32(0.5))
+    assert c.dtype == np.float32 and c.min() == -0.5 and c.max() == 0.5
+    assert float(np.sort(c) @ np.ones(pop)) == 0.0 or abs(c.astype(np.float64).sum()) < 1e-6
+    assert (np.sort(c) == -np.sort(c)[::-1]).all()                       # exactly antisymmetric
+    assert (rank == _brute_rank(f)).all()
+    assert rank[np.argmax(f)] == pop - 1 and rank[np.argmin(f)] == 0
+    # invariant under strictly monotone transforms
+    assert (pgpe.centered_rank(np.exp(f / 3) * 7 - 2)[0] == rank).all()
+    assert (pgpe.centered_rank(-f)[0] == pop - 1 - rank).all()
+
+
+def test_centered_rank_ties_and_specials():
+    assert (pgpe.centered_rank(np.full(9, 3.0, np.float32))[0] == np.arange(9)).all()
+    f = np.array([1.0, -0.0, 0.0, 1.0, -np.inf, np.nan, np.inf, np.nan, -5.0, 0.0], np.float32)
+    rank, _ = pgpe.centered_rank(f)
+    #        NaN(5) NaN(7) -inf(4) -5(8) -0(1) 0(2) 0(9) 1(0) 1(3) inf(6)
+    want = np.empty(10, np.uint32)
+    want[[5, 7, 4, 8, 1, 2, 9, 0, 3, 6]] = np.arange(10)
+    assert (rank == want).all()
+    assert (rank == _brute_rank(f)).all()
+    q = np.round(np.random.default_rng(3).standard_normal(200) * 2).astype(np.float32)
+    assert (pgpe.centered_rank(q)[0] == _brute_rank(q)).all()
+    # key map is monotone in the usual float order
+    s = np.sort(np.random.default_rng(4).standard_normal(1000).astype(np.float32))
+    assert (np.diff(pgpe.orderable_key(s).astype(np.int64)) >= 0).all()
+
+
+# ---------------------------------------------------------------- gradient estimator
+def _textbook_pgpe(theta, mu, sigma, f):
+    """Symmetric-sampling PGPE written with eps = theta+ - mu on materialised samples:
+    grad_mu = (1/N) sum_k eps_k (f+ - f-)/2 ; grad_sigma = (1/N) sum_k ((f+ + f-)/2 - b)(eps_k^2 - sigma^2)/sigma."""
+    pop, P = theta.shape
+    N = pop // 2
+    b = sum(f) / pop
+    gm = [0.0] * P
+    gs = [0.0] * P
+    for k in range(N):
+        fp, fm = f[2 * k], f[2 * k + 1]
+        for i in range(P):
+            eps = theta[2 * k, i] - mu[i]
+            gm[i] += eps * (fp - fm) / 2.0 / N
+            gs[i] += ((fp + fm) / 2.0 - b) * (eps * eps - sigma[i] ** 2) / sigma[i] / N
+    return np.array(gm), np.array(gs)
+
+
+def test_gradient_brute_force_tiny():
+    P, pop, seed = 5, 8, 31
+    mu = np.random.default_rng(5).standard_normal(P)
+    sigma = np.abs(np.random.default_rng(6).standard_normal(P)) + 0.1
+    z = philox.pair_noise(seed, 1, np.arange(pop // 2), P)
+    theta = np.empty((pop, P))
+    theta[0::2] = mu + sigma * z
+    theta[1::2] = mu - sigma * z
+    f = np.random.default_rng(7).standard_normal(pop)
+    gm, gs = pgpe.gradients(z, sigma, f)
+    wm, ws = _textbook_pgpe(theta, mu, sigma, f.tolist())
+    np.testing.assert_allclose(gm, wm, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gs, ws, rtol=1e-10, atol=1e-13)
+
+
+def test_gradient_identities():
+    P, N = 7, 6
+    z = philox.pair_noise(8, 2, np.arange(N), P)
+    sigma = np.full(P, 0.3)
+    f = np.random.default_rng(8).standard_normal(2 * N)
+    gm, gs = pgpe.gradients(z, sigma, f)
+    swapped = f.reshape(N, 2)[:, ::-1].reshape(-1)
+    gm2, gs2 = pgpe.gradients(z, sigma, swapped)
+    np.testing.assert_allclose(gm2, -gm, rtol=1e-12)
+    np.testing.assert_allclose(gs2, gs, rtol=1e-12)
+    gm3, gs3 = pgpe.gradients(z, sigma, f + 123.0)
+    np.testing.assert_allclose(gm3, gm, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(gs3, gs, rtol=1e-9, atol=1e-12)
+
+
+def test_gradient_expectations_closed_form():
+    """Raw fitness: linear f = a.x gives E[g_mu] = sigma^2 a, E[g_sigma] = 0;
+    sphere f = -|x|^2 gives E[g_mu] = -2 sigma^2 mu, E[g_sigma] = -2 sigma^3."""
+    P, N = 3, 100000
+    mu = np.array([0.5, -1.0, 2.0])
+    sigma = np.array([0.2, 0.5, 1.0])
+    z = philox.pair_noise(2024, 1, np.arange(N), P)
+    plus, minus = mu + sigma * z, mu - sigma * z
+    a = np.array([1.0, -2.0, 0.5])
+    f = np.empty(2 * N)
+    f[0::2], f[1::2] = plus @ a, minus @ a
+    gm, gs = pgpe.gradients(z, sigma, f)
+    tol = 5.0 / np.sqrt(N)
+    assert np.abs(gm - sigma ** 2 * a).max() < tol * np.abs(sigma ** 2 * a).max() * 3
+    assert np.abs(gs).max() < 1e-9                # (f+ + f-)/2 - b vanishes identically for linear f
+    f[0::2], f[1::2] = -(plus ** 2).sum(1), -(minus ** 2).sum(1)
+    gm, gs = pgpe.gradients(z, sigma, f)
+    assert np.abs(gm - (-2 * sigma ** 2 * mu)).max() < 20 * tol
+    assert np.abs(gs - (-2 * sigma ** 3)).max() < 20 * tol
+    assert (np.sign(gs) == -1).all()
+
+
+# ---------------------------------------------------------------- optimiser
+def test_adam_first_step_and_constant_gradient():
+    g = np.array([1e-3, -2.0, 5e-5, 0.0])
+    x, m, v = pgpe.adam_ascent(np.zeros(4), np.zeros(4), np.zeros(4), g, 0.01, 0.9, 0.999, 1e-8, 1)
+    np.testing.assert_allclose(x, 0.01 * g / (np.abs(g) + 1e-8), rtol=1e-12)
+    x = np.zeros(4)
+    m = np.zeros(4)
+    v = np.zeros(4)
+    for t in range(1, 51):
+        x, m, v = pgpe.adam_ascent(x, m, v, g, 0.01, 0.9, 0.999, 1e-8, t)
+    np.testing.assert_allclose(x[:3], 0.01 * 50 * np.sign(g[:3]), rtol=3e-4)
+    assert x[3] == 0.0
+
+
+def test_adam_matches_torch_optimizer():
+    """torch.optim.Adam minimises; ascent on f equals descent with the negated gradient."""
+    rng = np.random.default_rng(9)
+    x0 = rng.standard_normal(6)
+    p = torch.nn.Parameter(torch.tensor(x0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=0.01, betas=(0.9, 0.999), eps=1e-8)
+    x, m, v = x0.copy(), np.zeros(6), np.zeros(6)
+    for t in range(1, 8):
+        g = rng.standard_normal(6)
+        p.grad = torch.tensor(-g)
+        opt.step()
+        x, m, v = pgpe.adam_ascent(x, m, v, g, 0.01, 0.9, 0.999, 1e-8, t)
+        np.testing.assert_allclose(x, p.detach().numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_tell_equals_materialised_gradient_and_sigma_rules():
+    P, pop, seed = 203, 12, 77
+    for rule in (0, 1):
+        for shaping in (1, 0):
+            mu0 = np.random.default_rng(10).standard_normal(P).astype(np.float32)
+            st = _state(P, mu0, sigma_rule=rule, shaping=shaping)
+            pgpe.ask(st, seed, pop)
+            f = np.random.default_rng(11).standard_normal(pop).astype(np.float32)
+            sg0 = st.sigma.astype(np.float64).copy()
+            g_mu, g_sg = pgpe.tell(st, f, chunk=64, return_grads=True)
+            z = philox.pair_noise(seed, 1, np.arange(pop // 2), P)
+            c = pgpe.centered_rank(f)[1] if shaping else f
+            wm, ws = pgpe.gradients(z, sg0, c)
+            np.testing.assert_allclose(g_mu, wm, rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(g_sg, ws, rtol=1e-12, atol=1e-15)
+            # first Adam step is lr * sign(g) (up to eps)
+            np.testing.assert_allclose(st.mu - mu0, 0.01 * np.sign(wm), rtol=0, atol=2e-4)
+            assert st.t == 2 and st.last is None
+            if rule == 0:
+                step = st.sigma.astype(np.float64) - sg0
+                np.testing.assert_allclose(step, np.clip(0.1 * ws, -0.2 * sg0, 0.2 * sg0), atol=1e-8)
+                assert (np.abs(step) <= 0.2 * sg0 + 1e-8).all() and (st.sigma > 0).all()
+            else:
+                np.testing.assert_allclose(st.sigma.astype(np.float64) - sg0, 0.1 * np.sign(ws), atol=2e-3)
+                assert (st.sigma >= np.float32(1e-8)).all()
+    with pytest.raises(RuntimeError):
+        pgpe.tell(st, f)
+
+
+def test_pgpe_converges_on_sphere():
+    P = 20
+    mu0 = np.full(P, 1.5, np.float32)
+    st = _state(P, mu0, lr_mu=0.05)
+    hist = []
+    for g in range(200):
+        th = pgpe.ask(st, 4242, 32)
+        f = -(th.astype(np.float64) ** 2).sum(1)
+        pgpe.tell(st, f.astype(np.float32))
+        hist.append(-(st.mu.astype(np.float64) ** 2).sum())
+    assert hist[0] < -40 and hist[-1] > -0.5
+    quart = [np.mean(hist[i:i + 50]) for i in range(0, 200, 50)]
+    assert quart[0] < quart[1] < quart[2] <= quart[3] + 0.2
