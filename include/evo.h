@@ -1,0 +1,221 @@
+/*
+ * evo.h -- C ABI of the MI355X (gfx950) neuroevolution hot path: one PGPE generation on
+ * the device for a population in which every member has its own weights.
+ *
+ * The calls follow the component interfaces the EvoJAX paper describes in Section 4
+ * ("Extending EvoJAX"): the algorithm's ask / tell, the global policy's batched
+ * get_actions (here pop_forward) and the vectorised task's reset / step loop (here the
+ * fused rollout).  The paper prints no formulae; the arithmetic is stated next to each
+ * call.
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the CALLER.  The library never
+ *     allocates, frees or retains device memory, never synchronises, and enqueues all work
+ *     on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Pointers without the suffix are host memory, read during the call only.
+ *   - Return value: EVO_OK (0) or a negative evo_err.  evo_last_error() gives a
+ *     thread-local message for the last failure.  No C++ exception crosses the boundary.
+ *   - Notation: pop members, N = pop/2 antithetic pairs, P parameters per member,
+ *     generation index t >= 1.  Member m belongs to pair k = m >> 1 with sign +1 (m even)
+ *     or -1 (m odd).
+ *   - Arrays are dense, row-major, without padding: params[pop][P], obs[pop][B][D],
+ *     out[pop][B][A], fitness[pop].  Device pointers must be 16-byte aligned.
+ */
+#ifndef EVO_GFX950_H
+#define EVO_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EVO_OK = 0,
+  EVO_ERR_ARG = -1,         /* null pointer, odd or out-of-range pop, bad enum value      */
+  EVO_ERR_STATE = -2,       /* tell without a pending ask                                   */
+  EVO_ERR_UNSUPPORTED = -3, /* a shape outside the limits of the kernels                    */
+  EVO_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                   */
+} evo_err;
+
+enum { EVO_F32 = 0, EVO_BF16 = 1 };                                   /* parameter storage  */
+enum { EVO_ACT_NONE = 0, EVO_ACT_TANH = 1, EVO_ACT_RELU = 2 };
+enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1 };
+enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3 };
+enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1 };                        /* Philox stream tags */
+#define EVO_POP_MAX 4096
+#define EVO_MAX_LAYERS 8
+
+/* ------------------------------------------------------------------------------------
+ * PGPE: the neuroevolution algorithm behind ask / tell (Section 4, "Devising New
+ * Algorithms"; PGPE is the algorithm named in Section 5; its gradient estimate is fed to a
+ * deep-learning optimizer as Section 2, "Modern ML Optimizers", describes).
+ *
+ * Noise.  z_k[i] is never stored: both ask and tell regenerate it from the counter-based
+ * generator Philox4x32-10 with counter (i >> 2, k, t, EVO_TAG_NOISE) and key
+ * (seed & 0xffffffff, seed >> 32).  Word x -> u = (2 (x >> 9) + 1) 2^-24; Box-Muller:
+ * words (x0,x1) give z[4j] = r cos(2 pi u1), z[4j+1] = r sin(2 pi u1) with
+ * r = sqrt(-2 ln u0); words (x2,x3) give z[4j+2], z[4j+3] the same way.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t P;                /* parameters per member, >= 1                                  */
+  int32_t pop_max;          /* largest pop that will be asked, even, <= EVO_POP_MAX         */
+  float sigma_init;         /* initial standard deviation of every parameter                */
+  float lr_mu;              /* Adam step size for the centre mu                             */
+  float lr_sigma;           /* step size for sigma                                          */
+  float sigma_max_change;   /* rule 0: |delta sigma| <= sigma_max_change * sigma            */
+  float beta1, beta2, eps;  /* Adam constants                                               */
+  int32_t sigma_rule;       /* 0 = clipped ascent, 1 = Adam on sigma                        */
+  int32_t shaping;          /* 1 = centered ranks, 0 = raw fitness                          */
+} pgpe_config;
+
+typedef struct pgpe_state pgpe_state; /* host handle: config, t, pending (seed, pop), pointers */
+
+/* Bytes of device workspace a state needs (ranks, shaped fitness, pair weights). */
+size_t pgpe_workspace_bytes(const pgpe_config* cfg);
+
+/* Create a host handle around caller-owned device arrays mu, sigma, m, v (fp32[P] each),
+ * aux (fp32[2P]: Adam moments of sigma; required iff sigma_rule == 1, else may be NULL) and
+ * work (pgpe_workspace_bytes(cfg) bytes).  Touches no device memory; t starts at 1.
+ * The arrays must outlive the handle.  Errors: EVO_ERR_ARG. */
+int pgpe_create(pgpe_state** out, const pgpe_config* cfg, float* mu_dev, float* sigma_dev, float* m_dev,
+                float* v_dev, float* aux_dev, void* work_dev);
+int pgpe_destroy(pgpe_state* st);
+
+/* sigma <- sigma_init, m = v = aux = 0, t <- 1, pending ask dropped.  mu is left as the
+ * caller set it (the initial centre is an input). */
+int pgpe_reset(pgpe_state* st, void* stream);
+
+/* Generation index t of the next ask (1 after create/reset; +1 per tell); set it to resume. */
+int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out);
+int pgpe_set_generation(pgpe_state* st, uint32_t t);
+
+/* ask: theta[2k][i] = mu[i] + sigma[i] z_k[i],  theta[2k+1][i] = mu[i] - sigma[i] z_k[i],
+ * written to params_dev[pop][P] as fp32 (EVO_F32) or bfloat16 rounded to nearest even
+ * (EVO_BF16).  Records (seed, pop) as the pending ask.
+ * Errors: EVO_ERR_ARG (null, pop odd / <= 0 / > pop_max, bad dtype), EVO_ERR_HIP. */
+int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params_dev, int32_t dtype, void* stream);
+
+/* tell: consumes fitness_dev[pop] (fp32, larger is better) of the pending ask.
+ *   ranks   r_m = position of (fitness_m, m) in ascending order (ties -> lower index first;
+ *           -0 counts as +0; NaN ranks lowest);  c_m = (2 r_m - (pop-1)) / (2 (pop-1));
+ *           with shaping == 0, c_m = fitness_m.
+ *   pairs   b = mean(c);  w_k = (c[2k] - c[2k+1]) / 2;  u_k = (c[2k] + c[2k+1]) / 2 - b
+ *   grads   g_mu[i] = sigma[i] / N sum_k w_k z_k[i];  g_sigma[i] = sigma[i] / N sum_k u_k (z_k[i]^2 - 1)
+ *   update  Adam ascent on mu (bias-corrected with t, eps outside the square root);
+ *           sigma: rule 0: sigma += clip(lr_sigma g_sigma, -+ sigma_max_change sigma);
+ *                  rule 1: Adam ascent with moments in aux, then sigma = max(sigma, 1e-8);
+ *           t <- t + 1, pending ask cleared.
+ * Results are deterministic (fixed reduction order, no floating-point atomics).
+ * Errors: EVO_ERR_STATE (no pending ask), EVO_ERR_ARG, EVO_ERR_HIP. */
+int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Global policy (Section 2, "Global Policy"; Section 4, "Exploring Novel Policy
+ * Architectures"): one network definition evaluated for all members, parameters and
+ * observations both being data.
+ *
+ * MLP  (kind EVO_POLICY_MLP): n_layers dense layers, dims[0..n_layers] widths, act[l] after
+ *      layer l.  Flat parameters per layer l in order: W_l[in][out] (out contiguous), b_l[out];
+ *      h_{l+1} = act_l(h_l W_l + b_l).  dtype EVO_F32: fp32 arithmetic.  dtype EVO_BF16:
+ *      bfloat16 parameters, activations rounded to bfloat16 at each layer input, products
+ *      accumulated in fp32 on the matrix cores, bias and activation in fp32.
+ * ConvNet (kind EVO_POLICY_CONVNET): dims = {H, c1, c2, n_cls}; input images [B][1][H][H];
+ *      conv3x3 (zero-padded, stride 1) -> ReLU -> maxpool 2x2/2, twice, then a dense layer.
+ *      Flat parameters: W1[3][3][1][c1], b1[c1], W2[3][3][c1][c2], b2[c2],
+ *      Wd[(H/4)(H/4)c2][n_cls], bd[n_cls]; dense input flattened (h, w, c), c fastest.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t kind;
+  int32_t n_layers;                 /* MLP only */
+  int32_t dims[EVO_MAX_LAYERS + 1];
+  int32_t act[EVO_MAX_LAYERS];
+  int32_t dtype;                    /* storage type of params */
+} policy_desc;
+
+/* Number of parameters P the description implies, or a negative evo_err. */
+int64_t policy_param_count(const policy_desc* pd);
+
+/* out_dev[pop][B][A] (fp32) = policy(params_dev[m], obs of member m) for every member.
+ * obs_dev is fp32 [pop][B][D] with obs_member_stride = B*D elements, or one shared batch
+ * [B][D] with obs_member_stride = 0 (every member sees identical observations).
+ * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED (widths / shapes beyond kernel limits), EVO_ERR_HIP. */
+int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_dev, int64_t obs_member_stride,
+                float* out_dev, int32_t pop, int32_t B, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Tasks and the fused roll-out (Section 4, "Experimenting with More Tasks": stateless
+ * reset(keys) / step; Section 3: supervised problems are single-step tasks, control tasks
+ * run a roll-out loop).  fitness_dev[pop] receives, per member:
+ *   CLASSIFY  -mean_b CE(softmax(policy(obs_b)), labels[b])        target_dev = int32 labels[B]
+ *   REGRESS   -mean_{b,a} (policy(obs_b)[a] - target[m][b][a])^2   target_dev = fp32 [pop][B][A]
+ *   SPHERE    -sum_i (theta[m][i] - x_star[i])^2                    target_dev = fp32 x_star[P]; policy may be NULL
+ *   CARTPOLE  mean over n_rollouts of the episode return of the swing-up task below; the whole
+ *             episode (policy weights, environment state) stays on chip for all `steps`.
+ * Cart-pole: state (x, x_d, th, th_d), th from upright; cp = {g, m_cart M, m_pole m, length l,
+ *   friction b, force scale, dt, x_limit}; F = force_scale * a - b x_d (a = policy output);
+ *   D = 4(M+m) - 3 m cos^2 th;  x_dd = [4F + 2 m l th_d^2 sin th - 3 m g sin th cos th] / D;
+ *   th_dd = 3 (g sin th - x_dd cos th) / (2 l);  explicit Euler, derivatives at the old state;
+ *   observation (x, x_d, cos th, sin th, th_d); step reward cos(th') exp(-x'^2) at the new
+ *   state, counted while alive; the episode dies after a step ending with |x'| > x_limit.
+ *   Reset of roll-out r: (x, x_d, th - pi, th_d) = init_scale * the four normals of Philox
+ *   counter (0, r, generation, EVO_TAG_RESET) under reset_seed: the same for every member.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t kind;
+  int32_t n_rollouts;          /* CARTPOLE: roll-outs per member (1..64)                     */
+  int32_t B;                   /* CLASSIFY / REGRESS: samples per member                     */
+  int32_t P;                   /* SPHERE: parameters per member                              */
+  uint64_t reset_seed;         /* CARTPOLE                                                   */
+  uint32_t generation;         /* CARTPOLE: counter word t of the reset stream               */
+  int32_t reserved;
+  const float* obs_dev;        /* CLASSIFY / REGRESS: observations, see pop_forward          */
+  int64_t obs_member_stride;
+  const void* target_dev;      /* labels / targets / x_star, see above                       */
+  float cp[8];                 /* CARTPOLE constants                                         */
+  float init_scale;            /* CARTPOLE: scale of the reset normals                       */
+  int32_t reserved2;
+  void* work_dev;              /* workspace of rollout_workspace_bytes(...) bytes, or NULL if 0 */
+} task_desc;
+
+/* Bytes of device workspace `rollout` needs for this task / policy / pop (may be 0). */
+size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop);
+
+/* Evaluate every member: fitness_dev[pop] as defined above.  `steps` is the episode length
+ * for CARTPOLE and must be 1 for the single-step tasks.
+ * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED, EVO_ERR_HIP. */
+int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
+            float* fitness_dev, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Hooks that expose intermediate results for exact checks.
+ * ------------------------------------------------------------------------------------ */
+/* Raw Philox words of counters (block0 + n, pair, gen, tag), n < nblocks: out_dev[4*nblocks]. */
+int evo_philox_u32(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks, uint32_t tag,
+                   uint32_t* out_dev, void* stream);
+/* The fp32 standard normals ask/tell derive from those words: out_dev[4*nblocks]. */
+int evo_philox_normal(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks, uint32_t tag,
+                      float* out_dev, void* stream);
+/* Ranks and shaped fitness of tell's first stage: rank_dev[pop] (u32), shaped_dev[pop] (fp32). */
+int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t* rank_dev, float* shaped_dev, void* stream);
+/* The gradient estimate tell would use for the pending ask, without updating anything:
+ * gmu_dev[P], gsigma_dev[P].  The pending ask stays pending. */
+int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev, void* stream);
+/* One cart-pole step for n independent (state, action) pairs: state_dev[n][4], action_dev[n]
+ * -> next_dev[n][4], reward_dev[n].  Only td->cp is read. */
+int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,
+                  float* reward_dev, int32_t n, void* stream);
+/* Per-roll-out details of a CARTPOLE rollout: ret_dev[pop][n_rollouts] episode returns and
+ * final_dev[pop][n_rollouts][4] final states (either may be NULL). */
+int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                        int32_t steps, float* ret_dev, float* final_dev, void* stream);
+
+const char* evo_last_error(void);
+/* Library version string, e.g. "evo-gfx950 0.1". */
+const char* evo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVO_GFX950_H */

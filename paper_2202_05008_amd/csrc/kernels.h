@@ -1,0 +1,55 @@
+// Launchers shared between the ABI dispatch (rollout.hip) and the kernel files.
+#pragma once
+#include "common.h"
+
+namespace evo {
+
+struct MlpShape {
+  int n_layers;
+  int dims[EVO_MAX_LAYERS + 1];
+  int act[EVO_MAX_LAYERS];
+  int P;
+  int max_width;
+};
+
+struct ConvShape {
+  int H, c1, c2, n_cls, P;
+};
+
+enum LossKind { LOSS_NONE = -1, LOSS_CE = 0, LOSS_MSE = 1 };
+
+// Samples per workgroup of the fp32 MLP kernel; one partial loss per (member, tile).
+constexpr int kMlpTile = 64;
+
+// fp32 MLP.  loss == LOSS_NONE: writes out[pop][B][A].  Otherwise writes the per-tile loss
+// sums partial[pop][tiles] (tiles = ceil(B / kMlpTile)).
+int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, int64_t obs_stride, int pop, int B,
+                   float* out, int loss, const void* target, float* partial, hipStream_t s);
+
+// bf16-weight MLP on the matrix cores; same contract, one workgroup per member.
+int mlp_bf16_supported(const MlpShape& sh, int B);
+int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs, int64_t obs_stride, int pop, int B,
+                    float* out, int loss, const void* target, float* fitness, hipStream_t s);
+
+// fp32 ConvNet; images shared by all members.  Partials per (member, chunk).
+int convnet_supported(const ConvShape& sh);
+int convnet_chunks(const ConvShape& sh, int pop, int B);
+int launch_convnet_f32(const ConvShape& sh, const float* params, const float* images, int pop, int B, float* out,
+                       const int32_t* labels, float* partial, int chunks, hipStream_t s);
+
+// fitness[m] = scale * sum_j partial[m][j], j in increasing order.
+int launch_finalize(const float* partial, int pop, int n, float scale, float* fitness, hipStream_t s);
+
+// fitness[m] = -sum_i (theta[m][i] - x_star[i])^2
+int launch_sphere(const void* params, int dtype, const float* x_star, int pop, int P, float* fitness,
+                  hipStream_t s);
+
+// Fused cart-pole episodes.
+int cartpole_supported(const MlpShape& sh, int n_rollouts);
+int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_rollouts, int steps, const float* cp,
+                    float init_scale, uint64_t seed, uint32_t gen, float* fitness, float* ret, float* final_state,
+                    hipStream_t s);
+int launch_cartpole_step(const float* cp, const float* state, const float* action, float* next, float* reward,
+                         int n, hipStream_t s);
+
+}  // namespace evo

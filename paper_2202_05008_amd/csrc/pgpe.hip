@@ -1,0 +1,526 @@
+// PGPE ask / tell for gfx950 (Section 4, "Devising New Algorithms": ask generates a
+// population of parameters, tell reports the evaluation results back for the state update;
+// PGPE is the algorithm named in Section 5; Section 2, "Modern ML Optimizers": the gradient
+// estimate is handed to an Adam-class optimizer).
+//
+// Design: the perturbations are never stored.  ask streams mu and sigma once and writes the
+// population; tell regenerates every normal from the counter-based generator, reduces the
+// rank-weighted sums in registers / LDS in a fixed order and applies the optimizer in the
+// same kernel, so mu, sigma and the moments are read and written exactly once.
+#include "common.h"
+#include "philox.h"
+
+#include <math.h>
+#include <new>
+
+struct pgpe_state {
+  pgpe_config cfg;
+  float* mu;
+  float* sigma;
+  float* m;
+  float* v;
+  float* aux;
+  void* work;
+  uint32_t t;
+  bool pending;
+  uint64_t seed;
+  int32_t pop;
+};
+
+namespace evo {
+
+// ---- workspace layout ------------------------------------------------------------------
+struct Workspace {
+  float* shaped;   // [pop_max] utilities c_m
+  uint32_t* rank;  // [pop_max]
+  float* w;        // [pop_max/2] pair weights of the mu gradient
+  float* u;        // [pop_max/2] pair weights of the sigma gradient
+};
+
+static inline size_t ws_bytes(int pop_max) { return (static_cast<size_t>(pop_max) * 3 * 4 + 255) & ~size_t(255); }
+
+static inline Workspace ws_carve(void* base, int pop_max) {
+  Workspace w;
+  w.shaped = static_cast<float*>(base);
+  w.rank = reinterpret_cast<uint32_t*>(w.shaped + pop_max);
+  w.w = reinterpret_cast<float*>(w.rank + pop_max);
+  w.u = w.w + pop_max / 2;
+  return w;
+}
+
+// ---- ask -------------------------------------------------------------------------------
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((b >> 16) | 0x0040u);  // quiet NaN
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return static_cast<uint16_t>(b >> 16);
+}
+
+__device__ __forceinline__ void store_row4(float* row, int col, int P, const float v[4], bool vec) {
+  if (vec) {
+    *reinterpret_cast<float4*>(row + col) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (col + i < P) row[col + i] = v[i];
+  }
+}
+
+__device__ __forceinline__ void store_row4(uint16_t* row, int col, int P, const float v[4], bool vec) {
+  if (vec) {
+    uint2 pk;
+    pk.x = f32_to_bf16_rne(v[0]) | (static_cast<uint32_t>(f32_to_bf16_rne(v[1])) << 16);
+    pk.y = f32_to_bf16_rne(v[2]) | (static_cast<uint32_t>(f32_to_bf16_rne(v[3])) << 16);
+    *reinterpret_cast<uint2*>(row + col) = pk;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (col + i < P) row[col + i] = f32_to_bf16_rne(v[i]);
+  }
+}
+
+// One thread owns four consecutive parameters (one Philox counter) and walks over a chunk
+// of pairs; mu and sigma are loaded once per thread, the two mirrored rows share one draw.
+template <typename OutT>
+__global__ __launch_bounds__(256) void ask_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
+                                                  OutT* __restrict__ params, int P, int nquads, int N,
+                                                  int pairs_per_block, uint32_t gen, uint32_t key0, uint32_t key1) {
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= nquads) return;
+  const int col = q * 4;
+  const bool vec = (P & 3) == 0;  // rows are 16-byte (fp32) / 8-byte (bf16) aligned only then
+  float mu4[4], sg4[4];
+  if (col + 3 < P) {
+    const float4 a = *reinterpret_cast<const float4*>(mu + col);
+    const float4 b = *reinterpret_cast<const float4*>(sigma + col);
+    mu4[0] = a.x, mu4[1] = a.y, mu4[2] = a.z, mu4[3] = a.w;
+    sg4[0] = b.x, sg4[1] = b.y, sg4[2] = b.z, sg4[3] = b.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mu4[i] = col + i < P ? mu[col + i] : 0.f;
+      sg4[i] = col + i < P ? sigma[col + i] : 0.f;
+    }
+  }
+  const int k_begin = blockIdx.y * pairs_per_block;
+  const int k_end = min(N, k_begin + pairs_per_block);
+  for (int k = k_begin; k < k_end; ++k) {
+    float z[4], plus[4], minus[4];
+    philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(k), gen, EVO_TAG_NOISE, key0, key1, z);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float e = sg4[i] * z[i];
+      plus[i] = mu4[i] + e;
+      minus[i] = mu4[i] - e;
+    }
+    OutT* row = params + static_cast<size_t>(2 * k) * P;
+    store_row4(row, col, P, plus, vec);
+    store_row4(row + P, col, P, minus, vec);
+  }
+}
+
+// ---- centered ranks and pair weights ------------------------------------------------------
+// fp32 bits -> u32 that orders like the float: -0 counts as +0, NaN sorts lowest.
+__device__ __forceinline__ uint32_t orderable(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return 0u;
+  if (b == 0x80000000u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int kRankThreads = 1024;
+
+// One workgroup: bitonic sort of 64-bit keys (orderable fitness << 32 | member index) in LDS.
+// Keys are unique, so the permutation is unique and the ranks are exact.  Then the shaped
+// utilities c, their mean b (fp64, fixed tree) and the pair weights w, u.
+__global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int npow2,
+                                                            int shaping, uint32_t* __restrict__ rank_out,
+                                                            float* __restrict__ shaped_out,
+                                                            float* __restrict__ w_out, float* __restrict__ u_out) {
+  __shared__ uint64_t keys[EVO_POP_MAX];
+  __shared__ float cs[EVO_POP_MAX];
+  __shared__ double red[kRankThreads];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < npow2; i += kRankThreads)
+    keys[i] = i < pop ? (static_cast<uint64_t>(orderable(fitness[i])) << 32) | static_cast<uint32_t>(i)
+                      : ~uint64_t(0);
+  __syncthreads();
+  for (int k = 2; k <= npow2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < npow2; i += kRankThreads) {
+        const int p = i ^ j;
+        if (p > i) {
+          const uint64_t a = keys[i], b = keys[p];
+          const bool ascending = (i & k) == 0;
+          if ((a > b) == ascending) {
+            keys[i] = b;
+            keys[p] = a;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  const float denom = static_cast<float>(2 * (pop - 1));
+  for (int p = tid; p < pop; p += kRankThreads) {
+    const uint32_t member = static_cast<uint32_t>(keys[p]);
+    const float c = static_cast<float>(2 * p - (pop - 1)) / denom;  // one correctly rounded divide
+    if (rank_out) rank_out[member] = static_cast<uint32_t>(p);
+    cs[member] = c;
+  }
+  __syncthreads();
+  if (!shaping) {
+    for (int i = tid; i < pop; i += kRankThreads) cs[i] = fitness[i];
+    __syncthreads();
+  }
+  double acc = 0.0;
+  for (int i = tid; i < pop; i += kRankThreads) acc += static_cast<double>(cs[i]);
+  red[tid] = acc;
+  __syncthreads();
+  for (int s = kRankThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  const double b = red[0] / static_cast<double>(pop);
+  for (int i = tid; i < pop; i += kRankThreads)
+    if (shaped_out) shaped_out[i] = cs[i];
+  if (w_out) {
+    for (int k = tid; k < pop / 2; k += kRankThreads) {
+      const double cp = cs[2 * k], cm = cs[2 * k + 1];
+      w_out[k] = static_cast<float>(0.5 * (cp - cm));
+      u_out[k] = static_cast<float>(0.5 * (cp + cm) - b);
+    }
+  }
+}
+
+// ---- tell --------------------------------------------------------------------------------
+struct TellArgs {
+  float* mu;
+  float* sigma;
+  float* m;
+  float* v;
+  float* ms;  // sigma moments (rule 1) or null
+  float* vs;
+  float* gmu_out;  // gradient-only mode
+  float* gsg_out;
+  const float* w;
+  const float* u;
+  int P, nquads, N, KS;
+  uint32_t gen, key0, key1;
+  float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2;
+};
+
+__device__ __forceinline__ float adam_step(float x, float g, float& m, float& v, float lr, const TellArgs& a) {
+  m = a.beta1 * m + (1.0f - a.beta1) * g;
+  v = a.beta2 * v + (1.0f - a.beta2) * g * g;
+  const float m_hat = m * a.bc1;
+  const float v_hat = v * a.bc2;
+  return x + lr * m_hat / (sqrtf(v_hat) + a.eps);
+}
+
+// Thread (q, ks): parameter quad q, pairs ks, ks+KS, ks+2KS, ...  The KS partial sums of a
+// quad are added in increasing ks by one thread, so the result does not depend on timing.
+template <int MODE>  // 0: sigma rule 0, 1: sigma rule 1 (Adam), 2: gradients only
+__global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
+  extern __shared__ float smem[];
+  float* w_s = smem;
+  float* u_s = smem + a.N;
+  float* part = smem + 2 * a.N;  // [KS][QPB][8] when KS > 1
+  const int tid = threadIdx.x;
+  const int QPB = 256 / a.KS;
+  const int ql = tid % QPB;
+  const int ks = tid / QPB;
+  const int q = blockIdx.x * QPB + ql;
+  for (int i = tid; i < a.N; i += 256) {
+    w_s[i] = a.w[i];
+    u_s[i] = a.u[i];
+  }
+  __syncthreads();
+  float A[4] = {0.f, 0.f, 0.f, 0.f}, B[4] = {0.f, 0.f, 0.f, 0.f};
+  if (q < a.nquads) {
+    for (int k = ks; k < a.N; k += a.KS) {
+      float z[4];
+      philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(k), a.gen, EVO_TAG_NOISE, a.key0, a.key1, z);
+      const float wk = w_s[k], uk = u_s[k];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        A[i] = fmaf(wk, z[i], A[i]);
+        B[i] = fmaf(uk, fmaf(z[i], z[i], -1.0f), B[i]);
+      }
+    }
+  }
+  if (a.KS > 1) {
+    float* mine = part + (static_cast<size_t>(ks) * QPB + ql) * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      mine[i] = A[i];
+      mine[4 + i] = B[i];
+    }
+    __syncthreads();
+    if (ks == 0) {
+      for (int s = 1; s < a.KS; ++s) {
+        const float* other = part + (static_cast<size_t>(s) * QPB + ql) * 8;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          A[i] += other[i];
+          B[i] += other[4 + i];
+        }
+      }
+    }
+  }
+  if (ks != 0 || q >= a.nquads) return;
+  const int col = q * 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = col + i;
+    if (c >= a.P) break;
+    const float sg = a.sigma[c];
+    const float g_mu = sg * A[i] * a.inv_n;
+    const float g_sg = sg * B[i] * a.inv_n;
+    if (MODE == 2) {
+      a.gmu_out[c] = g_mu;
+      a.gsg_out[c] = g_sg;
+      continue;
+    }
+    float m = a.m[c], v = a.v[c];
+    a.mu[c] = adam_step(a.mu[c], g_mu, m, v, a.lr_mu, a);
+    a.m[c] = m;
+    a.v[c] = v;
+    if (MODE == 0) {
+      const float lim = a.max_change * sg;
+      a.sigma[c] = sg + fminf(fmaxf(a.lr_sigma * g_sg, -lim), lim);
+    } else {
+      float ms = a.ms[c], vs = a.vs[c];
+      a.sigma[c] = fmaxf(adam_step(sg, g_sg, ms, vs, a.lr_sigma, a), 1e-8f);
+      a.ms[c] = ms;
+      a.vs[c] = vs;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t n, float value) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) p[i] = value;
+}
+
+static int fill(float* p, size_t n, float value, hipStream_t s) {
+  if (n == 0) return EVO_OK;
+  const unsigned blocks = static_cast<unsigned>(n / 256 + 1 < 4096 ? n / 256 + 1 : 4096);
+  hipLaunchKernelGGL(fill_kernel, dim3(blocks), dim3(256), 0, s, p, n, value);
+  return check_launch("fill_kernel");
+}
+
+__global__ __launch_bounds__(256) void philox_words_kernel(uint32_t gen, uint32_t pair, uint32_t block0,
+                                                           uint32_t nblocks, uint32_t tag, uint32_t key0,
+                                                           uint32_t key1, uint32_t* __restrict__ words,
+                                                           float* __restrict__ normals) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= nblocks) return;
+  if (words) {
+    const u32x4 w = philox4x32_10(block0 + i, pair, gen, tag, key0, key1);
+    reinterpret_cast<uint4*>(words)[i] = make_uint4(w.x, w.y, w.z, w.w);
+  }
+  if (normals) {
+    float z[4];
+    philox_normal4(block0 + i, pair, gen, tag, key0, key1, z);
+    reinterpret_cast<float4*>(normals)[i] = make_float4(z[0], z[1], z[2], z[3]);
+  }
+}
+
+static int next_pow2(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+static int launch_rank(const float* fitness, int pop, int shaping, uint32_t* rank, float* shaped, float* w,
+                       float* u, hipStream_t s) {
+  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(kRankThreads), 0, s, fitness, pop, next_pow2(pop), shaping, rank,
+                     shaped, w, u);
+  return check_launch("rank_kernel");
+}
+
+static int check_cfg(const pgpe_config* c) {
+  EVO_REQUIRE(c != nullptr, EVO_ERR_ARG, "pgpe_config is null");
+  EVO_REQUIRE(c->P >= 1, EVO_ERR_ARG, "P must be >= 1 (got %d)", c->P);
+  EVO_REQUIRE(c->pop_max >= 2 && c->pop_max <= EVO_POP_MAX && (c->pop_max & 1) == 0, EVO_ERR_ARG,
+              "pop_max must be even and in [2, %d] (got %d)", EVO_POP_MAX, c->pop_max);
+  EVO_REQUIRE(c->sigma_rule == 0 || c->sigma_rule == 1, EVO_ERR_ARG, "sigma_rule must be 0 or 1");
+  EVO_REQUIRE(c->shaping == 0 || c->shaping == 1, EVO_ERR_ARG, "shaping must be 0 or 1");
+  EVO_REQUIRE(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f, EVO_ERR_ARG,
+              "Adam betas must lie in [0,1)");
+  return EVO_OK;
+}
+
+// Shared by pgpe_tell and the gradient hook.
+static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, hipStream_t s) {
+  const pgpe_config& c = st->cfg;
+  const int pop = st->pop, N = pop / 2, P = c.P;
+  Workspace ws = ws_carve(st->work, c.pop_max);
+  int rc = launch_rank(fitness, pop, c.shaping, ws.rank, ws.shaped, ws.w, ws.u, s);
+  if (rc) return rc;
+  TellArgs a;
+  a.mu = st->mu, a.sigma = st->sigma, a.m = st->m, a.v = st->v;
+  a.ms = st->aux, a.vs = st->aux ? st->aux + P : nullptr;
+  a.gmu_out = gmu, a.gsg_out = gsg;
+  a.w = ws.w, a.u = ws.u;
+  a.P = P, a.nquads = (P + 3) / 4, a.N = N;
+  // split the pair loop KS ways when there are too few parameter quads to fill the chip
+  int KS = 1;
+  while (KS < 256 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < 131072) KS *= 2;
+  a.KS = KS;
+  a.gen = st->t, a.key0 = static_cast<uint32_t>(st->seed), a.key1 = static_cast<uint32_t>(st->seed >> 32);
+  a.inv_n = 1.0f / static_cast<float>(N);
+  a.lr_mu = c.lr_mu, a.lr_sigma = c.lr_sigma, a.max_change = c.sigma_max_change;
+  a.beta1 = c.beta1, a.beta2 = c.beta2, a.eps = c.eps;
+  a.bc1 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta1), static_cast<double>(st->t))));
+  a.bc2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta2), static_cast<double>(st->t))));
+  const int QPB = 256 / KS;
+  const unsigned blocks = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
+  const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + (KS > 1 ? 256 * 8 : 0));
+  if (gmu) {
+    hipLaunchKernelGGL(tell_kernel<2>, dim3(blocks), dim3(256), shmem, s, a);
+  } else if (c.sigma_rule == 0) {
+    hipLaunchKernelGGL(tell_kernel<0>, dim3(blocks), dim3(256), shmem, s, a);
+  } else {
+    hipLaunchKernelGGL(tell_kernel<1>, dim3(blocks), dim3(256), shmem, s, a);
+  }
+  return check_launch("tell_kernel");
+}
+
+}  // namespace evo
+
+using namespace evo;
+
+extern "C" size_t pgpe_workspace_bytes(const pgpe_config* cfg) {
+  if (check_cfg(cfg) != EVO_OK) return 0;
+  return ws_bytes(cfg->pop_max);
+}
+
+extern "C" int pgpe_create(pgpe_state** out, const pgpe_config* cfg, float* mu_dev, float* sigma_dev,
+                           float* m_dev, float* v_dev, float* aux_dev, void* work_dev) {
+  EVO_REQUIRE(out != nullptr, EVO_ERR_ARG, "pgpe_create: out is null");
+  *out = nullptr;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  EVO_REQUIRE(mu_dev && sigma_dev && m_dev && v_dev && work_dev, EVO_ERR_ARG,
+              "pgpe_create: mu, sigma, m, v and work must be non-null");
+  EVO_REQUIRE(cfg->sigma_rule == 0 || aux_dev != nullptr, EVO_ERR_ARG,
+              "pgpe_create: sigma_rule 1 needs aux_dev[2P]");
+  EVO_REQUIRE(aligned16(mu_dev) && aligned16(sigma_dev) && aligned16(m_dev) && aligned16(v_dev) &&
+                  aligned16(work_dev) && aligned16(aux_dev),
+              EVO_ERR_ARG, "pgpe_create: device pointers must be 16-byte aligned");
+  pgpe_state* st = new (std::nothrow) pgpe_state;
+  EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_create: out of host memory");
+  st->cfg = *cfg;
+  st->mu = mu_dev, st->sigma = sigma_dev, st->m = m_dev, st->v = v_dev, st->aux = aux_dev, st->work = work_dev;
+  st->t = 1, st->pending = false, st->seed = 0, st->pop = 0;
+  *out = st;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_destroy(pgpe_state* st) {
+  delete st;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_reset(pgpe_state* st, void* stream) {
+  EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_reset: state is null");
+  hipStream_t s = as_stream(stream);
+  const size_t P = static_cast<size_t>(st->cfg.P);
+  int rc = fill(st->sigma, P, st->cfg.sigma_init, s);
+  if (!rc) rc = fill(st->m, P, 0.f, s);
+  if (!rc) rc = fill(st->v, P, 0.f, s);
+  if (!rc && st->aux) rc = fill(st->aux, 2 * P, 0.f, s);
+  st->t = 1;
+  st->pending = false;
+  return rc;
+}
+
+extern "C" int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out) {
+  EVO_REQUIRE(st && t_out, EVO_ERR_ARG, "pgpe_get_generation: null argument");
+  *t_out = st->t;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_set_generation(pgpe_state* st, uint32_t t) {
+  EVO_REQUIRE(st != nullptr && t >= 1, EVO_ERR_ARG, "pgpe_set_generation: state null or t < 1");
+  st->t = t;
+  st->pending = false;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params_dev, int32_t dtype,
+                        void* stream) {
+  EVO_REQUIRE(st != nullptr && params_dev != nullptr, EVO_ERR_ARG, "pgpe_ask: null argument");
+  EVO_REQUIRE(pop >= 2 && (pop & 1) == 0 && pop <= st->cfg.pop_max, EVO_ERR_ARG,
+              "pgpe_ask: pop must be even and in [2, pop_max=%d] (got %d)", st->cfg.pop_max, pop);
+  EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "pgpe_ask: bad dtype %d", dtype);
+  EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "pgpe_ask: params_dev must be 16-byte aligned");
+  const int P = st->cfg.P, N = pop / 2, nquads = (P + 3) / 4;
+  const int xblocks = (nquads + 255) / 256;
+  long ppb = static_cast<long>(N) * xblocks / 8192;
+  ppb = ppb < 1 ? 1 : (ppb > 16 ? 16 : ppb);
+  const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>((N + ppb - 1) / ppb));
+  hipStream_t s = as_stream(stream);
+  const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+  if (dtype == EVO_F32) {
+    hipLaunchKernelGGL(ask_kernel<float>, grid, dim3(256), 0, s, st->mu, st->sigma,
+                       static_cast<float*>(params_dev), P, nquads, N, static_cast<int>(ppb), st->t, k0, k1);
+  } else {
+    hipLaunchKernelGGL(ask_kernel<uint16_t>, grid, dim3(256), 0, s, st->mu, st->sigma,
+                       static_cast<uint16_t*>(params_dev), P, nquads, N, static_cast<int>(ppb), st->t, k0, k1);
+  }
+  int rc = check_launch("ask_kernel");
+  if (rc) return rc;
+  st->pending = true;
+  st->seed = seed;
+  st->pop = pop;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream) {
+  EVO_REQUIRE(st != nullptr && fitness_dev != nullptr, EVO_ERR_ARG, "pgpe_tell: null argument");
+  EVO_REQUIRE(st->pending, EVO_ERR_STATE, "pgpe_tell: no pending ask");
+  int rc = run_tell(st, fitness_dev, nullptr, nullptr, as_stream(stream));
+  if (rc) return rc;
+  st->pending = false;
+  st->t += 1;
+  return EVO_OK;
+}
+
+extern "C" int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev,
+                                  void* stream) {
+  EVO_REQUIRE(st && fitness_dev && gmu_dev && gsigma_dev, EVO_ERR_ARG, "evo_pgpe_gradients: null argument");
+  EVO_REQUIRE(st->pending, EVO_ERR_STATE, "evo_pgpe_gradients: no pending ask");
+  return run_tell(st, fitness_dev, gmu_dev, gsigma_dev, as_stream(stream));
+}
+
+extern "C" int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t* rank_dev, float* shaped_dev,
+                                 void* stream) {
+  EVO_REQUIRE(fitness_dev && rank_dev && shaped_dev, EVO_ERR_ARG, "evo_centered_rank: null argument");
+  EVO_REQUIRE(pop >= 2 && pop <= EVO_POP_MAX, EVO_ERR_ARG, "evo_centered_rank: pop must be in [2, %d] (got %d)",
+              EVO_POP_MAX, pop);
+  return launch_rank(fitness_dev, pop, 1, rank_dev, shaped_dev, nullptr, nullptr, as_stream(stream));
+}
+
+static int philox_hook(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks, uint32_t tag,
+                       uint32_t* words, float* normals, void* stream) {
+  EVO_REQUIRE(words || normals, EVO_ERR_ARG, "philox hook: output pointer is null");
+  EVO_REQUIRE(aligned16(words) && aligned16(normals), EVO_ERR_ARG, "philox hook: output must be 16-byte aligned");
+  if (nblocks == 0) return EVO_OK;
+  hipLaunchKernelGGL(philox_words_kernel, dim3((nblocks + 255) / 256), dim3(256), 0, as_stream(stream), gen, pair,
+                     block0, nblocks, tag, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), words,
+                     normals);
+  return check_launch("philox_words_kernel");
+}
+
+extern "C" int evo_philox_u32(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks,
+                              uint32_t tag, uint32_t* out_dev, void* stream) {
+  return philox_hook(seed, gen, pair, block0, nblocks, tag, out_dev, nullptr, stream);
+}
+
+extern "C" int evo_philox_normal(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks,
+                                 uint32_t tag, float* out_dev, void* stream) {
+  return philox_hook(seed, gen, pair, block0, nblocks, tag, nullptr, out_dev, stream);
+}

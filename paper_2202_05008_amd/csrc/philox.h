@@ -1,0 +1,60 @@
+// Device-side Philox4x32-10 and the word -> standard normal transform used by ask and tell.
+//
+// Generator: Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3"
+// (SC'11).  The EvoJAX paper only speaks of seeding by keys (Section 4); the counter
+// layout (i >> 2, pair, generation, tag) with key = the two halves of the 64-bit seed lets
+// ask and tell regenerate any perturbation instead of storing it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace evo {
+
+struct u32x4 {
+  uint32_t x, y, z, w;
+};
+
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    // one 32x32 -> 64 bit multiply per lane pair (v_mad_u64_u32 gives both halves)
+    const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+    const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    c1 = static_cast<uint32_t>(p1);
+    c3 = static_cast<uint32_t>(p0);
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return u32x4{c0, c1, c2, c3};
+}
+
+// (2 (x >> 9) + 1) 2^-24: an odd multiple of 2^-24 in (0,1); the conversion is exact.
+__device__ __forceinline__ float unit_open(uint32_t x) {
+  return static_cast<float>(2u * (x >> 9) + 1u) * 5.9604644775390625e-08f;
+}
+
+// Box-Muller on two words: za = r cos(2 pi ub), zb = r sin(2 pi ub), r = sqrt(-2 ln ua).
+// sincospi takes the angle in half turns, and 2 ub is exact, so no rounding enters the
+// angle before the range reduction.
+__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float& za, float& zb) {
+  const float r = sqrtf(-2.0f * logf(unit_open(xa)));
+  float s, c;
+  sincospif(2.0f * unit_open(xb), &s, &c);
+  za = r * c;
+  zb = r * s;
+}
+
+// Four standard normals of counter (j, pair, gen, tag).
+__device__ __forceinline__ void philox_normal4(uint32_t j, uint32_t pair, uint32_t gen, uint32_t tag, uint32_t k0,
+                                               uint32_t k1, float z[4]) {
+  const u32x4 w = philox4x32_10(j, pair, gen, tag, k0, k1);
+  box_muller(w.x, w.y, z[0], z[1]);
+  box_muller(w.z, w.w, z[2], z[3]);
+}
+
+}  // namespace evo

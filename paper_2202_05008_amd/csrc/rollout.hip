@@ -1,0 +1,230 @@
+// ABI dispatch for the global policy (pop_forward) and the task roll-out (rollout):
+// validates the host-side descriptions, then launches the kernels of the matching family.
+// Interfaces after Section 4 of the paper: PolicyNetwork.get_actions on batched task states
+// and population parameters; VectorizedTask reset / step carried over the roll-out steps.
+#include "kernels.h"
+
+using namespace evo;
+
+namespace {
+
+int mlp_shape(const policy_desc* pd, MlpShape* sh) {
+  EVO_REQUIRE(pd->n_layers >= 1 && pd->n_layers <= EVO_MAX_LAYERS, EVO_ERR_ARG,
+              "policy: n_layers must be in [1, %d] (got %d)", EVO_MAX_LAYERS, pd->n_layers);
+  sh->n_layers = pd->n_layers;
+  long P = 0;
+  int mw = 0;
+  for (int i = 0; i <= pd->n_layers; ++i) {
+    EVO_REQUIRE(pd->dims[i] >= 1 && pd->dims[i] <= 65536, EVO_ERR_ARG, "policy: dims[%d] = %d out of range", i,
+                pd->dims[i]);
+    sh->dims[i] = pd->dims[i];
+    mw = pd->dims[i] > mw ? pd->dims[i] : mw;
+  }
+  for (int l = 0; l < pd->n_layers; ++l) {
+    EVO_REQUIRE(pd->act[l] >= EVO_ACT_NONE && pd->act[l] <= EVO_ACT_RELU, EVO_ERR_ARG, "policy: bad activation %d",
+                pd->act[l]);
+    sh->act[l] = pd->act[l];
+    P += static_cast<long>(pd->dims[l]) * pd->dims[l + 1] + pd->dims[l + 1];
+  }
+  EVO_REQUIRE(P < (1l << 30), EVO_ERR_UNSUPPORTED, "policy: too many parameters");
+  sh->P = static_cast<int>(P);
+  sh->max_width = mw;
+  return EVO_OK;
+}
+
+int conv_shape(const policy_desc* pd, ConvShape* sh) {
+  sh->H = pd->dims[0], sh->c1 = pd->dims[1], sh->c2 = pd->dims[2], sh->n_cls = pd->dims[3];
+  EVO_REQUIRE(sh->H >= 4 && sh->c1 >= 1 && sh->c2 >= 1 && sh->n_cls >= 1, EVO_ERR_ARG,
+              "convnet: dims must be {H, c1, c2, n_cls}, all positive");
+  EVO_REQUIRE(sh->H % 4 == 0, EVO_ERR_ARG, "convnet: H must be a multiple of 4 (got %d)", sh->H);
+  const int feat = (sh->H / 4) * (sh->H / 4) * sh->c2;
+  sh->P = 9 * sh->c1 + sh->c1 + 9 * sh->c1 * sh->c2 + sh->c2 + feat * sh->n_cls + sh->n_cls;
+  return EVO_OK;
+}
+
+int check_policy(const policy_desc* pd) {
+  EVO_REQUIRE(pd != nullptr, EVO_ERR_ARG, "policy_desc is null");
+  EVO_REQUIRE(pd->kind == EVO_POLICY_MLP || pd->kind == EVO_POLICY_CONVNET, EVO_ERR_ARG, "policy: bad kind %d",
+              pd->kind);
+  EVO_REQUIRE(pd->dtype == EVO_F32 || pd->dtype == EVO_BF16, EVO_ERR_ARG, "policy: bad dtype %d", pd->dtype);
+  return EVO_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t policy_param_count(const policy_desc* pd) {
+  int rc = check_policy(pd);
+  if (rc) return rc;
+  if (pd->kind == EVO_POLICY_MLP) {
+    MlpShape sh;
+    rc = mlp_shape(pd, &sh);
+    return rc ? rc : sh.P;
+  }
+  ConvShape cs;
+  rc = conv_shape(pd, &cs);
+  return rc ? rc : cs.P;
+}
+
+extern "C" int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_dev,
+                           int64_t obs_member_stride, float* out_dev, int32_t pop, int32_t B, void* stream) {
+  int rc = check_policy(pd);
+  if (rc) return rc;
+  EVO_REQUIRE(params_dev && obs_dev && out_dev, EVO_ERR_ARG, "pop_forward: null device pointer");
+  EVO_REQUIRE(pop >= 1 && pop <= 65535 && B >= 1, EVO_ERR_ARG, "pop_forward: pop must be in [1,65535], B >= 1");
+  EVO_REQUIRE(obs_member_stride >= 0, EVO_ERR_ARG, "pop_forward: negative obs_member_stride");
+  EVO_REQUIRE(aligned16(params_dev) && aligned16(obs_dev) && aligned16(out_dev), EVO_ERR_ARG,
+              "pop_forward: device pointers must be 16-byte aligned");
+  hipStream_t s = as_stream(stream);
+  if (pd->kind == EVO_POLICY_MLP) {
+    MlpShape sh;
+    rc = mlp_shape(pd, &sh);
+    if (rc) return rc;
+    EVO_REQUIRE(obs_member_stride == 0 || obs_member_stride == static_cast<int64_t>(B) * sh.dims[0], EVO_ERR_ARG,
+                "pop_forward: obs_member_stride must be 0 or B*D");
+    if (pd->dtype == EVO_F32)
+      return launch_mlp_f32(sh, static_cast<const float*>(params_dev), obs_dev, obs_member_stride, pop, B, out_dev,
+                            LOSS_NONE, nullptr, nullptr, s);
+    rc = mlp_bf16_supported(sh, B);
+    if (rc) return rc;
+    return launch_mlp_bf16(sh, static_cast<const uint16_t*>(params_dev), obs_dev, obs_member_stride, pop, B, out_dev,
+                           LOSS_NONE, nullptr, nullptr, s);
+  }
+  ConvShape cs;
+  rc = conv_shape(pd, &cs);
+  if (rc) return rc;
+  EVO_REQUIRE(pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED, "convnet: only fp32 parameters are supported");
+  EVO_REQUIRE(obs_member_stride == 0, EVO_ERR_UNSUPPORTED, "convnet: images must be shared (obs_member_stride 0)");
+  rc = convnet_supported(cs);
+  if (rc) return rc;
+  return launch_convnet_f32(cs, static_cast<const float*>(params_dev), obs_dev, pop, B, out_dev, nullptr, nullptr, 0,
+                            s);
+}
+
+namespace {
+
+// Number of partial sums per member that `rollout` keeps in the workspace.
+int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
+  if (td->kind != EVO_TASK_CLASSIFY && td->kind != EVO_TASK_REGRESS) return 0;
+  if (pd->kind == EVO_POLICY_CONVNET) {
+    ConvShape cs;
+    if (conv_shape(pd, &cs)) return 0;
+    return convnet_chunks(cs, pop, td->B);
+  }
+  if (pd->dtype == EVO_BF16) return 0;
+  return (td->B + kMlpTile - 1) / kMlpTile;
+}
+
+int check_task(const task_desc* td) {
+  EVO_REQUIRE(td != nullptr, EVO_ERR_ARG, "task_desc is null");
+  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_SPHERE, EVO_ERR_ARG, "task: bad kind %d",
+              td->kind);
+  return EVO_OK;
+}
+
+}  // namespace
+
+extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop) {
+  if (check_task(td) || pop < 1) return 0;
+  if (td->kind == EVO_TASK_SPHERE || td->kind == EVO_TASK_CARTPOLE) return 0;
+  if (check_policy(pd)) return 0;
+  return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
+}
+
+static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                        int32_t steps, float* fitness_dev, float* ret_dev, float* final_dev, void* stream) {
+  int rc = check_task(td);
+  if (rc) return rc;
+  EVO_REQUIRE(params_dev != nullptr, EVO_ERR_ARG, "rollout: null device pointer");
+  EVO_REQUIRE(pop >= 1 && pop <= 65535, EVO_ERR_ARG, "rollout: pop must be in [1,65535] (got %d)", pop);
+  EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "rollout: params_dev must be 16-byte aligned");
+  hipStream_t s = as_stream(stream);
+  if (td->kind == EVO_TASK_SPHERE) {
+    EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
+    EVO_REQUIRE(steps == 1, EVO_ERR_ARG, "rollout: single-step task needs steps == 1");
+    EVO_REQUIRE(td->P >= 1 && td->target_dev != nullptr, EVO_ERR_ARG, "sphere: needs P >= 1 and x_star");
+    const int dtype = pd ? pd->dtype : EVO_F32;
+    EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "sphere: bad dtype");
+    return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P, fitness_dev, s);
+  }
+  rc = check_policy(pd);
+  if (rc) return rc;
+  if (td->kind == EVO_TASK_CARTPOLE) {
+    EVO_REQUIRE(pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
+                "cartpole: needs an fp32 MLP policy");
+    EVO_REQUIRE(steps >= 1 && steps <= (1 << 24), EVO_ERR_ARG, "cartpole: steps out of range");
+    EVO_REQUIRE(fitness_dev || ret_dev || final_dev, EVO_ERR_ARG, "cartpole: no output requested");
+    MlpShape sh;
+    rc = mlp_shape(pd, &sh);
+    if (rc) return rc;
+    rc = cartpole_supported(sh, td->n_rollouts);
+    if (rc) return rc;
+    return launch_cartpole(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp,
+                           td->init_scale, td->reset_seed, td->generation, fitness_dev, ret_dev, final_dev, s);
+  }
+  // supervised single-step tasks
+  EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
+  EVO_REQUIRE(steps == 1, EVO_ERR_ARG, "rollout: single-step task needs steps == 1");
+  EVO_REQUIRE(td->B >= 1 && td->obs_dev && td->target_dev, EVO_ERR_ARG, "rollout: needs B >= 1, obs and targets");
+  EVO_REQUIRE(td->obs_member_stride >= 0, EVO_ERR_ARG, "rollout: negative obs_member_stride");
+  EVO_REQUIRE(aligned16(td->obs_dev) && aligned16(td->target_dev), EVO_ERR_ARG,
+              "rollout: obs and target must be 16-byte aligned");
+  const int loss = td->kind == EVO_TASK_CLASSIFY ? LOSS_CE : LOSS_MSE;
+  const int n_part = partials_per_member(td, pd, pop);
+  EVO_REQUIRE(n_part == 0 || td->work_dev != nullptr, EVO_ERR_ARG,
+              "rollout: work_dev is null but rollout_workspace_bytes() > 0");
+  float* partial = static_cast<float*>(td->work_dev);
+  if (pd->kind == EVO_POLICY_CONVNET) {
+    EVO_REQUIRE(loss == LOSS_CE, EVO_ERR_UNSUPPORTED, "convnet: only the classification task is supported");
+    EVO_REQUIRE(pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED, "convnet: only fp32 parameters are supported");
+    EVO_REQUIRE(td->obs_member_stride == 0, EVO_ERR_UNSUPPORTED, "convnet: images must be shared");
+    ConvShape cs;
+    rc = conv_shape(pd, &cs);
+    if (rc) return rc;
+    rc = convnet_supported(cs);
+    if (rc) return rc;
+    rc = launch_convnet_f32(cs, static_cast<const float*>(params_dev), td->obs_dev, pop, td->B, nullptr,
+                            static_cast<const int32_t*>(td->target_dev), partial, n_part, s);
+    if (rc) return rc;
+    return launch_finalize(partial, pop, n_part, -1.0f / static_cast<float>(td->B), fitness_dev, s);
+  }
+  MlpShape sh;
+  rc = mlp_shape(pd, &sh);
+  if (rc) return rc;
+  EVO_REQUIRE(td->obs_member_stride == 0 || td->obs_member_stride == static_cast<int64_t>(td->B) * sh.dims[0],
+              EVO_ERR_ARG, "rollout: obs_member_stride must be 0 or B*D");
+  const int A = sh.dims[sh.n_layers];
+  if (pd->dtype == EVO_BF16) {
+    rc = mlp_bf16_supported(sh, td->B);
+    if (rc) return rc;
+    return launch_mlp_bf16(sh, static_cast<const uint16_t*>(params_dev), td->obs_dev, td->obs_member_stride, pop,
+                           td->B, nullptr, loss, td->target_dev, fitness_dev, s);
+  }
+  rc = launch_mlp_f32(sh, static_cast<const float*>(params_dev), td->obs_dev, td->obs_member_stride, pop, td->B,
+                      nullptr, loss, td->target_dev, partial, s);
+  if (rc) return rc;
+  const float scale = loss == LOSS_CE ? -1.0f / static_cast<float>(td->B)
+                                      : -1.0f / (static_cast<float>(td->B) * static_cast<float>(A));
+  return launch_finalize(partial, pop, n_part, scale, fitness_dev, s);
+}
+
+extern "C" int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                       int32_t steps, float* fitness_dev, void* stream) {
+  EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
+  return rollout_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, stream);
+}
+
+extern "C" int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                                   int32_t steps, float* ret_dev, float* final_dev, void* stream) {
+  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_CARTPOLE, EVO_ERR_ARG,
+              "evo_rollout_details: only the cart-pole task has per-roll-out details");
+  EVO_REQUIRE(ret_dev || final_dev, EVO_ERR_ARG, "evo_rollout_details: no output requested");
+  return rollout_impl(td, pd, params_dev, pop, steps, nullptr, ret_dev, final_dev, stream);
+}
+
+extern "C" int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,
+                             float* reward_dev, int32_t n, void* stream) {
+  EVO_REQUIRE(td && state_dev && action_dev && next_dev && reward_dev, EVO_ERR_ARG, "evo_task_step: null argument");
+  EVO_REQUIRE(n >= 0, EVO_ERR_ARG, "evo_task_step: negative n");
+  if (n == 0) return EVO_OK;
+  return launch_cartpole_step(td->cp, state_dev, action_dev, next_dev, reward_dev, n, as_stream(stream));
+}
