@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of one whole PGPE generation (ask -> evaluate -> tell) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+A step is one generation of the named synthetic workload with every input already resident
+in device memory.  Prints ONE JSON line: whole-job throughput in member-evals/s, ms per
+generation, the roofline of the dominant kernel (timed with events on the launch stream) and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_MFMA_F32_TF = 157.3       # dense fp32 matrix
+PEAK_MFMA_BF16_TF = 2500.0
+PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 16 lanes x 2.4 GHz x 2 flop x 2 packed)
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this file (scaled by what the same counters read for a copy kernel of known size); see profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _build_workload(name, seed):
+    import numpy as np
+    import torch
+    import paper_2202_05008_amd as evo
+    from workloads import CONFIGS, generators as gen
+    from workloads import configs as wc
+
+    c = CONFIGS[name]
+    dev = torch.device("cuda:0")
+    mu0 = None if name == "cfg5" else gen.initial_mu(c.data_seed, c.P)
+    pg = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop, sigma_init=c.sigma_init, lr_mu=c.lr_mu,
+                                       lr_sigma=c.lr_sigma, sigma_max_change=c.sigma_max_change), mu0)
+    tdtype = torch.bfloat16 if c.dtype == wc.DT_BF16 else torch.float32
+    params = torch.empty(c.pop, c.P, dtype=tdtype, device=dev)
+    fitness = torch.empty(c.pop, dtype=torch.float32, device=dev)
+    wl = {"cfg": c, "pgpe": pg, "params": params, "fitness": fitness, "evo": evo}
+
+    def with_work(make):
+        td = make(None)
+        n = evo.rollout_workspace_bytes(td, wl.get("pd"), c.pop)
+        work = torch.empty(max(n, 16), dtype=torch.uint8, device=dev)
+        wl.setdefault("keep", []).append(work)
+        return make(work)
+
+    if name in ("cfg1", "cfg2"):
+        if name == "cfg1":
+            wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+            x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
+            batches = [(torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev))]
+            flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.pop * c.B
+            wl["roofline"] = ("alu", flops, PEAK_ALU_F32_TF, "TFLOP/s")
+            wl["desc"] = "cfg1: plumbing classifier, fp32 MLP 16-32-4, pop 64, 512 samples"
+        else:
+            wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_CONVNET, (28,) + tuple(c.dims))
+            batches = []
+            for g in range(4):      # four distinct batches, cycled: a new batch every generation
+                x, y = gen.mnist_shaped_batch(c.data_seed, g + 1, c.B)
+                batches.append((torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)))
+            c1, c2, ncls = c.dims
+            per_img = 2.0 * (9 * c1 * 28 * 28 + 9 * c1 * c2 * 14 * 14 + 7 * 7 * c2 * ncls)
+            wl["roofline"] = ("mfma", per_img * c.pop * c.B, PEAK_MFMA_F32_TF, "TFLOP/s")
+            wl["desc"] = "cfg2: MNIST-shaped synthetic images, per-member fp32 ConvNet P=9098, pop 256, batch 1024"
+        tds = [with_work(lambda w, b=b: evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=b[0], target=b[1], work=w))
+               for b in batches]
+        wl["keep"].append(batches)
+        wl["task"] = lambda t: tds[t % len(tds)]
+        wl["dtype"] = "f32"
+    elif name == "cfg3":
+        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+        wl["task"] = lambda t: evo.make_task_desc(evo.EVO_TASK_CARTPOLE, n_rollouts=c.n_rollouts, reset_seed=seed,
+                                                  generation=t + 1, cp=c.cartpole, init_scale=c.init_scale)
+        flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.evals_per_generation
+        wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
+        wl["desc"] = "cfg3: cart-pole swing-up, fp32 MLP 5-64-64-1, pop 1024 x 16 roll-outs x 1000 steps"
+        wl["dtype"] = "f32"
+    elif name == "cfg4":
+        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts, evo.EVO_BF16)
+        obs, tgt = gen.teacher_regression(c.data_seed, c.pop, c.B, c.dims)
+        od, tg = torch.from_numpy(obs).to(dev), torch.from_numpy(tgt).to(dev)
+        wl["keep"] = [od, tg]
+        td = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=c.B, obs=od, obs_member_stride=c.B * c.dims[0], target=tg)
+        wl["task"] = lambda t: td
+        nbytes = c.pop * (c.P * 2.0 + c.B * c.dims[0] * 4.0 + c.B * c.dims[-1] * 4.0 + 4.0)
+        wl["roofline"] = ("hbm", nbytes, PEAK_HBM_GBS, "GB/s")
+        wl["desc"] = "cfg4: wide bf16 MLP 64-256-256-16, pop 4096, 64 observations per member"
+        wl["dtype"] = "bf16"
+    elif name == "cfg5":
+        wl["pd"] = None
+        xs = torch.from_numpy(gen.sphere_target(c.data_seed, c.P)).to(dev)
+        wl["keep"] = [xs]
+        td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=c.P, target=xs)
+        wl["task"] = lambda t: td
+        wl["roofline"] = ("hbm", c.pop * c.P * 4.0 + 2 * c.P * 4.0, PEAK_HBM_GBS, "GB/s")
+        wl["roofline_stage"] = "ask"
+        wl["desc"] = "cfg5: ask/tell stress on a sphere, P=2^20, pop 1024"
+        wl["dtype"] = "f32"
+    else:
+        raise SystemExit("unknown workload %r" % name)
+    wl.setdefault("roofline_stage", "rollout")
+    return wl
+
+
+def _cpu_baseline(name, seed):
+    """The oracle, as it stands, on a bounded sample of the workload; one BLAS thread."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import pgpe as opgpe, generation as ogen
+    from workloads import CONFIGS, generators as gen
+    from workloads import configs as wc
+
+    c = CONFIGS[name]
+    sample_pop = {"cfg1": 64, "cfg2": 32, "cfg3": 512, "cfg4": 1024, "cfg5": 96}[name]
+    gens = {"cfg1": 600}.get(name, 1)
+    dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
+    if name == "cfg1":
+        x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
+        task = {"kind": "classify", "dims": c.dims, "acts": c.acts, "obs": x, "labels": y}
+        evals = sample_pop * c.B
+    elif name == "cfg2":
+        x, y = gen.mnist_shaped_batch(c.data_seed, 1, c.B)
+        task = {"kind": "classify", "convnet": True, "dims": c.dims, "obs": x, "labels": y}
+        evals = sample_pop * c.B
+    elif name == "cfg3":
+        task = {"kind": "cartpole", "dims": c.dims, "acts": c.acts, "n_rollouts": c.n_rollouts, "steps": c.steps,
+                "cp": c.cartpole, "init_scale": c.init_scale}
+        evals = sample_pop * c.n_rollouts * c.steps
+    elif name == "cfg4":
+        obs, tgt = gen.teacher_regression(c.data_seed, sample_pop, c.B, c.dims)
+        task = {"kind": "regress", "dims": c.dims, "acts": c.acts, "obs": obs, "targets": tgt}
+        evals = sample_pop * c.B
+    else:
+        task = {"kind": "sphere", "x_star": gen.sphere_target(c.data_seed, c.P)}
+        evals = sample_pop
+    mu0 = None if name == "cfg5" else gen.initial_mu(c.data_seed, c.P)
+    st = opgpe.PGPEState.create(opgpe.PGPEConfig(P=c.P, pop_max=sample_pop), mu0)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        for _ in range(gens):
+            ogen.run_generation(st, task, seed, sample_pop, dtype)
+        dt = time.perf_counter() - t0
+    return {"value": evals * gens / dt, "unit": "member-evals/s", "cores": 1, "kind": "oracle",
+            "sample": "%d generation(s) of %s with pop=%d (all other sizes as configured), %.1f s"
+                      % (gens, name, sample_pop, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--seed", type=int, default=20220509)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = _build_workload(args.workload, args.seed)
+    c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20}[args.workload]
+    stage_names = ("ask", "rollout", "tell")
+    events = []
+
+    def generation(t, timed):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if timed else None
+        td = wl["task"](t)
+        if timed:
+            ev[0].record()
+        pg.ask(args.seed, c.pop, wl["params"], c.dtype)
+        if timed:
+            ev[1].record()
+        evo.rollout(td, wl["pd"], wl["params"], c.pop, c.steps, wl["fitness"])
+        if timed:
+            ev[2].record()
+        pg.tell(wl["fitness"])
+        if timed:
+            ev[3].record()
+            events.append(ev)
+
+    for t in range(args.warmup):
+        generation(t, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        generation(args.warmup + t, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in events) / len(events) for i, n in enumerate(stage_names)}
+    assert torch.isfinite(wl["fitness"]).all(), "non-finite fitness after the timed region"
+    ms_per_step = elapsed * 1e3 / steps
+    value = c.evals_per_generation * steps / elapsed
+    bound, work, peak, unit = wl["roofline"]
+    dom_ms = stage_ms[wl["roofline_stage"]]
+    achieved = work / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+    out = {
+        "metric": "member-evals/sec (pop x samples, or env-steps/s, or pop for the sphere) for one whole ES generation",
+        "value": value, "unit": "member-evals/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl["dtype"], "data": "synthetic",
+        "config": {"workload": wl["desc"], "pop": c.pop, "P": c.P, "generation": "ask -> rollout -> tell"},
+        "stage_ms": stage_ms,
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "kernel": wl["roofline_stage"], "kernel_ms": dom_ms},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(args.workload, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,12 @@ class PGPEConfig:
     sigma_rule: int = 0     # 0 clipped ascent, 1 Adam
     shaping: int = 1        # 1 centered ranks, 0 raw fitness
 
+    def __post_init__(self):
+        # the hyper-parameters cross the library boundary as fp32: the oracle computes in fp64 on
+        # those fp32 values (e.g. 1 - beta2 is taken from float32(0.999), not from 0.999)
+        for name in ("sigma_init", "lr_mu", "lr_sigma", "sigma_max_change", "beta1", "beta2", "eps"):
+            setattr(self, name, float(np.float32(getattr(self, name))))
+
 
 @dataclass
 class PGPEState:

@@ -105,7 +105,7 @@ def test_convnet_many_chunks_and_zero_weights(evo):
     fit = _classify(evo, pd, dev(params), dev(img), dev(y), pop, B)
     ref = otasks.classify_fitness(opolicy.convnet_forward(params, img), y)
     assert_scalar_rel(fit, ref, 1e-5, "convnet fitness")
-    assert abs(fit[3] + np.log(10.0)) < 1e-6
+    assert abs(fit[3] + np.log(10.0)) < 1e-5 * np.log(10.0)
 
 
 # ---------------------------------------------------------------- bf16 MLP on the matrix cores
@@ -190,11 +190,11 @@ def test_cartpole_short_horizon(evo, dims, acts, pop, R, steps):
 def test_cartpole_termination_and_zero_policy(evo):
     dims, acts = (5, 16, 16, 1), (1, 1, 1)
     P = mlp_param_count(dims)
-    params = gen.random_params(26, 4, P, 1.5)
+    params = gen.random_params(26, 4, P, 0.5)
     params[3] = 0.0
-    tight = CP[:6] + (0.02, 0.45)
-    fit, ret, fin = _cartpole(evo, dims, acts, params, 16, 60, 31, 1, tight)
-    rfit, rret, rfin, alive = otasks.cartpole_rollout(params, dims, acts, 31, 1, 16, 60, tight, return_details=True)
+    tight = CP[:6] + (0.02, 0.3)       # narrow track: some episodes end early, a short horizon keeps chaos small
+    fit, ret, fin = _cartpole(evo, dims, acts, params, 16, 20, 31, 1, tight)
+    rfit, rret, rfin, alive = otasks.cartpole_rollout(params, dims, acts, 31, 1, 16, 20, tight, return_details=True)
     assert (~alive).any() and alive.any()
     assert_close(ret, rret, 1e-5, "returns with termination")
     assert_close(fin, rfin, 1e-5, "frozen final states")
