@@ -109,9 +109,9 @@ __global__ __launch_bounds__(256) void ask_kernel(const float* __restrict__ mu, 
     philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(k), gen, EVO_TAG_NOISE, key0, key1, z);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float e = sg4[i] * z[i];
-      plus[i] = mu4[i] + e;
-      minus[i] = mu4[i] - e;
+      // both members from the exact product: each is rounded once, so they mirror about mu
+      plus[i] = fmaf(sg4[i], z[i], mu4[i]);
+      minus[i] = fmaf(-sg4[i], z[i], mu4[i]);
     }
     OutT* row = params + static_cast<size_t>(2 * k) * P;
     store_row4(row, col, P, plus, vec);

@@ -128,7 +128,9 @@ def _compare_state(g, o, ill, tol=1e-5):
                                                 (7, 2, 1, 0), (20000, 1024, 0, 1), (131072 + 4, 8, 0, 1)])
 def test_tell_against_oracle(evo, P, pop, rule, shaping):
     mu0 = gen.initial_mu(4, P)
-    g, o = _states(evo, P, pop, mu0, sigma_rule=rule, shaping=shaping)
+    # Adam moves sigma by about lr_sigma per step whatever the gradient's size: keep it well below sigma
+    kw = {"lr_sigma": 0.005} if rule == 1 else {}
+    g, o = _states(evo, P, pop, mu0, sigma_rule=rule, shaping=shaping, **kw)
     params = torch.empty(pop, P, dtype=torch.float32, device="cuda")
     ill = np.zeros(P, dtype=bool)
     for it in range(3):
