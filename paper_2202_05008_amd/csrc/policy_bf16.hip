@@ -156,6 +156,195 @@ __global__ __launch_bounds__(kBf16Threads) void mlp_bf16_kernel(Bf16Args a) {
   }
 }
 
+
+// ---- streaming kernel for three-layer networks D0 -> H -> H -> A with H = 256 -----------------
+// The weights are the dominant HBM stream (2 P bytes per member, used once).  Eight waves per
+// member, wave w owning output columns 32 w .. 32 w + 31 of both hidden layers, so every wave
+// pulls its own slice of W1 and W2 straight from HBM into matrix B-operand registers: all loads
+// of a layer are issued before the layer is computed (they do not depend on activations), which
+// keeps tens of kilobytes in flight per CU without any staging through LDS or barriers for the
+// weights.  A B operand needs eight consecutive k at one column, i.e. eight 2-byte loads with a
+// row stride; 32 lanes of a row group cover 64 contiguous bytes per load.
+typedef float floatx4v __attribute__((ext_vector_type(4)));
+
+template <int KSTEPS, int N>
+__device__ __forceinline__ void load_b_operands(const uint16_t* __restrict__ W, int col, int g, uint4 (&b)[KSTEPS],
+                                                int s_begin) {
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) {
+    const uint16_t* wp = W + static_cast<size_t>(16 * (s_begin + s) + 8 * g) * N + col;
+    uint32_t h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = wp[static_cast<size_t>(i) * N];
+    b[s] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+  }
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
+  Pack8 p;
+  p.v = v;
+  return p.b;
+}
+
+__device__ __forceinline__ float act_f(float v, int act) {
+  if (act == EVO_ACT_TANH) return tanhf(v);
+  if (act == EVO_ACT_RELU) return fmaxf(v, 0.f);
+  return v;
+}
+
+template <int D0, int H, int A>
+__global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
+  static_assert(H == 256 && D0 % 16 == 0 && A == 16, "shape of the streaming kernel");
+  constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
+  __shared__ __attribute__((aligned(16))) uint16_t x_s[64 * LD0];
+  __shared__ __attribute__((aligned(16))) uint16_t h_s[64 * LDH];
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 31, g = lane >> 5;
+  const int member = blockIdx.x, B = a.B;
+  const uint16_t* theta = a.params + static_cast<size_t>(member) * a.sh.P;
+  const uint16_t* W1 = theta;
+  const uint16_t* B1 = W1 + D0 * H;
+  const uint16_t* W2 = B1 + H;
+  const uint16_t* B2 = W2 + H * H;
+  const uint16_t* W3 = B2 + H;
+  const uint16_t* B3 = W3 + H * A;
+  const int col = 32 * wave + c;
+
+  // ---- issue the weight stream of layers 1 and 2 (first half) before anything else ------------
+  uint4 b1[D0 / 16], b2a[8], b2b[8];
+  load_b_operands<D0 / 16, H>(W1, col, g, b1, 0);
+  load_b_operands<8, H>(W2, col, g, b2a, 0);
+  const float bias1 = from_bf16(B1[col]), bias2 = from_bf16(B2[col]);
+
+  // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
+  {
+    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
+    for (int i = tid; i < 64 * D0 / 4; i += 512) {
+      const int r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < B) v = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
+      uint2 pk;
+      pk.x = to_bf16(v.x) | (static_cast<uint32_t>(to_bf16(v.y)) << 16);
+      pk.y = to_bf16(v.z) | (static_cast<uint32_t>(to_bf16(v.w)) << 16);
+      *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
+    }
+  }
+  __syncthreads();
+
+  // ---- layer 1 ----------------------------------------------------------------------------------
+  floatx16 acc[2];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = bias1;
+#pragma unroll
+  for (int s = 0; s < D0 / 16; ++s)
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      const uint4 av = *reinterpret_cast<const uint4*>(x_s + (mt * 32 + c) * LD0 + 16 * s + 8 * g);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(b1[s]), acc[mt], 0, 0, 0);
+    }
+  load_b_operands<8, H>(W2, col, g, b2b, 8);  // second half of layer 2 while layer 1 drains
+  {
+    const int act = a.sh.act[0];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        h_s[row * LDH + col] = to_bf16(act_f(acc[mt][r], act));
+      }
+  }
+  __syncthreads();
+
+  // ---- layer 2 ----------------------------------------------------------------------------------
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = bias2;
+#pragma unroll
+  for (int s = 0; s < 16; ++s)
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (mt * 32 + c) * LDH + 16 * s + 8 * g);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(s < 8 ? b2a[s] : b2b[s - 8]), acc[mt],
+                                                        0, 0, 0);
+    }
+  // layer 3 operands (16x16x32 tiles: lane = 16 g4 + c16, k = 32 s + 8 g4 + i) and the targets
+  const int c16 = lane & 15, g4 = lane >> 4;
+  uint4 b3[8];
+  float tgt[4] = {0.f, 0.f, 0.f, 0.f};
+  float bias3 = 0.f;
+  if (wave < 4) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const uint16_t* wp = W3 + static_cast<size_t>(32 * s + 8 * g4) * A + c16;
+      uint32_t h[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = wp[i * A];
+      b3[s] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+    bias3 = from_bf16(B3[c16]);
+    if (a.loss != LOSS_NONE) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * wave + 4 * g4 + i;
+        if (row < B) tgt[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
+      }
+    }
+  }
+  __syncthreads();  // every wave has read h1: the buffer can take h2
+  {
+    const int act = a.sh.act[1];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        h_s[row * LDH + col] = to_bf16(act_f(acc[mt][r], act));
+      }
+  }
+  __syncthreads();
+
+  // ---- layer 3: four waves, one 16-row tile each ---------------------------------------------------
+  float loss_acc = 0.f;
+  if (wave < 4) {
+    floatx4v o = {bias3, bias3, bias3, bias3};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * s + 8 * g4);
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), as_bf16x8(b3[s]), o, 0, 0, 0);
+    }
+    const int act = a.sh.act[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 16 * wave + 4 * g4 + i;
+      const float v = act_f(o[i], act);
+      if (row < B) {
+        if (a.loss == LOSS_NONE) {
+          a.out[(static_cast<size_t>(member) * B + row) * A + c16] = v;
+        } else {
+          const float d = v - tgt[i];
+          loss_acc = fmaf(d, d, loss_acc);
+        }
+      }
+    }
+  }
+  if (a.loss == LOSS_NONE) return;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
+  if (lane == 0 && wave < 4) red[wave] = loss_acc;
+  __syncthreads();
+  if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
+}
+
+static bool stream_shape(const MlpShape& sh, int B) {
+  return sh.n_layers == 3 && sh.dims[0] == 64 && sh.dims[1] == 256 && sh.dims[2] == 256 && sh.dims[3] == 16 &&
+         B <= 64;
+}
+
 int mlp_bf16_supported(const MlpShape& sh, int B) {
   EVO_REQUIRE(B >= 1 && B <= kMaxRows, EVO_ERR_UNSUPPORTED, "bf16 MLP: B must be in [1, %d] (got %d)", kMaxRows, B);
   EVO_REQUIRE(sh.max_width <= kMaxWidth, EVO_ERR_UNSUPPORTED, "bf16 MLP: widths above %d are not supported (%d)",
@@ -172,6 +361,11 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
   Bf16Args a;
   a.sh = sh, a.params = params, a.obs = obs, a.obs_stride = obs_stride, a.B = B;
   a.out = out, a.target = static_cast<const float*>(target), a.fitness = fitness, a.loss = loss;
+  if (stream_shape(sh, B)) {
+    a.buf_elems = 0;
+    hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16>), dim3(pop), dim3(512), 0, s, a);
+    return check_launch("mlp_bf16_stream_kernel");
+  }
   const int rows = ((B + 31) / 32) * 32;
   a.buf_elems = rows * (sh.max_width + kRowPad);
   const size_t shmem = static_cast<size_t>(a.buf_elems) * 2 * sizeof(uint16_t);
