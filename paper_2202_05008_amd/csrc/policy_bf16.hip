@@ -167,17 +167,21 @@ __global__ __launch_bounds__(kBf16Threads) void mlp_bf16_kernel(Bf16Args a) {
 // row stride; 32 lanes of a row group cover 64 contiguous bytes per load.
 typedef float floatx4v __attribute__((ext_vector_type(4)));
 
-template <int KSTEPS, int N>
-__device__ __forceinline__ void load_b_operands(const uint16_t* __restrict__ W, int col, int g, uint4 (&b)[KSTEPS],
-                                                int s_begin) {
+struct RawB {
+  uint32_t h[8];  // eight 16-bit loads, one per k row
+};
+
+// Issue the eight row loads of one B operand: rows k, k+1, .. k+7 of column `col`.
+__device__ __forceinline__ void issue_b(const uint16_t* __restrict__ W, int k, int col, int N, RawB& r) {
+  const uint16_t* wp = W + static_cast<size_t>(k) * N + col;
 #pragma unroll
-  for (int s = 0; s < KSTEPS; ++s) {
-    const uint16_t* wp = W + static_cast<size_t>(16 * (s_begin + s) + 8 * g) * N + col;
-    uint32_t h[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) h[i] = wp[static_cast<size_t>(i) * N];
-    b[s] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-  }
+  for (int i = 0; i < 8; ++i) r.h[i] = wp[static_cast<size_t>(i) * N];
+}
+
+__device__ __forceinline__ bf16x8 pack_b(const RawB& r) {
+  Pack8 p;
+  p.v = make_uint4(r.h[0] | (r.h[1] << 16), r.h[2] | (r.h[3] << 16), r.h[4] | (r.h[5] << 16), r.h[6] | (r.h[7] << 16));
+  return p.b;
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
@@ -192,16 +196,24 @@ __device__ __forceinline__ float act_f(float v, int act) {
   return v;
 }
 
+// The weight stream of one wave is a fixed sequence of B operands ("units"): D0/16 of layer 1,
+// 16 of layer 2 and (waves 0..3) 8 of layer 3.  kDepth units are kept in flight in a register
+// ring; the loads do not depend on activations, so the stream runs ahead across the layer
+// boundaries and the workgroup barriers.
+constexpr int kDepth = 6;
+
 template <int D0, int H, int A>
-__global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
+__global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   static_assert(H == 256 && D0 % 16 == 0 && A == 16, "shape of the streaming kernel");
   constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
+  constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32, UT = U1 + U2 + U3;
   __shared__ __attribute__((aligned(16))) uint16_t x_s[64 * LD0];
   __shared__ __attribute__((aligned(16))) uint16_t h_s[64 * LDH];
   __shared__ float red[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 31, g = lane >> 5;
+  const int c16 = lane & 15, g4 = lane >> 4;
   const int member = blockIdx.x, B = a.B;
   const uint16_t* theta = a.params + static_cast<size_t>(member) * a.sh.P;
   const uint16_t* W1 = theta;
@@ -211,12 +223,20 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
   const uint16_t* W3 = B2 + H;
   const uint16_t* B3 = W3 + H * A;
   const int col = 32 * wave + c;
+  const bool tail = wave < 4;  // waves that also run layer 3
 
-  // ---- issue the weight stream of layers 1 and 2 (first half) before anything else ------------
-  uint4 b1[D0 / 16], b2a[8], b2b[8];
-  load_b_operands<D0 / 16, H>(W1, col, g, b1, 0);
-  load_b_operands<8, H>(W2, col, g, b2a, 0);
+  RawB ring[kDepth];
+  // unit u -> its loads (compile-time u after unrolling)
+  auto issue = [&](int u) {
+    RawB& r = ring[u % kDepth];
+    if (u < U1) issue_b(W1, 16 * u + 8 * g, col, H, r);
+    else if (u < U1 + U2) issue_b(W2, 16 * (u - U1) + 8 * g, col, H, r);
+    else if (u < UT && tail) issue_b(W3, 32 * (u - U1 - U2) + 8 * g4, c16, A, r);
+  };
+#pragma unroll
+  for (int u = 0; u < kDepth; ++u) issue(u);
   const float bias1 = from_bf16(B1[col]), bias2 = from_bf16(B2[col]);
+  const float bias3 = from_bf16(B3[c16]);
 
   // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
   {
@@ -231,6 +251,15 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
       *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
     }
   }
+  // targets of this lane's four output rows (layer 3 tile of wave < 4)
+  float tgt[4] = {0.f, 0.f, 0.f, 0.f};
+  if (tail && a.loss != LOSS_NONE) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 16 * wave + 4 * g4 + i;
+      if (row < B) tgt[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
+    }
+  }
   __syncthreads();
 
   // ---- layer 1 ----------------------------------------------------------------------------------
@@ -240,13 +269,15 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = bias1;
 #pragma unroll
-  for (int s = 0; s < D0 / 16; ++s)
+  for (int u = 0; u < U1; ++u) {
+    const bf16x8 bv = pack_b(ring[u % kDepth]);
+    issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-      const uint4 av = *reinterpret_cast<const uint4*>(x_s + (mt * 32 + c) * LD0 + 16 * s + 8 * g);
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(b1[s]), acc[mt], 0, 0, 0);
+      const uint4 av = *reinterpret_cast<const uint4*>(x_s + (mt * 32 + c) * LD0 + 16 * u + 8 * g);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
     }
-  load_b_operands<8, H>(W2, col, g, b2b, 8);  // second half of layer 2 while layer 1 drains
+  }
   {
     const int act = a.sh.act[0];
 #pragma unroll
@@ -265,34 +296,13 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = bias2;
 #pragma unroll
-  for (int s = 0; s < 16; ++s)
+  for (int u = U1; u < U1 + U2; ++u) {
+    const bf16x8 bv = pack_b(ring[u % kDepth]);
+    issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (mt * 32 + c) * LDH + 16 * s + 8 * g);
-      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(s < 8 ? b2a[s] : b2b[s - 8]), acc[mt],
-                                                        0, 0, 0);
-    }
-  // layer 3 operands (16x16x32 tiles: lane = 16 g4 + c16, k = 32 s + 8 g4 + i) and the targets
-  const int c16 = lane & 15, g4 = lane >> 4;
-  uint4 b3[8];
-  float tgt[4] = {0.f, 0.f, 0.f, 0.f};
-  float bias3 = 0.f;
-  if (wave < 4) {
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const uint16_t* wp = W3 + static_cast<size_t>(32 * s + 8 * g4) * A + c16;
-      uint32_t h[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) h[i] = wp[i * A];
-      b3[s] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    }
-    bias3 = from_bf16(B3[c16]);
-    if (a.loss != LOSS_NONE) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 16 * wave + 4 * g4 + i;
-        if (row < B) tgt[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
-      }
+      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (mt * 32 + c) * LDH + 16 * (u - U1) + 8 * g);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
     }
   }
   __syncthreads();  // every wave has read h1: the buffer can take h2
@@ -308,14 +318,16 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
   }
   __syncthreads();
 
-  // ---- layer 3: four waves, one 16-row tile each ---------------------------------------------------
+  // ---- layer 3: four waves, one 16-row tile each (16x16x32 tiles: lane = 16 g4 + c16) -------------
   float loss_acc = 0.f;
-  if (wave < 4) {
+  if (tail) {
     floatx4v o = {bias3, bias3, bias3, bias3};
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * s + 8 * g4);
-      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), as_bf16x8(b3[s]), o, 0, 0, 0);
+    for (int u = U1 + U2; u < UT; ++u) {
+      const bf16x8 bv = pack_b(ring[u % kDepth]);
+      issue(u + kDepth);
+      const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * (u - U1 - U2) + 8 * g4);
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
     }
     const int act = a.sh.act[2];
 #pragma unroll
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(512) void mlp_bf16_stream_kernel(Bf16Args a) {
   if (a.loss == LOSS_NONE) return;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
-  if (lane == 0 && wave < 4) red[wave] = loss_acc;
+  if (lane == 0 && tail) red[wave] = loss_acc;
   __syncthreads();
   if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
 }
