@@ -160,28 +160,26 @@ __global__ __launch_bounds__(kBf16Threads) void mlp_bf16_kernel(Bf16Args a) {
 // ---- streaming kernel for three-layer networks D0 -> H -> H -> A with H = 256 -----------------
 // The weights are the dominant HBM stream (2 P bytes per member, used once).  Eight waves per
 // member, wave w owning output columns 32 w .. 32 w + 31 of both hidden layers, so every wave
-// pulls its own slice of W1 and W2 straight from HBM into matrix B-operand registers: all loads
-// of a layer are issued before the layer is computed (they do not depend on activations), which
-// keeps tens of kilobytes in flight per CU without any staging through LDS or barriers for the
-// weights.  A B operand needs eight consecutive k at one column, i.e. eight 2-byte loads with a
-// row stride; 32 lanes of a row group cover 64 contiguous bytes per load.
+// streams its own slice of W1 and W2 (and waves 0..3 all of W3) with 16-byte loads.  A matrix
+// B operand needs eight consecutive k at one column while memory is contiguous along the
+// columns: the slice goes through a small wave-private LDS tile and comes back transposed with
+// ds_read_b64_tr_b16.  Within each group of 16 lanes that instruction returns to lane l,
+// element j, the 16-bit element (l & 3) of the 8 bytes addressed by lane (l >> 2) + 4 j; with
+// lane r pointing at row (r >> 2), columns 4 (r & 3) .. +3 of the tile, lane l receives rows
+// 0..3 of column l: four consecutive k for its own column.
 typedef float floatx4v __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
-struct RawB {
-  uint32_t h[8];  // eight 16-bit loads, one per k row
-};
-
-// Issue the eight row loads of one B operand: rows k, k+1, .. k+7 of column `col`.
-__device__ __forceinline__ void issue_b(const uint16_t* __restrict__ W, int k, int col, int N, RawB& r) {
-  const uint16_t* wp = W + static_cast<size_t>(k) * N + col;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) r.h[i] = wp[static_cast<size_t>(i) * N];
-}
-
-__device__ __forceinline__ bf16x8 pack_b(const RawB& r) {
-  Pack8 p;
-  p.v = make_uint4(r.h[0] | (r.h[1] << 16), r.h[2] | (r.h[3] << 16), r.h[4] | (r.h[5] << 16), r.h[6] | (r.h[7] << 16));
-  return p.b;
+__device__ __forceinline__ bf16x8 join_bf16(short4v lo, short4v hi) {
+  union {
+    short4v h[2];
+    bf16x8 b;
+  } u;
+  u.h[0] = lo;
+  u.h[1] = hi;
+  return u.b;
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
@@ -196,11 +194,14 @@ __device__ __forceinline__ float act_f(float v, int act) {
   return v;
 }
 
-// The weight stream of one wave is a fixed sequence of B operands ("units"): D0/16 of layer 1,
-// 16 of layer 2 and (waves 0..3) 8 of layer 3.  kDepth units are kept in flight in a register
-// ring; the loads do not depend on activations, so the stream runs ahead across the layer
-// boundaries and the workgroup barriers.
-constexpr int kDepth = 6;
+// The weight stream of one wave is a fixed sequence of B operands ("units", 1 KB each): D0/16 of
+// layer 1, 16 of layer 2 and (waves 0..3) 8 of layer 3.  kDepth units are kept in flight in a
+// register ring (one 16-byte load per lane and unit); the loads do not depend on activations, so
+// the stream runs ahead across the layer boundaries and the workgroup barriers.
+constexpr int kDepth = 12;
+constexpr int kStageLd = 40;   // row stride (elements) of the 16 x 32 staging tile of layers 1, 2
+constexpr int kStageLd3 = 24;  // row stride of the 32 x 16 staging tile of layer 3
+constexpr int kStageElems = 32 * kStageLd3;  // 768 elements >= 16 * kStageLd
 
 template <int D0, int H, int A>
 __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
@@ -209,11 +210,13 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32, UT = U1 + U2 + U3;
   __shared__ __attribute__((aligned(16))) uint16_t x_s[64 * LD0];
   __shared__ __attribute__((aligned(16))) uint16_t h_s[64 * LDH];
+  __shared__ __attribute__((aligned(16))) uint16_t stage_s[8 * kStageElems];
   __shared__ float red[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 31, g = lane >> 5;
   const int c16 = lane & 15, g4 = lane >> 4;
+  uint16_t* stage = stage_s + wave * kStageElems;
   const int member = blockIdx.x, B = a.B;
   const uint16_t* theta = a.params + static_cast<size_t>(member) * a.sh.P;
   const uint16_t* W1 = theta;
@@ -225,13 +228,42 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   const int col = 32 * wave + c;
   const bool tail = wave < 4;  // waves that also run layer 3
 
-  RawB ring[kDepth];
-  // unit u -> its loads (compile-time u after unrolling)
+  u32x4v ring[kDepth];
+  // unit u -> its 16-byte load (compile-time u after unrolling).  Layers 1, 2: tile of 16 rows x
+  // 32 columns, lane = (row lane >> 2, 8 columns from 8 (lane & 3)); layer 3: 32 rows x 16 columns,
+  // lane = (row lane >> 1, 8 columns from 8 (lane & 1)).
+  const uint16_t* p12 = theta + static_cast<size_t>(lane >> 2) * H + 32 * wave + 8 * (lane & 3);
+  const uint16_t* p3 = W3 + (lane >> 1) * A + 8 * (lane & 1);
   auto issue = [&](int u) {
-    RawB& r = ring[u % kDepth];
-    if (u < U1) issue_b(W1, 16 * u + 8 * g, col, H, r);
-    else if (u < U1 + U2) issue_b(W2, 16 * (u - U1) + 8 * g, col, H, r);
-    else if (u < UT && tail) issue_b(W3, 32 * (u - U1 - U2) + 8 * g4, c16, A, r);
+    u32x4v& r = ring[u % kDepth];
+    if (u < U1) r = *reinterpret_cast<const u32x4v*>(p12 + static_cast<size_t>(16 * u) * H);
+    else if (u < U1 + U2) r = *reinterpret_cast<const u32x4v*>(p12 + (W2 - theta) + static_cast<size_t>(16 * (u - U1)) * H);
+    else if (u < UT && tail) r = *reinterpret_cast<const u32x4v*>(p3 + 32 * (u - U1 - U2) * A);
+  };
+  // registers of unit u -> staging tile -> transposed B operand of this lane
+  auto operand12 = [&](int u) -> bf16x8 {
+    *reinterpret_cast<u32x4v*>(stage + (lane >> 2) * kStageLd + 8 * (lane & 3)) = ring[u % kDepth];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t* q = stage + (8 * g + (c16 >> 2)) * kStageLd + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return join_bf16(lo, hi);
+  };
+  auto operand3 = [&](int u) -> bf16x8 {
+    *reinterpret_cast<u32x4v*>(stage + (lane >> 1) * kStageLd3 + 8 * (lane & 1)) = ring[u % kDepth];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t* q = stage + (8 * g4 + (c16 >> 2)) * kStageLd3 + 4 * (lane & 3);
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd3));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return join_bf16(lo, hi);
   };
 #pragma unroll
   for (int u = 0; u < kDepth; ++u) issue(u);
@@ -270,7 +302,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     for (int r = 0; r < 16; ++r) acc[mt][r] = bias1;
 #pragma unroll
   for (int u = 0; u < U1; ++u) {
-    const bf16x8 bv = pack_b(ring[u % kDepth]);
+    const bf16x8 bv = operand12(u);
     issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
@@ -297,7 +329,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     for (int r = 0; r < 16; ++r) acc[mt][r] = bias2;
 #pragma unroll
   for (int u = U1; u < U1 + U2; ++u) {
-    const bf16x8 bv = pack_b(ring[u % kDepth]);
+    const bf16x8 bv = operand12(u);
     issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
@@ -324,7 +356,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     floatx4v o = {bias3, bias3, bias3, bias3};
 #pragma unroll
     for (int u = U1 + U2; u < UT; ++u) {
-      const bf16x8 bv = pack_b(ring[u % kDepth]);
+      const bf16x8 bv = operand3(u);
       issue(u + kDepth);
       const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * (u - U1 - U2) + 8 * g4);
       o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
