@@ -9,6 +9,7 @@
 // same kernel, so mu, sigma and the moments are read and written exactly once.
 #include "common.h"
 #include "philox.h"
+#include "bf16.h"
 
 #include <math.h>
 #include <new>
@@ -49,13 +50,6 @@ static inline Workspace ws_carve(void* base, int pop_max) {
 }
 
 // ---- ask -------------------------------------------------------------------------------
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t b = __float_as_uint(f);
-  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((b >> 16) | 0x0040u);  // quiet NaN
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return static_cast<uint16_t>(b >> 16);
-}
-
 __device__ __forceinline__ void store_row4(float* row, int col, int P, const float v[4], bool vec) {
   if (vec) {
     *reinterpret_cast<float4*>(row + col) = make_float4(v[0], v[1], v[2], v[3]);
@@ -69,13 +63,13 @@ __device__ __forceinline__ void store_row4(float* row, int col, int P, const flo
 __device__ __forceinline__ void store_row4(uint16_t* row, int col, int P, const float v[4], bool vec) {
   if (vec) {
     uint2 pk;
-    pk.x = f32_to_bf16_rne(v[0]) | (static_cast<uint32_t>(f32_to_bf16_rne(v[1])) << 16);
-    pk.y = f32_to_bf16_rne(v[2]) | (static_cast<uint32_t>(f32_to_bf16_rne(v[3])) << 16);
+    pk.x = pack_bf16x2(v[0], v[1]);
+    pk.y = pack_bf16x2(v[2], v[3]);
     *reinterpret_cast<uint2*>(row + col) = pk;
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      if (col + i < P) row[col + i] = f32_to_bf16_rne(v[i]);
+      if (col + i < P) row[col + i] = to_bf16(v[i]);
   }
 }
 

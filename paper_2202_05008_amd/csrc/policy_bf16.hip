@@ -12,6 +12,7 @@
 // Register layouts of v_mfma_f32_32x32x16_bf16 (lane = 32 g + c):
 //   A[row c][k = 8 g + i], B[k = 8 g + i][col c], i = 0..7 (eight bf16 per lane)
 //   D[row 8 b + 4 g + i][col c] in register 4 b + i, b = 0..3, i = 0..3
+#include "bf16.h"
 #include "kernels.h"
 
 namespace evo {
@@ -37,15 +38,6 @@ struct Bf16Args {
   int loss;
   int buf_elems;  // bf16 elements per activation buffer
 };
-
-__device__ __forceinline__ uint16_t to_bf16(float f) {
-  uint32_t b = __float_as_uint(f);
-  if ((b & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((b >> 16) | 0x0040u);
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return static_cast<uint16_t>(b >> 16);
-}
-
-__device__ __forceinline__ float from_bf16(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
 
 union Pack8 {
   uint16_t h[8];
@@ -205,7 +197,7 @@ constexpr int kStageElems = 32 * kStageLd3;  // 768 elements >= 16 * kStageLd
 
 template <int D0, int H, int A>
 __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
-  static_assert(H == 256 && D0 % 16 == 0 && A == 16, "shape of the streaming kernel");
+  static_assert(H == 256 && D0 % 32 == 0 && A == 16, "shape of the streaming kernel");
   constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
   constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32, UT = U1 + U2 + U3;
   __shared__ __attribute__((aligned(16))) uint16_t x_s[64 * LD0];
@@ -265,23 +257,31 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     __builtin_amdgcn_wave_barrier();
     return join_bf16(lo, hi);
   };
+  // the observation loads go first so that waiting for them does not drain the weight stream
+  constexpr int kObsPieces = 64 * D0 / 4 / 512;
+  float4 ov[kObsPieces];
+  {
+    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
+#pragma unroll
+    for (int j = 0; j < kObsPieces; ++j) {
+      const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      ov[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < B) ov[j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
+    }
+  }
 #pragma unroll
   for (int u = 0; u < kDepth; ++u) issue(u);
   const float bias1 = from_bf16(B1[col]), bias2 = from_bf16(B2[col]);
   const float bias3 = from_bf16(B3[c16]);
 
   // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
-  {
-    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
-    for (int i = tid; i < 64 * D0 / 4; i += 512) {
-      const int r = i / (D0 / 4), d4 = i - r * (D0 / 4);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < B) v = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
-      uint2 pk;
-      pk.x = to_bf16(v.x) | (static_cast<uint32_t>(to_bf16(v.y)) << 16);
-      pk.y = to_bf16(v.z) | (static_cast<uint32_t>(to_bf16(v.w)) << 16);
-      *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
-    }
+#pragma unroll
+  for (int j = 0; j < kObsPieces; ++j) {
+    const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+    uint2 pk;
+    pk.x = pack_bf16x2(ov[j].x, ov[j].y);
+    pk.y = pack_bf16x2(ov[j].z, ov[j].w);
+    *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
   }
   // targets of this lane's four output rows (layer 3 tile of wave < 4)
   float tgt[4] = {0.f, 0.f, 0.f, 0.f};
