@@ -52,7 +52,9 @@ static inline Workspace ws_carve(void* base, int pop_max) {
 // ---- ask -------------------------------------------------------------------------------
 __device__ __forceinline__ void store_row4(float* row, int col, int P, const float v[4], bool vec) {
   if (vec) {
-    *reinterpret_cast<float4*>(row + col) = make_float4(v[0], v[1], v[2], v[3]);
+    // streaming store: the population is written once and read by a later kernel
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(row + col));
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -65,7 +67,8 @@ __device__ __forceinline__ void store_row4(uint16_t* row, int col, int P, const 
     uint2 pk;
     pk.x = pack_bf16x2(v[0], v[1]);
     pk.y = pack_bf16x2(v[2], v[3]);
-    *reinterpret_cast<uint2*>(row + col) = pk;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(u32x2{pk.x, pk.y}, reinterpret_cast<u32x2*>(row + col));
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
