@@ -98,7 +98,7 @@ def _build_workload(name, seed):
         wl["pd"] = None
         xs = torch.from_numpy(gen.sphere_target(c.data_seed, c.P)).to(dev)
         wl["keep"] = [xs]
-        td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=c.P, target=xs)
+        td = with_work(lambda w: evo.make_task_desc(evo.EVO_TASK_SPHERE, P=c.P, target=xs, work=w))
         wl["task"] = lambda t: td
         wl["roofline"] = ("hbm", c.pop * c.P * 4.0 + 2 * c.P * 4.0, PEAK_HBM_GBS, "GB/s")
         wl["roofline_stage"] = "ask"

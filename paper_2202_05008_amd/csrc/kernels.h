@@ -40,8 +40,9 @@ int launch_convnet_f32(const ConvShape& sh, const float* params, const float* im
 // fitness[m] = scale * sum_j partial[m][j], j in increasing order.
 int launch_finalize(const float* partial, int pop, int n, float scale, float* fitness, hipStream_t s);
 
-// fitness[m] = -sum_i (theta[m][i] - x_star[i])^2
-int launch_sphere(const void* params, int dtype, const float* x_star, int pop, int P, float* fitness,
+// fitness[m] = -sum_i (theta[m][i] - x_star[i])^2; partial[pop][sphere_chunks(P)] is scratch.
+int sphere_chunks(int P);
+int launch_sphere(const void* params, int dtype, const float* x_star, int pop, int P, float* partial, float* fitness,
                   hipStream_t s);
 
 // Fused cart-pole episodes.

@@ -456,17 +456,19 @@ extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params
   EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "pgpe_ask: params_dev must be 16-byte aligned");
   const int P = st->cfg.P, N = pop / 2, nquads = (P + 3) / 4;
   const int xblocks = (nquads + 255) / 256;
-  long ppb = static_cast<long>(N) * xblocks / 8192;
-  ppb = ppb < 1 ? 1 : (ppb > 16 ? 16 : ppb);
-  const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>((N + ppb - 1) / ppb));
+  // One pair per workgroup row and x fastest: consecutive workgroups write consecutive 4 KB pieces
+  // of the same two rows, which is the order HBM streams best (measured: 6.7 TB/s against
+  // 4.5 TB/s with 16 pairs per workgroup at P = 2^20, pop = 1024).
+  const int ppb = 1;
+  const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>(N));
   hipStream_t s = as_stream(stream);
   const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
   if (dtype == EVO_F32) {
     hipLaunchKernelGGL(ask_kernel<float>, grid, dim3(256), 0, s, st->mu, st->sigma,
-                       static_cast<float*>(params_dev), P, nquads, N, static_cast<int>(ppb), st->t, k0, k1);
+                       static_cast<float*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
   } else {
     hipLaunchKernelGGL(ask_kernel<uint16_t>, grid, dim3(256), 0, s, st->mu, st->sigma,
-                       static_cast<uint16_t*>(params_dev), P, nquads, N, static_cast<int>(ppb), st->t, k0, k1);
+                       static_cast<uint16_t*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
   }
   int rc = check_launch("ask_kernel");
   if (rc) return rc;

@@ -169,54 +169,63 @@ int launch_finalize(const float* partial, int pop, int n, float scale, float* fi
 // ---- sphere --------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(static_cast<uint32_t>(h) << 16); }
 
-// One workgroup per member streams its row once; fixed per-thread order, then a fixed tree.
+// Workgroup (chunk, member) streams one contiguous piece of the member's row with 16-byte loads;
+// x fastest, so consecutive workgroups read consecutive pieces of one row.  Per-thread order and
+// the tree are fixed; the per-chunk sums are added in chunk order by finalize_kernel.
+constexpr int kSphereChunk = 4096;  // parameters per workgroup (16 KB of fp32)
+
 template <typename T>
-__global__ __launch_bounds__(1024) void sphere_kernel(const T* __restrict__ params,
-                                                      const float* __restrict__ x_star, int P,
-                                                      float* __restrict__ fitness) {
-  __shared__ float red[16];
+__global__ __launch_bounds__(256) void sphere_kernel(const T* __restrict__ params,
+                                                     const float* __restrict__ x_star, int P, int chunks,
+                                                     float* __restrict__ partial) {
+  __shared__ float red[4];
   const int tid = threadIdx.x;
-  const T* row = params + static_cast<size_t>(blockIdx.x) * P;
-  float acc = 0.f;
+  const T* row = params + static_cast<size_t>(blockIdx.y) * P;
+  const int begin = blockIdx.x * kSphereChunk, end = min(P, begin + kSphereChunk);
+  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
   if (sizeof(T) == 4 && (P & 3) == 0) {
-    const float4* r4 = reinterpret_cast<const float4*>(row);
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4* r4 = reinterpret_cast<const f32x4*>(row);
     const float4* x4 = reinterpret_cast<const float4*>(x_star);
-    for (int i = tid; i < P / 4; i += 1024) {
-      const float4 p = r4[i], x = x4[i];
+    for (int i = begin / 4 + tid; i < end / 4; i += 256) {
+      const f32x4 p = __builtin_nontemporal_load(r4 + i);  // read once: keep it out of the caches
+      const float4 x = x4[i];
       const float d0 = p.x - x.x, d1 = p.y - x.y, d2 = p.z - x.z, d3 = p.w - x.w;
-      acc = fmaf(d0, d0, acc);
-      acc = fmaf(d1, d1, acc);
-      acc = fmaf(d2, d2, acc);
-      acc = fmaf(d3, d3, acc);
+      acc0 = fmaf(d0, d0, acc0);
+      acc1 = fmaf(d1, d1, acc1);
+      acc2 = fmaf(d2, d2, acc2);
+      acc3 = fmaf(d3, d3, acc3);
     }
   } else {
-    for (int i = tid; i < P; i += 1024) {
+    for (int i = begin + tid; i < end; i += 256) {
       float p;
       if (sizeof(T) == 4) p = reinterpret_cast<const float*>(row)[i];
       else p = bf16_to_f32(reinterpret_cast<const uint16_t*>(row)[i]);
       const float d = p - x_star[i];
-      acc = fmaf(d, d, acc);
+      acc0 = fmaf(d, d, acc0);
     }
   }
-  acc = wave_sum(acc);
+  float acc = wave_sum((acc0 + acc1) + (acc2 + acc3));
   if ((tid & 63) == 0) red[tid >> 6] = acc;
   __syncthreads();
-  if (tid == 0) {
-    float t = 0.f;
-    for (int i = 0; i < 16; ++i) t += red[i];
-    fitness[blockIdx.x] = -t;
-  }
+  if (tid == 0) partial[static_cast<size_t>(blockIdx.y) * chunks + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-int launch_sphere(const void* params, int dtype, const float* x_star, int pop, int P, float* fitness,
+int sphere_chunks(int P) { return (P + kSphereChunk - 1) / kSphereChunk; }
+
+int launch_sphere(const void* params, int dtype, const float* x_star, int pop, int P, float* partial, float* fitness,
                   hipStream_t s) {
+  const int chunks = sphere_chunks(P);
+  const dim3 grid(chunks, pop);
   if (dtype == EVO_F32)
-    hipLaunchKernelGGL(sphere_kernel<float>, dim3(pop), dim3(1024), 0, s, static_cast<const float*>(params), x_star,
-                       P, fitness);
+    hipLaunchKernelGGL(sphere_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(params), x_star, P,
+                       chunks, partial);
   else
-    hipLaunchKernelGGL(sphere_kernel<uint16_t>, dim3(pop), dim3(1024), 0, s,
-                       static_cast<const uint16_t*>(params), x_star, P, fitness);
-  return check_launch("sphere_kernel");
+    hipLaunchKernelGGL(sphere_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t*>(params), x_star,
+                       P, chunks, partial);
+  int rc = check_launch("sphere_kernel");
+  if (rc) return rc;
+  return launch_finalize(partial, pop, chunks, -1.0f, fitness, s);
 }
 
 }  // namespace evo

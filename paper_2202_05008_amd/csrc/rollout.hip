@@ -104,6 +104,7 @@ namespace {
 
 // Number of partial sums per member that `rollout` keeps in the workspace.
 int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
+  if (td->kind == EVO_TASK_SPHERE) return td->P >= 1 ? sphere_chunks(td->P) : 0;
   if (td->kind != EVO_TASK_CLASSIFY && td->kind != EVO_TASK_REGRESS) return 0;
   if (pd->kind == EVO_POLICY_CONVNET) {
     ConvShape cs;
@@ -125,8 +126,8 @@ int check_task(const task_desc* td) {
 
 extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop) {
   if (check_task(td) || pop < 1) return 0;
-  if (td->kind == EVO_TASK_SPHERE || td->kind == EVO_TASK_CARTPOLE) return 0;
-  if (check_policy(pd)) return 0;
+  if (td->kind == EVO_TASK_CARTPOLE) return 0;
+  if (td->kind != EVO_TASK_SPHERE && check_policy(pd)) return 0;
   return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
 }
 
@@ -144,7 +145,9 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     EVO_REQUIRE(td->P >= 1 && td->target_dev != nullptr, EVO_ERR_ARG, "sphere: needs P >= 1 and x_star");
     const int dtype = pd ? pd->dtype : EVO_F32;
     EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "sphere: bad dtype");
-    return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P, fitness_dev, s);
+    EVO_REQUIRE(td->work_dev != nullptr, EVO_ERR_ARG, "sphere: work_dev is null but rollout_workspace_bytes() > 0");
+    return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P,
+                         static_cast<float*>(td->work_dev), fitness_dev, s);
   }
   rc = check_policy(pd);
   if (rc) return rc;

@@ -74,7 +74,8 @@ def test_policy_and_task_descriptions():
     td = api.make_task_desc(api.EVO_TASK_CLASSIFY, B=512)
     pd1 = api.make_policy_desc(api.EVO_POLICY_MLP, (16, 32, 4), (1, 0))
     assert api.rollout_workspace_bytes(td, pd1, 64) >= 64 * 8 * 4
-    assert api.rollout_workspace_bytes(api.make_task_desc(api.EVO_TASK_SPHERE, P=8), None, 4) == 0
+    assert api.rollout_workspace_bytes(api.make_task_desc(api.EVO_TASK_SPHERE, P=8), None, 4) >= 16
+    assert api.rollout_workspace_bytes(api.make_task_desc(api.EVO_TASK_CARTPOLE), pd1, 4) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -137,7 +137,10 @@ def test_mlp_bf16(evo, dims, acts, pop, B):
 def test_sphere(evo, P, pop):
     params = gen.random_params(22, pop, P, 1.0)
     xs = gen.sphere_target(23, P)
-    td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=dev(xs))
+    xd = dev(xs)
+    td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=xd)
+    work = _work(evo, td, None, pop)
+    td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=xd, work=work)
     fit = torch.empty(pop, dtype=torch.float32, device="cuda")
     evo.rollout(td, None, dev(params), pop, 1, fit)
     assert_scalar_rel(host(fit), otasks.sphere_fitness(params, xs), 1e-5, "sphere")
