@@ -2,16 +2,21 @@
 // roll-out loop; Section 4, "Experimenting with More Tasks": reset(keys) / step with the
 // state carried over the steps; all members start from identical observations).
 //
-// One wavefront owns one member: its policy weights sit in registers as matrix-core
-// B operands for the whole episode, the 16 roll-outs of the member are the 16 rows of
-// v_mfma_f32_16x16x4_f32, and the environment state of roll-out r lives in the lanes with
-// lane % 16 == r.  Nothing but the final return touches HBM.
+// One workgroup owns one member; wave w owns hidden neurons 16 w .. 16 w + 15 of both hidden
+// layers, whose weights sit in its registers as matrix-core B operands for the whole episode.
+// The 16 roll-outs of the member are the 16 rows of v_mfma_f32_16x16x4_f32.  Every wave carries
+// the environment state of roll-out r in its lanes with lane % 16 == r and advances it itself
+// (a few dozen instructions), so observations never travel between waves; only the hidden
+// activations (LDS transpose between the layers) and the four partial sums of the output
+// layer do.  Two workgroup barriers per step; nothing but the final return touches HBM.
+// Several members share a SIMD (one wave each), which hides the latency of the serial
+// per-step chain.
 //
 // Register layouts of v_mfma_f32_16x16x4_f32 (lane = 16 q + j):
 //   A[row j][k = q]   one float        B[k = q][col j]   one float
 //   D[row 4 q + i][col j], i = 0..3    four floats
 // The contraction index inside a layer may be permuted freely as long as A and B agree;
-// layer 2 uses k = (H1/4) q + s at step s so that a lane reads H1/4 consecutive floats.
+// layer 2 uses k = (H/4) q + s at step s so that a lane reads H/4 consecutive floats.
 #include "kernels.h"
 #include "philox.h"
 
@@ -34,9 +39,9 @@ struct CartpoleArgs {
   float* final_state;
 };
 
+// tanh(x) = 1 - 2 / (e^{2x} + 1) on the hardware exp2 / reciprocal; saturates cleanly at +-1.
 __device__ __forceinline__ float tanh_fast(float x) {
-  // 1 - 2 / (e^{2x} + 1); saturates cleanly at +-1 for large |x|
-  const float e = __expf(2.0f * x);
+  const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);  // e^{2x} = 2^{2x log2 e}
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
@@ -44,6 +49,17 @@ __device__ __forceinline__ float act_apply(float x, int act) {
   if (act == EVO_ACT_TANH) return tanh_fast(x);
   if (act == EVO_ACT_RELU) return fmaxf(x, 0.f);
   return x;
+}
+
+// sin and cos of an angle in radians: two-term reduction by 2 pi (2 pi = hi - lo with hi the fp32
+// nearest to 2 pi), then the hardware sine / cosine, which take revolutions.
+__device__ __forceinline__ void sincos_fast(float th, float& s, float& c) {
+  const float n = rintf(th * 0.15915494309189535f);
+  float r = fmaf(n, -6.2831854820251465f, th);
+  r = fmaf(n, 1.7484555e-07f, r);
+  const float t = r * 0.15915494309189535f;
+  s = __builtin_amdgcn_sinf(t);
+  c = __builtin_amdgcn_cosf(t);
 }
 
 struct CpState {
@@ -63,57 +79,66 @@ __device__ __forceinline__ CpState cartpole_advance(const CpState& s, float sn, 
   n.xd = s.xd + c.dt * xdd;
   n.th = s.th + c.dt * s.thd;
   n.thd = s.thd + c.dt * thdd;
-  sincosf(n.th, &sn_new, &cs_new);
+  sincos_fast(n.th, sn_new, cs_new);
   return n;
+}
+
+__device__ __forceinline__ float step_reward(float x_new, float cs_new) {
+  return cs_new * __builtin_amdgcn_exp2f(-1.4426950408889634f * x_new * x_new);  // cos(th') exp(-x'^2)
+}
+
+// Sum over the 16 lanes of a row with DPP moves (xor 1, xor 2, half-row mirror, row mirror):
+// every lane of the row ends with the total; the order is fixed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = dpp_add<0x141>(v);  // row_half_mirror
+  v = dpp_add<0x140>(v);  // row_mirror
+  return v;
 }
 
 constexpr int kHStride = 68;  // LDS row stride of the hidden-activation transpose buffer
 
-template <int NT1, int NT2>  // hidden widths in tiles of 16; NT2 == 0: one hidden layer
-__global__ __launch_bounds__(64) void cartpole_kernel(CartpoleArgs a, int act1, int act2, int act3) {
-  constexpr int H1 = 16 * NT1, H2 = 16 * NT2;
-  constexpr int KS2 = H1 / 4;  // matrix-core steps of layer 2
-  __shared__ float hbuf[16 * kHStride];
-  __shared__ float abuf[16];
-  const int lane = threadIdx.x;
+template <int NT, bool TWO>  // hidden width 16 NT (NT waves); TWO: two hidden layers of that width
+__global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1, int act2, int act3) {
+  constexpr int H = 16 * NT;
+  constexpr int KS2 = H / 4;  // matrix-core steps of layer 2
+  __shared__ __attribute__((aligned(16))) float hbuf[16 * kHStride];
+  __shared__ float part[NT][16];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, q = lane >> 4;
   const int member = blockIdx.x;
   const float* theta = a.params + static_cast<size_t>(member) * a.P;
+  const int col = 16 * wave + j;  // this lane's hidden neuron
 
-  // ---- weights -> registers (B operands) ------------------------------------------------
-  float w1[2][NT1], bias1[NT1];
+  // ---- weights -> registers (B operands of this wave's column tile) ----------------------------
+  const float w1a = theta[q * H + col];                      // k = q      (x, x_d, cos, sin)
+  const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding)
+  const float bias1 = theta[5 * H + col];
+  const float* th2 = theta + 5 * H + H;
+  float w2[TWO ? KS2 : 1];
+  float bias2 = 0.f, w3, b3;
+  if (TWO) {
 #pragma unroll
-  for (int t = 0; t < NT1; ++t) {
-    w1[0][t] = theta[q * H1 + 16 * t + j];
-    w1[1][t] = (q == 0) ? theta[4 * H1 + 16 * t + j] : 0.f;
-    bias1[t] = theta[5 * H1 + 16 * t + j];
-  }
-  const float* th2 = theta + 5 * H1 + H1;
-  float w2[NT2 > 0 ? KS2 : 1][NT2 > 0 ? NT2 : 1], bias2[NT2 > 0 ? NT2 : 1];
-  float w3[NT2 > 0 ? NT2 : NT1];
-  float b3;
-  if (NT2 > 0) {
-#pragma unroll
-    for (int s = 0; s < KS2; ++s)
-#pragma unroll
-      for (int t = 0; t < NT2; ++t) w2[s][t] = th2[(KS2 * q + s) * H2 + 16 * t + j];
-#pragma unroll
-    for (int t = 0; t < NT2; ++t) {
-      bias2[t] = th2[H1 * H2 + 16 * t + j];
-      w3[t] = th2[H1 * H2 + H2 + 16 * t + j];
-    }
-    b3 = th2[H1 * H2 + H2 + H2];
+    for (int s = 0; s < KS2; ++s) w2[s] = th2[(KS2 * q + s) * H + col];
+    bias2 = th2[H * H + col];
+    w3 = th2[H * H + H + col];
+    b3 = th2[H * H + H + H];
   } else {
-#pragma unroll
-    for (int t = 0; t < NT1; ++t) w3[t] = th2[16 * t + j];
-    b3 = th2[H1];
+    w3 = th2[col];
+    b3 = th2[H];
   }
 
   float total = 0.f;  // sum of the returns of this lane's roll-outs over all passes
   for (int r0 = 0; r0 < a.R; r0 += 16) {
     const int r = r0 + j;
     const bool valid = r < a.R;
-    // ---- reset: identical for every member --------------------------------------------
+    // ---- reset: identical for every member ----------------------------------------------------
     float z[4];
     philox_normal4(0u, static_cast<uint32_t>(r), a.gen, EVO_TAG_RESET, a.key0, a.key1, z);
     CpState s;
@@ -122,30 +147,23 @@ __global__ __launch_bounds__(64) void cartpole_kernel(CartpoleArgs a, int act1, 
     s.th = a.init_scale * z[2] + 3.14159265358979323846f;
     s.thd = a.init_scale * z[3];
     float sn, cs;
-    sincosf(s.th, &sn, &cs);
+    sincos_fast(s.th, sn, cs);
     float ret = 0.f;
     bool alive = true;
 
     for (int step = 0; step < a.steps; ++step) {
-      // ---- layer 1: observation (x, x_d, cos, sin, th_d) is the A operand directly -------
+      // ---- layer 1: observation (x, x_d, cos, sin, th_d) is the A operand directly -------------
       const float a0 = q == 0 ? s.x : (q == 1 ? s.xd : (q == 2 ? cs : sn));
       const float a1 = q == 0 ? s.thd : 0.f;
-      float p[4] = {0.f, 0.f, 0.f, 0.f};  // partial products of the output layer
+      floatx4 acc = {bias1, bias1, bias1, bias1};
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, w1b, acc, 0, 0, 0);
+      float p[4];
+      if (TWO) {
 #pragma unroll
-      for (int t = 0; t < NT1; ++t) {
-        floatx4 acc = {bias1[t], bias1[t], bias1[t], bias1[t]};
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1[0][t], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, w1[1][t], acc, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float h = act_apply(acc[i], act1);
-          if (NT2 > 0) hbuf[(4 * q + i) * kHStride + 16 * t + j] = h;
-          else p[i] = fmaf(h, w3[t], p[i]);
-        }
-      }
-      if (NT2 > 0) {
+        for (int i = 0; i < 4; ++i) hbuf[(4 * q + i) * kHStride + col] = act_apply(acc[i], act1);
         __syncthreads();
-        // ---- layer 2: lane (row j, k group q) reads KS2 consecutive activations -------------
+        // ---- layer 2: lane (row j, k group q) reads KS2 consecutive activations ----------------
         float a2[KS2];
         const float4* src = reinterpret_cast<const float4*>(hbuf + j * kHStride + KS2 * q);
 #pragma unroll
@@ -153,32 +171,31 @@ __global__ __launch_bounds__(64) void cartpole_kernel(CartpoleArgs a, int act1, 
           const float4 v = src[c4];
           a2[4 * c4 + 0] = v.x, a2[4 * c4 + 1] = v.y, a2[4 * c4 + 2] = v.z, a2[4 * c4 + 3] = v.w;
         }
+        floatx4 acc2 = {bias2, bias2, bias2, bias2};
 #pragma unroll
-        for (int t = 0; t < NT2; ++t) {
-          floatx4 acc = {bias2[t], bias2[t], bias2[t], bias2[t]};
+        for (int s2 = 0; s2 < KS2; ++s2) acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[s2], w2[s2], acc2, 0, 0, 0);
 #pragma unroll
-          for (int s2 = 0; s2 < KS2; ++s2) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[s2], w2[s2][t], acc, 0, 0, 0);
+        for (int i = 0; i < 4; ++i) p[i] = act_apply(acc2[i], act2) * w3;
+      } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) p[i] = fmaf(act_apply(acc[i], act2), w3[t], p[i]);
-        }
+        for (int i = 0; i < 4; ++i) p[i] = act_apply(acc[i], act1) * w3;
       }
-      // ---- output layer: sum over the 16 columns of a row group, then hand row r its action
+      // ---- output layer: this wave's 16 columns, then the waves' partial sums in wave order ----
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) p[i] += __shfl_xor(p[i], off, 64);
-      }
+      for (int i = 0; i < 4; ++i) p[i] = row16_sum(p[i]);
       if (j == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) abuf[4 * q + i] = p[i];
+        for (int i = 0; i < 4; ++i) part[wave][4 * q + i] = p[i];
       }
       __syncthreads();
-      const float action = act_apply(abuf[j] + b3, act3);
-      __syncthreads();
-      // ---- environment step --------------------------------------------------------------
+      float pre = part[0][j];
+#pragma unroll
+      for (int w = 1; w < NT; ++w) pre += part[w][j];
+      const float action = act_apply(pre + b3, act3);
+      // ---- environment step (every wave advances its own copy of the state) -------------------
       float sn_n, cs_n;
       const CpState n = cartpole_advance(s, sn, cs, action, a.c, sn_n, cs_n);
-      const float reward = cs_n * expf(-n.x * n.x);
+      const float reward = step_reward(n.x, cs_n);
       if (alive) {
         ret += reward;
         s = n;
@@ -186,8 +203,9 @@ __global__ __launch_bounds__(64) void cartpole_kernel(CartpoleArgs a, int act1, 
         cs = cs_n;
         alive = fabsf(n.x) <= a.c.xlim;
       }
+      if (!TWO) __syncthreads();  // the partial sums are rewritten next step
     }
-    if (valid && q == 0) {
+    if (valid && q == 0 && wave == 0) {
       if (a.ret) a.ret[static_cast<size_t>(member) * a.R + r] = ret;
       if (a.final_state) {
         float* f = a.final_state + (static_cast<size_t>(member) * a.R + r) * 4;
@@ -195,11 +213,11 @@ __global__ __launch_bounds__(64) void cartpole_kernel(CartpoleArgs a, int act1, 
       }
     }
     total += valid ? ret : 0.f;
+    __syncthreads();
   }
-  // ---- fitness = mean return; rows j = 0..15 of lane group q == 0, fixed butterfly --------
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) total += __shfl_xor(total, off, 64);
-  if (lane == 0 && a.fitness) a.fitness[member] = total / static_cast<float>(a.R);
+  // ---- fitness = mean return over the roll-outs (rows j = 0..15, fixed order) -----------------
+  total = row16_sum(total);
+  if (threadIdx.x == 0 && a.fitness) a.fitness[member] = total / static_cast<float>(a.R);
 }
 
 __global__ __launch_bounds__(256) void cartpole_step_kernel(CartpoleConst c, const float* __restrict__ state,
@@ -211,10 +229,10 @@ __global__ __launch_bounds__(256) void cartpole_step_kernel(CartpoleConst c, con
   const float4 v = reinterpret_cast<const float4*>(state)[i];
   CpState s{v.x, v.y, v.z, v.w};
   float sn, cs, sn_n, cs_n;
-  sincosf(s.th, &sn, &cs);
+  sincos_fast(s.th, sn, cs);
   const CpState nx = cartpole_advance(s, sn, cs, action[i], c, sn_n, cs_n);
   reinterpret_cast<float4*>(next)[i] = make_float4(nx.x, nx.xd, nx.th, nx.thd);
-  reward[i] = cs_n * expf(-nx.x * nx.x);
+  reward[i] = step_reward(nx.x, cs_n);
 }
 
 static CartpoleConst make_const(const float* cp) {
@@ -247,18 +265,18 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
   a.fitness = fitness, a.ret = ret, a.final_state = final_state;
   const int H = sh.dims[1];
   const int a1 = sh.act[0], a2 = sh.n_layers == 3 ? sh.act[1] : 0, a3 = sh.act[sh.n_layers - 1];
-  const dim3 grid(pop), block(64);
-#define EVO_CP_CASE(T1, T2)                                                                  \
-  hipLaunchKernelGGL((cartpole_kernel<T1, T2>), grid, block, 0, s, a, a1, a2, a3);          \
+  const dim3 grid(pop);
+#define EVO_CP_CASE(NTV, TWOV)                                                                        \
+  hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);       \
   return check_launch("cartpole_kernel")
   if (sh.n_layers == 3) {
-    if (H == 64) { EVO_CP_CASE(4, 4); }
-    if (H == 32) { EVO_CP_CASE(2, 2); }
-    EVO_CP_CASE(1, 1);
+    if (H == 64) { EVO_CP_CASE(4, true); }
+    if (H == 32) { EVO_CP_CASE(2, true); }
+    EVO_CP_CASE(1, true);
   }
-  if (H == 64) { EVO_CP_CASE(4, 0); }
-  if (H == 32) { EVO_CP_CASE(2, 0); }
-  EVO_CP_CASE(1, 0);
+  if (H == 64) { EVO_CP_CASE(4, false); }
+  if (H == 32) { EVO_CP_CASE(2, false); }
+  EVO_CP_CASE(1, false);
 #undef EVO_CP_CASE
 }
 
