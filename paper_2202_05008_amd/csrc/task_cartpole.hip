@@ -103,8 +103,12 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 constexpr int kHStride = 68;  // LDS row stride of the hidden-activation transpose buffer
 
-template <int NT, bool TWO>  // hidden width 16 NT (NT waves); TWO: two hidden layers of that width
-__global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1, int act2, int act3) {
+// NT: hidden width 16 NT (NT waves); TWO: two hidden layers of that width; TANH: every activation
+// is tanh (the usual policy), which removes the per-value activation switch from the step loop.
+template <int NT, bool TWO, bool TANH>
+__global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1_rt, int act2_rt, int act3_rt) {
+  const int act1 = TANH ? EVO_ACT_TANH : act1_rt, act2 = TANH ? EVO_ACT_TANH : act2_rt;
+  const int act3 = TANH ? EVO_ACT_TANH : act3_rt;
   constexpr int H = 16 * NT;
   constexpr int KS2 = H / 4;  // matrix-core steps of layer 2
   __shared__ __attribute__((aligned(16))) float hbuf[16 * kHStride];
@@ -266,8 +270,12 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
   const int H = sh.dims[1];
   const int a1 = sh.act[0], a2 = sh.n_layers == 3 ? sh.act[1] : 0, a3 = sh.act[sh.n_layers - 1];
   const dim3 grid(pop);
-#define EVO_CP_CASE(NTV, TWOV)                                                                        \
-  hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);       \
+  const bool all_tanh = a1 == EVO_ACT_TANH && a3 == EVO_ACT_TANH && (sh.n_layers == 2 || a2 == EVO_ACT_TANH);
+#define EVO_CP_CASE(NTV, TWOV)                                                                              \
+  if (all_tanh)                                                                                             \
+    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, true>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);     \
+  else                                                                                                      \
+    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, false>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);    \
   return check_launch("cartpole_kernel")
   if (sh.n_layers == 3) {
     if (H == 64) { EVO_CP_CASE(4, true); }
