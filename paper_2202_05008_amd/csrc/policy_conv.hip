@@ -5,20 +5,27 @@
 //
 // conv3x3 -> ReLU -> maxpool2 -> conv3x3 -> ReLU -> maxpool2 -> dense, c1 = 8, c2 = 16.
 //
-// Each wavefront runs whole images end to end out of its private slice of LDS, with no
+// Each wavefront runs whole images end to end out of its private 8 KB slice of LDS, with no
 // workgroup barrier in the loop: conv1 (K = 9) on the vector ALU, conv2 (K = 72, N = 16:
 // 78% of the flops) as implicit GEMM on v_mfma_f32_16x16x4_f32, the dense layer on the
-// vector ALU against a workgroup-shared LDS copy of its weights.  The eight waves of a
-// workgroup are at different stages, so matrix and vector work overlap on a SIMD.  The next
-// image is prefetched into registers while the current one is computed.  Activations never
-// leave the chip; per image the kernel reads 3 KB (L2 resident, shared by all members).
+// vector ALU against a workgroup-shared LDS copy of its weights.  Sixteen waves per
+// workgroup (four per SIMD) sit at different stages, so matrix and vector work of different
+// waves overlap.  The next image is prefetched into registers while the current one is
+// computed.  Activations never leave the chip; per image the kernel reads 3 KB (L2 resident,
+// shared by all members).
+//
+// Band pipeline.  conv2 output row b needs the (zero-padded) conv1 rows 2b .. 2b+3 only, so the
+// conv1 output is never held whole: pass b of conv1 produces padded rows 2b+2 and 2b+3 and
+// stores them twice, as rows 2, 3 of the four-row buffer of band b and as rows 0, 1 of the
+// buffer of band b+1 (two buffers, used alternately); pass -1 primes band 0.  Every LDS offset
+// of the matrix A operand is then a compile-time constant relative to one per-lane base.  The
+// conv2 output overwrites the part of the image buffer that conv1 has already consumed.
 //
 // conv2 tiling.  The 16 rows of a matrix tile are 4 pooling windows x their 4 pixels, so
 // that the 4 accumulator registers of a lane (rows 4q..4q+3 of column n) are exactly one
 // pooling window of output channel n: max-pooling is three v_max on registers.  The
 // contraction index k = tap * 8 + channel; lane group q supplies k = 4 step + q, i.e.
-// input channel 4 (step & 1) + q of tap step >> 1, read from channel-major planes in LDS
-// with compile-time offsets from one per-lane base.
+// input channel 4 (step & 1) + q of tap step >> 1, read from channel-major planes in LDS.
 #include "kernels.h"
 
 namespace evo {
@@ -28,12 +35,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
 constexpr int kImgW = kHMax + 2;                     // padded image row (30)
-constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; later the conv2 output (784)
-constexpr int kA1W = kHMax / 2 + 2;                  // padded conv1-output row (16)
-constexpr int kA1Plane = kA1W * kA1W + 8;            // 264: plane stride = 8 mod 32 banks
-constexpr int kA1Floats = kC1 * kA1Plane;            // 2112: conv1 output; later the dense partial sums
-constexpr int kWaveFloats = kImgFloats + kA1Floats;  // 3016 floats = 12,064 bytes per wave
-constexpr int kConvWaves = 8;
+constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; its consumed part takes the conv2 output
+constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16)
+constexpr int kBandPlane = 4 * kBandW + 8;           // 72: four rows per channel plane; stride = 8 mod 32 banks
+constexpr int kBandFloats = kC1 * kBandPlane;        // 576 per band buffer
+constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2056 floats = 8,224 bytes per wave
+constexpr int kConvWavesMax = 16;
 constexpr int kMaxCls = 16;
 constexpr int kMaxFeat = (kHMax / 4) * (kHMax / 4) * kC2;  // 784
 
@@ -56,23 +63,23 @@ __device__ __forceinline__ void wave_sync() {
 
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
 // (10 for the ten-class case, 16 for any n_cls <= 16 with zero padding).
-template <int NCS>
+// kConvWaves: waves per workgroup (16 with ten classes, 12 when the padded dense weights take 49 KB).
+template <int NCS, int kConvWaves>
 __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
-  __shared__ float wave_loss[kConvWaves];
+  __shared__ float wave_loss[kConvWavesMax];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int member = blockIdx.y;
   const int H = a.H, H2 = H / 2, H4 = H / 4;
-  const int n_win1 = H2 * H2;  // pooled outputs of conv1
   const int n_win2 = H4 * H4;  // pooled outputs of conv2
   const int n_feat = n_win2 * kC2;
   const int n_cls = a.n_cls;
 
   float* wd_s = lds;                                   // [n_feat][NCS] dense weights, shared by the waves
   float* img = lds + kMaxFeat * NCS + wave * kWaveFloats;
-  float* a1 = img + kImgFloats;
-  float* a2 = img;                                     // conv2 output reuses the image buffer
+  float* band = img + kImgFloats;                      // two band buffers of conv1 output
+  float* a2 = img;                                     // conv2 output reuses the consumed image rows
 
   const float* theta = a.params + static_cast<size_t>(member) * a.P;
   const float* W1 = theta;                 // [3][3][1][8]
@@ -97,6 +104,29 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   for (int st = 0; st < 18; ++st) w2r[st] = W2[(4 * st + q) * kC2 + n];
   const float bias2 = b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
+
+  // conv1 role of this lane: pooled pixel (row select rs, column wx) x four channels 4 cg .. 4 cg + 3
+  const int c1_win = lane % (2 * H2), c1_cg = min(lane / (2 * H2), 1);
+  const bool c1_on = lane < 4 * H2;
+  const int c1_rs = c1_win / H2, c1_wx = c1_win - c1_rs * H2;
+  float w1v[9][4], bias1v[4];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) w1v[t][c] = W1[t * kC1 + 4 * c1_cg + c];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) bias1v[c] = b1[4 * c1_cg + c];
+
+  // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3
+  int a_off[2];
+  {
+    const int r = lane & 15, i = r & 3;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int wxA = min(4 * h + (r >> 2), H4 - 1);
+      a_off[h] = q * kBandPlane + (i >> 1) * kBandW + 2 * wxA + (i & 1);
+    }
+  }
 
   const int img_begin = blockIdx.x * a.imgs_per_chunk;
   const int img_end = min(a.B, img_begin + a.imgs_per_chunk);
@@ -133,28 +163,19 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
     wave_sync();
 
-    // ---- conv1 + ReLU + pool: lane = pooled output pixel; two passes of four channels so that
-    //      the 40 wave-uniform weights of a pass fit in scalar registers --------------------------
 #pragma unroll 1
-    for (int cg = 0; cg < 2; ++cg) {
-      float w1r[9][4], bias1[4];
-#pragma unroll
-      for (int t = 0; t < 9; ++t)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w1r[t][c] = W1[t * kC1 + 4 * cg + c];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) bias1[c] = b1[4 * cg + c];
-#pragma unroll 1
-      for (int w0 = 0; w0 < n_win1; w0 += 64) {
-        const int w = w0 + lane;
-        if (w < n_win1) {
-          const int wy = w / H2, wx = w - wy * H2;
+    for (int b = -1; b < H4; ++b) {
+      // ---- conv1 + ReLU + pool, pass b: padded conv1 rows 2b+2, 2b+3 (pooled rows 2b+1, 2b+2) ----
+      if (c1_on) {
+        const int pr = 2 * b + 1 + c1_rs;  // pooled row of this lane; outside [0, H2) it is the zero border
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (pr >= 0 && pr < H2) {
           float p[4][4];
 #pragma unroll
           for (int dy = 0; dy < 4; ++dy) {
-            const float2* rowp = reinterpret_cast<const float2*>(img + (2 * wy + dy) * kImgW + 2 * wx);
-            const float2 u = rowp[0], v = rowp[1];
-            p[dy][0] = u.x, p[dy][1] = u.y, p[dy][2] = v.x, p[dy][3] = v.y;
+            const float2* rowp = reinterpret_cast<const float2*>(img + (2 * pr + dy) * kImgW + 2 * c1_wx);
+            const float2 u = rowp[0], w = rowp[1];
+            p[dy][0] = u.x, p[dy][1] = u.y, p[dy][2] = w.x, p[dy][3] = w.y;
           }
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
@@ -163,47 +184,46 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
               for (int dx = 0; dx < 3; ++dx) {
-                const float wv = w1r[dy * 3 + dx][c];
+                const float wv = w1v[dy * 3 + dx][c];
                 o00 = fmaf(p[dy][dx], wv, o00);
                 o01 = fmaf(p[dy][dx + 1], wv, o01);
                 o10 = fmaf(p[dy + 1][dx], wv, o10);
                 o11 = fmaf(p[dy + 1][dx + 1], wv, o11);
               }
-            const float v = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) + bias1[c], 0.f);
-            a1[(4 * cg + c) * kA1Plane + (wy + 1) * kA1W + wx + 1] = v;
+            v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) + bias1v[c], 0.f);
           }
         }
-      }
-    }
-    wave_sync();
-    // ---- conv2 + ReLU + pool on the matrix cores, two independent tiles per pass ---------------
-    for (int g0 = 0; g0 < n_win2; g0 += 8) {
-      // A role: row r = lane & 15 -> window g0 + (r >> 2), pixel r & 3; k group = lane >> 4
-      const int r = lane & 15;
-      const float* base[2];
+        // rows 2, 3 of this band's buffer and rows 0, 1 of the next band's buffer
+        float* cur = band + (b & 1) * kBandFloats + (4 * c1_cg) * kBandPlane + (2 + c1_rs) * kBandW + c1_wx + 1;
+        float* nxt = band + ((b + 1) & 1) * kBandFloats + (4 * c1_cg) * kBandPlane + c1_rs * kBandW + c1_wx + 1;
+        if (b >= 0) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int gA = min(g0 + 4 * h + (r >> 2), n_win2 - 1);
-        const int wyA = gA / H4, wxA = gA - wyA * H4;
-        base[h] = a1 + q * kA1Plane + (2 * wyA + ((r >> 1) & 1)) * kA1W + 2 * wxA + (r & 1);
+          for (int c = 0; c < 4; ++c) cur[c * kBandPlane] = v[c];
+        }
+        if (b + 1 < H4) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) nxt[c * kBandPlane] = v[c];
+        }
       }
+      wave_sync();
+      if (b < 0) continue;
+
+      // ---- conv2 + ReLU + pool, band b: two independent tiles (windows 0..3 and 4..7 of the row) --
+      const float* bb = band + (b & 1) * kBandFloats;
       floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int st = 0; st < 18; ++st) {
         const int tap = st >> 1, dy = tap / 3, dx = tap - 3 * dy;
-        const int o = (4 * (st & 1)) * kA1Plane + dy * kA1W + dx;
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(base[0][o], w2r[st], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(base[1][o], w2r[st], acc1, 0, 0, 0);
+        const int o = (4 * (st & 1)) * kBandPlane + dy * kBandW + dx;
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(bb[a_off[0] + o], w2r[st], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(bb[a_off[1] + o], w2r[st], acc1, 0, 0, 0);
       }
-      // D role: the four registers of lane (q, n) are window g0 + q (+4) of channel n.  The
-      // writes go to the image buffer, whose last reader (conv1) is done.
-      const int gD0 = g0 + q, gD1 = g0 + 4 + q;
-      if (gD0 < n_win2)
-        a2[gD0 * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
-      if (gD1 < n_win2)
-        a2[gD1 * kC2 + n] = fmaxf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])) + bias2, 0.f);
+      // D role: the four registers of lane (q, n) are window q (+4) of channel n
+      if (q < H4) a2[(b * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
+      if (q + 4 < H4)
+        a2[(b * H4 + q + 4) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])) + bias2, 0.f);
+      wave_sync();
     }
-    wave_sync();
 
     // ---- dense: lane takes features lane, lane + 64, ... and accumulates every class ---------
     float acc[NCS];
@@ -215,8 +235,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
       for (int c = 0; c < NCS; ++c) acc[c] = fmaf(x, wrow[c], acc[c]);
     }
-    // transpose-reduce through LDS (conv1's buffer is free now): lane (c, part) adds 16 partials
-    float* red = a1;
+    // transpose-reduce through LDS (the band buffers are free now): lane (c, part) adds 16 partials
+    float* red = band;
 #pragma unroll
     for (int c = 0; c < NCS; ++c) red[lane * NCS + c] = acc[c];
     wave_sync();
@@ -282,19 +302,21 @@ int convnet_supported(const ConvShape& sh) {
 // image per wave.
 int convnet_chunks(const ConvShape&, int pop, int B) {
   int chunks = (2048 + pop - 1) / pop;
-  const int max_chunks = (B + kConvWaves - 1) / kConvWaves;
+  const int max_chunks = (B + kConvWavesMax - 1) / kConvWavesMax;
   if (chunks > max_chunks) chunks = max_chunks;
   if (chunks < 1) chunks = 1;
   return chunks;
 }
 
-template <int NCS>
+template <int NCS, int WAVES>
 static int launch_conv(const ConvArgs& a, int pop, hipStream_t s) {
-  const size_t shmem = sizeof(float) * (static_cast<size_t>(kMaxFeat) * NCS + kConvWaves * kWaveFloats);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(convnet_kernel<NCS>),
+  const size_t shmem = sizeof(float) * (static_cast<size_t>(kMaxFeat) * NCS + WAVES * kWaveFloats);
+  static_assert(sizeof(float) * (kMaxFeat * NCS + WAVES * kWaveFloats) + 256 <= 160 * 1024, "LDS budget of a CU");
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(convnet_kernel<NCS, WAVES>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
+  if (e != hipSuccess) (void)hipGetLastError();  // do not leave the error sticky for the caller's next HIP call
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL(convnet_kernel<NCS>, dim3(a.chunks, pop), dim3(64 * kConvWaves), shmem, s, a);
+  hipLaunchKernelGGL((convnet_kernel<NCS, WAVES>), dim3(a.chunks, pop), dim3(64 * WAVES), shmem, s, a);
   return check_launch("convnet_kernel");
 }
 
@@ -306,7 +328,7 @@ int launch_convnet_f32(const ConvShape& sh, const float* params, const float* im
   if (chunks <= 0) chunks = convnet_chunks(sh, pop, B);
   a.chunks = chunks;
   a.imgs_per_chunk = (B + chunks - 1) / chunks;
-  return sh.n_cls == 10 ? launch_conv<10>(a, pop, s) : launch_conv<16>(a, pop, s);
+  return sh.n_cls == 10 ? launch_conv<10, 16>(a, pop, s) : launch_conv<16, 12>(a, pop, s);
 }
 
 }  // namespace evo
