@@ -152,17 +152,19 @@ int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, in
   return launch(mlp_f32_kernel<LOSS_MSE>);
 }
 
-__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int pop, int n,
-                                                       float scale, float* __restrict__ fitness) {
-  const int m = blockIdx.x * 256 + threadIdx.x;
-  if (m >= pop) return;
+// One wavefront per member: lanes read the partial sums coalesced (lane, lane + 64, ...) and the
+// 64 lane totals are combined by a fixed butterfly, so the result does not depend on timing.
+__global__ __launch_bounds__(64) void finalize_kernel(const float* __restrict__ partial, int pop, int n,
+                                                      float scale, float* __restrict__ fitness) {
+  const int m = blockIdx.x, lane = threadIdx.x;
   float acc = 0.f;
-  for (int j = 0; j < n; ++j) acc += partial[static_cast<size_t>(m) * n + j];
-  fitness[m] = scale * acc;
+  for (int j = lane; j < n; j += 64) acc += partial[static_cast<size_t>(m) * n + j];
+  acc = wave_sum(acc);
+  if (lane == 0) fitness[m] = scale * acc;
 }
 
 int launch_finalize(const float* partial, int pop, int n, float scale, float* fitness, hipStream_t s) {
-  hipLaunchKernelGGL(finalize_kernel, dim3((pop + 255) / 256), dim3(256), 0, s, partial, pop, n, scale, fitness);
+  hipLaunchKernelGGL(finalize_kernel, dim3(pop), dim3(64), 0, s, partial, pop, n, scale, fitness);
   return check_launch("finalize_kernel");
 }
 
