@@ -127,9 +127,20 @@ __device__ __forceinline__ uint32_t orderable(float f) {
 
 constexpr int kRankThreads = 1024;
 
-// One workgroup: bitonic sort of 64-bit keys (orderable fitness << 32 | member index) in LDS.
-// Keys are unique, so the permutation is unique and the ranks are exact.  Then the shaped
-// utilities c, their mean b (fp64, fixed tree) and the pair weights w, u.
+// One workgroup: bitonic sort of 64-bit keys (orderable fitness << 32 | member index).  Keys are
+// unique, so the permutation is unique and the ranks are exact.  Then the shaped utilities c,
+// their mean b (fp64, fixed tree) and the pair weights w, u.
+//
+// The keys live in registers: thread t owns elements t, t + 1024, ... (at most four).  A compare
+// distance j >= 1024 pairs two registers of one thread, j < 64 pairs two lanes of one wavefront
+// (cross-lane shuffle), and only 64 <= j < 1024 goes through LDS with workgroup barriers: 18 of
+// the 78 steps at 4096 keys.
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask) {
+  const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), mask, 64);
+  const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), mask, 64);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int npow2,
                                                             int shaping, uint32_t* __restrict__ rank_out,
                                                             float* __restrict__ shaped_out,
@@ -138,37 +149,59 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restr
   __shared__ float cs[EVO_POP_MAX];
   __shared__ double red[kRankThreads];
   const int tid = threadIdx.x;
-  for (int i = tid; i < npow2; i += kRankThreads)
-    keys[i] = i < pop ? (static_cast<uint64_t>(orderable(fitness[i])) << 32) | static_cast<uint32_t>(i)
-                      : ~uint64_t(0);
-  __syncthreads();
-  // Thread t owns elements t, t + 1024, ...; for a compare distance j < 64 both partners belong to
-  // one wavefront, whose LDS accesses execute in order, so only steps that reach across waves
-  // (before or after) need a workgroup barrier: 21 instead of 78 at 4096 keys.
-  int prev_j = kRankThreads;
+  constexpr int kMaxOwn = EVO_POP_MAX / kRankThreads;  // 4
+  const int own = npow2 > kRankThreads ? npow2 / kRankThreads : 1;
+  uint64_t e[kMaxOwn];
+#pragma unroll
+  for (int m = 0; m < kMaxOwn; ++m) {
+    const int i = tid + kRankThreads * m;
+    e[m] = (m < own && i < pop) ? (static_cast<uint64_t>(orderable(fitness[i])) << 32) | static_cast<uint32_t>(i)
+                                : ~uint64_t(0);
+  }
   for (int k = 2; k <= npow2; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
-      if (j >= 64 || prev_j >= 64) {
-        __syncthreads();
-      } else {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      }
-      prev_j = j;
-      for (int i = tid; i < npow2; i += kRankThreads) {
-        const int p = i ^ j;
-        if (p > i) {
-          const uint64_t a = keys[i], b = keys[p];
-          const bool ascending = (i & k) == 0;
-          if ((a > b) == ascending) {
-            keys[i] = b;
-            keys[p] = a;
+      if (j >= kRankThreads) {
+        // both elements in this thread's registers: m and m ^ (j / 1024)
+        const int dm = j / kRankThreads;
+#pragma unroll
+        for (int m = 0; m < kMaxOwn; ++m) {
+          const int pm = m ^ dm;
+          if (m < own && pm > m && pm < kMaxOwn) {
+            const int i = tid + kRankThreads * m;
+            const bool ascending = (i & k) == 0;
+            const uint64_t x = e[m], y = e[pm];
+            if ((x > y) == ascending) {
+              e[m] = y;
+              e[pm] = x;
+            }
           }
         }
+      } else {
+        const bool via_lds = j >= 64;
+        if (via_lds) {
+#pragma unroll
+          for (int m = 0; m < kMaxOwn; ++m)
+            if (m < own) keys[tid + kRankThreads * m] = e[m];
+          __syncthreads();
+        }
+#pragma unroll
+        for (int m = 0; m < kMaxOwn; ++m) {
+          if (m < own) {
+            const int i = tid + kRankThreads * m;
+            const uint64_t other = via_lds ? keys[i ^ j] : shfl_xor_u64(e[m], j);
+            // ascending pair: the lower index keeps the smaller key; descending: the larger one
+            const bool keep_min = ((i & j) == 0) == ((i & k) == 0);
+            const bool take = keep_min ? other < e[m] : other > e[m];
+            e[m] = take ? other : e[m];
+          }
+        }
+        if (via_lds) __syncthreads();
       }
     }
   }
+#pragma unroll
+  for (int m = 0; m < kMaxOwn; ++m)
+    if (m < own && tid + kRankThreads * m < npow2) keys[tid + kRankThreads * m] = e[m];
   __syncthreads();
   const float denom = static_cast<float>(2 * (pop - 1));
   for (int p = tid; p < pop; p += kRankThreads) {
