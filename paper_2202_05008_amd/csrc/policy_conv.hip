@@ -5,42 +5,56 @@
 //
 // conv3x3 -> ReLU -> maxpool2 -> conv3x3 -> ReLU -> maxpool2 -> dense, c1 = 8, c2 = 16.
 //
-// Each wavefront runs whole images end to end out of its private 8 KB slice of LDS, with no
+// Each wavefront runs whole images end to end out of its private 10 KB slice of LDS, with no
 // workgroup barrier in the loop: conv1 (K = 9) on the vector ALU, conv2 (K = 72, N = 16:
-// 78% of the flops) as implicit GEMM on v_mfma_f32_16x16x4_f32, the dense layer on the
-// vector ALU against a workgroup-shared LDS copy of its weights.  Sixteen waves per
-// workgroup (four per SIMD) sit at different stages, so matrix and vector work of different
-// waves overlap.  The next image is prefetched into registers while the current one is
-// computed.  Activations never leave the chip; per image the kernel reads 3 KB (L2 resident,
-// shared by all members).
+// 78% of the flops) as implicit GEMM on the matrix cores, the dense layer on the vector ALU
+// against a workgroup-shared LDS copy of its weights.  The next image is prefetched into
+// registers while the current one is computed.  Activations never leave the chip; per image
+// the kernel reads 3 KB (L2 resident, shared by all members).
+//
+// conv2 arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
+// v_mfma_f32_16x16x4_f32 takes 32 cycles (1024 MACs), and the two do not overlap, so the fp32
+// matrix instruction is only 1.4x the vector rate.  v_mfma_f32_16x16x32_bf16 takes 16 cycles
+// for 8192 MACs.  conv2 therefore runs on the bf16 matrix instruction with every fp32 operand
+// split exactly into three bfloat16 terms x = h + m + l (h = bf16(x), m = bf16(x - h),
+// l = bf16(x - h - m); 24 significand bits in all), and six of the nine partial products per
+// operand pair accumulated in fp32: hh' + hm' + mh' + mm' + hl' + lh'.  The three dropped
+// products are below 2^-24 of the full one, i.e. below the rounding of an fp32 multiply, and
+// each bf16 x bf16 product is exact in fp32: the result has fp32 accuracy at half the issue
+// cycles of the fp32 matrix instruction.
 //
 // Band pipeline.  conv2 output row b needs the (zero-padded) conv1 rows 2b .. 2b+3 only, so the
 // conv1 output is never held whole: pass b of conv1 produces padded rows 2b+2 and 2b+3 and
 // stores them twice, as rows 2, 3 of the four-row buffer of band b and as rows 0, 1 of the
-// buffer of band b+1 (two buffers, used alternately); pass -1 primes band 0.  Every LDS offset
-// of the matrix A operand is then a compile-time constant relative to one per-lane base.  The
-// conv2 output overwrites the part of the image buffer that conv1 has already consumed.
+// buffer of band b+1 (two buffers, used alternately); pass -1 primes band 0.  The conv2
+// output overwrites the part of the image buffer that conv1 has already consumed.
 //
 // conv2 tiling.  The 16 rows of a matrix tile are 4 pooling windows x their 4 pixels, so
 // that the 4 accumulator registers of a lane (rows 4q..4q+3 of column n) are exactly one
 // pooling window of output channel n: max-pooling is three v_max on registers.  The
-// contraction index k = tap * 8 + channel; lane group q supplies k = 4 step + q, i.e.
-// input channel 4 (step & 1) + q of tap step >> 1, read from channel-major planes in LDS.
+// contraction index k = tap * 8 + channel, padded from 72 to 96 = 3 steps of 32 with zero
+// weights; lane group q supplies the 8 channels of tap 4 step + q: one 16-byte LDS read per
+// split term from the band buffer, which holds [term][row][column][channel] bfloat16.
+#include "bf16.h"
 #include "kernels.h"
 
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
 constexpr int kImgW = kHMax + 2;                     // padded image row (30)
 constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; its consumed part takes the conv2 output
-constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16)
-constexpr int kBandPlane = 4 * kBandW + 8;           // 72: four rows per channel plane; stride = 8 mod 32 banks
-constexpr int kBandFloats = kC1 * kBandPlane;        // 576 per band buffer
-constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2056 floats = 8,224 bytes per wave
-constexpr int kConvWavesMax = 16;
+constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
+constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as bfloat16
+constexpr int kBandRow = (kBandW + 1) * kPixBytes;   // 272 bytes: one pixel of padding between rows
+constexpr int kBandTerm = 4 * kBandRow;              // 1088 bytes: four rows of one split term
+constexpr int kBandBytes = 3 * kBandTerm;            // 3264 bytes per band buffer
+constexpr int kBandFloats = kBandBytes / 4;          // 816
+constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2536 floats = 10,144 bytes per wave
+constexpr int kConvWavesMax = 12;
 constexpr int kMaxCls = 16;
 constexpr int kMaxFeat = (kHMax / 4) * (kHMax / 4) * kC2;  // 784
 
@@ -61,9 +75,18 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// x = h + m + l with three bfloat16 terms; both subtractions are exact in fp32.
+__device__ __forceinline__ void split3(float x, __bf16& h, __bf16& m, __bf16& l) {
+  h = static_cast<__bf16>(x);
+  float r = x - static_cast<float>(h);
+  m = static_cast<__bf16>(r);
+  r -= static_cast<float>(m);
+  l = static_cast<__bf16>(r);
+}
+
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
 // (10 for the ten-class case, 16 for any n_cls <= 16 with zero padding).
-// kConvWaves: waves per workgroup (16 with ten classes, 12 when the padded dense weights take 49 KB).
+// kConvWaves: waves per workgroup (12 with ten classes, 10 when the padded dense weights take 49 KB).
 template <int NCS, int kConvWaves>
 __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -97,11 +120,21 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // zero the padded buffers once: borders stay zero, interiors are overwritten per image
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
 
-  // conv2 weights as matrix B operands: 18 steps, k = 4 step + q, column n
+  // conv2 weights as matrix B operands, w2b[term][step]: lane group q holds tap 4 step + q (zero
+  // beyond tap 8), element j = input channel j, column n; each weight split into three terms
   const int n = lane & 15, q = lane >> 4;
-  float w2r[18];
+  bf16x8 w2b[3][3];
 #pragma unroll
-  for (int st = 0; st < 18; ++st) w2r[st] = W2[(4 * st + q) * kC2 + n];
+  for (int st = 0; st < 3; ++st) {
+    const int tap = 4 * st + q;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float x = tap < 9 ? W2[(tap * kC1 + j) * kC2 + n] : 0.f;
+      __bf16 h, m, l;
+      split3(x, h, m, l);
+      w2b[0][st][j] = h, w2b[1][st][j] = m, w2b[2][st][j] = l;
+    }
+  }
   const float bias2 = b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
@@ -117,16 +150,22 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
   for (int c = 0; c < 4; ++c) bias1v[c] = b1[4 * c1_cg + c];
 
-  // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3
-  int a_off[2];
+  // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3,
+  // shifted by tap 4 step + q (the padding taps 9..11 re-read tap 8 against zero weights)
+  int a_off[2][3];  // bytes from the start of a band buffer
   {
     const int r = lane & 15, i = r & 3;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int wxA = min(4 * h + (r >> 2), H4 - 1);
-      a_off[h] = q * kBandPlane + (i >> 1) * kBandW + 2 * wxA + (i & 1);
+#pragma unroll
+      for (int st = 0; st < 3; ++st) {
+        const int tap = min(4 * st + q, 8), dy = tap / 3, dx = tap - 3 * dy;
+        a_off[h][st] = ((i >> 1) + dy) * kBandRow + (2 * wxA + (i & 1) + dx) * kPixBytes;
+      }
     }
   }
+  char* const bandb = reinterpret_cast<char*>(band);
 
   const int img_begin = blockIdx.x * a.imgs_per_chunk;
   const int img_end = min(a.B, img_begin + a.imgs_per_chunk);
@@ -193,30 +232,51 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) + bias1v[c], 0.f);
           }
         }
+        // three bfloat16 terms of the four channels: 8 bytes per term
+        uint2 term[3];
+        {
+          __bf16 t[3][4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) split3(v[c], t[0][c], t[1][c], t[2][c]);
+#pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const bf16x2_t lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
+            term[k] = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+          }
+        }
         // rows 2, 3 of this band's buffer and rows 0, 1 of the next band's buffer
-        float* cur = band + (b & 1) * kBandFloats + (4 * c1_cg) * kBandPlane + (2 + c1_rs) * kBandW + c1_wx + 1;
-        float* nxt = band + ((b + 1) & 1) * kBandFloats + (4 * c1_cg) * kBandPlane + c1_rs * kBandW + c1_wx + 1;
+        char* cur = bandb + (b & 1) * kBandBytes + (2 + c1_rs) * kBandRow + (c1_wx + 1) * kPixBytes + 8 * c1_cg;
+        char* nxt = bandb + ((b + 1) & 1) * kBandBytes + c1_rs * kBandRow + (c1_wx + 1) * kPixBytes + 8 * c1_cg;
         if (b >= 0) {
 #pragma unroll
-          for (int c = 0; c < 4; ++c) cur[c * kBandPlane] = v[c];
+          for (int k = 0; k < 3; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
         }
         if (b + 1 < H4) {
 #pragma unroll
-          for (int c = 0; c < 4; ++c) nxt[c * kBandPlane] = v[c];
+          for (int k = 0; k < 3; ++k) *reinterpret_cast<uint2*>(nxt + k * kBandTerm) = term[k];
         }
       }
       wave_sync();
       if (b < 0) continue;
 
       // ---- conv2 + ReLU + pool, band b: two independent tiles (windows 0..3 and 4..7 of the row) --
-      const float* bb = band + (b & 1) * kBandFloats;
+      const char* bb = bandb + (b & 1) * kBandBytes;
       floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int st = 0; st < 18; ++st) {
-        const int tap = st >> 1, dy = tap / 3, dx = tap - 3 * dy;
-        const int o = (4 * (st & 1)) * kBandPlane + dy * kBandW + dx;
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(bb[a_off[0] + o], w2r[st], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(bb[a_off[1] + o], w2r[st], acc1, 0, 0, 0);
+      for (int st = 0; st < 3; ++st) {
+        bf16x8 a0[3], a1[3];  // [term] of tile 0 and tile 1
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          a0[k] = *reinterpret_cast<const bf16x8*>(bb + a_off[0][st] + k * kBandTerm);
+          a1[k] = *reinterpret_cast<const bf16x8*>(bb + a_off[1][st] + k * kBandTerm);
+        }
+        // the six partial products, smallest first: l h', h l', m m', m h', h m', h h'
+        constexpr int ka[6] = {2, 0, 1, 1, 0, 0}, kb[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int t = 0; t < 6; ++t) {
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ka[t]], w2b[kb[t]][st], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[ka[t]], w2b[kb[t]][st], acc1, 0, 0, 0);
+        }
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n
       if (q < H4) a2[(b * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
@@ -298,10 +358,10 @@ int convnet_supported(const ConvShape& sh) {
   return EVO_OK;
 }
 
-// Workgroups per member: enough to fill the chip several times over, but no fewer than one
-// image per wave.
+// Workgroups per member: two per compute unit over the whole grid (one resident, one queued, so
+// that the per-workgroup staging of the weights is paid rarely), but no fewer than one image per wave.
 int convnet_chunks(const ConvShape&, int pop, int B) {
-  int chunks = (2048 + pop - 1) / pop;
+  int chunks = (512 + pop - 1) / pop;
   const int max_chunks = (B + kConvWavesMax - 1) / kConvWavesMax;
   if (chunks > max_chunks) chunks = max_chunks;
   if (chunks < 1) chunks = 1;
@@ -328,7 +388,7 @@ int launch_convnet_f32(const ConvShape& sh, const float* params, const float* im
   if (chunks <= 0) chunks = convnet_chunks(sh, pop, B);
   a.chunks = chunks;
   a.imgs_per_chunk = (B + chunks - 1) / chunks;
-  return sh.n_cls == 10 ? launch_conv<10, 16>(a, pop, s) : launch_conv<16, 12>(a, pop, s);
+  return sh.n_cls == 10 ? launch_conv<10, 12>(a, pop, s) : launch_conv<16, 10>(a, pop, s);
 }
 
 }  // namespace evo
