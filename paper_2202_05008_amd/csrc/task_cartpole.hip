@@ -3,26 +3,44 @@
 // state carried over the steps; all members start from identical observations).
 //
 // One workgroup owns one member; wave w owns hidden neurons 16 w .. 16 w + 15 of both hidden
-// layers, whose weights sit in its registers as matrix-core B operands for the whole episode.
-// The 16 roll-outs of the member are the 16 rows of v_mfma_f32_16x16x4_f32.  Every wave carries
-// the environment state of roll-out r in its lanes with lane % 16 == r and advances it itself
-// (a few dozen instructions), so observations never travel between waves; only the hidden
-// activations (LDS transpose between the layers) and the four partial sums of the output
+// layers, whose weights sit in its registers as matrix-core operands for the whole episode.
+// The 16 roll-outs of the member are the 16 rows (or columns) of a matrix tile.  Every wave
+// carries the environment state of roll-out r in its lanes with lane % 16 == r and advances it
+// itself (a few dozen instructions), so observations never travel between waves; only the
+// hidden activations (through LDS between the layers) and the four partial sums of the output
 // layer do.  Two workgroup barriers per step; nothing but the final return touches HBM.
 // Several members share a SIMD (one wave each), which hides the latency of the serial
 // per-step chain.
 //
-// Register layouts of v_mfma_f32_16x16x4_f32 (lane = 16 q + j):
-//   A[row j][k = q]   one float        B[k = q][col j]   one float
-//   D[row 4 q + i][col j], i = 0..3    four floats
-// The contraction index inside a layer may be permuted freely as long as A and B agree;
-// layer 2 uses k = (H/4) q + s at step s so that a lane reads H/4 consecutive floats.
+// Register layouts (lane = 16 q + j):
+//   v_mfma_f32_16x16x4_f32    A[row j][k = q], B[k = q][col j]: one float each
+//   v_mfma_f32_16x16x32_bf16  A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7: eight bfloat16 each
+//   both                      D[row 4 q + i][col j], i = 0..3: four floats
+//
+// With two hidden layers, layer 1 (K = 5) is computed transposed on the fp32 instruction
+// (rows = neurons, columns = roll-outs), so that a lane ends up with four consecutive neurons
+// of one roll-out: after tanh they are split exactly into three bfloat16 terms h + m + l and
+// stored with one 8-byte LDS write per term.  Layer 2 (K = H) then runs on the bf16 instruction
+// (16 cycles for 8192 multiply-adds against 32 cycles for 1024 of the fp32 one) with the six
+// partial products hh' + hm' + mh' + mm' + hl' + lh' accumulated in fp32; the three products
+// left out are below 2^-24 of the full one, so the layer keeps fp32 accuracy.
+#include "bf16.h"
 #include "kernels.h"
 #include "philox.h"
 
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// x = h + m + l with three bfloat16 terms; both subtractions are exact in fp32.
+__device__ __forceinline__ void split3(float x, __bf16& h, __bf16& m, __bf16& l) {
+  h = static_cast<__bf16>(x);
+  float r = x - static_cast<float>(h);
+  m = static_cast<__bf16>(r);
+  r -= static_cast<float>(m);
+  l = static_cast<__bf16>(r);
+}
 
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
@@ -101,7 +119,6 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-constexpr int kHStride = 68;  // LDS row stride of the hidden-activation transpose buffer
 
 // NT: hidden width 16 NT (NT waves); TWO: two hidden layers of that width; TANH: every activation
 // is tanh (the usual policy), which removes the per-value activation switch from the step loop.
@@ -110,8 +127,11 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const int act1 = TANH ? EVO_ACT_TANH : act1_rt, act2 = TANH ? EVO_ACT_TANH : act2_rt;
   const int act3 = TANH ? EVO_ACT_TANH : act3_rt;
   constexpr int H = 16 * NT;
-  constexpr int KS2 = H / 4;  // matrix-core steps of layer 2
-  __shared__ __attribute__((aligned(16))) float hbuf[16 * kHStride];
+  constexpr int KP = H < 32 ? 32 : H;      // contraction length of layer 2, padded to the instruction's 32
+  constexpr int KS2 = KP / 32;             // matrix-core steps of layer 2 per split term pair
+  constexpr int kRowB = (KP + 8) * 2;      // bytes of one roll-out's row of one term (16 bytes of padding)
+  constexpr int kTermB = 16 * kRowB;       // one term of the hidden activations: [roll-out][neuron] bfloat16
+  __shared__ __attribute__((aligned(16))) unsigned char hb[TWO ? 3 * kTermB : 16];
   __shared__ float part[NT][16];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -125,14 +145,27 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding)
   const float bias1 = theta[5 * H + col];
   const float* th2 = theta + 5 * H + H;
-  float w2[TWO ? KS2 : 1];
+  bf16x8 w2b[3][TWO ? KS2 : 1];  // [term][step]: element e is W2[32 step + 8 q + e][col]
+  float bias1t[4];               // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
   float bias2 = 0.f, w3, b3;
   if (TWO) {
 #pragma unroll
-    for (int s = 0; s < KS2; ++s) w2[s] = th2[(KS2 * q + s) * H + col];
+    for (int s = 0; s < KS2; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int k = 32 * s + 8 * q + e;
+        __bf16 h, m, l;
+        split3(k < H ? th2[k * H + col] : 0.f, h, m, l);
+        w2b[0][s][e] = h, w2b[1][s][e] = m, w2b[2][s][e] = l;
+      }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bias1t[i] = theta[5 * H + 16 * wave + 4 * q + i];
     bias2 = th2[H * H + col];
     w3 = th2[H * H + H + col];
     b3 = th2[H * H + H + H];
+    // columns H .. KP - 1 of the activation rows are never written and must read as zero
+    for (int i = threadIdx.x; i < 3 * kTermB / 4; i += 64 * NT) reinterpret_cast<uint32_t*>(hb)[i] = 0u;
+    __syncthreads();
   } else {
     w3 = th2[col];
     b3 = th2[H];
@@ -159,28 +192,46 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
       // ---- layer 1: observation (x, x_d, cos, sin, th_d) is the A operand directly -------------
       const float a0 = q == 0 ? s.x : (q == 1 ? s.xd : (q == 2 ? cs : sn));
       const float a1 = q == 0 ? s.thd : 0.f;
-      floatx4 acc = {bias1, bias1, bias1, bias1};
-      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, w1b, acc, 0, 0, 0);
       float p[4];
       if (TWO) {
+        // transposed: rows = this wave's neurons, columns = roll-outs
+        floatx4 acc = {bias1t[0], bias1t[1], bias1t[2], bias1t[3]};
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a, a0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1b, a1, acc, 0, 0, 0);
+        // neurons 16 wave + 4 q .. + 3 of roll-out j: three terms, 8 bytes each
+        {
+          __bf16 t[3][4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) hbuf[(4 * q + i) * kHStride + col] = act_apply(acc[i], act1);
-        __syncthreads();
-        // ---- layer 2: lane (row j, k group q) reads KS2 consecutive activations ----------------
-        float a2[KS2];
-        const float4* src = reinterpret_cast<const float4*>(hbuf + j * kHStride + KS2 * q);
+          for (int i = 0; i < 4; ++i) split3(act_apply(acc[i], act1), t[0][i], t[1][i], t[2][i]);
+          unsigned char* dst = hb + j * kRowB + (16 * wave + 4 * q) * 2;
 #pragma unroll
-        for (int c4 = 0; c4 < KS2 / 4; ++c4) {
-          const float4 v = src[c4];
-          a2[4 * c4 + 0] = v.x, a2[4 * c4 + 1] = v.y, a2[4 * c4 + 2] = v.z, a2[4 * c4 + 3] = v.w;
+          for (int k = 0; k < 3; ++k) {
+            const bf16x2_t lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
+            *reinterpret_cast<uint2*>(dst + k * kTermB) =
+                make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+          }
         }
+        __syncthreads();
+        // ---- layer 2: lane (row j, k group q) reads 8 consecutive activations per term and step ----
         floatx4 acc2 = {bias2, bias2, bias2, bias2};
+        const unsigned char* src = hb + j * kRowB + 16 * q;
 #pragma unroll
-        for (int s2 = 0; s2 < KS2; ++s2) acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[s2], w2[s2], acc2, 0, 0, 0);
+        for (int s2 = 0; s2 < KS2; ++s2) {
+          bf16x8 at[3];
+#pragma unroll
+          for (int k = 0; k < 3; ++k) at[k] = *reinterpret_cast<const bf16x8*>(src + k * kTermB + 64 * s2);
+          // the six partial products, smallest first: l h', h l', m m', m h', h m', h h'
+          constexpr int ka[6] = {2, 0, 1, 1, 0, 0}, kb[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+          for (int t = 0; t < 6; ++t)
+            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at[ka[t]], w2b[kb[t]][s2], acc2, 0, 0, 0);
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = act_apply(acc2[i], act2) * w3;
       } else {
+        floatx4 acc = {bias1, bias1, bias1, bias1};
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, w1b, acc, 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = act_apply(acc[i], act1) * w3;
       }
