@@ -72,7 +72,7 @@ typedef struct {
 
 typedef struct pgpe_state pgpe_state; /* host handle: config, t, pending (seed, pop), pointers */
 
-/* Bytes of device workspace a state needs (ranks, shaped fitness, pair weights). */
+/* Bytes of device workspace a state needs (ranks and shaped fitness). */
 size_t pgpe_workspace_bytes(const pgpe_config* cfg);
 
 /* Create a host handle around caller-owned device arrays mu, sigma, m, v (fp32[P] each),

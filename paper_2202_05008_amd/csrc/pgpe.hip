@@ -34,8 +34,6 @@ namespace evo {
 struct Workspace {
   float* shaped;   // [pop_max] utilities c_m
   uint32_t* rank;  // [pop_max]
-  float* w;        // [pop_max/2] pair weights of the mu gradient
-  float* u;        // [pop_max/2] pair weights of the sigma gradient
 };
 
 static inline size_t ws_bytes(int pop_max) { return (static_cast<size_t>(pop_max) * 3 * 4 + 255) & ~size_t(255); }
@@ -44,8 +42,6 @@ static inline Workspace ws_carve(void* base, int pop_max) {
   Workspace w;
   w.shaped = static_cast<float*>(base);
   w.rank = reinterpret_cast<uint32_t*>(w.shaped + pop_max);
-  w.w = reinterpret_cast<float*>(w.rank + pop_max);
-  w.u = w.w + pop_max / 2;
   return w;
 }
 
@@ -125,112 +121,44 @@ __device__ __forceinline__ uint32_t orderable(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-constexpr int kRankThreads = 1024;
+// Centered ranks by counting: the rank of member m is the number of 64-bit keys
+// (orderable fitness << 32 | member index) below its own.  Keys are unique, so the ranks are
+// exactly those of a stable sort, and the count needs no sort at all: a workgroup stages the
+// orderable words of the whole population in LDS (at most 16 KB) and ranks 16 members, sixteen
+// lanes per member, each lane comparing against every sixteenth key (consecutive LDS words for
+// the sixteen lanes, the same words for the four members of a wavefront: no bank conflicts).
+// pop / 16 workgroups run side by side, so the stage costs a few microseconds at any pop.
+constexpr int kRankThreads = 256;
+constexpr int kRankMembers = 16;
 
-// One workgroup: bitonic sort of 64-bit keys (orderable fitness << 32 | member index).  Keys are
-// unique, so the permutation is unique and the ranks are exact.  Then the shaped utilities c,
-// their mean b (fp64, fixed tree) and the pair weights w, u.
-//
-// The keys live in registers: thread t owns elements t, t + 1024, ... (at most four).  A compare
-// distance j >= 1024 pairs two registers of one thread, j < 64 pairs two lanes of one wavefront
-// (cross-lane shuffle), and only 64 <= j < 1024 goes through LDS with workgroup barriers: 18 of
-// the 78 steps at 4096 keys.
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask) {
-  const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), mask, 64);
-  const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), mask, 64);
-  return (static_cast<uint64_t>(hi) << 32) | lo;
-}
-
-__global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int npow2,
-                                                            int shaping, uint32_t* __restrict__ rank_out,
-                                                            float* __restrict__ shaped_out,
-                                                            float* __restrict__ w_out, float* __restrict__ u_out) {
-  __shared__ uint64_t keys[EVO_POP_MAX];
-  __shared__ float cs[EVO_POP_MAX];
-  __shared__ double red[kRankThreads];
+__global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int shaping,
+                                                            uint32_t* __restrict__ rank_out,
+                                                            float* __restrict__ shaped_out) {
+  __shared__ uint32_t ord[EVO_POP_MAX];
   const int tid = threadIdx.x;
-  constexpr int kMaxOwn = EVO_POP_MAX / kRankThreads;  // 4
-  const int own = npow2 > kRankThreads ? npow2 / kRankThreads : 1;
-  uint64_t e[kMaxOwn];
-#pragma unroll
-  for (int m = 0; m < kMaxOwn; ++m) {
-    const int i = tid + kRankThreads * m;
-    e[m] = (m < own && i < pop) ? (static_cast<uint64_t>(orderable(fitness[i])) << 32) | static_cast<uint32_t>(i)
-                                : ~uint64_t(0);
-  }
-  for (int k = 2; k <= npow2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      if (j >= kRankThreads) {
-        // both elements in this thread's registers: m and m ^ (j / 1024)
-        const int dm = j / kRankThreads;
-#pragma unroll
-        for (int m = 0; m < kMaxOwn; ++m) {
-          const int pm = m ^ dm;
-          if (m < own && pm > m && pm < kMaxOwn) {
-            const int i = tid + kRankThreads * m;
-            const bool ascending = (i & k) == 0;
-            const uint64_t x = e[m], y = e[pm];
-            if ((x > y) == ascending) {
-              e[m] = y;
-              e[pm] = x;
-            }
-          }
-        }
-      } else {
-        const bool via_lds = j >= 64;
-        if (via_lds) {
-#pragma unroll
-          for (int m = 0; m < kMaxOwn; ++m)
-            if (m < own) keys[tid + kRankThreads * m] = e[m];
-          __syncthreads();
-        }
-#pragma unroll
-        for (int m = 0; m < kMaxOwn; ++m) {
-          if (m < own) {
-            const int i = tid + kRankThreads * m;
-            const uint64_t other = via_lds ? keys[i ^ j] : shfl_xor_u64(e[m], j);
-            // ascending pair: the lower index keeps the smaller key; descending: the larger one
-            const bool keep_min = ((i & j) == 0) == ((i & k) == 0);
-            const bool take = keep_min ? other < e[m] : other > e[m];
-            e[m] = take ? other : e[m];
-          }
-        }
-        if (via_lds) __syncthreads();
-      }
-    }
-  }
-#pragma unroll
-  for (int m = 0; m < kMaxOwn; ++m)
-    if (m < own && tid + kRankThreads * m < npow2) keys[tid + kRankThreads * m] = e[m];
+  for (int i = tid; i < pop; i += kRankThreads) ord[i] = orderable(fitness[i]);
   __syncthreads();
-  const float denom = static_cast<float>(2 * (pop - 1));
-  for (int p = tid; p < pop; p += kRankThreads) {
-    const uint32_t member = static_cast<uint32_t>(keys[p]);
-    const float c = static_cast<float>(2 * p - (pop - 1)) / denom;  // one correctly rounded divide
-    if (rank_out) rank_out[member] = static_cast<uint32_t>(p);
-    cs[member] = c;
+  const int part = tid & 15;
+  const int m = blockIdx.x * kRankMembers + (tid >> 4);
+  const int mc = min(m, pop - 1);
+  const uint64_t key_m = (static_cast<uint64_t>(ord[mc]) << 32) | static_cast<uint32_t>(mc);
+  uint32_t count = 0;
+#pragma unroll 8
+  for (int j = part; j < pop; j += 16) {
+    const uint64_t key_j = (static_cast<uint64_t>(ord[j]) << 32) | static_cast<uint32_t>(j);
+    count += key_j < key_m ? 1u : 0u;
   }
-  __syncthreads();
-  if (!shaping) {
-    for (int i = tid; i < pop; i += kRankThreads) cs[i] = fitness[i];
-    __syncthreads();
-  }
-  double acc = 0.0;
-  for (int i = tid; i < pop; i += kRankThreads) acc += static_cast<double>(cs[i]);
-  red[tid] = acc;
-  __syncthreads();
-  for (int s = kRankThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) red[tid] += red[tid + s];
-    __syncthreads();
-  }
-  const double b = red[0] / static_cast<double>(pop);
-  for (int i = tid; i < pop; i += kRankThreads)
-    if (shaped_out) shaped_out[i] = cs[i];
-  if (w_out) {
-    for (int k = tid; k < pop / 2; k += kRankThreads) {
-      const double cp = cs[2 * k], cm = cs[2 * k + 1];
-      w_out[k] = static_cast<float>(0.5 * (cp - cm));
-      u_out[k] = static_cast<float>(0.5 * (cp + cm) - b);
+  // sum over the sixteen lanes of the member (integer adds: any order gives the same count)
+  count += __shfl_xor(count, 1, 64);
+  count += __shfl_xor(count, 2, 64);
+  count += __shfl_xor(count, 4, 64);
+  count += __shfl_xor(count, 8, 64);
+  if (part == 0 && m < pop) {
+    if (rank_out) rank_out[m] = count;
+    if (shaped_out) {
+      // one correctly rounded divide of two exactly representable integers
+      const float c = static_cast<float>(2 * static_cast<int>(count) - (pop - 1)) / static_cast<float>(2 * (pop - 1));
+      shaped_out[m] = shaping ? c : fitness[m];
     }
   }
 }
@@ -245,8 +173,7 @@ struct TellArgs {
   float* vs;
   float* gmu_out;  // gradient-only mode
   float* gsg_out;
-  const float* w;
-  const float* u;
+  const float* shaped;  // utilities c[pop] (centered ranks or raw fitness)
   int P, nquads, N, KS;
   uint32_t gen, key0, key1;
   float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2;
@@ -273,11 +200,26 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
   const int ql = tid % QPB;
   const int ks = tid / QPB;
   const int q = blockIdx.x * QPB + ql;
-  for (int i = tid; i < a.N; i += 256) {
-    w_s[i] = a.w[i];
-    u_s[i] = a.u[i];
+  // pair weights from the utilities: b = mean(c) in fp64 with a fixed tree (every workgroup
+  // computes the same bits), w_k = (c[2k] - c[2k+1]) / 2, u_k = (c[2k] + c[2k+1]) / 2 - b
+  {
+    double* red = reinterpret_cast<double*>(part);  // 256 doubles: fits the partial-sum area or its minimum
+    double acc = 0.0;
+    for (int i = tid; i < 2 * a.N; i += 256) acc += static_cast<double>(a.shaped[i]);
+    red[tid] = acc;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if (tid < s) red[tid] += red[tid + s];
+      __syncthreads();
+    }
+    const double b = red[0] / static_cast<double>(2 * a.N);
+    for (int k = tid; k < a.N; k += 256) {
+      const double cp = a.shaped[2 * k], cm = a.shaped[2 * k + 1];
+      w_s[k] = static_cast<float>(0.5 * (cp - cm));
+      u_s[k] = static_cast<float>(0.5 * (cp + cm) - b);
+    }
+    __syncthreads();
   }
-  __syncthreads();
   float A[4] = {0.f, 0.f, 0.f, 0.f}, B[4] = {0.f, 0.f, 0.f, 0.f};
   if (q < a.nquads) {
     for (int k = ks; k < a.N; k += a.KS) {
@@ -369,16 +311,9 @@ __global__ __launch_bounds__(256) void philox_words_kernel(uint32_t gen, uint32_
   }
 }
 
-static int next_pow2(int x) {
-  int p = 1;
-  while (p < x) p <<= 1;
-  return p;
-}
-
-static int launch_rank(const float* fitness, int pop, int shaping, uint32_t* rank, float* shaped, float* w,
-                       float* u, hipStream_t s) {
-  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(kRankThreads), 0, s, fitness, pop, next_pow2(pop), shaping, rank,
-                     shaped, w, u);
+static int launch_rank(const float* fitness, int pop, int shaping, uint32_t* rank, float* shaped, hipStream_t s) {
+  hipLaunchKernelGGL(rank_kernel, dim3((pop + kRankMembers - 1) / kRankMembers), dim3(kRankThreads), 0, s, fitness,
+                     pop, shaping, rank, shaped);
   return check_launch("rank_kernel");
 }
 
@@ -399,17 +334,19 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   const pgpe_config& c = st->cfg;
   const int pop = st->pop, N = pop / 2, P = c.P;
   Workspace ws = ws_carve(st->work, c.pop_max);
-  int rc = launch_rank(fitness, pop, c.shaping, ws.rank, ws.shaped, ws.w, ws.u, s);
+  int rc = launch_rank(fitness, pop, c.shaping, ws.rank, ws.shaped, s);
   if (rc) return rc;
   TellArgs a;
   a.mu = st->mu, a.sigma = st->sigma, a.m = st->m, a.v = st->v;
   a.ms = st->aux, a.vs = st->aux ? st->aux + P : nullptr;
   a.gmu_out = gmu, a.gsg_out = gsg;
-  a.w = ws.w, a.u = ws.u;
+  a.shaped = ws.shaped;
   a.P = P, a.nquads = (P + 3) / 4, a.N = N;
-  // split the pair loop KS ways when there are too few parameter quads to fill the chip
+  // split the pair loop KS ways until about 2^19 threads (eight waves per SIMD) are in flight:
+  // measured, that is where the time stops falling, and beyond 64 slices the LDS reduction of
+  // the partial sums costs more than it gains
   int KS = 1;
-  while (KS < 256 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < 131072) KS *= 2;
+  while (KS < 64 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < 524288) KS *= 2;
   a.KS = KS;
   a.gen = st->t, a.key0 = static_cast<uint32_t>(st->seed), a.key1 = static_cast<uint32_t>(st->seed >> 32);
   a.inv_n = 1.0f / static_cast<float>(N);
@@ -419,7 +356,7 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   a.bc2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta2), static_cast<double>(st->t))));
   const int QPB = 256 / KS;
   const unsigned blocks = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
-  const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + (KS > 1 ? 256 * 8 : 0));
+  const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + 256 * 8);  // w, u, partial sums / mean tree
   if (gmu) {
     hipLaunchKernelGGL(tell_kernel<2>, dim3(blocks), dim3(256), shmem, s, a);
   } else if (c.sigma_rule == 0) {
@@ -545,7 +482,7 @@ extern "C" int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t
   EVO_REQUIRE(fitness_dev && rank_dev && shaped_dev, EVO_ERR_ARG, "evo_centered_rank: null argument");
   EVO_REQUIRE(pop >= 2 && pop <= EVO_POP_MAX, EVO_ERR_ARG, "evo_centered_rank: pop must be in [2, %d] (got %d)",
               EVO_POP_MAX, pop);
-  return launch_rank(fitness_dev, pop, 1, rank_dev, shaped_dev, nullptr, nullptr, as_stream(stream));
+  return launch_rank(fitness_dev, pop, 1, rank_dev, shaped_dev, as_stream(stream));
 }
 
 static int philox_hook(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block0, uint32_t nblocks, uint32_t tag,

@@ -33,9 +33,11 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return u32x4{c0, c1, c2, c3};
 }
 
-// (2 (x >> 9) + 1) 2^-24: an odd multiple of 2^-24 in (0,1); the conversion is exact.
+// (2 (x >> 9) + 1) 2^-24: an odd multiple of 2^-24 in (0,1).  Built without an integer
+// conversion: the 23 bits become the fraction of a float f in [1, 2), and f - (1 - 2^-24) is that
+// value exactly (the difference is an odd multiple of 2^-24 below 1, hence representable).
 __device__ __forceinline__ float unit_open(uint32_t x) {
-  return static_cast<float>(2u * (x >> 9) + 1u) * 5.9604644775390625e-08f;
+  return __uint_as_float((x >> 9) | 0x3F800000u) - 0.999999940395355224609375f;
 }
 
 // Box-Muller on two words: za = r cos(2 pi ub), zb = r sin(2 pi ub), r = sqrt(-2 ln ua).

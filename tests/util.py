@@ -31,6 +31,19 @@ def assert_scalar_rel(got, ref, tol=1e-5, what=""):
     assert worst <= tol, "%s: worst relative error %.3g exceeds %.1g" % (what, worst, tol)
 
 
+def adam_ill_conditioned(g, eps=1e-8):
+    """Elements of an ORACLE gradient g on which Adam's early, sign-like steps are ill-conditioned.
+
+    The gradient itself is gated at 1e-5 rms(g) (absolute).  Through the first Adam step
+    mu += lr g / (|g| + eps) that allowance moves mu by lr eps / (|g| + eps)^2 * 1e-5 rms(g), which
+    exceeds the 1e-5 lr allowed on mu exactly where eps rms(g) > |g| (|g| + eps).  Those elements
+    (and anything below 1e-4 rms(g), the fp32 noise floor of the sums) are compared on the gradient
+    only.  Later steps are less sensitive, so the first-step set is used for every step."""
+    g = np.abs(np.asarray(g, dtype=np.float64))
+    rms = float(np.sqrt(np.mean(g * g))) if g.size else 0.0
+    return (g < 1e-4 * rms) | (eps * rms > g * (g + eps))
+
+
 def dev(x, dtype=None):
     import torch
     t = torch.from_numpy(np.ascontiguousarray(x))
