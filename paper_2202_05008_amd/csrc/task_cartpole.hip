@@ -44,6 +44,7 @@ __device__ __forceinline__ void split3(float x, __bf16& h, __bf16& m, __bf16& l)
 
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
+  float inv_2l;  // 1 / (2 l), rounded once on the host
 };
 
 struct CartpoleArgs {
@@ -90,8 +91,10 @@ __device__ __forceinline__ CpState cartpole_advance(const CpState& s, float sn, 
                                                     const CartpoleConst& c, float& sn_new, float& cs_new) {
   const float Fe = c.fscale * a - c.b * s.xd;
   const float D = 4.0f * (c.M + c.m) - 3.0f * c.m * cs * cs;
-  const float xdd = (4.0f * Fe + 2.0f * c.m * c.l * s.thd * s.thd * sn - 3.0f * c.m * c.g * sn * cs) / D;
-  const float thdd = 3.0f * (c.g * sn - xdd * cs) / (2.0f * c.l);
+  // the hardware reciprocal is within one ulp; D >= 4 M + m > 0
+  const float xdd = (4.0f * Fe + 2.0f * c.m * c.l * s.thd * s.thd * sn - 3.0f * c.m * c.g * sn * cs) *
+                    __builtin_amdgcn_rcpf(D);
+  const float thdd = 3.0f * (c.g * sn - xdd * cs) * c.inv_2l;
   CpState n;
   n.x = s.x + c.dt * s.xd;
   n.xd = s.xd + c.dt * xdd;
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(256) void cartpole_step_kernel(CartpoleConst c, con
 }
 
 static CartpoleConst make_const(const float* cp) {
-  return CartpoleConst{cp[0], cp[1], cp[2], cp[3], cp[4], cp[5], cp[6], cp[7]};
+  return CartpoleConst{cp[0], cp[1], cp[2], cp[3], cp[4], cp[5], cp[6], cp[7], 1.0f / (2.0f * cp[3])};
 }
 
 int cartpole_supported(const MlpShape& sh, int n_rollouts) {
