@@ -34,7 +34,8 @@
 // pooling window of output channel n: max-pooling is three v_max on registers.  The
 // contraction index k = tap * 8 + channel, padded from 72 to 96 = 3 steps of 32 with zero
 // weights; lane group q supplies the 8 channels of tap 4 step + q: one 16-byte LDS read per
-// split term from the band buffer, which holds [term][row][column][channel] bfloat16.
+// split term from the band buffer, which holds [term][row pair][column][row parity][channel]
+// bfloat16.
 #include "bf16.h"
 #include "kernels.h"
 
@@ -49,11 +50,18 @@ constexpr int kImgW = kHMax + 2;                     // padded image row (30)
 constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; its consumed part takes the conv2 output
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
 constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as bfloat16
-constexpr int kBandRow = (kBandW + 1) * kPixBytes;   // 272 bytes: one pixel of padding between rows
-constexpr int kBandTerm = 4 * kBandRow;              // 1088 bytes: four rows of one split term
-constexpr int kBandBytes = 3 * kBandTerm;            // 3264 bytes per band buffer
-constexpr int kBandFloats = kBandBytes / 4;          // 816
-constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2536 floats = 10,144 bytes per wave
+constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 2a+1, interleaved pixel by pixel
+constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
+constexpr int kBandBytes = 3 * kBandTerm;            // 3072 bytes per band buffer
+constexpr int kBandFloats = kBandBytes / 4;          // 768
+constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2440 floats = 9,760 bytes per wave
+
+// Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
+// of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
+// a matrix A operand (4 windows x 2 x 2 pixels, any tap) fall on 64 different LDS banks.
+__device__ __forceinline__ constexpr int band_off(int row, int col) {
+  return (row >> 1) * kBandRowPair + col * 2 * kPixBytes + (row & 1) * kPixBytes;
+}
 constexpr int kConvWavesMax = 12;
 constexpr int kMaxCls = 16;
 constexpr int kMaxFeat = (kHMax / 4) * (kHMax / 4) * kC2;  // 784
@@ -73,6 +81,27 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Reductions over the 16 lanes of a row with DPP moves (xor 1, xor 2, half-row mirror, row mirror):
+// no LDS round trip, every lane of the row ends with the result, the order is fixed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141>(v);  // row_half_mirror
+  v += dpp_mov<0x140>(v);  // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_mov<0xB1>(v));
+  v = fmaxf(v, dpp_mov<0x4E>(v));
+  v = fmaxf(v, dpp_mov<0x141>(v));
+  v = fmaxf(v, dpp_mov<0x140>(v));
+  return v;
 }
 
 // x = h + m + l with three bfloat16 terms; both subtractions are exact in fp32.
@@ -161,7 +190,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
         const int tap = min(4 * st + q, 8), dy = tap / 3, dx = tap - 3 * dy;
-        a_off[h][st] = ((i >> 1) + dy) * kBandRow + (2 * wxA + (i & 1) + dx) * kPixBytes;
+        a_off[h][st] = band_off((i >> 1) + dy, 2 * wxA + (i & 1) + dx);
       }
     }
   }
@@ -245,8 +274,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
           }
         }
         // rows 2, 3 of this band's buffer and rows 0, 1 of the next band's buffer
-        char* cur = bandb + (b & 1) * kBandBytes + (2 + c1_rs) * kBandRow + (c1_wx + 1) * kPixBytes + 8 * c1_cg;
-        char* nxt = bandb + ((b + 1) & 1) * kBandBytes + c1_rs * kBandRow + (c1_wx + 1) * kPixBytes + 8 * c1_cg;
+        char* cur = bandb + (b & 1) * kBandBytes + band_off(2 + c1_rs, c1_wx + 1) + 8 * c1_cg;
+        char* nxt = bandb + ((b + 1) & 1) * kBandBytes + band_off(c1_rs, c1_wx + 1) + 8 * c1_cg;
         if (b >= 0) {
 #pragma unroll
           for (int k = 0; k < 3; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
@@ -324,16 +353,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       // cross-entropy over the 16 lanes of a row (classes beyond n_cls count as -inf)
       const int y = a.labels[im];  // a label outside [0, n_cls) contributes logit 0
       const float lv = cls < n_cls ? logit : -INFINITY;
-      float mx = lv;
-#pragma unroll
-      for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-      float se = cls < n_cls ? expf(lv - mx) : 0.f;
-      float picked = cls == y ? lv : 0.f;
-#pragma unroll
-      for (int off = 8; off > 0; off >>= 1) {
-        se += __shfl_xor(se, off, 64);
-        picked += __shfl_xor(picked, off, 64);
-      }
+      const float mx = row16_max(lv);
+      const float se = row16_sum(cls < n_cls ? expf(lv - mx) : 0.f);
+      const float picked = row16_sum(cls == y ? lv : 0.f);
       loss_sum += (mx + logf(se)) - picked;
     }
     wave_sync();
