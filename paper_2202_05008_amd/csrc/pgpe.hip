@@ -112,6 +112,33 @@ __global__ __launch_bounds__(256) void ask_kernel(const float* __restrict__ mu, 
   }
 }
 
+// bfloat16 population with P a multiple of 8: one thread owns eight consecutive parameters (two
+// Philox counters) of one pair, so that each row takes one 16-byte streaming store per thread.
+__global__ __launch_bounds__(256) void ask_bf16x8_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
+                                                         uint16_t* __restrict__ params, int P, int noct,
+                                                         uint32_t gen, uint32_t key0, uint32_t key1) {
+  const int o = blockIdx.x * 256 + threadIdx.x;
+  if (o >= noct) return;
+  const int col = o * 8, k = blockIdx.y;
+  const float4 ma = *reinterpret_cast<const float4*>(mu + col), mb = *reinterpret_cast<const float4*>(mu + col + 4);
+  const float4 sa = *reinterpret_cast<const float4*>(sigma + col), sb = *reinterpret_cast<const float4*>(sigma + col + 4);
+  const float mu8[8] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w};
+  const float sg8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+  float z[8];
+  philox_normal4(static_cast<uint32_t>(2 * o), static_cast<uint32_t>(k), gen, EVO_TAG_NOISE, key0, key1, z);
+  philox_normal4(static_cast<uint32_t>(2 * o + 1), static_cast<uint32_t>(k), gen, EVO_TAG_NOISE, key0, key1, z + 4);
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 plus, minus;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    plus[i] = pack_bf16x2(fmaf(sg8[2 * i], z[2 * i], mu8[2 * i]), fmaf(sg8[2 * i + 1], z[2 * i + 1], mu8[2 * i + 1]));
+    minus[i] = pack_bf16x2(fmaf(-sg8[2 * i], z[2 * i], mu8[2 * i]), fmaf(-sg8[2 * i + 1], z[2 * i + 1], mu8[2 * i + 1]));
+  }
+  uint16_t* row = params + static_cast<size_t>(2 * k) * P + col;
+  __builtin_nontemporal_store(plus, reinterpret_cast<u32x4*>(row));
+  __builtin_nontemporal_store(minus, reinterpret_cast<u32x4*>(row + P));
+}
+
 // ---- centered ranks and pair weights ------------------------------------------------------
 // fp32 bits -> u32 that orders like the float: -0 counts as +0, NaN sorts lowest.
 __device__ __forceinline__ uint32_t orderable(float f) {
@@ -448,6 +475,11 @@ extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params
   if (dtype == EVO_F32) {
     hipLaunchKernelGGL(ask_kernel<float>, grid, dim3(256), 0, s, st->mu, st->sigma,
                        static_cast<float*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
+  } else if ((P & 7) == 0) {
+    const int noct = P / 8;
+    hipLaunchKernelGGL(ask_bf16x8_kernel, dim3(static_cast<unsigned>((noct + 255) / 256), static_cast<unsigned>(N)),
+                       dim3(256), 0, s, st->mu, st->sigma, static_cast<uint16_t*>(params_dev), P, noct, st->t, k0,
+                       k1);
   } else {
     hipLaunchKernelGGL(ask_kernel<uint16_t>, grid, dim3(256), 0, s, st->mu, st->sigma,
                        static_cast<uint16_t*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
