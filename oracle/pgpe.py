@@ -11,14 +11,17 @@ perturbations eps = sigma * z, centered-rank fitness shaping and an Adam ascent 
   tell:  b = mean(c);  w_k = (c[2k] - c[2k+1]) / 2;  u_k = (c[2k] + c[2k+1]) / 2 - b
          g_mu    = sigma / N * sum_k w_k z_k
          g_sigma = sigma / N * sum_k u_k (z_k^2 - 1)
-         Adam ascent on mu (bias-corrected, eps outside the square root, t starts at 1)
+         Adam ascent on mu (bias-corrected, eps outside the square root, t starts at 1); or, by
+         cfg.optimizer, ClipUp (the optimizer cited with PGPE in Section 5: velocity of bounded
+         norm fed by the normalised gradient) or plain momentum ascent
          sigma: rule 0: sigma += clip(lr_sigma * g_sigma, -c_max sigma, +c_max sigma)
                 rule 1: Adam ascent with its own moments, then sigma = max(sigma, 1e-8)
 
 All arithmetic is fp64 on fp32-representable inputs; state arrays are rounded to fp32
 after every tell because that is the precision they are stored in.
 Pins: tests/test_oracle_pgpe.py (brute force on tiny populations, closed-form expected
-gradients, pair-swap / shift identities, Adam closed forms, sphere convergence).
+gradients, pair-swap / shift identities, Adam closed forms, ClipUp / momentum closed forms
+and a library optimizer, sphere convergence).
 """
 from dataclasses import dataclass, field
 import numpy as np
@@ -41,11 +44,15 @@ class PGPEConfig:
     eps: float = 1e-8
     sigma_rule: int = 0     # 0 clipped ascent, 1 Adam
     shaping: int = 1        # 1 centered ranks, 0 raw fitness
+    optimizer: int = 0      # update of mu: 0 Adam, 1 ClipUp, 2 momentum ascent (velocity kept in m)
+    momentum: float = 0.9   # ClipUp / momentum ascent
+    max_speed: float = 0.02  # ClipUp: bound on the norm of the velocity (customarily 2 lr_mu)
 
     def __post_init__(self):
         # the hyper-parameters cross the library boundary as fp32: the oracle computes in fp64 on
         # those fp32 values (e.g. 1 - beta2 is taken from float32(0.999), not from 0.999)
-        for name in ("sigma_init", "lr_mu", "lr_sigma", "sigma_max_change", "beta1", "beta2", "eps"):
+        for name in ("sigma_init", "lr_mu", "lr_sigma", "sigma_max_change", "beta1", "beta2", "eps", "momentum",
+                     "max_speed"):
             setattr(self, name, float(np.float32(getattr(self, name))))
 
 
@@ -165,6 +172,25 @@ def adam_ascent(x, m, v, g, lr, beta1, beta2, eps, t):
     return x + lr * m_hat / (np.sqrt(v_hat) + eps), m, v
 
 
+def clipup_ascent(x, vel, g, step, momentum, max_speed):
+    """One ClipUp step that INCREASES the objective (Toklu, Liskowski, Srivastava 2020): the
+    velocity takes momentum * velocity + step * g / |g| (only the direction of the gradient
+    enters), is scaled back to norm max_speed if longer, and is added to x.  Returns (x, vel)."""
+    g = np.asarray(g, dtype=np.float64)
+    norm = np.sqrt(np.sum(g * g))
+    vel = momentum * vel + (step * g / norm if norm > 0.0 else 0.0)
+    speed = np.sqrt(np.sum(vel * vel))
+    if speed > max_speed:
+        vel = vel * (max_speed / speed)
+    return x + vel, vel
+
+
+def momentum_ascent(x, vel, g, lr, momentum):
+    """Heavy-ball ascent: velocity = momentum * velocity + lr * g; x += velocity.  Returns (x, vel)."""
+    vel = momentum * vel + lr * np.asarray(g, dtype=np.float64)
+    return x + vel, vel
+
+
 def utilities(state, fitness):
     f = np.asarray(fitness, dtype=np.float32)
     return centered_rank(f)[1] if state.cfg.shaping == 1 else f
@@ -194,8 +220,15 @@ def tell(state, fitness, chunk=1 << 15, return_grads=False):
                                  philox.TAG_NOISE).reshape(N, -1)[:, lo - lo4: hi - lo4]
         g_mu[lo:hi] = sg[lo:hi] * (w @ z) / N
         g_sg[lo:hi] = sg[lo:hi] * (u @ (z * z - 1.0)) / N
-    mu, m, v = adam_ascent(state.mu.astype(np.float64), state.m.astype(np.float64), state.v.astype(np.float64),
-                           g_mu, cfg.lr_mu, cfg.beta1, cfg.beta2, cfg.eps, t)
+    mu0, m0, v = state.mu.astype(np.float64), state.m.astype(np.float64), state.v.astype(np.float64)
+    if cfg.optimizer == 0:
+        mu, m, v = adam_ascent(mu0, m0, v, g_mu, cfg.lr_mu, cfg.beta1, cfg.beta2, cfg.eps, t)
+    elif cfg.optimizer == 1:
+        mu, m = clipup_ascent(mu0, m0, g_mu, cfg.lr_mu, cfg.momentum, cfg.max_speed)
+    elif cfg.optimizer == 2:
+        mu, m = momentum_ascent(mu0, m0, g_mu, cfg.lr_mu, cfg.momentum)
+    else:
+        raise ValueError("optimizer must be 0 (Adam), 1 (ClipUp) or 2 (momentum)")
     if cfg.sigma_rule == 0:
         lim = cfg.sigma_max_change * sg
         new_sg = sg + np.clip(cfg.lr_sigma * g_sg, -lim, lim)

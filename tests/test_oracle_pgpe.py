@@ -264,3 +264,75 @@ def test_pgpe_converges_on_sphere():
     assert hist[0] < -40 and hist[-1] > -0.5
     quart = [np.mean(hist[i:i + 50]) for i in range(0, 200, 50)]
     assert quart[0] < quart[1] < quart[2] <= quart[3] + 0.2
+
+
+def test_clipup_closed_forms():
+    """ClipUp pins: first step has length `step` along g; the speed never exceeds max_speed and a
+    constant gradient drives it to min(step / (1 - momentum), max_speed); only the direction of the
+    gradient matters; a zero gradient only lets the velocity decay."""
+    rng = np.random.default_rng(11)
+    g = rng.standard_normal(50)
+    x0 = rng.standard_normal(50)
+    x1, v1 = pgpe.clipup_ascent(x0, np.zeros(50), g, 0.01, 0.9, 0.02)
+    np.testing.assert_allclose(x1 - x0, 0.01 * g / np.linalg.norm(g), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(np.linalg.norm(v1), 0.01, rtol=1e-12)
+    # scale invariance (any positive factor) and sign equivariance
+    x1b, v1b = pgpe.clipup_ascent(x0, np.zeros(50), 7.0 * g, 0.01, 0.9, 0.02)
+    np.testing.assert_allclose(v1b, v1, rtol=1e-12, atol=1e-18)
+    _, v1c = pgpe.clipup_ascent(x0, np.zeros(50), -g, 0.01, 0.9, 0.02)
+    np.testing.assert_allclose(v1c, -v1, rtol=1e-12, atol=1e-18)
+    # constant gradient: unclipped speed is the geometric sum step (1 - m^T) / (1 - m); clipped at max_speed
+    for max_speed, want in ((1.0, 0.01 * (1 - 0.9 ** 40) / 0.1), (0.02, 0.02)):
+        x, v = x0.copy(), np.zeros(50)
+        for _ in range(40):
+            x, v = pgpe.clipup_ascent(x, v, g, 0.01, 0.9, max_speed)
+            assert np.linalg.norm(v) <= max_speed * (1 + 1e-12)
+        np.testing.assert_allclose(np.linalg.norm(v), want, rtol=1e-10)
+        np.testing.assert_allclose(v / np.linalg.norm(v), g / np.linalg.norm(g), rtol=1e-9, atol=1e-12)
+    # zero gradient: no division by zero, the velocity decays by the momentum
+    x2, v2 = pgpe.clipup_ascent(x1, v1, np.zeros(50), 0.01, 0.9, 0.02)
+    np.testing.assert_allclose(v2, 0.9 * v1, rtol=1e-15)
+    np.testing.assert_allclose(x2, x1 + 0.9 * v1, rtol=1e-15)
+    # the clip is a projection: a velocity that would be three times too fast comes out at max_speed, same direction
+    _, v3 = pgpe.clipup_ascent(x0, np.zeros(50), g, 0.06, 0.9, 0.02)
+    np.testing.assert_allclose(v3, 0.02 * g / np.linalg.norm(g), rtol=1e-12, atol=1e-18)
+
+
+def test_momentum_ascent_closed_form_and_torch():
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal(20)
+    x, v = np.zeros(20), np.zeros(20)
+    for T in range(1, 8):
+        x, v = pgpe.momentum_ascent(x, v, g, 0.05, 0.9)
+        np.testing.assert_allclose(v, 0.05 * g * (1 - 0.9 ** T) / 0.1, rtol=1e-12)
+    # torch's SGD keeps the velocity before the learning rate: identical trajectory for a constant rate
+    p = torch.zeros(20, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=0.05, momentum=0.9, maximize=True)
+    x, v = np.zeros(20), np.zeros(20)
+    for it in range(5):
+        gi = rng.standard_normal(20)
+        p.grad = torch.from_numpy(gi.copy())
+        opt.step()
+        x, v = pgpe.momentum_ascent(x, v, gi, 0.05, 0.9)
+        np.testing.assert_allclose(p.detach().numpy(), x, rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("optimizer", [1, 2])
+def test_tell_with_other_optimizers_uses_the_same_gradient(optimizer):
+    P, pop = 40, 8
+    mu0 = np.linspace(-1, 1, P).astype(np.float32)
+    a = pgpe.PGPEState.create(pgpe.PGPEConfig(P=P, pop_max=pop), mu0)
+    b = pgpe.PGPEState.create(pgpe.PGPEConfig(P=P, pop_max=pop, optimizer=optimizer), mu0)
+    f = np.random.default_rng(3).standard_normal(pop).astype(np.float32)
+    pgpe.ask(a, 5, pop)
+    pgpe.ask(b, 5, pop)
+    ga, sa = pgpe.tell(a, f, return_grads=True)
+    gb, sb = pgpe.tell(b, f, return_grads=True)
+    assert np.array_equal(ga, gb) and np.array_equal(sa, sb)
+    assert np.array_equal(a.sigma, b.sigma)          # the sigma rule does not depend on the optimizer of mu
+    if optimizer == 1:
+        want, vel = pgpe.clipup_ascent(mu0.astype(np.float64), np.zeros(P), gb, b.cfg.lr_mu, b.cfg.momentum, b.cfg.max_speed)
+    else:
+        want, vel = pgpe.momentum_ascent(mu0.astype(np.float64), np.zeros(P), gb, b.cfg.lr_mu, b.cfg.momentum)
+    assert np.array_equal(b.mu, want.astype(np.float32)) and np.array_equal(b.m, vel.astype(np.float32))
+    assert not np.array_equal(a.mu, b.mu)
