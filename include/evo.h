@@ -44,6 +44,7 @@ enum { EVO_ACT_NONE = 0, EVO_ACT_TANH = 1, EVO_ACT_RELU = 2 };
 enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1 };
 enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3 };
 enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1 };                        /* Philox stream tags */
+enum { EVO_OPT_ADAM = 0, EVO_OPT_CLIPUP = 1, EVO_OPT_MOMENTUM = 2 };  /* optimizer of mu    */
 #define EVO_POP_MAX 4096
 #define EVO_MAX_LAYERS 8
 
@@ -68,6 +69,9 @@ typedef struct {
   float beta1, beta2, eps;  /* Adam constants                                               */
   int32_t sigma_rule;       /* 0 = clipped ascent, 1 = Adam on sigma                        */
   int32_t shaping;          /* 1 = centered ranks, 0 = raw fitness                          */
+  int32_t optimizer;        /* update of mu: EVO_OPT_ADAM, EVO_OPT_CLIPUP or EVO_OPT_MOMENTUM */
+  float momentum;           /* ClipUp / momentum ascent                                     */
+  float max_speed;          /* ClipUp: bound on the Euclidean norm of the velocity, > 0     */
 } pgpe_config;
 
 typedef struct pgpe_state pgpe_state; /* host handle: config, t, pending (seed, pop), pointers */
@@ -103,7 +107,13 @@ int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params_dev, int32
  *           with shaping == 0, c_m = fitness_m.
  *   pairs   b = mean(c);  w_k = (c[2k] - c[2k+1]) / 2;  u_k = (c[2k] + c[2k+1]) / 2 - b
  *   grads   g_mu[i] = sigma[i] / N sum_k w_k z_k[i];  g_sigma[i] = sigma[i] / N sum_k u_k (z_k[i]^2 - 1)
- *   update  Adam ascent on mu (bias-corrected with t, eps outside the square root);
+ *   update  mu, by cfg.optimizer (the velocity of ClipUp and of momentum ascent lives in m; ClipUp
+ *           also uses v as scratch):
+ *             ADAM      ascent, bias-corrected with t, eps outside the square root;
+ *             CLIPUP    (the optimizer cited with PGPE in Section 5) vel = momentum vel +
+ *                       lr_mu g_mu / |g_mu|_2 (zero gradient: + 0); if |vel|_2 > max_speed the
+ *                       velocity is scaled to that norm; mu += vel;
+ *             MOMENTUM  vel = momentum vel + lr_mu g_mu; mu += vel;
  *           sigma: rule 0: sigma += clip(lr_sigma g_sigma, -+ sigma_max_change sigma);
  *                  rule 1: Adam ascent with moments in aux, then sigma = max(sigma, 1e-8);
  *           t <- t + 1, pending ask cleared.

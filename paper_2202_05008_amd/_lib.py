@@ -15,7 +15,8 @@ EVO_POP_MAX = 4096
 class pgpe_config(C.Structure):
     _fields_ = [("P", C.c_int32), ("pop_max", C.c_int32), ("sigma_init", C.c_float), ("lr_mu", C.c_float),
                 ("lr_sigma", C.c_float), ("sigma_max_change", C.c_float), ("beta1", C.c_float),
-                ("beta2", C.c_float), ("eps", C.c_float), ("sigma_rule", C.c_int32), ("shaping", C.c_int32)]
+                ("beta2", C.c_float), ("eps", C.c_float), ("sigma_rule", C.c_int32), ("shaping", C.c_int32),
+                ("optimizer", C.c_int32), ("momentum", C.c_float), ("max_speed", C.c_float)]
 
 
 class policy_desc(C.Structure):

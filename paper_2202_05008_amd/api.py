@@ -14,6 +14,7 @@ EVO_ACT_NONE, EVO_ACT_TANH, EVO_ACT_RELU = 0, 1, 2
 EVO_POLICY_MLP, EVO_POLICY_CONVNET = 0, 1
 EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE = 0, 1, 2, 3
 EVO_TAG_NOISE, EVO_TAG_RESET = 0, 1
+EVO_OPT_ADAM, EVO_OPT_CLIPUP, EVO_OPT_MOMENTUM = 0, 1, 2
 
 
 class EvoError(RuntimeError):
@@ -48,9 +49,11 @@ def evo_version():
 
 
 def make_pgpe_config(P, pop_max, sigma_init=0.1, lr_mu=0.01, lr_sigma=0.1, sigma_max_change=0.2, beta1=0.9,
-                     beta2=0.999, eps=1e-8, sigma_rule=0, shaping=1):
+                     beta2=0.999, eps=1e-8, sigma_rule=0, shaping=1, optimizer=0, momentum=0.9, max_speed=None):
+    if max_speed is None:
+        max_speed = 2.0 * lr_mu
     return pgpe_config(P, pop_max, sigma_init, lr_mu, lr_sigma, sigma_max_change, beta1, beta2, eps, sigma_rule,
-                       shaping)
+                       shaping, optimizer, momentum, max_speed)
 
 
 def make_policy_desc(kind, dims, act=(), dtype=EVO_F32):

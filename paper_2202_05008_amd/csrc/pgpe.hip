@@ -31,17 +31,23 @@ struct pgpe_state {
 namespace evo {
 
 // ---- workspace layout ------------------------------------------------------------------
+constexpr int kNormBlocks = 256;  // partial sums of a squared norm over P (ClipUp)
+
 struct Workspace {
   float* shaped;   // [pop_max] utilities c_m
   uint32_t* rank;  // [pop_max]
+  float* norm;     // [2][kNormBlocks] partial sums of |g|^2 and |vel|^2
 };
 
-static inline size_t ws_bytes(int pop_max) { return (static_cast<size_t>(pop_max) * 3 * 4 + 255) & ~size_t(255); }
+static inline size_t ws_bytes(int pop_max) {
+  return ((static_cast<size_t>(pop_max) * 2 + 2 * kNormBlocks) * 4 + 255) & ~size_t(255);
+}
 
 static inline Workspace ws_carve(void* base, int pop_max) {
   Workspace w;
   w.shaped = static_cast<float*>(base);
   w.rank = reinterpret_cast<uint32_t*>(w.shaped + pop_max);
+  w.norm = reinterpret_cast<float*>(w.rank + pop_max);
   return w;
 }
 
@@ -203,7 +209,7 @@ struct TellArgs {
   const float* shaped;  // utilities c[pop] (centered ranks or raw fitness)
   int P, nquads, N, KS;
   uint32_t gen, key0, key1;
-  float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2;
+  float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2, momentum;
 };
 
 __device__ __forceinline__ float adam_step(float x, float g, float& m, float& v, float lr, const TellArgs& a) {
@@ -216,7 +222,9 @@ __device__ __forceinline__ float adam_step(float x, float g, float& m, float& v,
 
 // Thread (q, ks): parameter quad q, pairs ks, ks+KS, ks+2KS, ...  The KS partial sums of a
 // quad are added in increasing ks by one thread, so the result does not depend on timing.
-template <int MODE>  // 0: sigma rule 0, 1: sigma rule 1 (Adam), 2: gradients only
+// OPT: what happens to mu.  SRULE: sigma rule 0 (clipped ascent) or 1 (Adam); unused with OPT_GRAD.
+enum { OPT_ADAM = 0, OPT_CLIPUP_GRAD = 1, OPT_MOMENTUM = 2, OPT_GRAD = 3 };
+template <int OPT, int SRULE>
 __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
   extern __shared__ float smem[];
   float* w_s = smem;
@@ -288,16 +296,24 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
     const float sg = a.sigma[c];
     const float g_mu = sg * A[i] * a.inv_n;
     const float g_sg = sg * B[i] * a.inv_n;
-    if (MODE == 2) {
+    if (OPT == OPT_GRAD) {
       a.gmu_out[c] = g_mu;
       a.gsg_out[c] = g_sg;
       continue;
     }
-    float m = a.m[c], v = a.v[c];
-    a.mu[c] = adam_step(a.mu[c], g_mu, m, v, a.lr_mu, a);
-    a.m[c] = m;
-    a.v[c] = v;
-    if (MODE == 0) {
+    if (OPT == OPT_ADAM) {
+      float m = a.m[c], v = a.v[c];
+      a.mu[c] = adam_step(a.mu[c], g_mu, m, v, a.lr_mu, a);
+      a.m[c] = m;
+      a.v[c] = v;
+    } else if (OPT == OPT_MOMENTUM) {
+      const float vel = a.momentum * a.m[c] + a.lr_mu * g_mu;
+      a.m[c] = vel;
+      a.mu[c] += vel;
+    } else {
+      a.v[c] = g_mu;  // ClipUp needs |g_mu| over all of P first: the gradient waits in v
+    }
+    if (SRULE == 0) {
       const float lim = a.max_change * sg;
       a.sigma[c] = sg + fminf(fmaxf(a.lr_sigma * g_sg, -lim), lim);
     } else {
@@ -306,6 +322,70 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
       a.ms[c] = ms;
       a.vs[c] = vs;
     }
+  }
+}
+
+// ---- ClipUp: two norms over P, each as kNormBlocks partial sums in a fixed order ------------------
+// Sum of the 256 per-thread values of a workgroup, fixed tree; valid in thread 0.
+__device__ __forceinline__ float block_sum256(float v, float* scratch) {
+  scratch[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) scratch[threadIdx.x] += scratch[threadIdx.x + s];
+    __syncthreads();
+  }
+  return scratch[0];
+}
+
+// Total of kNormBlocks partial sums in increasing order, fp64; every thread gets the same bits.
+__device__ __forceinline__ double partials_total(const float* __restrict__ part, double* scratch) {
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int i = 0; i < kNormBlocks; ++i) t += static_cast<double>(part[i]);
+    scratch[0] = t;
+  }
+  __syncthreads();
+  return scratch[0];
+}
+
+// part[b] = sum of x[i]^2 over the elements of workgroup b (grid-stride, kNormBlocks workgroups).
+__global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ x, int P, float* __restrict__ part) {
+  __shared__ float scratch[256];
+  float acc = 0.f;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < P; i += kNormBlocks * 256) acc = fmaf(x[i], x[i], acc);
+  const float t = block_sum256(acc, scratch);
+  if (threadIdx.x == 0) part[blockIdx.x] = t;
+}
+
+// vel = momentum vel + step g / |g| (g waits in `g`, |g|^2 in part_g); partial sums of vel^2 to part_v.
+__global__ __launch_bounds__(256) void clipup_velocity_kernel(float* __restrict__ vel, const float* __restrict__ g,
+                                                              int P, float momentum, float step,
+                                                              const float* __restrict__ part_g,
+                                                              float* __restrict__ part_v) {
+  __shared__ float scratch[256];
+  __shared__ double total[1];
+  const double n2 = partials_total(part_g, total);
+  const float scale = n2 > 0.0 ? static_cast<float>(static_cast<double>(step) / sqrt(n2)) : 0.f;
+  float acc = 0.f;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < P; i += kNormBlocks * 256) {
+    const float v = fmaf(scale, g[i], momentum * vel[i]);
+    vel[i] = v;
+    acc = fmaf(v, v, acc);
+  }
+  const float t = block_sum256(acc, scratch);
+  if (threadIdx.x == 0) part_v[blockIdx.x] = t;
+}
+
+// Clip the velocity to max_speed and move mu.
+__global__ __launch_bounds__(256) void clipup_apply_kernel(float* __restrict__ mu, float* __restrict__ vel, int P,
+                                                           float max_speed, const float* __restrict__ part_v) {
+  __shared__ double total[1];
+  const double speed = sqrt(partials_total(part_v, total));
+  const float clip = speed > static_cast<double>(max_speed) ? static_cast<float>(static_cast<double>(max_speed) / speed) : 1.0f;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < P; i += kNormBlocks * 256) {
+    const float v = vel[i] * clip;
+    vel[i] = v;
+    mu[i] += v;
   }
 }
 
@@ -353,6 +433,11 @@ static int check_cfg(const pgpe_config* c) {
   EVO_REQUIRE(c->shaping == 0 || c->shaping == 1, EVO_ERR_ARG, "shaping must be 0 or 1");
   EVO_REQUIRE(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f, EVO_ERR_ARG,
               "Adam betas must lie in [0,1)");
+  EVO_REQUIRE(c->optimizer == EVO_OPT_ADAM || c->optimizer == EVO_OPT_CLIPUP || c->optimizer == EVO_OPT_MOMENTUM,
+              EVO_ERR_ARG, "optimizer must be EVO_OPT_ADAM, EVO_OPT_CLIPUP or EVO_OPT_MOMENTUM (got %d)", c->optimizer);
+  if (c->optimizer != EVO_OPT_ADAM)
+    EVO_REQUIRE(c->momentum >= 0.f && c->momentum < 1.f, EVO_ERR_ARG, "momentum must lie in [0,1)");
+  if (c->optimizer == EVO_OPT_CLIPUP) EVO_REQUIRE(c->max_speed > 0.f, EVO_ERR_ARG, "max_speed must be positive");
   return EVO_OK;
 }
 
@@ -378,20 +463,32 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   a.gen = st->t, a.key0 = static_cast<uint32_t>(st->seed), a.key1 = static_cast<uint32_t>(st->seed >> 32);
   a.inv_n = 1.0f / static_cast<float>(N);
   a.lr_mu = c.lr_mu, a.lr_sigma = c.lr_sigma, a.max_change = c.sigma_max_change;
-  a.beta1 = c.beta1, a.beta2 = c.beta2, a.eps = c.eps;
+  a.beta1 = c.beta1, a.beta2 = c.beta2, a.eps = c.eps, a.momentum = c.momentum;
   a.bc1 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta1), static_cast<double>(st->t))));
   a.bc2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta2), static_cast<double>(st->t))));
   const int QPB = 256 / KS;
   const unsigned blocks = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
   const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + 256 * 8);  // w, u, partial sums / mean tree
+#define EVO_TELL(OPTV, SRV) hipLaunchKernelGGL((tell_kernel<OPTV, SRV>), dim3(blocks), dim3(256), shmem, s, a)
   if (gmu) {
-    hipLaunchKernelGGL(tell_kernel<2>, dim3(blocks), dim3(256), shmem, s, a);
-  } else if (c.sigma_rule == 0) {
-    hipLaunchKernelGGL(tell_kernel<0>, dim3(blocks), dim3(256), shmem, s, a);
+    EVO_TELL(OPT_GRAD, 0);
+  } else if (c.optimizer == EVO_OPT_ADAM) {
+    if (c.sigma_rule == 0) EVO_TELL(OPT_ADAM, 0); else EVO_TELL(OPT_ADAM, 1);
+  } else if (c.optimizer == EVO_OPT_MOMENTUM) {
+    if (c.sigma_rule == 0) EVO_TELL(OPT_MOMENTUM, 0); else EVO_TELL(OPT_MOMENTUM, 1);
   } else {
-    hipLaunchKernelGGL(tell_kernel<1>, dim3(blocks), dim3(256), shmem, s, a);
+    if (c.sigma_rule == 0) EVO_TELL(OPT_CLIPUP_GRAD, 0); else EVO_TELL(OPT_CLIPUP_GRAD, 1);
   }
-  return check_launch("tell_kernel");
+#undef EVO_TELL
+  rc = check_launch("tell_kernel");
+  if (rc || gmu || c.optimizer != EVO_OPT_CLIPUP) return rc;
+  // ClipUp: |g|, velocity and its norm, clip and move; the gradient waits in v
+  hipLaunchKernelGGL(sqnorm_kernel, dim3(kNormBlocks), dim3(256), 0, s, st->v, P, ws.norm);
+  hipLaunchKernelGGL(clipup_velocity_kernel, dim3(kNormBlocks), dim3(256), 0, s, st->m, st->v, P, c.momentum, c.lr_mu,
+                     ws.norm, ws.norm + kNormBlocks);
+  hipLaunchKernelGGL(clipup_apply_kernel, dim3(kNormBlocks), dim3(256), 0, s, st->mu, st->m, P, c.max_speed,
+                     ws.norm + kNormBlocks);
+  return check_launch("clipup kernels");
 }
 
 }  // namespace evo

@@ -156,6 +156,52 @@ def test_tell_against_oracle(evo, P, pop, rule, shaping):
         assert g.generation == o.t == it + 2
 
 
+@pytest.mark.parametrize("P,pop,optimizer,rule", [(676, 64, 1, 0), (676, 64, 2, 0), (70001, 32, 1, 0), (9098, 256, 1, 1),
+                                                  (1 << 18, 8, 1, 0), (7, 2, 2, 1)])
+def test_tell_clipup_and_momentum_against_oracle(evo, P, pop, optimizer, rule):
+    """ClipUp (two global norms) and momentum ascent in tell, five generations: the velocity builds
+    up and, for ClipUp, reaches the speed bound (momentum 0.9, max_speed 1.2 lr_mu: two steps in
+    unrelated directions already exceed it)."""
+    mu0 = gen.initial_mu(6, P)
+    kw = {"lr_sigma": 0.005} if rule == 1 else {}
+    g, o = _states(evo, P, pop, mu0, sigma_rule=rule, optimizer=optimizer, max_speed=0.012, **kw)
+    params = torch.empty(pop, P, dtype=torch.float32, device="cuda")
+    clipped = False
+    for it in range(5):
+        seed = 2000 + it
+        g.ask(seed, pop, params)
+        opgpe.ask(o, seed, pop)
+        f = gen.random_fitness(80 + it, pop)
+        g.tell(dev(f))
+        opgpe.tell(o, f)
+        assert_close(host(g.mu), o.mu, 1e-5, "mu, generation %d" % (it + 1))
+        assert_close(host(g.m), o.m, 1e-5, "velocity, generation %d" % (it + 1))
+        assert_close(host(g.sigma), o.sigma, 1e-5, "sigma, generation %d" % (it + 1))
+        speed = float(np.linalg.norm(host(g.m).astype(np.float64)))
+        if optimizer == 1:
+            assert speed <= o.cfg.max_speed * (1 + 1e-5)
+            clipped |= speed > o.cfg.max_speed * (1 - 1e-5)
+        assert g.generation == o.t == it + 2
+    if optimizer == 1:
+        assert clipped, "five steps at momentum 0.9 must have hit the speed bound"
+
+
+def test_clipup_zero_gradient_and_config_errors(evo):
+    P, pop = 100, 8
+    mu0 = gen.initial_mu(7, P)
+    g, o = _states(evo, P, pop, mu0, optimizer=1)
+    params = torch.empty(pop, P, dtype=torch.float32, device="cuda")
+    g.ask(3, pop, params)
+    # raw equal fitness with shaping off gives w = u = 0: the gradient is exactly zero
+    g2, o2 = _states(evo, P, pop, mu0, optimizer=1, shaping=0)
+    g2.ask(3, pop, params)
+    g2.tell(dev(np.full(pop, 2.5, np.float32)))
+    assert np.array_equal(host(g2.mu), mu0) and not np.isnan(host(g2.m)).any() and (host(g2.m) == 0).all()
+    for bad in ({"optimizer": 3}, {"optimizer": 1, "max_speed": 0.0}, {"optimizer": 2, "momentum": 1.0}):
+        with pytest.raises(evo.EvoError):
+            evo.PGPE(evo.make_pgpe_config(P=P, pop_max=pop, **bad))
+
+
 def test_tell_errors_and_determinism(evo):
     P, pop = 5000, 128
     g, _ = _states(evo, P, pop)
