@@ -38,7 +38,8 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def _build_workload(name, seed):
+def _build_workload(name, seed, batch=None):
+    import dataclasses
     import numpy as np
     import torch
     import paper_2202_05008_amd as evo
@@ -46,6 +47,8 @@ def _build_workload(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
+    if batch is not None:      # cfg4 only: observations per member, for the sweep of arithmetic intensity
+        c = dataclasses.replace(c, B=batch)
     dev = torch.device("cuda:0")
     mu0 = None if name == "cfg5" else gen.initial_mu(c.data_seed, c.P)
     pg = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop, sigma_init=c.sigma_init, lr_mu=c.lr_mu,
@@ -102,7 +105,8 @@ def _build_workload(name, seed):
         wl["task"] = lambda t: td
         nbytes = c.pop * (c.P * 2.0 + c.B * c.dims[0] * 4.0 + c.B * c.dims[-1] * 4.0 + 4.0)
         wl["roofline"] = ("hbm", nbytes, PEAK_HBM_GBS, "GB/s")
-        wl["desc"] = "cfg4: wide bf16 MLP 64-256-256-16, pop 4096, 64 observations per member"
+        wl["desc"] = "cfg4: wide bf16 MLP 64-256-256-16, pop 4096, %d observations per member" % c.B
+        wl["mfma_tflops_work"] = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.pop * c.B
         wl["dtype"] = "bf16"
     elif name == "cfg5":
         wl["pd"] = None
@@ -171,6 +175,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--seed", type=int, default=20220509)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -181,7 +187,9 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = _build_workload(args.workload, args.seed)
+    if args.batch is not None and args.workload != "cfg4":
+        raise SystemExit("--batch applies to --workload cfg4 only")
+    wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
     steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20}[args.workload]
     stage_names = ("ask", "rollout", "tell")
@@ -236,7 +244,13 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": wl["roofline_stage"], "kernel_ms": dom_ms},
     }
-    if not args.no_cpu_baseline:
+    if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
+        out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
+        out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
+    if args.batch is not None:
+        out["config"]["batch_override"] = args.batch
+        out["roofline"]["traffic"] = None
+    if not args.no_cpu_baseline and args.batch is None:
         out["cpu_baseline"] = _cpu_baseline(args.workload, args.seed)
     print(json.dumps(out))
 

@@ -195,8 +195,12 @@ constexpr int kStageLd = 40;   // row stride (elements) of the 16 x 32 staging t
 constexpr int kStageLd3 = 24;  // row stride of the 32 x 16 staging tile of layer 3
 constexpr int kStageElems = 32 * kStageLd3;  // 768 elements >= 16 * kStageLd
 
-template <int D0, int H, int A>
-__global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
+// MULTI: more than 64 observations per member (a loop over tiles of 64 rows, which needs more
+// registers than the single-tile kernel keeps free for four waves per SIMD).
+// RELU: the hidden activations are ReLU and the output is linear (the shape's usual policy), which
+// removes the per-value activation switch from the epilogues.
+template <int D0, int H, int A, bool MULTI, bool RELU>
+__global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   static_assert(H == 256 && D0 % 32 == 0 && A == 16, "shape of the streaming kernel");
   constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
   constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32, UT = U1 + U2 + U3;
@@ -257,22 +261,28 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     __builtin_amdgcn_wave_barrier();
     return join_bf16(lo, hi);
   };
+  const float bias1 = from_bf16(B1[col]), bias2 = from_bf16(B2[col]);
+  const float bias3 = from_bf16(B3[c16]);
+  float loss_acc = 0.f;
+  // Tiles of 64 observations: beyond the first, the weights come again from L2 (a member's 173 KB
+  // stay resident there), so the HBM traffic per member does not grow with B.
+  const int row_end = MULTI ? B : 1;
+#pragma unroll 1
+  for (int row0 = 0; row0 < row_end; row0 += 64) {
   // the observation loads go first so that waiting for them does not drain the weight stream
   constexpr int kObsPieces = 64 * D0 / 4 / 512;
   float4 ov[kObsPieces];
   {
-    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
+    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride + static_cast<size_t>(row0) * D0;
 #pragma unroll
     for (int j = 0; j < kObsPieces; ++j) {
       const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
       ov[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < B) ov[j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
+      if (row0 + r < B) ov[j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
     }
   }
 #pragma unroll
   for (int u = 0; u < kDepth; ++u) issue(u);
-  const float bias1 = from_bf16(B1[col]), bias2 = from_bf16(B2[col]);
-  const float bias3 = from_bf16(B3[c16]);
 
   // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
 #pragma unroll
@@ -288,7 +298,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   if (tail && a.loss != LOSS_NONE) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = 16 * wave + 4 * g4 + i;
+      const int row = row0 + 16 * wave + 4 * g4 + i;
       if (row < B) tgt[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
     }
   }
@@ -311,7 +321,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
     }
   }
   {
-    const int act = a.sh.act[0];
+    const int act = RELU ? EVO_ACT_RELU : a.sh.act[0];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   }
   __syncthreads();  // every wave has read h1: the buffer can take h2
   {
-    const int act = a.sh.act[1];
+    const int act = RELU ? EVO_ACT_RELU : a.sh.act[1];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -351,7 +361,6 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   __syncthreads();
 
   // ---- layer 3: four waves, one 16-row tile each (16x16x32 tiles: lane = 16 g4 + c16) -------------
-  float loss_acc = 0.f;
   if (tail) {
     floatx4v o = {bias3, bias3, bias3, bias3};
 #pragma unroll
@@ -361,10 +370,10 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
       const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * (u - U1 - U2) + 8 * g4);
       o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
     }
-    const int act = a.sh.act[2];
+    const int act = RELU ? EVO_ACT_NONE : a.sh.act[2];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = 16 * wave + 4 * g4 + i;
+      const int row = row0 + 16 * wave + 4 * g4 + i;
       const float v = act_f(o[i], act);
       if (row < B) {
         if (a.loss == LOSS_NONE) {
@@ -376,6 +385,7 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
       }
     }
   }
+  }  // row tiles (the first barrier of the next tile comes after every wave's layer 3)
   if (a.loss == LOSS_NONE) return;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
@@ -384,12 +394,15 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
 }
 
+constexpr int kStreamMaxRows = 4096;  // observations per member of the streaming kernel (tiles of 64)
+
 static bool stream_shape(const MlpShape& sh, int B) {
   return sh.n_layers == 3 && sh.dims[0] == 64 && sh.dims[1] == 256 && sh.dims[2] == 256 && sh.dims[3] == 16 &&
-         B <= 64;
+         B <= kStreamMaxRows;
 }
 
 int mlp_bf16_supported(const MlpShape& sh, int B) {
+  if (B >= 1 && stream_shape(sh, B)) return EVO_OK;  // the streaming kernel walks over tiles of 64 rows
   EVO_REQUIRE(B >= 1 && B <= kMaxRows, EVO_ERR_UNSUPPORTED, "bf16 MLP: B must be in [1, %d] (got %d)", kMaxRows, B);
   EVO_REQUIRE(sh.max_width <= kMaxWidth, EVO_ERR_UNSUPPORTED, "bf16 MLP: widths above %d are not supported (%d)",
               kMaxWidth, sh.max_width);
@@ -407,7 +420,15 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
   a.out = out, a.target = static_cast<const float*>(target), a.fitness = fitness, a.loss = loss;
   if (stream_shape(sh, B)) {
     a.buf_elems = 0;
-    hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16>), dim3(pop), dim3(512), 0, s, a);
+    const bool relu = sh.act[0] == EVO_ACT_RELU && sh.act[1] == EVO_ACT_RELU && sh.act[2] == EVO_ACT_NONE;
+#define EVO_STREAM(MULTIV, RELUV) \
+  hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16, MULTIV, RELUV>), dim3(pop), dim3(512), 0, s, a)
+    if (B <= 64) {
+      if (relu) EVO_STREAM(false, true); else EVO_STREAM(false, false);
+    } else {
+      if (relu) EVO_STREAM(true, true); else EVO_STREAM(true, false);
+    }
+#undef EVO_STREAM
     return check_launch("mlp_bf16_stream_kernel");
   }
   const int rows = ((B + 31) / 32) * 32;
