@@ -133,7 +133,7 @@ def _cpu_baseline(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
-    sample_pop = {"cfg1": 64, "cfg2": 32, "cfg3": 512, "cfg4": 1024, "cfg5": 96}[name]
+    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96}[name]
     gens = {"cfg1": 600}.get(name, 1)
     dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
     if name == "cfg1":
