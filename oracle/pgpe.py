@@ -20,7 +20,8 @@ perturbations eps = sigma * z, centered-rank fitness shaping and an Adam ascent 
 All arithmetic is fp64 on fp32-representable inputs; state arrays are rounded to fp32
 after every tell because that is the precision they are stored in.
 Pins: tests/test_oracle_pgpe.py (brute force on tiny populations, closed-form expected
-gradients, pair-swap / shift identities, Adam closed forms, ClipUp / momentum closed forms
+gradients, pair-swap / shift identities, the stored-population form against the
+regenerating one, Adam closed forms, ClipUp / momentum closed forms
 and a library optimizer, sphere convergence).
 """
 from dataclasses import dataclass, field
@@ -163,6 +164,24 @@ def gradients(z, sigma, c):
     return g_mu, g_sigma
 
 
+def gradients_from_population(theta_plus, mu, sigma, c):
+    """The same estimate taken from the STORED population instead of regenerated noise: with
+    eps_k = theta[2k] - mu (the perturbation of the + member of pair k, as it was rounded when
+    the population was written),
+        g_mu = 1/N sum_k w_k eps_k,      g_sigma = 1/N sum_k u_k (eps_k^2 - sigma^2) / sigma,
+    which is `gradients` with eps = sigma z.  A parameter with sigma = 0 has eps = 0 and gets
+    g_sigma = 0.  theta_plus[N,P] holds the even rows of the population; fp64 throughout."""
+    w, u = pair_weights(c)
+    mu = np.asarray(mu, dtype=np.float64)
+    sg = np.asarray(sigma, dtype=np.float64)
+    eps = np.asarray(theta_plus, dtype=np.float64) - mu[None, :]
+    N = eps.shape[0]
+    g_mu = (w @ eps) / N
+    safe = np.where(sg > 0.0, sg, 1.0)
+    g_sigma = np.where(sg > 0.0, (u @ (eps * eps - (sg * sg)[None, :])) / safe / N, 0.0)
+    return g_mu, g_sigma
+
+
 def adam_ascent(x, m, v, g, lr, beta1, beta2, eps, t):
     """One bias-corrected Adam step that INCREASES the objective; returns (x, m, v) in fp64."""
     m = beta1 * m + (1.0 - beta1) * g
@@ -196,9 +215,11 @@ def utilities(state, fitness):
     return centered_rank(f)[1] if state.cfg.shaping == 1 else f
 
 
-def tell(state, fitness, chunk=1 << 15, return_grads=False):
+def tell(state, fitness, chunk=1 << 15, return_grads=False, stored=None):
     """Consume the fitness of the pending ask and update (mu, sigma, moments, t).
-    The noise is regenerated from the counter-based stream in column chunks."""
+    The noise is regenerated from the counter-based stream in column chunks; or, when `stored`
+    is the population [pop,P] that ask wrote (fp32), the perturbations are read back from its
+    even rows (`gradients_from_population`)."""
     if state.last is None:
         raise RuntimeError("tell without a pending ask")
     seed, pop, t = state.last
@@ -215,6 +236,10 @@ def tell(state, fitness, chunk=1 << 15, return_grads=False):
     pairs = np.arange(N)
     for lo in range(0, P, chunk):
         hi = min(P, lo + chunk)
+        if stored is not None:
+            g_mu[lo:hi], g_sg[lo:hi] = gradients_from_population(np.asarray(stored)[0::2, lo:hi], state.mu[lo:hi],
+                                                                 sg[lo:hi], c)
+            continue
         lo4 = lo & ~3
         z = philox.block_normals(seed, np.arange(lo4 >> 2, (hi + 3) >> 2)[None, :], pairs[:, None], t,
                                  philox.TAG_NOISE).reshape(N, -1)[:, lo - lo4: hi - lo4]

@@ -156,6 +156,45 @@ def test_gradient_brute_force_tiny():
     np.testing.assert_allclose(gs, ws, rtol=1e-10, atol=1e-13)
 
 
+def test_gradient_from_stored_population():
+    """The stored-population form against the double loop over members, against the
+    regenerating form (exact population in fp64: equal to rounding; population rounded to fp32:
+    equal to the rounding of eps), and sigma = 0 gives g_sigma = 0."""
+    P, pop, seed = 6, 10, 41
+    mu = np.random.default_rng(15).standard_normal(P)
+    sigma = np.abs(np.random.default_rng(16).standard_normal(P)) + 0.1
+    z = philox.pair_noise(seed, 3, np.arange(pop // 2), P)
+    theta = np.empty((pop, P))
+    theta[0::2] = mu + sigma * z
+    theta[1::2] = mu - sigma * z
+    f = np.random.default_rng(17).standard_normal(pop)
+    gm, gs = pgpe.gradients_from_population(theta[0::2], mu, sigma, f)
+    wm, ws = _textbook_pgpe(theta, mu, sigma, f.tolist())
+    np.testing.assert_allclose(gm, wm, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gs, ws, rtol=1e-10, atol=1e-13)
+    rm, rs = pgpe.gradients(z, sigma, f)
+    np.testing.assert_allclose(gm, rm, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(gs, rs, rtol=1e-10, atol=1e-13)
+    # through tell: a population rounded to fp32 moves the gradient by the rounding of eps only
+    P, pop = 301, 16
+    mu0 = np.random.default_rng(18).standard_normal(P).astype(np.float32)
+    a, b = _state(P, mu0), _state(P, mu0)
+    th = pgpe.ask(a, 5, pop)
+    pgpe.ask(b, 5, pop)
+    f = np.random.default_rng(19).standard_normal(pop).astype(np.float32)
+    ga = pgpe.tell(a, f, return_grads=True)
+    gb = pgpe.tell(b, f, return_grads=True, stored=th, chunk=100)
+    for x, y in zip(ga, gb):
+        # theta ~ 1 is stored to half an ulp = 6e-8, eps ~ 0.1: 1e-6 of a term, a few 1e-6 of the rms
+        assert np.abs(x - y).max() < 1e-5 * np.sqrt(np.mean(x * x))
+    assert np.abs(a.mu - b.mu).max() < 1e-4 and b.t == 2 and b.last is None
+    # sigma = 0: the parameter does not move and its sigma gradient is zero
+    sg = np.array([0.0, 0.5])
+    th = np.array([[1.0, 2.3], [1.0, 1.9]])
+    g0, g1 = pgpe.gradients_from_population(th, np.array([1.0, 2.0]), sg, np.array([3.0, 1.0, -2.0, 0.5]))
+    assert g0[0] == 0.0 and g1[0] == 0.0 and np.isfinite(g1).all()
+
+
 def test_gradient_identities():
     P, N = 7, 6
     z = philox.pair_noise(8, 2, np.arange(N), P)
