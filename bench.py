@@ -112,6 +112,7 @@ def _build_workload(name, seed, batch=None):
         wl["pd"] = None
         xs = torch.from_numpy(gen.sphere_target(c.data_seed, c.P)).to(dev)
         wl["keep"] = [xs]
+        wl["x_star"] = xs
         td = with_work(lambda w: evo.make_task_desc(evo.EVO_TASK_SPHERE, P=c.P, target=xs, work=w))
         wl["task"] = lambda t: td
         wl["roofline"] = ("hbm", c.pop * c.P * 4.0 + 2 * c.P * 4.0, PEAK_HBM_GBS, "GB/s")
@@ -177,6 +178,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=None,
                     help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
+    ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
+                    help="cfg5 only: 'fused' = ask fused with the sphere fitness (no population in memory), "
+                         "'stored' = tell reads the perturbations back from the stored population")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -189,6 +193,8 @@ def main():
     torch.cuda.set_device(0)
     if args.batch is not None and args.workload != "cfg4":
         raise SystemExit("--batch applies to --workload cfg4 only")
+    if args.variant != "materialised" and args.workload != "cfg5":
+        raise SystemExit("--variant applies to --workload cfg5 only")
     wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
     steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20}[args.workload]
@@ -200,13 +206,20 @@ def main():
         td = wl["task"](t)
         if timed:
             ev[0].record()
-        pg.ask(args.seed, c.pop, wl["params"], c.dtype)
+        if args.variant == "fused":      # one call stands for ask + rollout: the rollout stage reads 0
+            pg.ask_sphere(args.seed, c.pop, wl["x_star"], wl["fitness"])
+        else:
+            pg.ask(args.seed, c.pop, wl["params"], c.dtype)
         if timed:
             ev[1].record()
-        evo.rollout(td, wl["pd"], wl["params"], c.pop, c.steps, wl["fitness"])
+        if args.variant != "fused":
+            evo.rollout(td, wl["pd"], wl["params"], c.pop, c.steps, wl["fitness"])
         if timed:
             ev[2].record()
-        pg.tell(wl["fitness"])
+        if args.variant == "stored":
+            pg.tell_stored(wl["fitness"], wl["params"])
+        else:
+            pg.tell(wl["fitness"])
         if timed:
             ev[3].record()
             events.append(ev)
@@ -250,7 +263,16 @@ def main():
     if args.batch is not None:
         out["config"]["batch_override"] = args.batch
         out["roofline"]["traffic"] = None
-    if not args.no_cpu_baseline and args.batch is None:
+    if args.variant != "materialised":
+        out["config"]["generation"] = {"fused": "ask_sphere (ask + fitness in one kernel, no population) -> tell",
+                                       "stored": "ask -> rollout -> tell_stored"}[args.variant]
+        out["roofline"]["traffic"] = None
+        if args.variant == "fused":      # no population is written: the stage is bound by the noise generation
+            normals = c.pop / 2 * c.P
+            out["roofline"] = {"bound": "alu", "achieved": normals / (dom_ms * 1e-3) / 1e9, "peak": None,
+                               "unit": "Gnormal/s", "frac": None, "traffic": None, "kernel": "ask_sphere",
+                               "kernel_ms": dom_ms}
+    if not args.no_cpu_baseline and args.batch is None and args.variant == "materialised":
         out["cpu_baseline"] = _cpu_baseline(args.workload, args.seed)
     print(json.dumps(out))
 

@@ -121,6 +121,27 @@ int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params_dev, int32
  * Errors: EVO_ERR_STATE (no pending ask), EVO_ERR_ARG, EVO_ERR_HIP. */
 int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream);
 
+/* Measured alternatives to "materialise the population, regenerate the noise" (same Section 4
+ * ask / tell interface; both give the results of the calls above up to fp32 rounding order).
+ *
+ * pgpe_ask_sphere: ask fused with the SPHERE fitness of `rollout`, the population never being
+ * written: fitness_dev[m] = -sum_i (theta[m][i] - x_star_dev[i])^2 with theta[m][i] the fp32
+ * value pgpe_ask would store.  Records the pending ask like pgpe_ask.  work_dev: caller-owned,
+ * pgpe_ask_sphere_workspace_bytes(cfg) bytes (partial sums; contents need not be kept).
+ * Errors: EVO_ERR_ARG (null, misaligned, bad pop), EVO_ERR_HIP. */
+size_t pgpe_ask_sphere_workspace_bytes(const pgpe_config* cfg);
+int pgpe_ask_sphere(pgpe_state* st, uint64_t seed, int32_t pop, const float* x_star_dev, float* fitness_dev,
+                    void* work_dev, void* stream);
+
+/* pgpe_tell_stored: tell with the perturbations read back from the fp32 population params_dev[pop][P]
+ * that the pending pgpe_ask wrote (only its even rows are read) instead of regenerated:
+ * eps_k = theta[2k] - mu;  g_mu[i] = 1/N sum_k w_k eps_k[i];
+ * g_sigma[i] = 1/N sum_k u_k (eps_k[i]^2 - sigma[i]^2) / sigma[i]  (0 where sigma[i] = 0);
+ * ranks, pair weights, optimizer and sigma rule as in pgpe_tell.  The caller guarantees that
+ * params_dev still holds what the pending ask wrote.
+ * Errors: EVO_ERR_STATE (no pending ask), EVO_ERR_ARG, EVO_ERR_HIP. */
+int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* params_dev, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Global policy (Section 2, "Global Policy"; Section 4, "Exploring Novel Policy
  * Architectures"): one network definition evaluated for all members, parameters and
@@ -210,8 +231,10 @@ int evo_philox_normal(uint64_t seed, uint32_t gen, uint32_t pair, uint32_t block
 /* Ranks and shaped fitness of tell's first stage: rank_dev[pop] (u32), shaped_dev[pop] (fp32). */
 int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t* rank_dev, float* shaped_dev, void* stream);
 /* The gradient estimate tell would use for the pending ask, without updating anything:
- * gmu_dev[P], gsigma_dev[P].  The pending ask stays pending. */
-int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev, void* stream);
+ * gmu_dev[P], gsigma_dev[P].  params_dev NULL: as pgpe_tell (noise regenerated); else as
+ * pgpe_tell_stored from that fp32 population.  The pending ask stays pending. */
+int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev,
+                       const float* params_dev, void* stream);
 /* One cart-pole step for n independent (state, action) pairs: state_dev[n][4], action_dev[n]
  * -> next_dev[n][4], reward_dev[n].  Only td->cp is read. */
 int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,

@@ -42,6 +42,9 @@ _SIGNATURES = {
     "pgpe_set_generation": (C.c_int, [C.c_void_p, C.c_uint32]),
     "pgpe_ask": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "pgpe_tell": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "pgpe_ask_sphere_workspace_bytes": (C.c_size_t, [C.POINTER(pgpe_config)]),
+    "pgpe_ask_sphere": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "pgpe_tell_stored": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "policy_param_count": (C.c_int64, [C.POINTER(policy_desc)]),
     "pop_forward": (C.c_int, [C.POINTER(policy_desc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                               C.c_int32, C.c_void_p]),
@@ -53,7 +56,7 @@ _SIGNATURES = {
     "evo_philox_normal": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                     C.c_void_p, C.c_void_p]),
     "evo_centered_rank": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
-    "evo_pgpe_gradients": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "evo_pgpe_gradients": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "evo_task_step": (C.c_int, [C.POINTER(task_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                 C.c_void_p]),
     "evo_rollout_details": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,

@@ -125,6 +125,19 @@ def pgpe_tell(h, fitness):
     _check(_lib.load().pgpe_tell(h, _ptr(fitness, torch.float32), _stream()))
 
 
+def pgpe_ask_sphere_workspace_bytes(cfg):
+    return int(_lib.load().pgpe_ask_sphere_workspace_bytes(C.byref(cfg)))
+
+
+def pgpe_ask_sphere(h, seed, pop, x_star, fitness, work):
+    _check(_lib.load().pgpe_ask_sphere(h, seed, pop, _ptr(x_star, torch.float32), _ptr(fitness, torch.float32),
+                                       _ptr(work), _stream()))
+
+
+def pgpe_tell_stored(h, fitness, params):
+    _check(_lib.load().pgpe_tell_stored(h, _ptr(fitness, torch.float32), _ptr(params, torch.float32), _stream()))
+
+
 def policy_param_count(pd):
     n = _lib.load().policy_param_count(C.byref(pd))
     if n < 0:
@@ -159,9 +172,10 @@ def evo_centered_rank(fitness, pop, rank, shaped):
                                          _ptr(shaped, torch.float32), _stream()))
 
 
-def evo_pgpe_gradients(h, fitness, gmu, gsigma):
+def evo_pgpe_gradients(h, fitness, gmu, gsigma, params=None):
     _check(_lib.load().evo_pgpe_gradients(h, _ptr(fitness, torch.float32), _ptr(gmu, torch.float32),
-                                          _ptr(gsigma, torch.float32), _stream()))
+                                          _ptr(gsigma, torch.float32),
+                                          _ptr(params, torch.float32, allow_none=True), _stream()))
 
 
 def evo_task_step(td, state, action, nxt, reward, n):
@@ -198,6 +212,15 @@ class PGPE:
 
     def tell(self, fitness):
         pgpe_tell(self.handle, fitness)
+
+    def ask_sphere(self, seed, pop, x_star, fitness):
+        if getattr(self, "_sphere_work", None) is None:
+            self._sphere_work = torch.empty(pgpe_ask_sphere_workspace_bytes(self.cfg), dtype=torch.uint8,
+                                            device=self.mu.device)
+        pgpe_ask_sphere(self.handle, seed, pop, x_star, fitness, self._sphere_work)
+
+    def tell_stored(self, fitness, params):
+        pgpe_tell_stored(self.handle, fitness, params)
 
     @property
     def generation(self):

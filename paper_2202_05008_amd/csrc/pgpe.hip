@@ -145,6 +145,92 @@ __global__ __launch_bounds__(256) void ask_bf16x8_kernel(const float* __restrict
   __builtin_nontemporal_store(minus, reinterpret_cast<u32x4*>(row + P));
 }
 
+// ---- ask fused with the sphere fitness: the population is never written --------------------------
+// Thread = kFusedQuads parameter quads x kFusedPairs pairs: mu, sigma and x_star are loaded once
+// per quad, each draw serves both members of its pair, and theta is formed exactly as ask_kernel
+// stores it (one fused multiply-add, rounded once) before x_star is subtracted.  A workgroup
+// leaves one partial sum per member in part[member][blockIdx.x]; sphere_finish_kernel adds a
+// member's partial sums in a fixed order.
+constexpr int kFusedQuads = 4;
+constexpr int kFusedPairs = 4;
+
+__global__ __launch_bounds__(256) void ask_sphere_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
+                                                         const float* __restrict__ x_star, float* __restrict__ part,
+                                                         int P, int nquads, int N, int xblocks, uint32_t gen,
+                                                         uint32_t key0, uint32_t key1) {
+  __shared__ float red[4][2 * kFusedPairs];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int k0 = blockIdx.y * kFusedPairs;
+  float acc[kFusedPairs][2];
+#pragma unroll
+  for (int ki = 0; ki < kFusedPairs; ++ki) acc[ki][0] = acc[ki][1] = 0.f;
+  for (int qi = 0; qi < kFusedQuads; ++qi) {
+    const int q = (blockIdx.x * kFusedQuads + qi) * 256 + tid;
+    if (q >= nquads) break;
+    const int col = q * 4;
+    float mu4[4], sg4[4], xs4[4];
+    if (col + 3 < P) {
+      const float4 a = *reinterpret_cast<const float4*>(mu + col);
+      const float4 b = *reinterpret_cast<const float4*>(sigma + col);
+      const float4 c = *reinterpret_cast<const float4*>(x_star + col);
+      mu4[0] = a.x, mu4[1] = a.y, mu4[2] = a.z, mu4[3] = a.w;
+      sg4[0] = b.x, sg4[1] = b.y, sg4[2] = b.z, sg4[3] = b.w;
+      xs4[0] = c.x, xs4[1] = c.y, xs4[2] = c.z, xs4[3] = c.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {  // columns beyond P contribute (0 - 0)^2
+        mu4[i] = col + i < P ? mu[col + i] : 0.f;
+        sg4[i] = col + i < P ? sigma[col + i] : 0.f;
+        xs4[i] = col + i < P ? x_star[col + i] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int ki = 0; ki < kFusedPairs; ++ki) {
+      if (k0 + ki >= N) break;  // uniform over the workgroup
+      float z[4];
+      philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(k0 + ki), gen, EVO_TAG_NOISE, key0, key1, z);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float dp = fmaf(sg4[i], z[i], mu4[i]) - xs4[i];
+        const float dm = fmaf(-sg4[i], z[i], mu4[i]) - xs4[i];
+        acc[ki][0] = fmaf(dp, dp, acc[ki][0]);
+        acc[ki][1] = fmaf(dm, dm, acc[ki][1]);
+      }
+    }
+  }
+#pragma unroll
+  for (int ki = 0; ki < kFusedPairs; ++ki)
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      float v = acc[ki][s];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      if (lane == 0) red[wave][2 * ki + s] = v;
+    }
+  __syncthreads();
+  if (tid < 2 * kFusedPairs && k0 + (tid >> 1) < N) {
+    const float total = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+    part[static_cast<size_t>(2 * k0 + tid) * xblocks + blockIdx.x] = total;
+  }
+}
+
+// fitness[m] = -(sum of the member's xblocks partial sums): one wavefront per member, lane l adds
+// partial sums l, l + 64, ... in order, then a fixed butterfly over the lanes.
+__global__ __launch_bounds__(256) void sphere_finish_kernel(const float* __restrict__ part, int xblocks, int pop,
+                                                            float* __restrict__ fitness) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= pop) return;
+  const float* row = part + static_cast<size_t>(m) * xblocks;
+  float v = 0.f;
+  for (int i = lane; i < xblocks; i += 64) v += row[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  if (lane == 0) fitness[m] = -v;
+}
+
+static inline int fused_xblocks(int P) { return ((P + 3) / 4 + 256 * kFusedQuads - 1) / (256 * kFusedQuads); }
+
 // ---- centered ranks and pair weights ------------------------------------------------------
 // fp32 bits -> u32 that orders like the float: -0 counts as +0, NaN sorts lowest.
 __device__ __forceinline__ uint32_t orderable(float f) {
@@ -207,6 +293,7 @@ struct TellArgs {
   float* gmu_out;  // gradient-only mode
   float* gsg_out;
   const float* shaped;  // utilities c[pop] (centered ranks or raw fitness)
+  const float* theta;   // stored population [2N][P] (STORED form) or null
   int P, nquads, N, KS;
   uint32_t gen, key0, key1;
   float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2, momentum;
@@ -223,8 +310,10 @@ __device__ __forceinline__ float adam_step(float x, float g, float& m, float& v,
 // Thread (q, ks): parameter quad q, pairs ks, ks+KS, ks+2KS, ...  The KS partial sums of a
 // quad are added in increasing ks by one thread, so the result does not depend on timing.
 // OPT: what happens to mu.  SRULE: sigma rule 0 (clipped ascent) or 1 (Adam); unused with OPT_GRAD.
+// STORED: the perturbation eps = theta[2k] - mu is read back from the population that ask wrote
+// (sums of w eps and u (eps^2 - sigma^2)) instead of being regenerated (sums of w z and u (z^2 - 1)).
 enum { OPT_ADAM = 0, OPT_CLIPUP_GRAD = 1, OPT_MOMENTUM = 2, OPT_GRAD = 3 };
-template <int OPT, int SRULE>
+template <int OPT, int SRULE, bool STORED>
 __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
   extern __shared__ float smem[];
   float* w_s = smem;
@@ -256,7 +345,7 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
     __syncthreads();
   }
   float A[4] = {0.f, 0.f, 0.f, 0.f}, B[4] = {0.f, 0.f, 0.f, 0.f};
-  if (q < a.nquads) {
+  if (q < a.nquads && !STORED) {
     for (int k = ks; k < a.N; k += a.KS) {
       float z[4];
       philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(k), a.gen, EVO_TAG_NOISE, a.key0, a.key1, z);
@@ -265,6 +354,38 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
       for (int i = 0; i < 4; ++i) {
         A[i] = fmaf(wk, z[i], A[i]);
         B[i] = fmaf(uk, fmaf(z[i], z[i], -1.0f), B[i]);
+      }
+    }
+  }
+  if (q < a.nquads && STORED) {
+    const int col = q * 4;
+    const bool vec = (a.P & 3) == 0;  // rows are 16-byte aligned only then
+    float mu4[4], nv4[4];             // centre and -sigma^2
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = min(col + i, a.P - 1);
+      const float sg = a.sigma[c];
+      mu4[i] = a.mu[c];
+      nv4[i] = -sg * sg;
+    }
+#pragma unroll 8
+    for (int k = ks; k < a.N; k += a.KS) {
+      const float* row = a.theta + static_cast<size_t>(2 * k) * a.P;
+      float th[4];
+      if (vec) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + col));
+        th[0] = t[0], th[1] = t[1], th[2] = t[2], th[3] = t[3];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) th[i] = row[min(col + i, a.P - 1)];
+      }
+      const float wk = w_s[k], uk = u_s[k];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float e = th[i] - mu4[i];
+        A[i] = fmaf(wk, e, A[i]);
+        B[i] = fmaf(uk, fmaf(e, e, nv4[i]), B[i]);
       }
     }
   }
@@ -294,8 +415,8 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
     const int c = col + i;
     if (c >= a.P) break;
     const float sg = a.sigma[c];
-    const float g_mu = sg * A[i] * a.inv_n;
-    const float g_sg = sg * B[i] * a.inv_n;
+    const float g_mu = STORED ? A[i] * a.inv_n : sg * A[i] * a.inv_n;
+    const float g_sg = STORED ? (sg > 0.f ? B[i] / sg * a.inv_n : 0.f) : sg * B[i] * a.inv_n;
     if (OPT == OPT_GRAD) {
       a.gmu_out[c] = g_mu;
       a.gsg_out[c] = g_sg;
@@ -441,8 +562,15 @@ static int check_cfg(const pgpe_config* c) {
   return EVO_OK;
 }
 
-// Shared by pgpe_tell and the gradient hook.
-static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, hipStream_t s) {
+static int check_ask_pop(const pgpe_state* st, int32_t pop, const char* who) {
+  EVO_REQUIRE(pop >= 2 && (pop & 1) == 0 && pop <= st->cfg.pop_max, EVO_ERR_ARG,
+              "%s: pop must be even and in [2, pop_max=%d] (got %d)", who, st->cfg.pop_max, pop);
+  return EVO_OK;
+}
+
+// Shared by pgpe_tell, pgpe_tell_stored and the gradient hook (theta: stored population or null).
+static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, const float* theta,
+                    hipStream_t s) {
   const pgpe_config& c = st->cfg;
   const int pop = st->pop, N = pop / 2, P = c.P;
   Workspace ws = ws_carve(st->work, c.pop_max);
@@ -453,12 +581,14 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   a.ms = st->aux, a.vs = st->aux ? st->aux + P : nullptr;
   a.gmu_out = gmu, a.gsg_out = gsg;
   a.shaped = ws.shaped;
+  a.theta = theta;
   a.P = P, a.nquads = (P + 3) / 4, a.N = N;
   // split the pair loop KS ways until about 2^19 threads (eight waves per SIMD) are in flight:
   // measured, that is where the time stops falling, and beyond 64 slices the LDS reduction of
   // the partial sums costs more than it gains
   int KS = 1;
-  while (KS < 64 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < 524288) KS *= 2;
+  const long threads_wanted = theta ? 262144 : 524288;
+  while (KS < 64 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < threads_wanted) KS *= 2;
   a.KS = KS;
   a.gen = st->t, a.key0 = static_cast<uint32_t>(st->seed), a.key1 = static_cast<uint32_t>(st->seed >> 32);
   a.inv_n = 1.0f / static_cast<float>(N);
@@ -469,15 +599,22 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   const int QPB = 256 / KS;
   const unsigned blocks = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
   const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + 256 * 8);  // w, u, partial sums / mean tree
-#define EVO_TELL(OPTV, SRV) hipLaunchKernelGGL((tell_kernel<OPTV, SRV>), dim3(blocks), dim3(256), shmem, s, a)
+#define EVO_TELL(OPTV, SRV)                                                                          \
+  do {                                                                                               \
+    if (theta) hipLaunchKernelGGL((tell_kernel<OPTV, SRV, true>), dim3(blocks), dim3(256), shmem, s, a); \
+    else hipLaunchKernelGGL((tell_kernel<OPTV, SRV, false>), dim3(blocks), dim3(256), shmem, s, a);  \
+  } while (0)
   if (gmu) {
     EVO_TELL(OPT_GRAD, 0);
   } else if (c.optimizer == EVO_OPT_ADAM) {
-    if (c.sigma_rule == 0) EVO_TELL(OPT_ADAM, 0); else EVO_TELL(OPT_ADAM, 1);
+    if (c.sigma_rule == 0) EVO_TELL(OPT_ADAM, 0);
+    else EVO_TELL(OPT_ADAM, 1);
   } else if (c.optimizer == EVO_OPT_MOMENTUM) {
-    if (c.sigma_rule == 0) EVO_TELL(OPT_MOMENTUM, 0); else EVO_TELL(OPT_MOMENTUM, 1);
+    if (c.sigma_rule == 0) EVO_TELL(OPT_MOMENTUM, 0);
+    else EVO_TELL(OPT_MOMENTUM, 1);
   } else {
-    if (c.sigma_rule == 0) EVO_TELL(OPT_CLIPUP_GRAD, 0); else EVO_TELL(OPT_CLIPUP_GRAD, 1);
+    if (c.sigma_rule == 0) EVO_TELL(OPT_CLIPUP_GRAD, 0);
+    else EVO_TELL(OPT_CLIPUP_GRAD, 1);
   }
 #undef EVO_TELL
   rc = check_launch("tell_kernel");
@@ -556,8 +693,7 @@ extern "C" int pgpe_set_generation(pgpe_state* st, uint32_t t) {
 extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params_dev, int32_t dtype,
                         void* stream) {
   EVO_REQUIRE(st != nullptr && params_dev != nullptr, EVO_ERR_ARG, "pgpe_ask: null argument");
-  EVO_REQUIRE(pop >= 2 && (pop & 1) == 0 && pop <= st->cfg.pop_max, EVO_ERR_ARG,
-              "pgpe_ask: pop must be even and in [2, pop_max=%d] (got %d)", st->cfg.pop_max, pop);
+  if (int rc = check_ask_pop(st, pop, "pgpe_ask")) return rc;
   EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "pgpe_ask: bad dtype %d", dtype);
   EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "pgpe_ask: params_dev must be 16-byte aligned");
   const int P = st->cfg.P, N = pop / 2, nquads = (P + 3) / 4;
@@ -589,10 +725,51 @@ extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params
   return EVO_OK;
 }
 
+extern "C" size_t pgpe_ask_sphere_workspace_bytes(const pgpe_config* cfg) {
+  if (check_cfg(cfg) != EVO_OK) return 0;
+  return (static_cast<size_t>(cfg->pop_max) * fused_xblocks(cfg->P) * sizeof(float) + 255) & ~size_t(255);
+}
+
+extern "C" int pgpe_ask_sphere(pgpe_state* st, uint64_t seed, int32_t pop, const float* x_star_dev,
+                               float* fitness_dev, void* work_dev, void* stream) {
+  EVO_REQUIRE(st && x_star_dev && fitness_dev && work_dev, EVO_ERR_ARG, "pgpe_ask_sphere: null argument");
+  int rc = check_ask_pop(st, pop, "pgpe_ask_sphere");
+  if (rc) return rc;
+  EVO_REQUIRE(aligned16(x_star_dev) && aligned16(work_dev), EVO_ERR_ARG,
+              "pgpe_ask_sphere: x_star_dev and work_dev must be 16-byte aligned");
+  const int P = st->cfg.P, N = pop / 2, nquads = (P + 3) / 4, xblocks = fused_xblocks(P);
+  hipStream_t s = as_stream(stream);
+  float* part = static_cast<float*>(work_dev);
+  const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>((N + kFusedPairs - 1) / kFusedPairs));
+  hipLaunchKernelGGL(ask_sphere_kernel, grid, dim3(256), 0, s, st->mu, st->sigma, x_star_dev, part, P, nquads, N,
+                     xblocks, st->t, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
+  rc = check_launch("ask_sphere_kernel");
+  if (rc) return rc;
+  hipLaunchKernelGGL(sphere_finish_kernel, dim3(static_cast<unsigned>((pop + 3) / 4)), dim3(256), 0, s, part, xblocks,
+                     pop, fitness_dev);
+  rc = check_launch("sphere_finish_kernel");
+  if (rc) return rc;
+  st->pending = true;
+  st->seed = seed;
+  st->pop = pop;
+  return EVO_OK;
+}
+
 extern "C" int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream) {
   EVO_REQUIRE(st != nullptr && fitness_dev != nullptr, EVO_ERR_ARG, "pgpe_tell: null argument");
   EVO_REQUIRE(st->pending, EVO_ERR_STATE, "pgpe_tell: no pending ask");
-  int rc = run_tell(st, fitness_dev, nullptr, nullptr, as_stream(stream));
+  int rc = run_tell(st, fitness_dev, nullptr, nullptr, nullptr, as_stream(stream));
+  if (rc) return rc;
+  st->pending = false;
+  st->t += 1;
+  return EVO_OK;
+}
+
+extern "C" int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* params_dev, void* stream) {
+  EVO_REQUIRE(st && fitness_dev && params_dev, EVO_ERR_ARG, "pgpe_tell_stored: null argument");
+  EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "pgpe_tell_stored: params_dev must be 16-byte aligned");
+  EVO_REQUIRE(st->pending, EVO_ERR_STATE, "pgpe_tell_stored: no pending ask");
+  int rc = run_tell(st, fitness_dev, nullptr, nullptr, params_dev, as_stream(stream));
   if (rc) return rc;
   st->pending = false;
   st->t += 1;
@@ -600,10 +777,10 @@ extern "C" int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream)
 }
 
 extern "C" int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev,
-                                  void* stream) {
+                                  const float* params_dev, void* stream) {
   EVO_REQUIRE(st && fitness_dev && gmu_dev && gsigma_dev, EVO_ERR_ARG, "evo_pgpe_gradients: null argument");
   EVO_REQUIRE(st->pending, EVO_ERR_STATE, "evo_pgpe_gradients: no pending ask");
-  return run_tell(st, fitness_dev, gmu_dev, gsigma_dev, as_stream(stream));
+  return run_tell(st, fitness_dev, gmu_dev, gsigma_dev, params_dev, as_stream(stream));
 }
 
 extern "C" int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t* rank_dev, float* shaped_dev,

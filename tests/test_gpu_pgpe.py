@@ -3,9 +3,9 @@ Every expected value comes from oracle/ on the same seeded inputs."""
 import numpy as np
 import pytest
 
-from oracle import pgpe as opgpe, philox as ophilox
+from oracle import pgpe as opgpe, philox as ophilox, tasks as otasks
 from workloads import generators as gen
-from tests.util import adam_ill_conditioned, assert_close, dev, host
+from tests.util import adam_ill_conditioned, assert_close, assert_scalar_rel, dev, host
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -200,6 +200,86 @@ def test_clipup_zero_gradient_and_config_errors(evo):
     for bad in ({"optimizer": 3}, {"optimizer": 1, "max_speed": 0.0}, {"optimizer": 2, "momentum": 1.0}):
         with pytest.raises(evo.EvoError):
             evo.PGPE(evo.make_pgpe_config(P=P, pop_max=pop, **bad))
+
+
+@pytest.mark.parametrize("P,pop", [(676, 64), (10007, 10), (4096, 2), (3, 4), (40000, 38), (16384 + 4, 8)])
+def test_ask_sphere_fused_against_oracle(evo, P, pop):
+    """ask fused with the sphere fitness (no population in memory) against the oracle's ask followed
+    by its sphere fitness; several workgroups per row, ragged ends in P and in the pairs."""
+    mu0 = gen.initial_mu(11, P)
+    x_star = gen.sphere_target(12, P)
+    g, o = _states(evo, P, 64, mu0)
+    fit = torch.full((pop,), 7.0, dtype=torch.float32, device="cuda")
+    for it in range(2):                       # the second generation runs from an updated mu, sigma
+        g.ask_sphere(900 + it, pop, dev(x_star), fit)
+        ref = otasks.sphere_fitness(opgpe.ask(o, 900 + it, pop), x_star)
+        assert_scalar_rel(host(fit), ref, 1e-5, "fused sphere fitness, generation %d" % (it + 1))
+        # the materialised path of the library gives the same values up to the order of the sums
+        params = torch.empty(pop, P, dtype=torch.float32, device="cuda")
+        h, _ = _states(evo, P, 64, host(g.mu).copy())
+        h.sigma.copy_(g.sigma)
+        evo.pgpe_set_generation(h.handle, it + 1)
+        h.ask(900 + it, pop, params)
+        td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=dev(x_star))
+        td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=dev(x_star), work=torch.empty(
+            max(evo.rollout_workspace_bytes(td, None, pop), 16), dtype=torch.uint8, device="cuda"))
+        fit2 = torch.empty(pop, dtype=torch.float32, device="cuda")
+        evo.rollout(td, None, params, pop, 1, fit2)
+        assert_scalar_rel(host(fit), host(fit2), 2e-6, "fused against materialised")
+        f = gen.random_fitness(60 + it, pop)   # the fused call leaves a pending ask like pgpe_ask
+        g.tell(dev(f))
+        opgpe.tell(o, f)
+        assert g.generation == o.t == it + 2
+        g.mu.copy_(dev(o.mu))                  # teacher-forced: the next ask starts from the oracle's state
+        g.sigma.copy_(dev(o.sigma))
+    with pytest.raises(evo.EvoError):
+        g.ask_sphere(1, pop + 1, dev(x_star), fit)
+
+
+@pytest.mark.parametrize("P,pop,rule,shaping,optimizer", [(676, 64, 0, 1, 0), (9098, 256, 1, 1, 0), (4609, 10, 0, 0, 0),
+                                                          (7, 2, 0, 1, 2), (20000, 1024, 0, 1, 0),
+                                                          (131072 + 4, 8, 0, 1, 1), (1001, 6, 0, 1, 0)])
+def test_tell_stored_against_oracle(evo, P, pop, rule, shaping, optimizer):
+    """tell with the perturbations read back from the stored population.  The population handed to
+    the library is the ORACLE's (uploaded), so that both sides read the same fp32 values."""
+    mu0 = gen.initial_mu(13, P)
+    kw = {"lr_sigma": 0.005} if rule == 1 else {}
+    g, o = _states(evo, P, pop, mu0, sigma_rule=rule, shaping=shaping, optimizer=optimizer, **kw)
+    scratch = torch.empty(pop, P, dtype=torch.float32, device="cuda")
+    ill = np.zeros(P, dtype=bool)
+    for it in range(2):
+        seed = 3000 + it
+        g.ask(seed, pop, scratch)              # records the pending ask
+        theta = opgpe.ask(o, seed, pop)
+        params = dev(theta)
+        f = gen.random_fitness(90 + it, pop, ties=3 if it == 1 else 0)
+        fd = dev(f)
+        gmu = torch.empty(P, dtype=torch.float32, device="cuda")
+        gsg = torch.empty(P, dtype=torch.float32, device="cuda")
+        evo.evo_pgpe_gradients(g.handle, fd, gmu, gsg, params)
+        g.tell_stored(fd, params)
+        ref_gmu, ref_gsg = opgpe.tell(o, f, return_grads=True, stored=theta)
+        assert_close(host(gmu), ref_gmu, 1e-5, "g_mu from the stored population")
+        assert_close(host(gsg), ref_gsg, 1e-5, "g_sigma from the stored population")
+        if optimizer == 0:
+            ill |= adam_ill_conditioned(ref_gmu, o.cfg.eps)
+            if rule == 1:
+                ill |= adam_ill_conditioned(ref_gsg, o.cfg.eps)
+            assert ill.mean() < 2e-2
+        if optimizer == 0:
+            _compare_state(g, o, ill)
+        else:                                  # m holds the velocity; ClipUp uses v as scratch
+            for name in ("mu", "sigma", "m"):
+                assert_close(host(getattr(g, name)), getattr(o, name), 1e-5, name)
+        assert g.generation == o.t == it + 2
+        # teacher-forced: eps = theta - mu is taken against the library's own mu, so a mu that differs
+        # from the oracle's within its tolerance (1e-5 |mu|) would enter eps ~ sigma amplified by 1 / sigma
+        g.mu.copy_(dev(o.mu)), g.sigma.copy_(dev(o.sigma)), g.m.copy_(dev(o.m)), g.v.copy_(dev(o.v))
+        if rule == 1:
+            g.aux.copy_(dev(np.concatenate([o.m_sigma, o.v_sigma])))
+    with pytest.raises(evo.EvoError) as ei:
+        g.tell_stored(fd, params)
+    assert ei.value.code == -2
 
 
 def test_tell_errors_and_determinism(evo):
