@@ -10,8 +10,9 @@
  *
  * Conventions
  *   - Every pointer named *_dev is DEVICE memory owned by the CALLER.  The library never
- *     allocates, frees or retains device memory, never synchronises, and enqueues all work
- *     on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     allocates, frees or retains device memory, never synchronises (the two checkpoint calls
+ *     excepted), and enqueues all work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).
  *   - Pointers without the suffix are host memory, read during the call only.
  *   - Return value: EVO_OK (0) or a negative evo_err.  evo_last_error() gives a
  *     thread-local message for the last failure.  No C++ exception crosses the boundary.
@@ -94,6 +95,23 @@ int pgpe_reset(pgpe_state* st, void* stream);
 /* Generation index t of the next ask (1 after create/reset; +1 per tell); set it to resume. */
 int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out);
 int pgpe_set_generation(pgpe_state* st, uint32_t t);
+
+/* The centre without perturbation, for testing the current solution (the trainer's "testing" of
+ * Section 2): params_dev[r][i] = mu[i] for r < rows, as fp32 or bfloat16 (nearest even).
+ * Errors: EVO_ERR_ARG (null, rows outside [1, EVO_POP_MAX], bad dtype), EVO_ERR_HIP. */
+int pgpe_center(const pgpe_state* st, int32_t rows, void* params_dev, int32_t dtype, void* stream);
+
+/* Checkpoint (the trainer's periodic model saving, Section 2).  The state of the algorithm is
+ * (config, t, mu, sigma, moments): the noise needs no generator state beyond (seed, t), so a run
+ * resumed from an exported state continues bit-for-bit.  pgpe_state_export writes a header and the
+ * arrays into host_buf (HOST memory, pgpe_state_bytes(st) bytes); pgpe_state_import loads such a
+ * buffer into the arrays of a handle created with the same P and sigma_rule and sets t.  Unlike
+ * every other call, both wait for `stream` before they return.
+ * Errors: EVO_ERR_ARG (null, short buffer, foreign or mismatched state), EVO_ERR_STATE (export
+ * while an ask is pending), EVO_ERR_HIP. */
+size_t pgpe_state_bytes(const pgpe_state* st);
+int pgpe_state_export(const pgpe_state* st, void* host_buf, size_t bytes, void* stream);
+int pgpe_state_import(pgpe_state* st, const void* host_buf, size_t bytes, void* stream);
 
 /* ask: theta[2k][i] = mu[i] + sigma[i] z_k[i],  theta[2k+1][i] = mu[i] - sigma[i] z_k[i],
  * written to params_dev[pop][P] as fp32 (EVO_F32) or bfloat16 rounded to nearest even

@@ -40,6 +40,10 @@ _SIGNATURES = {
     "pgpe_reset": (C.c_int, [C.c_void_p, C.c_void_p]),
     "pgpe_get_generation": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "pgpe_set_generation": (C.c_int, [C.c_void_p, C.c_uint32]),
+    "pgpe_center": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
+    "pgpe_state_bytes": (C.c_size_t, [C.c_void_p]),
+    "pgpe_state_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "pgpe_state_import": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "pgpe_ask": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "pgpe_tell": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "pgpe_ask_sphere_workspace_bytes": (C.c_size_t, [C.POINTER(pgpe_config)]),

@@ -116,6 +116,28 @@ def pgpe_set_generation(h, t):
     _check(_lib.load().pgpe_set_generation(h, t))
 
 
+def pgpe_center(h, rows, params, dtype=EVO_F32):
+    want = torch.float32 if dtype == EVO_F32 else torch.bfloat16
+    _check(_lib.load().pgpe_center(h, rows, _ptr(params, want), dtype, _stream()))
+
+
+def pgpe_state_bytes(h):
+    return int(_lib.load().pgpe_state_bytes(h))
+
+
+def pgpe_state_export(h):
+    """The state as a bytes object (header + arrays); waits for the current stream."""
+    n = pgpe_state_bytes(h)
+    buf = C.create_string_buffer(n)
+    _check(_lib.load().pgpe_state_export(h, buf, n, _stream()))
+    return buf.raw
+
+
+def pgpe_state_import(h, blob):
+    buf = C.create_string_buffer(bytes(blob), len(blob))
+    _check(_lib.load().pgpe_state_import(h, buf, len(blob), _stream()))
+
+
 def pgpe_ask(h, seed, pop, params, dtype=EVO_F32):
     want = torch.float32 if dtype == EVO_F32 else torch.bfloat16
     _check(_lib.load().pgpe_ask(h, seed, pop, _ptr(params, want), dtype, _stream()))
@@ -221,6 +243,15 @@ class PGPE:
 
     def tell_stored(self, fitness, params):
         pgpe_tell_stored(self.handle, fitness, params)
+
+    def center(self, rows, params, dtype=EVO_F32):
+        pgpe_center(self.handle, rows, params, dtype)
+
+    def export_state(self):
+        return pgpe_state_export(self.handle)
+
+    def import_state(self, blob):
+        pgpe_state_import(self.handle, blob)
 
     @property
     def generation(self):

@@ -12,6 +12,7 @@
 #include "bf16.h"
 
 #include <math.h>
+#include <string.h>
 #include <new>
 
 struct pgpe_state {
@@ -510,6 +511,19 @@ __global__ __launch_bounds__(256) void clipup_apply_kernel(float* __restrict__ m
   }
 }
 
+// rows copies of the centre: params[r][i] = mu[i] (fp32) or its bfloat16 rounding.
+template <typename OutT>
+__global__ __launch_bounds__(256) void center_kernel(const float* __restrict__ mu, OutT* __restrict__ params, int P,
+                                                     int rows) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= P) return;
+  const float v = mu[i];
+  for (int r = 0; r < rows; ++r) {
+    if (sizeof(OutT) == 4) reinterpret_cast<float*>(params)[static_cast<size_t>(r) * P + i] = v;
+    else reinterpret_cast<uint16_t*>(params)[static_cast<size_t>(r) * P + i] = to_bf16(v);
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t n, float value) {
   const size_t stride = static_cast<size_t>(gridDim.x) * 256;
   for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) p[i] = value;
@@ -675,6 +689,97 @@ extern "C" int pgpe_reset(pgpe_state* st, void* stream) {
   st->t = 1;
   st->pending = false;
   return rc;
+}
+
+extern "C" int pgpe_center(const pgpe_state* st, int32_t rows, void* params_dev, int32_t dtype, void* stream) {
+  EVO_REQUIRE(st != nullptr && params_dev != nullptr, EVO_ERR_ARG, "pgpe_center: null argument");
+  EVO_REQUIRE(rows >= 1 && rows <= EVO_POP_MAX, EVO_ERR_ARG, "pgpe_center: rows must be in [1, %d] (got %d)",
+              EVO_POP_MAX, rows);
+  EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "pgpe_center: bad dtype %d", dtype);
+  const int P = st->cfg.P;
+  const dim3 grid(static_cast<unsigned>((P + 255) / 256));
+  if (dtype == EVO_F32)
+    hipLaunchKernelGGL(center_kernel<float>, grid, dim3(256), 0, as_stream(stream), st->mu,
+                       static_cast<float*>(params_dev), P, rows);
+  else
+    hipLaunchKernelGGL(center_kernel<uint16_t>, grid, dim3(256), 0, as_stream(stream), st->mu,
+                       static_cast<uint16_t*>(params_dev), P, rows);
+  return check_launch("center_kernel");
+}
+
+// ---- checkpoint: header + the state arrays, in host memory ---------------------------------------
+namespace {
+struct StateHeader {
+  char magic[8];  // "EVOPGPE1"
+  uint32_t header_bytes;
+  uint32_t t;
+  pgpe_config cfg;
+};
+const char kStateMagic[8] = {'E', 'V', 'O', 'P', 'G', 'P', 'E', '1'};
+
+size_t state_bytes(const pgpe_config& c) {
+  const size_t arrays = c.sigma_rule == 1 ? 6 : 4;  // mu, sigma, m, v (+ the two sigma moments)
+  return sizeof(StateHeader) + arrays * static_cast<size_t>(c.P) * sizeof(float);
+}
+
+int copy_checked(void* dst, const void* src, size_t n, hipMemcpyKind kind, hipStream_t s, const char* who) {
+  hipError_t e = hipMemcpyAsync(dst, src, n, kind, s);
+  if (e != hipSuccess) {
+    set_error("%s: copy failed: %s", who, hipGetErrorString(e));
+    return EVO_ERR_HIP;
+  }
+  return EVO_OK;
+}
+}  // namespace
+
+extern "C" size_t pgpe_state_bytes(const pgpe_state* st) { return st ? state_bytes(st->cfg) : 0; }
+
+extern "C" int pgpe_state_export(const pgpe_state* st, void* host_buf, size_t bytes, void* stream) {
+  EVO_REQUIRE(st != nullptr && host_buf != nullptr, EVO_ERR_ARG, "pgpe_state_export: null argument");
+  EVO_REQUIRE(bytes >= state_bytes(st->cfg), EVO_ERR_ARG, "pgpe_state_export: buffer of %zu bytes, %zu needed", bytes,
+              state_bytes(st->cfg));
+  EVO_REQUIRE(!st->pending, EVO_ERR_STATE, "pgpe_state_export: an ask is pending (export between tell and ask)");
+  StateHeader h;
+  memcpy(h.magic, kStateMagic, 8);
+  h.header_bytes = sizeof(StateHeader);
+  h.t = st->t;
+  h.cfg = st->cfg;
+  memcpy(host_buf, &h, sizeof(h));
+  hipStream_t s = as_stream(stream);
+  char* out = static_cast<char*>(host_buf) + sizeof(StateHeader);
+  const size_t row = static_cast<size_t>(st->cfg.P) * sizeof(float);
+  const float* arrays[6] = {st->mu, st->sigma, st->m, st->v, st->aux, st->aux ? st->aux + st->cfg.P : nullptr};
+  const int n = st->cfg.sigma_rule == 1 ? 6 : 4;
+  for (int i = 0; i < n; ++i)
+    if (int rc = copy_checked(out + i * row, arrays[i], row, hipMemcpyDeviceToHost, s, "pgpe_state_export")) return rc;
+  hipError_t e = hipStreamSynchronize(s);
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "pgpe_state_export: %s", hipGetErrorString(e));
+  return EVO_OK;
+}
+
+extern "C" int pgpe_state_import(pgpe_state* st, const void* host_buf, size_t bytes, void* stream) {
+  EVO_REQUIRE(st != nullptr && host_buf != nullptr, EVO_ERR_ARG, "pgpe_state_import: null argument");
+  EVO_REQUIRE(bytes >= sizeof(StateHeader), EVO_ERR_ARG, "pgpe_state_import: buffer shorter than the header");
+  StateHeader h;
+  memcpy(&h, host_buf, sizeof(h));
+  EVO_REQUIRE(memcmp(h.magic, kStateMagic, 8) == 0 && h.header_bytes == sizeof(StateHeader), EVO_ERR_ARG,
+              "pgpe_state_import: not a state written by pgpe_state_export of this library version");
+  EVO_REQUIRE(h.cfg.P == st->cfg.P && h.cfg.sigma_rule == st->cfg.sigma_rule, EVO_ERR_ARG,
+              "pgpe_state_import: state has P = %d, sigma_rule = %d; the handle has P = %d, sigma_rule = %d", h.cfg.P,
+              h.cfg.sigma_rule, st->cfg.P, st->cfg.sigma_rule);
+  EVO_REQUIRE(h.t >= 1 && bytes >= state_bytes(st->cfg), EVO_ERR_ARG, "pgpe_state_import: truncated state");
+  hipStream_t s = as_stream(stream);
+  const char* in = static_cast<const char*>(host_buf) + sizeof(StateHeader);
+  const size_t row = static_cast<size_t>(st->cfg.P) * sizeof(float);
+  float* arrays[6] = {st->mu, st->sigma, st->m, st->v, st->aux, st->aux ? st->aux + st->cfg.P : nullptr};
+  const int n = st->cfg.sigma_rule == 1 ? 6 : 4;
+  for (int i = 0; i < n; ++i)
+    if (int rc = copy_checked(arrays[i], in + i * row, row, hipMemcpyHostToDevice, s, "pgpe_state_import")) return rc;
+  hipError_t e = hipStreamSynchronize(s);  // the host buffer may be released on return
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "pgpe_state_import: %s", hipGetErrorString(e));
+  st->t = h.t;
+  st->pending = false;
+  return EVO_OK;
 }
 
 extern "C" int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out) {

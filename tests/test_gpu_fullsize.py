@@ -49,12 +49,20 @@ def test_cfg5_ask_fitness_tell_full_size(evo):
     evo.rollout(td, None, params, pop, 1, fit)
     assert_scalar_rel(host(fit)[rows], otasks.sphere_fitness(ref_rows, xs), 1e-5, "cfg5 sphere fitness")
     assert np.isfinite(host(fit)).all()
+    # (2b) the same fitness from the fused ask + fitness call, which never writes the population
+    fused = torch.empty(pop, dtype=torch.float32, device="cuda")
+    g.ask_sphere(seed, pop, xd, fused)
+    assert_scalar_rel(host(fused)[rows], otasks.sphere_fitness(ref_rows, xs), 1e-5, "cfg5 fused sphere fitness")
+    assert_scalar_rel(host(fused), host(fit), 2e-6, "cfg5 fused against materialised")
     # (3) tell on a seeded fitness vector (the same for both sides), checked on the sampled columns
     f = gen.random_fitness(77, pop)
     gmu = torch.empty(P, dtype=torch.float32, device="cuda")
     gsg = torch.empty(P, dtype=torch.float32, device="cuda")
     fd = dev(f)
     evo.evo_pgpe_gradients(g.handle, fd, gmu, gsg)
+    smu = torch.empty(P, dtype=torch.float32, device="cuda")
+    ssg = torch.empty(P, dtype=torch.float32, device="cuda")
+    evo.evo_pgpe_gradients(g.handle, fd, smu, ssg, params)      # the stored-population form of the same estimate
     g.tell(fd)
     z = ophilox.pair_noise(seed, 1, np.arange(N), P, cols)
     cshaped = opgpe.centered_rank(f)[1]
@@ -62,6 +70,9 @@ def test_cfg5_ask_fitness_tell_full_size(evo):
     ref_gmu, ref_gsg = opgpe.gradients(z, sg0, cshaped)
     assert_close(host(gmu)[cols], ref_gmu, 1e-5, "cfg5 g_mu")
     assert_close(host(gsg)[cols], ref_gsg, 1e-5, "cfg5 g_sigma")
+    st_gmu, st_gsg = opgpe.gradients_from_population(ref_cols[0::2], np.zeros(len(cols)), sg0, cshaped)
+    assert_close(host(smu)[cols], st_gmu, 1e-5, "cfg5 g_mu from the stored population")
+    assert_close(host(ssg)[cols], st_gsg, 1e-5, "cfg5 g_sigma from the stored population")
     k = o.cfg
     mu1, m1, v1 = opgpe.adam_ascent(np.zeros(len(cols)), np.zeros(len(cols)), np.zeros(len(cols)), ref_gmu, k.lr_mu,
                                     k.beta1, k.beta2, k.eps, 1)
