@@ -30,11 +30,11 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # this file, scaled by what the same counters read for a 1 GiB copy in the same process (on this
 # box FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Sources: the summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1": 2891925,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 32544762,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
-    "cfg3": 19234938,      # profiles/cartpole_kernel_cfg3.md
-    "cfg4": 809177565,     # profiles/mlp_bf16_stream_kernel_cfg4.md
-    "cfg5": 4305221413,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
+    "cfg1": 2891926,       # profiles/mlp_f32_kernel_cfg1.md
+    "cfg2": 32558388,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
+    "cfg3": 19234522,      # profiles/cartpole_kernel_cfg3.md
+    "cfg4": 807679416,     # profiles/mlp_bf16_stream_kernel_cfg4.md
+    "cfg5": 4305241315,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
 }
 
 

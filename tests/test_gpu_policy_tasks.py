@@ -164,10 +164,11 @@ def test_cartpole_single_step(evo):
     assert_close(host(rew), ref_r, 1e-5, "reward")
 
 
-def _cartpole(evo, dims, acts, params, R, steps, seed, t, cp=CP):
+def _cartpole(evo, dims, acts, params, R, steps, seed, t, cp=CP, init_scale=0.2):
     pop = params.shape[0]
     pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
-    td = evo.make_task_desc(evo.EVO_TASK_CARTPOLE, n_rollouts=R, reset_seed=seed, generation=t, cp=cp, init_scale=0.2)
+    td = evo.make_task_desc(evo.EVO_TASK_CARTPOLE, n_rollouts=R, reset_seed=seed, generation=t, cp=cp,
+                            init_scale=init_scale)
     fit = torch.empty(pop, dtype=torch.float32, device="cuda")
     ret = torch.empty(pop, R, dtype=torch.float32, device="cuda")
     fin = torch.empty(pop, R, 4, dtype=torch.float32, device="cuda")
@@ -190,6 +191,24 @@ def test_cartpole_short_horizon(evo, dims, acts, pop, R, steps):
     assert_scalar_rel(fit, rfit, 1e-5, "fitness")
     if steps == 1:      # after one step the state is the reset state advanced once: same for all members in x, theta
         assert np.allclose(fin[0, :, 0], fin[1, :, 0]) and np.allclose(fin[0, :, 2], fin[1, :, 2])
+
+
+@pytest.mark.parametrize("init_scale", [0.02, 0.6])
+def test_cartpole_narrow_and_wide_reset(evo, init_scale):
+    """The spread of the initial states is the task's difficulty knob (Section 3: an easy and a hard
+    version of the swing-up): a narrow and a wide reset against the oracle, and the narrow one really
+    starts every roll-out next to the hanging-down state."""
+    dims, acts, pop, R, steps = (5, 64, 64, 1), (1, 1, 1), 4, 16, 24
+    params = gen.random_params(29, pop, mlp_param_count(dims), 0.5)
+    fit, ret, fin = _cartpole(evo, dims, acts, params, R, steps, 99, 2, init_scale=init_scale)
+    rfit, rret, rfin, _ = otasks.cartpole_rollout(params, dims, acts, 99, 2, R, steps, CP, init_scale=init_scale,
+                                                  return_details=True)
+    assert_close(fin, rfin, 1e-5, "final states")
+    assert_close(ret, rret, 1e-5, "returns")
+    assert_scalar_rel(fit, rfit, 1e-5, "fitness")
+    _, _, fin0 = _cartpole(evo, dims, acts, params, R, 1, 99, 2, init_scale=init_scale)
+    spread = np.abs(fin0[0, :, 2] - np.pi).max()      # one step after the reset
+    assert spread < 5.0 * init_scale and (init_scale > 0.1 or spread < 0.15)
 
 
 def test_cartpole_termination_and_zero_policy(evo):
