@@ -4,4 +4,4 @@ Test infrastructure only.  Nothing in the product path (the HIP library and its 
 binding) imports this package; it is used by tests/, by the smoke check and by the bench's
 cpu_baseline leg.  It shares no code with the HIP path.
 """
-from . import philox, pgpe, policy, tasks, generation  # noqa: F401
+from . import philox, pgpe, policy, tasks, seq2seq, generation  # noqa: F401

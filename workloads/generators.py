@@ -4,7 +4,8 @@ Every function returns plain numpy arrays that BOTH the CPU oracle and the HIP p
 fed with.  The recipes mirror the shapes and value distributions of the paper's example
 tasks (Section 3): Gaussian class blobs for the plumbing classifier, MNIST-shaped images
 (the MNIST example of Section 3 / Table 1; the real data set is not used), per-member
-observations with a fixed random teacher, and a shifted sphere.
+observations with a fixed random teacher, a shifted sphere, and the addition strings of the
+sequence-to-sequence example ("012+345=" -> "0357").
 """
 import numpy as np
 
@@ -87,3 +88,19 @@ def random_states(seed, n, scale=1.0):
     s = r.standard_normal((n, 4)) * np.array([1.0, 2.0, 3.0, 4.0]) * scale
     a = np.tanh(r.standard_normal(n))
     return s.astype(np.float32), a.astype(np.float32)
+
+
+def addition_batch(seed, generation, n=128, digits=3):
+    """Token strings for the addition of two random integers below 10^digits, zero-padded to equal
+    lengths as in the paper's sequence-to-sequence example: query[n, 2 digits + 2] =
+    "aaa+bbb=" with '+' = 10 and '=' = 11, answer[n, digits + 1] = the decimal digits of the sum,
+    most significant first.  int32."""
+    r = _rng(seed, 9, generation)
+    a = r.integers(0, 10 ** digits, n)
+    b = r.integers(0, 10 ** digits, n)
+
+    def dec(x, width):
+        return np.stack([(x // 10 ** (width - 1 - i)) % 10 for i in range(width)], axis=1)
+
+    query = np.concatenate([dec(a, digits), np.full((n, 1), 10), dec(b, digits), np.full((n, 1), 11)], axis=1)
+    return query.astype(np.int32), dec(a + b, digits + 1).astype(np.int32)
