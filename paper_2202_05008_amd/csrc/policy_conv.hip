@@ -14,14 +14,19 @@
 //
 // conv2 arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
 // v_mfma_f32_16x16x4_f32 takes 32 cycles (1024 MACs), and the two do not overlap, so the fp32
-// matrix instruction is only 1.4x the vector rate.  v_mfma_f32_16x16x32_bf16 takes 16 cycles
-// for 8192 MACs.  conv2 therefore runs on the bf16 matrix instruction with every fp32 operand
-// split exactly into three bfloat16 terms x = h + m + l (h = bf16(x), m = bf16(x - h),
-// l = bf16(x - h - m); 24 significand bits in all), and six of the nine partial products per
-// operand pair accumulated in fp32: hh' + hm' + mh' + mm' + hl' + lh'.  The three dropped
-// products are below 2^-24 of the full one, i.e. below the rounding of an fp32 multiply, and
-// each bf16 x bf16 product is exact in fp32: the result has fp32 accuracy at half the issue
-// cycles of the fp32 matrix instruction.
+// matrix instruction is only 1.4x the vector rate.  v_mfma_f32_16x16x32_f16 takes 16 cycles
+// for 8192 MACs.  conv2 therefore runs on the fp16 matrix instruction with every fp32 operand
+// split into two half-precision terms x ~ h + 2^-11 m: h = fp16(x) (11 significand bits) and
+// m = fp16(2^11 (x - h)), the residual (exact in fp32) scaled back into the normal range so that
+// it keeps 11 bits of its own: 22 bits in all, |x - h - 2^-11 m| <= 2^-22 |x|.  Three of the four
+// partial products are accumulated in fp32, h h' in one accumulator and h m' + m h' in a second
+// one that enters with the factor 2^-11; the dropped m m' is below 2^-22 of the full product.
+// Every fp16 x fp16 product is exact in fp32, so a product is within 3 * 2^-22 of the fp32 one
+// and a 72-term sum well inside the 1e-5 gate (measured: 4e-7 of the rms), at 3 / 16 of the
+// issue cycles of the fp32 matrix instruction.  The leading term needs |x| within the fp16
+// range: the kernel tracks the largest conv1 activation of an image and checks the conv2 weights
+// when it loads them, and where either exceeds the range it returns NaN logits for the image
+// (the member's fitness is then NaN and ranks lowest) instead of a wrong finite value.
 //
 // Band pipeline.  conv2 output row b needs the (zero-padded) conv1 rows 2b .. 2b+3 only, so the
 // conv1 output is never held whole: pass b of conv1 produces padded rows 2b+2 and 2b+3 and
@@ -35,26 +40,27 @@
 // contraction index k = tap * 8 + channel, padded from 72 to 96 = 3 steps of 32 with zero
 // weights; lane group q supplies the 8 channels of tap 4 step + q: one 16-byte LDS read per
 // split term from the band buffer, which holds [term][row pair][column][row parity][channel]
-// bfloat16.
+// half-precision values.
 #include "bf16.h"
 #include "kernels.h"
 
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
 constexpr int kImgW = kHMax + 2;                     // padded image row (30)
 constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; its consumed part takes the conv2 output
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
-constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as bfloat16
+constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as fp16
 constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 2a+1, interleaved pixel by pixel
 constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
-constexpr int kBandBytes = 3 * kBandTerm;            // 3072 bytes per band buffer
-constexpr int kBandFloats = kBandBytes / 4;          // 768
-constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 2440 floats = 9,760 bytes per wave
+constexpr int kBandBytes = 2 * kBandTerm;            // 2048 bytes per band buffer
+constexpr int kBandFloats = kBandBytes / 4;          // 512
+constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 1928 floats = 7,712 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -104,13 +110,12 @@ __device__ __forceinline__ float row16_max(float v) {
   return v;
 }
 
-// x = h + m + l with three bfloat16 terms; both subtractions are exact in fp32.
-__device__ __forceinline__ void split3(float x, __bf16& h, __bf16& m, __bf16& l) {
-  h = static_cast<__bf16>(x);
-  float r = x - static_cast<float>(h);
-  m = static_cast<__bf16>(r);
-  r -= static_cast<float>(m);
-  l = static_cast<__bf16>(r);
+// x ~ h + 2^-11 m with two fp16 terms (round to nearest); the subtraction is exact in fp32.
+constexpr float kSplitScale = 2048.0f, kSplitUnscale = 1.0f / 2048.0f;
+constexpr float kHalfMax = 65504.0f;  // largest finite fp16
+__device__ __forceinline__ void split2(float x, _Float16& h, _Float16& m) {
+  h = static_cast<_Float16>(x);
+  m = static_cast<_Float16>((x - static_cast<float>(h)) * kSplitScale);
 }
 
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
@@ -150,20 +155,24 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
 
   // conv2 weights as matrix B operands, w2b[term][step]: lane group q holds tap 4 step + q (zero
-  // beyond tap 8), element j = input channel j, column n; each weight split into three terms
+  // beyond tap 8), element j = input channel j, column n; each weight split into two terms
   const int n = lane & 15, q = lane >> 4;
-  bf16x8 w2b[3][3];
+  f16x8 w2b[2][3];
+  float w2_max = 0.f;
 #pragma unroll
   for (int st = 0; st < 3; ++st) {
     const int tap = 4 * st + q;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const float x = tap < 9 ? W2[(tap * kC1 + j) * kC2 + n] : 0.f;
-      __bf16 h, m, l;
-      split3(x, h, m, l);
-      w2b[0][st][j] = h, w2b[1][st][j] = m, w2b[2][st][j] = l;
+      w2_max = fmaxf(w2_max, fabsf(x));
+      _Float16 h, m;
+      split2(x, h, m);
+      w2b[0][st][j] = h, w2b[1][st][j] = m;
     }
   }
+  // a weight beyond the fp16 range (or a NaN, which the comparison also rejects) poisons the member
+  const bool w2_bad = __any(!(w2_max <= kHalfMax));
   const float bias2 = b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
@@ -231,6 +240,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
     wave_sync();
 
+    float a1_max = 0.f;  // largest conv1 activation of this image seen by this lane
 #pragma unroll 1
     for (int b = -1; b < H4; ++b) {
       // ---- conv1 + ReLU + pool, pass b: padded conv1 rows 2b+2, 2b+3 (pooled rows 2b+1, 2b+2) ----
@@ -260,16 +270,18 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
               }
             v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) + bias1v[c], 0.f);
           }
+          a1_max = fmaxf(fmaxf(a1_max, v[0]), v[1]);
+          a1_max = fmaxf(fmaxf(a1_max, v[2]), v[3]);
         }
-        // three bfloat16 terms of the four channels: 8 bytes per term
-        uint2 term[3];
+        // two fp16 terms of the four channels: 8 bytes per term
+        uint2 term[2];
         {
-          __bf16 t[3][4];
+          _Float16 t[2][4];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) split3(v[c], t[0][c], t[1][c], t[2][c]);
+          for (int c = 0; c < 4; ++c) split2(v[c], t[0][c], t[1][c]);
 #pragma unroll
-          for (int k = 0; k < 3; ++k) {
-            const bf16x2_t lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
+          for (int k = 0; k < 2; ++k) {
+            const f16x2 lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
             term[k] = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
           }
         }
@@ -278,11 +290,11 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         char* nxt = bandb + ((b + 1) & 1) * kBandBytes + band_off(c1_rs, c1_wx + 1) + 8 * c1_cg;
         if (b >= 0) {
 #pragma unroll
-          for (int k = 0; k < 3; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
+          for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
         }
         if (b + 1 < H4) {
 #pragma unroll
-          for (int k = 0; k < 3; ++k) *reinterpret_cast<uint2*>(nxt + k * kBandTerm) = term[k];
+          for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(nxt + k * kBandTerm) = term[k];
         }
       }
       wave_sync();
@@ -290,22 +302,27 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 
       // ---- conv2 + ReLU + pool, band b: two independent tiles (windows 0..3 and 4..7 of the row) --
       const char* bb = bandb + (b & 1) * kBandBytes;
-      floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+      floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h'
+      floatx4 low0 = {0.f, 0.f, 0.f, 0.f}, low1 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
-        bf16x8 a0[3], a1[3];  // [term] of tile 0 and tile 1
+        f16x8 a0[2], a1[2];  // [term] of tile 0 and tile 1
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          a0[k] = *reinterpret_cast<const bf16x8*>(bb + a_off[0][st] + k * kBandTerm);
-          a1[k] = *reinterpret_cast<const bf16x8*>(bb + a_off[1][st] + k * kBandTerm);
+        for (int k = 0; k < 2; ++k) {
+          a0[k] = *reinterpret_cast<const f16x8*>(bb + a_off[0][st] + k * kBandTerm);
+          a1[k] = *reinterpret_cast<const f16x8*>(bb + a_off[1][st] + k * kBandTerm);
         }
-        // the six partial products, smallest first: l h', h l', m m', m h', h m', h h'
-        constexpr int ka[6] = {2, 0, 1, 1, 0, 0}, kb[6] = {0, 2, 1, 0, 1, 0};
+        low0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[1], w2b[0][st], low0, 0, 0, 0);
+        low1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[1], w2b[0][st], low1, 0, 0, 0);
+        low0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[1][st], low0, 0, 0, 0);
+        low1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[1][st], low1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[0][st], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[0][st], acc1, 0, 0, 0);
+      }
 #pragma unroll
-        for (int t = 0; t < 6; ++t) {
-          acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ka[t]], w2b[kb[t]][st], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[ka[t]], w2b[kb[t]][st], acc1, 0, 0, 0);
-        }
+      for (int i = 0; i < 4; ++i) {
+        acc0[i] = fmaf(low0[i], kSplitUnscale, acc0[i]);
+        acc1[i] = fmaf(low1[i], kSplitUnscale, acc1[i]);
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n
       if (q < H4) a2[(b * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
@@ -340,6 +357,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       logit += __shfl_xor(logit, 32, 64);
       logit += bias_d;
     }
+    if (w2_bad || __any(!(a1_max <= kHalfMax))) logit = __builtin_nanf("");  // outside the range of the split
     wave_sync();
     // both scratch uses sat on zero-padded buffers: restore the zeros (the next image's
     // interior is rewritten anyway, the borders must read as zero again)

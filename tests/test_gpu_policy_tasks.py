@@ -108,6 +108,38 @@ def test_convnet_many_chunks_and_zero_weights(evo):
     assert abs(fit[3] + np.log(10.0)) < 1e-5 * np.log(10.0)
 
 
+@pytest.mark.parametrize("scale", [1e-3, 0.02, 3.0])
+def test_convnet_keeps_fp32_accuracy_over_value_ranges(evo, scale):
+    """conv2 runs on the fp16 matrix instruction with every operand split into two scaled fp16
+    terms: the result must stay fp32-accurate for small and for large weights alike."""
+    H, n_cls, pop, B = 28, 10, 3, 21
+    P = convnet_param_count(8, 16, n_cls, H)
+    params = gen.random_params(31, pop, P, scale)
+    img, _ = gen.mnist_shaped_batch(32, 1, B, n_cls, H)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_CONVNET, (H, 8, 16, n_cls))
+    out = torch.empty(pop, B, n_cls, dtype=torch.float32, device="cuda")
+    evo.pop_forward(pd, dev(params), dev(img), 0, out, pop, B)
+    assert_close(host(out), opolicy.convnet_forward(params, img, 8, 16, n_cls), 1e-5, "convnet logits, scale %g" % scale)
+
+
+def test_convnet_beyond_the_fp16_range_is_loud(evo):
+    """A conv2 weight of 1e5 is outside the range of the leading fp16 term: that member's logits are
+    non-finite (its fitness then ranks lowest), the other members are untouched."""
+    H, n_cls, pop, B = 28, 10, 2, 5
+    P = convnet_param_count(8, 16, n_cls, H)
+    params = gen.random_params(33, pop, P, 0.2)
+    params[1, 88 + 7] = 1.0e5                      # one weight of W2 (W1 and b1 take 80 + 8 entries)
+    img, y = gen.mnist_shaped_batch(34, 1, B, n_cls, H)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_CONVNET, (H, 8, 16, n_cls))
+    out = torch.empty(pop, B, n_cls, dtype=torch.float32, device="cuda")
+    evo.pop_forward(pd, dev(params), dev(img), 0, out, pop, B)
+    got = host(out)
+    assert_close(got[0], opolicy.convnet_forward(params[:1], img, 8, 16, n_cls)[0], 1e-5, "the in-range member")
+    assert not np.isfinite(got[1]).any()
+    fit = _classify(evo, pd, dev(params), dev(img), dev(y), pop, B)
+    assert np.isfinite(fit[0]) and not np.isfinite(fit[1])
+
+
 # ---------------------------------------------------------------- bf16 MLP on the matrix cores
 @pytest.mark.parametrize("dims,acts,pop,B", [((64, 256, 256, 16), (2, 2, 0), 6, 64), ((64, 256, 256, 16), (2, 2, 0), 3, 40),
                                              ((64, 256, 256, 16), (2, 2, 0), 3, 128),       # two tiles of 64 rows
