@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # The ConvNet and cart-pole kernels deliver fp32-accurate results (the algorithmic flops below are
 # fp32 flops) and are priced against the fp32 matrix peak, although their contractions are issued
-# as bf16 matrix instructions on exact three-term operand splits (six instructions per product).
+# as fp16 matrix instructions on two-term scaled operand splits (three instructions per product).
 PEAK_MFMA_F32_TF = 157.3       # dense fp32 matrix
 PEAK_MFMA_BF16_TF = 2500.0
 PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 GHz x 2 flop)

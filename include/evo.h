@@ -174,6 +174,9 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      conv3x3 (zero-padded, stride 1) -> ReLU -> maxpool 2x2/2, twice, then a dense layer.
  *      Flat parameters: W1[3][3][1][c1], b1[c1], W2[3][3][c1][c2], b2[c2],
  *      Wd[(H/4)(H/4)c2][n_cls], bd[n_cls]; dense input flattened (h, w, c), c fastest.
+ *      fp32 results; the second convolution is evaluated on 16-bit matrix instructions with
+ *      two-term operand splits, which needs its weights and input activations below 65504 in
+ *      magnitude: an image for which they are not gets NaN logits (a NaN fitness ranks lowest).
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
@@ -201,7 +204,9 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *   REGRESS   -mean_{b,a} (policy(obs_b)[a] - target[m][b][a])^2   target_dev = fp32 [pop][B][A]
  *   SPHERE    -sum_i (theta[m][i] - x_star[i])^2                    target_dev = fp32 x_star[P]; policy may be NULL
  *   CARTPOLE  mean over n_rollouts of the episode return of the swing-up task below; the whole
- *             episode (policy weights, environment state) stays on chip for all `steps`.
+ *             episode (policy weights, environment state) stays on chip for all `steps`.  With two
+ *             hidden layers the second one has the same 65504 limit on its weights and inputs as the
+ *             ConvNet's second convolution: a member outside it gets a NaN fitness.
  * Cart-pole: state (x, x_d, th, th_d), th from upright; cp = {g, m_cart M, m_pole m, length l,
  *   friction b, force scale, dt, x_limit}; F = force_scale * a - b x_d (a = policy output);
  *   D = 4(M+m) - 3 m cos^2 th;  x_dd = [4F + 2 m l th_d^2 sin th - 3 m g sin th cos th] / D;

@@ -14,16 +14,20 @@
 //
 // Register layouts (lane = 16 q + j):
 //   v_mfma_f32_16x16x4_f32    A[row j][k = q], B[k = q][col j]: one float each
-//   v_mfma_f32_16x16x32_bf16  A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7: eight bfloat16 each
+//   v_mfma_f32_16x16x32_f16   A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7: eight fp16 each
 //   both                      D[row 4 q + i][col j], i = 0..3: four floats
 //
 // With two hidden layers, layer 1 (K = 5) is computed transposed on the fp32 instruction
 // (rows = neurons, columns = roll-outs), so that a lane ends up with four consecutive neurons
-// of one roll-out: after tanh they are split exactly into three bfloat16 terms h + m + l and
-// stored with one 8-byte LDS write per term.  Layer 2 (K = H) then runs on the bf16 instruction
-// (16 cycles for 8192 multiply-adds against 32 cycles for 1024 of the fp32 one) with the six
-// partial products hh' + hm' + mh' + mm' + hl' + lh' accumulated in fp32; the three products
-// left out are below 2^-24 of the full one, so the layer keeps fp32 accuracy.
+// of one roll-out: after the activation they are split into two half-precision terms
+// x ~ h + 2^-11 m (h = fp16(x), m = fp16(2^11 (x - h)): 22 significand bits, the residual scaled
+// back into the normal range) and stored with one 8-byte LDS write per term.  Layer 2 (K = H)
+// then runs on the fp16 instruction (16 cycles for 8192 multiply-adds against 32 cycles for 1024
+// of the fp32 one) with h h' in one fp32 accumulator and h m' + m h' in a second one that enters
+// with the factor 2^-11; the dropped m m' is below 2^-22 of the full product, so the layer stays
+// within a few 1e-7 of fp32 arithmetic.  The leading term needs |x| within the fp16 range: the
+// weights are checked when they are loaded, activations other than tanh are tracked, and a member
+// outside the range gets a NaN fitness (it then ranks lowest) instead of a wrong finite one.
 #include "bf16.h"
 #include "kernels.h"
 #include "philox.h"
@@ -31,15 +35,15 @@
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-// x = h + m + l with three bfloat16 terms; both subtractions are exact in fp32.
-__device__ __forceinline__ void split3(float x, __bf16& h, __bf16& m, __bf16& l) {
-  h = static_cast<__bf16>(x);
-  float r = x - static_cast<float>(h);
-  m = static_cast<__bf16>(r);
-  r -= static_cast<float>(m);
-  l = static_cast<__bf16>(r);
+// x ~ h + 2^-11 m with two fp16 terms (round to nearest); the subtraction is exact in fp32.
+constexpr float kSplitScale = 2048.0f, kSplitUnscale = 1.0f / 2048.0f;
+constexpr float kHalfMax = 65504.0f;  // largest finite fp16
+__device__ __forceinline__ void split2(float x, _Float16& h, _Float16& m) {
+  h = static_cast<_Float16>(x);
+  m = static_cast<_Float16>((x - static_cast<float>(h)) * kSplitScale);
 }
 
 struct CartpoleConst {
@@ -133,8 +137,8 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   constexpr int KP = H < 32 ? 32 : H;      // contraction length of layer 2, padded to the instruction's 32
   constexpr int KS2 = KP / 32;             // matrix-core steps of layer 2 per split term pair
   constexpr int kRowB = (KP + 8) * 2;      // bytes of one roll-out's row of one term (16 bytes of padding)
-  constexpr int kTermB = 16 * kRowB;       // one term of the hidden activations: [roll-out][neuron] bfloat16
-  __shared__ __attribute__((aligned(16))) unsigned char hb[TWO ? 3 * kTermB : 16];
+  constexpr int kTermB = 16 * kRowB;       // one term of the hidden activations: [roll-out][neuron] fp16
+  __shared__ __attribute__((aligned(16))) unsigned char hb[TWO ? 2 * kTermB : 16];
   __shared__ float part[NT][16];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -148,7 +152,8 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding)
   const float bias1 = theta[5 * H + col];
   const float* th2 = theta + 5 * H + H;
-  bf16x8 w2b[3][TWO ? KS2 : 1];  // [term][step]: element e is W2[32 step + 8 q + e][col]
+  f16x8 w2b[2][TWO ? KS2 : 1];  // [term][step]: element e is W2[32 step + 8 q + e][col]
+  float range_max = 0.f;         // largest |layer-2 weight| (and, unless tanh bounds them, |activation|) of this lane
   float bias1t[4];               // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
   float bias2 = 0.f, w3, b3;
   if (TWO) {
@@ -157,9 +162,11 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int k = 32 * s + 8 * q + e;
-        __bf16 h, m, l;
-        split3(k < H ? th2[k * H + col] : 0.f, h, m, l);
-        w2b[0][s][e] = h, w2b[1][s][e] = m, w2b[2][s][e] = l;
+        const float x = k < H ? th2[k * H + col] : 0.f;
+        range_max = fmaxf(range_max, fabsf(x));
+        _Float16 h, m;
+        split2(x, h, m);
+        w2b[0][s][e] = h, w2b[1][s][e] = m;
       }
 #pragma unroll
     for (int i = 0; i < 4; ++i) bias1t[i] = theta[5 * H + 16 * wave + 4 * q + i];
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     w3 = th2[H * H + H + col];
     b3 = th2[H * H + H + H];
     // columns H .. KP - 1 of the activation rows are never written and must read as zero
-    for (int i = threadIdx.x; i < 3 * kTermB / 4; i += 64 * NT) reinterpret_cast<uint32_t*>(hb)[i] = 0u;
+    for (int i = threadIdx.x; i < 2 * kTermB / 4; i += 64 * NT) reinterpret_cast<uint32_t*>(hb)[i] = 0u;
     __syncthreads();
   } else {
     w3 = th2[col];
@@ -201,36 +208,39 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         floatx4 acc = {bias1t[0], bias1t[1], bias1t[2], bias1t[3]};
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a, a0, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1b, a1, acc, 0, 0, 0);
-        // neurons 16 wave + 4 q .. + 3 of roll-out j: three terms, 8 bytes each
+        // neurons 16 wave + 4 q .. + 3 of roll-out j: two terms, 8 bytes each
         {
-          __bf16 t[3][4];
+          _Float16 t[2][4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) split3(act_apply(acc[i], act1), t[0][i], t[1][i], t[2][i]);
+          for (int i = 0; i < 4; ++i) {
+            const float h1 = act_apply(acc[i], act1);
+            if (!TANH) range_max = fmaxf(range_max, fabsf(h1));
+            split2(h1, t[0][i], t[1][i]);
+          }
           unsigned char* dst = hb + j * kRowB + (16 * wave + 4 * q) * 2;
 #pragma unroll
-          for (int k = 0; k < 3; ++k) {
-            const bf16x2_t lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
+          for (int k = 0; k < 2; ++k) {
+            const f16x2 lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
             *reinterpret_cast<uint2*>(dst + k * kTermB) =
                 make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
           }
         }
         __syncthreads();
         // ---- layer 2: lane (row j, k group q) reads 8 consecutive activations per term and step ----
-        floatx4 acc2 = {bias2, bias2, bias2, bias2};
+        floatx4 acc2 = {bias2, bias2, bias2, bias2};  // bias + h h'
+        floatx4 low2 = {0.f, 0.f, 0.f, 0.f};          // 2^11 (h m' + m h')
         const unsigned char* src = hb + j * kRowB + 16 * q;
 #pragma unroll
         for (int s2 = 0; s2 < KS2; ++s2) {
-          bf16x8 at[3];
+          f16x8 at[2];
 #pragma unroll
-          for (int k = 0; k < 3; ++k) at[k] = *reinterpret_cast<const bf16x8*>(src + k * kTermB + 64 * s2);
-          // the six partial products, smallest first: l h', h l', m m', m h', h m', h h'
-          constexpr int ka[6] = {2, 0, 1, 1, 0, 0}, kb[6] = {0, 2, 1, 0, 1, 0};
-#pragma unroll
-          for (int t = 0; t < 6; ++t)
-            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at[ka[t]], w2b[kb[t]][s2], acc2, 0, 0, 0);
+          for (int k = 0; k < 2; ++k) at[k] = *reinterpret_cast<const f16x8*>(src + k * kTermB + 64 * s2);
+          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[1], w2b[0][s2], low2, 0, 0, 0);
+          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0], w2b[1][s2], low2, 0, 0, 0);
+          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0], w2b[0][s2], acc2, 0, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] = act_apply(acc2[i], act2) * w3;
+        for (int i = 0; i < 4; ++i) p[i] = act_apply(fmaf(low2[i], kSplitUnscale, acc2[i]), act2) * w3;
       } else {
         floatx4 acc = {bias1, bias1, bias1, bias1};
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
@@ -272,6 +282,15 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     }
     total += valid ? ret : 0.f;
     __syncthreads();
+  }
+  // a layer-2 operand outside the fp16 range (or NaN) anywhere in the workgroup poisons the member
+  if (TWO) {
+    __shared__ int out_of_range;
+    if (threadIdx.x == 0) out_of_range = 0;
+    __syncthreads();
+    if (!(range_max <= kHalfMax)) out_of_range = 1;
+    __syncthreads();
+    if (out_of_range) total = __builtin_nanf("");
   }
   // ---- fitness = mean return over the roll-outs (rows j = 0..15, fixed order) -----------------
   total = row16_sum(total);

@@ -243,6 +243,27 @@ def test_cartpole_narrow_and_wide_reset(evo, init_scale):
     assert spread < 5.0 * init_scale and (init_scale > 0.1 or spread < 0.15)
 
 
+def test_cartpole_layer2_range(evo):
+    """Layer 2 runs on the fp16 matrix instruction with two-term operands: small and large weights
+    keep fp32 accuracy, and a weight beyond the fp16 range gives that member a NaN fitness."""
+    dims, acts, R = (5, 64, 64, 1), (1, 1, 1), 16
+    P = mlp_param_count(dims)
+    # (large weights saturate the tanh units and make the closed loop so sensitive that any fp32
+    # evaluation leaves the fp64 trajectory within a few steps: two steps there, twelve for small weights)
+    for scale, steps in ((1e-3, 12), (1.0, 2)):
+        params = gen.random_params(41, 3, P, scale)
+        fit, ret, fin = _cartpole(evo, dims, acts, params, R, steps, 5, 1)
+        rfit, rret, rfin, _ = otasks.cartpole_rollout(params, dims, acts, 5, 1, R, steps, CP, return_details=True)
+        assert_close(fin, rfin, 1e-5, "final states, weight scale %g" % scale)
+        assert_scalar_rel(fit, rfit, 1e-5, "fitness, weight scale %g" % scale)
+    params = gen.random_params(42, 2, P, 0.5)
+    params[1, 5 * 64 + 64 + 70] = -1.0e5             # one weight of the second layer
+    fit, _, _ = _cartpole(evo, dims, acts, params, R, 12, 5, 1)
+    rfit = otasks.cartpole_rollout(params[:1], dims, acts, 5, 1, R, 12, CP)
+    assert_scalar_rel(fit[:1], rfit, 1e-5, "the in-range member")
+    assert np.isnan(fit[1])
+
+
 def test_cartpole_termination_and_zero_policy(evo):
     dims, acts = (5, 16, 16, 1), (1, 1, 1)
     P = mlp_param_count(dims)
