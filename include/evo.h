@@ -42,8 +42,8 @@ typedef enum {
 
 enum { EVO_F32 = 0, EVO_BF16 = 1 };                                   /* parameter storage  */
 enum { EVO_ACT_NONE = 0, EVO_ACT_TANH = 1, EVO_ACT_RELU = 2 };
-enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1 };
-enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3 };
+enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1, EVO_POLICY_LSTM_SEQ2SEQ = 2 };
+enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3, EVO_TASK_SEQ2SEQ = 4 };
 enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1 };                        /* Philox stream tags */
 enum { EVO_OPT_ADAM = 0, EVO_OPT_CLIPUP = 1, EVO_OPT_MOMENTUM = 2 };  /* optimizer of mu    */
 #define EVO_POP_MAX 4096
@@ -177,6 +177,16 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      fp32 results; the second convolution is evaluated on 16-bit matrix instructions with
  *      two-term operand splits, which needs its weights and input activations below 65504 in
  *      magnitude: an image for which they are not gets NaN logits (a NaN fitness ranks lowest).
+ * LSTM sequence-to-sequence (kind EVO_POLICY_LSTM_SEQ2SEQ; Section 3, "Seq2Seq Learning"; the carried
+ *      cells are the policy state of Section 4): dims = {V, H, n_out}, H = 64 or 128, n_out <= V <= 16.
+ *      Tokens are integers in [0, V).  LSTM cell, gates i, f, g, o in columns g H + u:
+ *        a = Wx[token] + h Wh + b;  c' = sigmoid(a_f) c + sigmoid(a_i) tanh(a_g);  h' = sigmoid(a_o) tanh(c').
+ *      The encoder cell starts from h = c = 0 and reads the query; the decoder cell starts from the
+ *      encoder's final (h, c) and takes one step per answer position j, its input being token V - 1
+ *      for j = 0 and the true answer token j - 1 afterwards; logits_j = h_j Wo + bo.
+ *      Flat parameters: enc Wx[V][4H], Wh[H][4H], b[4H]; dec Wx[V][4H], Wh[H][4H], b[4H];
+ *      Wo[H][n_out]; bo[n_out].  fp32 results; the recurrent and output weights must stay below
+ *      65504 in magnitude (two-term fp16 operand splits), else the member's outputs are NaN.
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
@@ -203,6 +213,10 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *   CLASSIFY  -mean_b CE(softmax(policy(obs_b)), labels[b])        target_dev = int32 labels[B]
  *   REGRESS   -mean_{b,a} (policy(obs_b)[a] - target[m][b][a])^2   target_dev = fp32 [pop][B][A]
  *   SPHERE    -sum_i (theta[m][i] - x_star[i])^2                    target_dev = fp32 x_star[P]; policy may be NULL
+ *   SEQ2SEQ   -mean over samples and answer positions of the cross-entropy of the true answer token
+ *             under an EVO_POLICY_LSTM_SEQ2SEQ policy; obs_dev = int32 query tokens [B][seq_in]
+ *             (passed through the float pointer), target_dev = int32 answer tokens [B][seq_out],
+ *             shared by all members (obs_member_stride = 0); seq_in <= 32, seq_out <= 16.
  *   CARTPOLE  mean over n_rollouts of the episode return of the swing-up task below; the whole
  *             episode (policy weights, environment state) stays on chip for all `steps`.  With two
  *             hidden layers the second one has the same 65504 limit on its weights and inputs as the
@@ -223,13 +237,13 @@ typedef struct {
   int32_t P;                   /* SPHERE: parameters per member                              */
   uint64_t reset_seed;         /* CARTPOLE                                                   */
   uint32_t generation;         /* CARTPOLE: counter word t of the reset stream               */
-  int32_t reserved;
+  int32_t seq_in;              /* SEQ2SEQ: tokens per query                                  */
   const float* obs_dev;        /* CLASSIFY / REGRESS: observations, see pop_forward          */
   int64_t obs_member_stride;
   const void* target_dev;      /* labels / targets / x_star, see above                       */
   float cp[8];                 /* CARTPOLE constants                                         */
   float init_scale;            /* CARTPOLE: scale of the reset normals                       */
-  int32_t reserved2;
+  int32_t seq_out;             /* SEQ2SEQ: tokens per answer                                 */
   void* work_dev;              /* workspace of rollout_workspace_bytes(...) bytes, or NULL if 0 */
 } task_desc;
 
@@ -266,6 +280,10 @@ int evo_task_step(const task_desc* td, const float* state_dev, const float* acti
  * final_dev[pop][n_rollouts][4] final states (either may be NULL). */
 int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                         int32_t steps, float* ret_dev, float* final_dev, void* stream);
+
+/* Logits of an EVO_TASK_SEQ2SEQ task: logits_dev[pop][B][seq_out][n_out] (fp32). */
+int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                       float* logits_dev, void* stream);
 
 const char* evo_last_error(void);
 /* Library version string, e.g. "evo-gfx950 0.1". */

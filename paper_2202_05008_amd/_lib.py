@@ -26,9 +26,9 @@ class policy_desc(C.Structure):
 
 class task_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("n_rollouts", C.c_int32), ("B", C.c_int32), ("P", C.c_int32),
-                ("reset_seed", C.c_uint64), ("generation", C.c_uint32), ("reserved", C.c_int32),
+                ("reset_seed", C.c_uint64), ("generation", C.c_uint32), ("seq_in", C.c_int32),
                 ("obs_dev", C.c_void_p), ("obs_member_stride", C.c_int64), ("target_dev", C.c_void_p),
-                ("cp", C.c_float * 8), ("init_scale", C.c_float), ("reserved2", C.c_int32),
+                ("cp", C.c_float * 8), ("init_scale", C.c_float), ("seq_out", C.c_int32),
                 ("work_dev", C.c_void_p)]
 
 
@@ -65,6 +65,8 @@ _SIGNATURES = {
                                 C.c_void_p]),
     "evo_rollout_details": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "evo_seq2seq_logits": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
+                                     C.c_void_p, C.c_void_p]),
     "evo_last_error": (C.c_char_p, []),
     "evo_version": (C.c_char_p, []),
 }

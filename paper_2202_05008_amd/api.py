@@ -11,8 +11,8 @@ from ._lib import pgpe_config, policy_desc, task_desc
 
 EVO_F32, EVO_BF16 = 0, 1
 EVO_ACT_NONE, EVO_ACT_TANH, EVO_ACT_RELU = 0, 1, 2
-EVO_POLICY_MLP, EVO_POLICY_CONVNET = 0, 1
-EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE = 0, 1, 2, 3
+EVO_POLICY_MLP, EVO_POLICY_CONVNET, EVO_POLICY_LSTM_SEQ2SEQ = 0, 1, 2
+EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE, EVO_TASK_SEQ2SEQ = 0, 1, 2, 3, 4
 EVO_TAG_NOISE, EVO_TAG_RESET = 0, 1
 EVO_OPT_ADAM, EVO_OPT_CLIPUP, EVO_OPT_MOMENTUM = 0, 1, 2
 
@@ -69,9 +69,10 @@ def make_policy_desc(kind, dims, act=(), dtype=EVO_F32):
 
 
 def make_task_desc(kind, n_rollouts=1, B=0, P=0, reset_seed=0, generation=1, obs=None, obs_member_stride=0,
-                   target=None, cp=None, init_scale=0.2, work=None):
+                   target=None, cp=None, init_scale=0.2, work=None, seq_in=0, seq_out=0):
     td = task_desc()
     td.kind, td.n_rollouts, td.B, td.P = kind, n_rollouts, B, P
+    td.seq_in, td.seq_out = seq_in, seq_out
     td.reset_seed, td.generation = reset_seed, generation
     td.obs_dev = obs.data_ptr() if obs is not None else None
     td.obs_member_stride = obs_member_stride
@@ -198,6 +199,11 @@ def evo_pgpe_gradients(h, fitness, gmu, gsigma, params=None):
     _check(_lib.load().evo_pgpe_gradients(h, _ptr(fitness, torch.float32), _ptr(gmu, torch.float32),
                                           _ptr(gsigma, torch.float32),
                                           _ptr(params, torch.float32, allow_none=True), _stream()))
+
+
+def evo_seq2seq_logits(td, pd, params, pop, logits):
+    _check(_lib.load().evo_seq2seq_logits(C.byref(td), C.byref(pd), _ptr(params, torch.float32), pop,
+                                          _ptr(logits, torch.float32), _stream()))
 
 
 def evo_task_step(td, state, action, nxt, reward, n):

@@ -53,4 +53,11 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
 int launch_cartpole_step(const float* cp, const float* state, const float* action, float* next, float* reward,
                          int n, hipStream_t s);
 
+// LSTM sequence-to-sequence policy on shared token strings: fitness[pop] = -mean cross-entropy of
+// the answer digits and / or logits[pop][B][La][n_out].
+int lstm_supported(int V, int H, int n_out, int Lq, int La);
+int64_t lstm_param_count(int V, int H, int n_out);
+int launch_lstm_seq2seq(int V, int H, int n_out, const float* params, const int32_t* query, const int32_t* answer,
+                        int pop, int B, int Lq, int La, float* fitness, float* logits, hipStream_t s);
+
 }  // namespace evo

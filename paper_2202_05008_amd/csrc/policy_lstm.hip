@@ -1,0 +1,309 @@
+// A policy with carried state: the LSTM sequence-to-sequence model of the paper's "Seq2Seq
+// Learning" example (Section 3: the query is the string of an addition, "012+345=", the answer the
+// string of the sum) evaluated for every member with its own weights on one shared batch; the
+// cells (h, c) are the policy state that Section 4 ("Exploring Novel Policy Architectures")
+// passes from one get_actions call to the next.  Here the whole sequence runs inside one kernel
+// and that state never leaves the chip.
+//
+// Model.  Tokens are integers below V; an encoder cell reads the query, a decoder cell (own weights)
+// starts from the encoder's final (h, c) and takes one step per answer position, fed with the token
+// '=' (V - 1) first and with the true previous answer digit afterwards; logits_j = h_j Wo + bo.
+//   a = Wx[token] + h Wh + b   (gates i, f, g, o: columns g H + u)
+//   c' = sigmoid(a_f) c + sigmoid(a_i) tanh(a_g);   h' = sigmoid(a_o) tanh(c')
+// Flat parameters: enc Wx[V][4H], Wh[H][4H], b[4H]; dec Wx, Wh, b; Wo[H][n_out]; bo[n_out].
+//
+// Mapping.  One workgroup owns one member; wave w owns hidden units 16 w .. 16 w + 15 in all four
+// gates, and the 64 K recurrent weights of the active cell sit in the registers of the workgroup's
+// waves as matrix-core operands for the whole phase (H = 128: 128 registers per lane).  The
+// recurrent product runs transposed on v_mfma_f32_16x16x32_f16: rows = the wave's 16 units of one
+// gate, columns = 16 samples, so that a lane ends up with the four gates of four consecutive units
+// of one sample: the cell update is lane-local, c stays in registers, and h' leaves as one 8-byte
+// LDS store per split term.  h is kept in LDS as two half-precision terms (split16.h: 22
+// significand bits, three matrix instructions per product, within a few 1e-7 of fp32 arithmetic).
+// h lies in (-1, 1) and is stored times 2^14, the weights are stored times 2^8, so the gate
+// pre-activations come out times 2^22 and the factor is folded into the exp2 arguments of the
+// sigmoids and tanh; only the weights have to be checked against the fp16 range (|w| < 255.9),
+// and a member outside it gets NaN logits.  The input term needs no product at all: a
+// one-hot token selects a row of Wx, which is kept with the bias added in an LDS table.  Two
+// h buffers alternate, so one workgroup barrier per step suffices.  Samples are processed in
+// chunks of 64 (four column tiles).
+//
+// Register layouts (lane = 16 q + j):  A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7;
+// D[row 4 q + i][col j], i = 0..3.
+#include "kernels.h"
+#include "split16.h"
+
+namespace evo {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kChunk = 64;            // samples per pass: four column tiles
+constexpr int kMaxV = 16, kMaxOut = 16, kMaxLq = 32, kMaxLa = 16;
+constexpr float kSH = 16384.0f;                 // 2^14: scale of the stored h
+constexpr float kSW = 256.0f;                   // 2^8: scale of the stored weights
+constexpr float kSA = kSH * kSW;                // 2^22: scale of the accumulators
+constexpr float kUA = 1.0f / kSA;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// sigmoid and tanh of a pre-activation that is held times 2^22 (the factor rides in the exp2 argument)
+__device__ __forceinline__ float exp_neg_scaled(float A) { return __builtin_amdgcn_exp2f((-kLog2e * kUA) * A); }
+__device__ __forceinline__ float sigmoid_scaled(float A) { return __builtin_amdgcn_rcpf(1.0f + exp_neg_scaled(A)); }
+__device__ __forceinline__ float tanh_scaled(float A) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f((2.0f * kLog2e * kUA) * A) + 1.0f);
+}
+
+__device__ __forceinline__ float tanh_fast(float x) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f((2.0f * kLog2e) * x) + 1.0f);
+}
+
+struct LstmArgs {
+  const float* params;
+  const int32_t* query;   // [B][Lq]
+  const int32_t* answer;  // [B][La]
+  float* fitness;         // [pop] or null
+  float* logits;          // [pop][B][La][n_out] or null
+  int P, B, Lq, La, V, n_out;
+};
+
+template <int H>
+__global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
+  constexpr int NW = H / 16;            // waves
+  constexpr int KS = H / 32;            // matrix-core steps over the hidden units
+  constexpr int G4 = 4 * H;             // gate columns
+  constexpr int kRowB = (H + 8) * 2;    // bytes of one sample's row of one term (16 bytes of padding)
+  constexpr int kTermB = kChunk * kRowB;
+  constexpr int kBufB = 2 * kTermB;     // both terms of one h buffer
+  __shared__ __attribute__((aligned(16))) unsigned char hbuf[2 * kBufB];
+  constexpr int kTabRow = G4 + 4;       // floats per token row: 16 bytes of padding spread the tokens over the banks
+  __shared__ __attribute__((aligned(16))) float tab[kMaxV * kTabRow];     // Wx[token] + b of the active cell
+  __shared__ __attribute__((aligned(16))) f16x8 wo_s[2][KS][64];          // Wo^T as A operands, two terms
+  __shared__ unsigned char tokq[kChunk * kMaxLq];
+  __shared__ unsigned char toka[kChunk * kMaxLa];
+  __shared__ float wave_loss[NW];
+  __shared__ int out_of_range;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, q = lane >> 4;
+  const int member = blockIdx.x;
+  const int V = a.V, n_out = a.n_out, Lq = a.Lq, La = a.La;
+  const float* theta = a.params + static_cast<size_t>(member) * a.P;
+  const int cell_size = V * G4 + H * G4 + G4;
+  const float* Wo = theta + 2 * cell_size;
+  const float* bo = Wo + H * n_out;
+
+  // ---- once: output layer as A operands (row j = output j, zero beyond n_out), bias of this lane's rows ----
+  float range_max = 0.f;
+  for (int i = tid; i < KS * 64; i += 4 * H) {
+    const int kb = i >> 6, l = i & 63, jj = l & 15, qq = l >> 4;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[e] = jj < n_out ? kSW * Wo[(32 * kb + 8 * qq + e) * n_out + jj] : 0.f;
+      range_max = fmaxf(range_max, fabsf(x[e]));
+    }
+    split2_x8(x, wo_s[0][kb][l], wo_s[1][kb][l]);
+  }
+  float bo4[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) bo4[i] = 4 * q + i < n_out ? kSA * bo[4 * q + i] : 0.f;
+  if (tid == 0) out_of_range = 0;
+
+  float loss_acc = 0.f;  // sum over this lane's samples and positions (lanes with q == 0 of waves 0..3)
+
+  for (int c0 = 0; c0 < a.B; c0 += kChunk) {
+    // ---- tokens of the chunk -> LDS (samples beyond B read token 0 and are masked from the loss) ----
+    __syncthreads();  // the previous chunk is done with the token arrays and the h buffers
+    for (int i = tid; i < kChunk * Lq; i += 4 * H) {
+      const int s = i / Lq, t = i - s * Lq;
+      const int v = c0 + s < a.B ? a.query[static_cast<size_t>(c0 + s) * Lq + t] : 0;
+      tokq[s * kMaxLq + t] = static_cast<unsigned char>(min(max(v, 0), V - 1));
+    }
+    for (int i = tid; i < kChunk * La; i += 4 * H) {
+      const int s = i / La, t = i - s * La;
+      const int v = c0 + s < a.B ? a.answer[static_cast<size_t>(c0 + s) * La + t] : 0;
+      toka[s * kMaxLa + t] = static_cast<unsigned char>(min(max(v, 0), n_out - 1));
+    }
+    for (int i = tid; i < kBufB / 4; i += 4 * H) reinterpret_cast<uint32_t*>(hbuf)[i] = 0u;  // h_0 = 0
+    floatx4 cst[4];  // c of (units 16 wave + 4 q + i, sample 16 st + j)
+#pragma unroll
+    for (int st = 0; st < 4; ++st) cst[st] = floatx4{0.f, 0.f, 0.f, 0.f};
+    int cur = 0;  // h buffer that holds the current h
+
+#pragma unroll 1
+    for (int phase = 0; phase < 2; ++phase) {
+      const float* Wx = theta + phase * cell_size;
+      const float* Wh = Wx + V * G4;
+      const float* bg = Wh + H * G4;
+      // ---- recurrent weights of this cell -> registers: wh[term][gate][step], element e is
+      //      Wh[32 step + 8 q + e][gate H + 16 wave + j] ----
+      f16x8 wh[2][4][KS];
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int kb = 0; kb < KS; ++kb) {
+          float x[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            x[e] = kSW * Wh[(32 * kb + 8 * q + e) * G4 + g * H + 16 * wave + j];
+            range_max = fmaxf(range_max, fabsf(x[e]));
+          }
+          split2_x8(x, wh[0][g][kb], wh[1][g][kb]);
+        }
+      __syncthreads();  // every wave is done with the previous cell's table
+      for (int i = tid; i < V * G4; i += 4 * H) tab[(i / G4) * kTabRow + i % G4] = kSA * (Wx[i] + bg[i % G4]);
+      __syncthreads();
+
+      const int n_steps = phase == 0 ? Lq : La;
+#pragma unroll 1
+      for (int t = 0; t < n_steps; ++t) {
+        const unsigned char* hc = hbuf + cur * kBufB;
+        unsigned char* hn = hbuf + (cur ^ 1) * kBufB;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          const int s = 16 * st + j;  // this lane's sample (column)
+          const int tok = phase == 0 ? tokq[s * kMaxLq + t] : (t == 0 ? V - 1 : toka[s * kMaxLa + t - 1]);
+          floatx4 acc[4], low[4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            acc[g] = *reinterpret_cast<const floatx4*>(tab + tok * kTabRow + g * H + 16 * wave + 4 * q);
+            low[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+          }
+          const unsigned char* src = hc + s * kRowB + 16 * q;
+#pragma unroll
+          for (int kb = 0; kb < KS; ++kb) {
+            const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
+            const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b1, low[g], 0, 0, 0);
+              low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[1][g][kb], b0, low[g], 0, 0, 0);
+              acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b0, acc[g], 0, 0, 0);
+            }
+          }
+          // ---- cell update of units 16 wave + 4 q + i for sample s; h' -> the other buffer ----
+          float hs[4];  // h' times 2^14
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float ai = fmaf(low[0][i], kSplitLowUnscale, acc[0][i]);
+            const float af = fmaf(low[1][i], kSplitLowUnscale, acc[1][i]);
+            const float ag = fmaf(low[2][i], kSplitLowUnscale, acc[2][i]);
+            const float ao = fmaf(low[3][i], kSplitLowUnscale, acc[3][i]);
+            const float c = fmaf(sigmoid_scaled(af), cst[st][i], sigmoid_scaled(ai) * tanh_scaled(ag));
+            cst[st][i] = c;
+            // 2^14 sigmoid(a_o) = 1 / (2^-14 (1 + e^-a_o))
+            const float so = __builtin_amdgcn_rcpf(fmaf(exp_neg_scaled(ao), 1.0f / kSH, 1.0f / kSH));
+            hs[i] = so * tanh_fast(c);
+          }
+          uint2 lead, resid;
+          split2_pair(hs[0], hs[1], lead.x, resid.x);
+          split2_pair(hs[2], hs[3], lead.y, resid.y);
+          unsigned char* dst = hn + s * kRowB + (16 * wave + 4 * q) * 2;
+          *reinterpret_cast<uint2*>(dst) = lead;
+          *reinterpret_cast<uint2*>(dst + kTermB) = resid;
+        }
+        __syncthreads();  // h' is complete; nobody reads the old h any more
+        cur ^= 1;
+
+        if (phase == 1 && wave < 4) {
+          // ---- logits of answer position t for sample tile `wave`: rows = outputs, columns = samples ----
+          const int s = 16 * wave + j;
+          const unsigned char* src = hbuf + cur * kBufB + s * kRowB + 16 * q;
+          floatx4 lg = {bo4[0], bo4[1], bo4[2], bo4[3]}, lw = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kb = 0; kb < KS; ++kb) {
+            const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
+            const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
+            const f16x8 w0 = wo_s[0][kb][lane], w1 = wo_s[1][kb][lane];
+            lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b1, lw, 0, 0, 0);
+            lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1, b0, lw, 0, 0, 0);
+            lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b0, lg, 0, 0, 0);
+          }
+          float z[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) z[i] = fmaf(lw[i], kSplitLowUnscale, lg[i]) * kUA;
+          const bool valid = c0 + s < a.B;
+          if (a.logits && valid) {
+            float* out = a.logits + ((static_cast<size_t>(member) * a.B + c0 + s) * La + t) * n_out;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (4 * q + i < n_out) out[4 * q + i] = z[i];
+          }
+          // cross-entropy of the true digit: softmax over the rows, i.e. over i and the four q groups
+          const int y = toka[s * kMaxLa + t];
+          float mx = -INFINITY, picked = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (4 * q + i < n_out) mx = fmaxf(mx, z[i]);
+            if (4 * q + i == y) picked = z[i];
+          }
+          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          float se = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (4 * q + i < n_out) se += expf(z[i] - mx);
+          se += __shfl_xor(se, 16, 64);
+          se += __shfl_xor(se, 32, 64);
+          picked += __shfl_xor(picked, 16, 64);
+          picked += __shfl_xor(picked, 32, 64);
+          if (valid && q == 0) loss_acc += (mx + logf(se)) - picked;
+        }
+      }
+    }
+  }
+
+  // ---- a weight outside the fp16 range (or NaN) anywhere in the workgroup poisons the member ----
+  __syncthreads();
+  if (!(range_max <= kSplitMax)) out_of_range = 1;
+  // ---- fitness: lanes in a fixed order, then waves 0..3 in order ----
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
+  if (lane == 0) wave_loss[wave] = loss_acc;
+  __syncthreads();
+  if (out_of_range && a.logits) {
+    const size_t n = static_cast<size_t>(a.B) * La * n_out;
+    float* out = a.logits + static_cast<size_t>(member) * n;
+    for (size_t i = tid; i < n; i += 4 * H) out[i] = __builtin_nanf("");
+  }
+  if (tid == 0 && a.fitness) {
+    const float total = ((wave_loss[0] + wave_loss[1]) + wave_loss[2]) + wave_loss[3];
+    a.fitness[member] =
+        out_of_range ? __builtin_nanf("") : -total / (static_cast<float>(a.B) * static_cast<float>(La));
+  }
+}
+
+}  // namespace
+
+int lstm_supported(int V, int H, int n_out, int Lq, int La) {
+  EVO_REQUIRE(H == 64 || H == 128, EVO_ERR_UNSUPPORTED, "lstm: hidden width must be 64 or 128 (got %d)", H);
+  EVO_REQUIRE(V >= 1 && V <= kMaxV, EVO_ERR_UNSUPPORTED, "lstm: vocabulary must be in [1, %d] (got %d)", kMaxV, V);
+  EVO_REQUIRE(n_out >= 1 && n_out <= kMaxOut && n_out <= V, EVO_ERR_UNSUPPORTED,
+              "lstm: outputs must be in [1, %d] and, being fed back as tokens, at most V (got %d)", kMaxOut, n_out);
+  EVO_REQUIRE(Lq >= 1 && Lq <= kMaxLq && La >= 1 && La <= kMaxLa, EVO_ERR_UNSUPPORTED,
+              "lstm: query length must be in [1, %d] and answer length in [1, %d] (got %d, %d)", kMaxLq, kMaxLa, Lq,
+              La);
+  return EVO_OK;
+}
+
+int64_t lstm_param_count(int V, int H, int n_out) {
+  return 2 * (static_cast<int64_t>(V) * 4 * H + static_cast<int64_t>(H) * 4 * H + 4 * H) +
+         static_cast<int64_t>(H) * n_out + n_out;
+}
+
+int launch_lstm_seq2seq(int V, int H, int n_out, const float* params, const int32_t* query, const int32_t* answer,
+                        int pop, int B, int Lq, int La, float* fitness, float* logits, hipStream_t s) {
+  LstmArgs a;
+  a.params = params, a.query = query, a.answer = answer, a.fitness = fitness, a.logits = logits;
+  a.P = static_cast<int>(lstm_param_count(V, H, n_out));
+  a.B = B, a.Lq = Lq, a.La = La, a.V = V, a.n_out = n_out;
+  if (H == 128)
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<128>), dim3(pop), dim3(512), 0, s, a);
+  else
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<64>), dim3(pop), dim3(256), 0, s, a);
+  return check_launch("lstm_seq2seq_kernel");
+}
+
+}  // namespace evo

@@ -44,8 +44,8 @@ int conv_shape(const policy_desc* pd, ConvShape* sh) {
 
 int check_policy(const policy_desc* pd) {
   EVO_REQUIRE(pd != nullptr, EVO_ERR_ARG, "policy_desc is null");
-  EVO_REQUIRE(pd->kind == EVO_POLICY_MLP || pd->kind == EVO_POLICY_CONVNET, EVO_ERR_ARG, "policy: bad kind %d",
-              pd->kind);
+  EVO_REQUIRE(pd->kind == EVO_POLICY_MLP || pd->kind == EVO_POLICY_CONVNET || pd->kind == EVO_POLICY_LSTM_SEQ2SEQ,
+              EVO_ERR_ARG, "policy: bad kind %d", pd->kind);
   EVO_REQUIRE(pd->dtype == EVO_F32 || pd->dtype == EVO_BF16, EVO_ERR_ARG, "policy: bad dtype %d", pd->dtype);
   return EVO_OK;
 }
@@ -59,6 +59,12 @@ extern "C" int64_t policy_param_count(const policy_desc* pd) {
     MlpShape sh;
     rc = mlp_shape(pd, &sh);
     return rc ? rc : sh.P;
+  }
+  if (pd->kind == EVO_POLICY_LSTM_SEQ2SEQ) {
+    EVO_REQUIRE(pd->dims[0] >= 1 && pd->dims[1] >= 1 && pd->dims[2] >= 1 && pd->dims[1] <= 4096 &&
+                    pd->dims[0] <= 65536 && pd->dims[2] <= 65536,
+                EVO_ERR_ARG, "lstm: dims must be {V, H, n_out}, all positive");
+    return lstm_param_count(pd->dims[0], pd->dims[1], pd->dims[2]);
   }
   ConvShape cs;
   rc = conv_shape(pd, &cs);
@@ -89,6 +95,8 @@ extern "C" int pop_forward(const policy_desc* pd, const void* params_dev, const 
     return launch_mlp_bf16(sh, static_cast<const uint16_t*>(params_dev), obs_dev, obs_member_stride, pop, B, out_dev,
                            LOSS_NONE, nullptr, nullptr, s);
   }
+  EVO_REQUIRE(pd->kind != EVO_POLICY_LSTM_SEQ2SEQ, EVO_ERR_UNSUPPORTED,
+              "pop_forward: the sequence-to-sequence policy consumes token strings: use rollout or evo_seq2seq_logits");
   ConvShape cs;
   rc = conv_shape(pd, &cs);
   if (rc) return rc;
@@ -106,6 +114,7 @@ namespace {
 int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
   if (td->kind == EVO_TASK_SPHERE) return td->P >= 1 ? sphere_chunks(td->P) : 0;
   if (td->kind != EVO_TASK_CLASSIFY && td->kind != EVO_TASK_REGRESS) return 0;
+  if (pd->kind == EVO_POLICY_LSTM_SEQ2SEQ) return 0;
   if (pd->kind == EVO_POLICY_CONVNET) {
     ConvShape cs;
     if (conv_shape(pd, &cs)) return 0;
@@ -117,7 +126,7 @@ int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
 
 int check_task(const task_desc* td) {
   EVO_REQUIRE(td != nullptr, EVO_ERR_ARG, "task_desc is null");
-  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_SPHERE, EVO_ERR_ARG, "task: bad kind %d",
+  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_SEQ2SEQ, EVO_ERR_ARG, "task: bad kind %d",
               td->kind);
   return EVO_OK;
 }
@@ -126,9 +135,28 @@ int check_task(const task_desc* td) {
 
 extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop) {
   if (check_task(td) || pop < 1) return 0;
-  if (td->kind == EVO_TASK_CARTPOLE) return 0;
+  if (td->kind == EVO_TASK_CARTPOLE || td->kind == EVO_TASK_SEQ2SEQ) return 0;
   if (td->kind != EVO_TASK_SPHERE && check_policy(pd)) return 0;
   return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
+}
+
+// The sequence-to-sequence task: fitness and / or logits of every member.
+static int seq2seq_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                        float* fitness_dev, float* logits_dev, void* stream) {
+  int rc = check_policy(pd);
+  if (rc) return rc;
+  EVO_REQUIRE(pd->kind == EVO_POLICY_LSTM_SEQ2SEQ && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
+              "seq2seq: needs an fp32 EVO_POLICY_LSTM_SEQ2SEQ policy");
+  EVO_REQUIRE(td->B >= 1 && td->obs_dev && td->target_dev, EVO_ERR_ARG,
+              "seq2seq: needs B >= 1, query tokens (obs_dev) and answer tokens (target_dev)");
+  EVO_REQUIRE(td->obs_member_stride == 0, EVO_ERR_UNSUPPORTED, "seq2seq: the token strings must be shared");
+  const int V = pd->dims[0], H = pd->dims[1], n_out = pd->dims[2];
+  rc = lstm_supported(V, H, n_out, td->seq_in, td->seq_out);
+  if (rc) return rc;
+  return launch_lstm_seq2seq(V, H, n_out, static_cast<const float*>(params_dev),
+                             reinterpret_cast<const int32_t*>(td->obs_dev),
+                             static_cast<const int32_t*>(td->target_dev), pop, td->B, td->seq_in, td->seq_out,
+                             fitness_dev, logits_dev, as_stream(stream));
 }
 
 static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
@@ -149,6 +177,11 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P,
                          static_cast<float*>(td->work_dev), fitness_dev, s);
   }
+  if (td->kind == EVO_TASK_SEQ2SEQ) {
+    EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
+    EVO_REQUIRE(steps == 1, EVO_ERR_ARG, "rollout: the sequence-to-sequence task is a single-step task (steps == 1)");
+    return seq2seq_impl(td, pd, params_dev, pop, fitness_dev, nullptr, stream);
+  }
   rc = check_policy(pd);
   if (rc) return rc;
   if (td->kind == EVO_TASK_CARTPOLE) {
@@ -165,6 +198,8 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
                            td->init_scale, td->reset_seed, td->generation, fitness_dev, ret_dev, final_dev, s);
   }
   // supervised single-step tasks
+  EVO_REQUIRE(pd->kind != EVO_POLICY_LSTM_SEQ2SEQ, EVO_ERR_UNSUPPORTED,
+              "rollout: the sequence-to-sequence policy needs the EVO_TASK_SEQ2SEQ task");
   EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
   EVO_REQUIRE(steps == 1, EVO_ERR_ARG, "rollout: single-step task needs steps == 1");
   EVO_REQUIRE(td->B >= 1 && td->obs_dev && td->target_dev, EVO_ERR_ARG, "rollout: needs B >= 1, obs and targets");
@@ -222,6 +257,16 @@ extern "C" int evo_rollout_details(const task_desc* td, const policy_desc* pd, c
               "evo_rollout_details: only the cart-pole task has per-roll-out details");
   EVO_REQUIRE(ret_dev || final_dev, EVO_ERR_ARG, "evo_rollout_details: no output requested");
   return rollout_impl(td, pd, params_dev, pop, steps, nullptr, ret_dev, final_dev, stream);
+}
+
+extern "C" int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                                  float* logits_dev, void* stream) {
+  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_SEQ2SEQ, EVO_ERR_ARG,
+              "evo_seq2seq_logits: needs an EVO_TASK_SEQ2SEQ task");
+  EVO_REQUIRE(params_dev && logits_dev, EVO_ERR_ARG, "evo_seq2seq_logits: null device pointer");
+  EVO_REQUIRE(pop >= 1 && pop <= 65535, EVO_ERR_ARG, "evo_seq2seq_logits: pop must be in [1,65535] (got %d)", pop);
+  EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "evo_seq2seq_logits: params_dev must be 16-byte aligned");
+  return seq2seq_impl(td, pd, params_dev, pop, nullptr, logits_dev, stream);
 }
 
 extern "C" int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,

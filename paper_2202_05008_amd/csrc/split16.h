@@ -1,0 +1,52 @@
+// fp32-accurate products on the 16-bit matrix instruction: two-term half-precision operand splits.
+//
+// A value x (already multiplied by a power of two s chosen per tensor so that it sits well inside
+// fp16's exponent range) is represented as x ~ h + 2^-11 m with h = fp16(x) and
+// m = fp16(2^11 (x - h)): the residual is exact in fp32, at most half an ulp of h, and scaling it
+// by 2^11 brings it back to the magnitude of x, so it keeps 11 significand bits of its own;
+// |x - h - 2^-11 m| <= 2^-22 |x|.  A product of two such values is accumulated in fp32 as
+//     h h'  (one accumulator)   and   h m' + m h'  (a second one, added with the factor 2^-11);
+// every fp16 x fp16 product is exact in fp32 and the dropped m m' is below 2^-22 of the product.
+//
+// Two hardware facts shape the code.  (1) v_cvt_pk_f16_f32, which the compiler picks for a pair of
+// conversions, returns zero where the single conversion returns a subnormal: the residual must be
+// taken against the value that is actually stored, so the pair is converted once and the same
+// register feeds both uses.  A leading term that came out as zero is harmless: the whole value
+// then sits in m (11 bits of it), and the tensor scales keep such values below 2^-14 / s.
+// (2) The leading term overflows beyond 65504 / s: callers check their operands against
+// kSplitMax and poison the result with NaN instead of returning a wrong finite value.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace evo {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kSplitLowScale = 2048.0f;           // 2^11: the residual term is stored times this
+constexpr float kSplitLowUnscale = 1.0f / 2048.0f;  // factor of the second accumulator
+constexpr float kSplitMax = 65504.0f;               // largest finite fp16: bound on |s x|
+
+// Two values -> the packed leading terms and the packed scaled residual terms.
+__device__ __forceinline__ void split2_pair(float x0, float x1, uint32_t& lead, uint32_t& resid) {
+  uint32_t hb = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x0, x1}, f16x2));
+  asm volatile("" : "+v"(hb));  // one conversion: what is stored is what the residual is taken against
+  const f16x2 h = __builtin_bit_cast(f16x2, hb);
+  const f32x2 r = {(x0 - static_cast<float>(h[0])) * kSplitLowScale, (x1 - static_cast<float>(h[1])) * kSplitLowScale};
+  lead = hb;
+  resid = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2));
+}
+
+// Eight values -> the two matrix operands (leading, residual).
+__device__ __forceinline__ void split2_x8(const float x[8], f16x8& lead, f16x8& resid) {
+  uint32_t l[4], r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split2_pair(x[2 * i], x[2 * i + 1], l[i], r[i]);
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  lead = __builtin_bit_cast(f16x8, u32x4{l[0], l[1], l[2], l[3]});
+  resid = __builtin_bit_cast(f16x8, u32x4{r[0], r[1], r[2], r[3]});
+}
+
+}  // namespace evo

@@ -41,8 +41,11 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 // x ~ h + 2^-11 m with two fp16 terms (round to nearest); the subtraction is exact in fp32.
 constexpr float kSplitScale = 2048.0f, kSplitUnscale = 1.0f / 2048.0f;
 constexpr float kHalfMax = 65504.0f;  // largest finite fp16
+// The matrix cores flush subnormal fp16 inputs, so a value below 2^-13 keeps a zero leading term
+// and goes into the scaled term whole (11 bits of it: absolute error below 2^-25).
+constexpr float kSplitMin = 0.0001220703125f;  // 2^-13
 __device__ __forceinline__ void split2(float x, _Float16& h, _Float16& m) {
-  h = static_cast<_Float16>(x);
+  h = static_cast<_Float16>(fabsf(x) >= kSplitMin ? x : 0.f);
   m = static_cast<_Float16>((x - static_cast<float>(h)) * kSplitScale);
 }
 

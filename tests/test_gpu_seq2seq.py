@@ -1,0 +1,83 @@
+"""GPU parity of the LSTM sequence-to-sequence policy (carried cell state) on the addition-string
+task: logits and fitness against oracle/seq2seq.py on the same seeded parameters and tokens."""
+import numpy as np
+import pytest
+
+from oracle import seq2seq as os2s
+from workloads import generators as gen
+from tests.util import assert_close, assert_scalar_rel, dev, host
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def evo():
+    import paper_2202_05008_amd as e
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return e
+
+
+def _run(evo, H, params, query, answer, V=12, n_out=10):
+    pop, B = params.shape[0], query.shape[0]
+    pd = evo.make_policy_desc(evo.EVO_POLICY_LSTM_SEQ2SEQ, (V, H, n_out))
+    assert evo.policy_param_count(pd) == params.shape[1]
+    qd, ad = dev(query), dev(answer)
+    td = evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=B, obs=qd, target=ad, seq_in=query.shape[1], seq_out=answer.shape[1])
+    assert evo.rollout_workspace_bytes(td, pd, pop) == 0
+    logits = torch.full((pop, B, answer.shape[1], n_out), 7.0, dtype=torch.float32, device="cuda")
+    fit = torch.full((pop,), 7.0, dtype=torch.float32, device="cuda")
+    pdv = dev(params)
+    evo.evo_seq2seq_logits(td, pd, pdv, pop, logits)
+    evo.rollout(td, pd, pdv, pop, 1, fit)
+    return host(logits), host(fit)
+
+
+@pytest.mark.parametrize("H,pop,B,digits,scale", [(64, 3, 5, 3, 0.3), (64, 2, 64, 3, 0.3), (128, 3, 100, 3, 0.2),
+                                                  (128, 2, 1, 1, 0.3), (64, 2, 130, 5, 0.5), (128, 2, 64, 3, 1e-3)])
+def test_logits_and_fitness_against_oracle(evo, H, pop, B, digits, scale):
+    P = os2s.param_count(H)
+    params = gen.random_params(51, pop, P, scale)
+    query, answer = gen.addition_batch(52, 1, B, digits)
+    logits, fit = _run(evo, H, params, query, answer)
+    ref = os2s.forward(params, query, answer, H)
+    assert_close(logits, ref, 1e-5, "seq2seq logits")
+    assert_scalar_rel(fit, os2s.fitness(ref, answer), 1e-5, "seq2seq fitness")
+
+
+def test_zero_weights_and_out_of_range(evo):
+    H, B = 64, 20
+    P = os2s.param_count(H)
+    params = gen.random_params(53, 3, P, 0.3)
+    params[0] = 0.0                                   # logits = 0: cross-entropy ln 10
+    params[2, 2 * (12 * 256) + 5] = 3.0e5             # a recurrent weight beyond the fp16 range
+    params[2, 12 * 256 + 77] = 3.0e5
+    query, answer = gen.addition_batch(54, 2, B, 3)
+    logits, fit = _run(evo, H, params, query, answer)
+    assert np.all(logits[0] == 0.0) and abs(fit[0] + np.log(10.0)) < 1e-6
+    ref = os2s.forward(params[1:2], query, answer, H)
+    assert_close(logits[1], ref[0], 1e-5, "the in-range member")
+    assert np.isnan(logits[2]).all() and np.isnan(fit[2])
+
+
+def test_unsupported_shapes_are_refused(evo):
+    query, answer = gen.addition_batch(55, 1, 4, 3)
+    qd, ad = dev(query), dev(answer)
+    td = evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=4, obs=qd, target=ad, seq_in=8, seq_out=4)
+    fit = torch.empty(2, dtype=torch.float32, device="cuda")
+    for dims in ((12, 96, 10), (20, 64, 10), (12, 64, 13)):
+        pd = evo.make_policy_desc(evo.EVO_POLICY_LSTM_SEQ2SEQ, dims)
+        params = torch.zeros(2, evo.policy_param_count(pd), dtype=torch.float32, device="cuda")
+        with pytest.raises(evo.EvoError) as ei:
+            evo.rollout(td, pd, params, 2, 1, fit)
+        assert ei.value.code == -3
+    pd = evo.make_policy_desc(evo.EVO_POLICY_LSTM_SEQ2SEQ, (12, 64, 10))
+    params = torch.zeros(2, evo.policy_param_count(pd), dtype=torch.float32, device="cuda")
+    with pytest.raises(evo.EvoError):                 # a sequence task is not a feed-forward batch
+        evo.pop_forward(pd, params, torch.zeros(4, 8, device="cuda"), 0, torch.zeros(2, 4, 10, device="cuda"), 2, 4)
+    long_td = evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=4, obs=qd, target=ad, seq_in=40, seq_out=4)
+    with pytest.raises(evo.EvoError):
+        evo.rollout(long_td, pd, params, 2, 1, fit)
+    mlp = evo.make_policy_desc(evo.EVO_POLICY_MLP, (16, 32, 4), (1, 0))
+    with pytest.raises(evo.EvoError):
+        evo.rollout(td, mlp, params, 2, 1, fit)
