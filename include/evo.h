@@ -175,8 +175,9 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      Flat parameters: W1[3][3][1][c1], b1[c1], W2[3][3][c1][c2], b2[c2],
  *      Wd[(H/4)(H/4)c2][n_cls], bd[n_cls]; dense input flattened (h, w, c), c fastest.
  *      fp32 results; the second convolution is evaluated on 16-bit matrix instructions with
- *      two-term operand splits, which needs its weights and input activations below 65504 in
- *      magnitude: an image for which they are not gets NaN logits (a NaN fitness ranks lowest).
+ *      two-term operand splits, which needs its weights below 255.9 and its input activations
+ *      below 4094 in magnitude: an image for which they are not gets NaN logits (a NaN fitness
+ *      ranks lowest).
  * LSTM sequence-to-sequence (kind EVO_POLICY_LSTM_SEQ2SEQ; Section 3, "Seq2Seq Learning"; the carried
  *      cells are the policy state of Section 4): dims = {V, H, n_out}, H = 64 or 128, n_out <= V <= 16.
  *      Tokens are integers in [0, V).  LSTM cell, gates i, f, g, o in columns g H + u:
@@ -186,7 +187,7 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      for j = 0 and the true answer token j - 1 afterwards; logits_j = h_j Wo + bo.
  *      Flat parameters: enc Wx[V][4H], Wh[H][4H], b[4H]; dec Wx[V][4H], Wh[H][4H], b[4H];
  *      Wo[H][n_out]; bo[n_out].  fp32 results; the recurrent and output weights must stay below
- *      65504 in magnitude (two-term fp16 operand splits), else the member's outputs are NaN.
+ *      255.9 in magnitude (two-term fp16 operand splits), else the member's outputs are NaN.
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
@@ -219,8 +220,9 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *             shared by all members (obs_member_stride = 0); seq_in <= 32, seq_out <= 16.
  *   CARTPOLE  mean over n_rollouts of the episode return of the swing-up task below; the whole
  *             episode (policy weights, environment state) stays on chip for all `steps`.  With two
- *             hidden layers the second one has the same 65504 limit on its weights and inputs as the
- *             ConvNet's second convolution: a member outside it gets a NaN fitness.
+ *             hidden layers the second one has the same limits on its weights (255.9) and, unless a
+ *             tanh bounds them, its inputs (4094) as the ConvNet's second convolution: a member
+ *             outside them gets a NaN fitness.
  * Cart-pole: state (x, x_d, th, th_d), th from upright; cp = {g, m_cart M, m_pole m, length l,
  *   friction b, force scale, dt, x_limit}; F = force_scale * a - b x_d (a = policy output);
  *   D = 4(M+m) - 3 m cos^2 th;  x_dd = [4F + 2 m l th_d^2 sin th - 3 m g sin th cos th] / D;

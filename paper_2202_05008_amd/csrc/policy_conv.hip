@@ -16,17 +16,15 @@
 // v_mfma_f32_16x16x4_f32 takes 32 cycles (1024 MACs), and the two do not overlap, so the fp32
 // matrix instruction is only 1.4x the vector rate.  v_mfma_f32_16x16x32_f16 takes 16 cycles
 // for 8192 MACs.  conv2 therefore runs on the fp16 matrix instruction with every fp32 operand
-// split into two half-precision terms x ~ h + 2^-11 m: h = fp16(x) (11 significand bits) and
-// m = fp16(2^11 (x - h)), the residual (exact in fp32) scaled back into the normal range so that
-// it keeps 11 bits of its own: 22 bits in all, |x - h - 2^-11 m| <= 2^-22 |x|.  Three of the four
-// partial products are accumulated in fp32, h h' in one accumulator and h m' + m h' in a second
-// one that enters with the factor 2^-11; the dropped m m' is below 2^-22 of the full product.
-// Every fp16 x fp16 product is exact in fp32, so a product is within 3 * 2^-22 of the fp32 one
-// and a 72-term sum well inside the 1e-5 gate (measured: 4e-7 of the rms), at 3 / 16 of the
-// issue cycles of the fp32 matrix instruction.  The leading term needs |x| within the fp16
-// range: the kernel tracks the largest conv1 activation of an image and checks the conv2 weights
-// when it loads them, and where either exceeds the range it returns NaN logits for the image
-// (the member's fitness is then NaN and ranks lowest) instead of a wrong finite value.
+// split into two half-precision terms (split16.h): three matrix instructions per product, a
+// product within 3 * 2^-22 of the fp32 one, a 72-term sum well inside the 1e-5 gate (measured:
+// 4e-7 of the rms), at 3 / 16 of the issue cycles of the fp32 matrix instruction.  The conv1
+// activations are produced times 2^4 (the factor sits in the conv1 weights and bias), the conv2
+// weights are stored times 2^8, and the 2^12 of the conv2 output is taken out by the staged dense
+// weights.  The fp16 range then allows activations below 4094 and weights below 255.9: the
+// kernel tracks the largest conv1 activation of an image and checks the conv2 weights when it
+// loads them, and where either exceeds the range it returns NaN logits for the image (the
+// member's fitness is then NaN and ranks lowest) instead of a wrong finite value.
 //
 // Band pipeline.  conv2 output row b needs the (zero-padded) conv1 rows 2b .. 2b+3 only, so the
 // conv1 output is never held whole: pass b of conv1 produces padded rows 2b+2 and 2b+3 and
@@ -41,14 +39,16 @@
 // weights; lane group q supplies the 8 channels of tap 4 step + q: one 16-byte LDS read per
 // split term from the band buffer, which holds [term][row pair][column][row parity][channel]
 // half-precision values.
-#include "bf16.h"
 #include "kernels.h"
+#include "split16.h"
 
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kSA1 = 16.0f;            // 2^4: scale of the stored conv1 activations
+constexpr float kSW2 = 256.0f;           // 2^8: scale of the stored conv2 weights
+constexpr float kSA2 = kSA1 * kSW2;      // 2^12: scale of the conv2 output
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
@@ -110,17 +110,6 @@ __device__ __forceinline__ float row16_max(float v) {
   return v;
 }
 
-// x ~ h + 2^-11 m with two fp16 terms (round to nearest); the subtraction is exact in fp32.
-constexpr float kSplitScale = 2048.0f, kSplitUnscale = 1.0f / 2048.0f;
-constexpr float kHalfMax = 65504.0f;  // largest finite fp16
-// The matrix cores flush subnormal fp16 inputs, so a value below 2^-13 keeps a zero leading term
-// and goes into the scaled term whole (11 bits of it: absolute error below 2^-25).
-constexpr float kSplitMin = 0.0001220703125f;  // 2^-13
-__device__ __forceinline__ void split2(float x, _Float16& h, _Float16& m) {
-  h = static_cast<_Float16>(fabsf(x) >= kSplitMin ? x : 0.f);
-  m = static_cast<_Float16>((x - static_cast<float>(h)) * kSplitScale);
-}
-
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
 // (10 for the ten-class case, 16 for any n_cls <= 16 with zero padding).
 // kConvWaves: waves per workgroup (12 with ten classes, 10 when the padded dense weights take 49 KB).
@@ -152,7 +141,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // ---- once per workgroup: dense weights -> LDS (rows padded to NCS with zeros) ----------------
   for (int i = threadIdx.x; i < n_feat * NCS; i += 64 * kConvWaves) {
     const int f = i / NCS, c = i - f * NCS;
-    wd_s[i] = c < n_cls ? Wd[f * n_cls + c] : 0.f;
+    wd_s[i] = c < n_cls ? Wd[f * n_cls + c] * (1.0f / kSA2) : 0.f;  // takes the scale of the conv2 output out
   }
   // zero the padded buffers once: borders stay zero, interiors are overwritten per image
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
@@ -165,18 +154,17 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
   for (int st = 0; st < 3; ++st) {
     const int tap = 4 * st + q;
+    float x[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float x = tap < 9 ? W2[(tap * kC1 + j) * kC2 + n] : 0.f;
-      w2_max = fmaxf(w2_max, fabsf(x));
-      _Float16 h, m;
-      split2(x, h, m);
-      w2b[0][st][j] = h, w2b[1][st][j] = m;
+      x[j] = tap < 9 ? kSW2 * W2[(tap * kC1 + j) * kC2 + n] : 0.f;
+      w2_max = fmaxf(w2_max, fabsf(x[j]));
     }
+    split2_x8(x, w2b[0][st], w2b[1][st]);
   }
   // a weight beyond the fp16 range (or a NaN, which the comparison also rejects) poisons the member
-  const bool w2_bad = __any(!(w2_max <= kHalfMax));
-  const float bias2 = b2[n];
+  const bool w2_bad = __any(!(w2_max <= kSplitMax));
+  const float bias2 = kSA2 * b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
   // conv1 role of this lane: pooled pixel (row select rs, column wx) x four channels 4 cg .. 4 cg + 3
@@ -187,9 +175,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) w1v[t][c] = W1[t * kC1 + 4 * c1_cg + c];
+    for (int c = 0; c < 4; ++c) w1v[t][c] = kSA1 * W1[t * kC1 + 4 * c1_cg + c];  // conv1 output times 2^4
 #pragma unroll
-  for (int c = 0; c < 4; ++c) bias1v[c] = b1[4 * c1_cg + c];
+  for (int c = 0; c < 4; ++c) bias1v[c] = kSA1 * b1[4 * c1_cg + c];
 
   // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3,
   // shifted by tap 4 step + q (the padding taps 9..11 re-read tap 8 against zero weights)
@@ -278,16 +266,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         }
         // two fp16 terms of the four channels: 8 bytes per term
         uint2 term[2];
-        {
-          _Float16 t[2][4];
-#pragma unroll
-          for (int c = 0; c < 4; ++c) split2(v[c], t[0][c], t[1][c]);
-#pragma unroll
-          for (int k = 0; k < 2; ++k) {
-            const f16x2 lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
-            term[k] = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
-          }
-        }
+        split2_pair(v[0], v[1], term[0].x, term[1].x);
+        split2_pair(v[2], v[3], term[0].y, term[1].y);
         // rows 2, 3 of this band's buffer and rows 0, 1 of the next band's buffer
         char* cur = bandb + (b & 1) * kBandBytes + band_off(2 + c1_rs, c1_wx + 1) + 8 * c1_cg;
         char* nxt = bandb + ((b + 1) & 1) * kBandBytes + band_off(c1_rs, c1_wx + 1) + 8 * c1_cg;
@@ -324,8 +304,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        acc0[i] = fmaf(low0[i], kSplitUnscale, acc0[i]);
-        acc1[i] = fmaf(low1[i], kSplitUnscale, acc1[i]);
+        acc0[i] = fmaf(low0[i], kSplitLowUnscale, acc0[i]);
+        acc1[i] = fmaf(low1[i], kSplitLowUnscale, acc1[i]);
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n
       if (q < H4) a2[(b * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
@@ -360,7 +340,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       logit += __shfl_xor(logit, 32, 64);
       logit += bias_d;
     }
-    if (w2_bad || __any(!(a1_max <= kHalfMax))) logit = __builtin_nanf("");  // outside the range of the split
+    if (w2_bad || __any(!(a1_max <= kSplitMax))) logit = __builtin_nanf("");  // outside the range of the split
     wave_sync();
     // both scratch uses sat on zero-padded buffers: restore the zeros (the next image's
     // interior is rewritten anyway, the borders must read as zero again)

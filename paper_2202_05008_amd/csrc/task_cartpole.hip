@@ -20,34 +20,23 @@
 // With two hidden layers, layer 1 (K = 5) is computed transposed on the fp32 instruction
 // (rows = neurons, columns = roll-outs), so that a lane ends up with four consecutive neurons
 // of one roll-out: after the activation they are split into two half-precision terms
-// x ~ h + 2^-11 m (h = fp16(x), m = fp16(2^11 (x - h)): 22 significand bits, the residual scaled
-// back into the normal range) and stored with one 8-byte LDS write per term.  Layer 2 (K = H)
-// then runs on the fp16 instruction (16 cycles for 8192 multiply-adds against 32 cycles for 1024
-// of the fp32 one) with h h' in one fp32 accumulator and h m' + m h' in a second one that enters
-// with the factor 2^-11; the dropped m m' is below 2^-22 of the full product, so the layer stays
-// within a few 1e-7 of fp32 arithmetic.  The leading term needs |x| within the fp16 range: the
-// weights are checked when they are loaded, activations other than tanh are tracked, and a member
-// outside the range gets a NaN fitness (it then ranks lowest) instead of a wrong finite one.
-#include "bf16.h"
+// (split16.h) and stored with one 8-byte LDS write per term.  Layer 2 (K = H) then runs on the
+// fp16 instruction (16 cycles for 8192 multiply-adds against 32 cycles for 1024 of the fp32 one),
+// three instructions per product, within a few 1e-7 of fp32 arithmetic.  The activations are
+// stored times 2^14 when they come from a tanh (times 2^4 otherwise), the weights times 2^8; the
+// factor of the layer-2 pre-activation rides in the argument of the next activation.  The weights
+// are checked against the fp16 range (|w| < 255.9) when they are loaded, activations other than
+// tanh are tracked, and a member outside the range gets a NaN fitness (it then ranks lowest)
+// instead of a wrong finite one.
 #include "kernels.h"
 #include "philox.h"
+#include "split16.h"
 
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-// x ~ h + 2^-11 m with two fp16 terms (round to nearest); the subtraction is exact in fp32.
-constexpr float kSplitScale = 2048.0f, kSplitUnscale = 1.0f / 2048.0f;
-constexpr float kHalfMax = 65504.0f;  // largest finite fp16
-// The matrix cores flush subnormal fp16 inputs, so a value below 2^-13 keeps a zero leading term
-// and goes into the scaled term whole (11 bits of it: absolute error below 2^-25).
-constexpr float kSplitMin = 0.0001220703125f;  // 2^-13
-__device__ __forceinline__ void split2(float x, _Float16& h, _Float16& m) {
-  h = static_cast<_Float16>(fabsf(x) >= kSplitMin ? x : 0.f);
-  m = static_cast<_Float16>((x - static_cast<float>(h)) * kSplitScale);
-}
+constexpr float kSW2 = 256.0f;  // 2^8: scale of the stored layer-2 weights
 
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
@@ -75,6 +64,12 @@ __device__ __forceinline__ float act_apply(float x, int act) {
   if (act == EVO_ACT_TANH) return tanh_fast(x);
   if (act == EVO_ACT_RELU) return fmaxf(x, 0.f);
   return x;
+}
+
+// scale * tanh(x * inv): a pre-activation that is held times 1 / inv, a result wanted times scale
+__device__ __forceinline__ float tanh_scaled(float x, float inv, float scale) {
+  const float e = __builtin_amdgcn_exp2f((2.885390081777927f * inv) * x);
+  return fmaf(-2.0f * scale, __builtin_amdgcn_rcpf(e + 1.0f), scale);
 }
 
 // sin and cos of an angle in radians: two-term reduction by 2 pi (2 pi = hi - lo with hi the fp32
@@ -136,6 +131,9 @@ template <int NT, bool TWO, bool TANH>
 __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1_rt, int act2_rt, int act3_rt) {
   const int act1 = TANH ? EVO_ACT_TANH : act1_rt, act2 = TANH ? EVO_ACT_TANH : act2_rt;
   const int act3 = TANH ? EVO_ACT_TANH : act3_rt;
+  constexpr float kSH1 = TANH ? 16384.0f : 16.0f;  // scale of the stored layer-1 activations: 2^14 behind a tanh
+  constexpr float kSA2 = kSH1 * kSW2;              // scale of the layer-2 accumulators
+  constexpr float kUA2 = 1.0f / kSA2;
   constexpr int H = 16 * NT;
   constexpr int KP = H < 32 ? 32 : H;      // contraction length of layer 2, padded to the instruction's 32
   constexpr int KS2 = KP / 32;             // matrix-core steps of layer 2 per split term pair
@@ -161,19 +159,19 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   float bias2 = 0.f, w3, b3;
   if (TWO) {
 #pragma unroll
-    for (int s = 0; s < KS2; ++s)
+    for (int s = 0; s < KS2; ++s) {
+      float x[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int k = 32 * s + 8 * q + e;
-        const float x = k < H ? th2[k * H + col] : 0.f;
-        range_max = fmaxf(range_max, fabsf(x));
-        _Float16 h, m;
-        split2(x, h, m);
-        w2b[0][s][e] = h, w2b[1][s][e] = m;
+        x[e] = k < H ? kSW2 * th2[k * H + col] : 0.f;
+        range_max = fmaxf(range_max, fabsf(x[e]));
       }
+      split2_x8(x, w2b[0][s], w2b[1][s]);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) bias1t[i] = theta[5 * H + 16 * wave + 4 * q + i];
-    bias2 = th2[H * H + col];
+    bias2 = kSA2 * th2[H * H + col];
     w3 = th2[H * H + H + col];
     b3 = th2[H * H + H + H];
     // columns H .. KP - 1 of the activation rows are never written and must read as zero
@@ -213,20 +211,18 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1b, a1, acc, 0, 0, 0);
         // neurons 16 wave + 4 q .. + 3 of roll-out j: two terms, 8 bytes each
         {
-          _Float16 t[2][4];
+          float h1[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float h1 = act_apply(acc[i], act1);
-            if (!TANH) range_max = fmaxf(range_max, fabsf(h1));
-            split2(h1, t[0][i], t[1][i]);
+            h1[i] = TANH ? tanh_scaled(acc[i], 1.0f, kSH1) : kSH1 * act_apply(acc[i], act1);
+            if (!TANH) range_max = fmaxf(range_max, fabsf(h1[i]));
           }
+          uint2 lead, resid;
+          split2_pair(h1[0], h1[1], lead.x, resid.x);
+          split2_pair(h1[2], h1[3], lead.y, resid.y);
           unsigned char* dst = hb + j * kRowB + (16 * wave + 4 * q) * 2;
-#pragma unroll
-          for (int k = 0; k < 2; ++k) {
-            const f16x2 lo = {t[k][0], t[k][1]}, hi = {t[k][2], t[k][3]};
-            *reinterpret_cast<uint2*>(dst + k * kTermB) =
-                make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
-          }
+          *reinterpret_cast<uint2*>(dst) = lead;
+          *reinterpret_cast<uint2*>(dst + kTermB) = resid;
         }
         __syncthreads();
         // ---- layer 2: lane (row j, k group q) reads 8 consecutive activations per term and step ----
@@ -243,7 +239,10 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
           acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0], w2b[0][s2], acc2, 0, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] = act_apply(fmaf(low2[i], kSplitUnscale, acc2[i]), act2) * w3;
+        for (int i = 0; i < 4; ++i) {
+          const float pre = fmaf(low2[i], kSplitLowUnscale, acc2[i]);  // layer-2 pre-activation times kSA2
+          p[i] = (TANH ? tanh_scaled(pre, kUA2, 1.0f) : act_apply(pre * kUA2, act2)) * w3;
+        }
       } else {
         floatx4 acc = {bias1, bias1, bias1, bias1};
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
@@ -291,7 +290,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     __shared__ int out_of_range;
     if (threadIdx.x == 0) out_of_range = 0;
     __syncthreads();
-    if (!(range_max <= kHalfMax)) out_of_range = 1;
+    if (!(range_max <= kSplitMax)) out_of_range = 1;
     __syncthreads();
     if (out_of_range) total = __builtin_nanf("");
   }
