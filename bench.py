@@ -119,6 +119,23 @@ def _build_workload(name, seed, batch=None):
         wl["roofline_stage"] = "ask"
         wl["desc"] = "cfg5: ask/tell stress on a sphere, P=2^20, pop 1024"
         wl["dtype"] = "f32"
+    elif name == "seq2seq":
+        V, H, n_out = c.dims
+        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_LSTM_SEQ2SEQ, c.dims)
+        tds = []
+        for g in range(4):      # four distinct batches, cycled: a new batch every generation
+            q, a = gen.addition_batch(c.data_seed, g + 1, c.B, c.digits)
+            qd, ad = torch.from_numpy(q).to(dev), torch.from_numpy(a).to(dev)
+            wl.setdefault("keep", []).append((qd, ad))
+            tds.append(evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=c.B, obs=qd, target=ad, seq_in=q.shape[1],
+                                          seq_out=a.shape[1]))
+        wl["task"] = lambda t: tds[t % len(tds)]
+        Lq, La = 2 * c.digits + 2, c.digits + 1
+        flops = 2.0 * ((Lq + La) * H * 4 * H + La * H * n_out) * c.pop * c.B
+        wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
+        wl["desc"] = ("seq2seq: LSTM encoder-decoder H=128 (P=145674) on three-digit addition strings, pop 1024, "
+                      "128 strings per member")
+        wl["dtype"] = "f32"
     else:
         raise SystemExit("unknown workload %r" % name)
     wl.setdefault("roofline_stage", "rollout")
@@ -134,7 +151,7 @@ def _cpu_baseline(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
-    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96}[name]
+    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}[name]
     gens = {"cfg1": 600}.get(name, 1)
     dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
     if name == "cfg1":
@@ -152,6 +169,10 @@ def _cpu_baseline(name, seed):
     elif name == "cfg4":
         obs, tgt = gen.teacher_regression(c.data_seed, sample_pop, c.B, c.dims)
         task = {"kind": "regress", "dims": c.dims, "acts": c.acts, "obs": obs, "targets": tgt}
+        evals = sample_pop * c.B
+    elif name == "seq2seq":
+        q, a = gen.addition_batch(c.data_seed, 1, c.B, c.digits)
+        task = {"kind": "seq2seq", "H": c.dims[1], "query": q, "answer": a}
         evals = sample_pop * c.B
     else:
         task = {"kind": "sphere", "x_star": gen.sphere_target(c.data_seed, c.P)}
@@ -173,7 +194,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq"])
     ap.add_argument("--seed", type=int, default=20220509)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=None,
@@ -197,7 +218,7 @@ def main():
         raise SystemExit("--variant applies to --workload cfg5 only")
     wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20}[args.workload]
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}[args.workload]
     stage_names = ("ask", "rollout", "tell")
     events = []
 

@@ -24,9 +24,12 @@
 // pre-activations come out times 2^22 and the factor is folded into the exp2 arguments of the
 // sigmoids and tanh; only the weights have to be checked against the fp16 range (|w| < 255.9),
 // and a member outside it gets NaN logits.  The input term needs no product at all: a
-// one-hot token selects a row of Wx, which is kept with the bias added in an LDS table.  Two
-// h buffers alternate, so one workgroup barrier per step suffices.  Samples are processed in
-// chunks of 64 (four column tiles).
+// one-hot token selects a row of Wx, which is kept with the bias added in an LDS table.  A step
+// writes h' into a buffer nobody reads, so one workgroup barrier per step suffices.  Samples are
+// processed in chunks of 64 (four column tiles); two chunks are in flight per pass (three h
+// buffers rotate: the current h of each chunk and the free one), so that a cell's weights are
+// loaded once per 128 samples.  The weights arrive with coalesced 16-byte loads that are all in
+// flight together and reach their owners through LDS.
 //
 // Register layouts (lane = 16 q + j):  A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7;
 // D[row 4 q + i][col j], i = 0..3.
@@ -67,6 +70,59 @@ struct LstmArgs {
   int P, B, Lq, La, V, n_out;
 };
 
+// One cell step of one chunk of 64 samples: gates from the current h (LDS, two terms), cell
+// update in registers, h' into the free buffer.  `tok_of(s)` gives the input token of sample s.
+template <int H, typename TokOf>
+__device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], floatx4 (&cst)[4], const float* tab,
+                                          const unsigned char* hc, unsigned char* hn, int wave, int j, int q,
+                                          TokOf tok_of) {
+  constexpr int KS = H / 32, kRowB = (H + 8) * 2, kTermB = kChunk * kRowB, kTabRow = 4 * H + 4;
+#pragma unroll
+  for (int st = 0; st < 4; ++st) {
+    const int s = 16 * st + j;  // this lane's sample (column)
+    const int tok = tok_of(s);
+    floatx4 acc[4], low[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      acc[g] = *reinterpret_cast<const floatx4*>(tab + tok * kTabRow + g * H + 16 * wave + 4 * q);
+      low[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const unsigned char* src = hc + s * kRowB + 16 * q;
+#pragma unroll
+    for (int kb = 0; kb < KS; ++kb) {
+      const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
+      const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
+      // three rounds over the gates: four independent instructions between two that share an accumulator
+#pragma unroll
+      for (int g = 0; g < 4; ++g) low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b1, low[g], 0, 0, 0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b0, acc[g], 0, 0, 0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[1][g][kb], b0, low[g], 0, 0, 0);
+    }
+    // ---- cell update of units 16 wave + 4 q + i for sample s; h' (times 2^14) -> the free buffer ----
+    float hs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float ai = fmaf(low[0][i], kSplitLowUnscale, acc[0][i]);
+      const float af = fmaf(low[1][i], kSplitLowUnscale, acc[1][i]);
+      const float ag = fmaf(low[2][i], kSplitLowUnscale, acc[2][i]);
+      const float ao = fmaf(low[3][i], kSplitLowUnscale, acc[3][i]);
+      const float c = fmaf(sigmoid_scaled(af), cst[st][i], sigmoid_scaled(ai) * tanh_scaled(ag));
+      cst[st][i] = c;
+      // 2^14 sigmoid(a_o) = 1 / (2^-14 (1 + e^-a_o))
+      const float so = __builtin_amdgcn_rcpf(fmaf(exp_neg_scaled(ao), 1.0f / kSH, 1.0f / kSH));
+      hs[i] = so * tanh_fast(c);
+    }
+    uint2 lead, resid;
+    split2_pair(hs[0], hs[1], lead.x, resid.x);
+    split2_pair(hs[2], hs[3], lead.y, resid.y);
+    unsigned char* dst = hn + s * kRowB + (16 * wave + 4 * q) * 2;
+    *reinterpret_cast<uint2*>(dst) = lead;
+    *reinterpret_cast<uint2*>(dst + kTermB) = resid;
+  }
+}
+
 template <int H>
 __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   constexpr int NW = H / 16;            // waves
@@ -75,12 +131,13 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   constexpr int kRowB = (H + 8) * 2;    // bytes of one sample's row of one term (16 bytes of padding)
   constexpr int kTermB = kChunk * kRowB;
   constexpr int kBufB = 2 * kTermB;     // both terms of one h buffer
-  __shared__ __attribute__((aligned(16))) unsigned char hbuf[2 * kBufB];
   constexpr int kTabRow = G4 + 4;       // floats per token row: 16 bytes of padding spread the tokens over the banks
-  __shared__ __attribute__((aligned(16))) float tab[kMaxV * kTabRow];     // Wx[token] + b of the active cell
+  // three h buffers: the current h of each of the two chunks in flight and the one the next step writes
+  __shared__ __attribute__((aligned(16))) unsigned char hbuf[3 * kBufB];
+  __shared__ __attribute__((aligned(16))) float tab[kMaxV * kTabRow];     // 2^22 (Wx[token] + b) of the active cell
   __shared__ __attribute__((aligned(16))) f16x8 wo_s[2][KS][64];          // Wo^T as A operands, two terms
-  __shared__ unsigned char tokq[kChunk * kMaxLq];
-  __shared__ unsigned char toka[kChunk * kMaxLa];
+  __shared__ unsigned char tokq[2 * kChunk * kMaxLq];
+  __shared__ unsigned char toka[2 * kChunk * kMaxLa];
   __shared__ float wave_loss[NW];
   __shared__ int out_of_range;
 
@@ -113,24 +170,28 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
 
   float loss_acc = 0.f;  // sum over this lane's samples and positions (lanes with q == 0 of waves 0..3)
 
-  for (int c0 = 0; c0 < a.B; c0 += kChunk) {
-    // ---- tokens of the chunk -> LDS (samples beyond B read token 0 and are masked from the loss) ----
-    __syncthreads();  // the previous chunk is done with the token arrays and the h buffers
-    for (int i = tid; i < kChunk * Lq; i += 4 * H) {
+  // Two chunks of 64 samples share one load of each cell's weights.
+  for (int c0 = 0; c0 < a.B; c0 += 2 * kChunk) {
+    const int n_chunks = a.B - c0 > kChunk ? 2 : 1;
+    // ---- tokens -> LDS (samples beyond B read token 0 and are masked from the loss) ----
+    __syncthreads();  // the previous pass is done with the token arrays and the h buffers
+    for (int i = tid; i < 2 * kChunk * Lq; i += 4 * H) {
       const int s = i / Lq, t = i - s * Lq;
       const int v = c0 + s < a.B ? a.query[static_cast<size_t>(c0 + s) * Lq + t] : 0;
       tokq[s * kMaxLq + t] = static_cast<unsigned char>(min(max(v, 0), V - 1));
     }
-    for (int i = tid; i < kChunk * La; i += 4 * H) {
+    for (int i = tid; i < 2 * kChunk * La; i += 4 * H) {
       const int s = i / La, t = i - s * La;
       const int v = c0 + s < a.B ? a.answer[static_cast<size_t>(c0 + s) * La + t] : 0;
       toka[s * kMaxLa + t] = static_cast<unsigned char>(min(max(v, 0), n_out - 1));
     }
-    for (int i = tid; i < kBufB / 4; i += 4 * H) reinterpret_cast<uint32_t*>(hbuf)[i] = 0u;  // h_0 = 0
-    floatx4 cst[4];  // c of (units 16 wave + 4 q + i, sample 16 st + j)
+    for (int i = tid; i < 2 * kBufB / 4; i += 4 * H) reinterpret_cast<uint32_t*>(hbuf)[i] = 0u;  // h_0 = 0, both chunks
+    floatx4 cst[2][4];  // c of (chunk, units 16 wave + 4 q + i, sample 16 st + j)
 #pragma unroll
-    for (int st = 0; st < 4; ++st) cst[st] = floatx4{0.f, 0.f, 0.f, 0.f};
-    int cur = 0;  // h buffer that holds the current h
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+      for (int st = 0; st < 4; ++st) cst[ch][st] = floatx4{0.f, 0.f, 0.f, 0.f};
+    int cur0 = 0, cur1 = 1, spare = 2;  // buffers holding h of chunk 0, of chunk 1, and the free one
 
 #pragma unroll 1
     for (int phase = 0; phase < 2; ++phase) {
@@ -138,118 +199,126 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
       const float* Wh = Wx + V * G4;
       const float* bg = Wh + H * G4;
       // ---- recurrent weights of this cell -> registers: wh[term][gate][step], element e is
-      //      Wh[32 step + 8 q + e][gate H + 16 wave + j] ----
-      f16x8 wh[2][4][KS];
+      //      2^8 Wh[32 step + 8 q + e][gate H + 16 wave + j].  The whole matrix is fetched with 16-byte
+      //      loads that are all in flight at once (one round trip to memory per cell), then handed
+      //      through LDS in pieces of 16 rows (the area of the token table, free between two cells):
+      //      piece (step, half) holds rows 32 step + 8 q' + 4 half + e', q' = 0..3, e' = 0..3. ----
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      constexpr int kPieces = 2 * KS;            // 16 rows each
+      constexpr int kVecPerThread = 4;           // float4 per thread and piece: 16 rows x H float4 over 4 H threads
+      f32x4 raw[kPieces][kVecPerThread];
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+      for (int pc = 0; pc < kPieces; ++pc)
 #pragma unroll
-        for (int kb = 0; kb < KS; ++kb) {
-          float x[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            x[e] = kSW * Wh[(32 * kb + 8 * q + e) * G4 + g * H + 16 * wave + j];
-            range_max = fmaxf(range_max, fabsf(x[e]));
-          }
-          split2_x8(x, wh[0][g][kb], wh[1][g][kb]);
+        for (int i = 0; i < kVecPerThread; ++i) {
+          const int f = tid + 4 * H * i;        // float4 index inside the piece: row r = f / H, column 4 (f % H)
+          const int r = f / H, c4 = f - r * H;
+          const int row = 32 * (pc >> 1) + 8 * (r >> 2) + 4 * (pc & 1) + (r & 3);
+          raw[pc][i] = *reinterpret_cast<const f32x4*>(Wh + static_cast<size_t>(row) * G4 + 4 * c4);
         }
-      __syncthreads();  // every wave is done with the previous cell's table
+      f16x8 wh[2][4][KS];
+      float xlo[4][4];  // rows e = 0..3 of the current step, kept until rows 4..7 arrive
+#pragma unroll
+      for (int pc = 0; pc < kPieces; ++pc) {
+        __syncthreads();  // the table (or the previous piece) is no longer read
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+          const int f = tid + 4 * H * i;
+          const int r = f / H, c4 = f - r * H;
+          *reinterpret_cast<f32x4*>(tab + r * kTabRow + 4 * c4) = raw[pc][i];
+        }
+        __syncthreads();
+        float x[4][4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            x[g][e] = kSW * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
+            range_max = fmaxf(range_max, fabsf(x[g][e]));
+          }
+        if ((pc & 1) == 0) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xlo[g][e] = x[g][e];
+        } else {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float x8[8] = {xlo[g][0], xlo[g][1], xlo[g][2], xlo[g][3], x[g][0], x[g][1], x[g][2], x[g][3]};
+            split2_x8(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
+          }
+        }
+      }
+      __syncthreads();  // every wave has read the last piece
       for (int i = tid; i < V * G4; i += 4 * H) tab[(i / G4) * kTabRow + i % G4] = kSA * (Wx[i] + bg[i % G4]);
       __syncthreads();
 
       const int n_steps = phase == 0 ? Lq : La;
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        if (ch >= n_chunks) break;
+        const unsigned char* tq = tokq + ch * kChunk * kMaxLq;
+        const unsigned char* ta = toka + ch * kChunk * kMaxLa;
 #pragma unroll 1
-      for (int t = 0; t < n_steps; ++t) {
-        const unsigned char* hc = hbuf + cur * kBufB;
-        unsigned char* hn = hbuf + (cur ^ 1) * kBufB;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          const int s = 16 * st + j;  // this lane's sample (column)
-          const int tok = phase == 0 ? tokq[s * kMaxLq + t] : (t == 0 ? V - 1 : toka[s * kMaxLa + t - 1]);
-          floatx4 acc[4], low[4];
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            acc[g] = *reinterpret_cast<const floatx4*>(tab + tok * kTabRow + g * H + 16 * wave + 4 * q);
-            low[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-          }
-          const unsigned char* src = hc + s * kRowB + 16 * q;
-#pragma unroll
-          for (int kb = 0; kb < KS; ++kb) {
-            const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
-            const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b1, low[g], 0, 0, 0);
-              low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[1][g][kb], b0, low[g], 0, 0, 0);
-              acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b0, acc[g], 0, 0, 0);
-            }
-          }
-          // ---- cell update of units 16 wave + 4 q + i for sample s; h' -> the other buffer ----
-          float hs[4];  // h' times 2^14
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float ai = fmaf(low[0][i], kSplitLowUnscale, acc[0][i]);
-            const float af = fmaf(low[1][i], kSplitLowUnscale, acc[1][i]);
-            const float ag = fmaf(low[2][i], kSplitLowUnscale, acc[2][i]);
-            const float ao = fmaf(low[3][i], kSplitLowUnscale, acc[3][i]);
-            const float c = fmaf(sigmoid_scaled(af), cst[st][i], sigmoid_scaled(ai) * tanh_scaled(ag));
-            cst[st][i] = c;
-            // 2^14 sigmoid(a_o) = 1 / (2^-14 (1 + e^-a_o))
-            const float so = __builtin_amdgcn_rcpf(fmaf(exp_neg_scaled(ao), 1.0f / kSH, 1.0f / kSH));
-            hs[i] = so * tanh_fast(c);
-          }
-          uint2 lead, resid;
-          split2_pair(hs[0], hs[1], lead.x, resid.x);
-          split2_pair(hs[2], hs[3], lead.y, resid.y);
-          unsigned char* dst = hn + s * kRowB + (16 * wave + 4 * q) * 2;
-          *reinterpret_cast<uint2*>(dst) = lead;
-          *reinterpret_cast<uint2*>(dst + kTermB) = resid;
-        }
-        __syncthreads();  // h' is complete; nobody reads the old h any more
-        cur ^= 1;
+        for (int t = 0; t < n_steps; ++t) {
+          int& cur = ch == 0 ? cur0 : cur1;
+          const unsigned char* hc = hbuf + cur * kBufB;
+          unsigned char* hn = hbuf + spare * kBufB;
+          if (phase == 0)
+            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q, [&](int s) { return int(tq[s * kMaxLq + t]); });
+          else
+            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q,
+                         [&](int s) { return t == 0 ? V - 1 : int(ta[s * kMaxLa + t - 1]); });
+          __syncthreads();  // h' is complete; nobody reads the old h any more
+          const int old = cur;
+          cur = spare;
+          spare = old;
 
-        if (phase == 1 && wave < 4) {
-          // ---- logits of answer position t for sample tile `wave`: rows = outputs, columns = samples ----
-          const int s = 16 * wave + j;
-          const unsigned char* src = hbuf + cur * kBufB + s * kRowB + 16 * q;
-          floatx4 lg = {bo4[0], bo4[1], bo4[2], bo4[3]}, lw = {0.f, 0.f, 0.f, 0.f};
+          if (phase == 1 && wave < 4) {
+            // ---- logits of answer position t for sample tile `wave`: rows = outputs, columns = samples ----
+            const int s = 16 * wave + j;
+            const unsigned char* src = hbuf + cur * kBufB + s * kRowB + 16 * q;
+            floatx4 lg = {bo4[0], bo4[1], bo4[2], bo4[3]}, lw = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int kb = 0; kb < KS; ++kb) {
-            const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
-            const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
-            const f16x8 w0 = wo_s[0][kb][lane], w1 = wo_s[1][kb][lane];
-            lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b1, lw, 0, 0, 0);
-            lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1, b0, lw, 0, 0, 0);
-            lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b0, lg, 0, 0, 0);
-          }
-          float z[4];
+            for (int kb = 0; kb < KS; ++kb) {
+              const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
+              const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
+              const f16x8 w0 = wo_s[0][kb][lane], w1 = wo_s[1][kb][lane];
+              lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b1, lw, 0, 0, 0);
+              lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1, b0, lw, 0, 0, 0);
+              lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b0, lg, 0, 0, 0);
+            }
+            float z[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) z[i] = fmaf(lw[i], kSplitLowUnscale, lg[i]) * kUA;
-          const bool valid = c0 + s < a.B;
-          if (a.logits && valid) {
-            float* out = a.logits + ((static_cast<size_t>(member) * a.B + c0 + s) * La + t) * n_out;
+            for (int i = 0; i < 4; ++i) z[i] = fmaf(lw[i], kSplitLowUnscale, lg[i]) * kUA;
+            const int gs = c0 + ch * kChunk + s;  // sample index in the batch
+            const bool valid = gs < a.B;
+            if (a.logits && valid) {
+              float* out = a.logits + ((static_cast<size_t>(member) * a.B + gs) * La + t) * n_out;
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (4 * q + i < n_out) out[4 * q + i] = z[i];
+            }
+            // cross-entropy of the true digit: softmax over the rows, i.e. over i and the four q groups
+            const int y = ta[s * kMaxLa + t];
+            float mx = -INFINITY, picked = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if (4 * q + i < n_out) mx = fmaxf(mx, z[i]);
+              if (4 * q + i == y) picked = z[i];
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            float se = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (4 * q + i < n_out) out[4 * q + i] = z[i];
+              if (4 * q + i < n_out) se += expf(z[i] - mx);
+            se += __shfl_xor(se, 16, 64);
+            se += __shfl_xor(se, 32, 64);
+            picked += __shfl_xor(picked, 16, 64);
+            picked += __shfl_xor(picked, 32, 64);
+            if (valid && q == 0) loss_acc += (mx + logf(se)) - picked;
           }
-          // cross-entropy of the true digit: softmax over the rows, i.e. over i and the four q groups
-          const int y = toka[s * kMaxLa + t];
-          float mx = -INFINITY, picked = 0.f;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if (4 * q + i < n_out) mx = fmaxf(mx, z[i]);
-            if (4 * q + i == y) picked = z[i];
-          }
-          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-          float se = 0.f;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (4 * q + i < n_out) se += expf(z[i] - mx);
-          se += __shfl_xor(se, 16, 64);
-          se += __shfl_xor(se, 32, 64);
-          picked += __shfl_xor(picked, 16, 64);
-          picked += __shfl_xor(picked, 32, 64);
-          if (valid && q == 0) loss_acc += (mx + logf(se)) - picked;
         }
       }
     }

@@ -11,13 +11,17 @@ from typing import Tuple
 
 # integer codes shared with the C ABI (include/evo.h) by value
 ACT_NONE, ACT_TANH, ACT_RELU = 0, 1, 2
-POLICY_MLP, POLICY_CONVNET = 0, 1
-TASK_CLASSIFY, TASK_REGRESS, TASK_CARTPOLE, TASK_SPHERE = 0, 1, 2, 3
+POLICY_MLP, POLICY_CONVNET, POLICY_LSTM_SEQ2SEQ = 0, 1, 2
+TASK_CLASSIFY, TASK_REGRESS, TASK_CARTPOLE, TASK_SPHERE, TASK_SEQ2SEQ = 0, 1, 2, 3, 4
 DT_F32, DT_BF16 = 0, 1
 
 
 def mlp_param_count(dims: Tuple[int, ...]) -> int:
     return sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(len(dims) - 1))
+
+
+def lstm_seq2seq_param_count(V: int = 12, H: int = 128, n_out: int = 10) -> int:
+    return 2 * (V * 4 * H + H * 4 * H + 4 * H) + H * n_out + n_out
 
 
 def convnet_param_count(c1: int = 8, c2: int = 16, n_cls: int = 10, hw: int = 28) -> int:
@@ -30,7 +34,7 @@ class WorkloadConfig:
     name: str
     pop: int
     policy_kind: int
-    dims: Tuple[int, ...]          # MLP: layer widths; ConvNet: (c1, c2, n_classes)
+    dims: Tuple[int, ...]          # MLP: layer widths; ConvNet: (c1, c2, n_classes); LSTM seq2seq: (V, H, n_out)
     acts: Tuple[int, ...]          # activation after each MLP layer
     dtype: int                     # DT_F32 or DT_BF16 (parameter storage)
     task_kind: int
@@ -50,6 +54,7 @@ class WorkloadConfig:
     # cart-pole constants: g, m_cart, m_pole, length, friction, force_scale, dt, x_limit
     cartpole: Tuple[float, ...] = field(default=(9.82, 0.5, 0.5, 0.6, 0.1, 10.0, 0.01, 2.4))
     init_scale: float = 0.2
+    digits: int = 3                # seq2seq: digits per operand ("012+345=" -> "0357")
 
     @property
     def P(self) -> int:
@@ -57,6 +62,8 @@ class WorkloadConfig:
             return self.dims[0]
         if self.policy_kind == POLICY_CONVNET:
             return convnet_param_count(self.dims[0], self.dims[1], self.dims[2])
+        if self.policy_kind == POLICY_LSTM_SEQ2SEQ:
+            return lstm_seq2seq_param_count(*self.dims)
         return mlp_param_count(self.dims)
 
     @property
@@ -83,4 +90,8 @@ CONFIGS = {
                            task_kind=TASK_REGRESS, B=64, shared_obs=False),
     "cfg5": WorkloadConfig("cfg5", pop=1024, policy_kind=POLICY_MLP, dims=(1 << 20,), acts=(),
                            dtype=DT_F32, task_kind=TASK_SPHERE, generations=10),
+    # beyond the five named configurations: the paper's sequence-to-sequence example (Section 3), an
+    # LSTM encoder-decoder of 145,674 parameters on strings of three-digit additions
+    "seq2seq": WorkloadConfig("seq2seq", pop=1024, policy_kind=POLICY_LSTM_SEQ2SEQ, dims=(12, 128, 10), acts=(),
+                              dtype=DT_F32, task_kind=TASK_SEQ2SEQ, B=128, digits=3),
 }
