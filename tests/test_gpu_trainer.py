@@ -122,3 +122,29 @@ def test_state_export_import_errors_and_sigma_adam_state(evo):
     other = evo.PGPE(evo.make_pgpe_config(P=P + 1, pop_max=pop, sigma_rule=1))
     with pytest.raises(evo.EvoError):
         other.import_state(blob)
+
+
+def test_seq2seq_training_improves(evo):
+    """PGPE on the LSTM sequence-to-sequence policy, one-digit additions: the cross-entropy of the
+    centre falls well below that of uniform guessing (ln 10) within a hundred generations."""
+    from paper_2202_05008_amd.trainer import Trainer
+    from oracle import seq2seq as os2s
+    H, pop, B, digits = 64, 256, 128, 1
+    P = os2s.param_count(H)
+    pg = evo.PGPE(evo.make_pgpe_config(P=P, pop_max=pop, lr_mu=0.05), gen.initial_mu(61, P, 0.05))
+    pd = evo.make_policy_desc(evo.EVO_POLICY_LSTM_SEQ2SEQ, (12, H, 10))
+    tasks = []
+    for g in range(8):
+        q, a = gen.addition_batch(62, g + 1, B, digits)
+        qd, ad = dev(q), dev(a)
+        tasks.append((evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=B, obs=qd, target=ad, seq_in=q.shape[1],
+                                         seq_out=a.shape[1]), q, a))
+    test_td, tq, ta = tasks[-1]
+    tr = Trainer(pg, pd, lambda t: tasks[t % 7][0], pop, seed=63, test_task=lambda t: test_td)
+    first = tr.test()
+    ref = os2s.fitness(os2s.forward(gen.initial_mu(61, P, 0.05)[None, :], tq, ta, H), ta)[0]
+    assert_scalar_rel(first, ref, 1e-5, "fitness of the initial centre on the held-out strings")
+    tr.run(100)
+    last = tr.test()
+    assert last > first + 0.3 and last > -np.log(10.0) + 0.3, (first, last)
+    assert tr.history[-1]["fitness_mean"] > tr.history[0]["fitness_mean"] + 0.2
