@@ -19,11 +19,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-# The ConvNet and cart-pole kernels deliver fp32-accurate results (the algorithmic flops below are
-# fp32 flops) and are priced against the fp32 matrix peak, although their contractions are issued
-# as fp16 matrix instructions on two-term scaled operand splits (three instructions per product).
+# The ConvNet, cart-pole and LSTM kernels deliver fp32-accurate results (the algorithmic flops below
+# are fp32 flops) and are priced against the fp32 matrix peak, although their contractions are issued
+# as fp16 matrix instructions on two-term scaled operand splits (three instructions per product):
+# `frac` can therefore exceed 1; `mfma_f16_issued_*` prices the same launch as issued.
 PEAK_MFMA_F32_TF = 157.3       # dense fp32 matrix
-PEAK_MFMA_BF16_TF = 2500.0
+PEAK_MFMA_BF16_TF = 2500.0     # dense bf16 / fp16 matrix
 PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 GHz x 2 flop)
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
@@ -82,6 +83,8 @@ def _build_workload(name, seed, batch=None):
             c1, c2, ncls = c.dims
             per_img = 2.0 * (9 * c1 * 28 * 28 + 9 * c1 * c2 * 14 * 14 + 7 * 7 * c2 * ncls)
             wl["roofline"] = ("mfma", per_img * c.pop * c.B, PEAK_MFMA_F32_TF, "TFLOP/s")
+            # conv2 as issued: k padded from 72 to 96, three fp16 matrix instructions per product
+            wl["f16_issued_flops"] = 3.0 * 2.0 * 96 * c2 * 14 * 14 * c.pop * c.B
             wl["desc"] = "cfg2: MNIST-shaped synthetic images, per-member fp32 ConvNet P=9098, pop 256, batch 1024"
         tds = [with_work(lambda w, b=b: evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=b[0], target=b[1], work=w))
                for b in batches]
@@ -94,6 +97,8 @@ def _build_workload(name, seed, batch=None):
                                                   generation=t + 1, cp=c.cartpole, init_scale=c.init_scale)
         flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.evals_per_generation
         wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
+        # layer 2 as issued: three fp16 matrix instructions per product (layer 1 runs on the fp32 instruction)
+        wl["f16_issued_flops"] = 3.0 * 2.0 * c.dims[1] * c.dims[2] * c.evals_per_generation
         wl["desc"] = "cfg3: cart-pole swing-up, fp32 MLP 5-64-64-1, pop 1024 x 16 roll-outs x 1000 steps"
         wl["dtype"] = "f32"
     elif name == "cfg4":
@@ -133,6 +138,7 @@ def _build_workload(name, seed, batch=None):
         Lq, La = 2 * c.digits + 2, c.digits + 1
         flops = 2.0 * ((Lq + La) * H * 4 * H + La * H * n_out) * c.pop * c.B
         wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
+        wl["f16_issued_flops"] = 3.0 * flops      # every product is three fp16 matrix instructions
         wl["desc"] = ("seq2seq: LSTM encoder-decoder H=128 (P=145674) on three-digit addition strings, pop 1024, "
                       "128 strings per member")
         wl["dtype"] = "f32"
@@ -278,6 +284,9 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": wl["roofline_stage"], "kernel_ms": dom_ms},
     }
+    if "f16_issued_flops" in wl:      # the same contraction counted as the fp16 matrix instructions that carry it
+        out["roofline"]["mfma_f16_issued_tflops"] = wl["f16_issued_flops"] / (dom_ms * 1e-3) / 1e12
+        out["roofline"]["mfma_f16_issued_frac"] = out["roofline"]["mfma_f16_issued_tflops"] / PEAK_MFMA_BF16_TF
     if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
         out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
