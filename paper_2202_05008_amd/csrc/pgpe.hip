@@ -58,6 +58,11 @@ __device__ __forceinline__ void store_row4(float* row, int col, int P, const flo
     // streaming store: the population is written once and read by a later kernel
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(row + col));
+  } else if ((P & 1) == 0 && col + 3 < P) {
+    // even P: rows are 8-byte aligned, two 8-byte streaming stores
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(f32x2{v[0], v[1]}, reinterpret_cast<f32x2*>(row + col));
+    __builtin_nontemporal_store(f32x2{v[2], v[3]}, reinterpret_cast<f32x2*>(row + col + 2));
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
