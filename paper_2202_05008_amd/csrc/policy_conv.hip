@@ -26,11 +26,12 @@
 // loads them, and where either exceeds the range it returns NaN logits for the image (the
 // member's fitness is then NaN and ranks lowest) instead of a wrong finite value.
 //
-// Band pipeline.  conv2 output row b needs the (zero-padded) conv1 rows 2b .. 2b+3 only, so the
-// conv1 output is never held whole: pass b of conv1 produces padded rows 2b+2 and 2b+3 and
-// stores them twice, as rows 2, 3 of the four-row buffer of band b and as rows 0, 1 of the
-// buffer of band b+1 (two buffers, used alternately); pass -1 primes band 0.  The conv2
-// output overwrites the part of the image buffer that conv1 has already consumed.
+// Band pipeline.  conv2 output row b needs the pooled conv1 rows 2b-1 .. 2b+2 only (rows -1 and
+// H/2 are the zero border), so the conv1 output is never held whole: pass b of conv1 produces the
+// pooled rows 2b and 2b+1 and stores each twice, as rows 1, 2 of the four-row buffer of band b
+// and as row 3 of band b-1 and row 0 of band b+1 (three buffers in rotation); conv2 of band b-1
+// follows pass b.  H/4 passes do exactly the H/2 rows.  The conv2 output overwrites the part of the
+// image buffer that conv1 has already consumed.
 //
 // conv2 tiling.  The 16 rows of a matrix tile are 4 pooling windows x their 4 pixels, so
 // that the 4 accumulator registers of a lane (rows 4q..4q+3 of column n) are exactly one
@@ -60,7 +61,7 @@ constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 
 constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
 constexpr int kBandBytes = 2 * kBandTerm;            // 2048 bytes per band buffer
 constexpr int kBandFloats = kBandBytes / 4;          // 512
-constexpr int kWaveFloats = kImgFloats + 2 * kBandFloats;  // 1928 floats = 7,712 bytes per wave
+constexpr int kWaveFloats = kImgFloats + 3 * kBandFloats;  // 2440 floats = 9,760 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 
   float* wd_s = lds;                                   // [n_feat][NCS] dense weights, shared by the waves
   float* img = lds + kMaxFeat * NCS + wave * kWaveFloats;
-  float* band = img + kImgFloats;                      // two band buffers of conv1 output
+  float* band = img + kImgFloats;                      // three band buffers of conv1 output
   float* a2 = img;                                     // conv2 output reuses the consumed image rows
 
   const float* theta = a.params + static_cast<size_t>(member) * a.P;
@@ -195,6 +196,14 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
   }
   char* const bandb = reinterpret_cast<char*>(band);
+  // conv1 store targets of this lane inside a band buffer: its row of the pass (2b or 2b+1) is row
+  // 1 or 2 of band b and row 3 of band b-1 or row 0 of band b+1
+  const int c1_dst_own = band_off(1 + c1_rs, c1_wx + 1) + 8 * c1_cg;
+  const int c1_dst_nbr = band_off(c1_rs ? 0 : 3, c1_wx + 1) + 8 * c1_cg;
+  // one padded band row (16 pixels of 16 bytes, both terms) set to zero by lanes 0..31
+  auto zero_band_row = [&](char* buf, int row) {
+    if (lane < 32) *reinterpret_cast<uint4*>(buf + (lane >> 4) * kBandTerm + band_off(row, lane & 15)) = make_uint4(0, 0, 0, 0);
+  };
 
   const int img_begin = blockIdx.x * a.imgs_per_chunk;
   const int img_end = min(a.B, img_begin + a.imgs_per_chunk);
@@ -232,13 +241,17 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     wave_sync();
 
     float a1_max = 0.f;  // largest conv1 activation of this image seen by this lane
+    zero_band_row(bandb, 0);  // band 0, row 0: the border above the image
+    int b3 = 0;               // b mod 3: buffer of band b
 #pragma unroll 1
-    for (int b = -1; b < H4; ++b) {
-      // ---- conv1 + ReLU + pool, pass b: padded conv1 rows 2b+2, 2b+3 (pooled rows 2b+1, 2b+2) ----
-      if (c1_on) {
-        const int pr = 2 * b + 1 + c1_rs;  // pooled row of this lane; outside [0, H2) it is the zero border
+    for (int b = 0; b <= H4; ++b) {
+      // ---- conv1 + ReLU + pool, pass b: pooled rows 2b and 2b+1 ----
+      if (b == H4) {
+        zero_band_row(bandb + (b3 == 0 ? 2 : b3 - 1) * kBandBytes, 3);  // last band, row 3: the border below the image
+      } else if (c1_on) {
+        const int pr = 2 * b + c1_rs;  // pooled row of this lane
         float v[4] = {0.f, 0.f, 0.f, 0.f};
-        if (pr >= 0 && pr < H2) {
+        {
           float p[4][4];
 #pragma unroll
           for (int dy = 0; dy < 4; ++dy) {
@@ -268,23 +281,24 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         uint2 term[2];
         split2_pair(v[0], v[1], term[0].x, term[1].x);
         split2_pair(v[2], v[3], term[0].y, term[1].y);
-        // rows 2, 3 of this band's buffer and rows 0, 1 of the next band's buffer
-        char* cur = bandb + (b & 1) * kBandBytes + band_off(2 + c1_rs, c1_wx + 1) + 8 * c1_cg;
-        char* nxt = bandb + ((b + 1) & 1) * kBandBytes + band_off(c1_rs, c1_wx + 1) + 8 * c1_cg;
-        if (b >= 0) {
+        // own band, and the neighbour band that shares the row
+        const int nbr3 = c1_rs ? (b3 == 2 ? 0 : b3 + 1) : (b3 == 0 ? 2 : b3 - 1);
+        char* cur = bandb + b3 * kBandBytes + c1_dst_own;
+        char* nxt = bandb + nbr3 * kBandBytes + c1_dst_nbr;
 #pragma unroll
-          for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
-        }
-        if (b + 1 < H4) {
+        for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
+        if (c1_rs ? b + 1 < H4 : b >= 1) {
 #pragma unroll
           for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(nxt + k * kBandTerm) = term[k];
         }
       }
       wave_sync();
-      if (b < 0) continue;
+      const int prev3 = b3 == 0 ? 2 : b3 - 1;  // buffer of band b - 1
+      b3 = b3 == 2 ? 0 : b3 + 1;
+      if (b == 0) continue;
 
-      // ---- conv2 + ReLU + pool, band b: two independent tiles (windows 0..3 and 4..7 of the row) --
-      const char* bb = bandb + (b & 1) * kBandBytes;
+      // ---- conv2 + ReLU + pool, band b-1: two independent tiles (windows 0..3 and 4..7 of the row) --
+      const char* bb = bandb + prev3 * kBandBytes;
       floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h'
       floatx4 low0 = {0.f, 0.f, 0.f, 0.f}, low1 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
 #pragma unroll
@@ -308,9 +322,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         acc1[i] = fmaf(low1[i], kSplitLowUnscale, acc1[i]);
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n
-      if (q < H4) a2[(b * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
+      if (q < H4) a2[((b - 1) * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
       if (q + 4 < H4)
-        a2[(b * H4 + q + 4) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])) + bias2, 0.f);
+        a2[((b - 1) * H4 + q + 4) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])) + bias2, 0.f);
       wave_sync();
     }
 
