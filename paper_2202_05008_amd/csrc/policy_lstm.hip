@@ -123,6 +123,8 @@ __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], float
   }
 }
 
+}  // namespace
+
 template <int H>
 __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   constexpr int NW = H / 16;            // waves
@@ -170,6 +172,15 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
 
   float loss_acc = 0.f;  // sum over this lane's samples and positions (lanes with q == 0 of waves 0..3)
 
+  // Byte offsets of this thread's four 16-byte pieces inside a 16-row piece of a recurrent matrix:
+  // float4 f = tid + 4 H i sits in row r = f / H (matrix row 8 (r >> 2) + (r & 3) of the piece), column 4 (f % H).
+  uint32_t lane_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int f = tid + 4 * H * i, r = f / H, c4 = f - r * H;
+    lane_off[i] = static_cast<uint32_t>(((8 * (r >> 2) + (r & 3)) * G4 + 4 * c4) * 4);
+  }
+
   // Two chunks of 64 samples share one load of each cell's weights.
   for (int c0 = 0; c0 < a.B; c0 += 2 * kChunk) {
     const int n_chunks = a.B - c0 > kChunk ? 2 : 1;
@@ -206,48 +217,53 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
       typedef float f32x4 __attribute__((ext_vector_type(4)));
       constexpr int kPieces = 2 * KS;            // 16 rows each
       constexpr int kVecPerThread = 4;           // float4 per thread and piece: 16 rows x H float4 over 4 H threads
-      f32x4 raw[kPieces][kVecPerThread];
-#pragma unroll
-      for (int pc = 0; pc < kPieces; ++pc)
-#pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-          const int f = tid + 4 * H * i;        // float4 index inside the piece: row r = f / H, column 4 (f % H)
-          const int r = f / H, c4 = f - r * H;
-          const int row = 32 * (pc >> 1) + 8 * (r >> 2) + 4 * (pc & 1) + (r & 3);
-          raw[pc][i] = *reinterpret_cast<const f32x4*>(Wh + static_cast<size_t>(row) * G4 + 4 * c4);
-        }
+      constexpr int kBatch = kPieces < 4 ? kPieces : 4;  // pieces fetched together (64 registers of raw weights)
       f16x8 wh[2][4][KS];
       float xlo[4][4];  // rows e = 0..3 of the current step, kept until rows 4..7 arrive
 #pragma unroll
-      for (int pc = 0; pc < kPieces; ++pc) {
-        __syncthreads();  // the table (or the previous piece) is no longer read
+      for (int p0 = 0; p0 < kPieces; p0 += kBatch) {
+        f32x4 raw[kBatch][kVecPerThread];
 #pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-          const int f = tid + 4 * H * i;
-          const int r = f / H, c4 = f - r * H;
-          *reinterpret_cast<f32x4*>(tab + r * kTabRow + 4 * c4) = raw[pc][i];
+        for (int pb = 0; pb < kBatch; ++pb) {
+          const int pc = p0 + pb;
+          // uniform base of the piece + four per-lane byte offsets that are the same for every piece
+          const char* piece = reinterpret_cast<const char*>(Wh + (32 * (pc >> 1) + 4 * (pc & 1)) * G4);
+#pragma unroll
+          for (int i = 0; i < kVecPerThread; ++i) raw[pb][i] = *reinterpret_cast<const f32x4*>(piece + lane_off[i]);
         }
-        __syncthreads();
-        float x[4][4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int pb = 0; pb < kBatch; ++pb) {
+          const int pc = p0 + pb;
+          __syncthreads();  // the table (or the previous piece) is no longer read
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            x[g][e] = kSW * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
-            range_max = fmaxf(range_max, fabsf(x[g][e]));
+          for (int i = 0; i < kVecPerThread; ++i) {
+            const int f = tid + 4 * H * i;
+            const int r = f / H, c4 = f - r * H;
+            *reinterpret_cast<f32x4*>(tab + r * kTabRow + 4 * c4) = raw[pb][i];
           }
-        if ((pc & 1) == 0) {
+          __syncthreads();
+          float x[4][4];
 #pragma unroll
           for (int g = 0; g < 4; ++g)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) xlo[g][e] = x[g][e];
-        } else {
+            for (int e = 0; e < 4; ++e) {
+              x[g][e] = kSW * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
+              range_max = fmaxf(range_max, fabsf(x[g][e]));
+            }
+          if ((pc & 1) == 0) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const float x8[8] = {xlo[g][0], xlo[g][1], xlo[g][2], xlo[g][3], x[g][0], x[g][1], x[g][2], x[g][3]};
-            split2_x8(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) xlo[g][e] = x[g][e];
+          } else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const float x8[8] = {xlo[g][0], xlo[g][1], xlo[g][2], xlo[g][3], x[g][0], x[g][1], x[g][2], x[g][3]};
+              split2_x8(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
+            }
           }
         }
+        __builtin_amdgcn_sched_barrier(0);  // the next batch is fetched only now: its registers are the ones just freed
       }
       __syncthreads();  // every wave has read the last piece
       for (int i = tid; i < V * G4; i += 4 * H) tab[(i / G4) * kTabRow + i % G4] = kSA * (Wx[i] + bg[i % G4]);
@@ -343,8 +359,6 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
         out_of_range ? __builtin_nanf("") : -total / (static_cast<float>(a.B) * static_cast<float>(La));
   }
 }
-
-}  // namespace
 
 int lstm_supported(int V, int H, int n_out, int Lq, int La) {
   EVO_REQUIRE(H == 64 || H == 128, EVO_ERR_UNSUPPORTED, "lstm: hidden width must be 64 or 128 (got %d)", H);
