@@ -31,11 +31,12 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # this file, scaled by what the same counters read for a 1 GiB copy in the same process (on this
 # box FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Sources: the summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1": 2891926,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 32558388,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
-    "cfg3": 19234522,      # profiles/cartpole_kernel_cfg3.md
-    "cfg4": 807679416,     # profiles/mlp_bf16_stream_kernel_cfg4.md
-    "cfg5": 4305241315,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
+    "cfg1": 2891893,       # profiles/mlp_f32_kernel_cfg1.md
+    "cfg2": 32755287,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
+    "cfg3": 19118589,      # profiles/cartpole_kernel_cfg3.md
+    "cfg4": 807734117,     # profiles/mlp_bf16_stream_kernel_cfg4.md
+    "cfg5": 4304870251,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
+    "seq2seq": 876919192,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
 }
 
 
@@ -157,7 +158,7 @@ def _cpu_baseline(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
-    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}[name]
+    sample_pop = {"cfg1": 2891893, "cfg2": 32755287, "cfg3": 19118589, "cfg4": 807734117, "cfg5": 96, "seq2seq": 32}[name]
     gens = {"cfg1": 600}.get(name, 1)
     dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
     if name == "cfg1":
@@ -224,7 +225,7 @@ def main():
         raise SystemExit("--variant applies to --workload cfg5 only")
     wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}[args.workload]
+    steps = args.steps if args.steps is not None else {"cfg1": 2891893, "cfg2": 32755287, "cfg3": 19118589, "cfg4": 807734117, "cfg5": 20, "seq2seq": 20}[args.workload]
     stage_names = ("ask", "rollout", "tell")
     events = []
 
