@@ -158,7 +158,7 @@ def _cpu_baseline(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
-    sample_pop = {"cfg1": 2891893, "cfg2": 32755287, "cfg3": 19118589, "cfg4": 807734117, "cfg5": 96, "seq2seq": 32}[name]
+    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}[name]
     gens = {"cfg1": 600}.get(name, 1)
     dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
     if name == "cfg1":
@@ -225,7 +225,7 @@ def main():
         raise SystemExit("--variant applies to --workload cfg5 only")
     wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
-    steps = args.steps if args.steps is not None else {"cfg1": 2891893, "cfg2": 32755287, "cfg3": 19118589, "cfg4": 807734117, "cfg5": 20, "seq2seq": 20}[args.workload]
+    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}[args.workload]
     stage_names = ("ask", "rollout", "tell")
     events = []
 
