@@ -40,6 +40,13 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# Timed generations per workload when --steps is not given (about a second of GPU time or less) and
+# the population of the oracle's bounded sample (about 10-30 s of CPU time on one core).
+DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}
+ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}
+ORACLE_SAMPLE_GENERATIONS = {"cfg1": 600}
+
+
 def _build_workload(name, seed, batch=None):
     import dataclasses
     import numpy as np
@@ -158,8 +165,8 @@ def _cpu_baseline(name, seed):
     from workloads import configs as wc
 
     c = CONFIGS[name]
-    sample_pop = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}[name]
-    gens = {"cfg1": 600}.get(name, 1)
+    sample_pop = ORACLE_SAMPLE_POP[name]
+    gens = ORACLE_SAMPLE_GENERATIONS.get(name, 1)
     dtype = opgpe.DT_BF16 if c.dtype == wc.DT_BF16 else opgpe.DT_F32
     if name == "cfg1":
         x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
@@ -225,7 +232,7 @@ def main():
         raise SystemExit("--variant applies to --workload cfg5 only")
     wl = _build_workload(args.workload, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
-    steps = args.steps if args.steps is not None else {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}[args.workload]
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload]
     stage_names = ("ask", "rollout", "tell")
     events = []
 
