@@ -142,6 +142,7 @@ def test_convnet_beyond_the_fp16_range_is_loud(evo):
 
 # ---------------------------------------------------------------- bf16 MLP on the matrix cores
 @pytest.mark.parametrize("dims,acts,pop,B", [((64, 256, 256, 16), (2, 2, 0), 6, 64), ((64, 256, 256, 16), (2, 2, 0), 3, 40),
+                                             ((64, 256, 256, 16), (2, 2, 0), 3, 520), ((64, 256, 256, 16), (1, 2, 0), 2, 448),
                                              ((64, 256, 256, 16), (2, 2, 0), 3, 128),       # two tiles of 64 rows
                                              ((64, 256, 256, 16), (2, 2, 0), 2, 200),       # ragged last tile
                                              ((32, 48, 16), (1, 0), 4, 17), ((16, 16), (0,), 2, 64)])
