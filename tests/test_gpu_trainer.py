@@ -148,3 +148,24 @@ def test_seq2seq_training_improves(evo):
     last = tr.test()
     assert last > first + 0.3 and last > -np.log(10.0) + 0.3, (first, last)
     assert tr.history[-1]["fitness_mean"] > tr.history[0]["fitness_mean"] + 0.2
+
+
+@pytest.mark.parametrize("workload,generations", [("cfg1", 12), ("cfg2", 2), ("cfg3", 1), ("cfg4", 2), ("cfg5", 2),
+                                                  ("seq2seq", 2)])
+def test_train_command_line(evo, tmp_path, capsys, workload, generations):
+    """The command line of the training shell on every named workload: one JSON line per generation,
+    finite numbers, and (cfg1) a run resumed from its checkpoint goes on from the right generation."""
+    from paper_2202_05008_amd import train
+    ck, log = str(tmp_path / "run.ckpt"), str(tmp_path / "run.jsonl")
+    assert train.main(["--workload", workload, "--generations", str(generations), "--test-every", "1", "--ckpt", ck,
+                       "--log", log]) == 0
+    lines = [json.loads(l) for l in capsys.readouterr().out.splitlines()]
+    assert [r["generation"] for r in lines[:-1]] == list(range(1, generations + 1))
+    assert all(np.isfinite(r["fitness_mean"]) and np.isfinite(r["test_fitness"]) for r in lines[:-1])
+    assert lines[-1]["generation"] == generations + 1 and np.isfinite(lines[-1]["final_test_fitness"])
+    assert len(open(log).readlines()) == generations
+    if workload == "cfg1":
+        assert train.main(["--workload", workload, "--generations", "3", "--ckpt", ck, "--resume"]) == 0
+        more = [json.loads(l) for l in capsys.readouterr().out.splitlines()]
+        assert more[0] == {"resumed_at_generation": generations + 1}
+        assert [r["generation"] for r in more[1:-1]] == [generations + 1, generations + 2, generations + 3]
