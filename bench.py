@@ -98,11 +98,13 @@ def _build_workload(name, seed, batch=None):
                for b in batches]
         wl["keep"].append(batches)
         wl["task"] = lambda t: tds[t % len(tds)]
+        wl["n_tasks"] = len(tds)
         wl["dtype"] = "f32"
     elif name == "cfg3":
         wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
         wl["task"] = lambda t: evo.make_task_desc(evo.EVO_TASK_CARTPOLE, n_rollouts=c.n_rollouts, reset_seed=seed,
-                                                  generation=t + 1, cp=c.cartpole, init_scale=c.init_scale)
+                                                  generation=t + 1, cp=c.cartpole, init_scale=c.init_scale,
+                                                  generation_dev=wl.get("gen_dev"))
         flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.evals_per_generation
         wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
         # layer 2 as issued: three fp16 matrix instructions per product (layer 1 runs on the fp32 instruction)
@@ -143,6 +145,7 @@ def _build_workload(name, seed, batch=None):
             tds.append(evo.make_task_desc(evo.EVO_TASK_SEQ2SEQ, B=c.B, obs=qd, target=ad, seq_in=q.shape[1],
                                           seq_out=a.shape[1]))
         wl["task"] = lambda t: tds[t % len(tds)]
+        wl["n_tasks"] = len(tds)
         Lq, La = 2 * c.digits + 2, c.digits + 1
         flops = 2.0 * ((Lq + La) * H * 4 * H + La * H * n_out) * c.pop * c.B
         wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
@@ -216,6 +219,9 @@ def main():
     ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
                     help="cfg5 only: 'fused' = ask fused with the sphere fitness (no population in memory), "
                          "'stored' = tell reads the perturbations back from the stored population")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each generation from a recorded HIP graph (generation index kept on the device); "
+                         "the per-stage times then come from an untimed pass of direct calls before the replays")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -265,14 +271,33 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.graph:
+        wl["gen_dev"] = pg.device_generation()
     for t in range(args.warmup):
         generation(t, False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(steps):
-        generation(args.warmup + t, True)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if args.graph:      # one recorded generation per distinct batch; each replay is the next generation
+        for t in range(min(steps, 20)):
+            generation(args.warmup + t, True)
+        graphs = []
+        for k in range(wl.get("n_tasks", 1)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                generation(k, False)
+            graphs.append(g)
+        _ = pg.generation      # recording moved the host copy of the index, not the device's: bring it back
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(steps):
+            graphs[t % len(graphs)].replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for t in range(steps):
+            generation(args.warmup + t, True)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
 
     stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in events) / len(events) for i, n in enumerate(stage_names)}
     assert torch.isfinite(wl["fitness"]).all(), "non-finite fitness after the timed region"
@@ -298,6 +323,8 @@ def main():
     if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
         out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
+    if args.graph:
+        out["config"]["launch"] = "HIP graph replay of one recorded generation; stage_ms from direct calls before it"
     if args.batch is not None:
         out["config"]["batch_override"] = args.batch
         out["roofline"]["traffic"] = None

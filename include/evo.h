@@ -77,7 +77,7 @@ typedef struct {
 
 typedef struct pgpe_state pgpe_state; /* host handle: config, t, pending (seed, pop), pointers */
 
-/* Bytes of device workspace a state needs (ranks and shaped fitness). */
+/* Bytes of device workspace a state needs (ranks, shaped fitness, norms, the device copy of t). */
 size_t pgpe_workspace_bytes(const pgpe_config* cfg);
 
 /* Create a host handle around caller-owned device arrays mu, sigma, m, v (fp32[P] each),
@@ -112,6 +112,18 @@ int pgpe_center(const pgpe_state* st, int32_t rows, void* params_dev, int32_t dt
 size_t pgpe_state_bytes(const pgpe_state* st);
 int pgpe_state_export(const pgpe_state* st, void* host_buf, size_t bytes, void* stream);
 int pgpe_state_import(pgpe_state* st, const void* host_buf, size_t bytes, void* stream);
+
+/* Generation index on the device, for callers that record one generation (ask, rollout, tell) in a
+ * HIP graph and replay it: kernel arguments are frozen in a graph, so t must not be one.  After this
+ * call the state also keeps t in its workspace (*gen_dev_out points at it), ask / tell / ask_sphere
+ * read it there, tell advances it with a one-thread kernel in stream order, and Adam's bias
+ * corrections are formed in the kernel (same double-precision formula).  Every replay of a captured
+ * generation is then the next generation.  The host copy keeps following direct calls;
+ * pgpe_sync_generation brings it up to date after replays (it waits for the stream), and
+ * pgpe_state_export reads the device copy.  pgpe_set_generation is refused in this mode.
+ * Errors: EVO_ERR_ARG, EVO_ERR_STATE (an ask is pending), EVO_ERR_HIP. */
+int pgpe_device_generation(pgpe_state* st, const uint32_t** gen_dev_out, void* stream);
+int pgpe_sync_generation(pgpe_state* st, void* stream);
 
 /* ask: theta[2k][i] = mu[i] + sigma[i] z_k[i],  theta[2k+1][i] = mu[i] - sigma[i] z_k[i],
  * written to params_dev[pop][P] as fp32 (EVO_F32) or bfloat16 rounded to nearest even
@@ -247,6 +259,8 @@ typedef struct {
   float init_scale;            /* CARTPOLE: scale of the reset normals                       */
   int32_t seq_out;             /* SEQ2SEQ: tokens per answer                                 */
   void* work_dev;              /* workspace of rollout_workspace_bytes(...) bytes, or NULL if 0 */
+  const uint32_t* generation_dev; /* CARTPOLE: if not NULL, t is read from this device word at run time
+                                     (see pgpe_device_generation) instead of `generation`            */
 } task_desc;
 
 /* Bytes of device workspace `rollout` needs for this task / policy / pop (may be 0). */

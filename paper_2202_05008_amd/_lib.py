@@ -29,7 +29,7 @@ class task_desc(C.Structure):
                 ("reset_seed", C.c_uint64), ("generation", C.c_uint32), ("seq_in", C.c_int32),
                 ("obs_dev", C.c_void_p), ("obs_member_stride", C.c_int64), ("target_dev", C.c_void_p),
                 ("cp", C.c_float * 8), ("init_scale", C.c_float), ("seq_out", C.c_int32),
-                ("work_dev", C.c_void_p)]
+                ("work_dev", C.c_void_p), ("generation_dev", C.c_void_p)]
 
 
 _SIGNATURES = {
@@ -44,6 +44,8 @@ _SIGNATURES = {
     "pgpe_state_bytes": (C.c_size_t, [C.c_void_p]),
     "pgpe_state_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "pgpe_state_import": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "pgpe_device_generation": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p]),
+    "pgpe_sync_generation": (C.c_int, [C.c_void_p, C.c_void_p]),
     "pgpe_ask": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "pgpe_tell": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "pgpe_ask_sphere_workspace_bytes": (C.c_size_t, [C.POINTER(pgpe_config)]),

@@ -69,7 +69,7 @@ def make_policy_desc(kind, dims, act=(), dtype=EVO_F32):
 
 
 def make_task_desc(kind, n_rollouts=1, B=0, P=0, reset_seed=0, generation=1, obs=None, obs_member_stride=0,
-                   target=None, cp=None, init_scale=0.2, work=None, seq_in=0, seq_out=0):
+                   target=None, cp=None, init_scale=0.2, work=None, seq_in=0, seq_out=0, generation_dev=None):
     td = task_desc()
     td.kind, td.n_rollouts, td.B, td.P = kind, n_rollouts, B, P
     td.seq_in, td.seq_out = seq_in, seq_out
@@ -82,6 +82,7 @@ def make_task_desc(kind, n_rollouts=1, B=0, P=0, reset_seed=0, generation=1, obs
             td.cp[i] = v
     td.init_scale = init_scale
     td.work_dev = work.data_ptr() if work is not None else None
+    td.generation_dev = generation_dev
     td._keepalive = (obs, target, work)
     return td
 
@@ -137,6 +138,17 @@ def pgpe_state_export(h):
 def pgpe_state_import(h, blob):
     buf = C.create_string_buffer(bytes(blob), len(blob))
     _check(_lib.load().pgpe_state_import(h, buf, len(blob), _stream()))
+
+
+def pgpe_device_generation(h):
+    """Keep the generation index on the device too (for HIP-graph replays); returns its device address."""
+    p = C.c_void_p()
+    _check(_lib.load().pgpe_device_generation(h, C.byref(p), _stream()))
+    return p.value
+
+
+def pgpe_sync_generation(h):
+    _check(_lib.load().pgpe_sync_generation(h, _stream()))
 
 
 def pgpe_ask(h, seed, pop, params, dtype=EVO_F32):
@@ -259,8 +271,15 @@ class PGPE:
     def import_state(self, blob):
         pgpe_state_import(self.handle, blob)
 
+    def device_generation(self):
+        """Switch to a device-resident generation index (graph replays then advance it); returns its address."""
+        self._gen_dev = pgpe_device_generation(self.handle)
+        return self._gen_dev
+
     @property
     def generation(self):
+        if getattr(self, "_gen_dev", None):
+            pgpe_sync_generation(self.handle)      # replays advance only the device copy
         return pgpe_get_generation(self.handle)
 
     def close(self):

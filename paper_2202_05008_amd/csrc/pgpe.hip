@@ -24,6 +24,7 @@ struct pgpe_state {
   float* aux;
   void* work;
   uint32_t t;
+  bool device_t;  // the generation index also lives on the device and the kernels read it there
   bool pending;
   uint64_t seed;
   int32_t pop;
@@ -38,17 +39,20 @@ struct Workspace {
   float* shaped;   // [pop_max] utilities c_m
   uint32_t* rank;  // [pop_max]
   float* norm;     // [2][kNormBlocks] partial sums of |g|^2 and |vel|^2
+  uint32_t* gen;   // generation index t on the device (used once pgpe_device_generation has been called)
 };
 
-static inline size_t ws_bytes(int pop_max) {
+static inline size_t ws_arrays_bytes(int pop_max) {
   return ((static_cast<size_t>(pop_max) * 2 + 2 * kNormBlocks) * 4 + 255) & ~size_t(255);
 }
+static inline size_t ws_bytes(int pop_max) { return ws_arrays_bytes(pop_max) + 256; }
 
 static inline Workspace ws_carve(void* base, int pop_max) {
   Workspace w;
   w.shaped = static_cast<float*>(base);
   w.rank = reinterpret_cast<uint32_t*>(w.shaped + pop_max);
   w.norm = reinterpret_cast<float*>(w.rank + pop_max);
+  w.gen = reinterpret_cast<uint32_t*>(static_cast<char*>(base) + ws_arrays_bytes(pop_max));
   return w;
 }
 
@@ -89,7 +93,9 @@ __device__ __forceinline__ void store_row4(uint16_t* row, int col, int P, const 
 template <typename OutT>
 __global__ __launch_bounds__(256) void ask_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
                                                   OutT* __restrict__ params, int P, int nquads, int N,
-                                                  int pairs_per_block, uint32_t gen, uint32_t key0, uint32_t key1) {
+                                                  int pairs_per_block, uint32_t gen_host,
+                                                  const uint32_t* __restrict__ gen_dev, uint32_t key0, uint32_t key1) {
+  const uint32_t gen = gen_dev ? *gen_dev : gen_host;  // uniform: the device copy when the state keeps one
   const int q = blockIdx.x * 256 + threadIdx.x;
   if (q >= nquads) return;
   const int col = q * 4;
@@ -128,7 +134,9 @@ __global__ __launch_bounds__(256) void ask_kernel(const float* __restrict__ mu, 
 // Philox counters) of one pair, so that each row takes one 16-byte streaming store per thread.
 __global__ __launch_bounds__(256) void ask_bf16x8_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
                                                          uint16_t* __restrict__ params, int P, int noct,
-                                                         uint32_t gen, uint32_t key0, uint32_t key1) {
+                                                         uint32_t gen_host, const uint32_t* __restrict__ gen_dev,
+                                                         uint32_t key0, uint32_t key1) {
+  const uint32_t gen = gen_dev ? *gen_dev : gen_host;
   const int o = blockIdx.x * 256 + threadIdx.x;
   if (o >= noct) return;
   const int col = o * 8, k = blockIdx.y;
@@ -162,8 +170,10 @@ constexpr int kFusedPairs = 4;
 
 __global__ __launch_bounds__(256) void ask_sphere_kernel(const float* __restrict__ mu, const float* __restrict__ sigma,
                                                          const float* __restrict__ x_star, float* __restrict__ part,
-                                                         int P, int nquads, int N, int xblocks, uint32_t gen,
-                                                         uint32_t key0, uint32_t key1) {
+                                                         int P, int nquads, int N, int xblocks, uint32_t gen_host,
+                                                         const uint32_t* __restrict__ gen_dev, uint32_t key0,
+                                                         uint32_t key1) {
+  const uint32_t gen = gen_dev ? *gen_dev : gen_host;
   __shared__ float red[4][2 * kFusedPairs];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int k0 = blockIdx.y * kFusedPairs;
@@ -302,6 +312,7 @@ struct TellArgs {
   const float* theta;   // stored population [2N][P] (STORED form) or null
   int P, nquads, N, KS;
   uint32_t gen, key0, key1;
+  const uint32_t* gen_dev;  // when set: t is read here and the bias corrections are formed in the kernel
   float inv_n, lr_mu, lr_sigma, max_change, beta1, beta2, eps, bc1, bc2, momentum;
 };
 
@@ -326,6 +337,12 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
   float* u_s = smem + a.N;
   float* part = smem + 2 * a.N;  // [KS][QPB][8] when KS > 1
   const int tid = threadIdx.x;
+  if (a.gen_dev) {  // generation index on the device: the same double-precision bias corrections the host forms
+    a.gen = *a.gen_dev;
+    const double t = static_cast<double>(a.gen);
+    a.bc1 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(a.beta1), t)));
+    a.bc2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(a.beta2), t)));
+  }
   const int QPB = 256 / a.KS;
   const int ql = tid % QPB;
   const int ks = tid / QPB;
@@ -529,6 +546,11 @@ __global__ __launch_bounds__(256) void center_kernel(const float* __restrict__ m
   }
 }
 
+// t <- value (set != 0) or t <- t + 1, by one thread, in stream order after the kernels that read t.
+__global__ void generation_kernel(uint32_t* __restrict__ gen, uint32_t value, int set) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *gen = set ? value : *gen + 1u;
+}
+
 __global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t n, float value) {
   const size_t stride = static_cast<size_t>(gridDim.x) * 256;
   for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) p[i] = value;
@@ -587,6 +609,36 @@ static int check_ask_pop(const pgpe_state* st, int32_t pop, const char* who) {
   return EVO_OK;
 }
 
+// The device copy of t, or null while the state keeps t on the host only.
+static const uint32_t* device_generation(const pgpe_state* st) {
+  return st->device_t ? ws_carve(st->work, st->cfg.pop_max).gen : nullptr;
+}
+
+// Host t -> device copy, in stream order.
+static int write_device_generation(pgpe_state* st, hipStream_t s) {
+  hipLaunchKernelGGL(generation_kernel, dim3(1), dim3(64), 0, s, ws_carve(st->work, st->cfg.pop_max).gen, st->t, 1);
+  return check_launch("generation_kernel");
+}
+
+// Device copy -> host t; waits for the stream.
+static int read_device_generation(pgpe_state* st, hipStream_t s) {
+  uint32_t t = 0;
+  hipError_t e = hipMemcpyAsync(&t, ws_carve(st->work, st->cfg.pop_max).gen, sizeof(t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "reading the generation index back failed: %s", hipGetErrorString(e));
+  st->t = t;
+  return EVO_OK;
+}
+
+// After a tell: t <- t + 1, on the host and (in stream order) on the device.
+static int advance_generation(pgpe_state* st, hipStream_t s) {
+  st->pending = false;
+  st->t += 1;
+  if (!st->device_t) return EVO_OK;
+  hipLaunchKernelGGL(generation_kernel, dim3(1), dim3(64), 0, s, ws_carve(st->work, st->cfg.pop_max).gen, 0u, 0);
+  return check_launch("generation_kernel");
+}
+
 // Shared by pgpe_tell, pgpe_tell_stored and the gradient hook (theta: stored population or null).
 static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, const float* theta,
                     hipStream_t s) {
@@ -610,6 +662,7 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   while (KS < 64 && KS * 2 <= N && static_cast<long>(a.nquads) * KS < threads_wanted) KS *= 2;
   a.KS = KS;
   a.gen = st->t, a.key0 = static_cast<uint32_t>(st->seed), a.key1 = static_cast<uint32_t>(st->seed >> 32);
+  a.gen_dev = st->device_t ? ws.gen : nullptr;
   a.inv_n = 1.0f / static_cast<float>(N);
   a.lr_mu = c.lr_mu, a.lr_sigma = c.lr_sigma, a.max_change = c.sigma_max_change;
   a.beta1 = c.beta1, a.beta2 = c.beta2, a.eps = c.eps, a.momentum = c.momentum;
@@ -673,7 +726,7 @@ extern "C" int pgpe_create(pgpe_state** out, const pgpe_config* cfg, float* mu_d
   EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_create: out of host memory");
   st->cfg = *cfg;
   st->mu = mu_dev, st->sigma = sigma_dev, st->m = m_dev, st->v = v_dev, st->aux = aux_dev, st->work = work_dev;
-  st->t = 1, st->pending = false, st->seed = 0, st->pop = 0;
+  st->t = 1, st->device_t = false, st->pending = false, st->seed = 0, st->pop = 0;
   *out = st;
   return EVO_OK;
 }
@@ -693,7 +746,22 @@ extern "C" int pgpe_reset(pgpe_state* st, void* stream) {
   if (!rc && st->aux) rc = fill(st->aux, 2 * P, 0.f, s);
   st->t = 1;
   st->pending = false;
+  if (!rc && st->device_t) rc = write_device_generation(st, s);
   return rc;
+}
+
+extern "C" int pgpe_device_generation(pgpe_state* st, const uint32_t** gen_dev_out, void* stream) {
+  EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_device_generation: state is null");
+  EVO_REQUIRE(!st->pending, EVO_ERR_STATE, "pgpe_device_generation: an ask is pending (call it between tell and ask)");
+  st->device_t = true;
+  if (gen_dev_out) *gen_dev_out = ws_carve(st->work, st->cfg.pop_max).gen;
+  return write_device_generation(st, as_stream(stream));
+}
+
+extern "C" int pgpe_sync_generation(pgpe_state* st, void* stream) {
+  EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_sync_generation: state is null");
+  if (!st->device_t) return EVO_OK;
+  return read_device_generation(st, as_stream(stream));
 }
 
 extern "C" int pgpe_center(const pgpe_state* st, int32_t rows, void* params_dev, int32_t dtype, void* stream) {
@@ -744,10 +812,16 @@ extern "C" int pgpe_state_export(const pgpe_state* st, void* host_buf, size_t by
   EVO_REQUIRE(bytes >= state_bytes(st->cfg), EVO_ERR_ARG, "pgpe_state_export: buffer of %zu bytes, %zu needed", bytes,
               state_bytes(st->cfg));
   EVO_REQUIRE(!st->pending, EVO_ERR_STATE, "pgpe_state_export: an ask is pending (export between tell and ask)");
+  uint32_t t_now = st->t;
+  if (st->device_t) {  // replays of a captured generation advance only the device copy
+    hipError_t e = hipMemcpyAsync(&t_now, device_generation(st), sizeof(t_now), hipMemcpyDeviceToHost, as_stream(stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(as_stream(stream));
+    EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "pgpe_state_export: %s", hipGetErrorString(e));
+  }
   StateHeader h;
   memcpy(h.magic, kStateMagic, 8);
   h.header_bytes = sizeof(StateHeader);
-  h.t = st->t;
+  h.t = t_now;
   h.cfg = st->cfg;
   memcpy(host_buf, &h, sizeof(h));
   hipStream_t s = as_stream(stream);
@@ -784,7 +858,7 @@ extern "C" int pgpe_state_import(pgpe_state* st, const void* host_buf, size_t by
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "pgpe_state_import: %s", hipGetErrorString(e));
   st->t = h.t;
   st->pending = false;
-  return EVO_OK;
+  return st->device_t ? write_device_generation(st, s) : EVO_OK;
 }
 
 extern "C" int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out) {
@@ -795,6 +869,8 @@ extern "C" int pgpe_get_generation(const pgpe_state* st, uint32_t* t_out) {
 
 extern "C" int pgpe_set_generation(pgpe_state* st, uint32_t t) {
   EVO_REQUIRE(st != nullptr && t >= 1, EVO_ERR_ARG, "pgpe_set_generation: state null or t < 1");
+  EVO_REQUIRE(!st->device_t, EVO_ERR_STATE,
+              "pgpe_set_generation: the state keeps t on the device; use pgpe_state_import or pgpe_reset");
   st->t = t;
   st->pending = false;
   return EVO_OK;
@@ -815,17 +891,18 @@ extern "C" int pgpe_ask(pgpe_state* st, uint64_t seed, int32_t pop, void* params
   const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>(N));
   hipStream_t s = as_stream(stream);
   const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+  const uint32_t* gen_dev = device_generation(st);
   if (dtype == EVO_F32) {
     hipLaunchKernelGGL(ask_kernel<float>, grid, dim3(256), 0, s, st->mu, st->sigma,
-                       static_cast<float*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
+                       static_cast<float*>(params_dev), P, nquads, N, ppb, st->t, gen_dev, k0, k1);
   } else if ((P & 7) == 0) {
     const int noct = P / 8;
     hipLaunchKernelGGL(ask_bf16x8_kernel, dim3(static_cast<unsigned>((noct + 255) / 256), static_cast<unsigned>(N)),
-                       dim3(256), 0, s, st->mu, st->sigma, static_cast<uint16_t*>(params_dev), P, noct, st->t, k0,
-                       k1);
+                       dim3(256), 0, s, st->mu, st->sigma, static_cast<uint16_t*>(params_dev), P, noct, st->t, gen_dev,
+                       k0, k1);
   } else {
     hipLaunchKernelGGL(ask_kernel<uint16_t>, grid, dim3(256), 0, s, st->mu, st->sigma,
-                       static_cast<uint16_t*>(params_dev), P, nquads, N, ppb, st->t, k0, k1);
+                       static_cast<uint16_t*>(params_dev), P, nquads, N, ppb, st->t, gen_dev, k0, k1);
   }
   int rc = check_launch("ask_kernel");
   if (rc) return rc;
@@ -852,7 +929,8 @@ extern "C" int pgpe_ask_sphere(pgpe_state* st, uint64_t seed, int32_t pop, const
   float* part = static_cast<float*>(work_dev);
   const dim3 grid(static_cast<unsigned>(xblocks), static_cast<unsigned>((N + kFusedPairs - 1) / kFusedPairs));
   hipLaunchKernelGGL(ask_sphere_kernel, grid, dim3(256), 0, s, st->mu, st->sigma, x_star_dev, part, P, nquads, N,
-                     xblocks, st->t, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
+                     xblocks, st->t, device_generation(st), static_cast<uint32_t>(seed),
+                     static_cast<uint32_t>(seed >> 32));
   rc = check_launch("ask_sphere_kernel");
   if (rc) return rc;
   hipLaunchKernelGGL(sphere_finish_kernel, dim3(static_cast<unsigned>((pop + 3) / 4)), dim3(256), 0, s, part, xblocks,
@@ -870,9 +948,7 @@ extern "C" int pgpe_tell(pgpe_state* st, const float* fitness_dev, void* stream)
   EVO_REQUIRE(st->pending, EVO_ERR_STATE, "pgpe_tell: no pending ask");
   int rc = run_tell(st, fitness_dev, nullptr, nullptr, nullptr, as_stream(stream));
   if (rc) return rc;
-  st->pending = false;
-  st->t += 1;
-  return EVO_OK;
+  return advance_generation(st, as_stream(stream));
 }
 
 extern "C" int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* params_dev, void* stream) {
@@ -881,9 +957,7 @@ extern "C" int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const 
   EVO_REQUIRE(st->pending, EVO_ERR_STATE, "pgpe_tell_stored: no pending ask");
   int rc = run_tell(st, fitness_dev, nullptr, nullptr, params_dev, as_stream(stream));
   if (rc) return rc;
-  st->pending = false;
-  st->t += 1;
-  return EVO_OK;
+  return advance_generation(st, as_stream(stream));
 }
 
 extern "C" int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev,

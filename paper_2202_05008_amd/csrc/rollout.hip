@@ -195,7 +195,8 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     rc = cartpole_supported(sh, td->n_rollouts);
     if (rc) return rc;
     return launch_cartpole(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp,
-                           td->init_scale, td->reset_seed, td->generation, fitness_dev, ret_dev, final_dev, s);
+                           td->init_scale, td->reset_seed, td->generation, td->generation_dev, fitness_dev, ret_dev,
+                           final_dev, s);
   }
   // supervised single-step tasks
   EVO_REQUIRE(pd->kind != EVO_POLICY_LSTM_SEQ2SEQ, EVO_ERR_UNSUPPORTED,

@@ -49,6 +49,7 @@ struct CartpoleArgs {
   CartpoleConst c;
   float init_scale;
   uint32_t key0, key1, gen;
+  const uint32_t* gen_dev;  // when set, the counter word t of the reset stream is read here
   float* fitness;
   float* ret;
   float* final_state;
@@ -145,6 +146,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, q = lane >> 4;
   const int member = blockIdx.x;
+  if (a.gen_dev) a.gen = *a.gen_dev;
   const float* theta = a.params + static_cast<size_t>(member) * a.P;
   const int col = 16 * wave + j;  // this lane's hidden neuron
 
@@ -332,8 +334,8 @@ int cartpole_supported(const MlpShape& sh, int n_rollouts) {
 }
 
 int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_rollouts, int steps, const float* cp,
-                    float init_scale, uint64_t seed, uint32_t gen, float* fitness, float* ret, float* final_state,
-                    hipStream_t s) {
+                    float init_scale, uint64_t seed, uint32_t gen, const uint32_t* gen_dev, float* fitness, float* ret,
+                    float* final_state, hipStream_t s) {
   CartpoleArgs a;
   a.params = params, a.P = sh.P, a.R = n_rollouts, a.steps = steps;
   a.c = make_const(cp);
@@ -341,6 +343,7 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
               "cartpole: dt, length and cart mass must be positive");
   a.init_scale = init_scale;
   a.key0 = static_cast<uint32_t>(seed), a.key1 = static_cast<uint32_t>(seed >> 32), a.gen = gen;
+  a.gen_dev = gen_dev;
   a.fitness = fitness, a.ret = ret, a.final_state = final_state;
   const int H = sh.dims[1];
   const int a1 = sh.act[0], a2 = sh.n_layers == 3 ? sh.act[1] : 0, a3 = sh.act[sh.n_layers - 1];
