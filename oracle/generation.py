@@ -3,13 +3,13 @@
 Strings the pieces together in the order the paper's training loop has them (Section 2,
 Figure 2 and the trainer / simulation-manager paragraph; Section 4's ask / tell):
 ask -> evaluate every member with the global policy on the vectorised task -> tell.
-`task` is a plain dict: kind in {"classify","regress","cartpole","sphere","seq2seq"}, the policy
+`task` is a plain dict: kind in {"classify","regress","cartpole","sphere","seq2seq","forage"}, the policy
 description and the task's input arrays.  parity unpinned as a whole: the paper prints no
 value of any generation; every stage it calls is pinned on its own.
 """
 import numpy as np
 
-from . import pgpe, policy, seq2seq, tasks
+from . import forage, pgpe, policy, seq2seq, tasks
 
 
 def evaluate(task, params, seed, generation):
@@ -21,6 +21,9 @@ def evaluate(task, params, seed, generation):
         return tasks.cartpole_rollout(params, task["dims"], task["acts"], seed, generation,
                                       task["n_rollouts"], task["steps"], task.get("cp", tasks.CP_DEFAULT),
                                       task.get("init_scale", 0.2))
+    if kind == "forage":
+        return forage.rollout(params, task["dims"], task["acts"], seed, generation, task["n_worlds"], task["steps"],
+                              task.get("world", forage.WORLD_DEFAULT))
     if kind == "seq2seq":
         return seq2seq.fitness(seq2seq.forward(params, task["query"], task["answer"], task["H"]), task["answer"])
     if task.get("convnet"):

@@ -12,7 +12,7 @@ from typing import Tuple
 # integer codes shared with the C ABI (include/evo.h) by value
 ACT_NONE, ACT_TANH, ACT_RELU = 0, 1, 2
 POLICY_MLP, POLICY_CONVNET, POLICY_LSTM_SEQ2SEQ = 0, 1, 2
-TASK_CLASSIFY, TASK_REGRESS, TASK_CARTPOLE, TASK_SPHERE, TASK_SEQ2SEQ = 0, 1, 2, 3, 4
+TASK_CLASSIFY, TASK_REGRESS, TASK_CARTPOLE, TASK_SPHERE, TASK_SEQ2SEQ, TASK_FORAGE = 0, 1, 2, 3, 4, 5
 DT_F32, DT_BF16 = 0, 1
 
 
@@ -55,6 +55,8 @@ class WorkloadConfig:
     cartpole: Tuple[float, ...] = field(default=(9.82, 0.5, 0.5, 0.6, 0.1, 10.0, 0.01, 2.4))
     init_scale: float = 0.2
     digits: int = 3                # seq2seq: digits per operand ("012+345=" -> "0357")
+    # shared world: dt, thrust, drag, vmax, touch radius, food items, poison items
+    world: Tuple[float, ...] = field(default=(0.0625, 0.015625, 0.875, 0.25, 0.03125, 24, 24))
 
     @property
     def P(self) -> int:
@@ -69,7 +71,7 @@ class WorkloadConfig:
     @property
     def evals_per_generation(self) -> int:
         """member-evals: pop x samples, or env-steps, or pop x P parameter samples."""
-        if self.task_kind == TASK_CARTPOLE:
+        if self.task_kind in (TASK_CARTPOLE, TASK_FORAGE):
             return self.pop * self.n_rollouts * self.steps
         if self.task_kind == TASK_SPHERE:
             return self.pop
@@ -94,4 +96,9 @@ CONFIGS = {
     # LSTM encoder-decoder of 145,674 parameters on strings of three-digit additions
     "seq2seq": WorkloadConfig("seq2seq", pop=1024, policy_kind=POLICY_LSTM_SEQ2SEQ, dims=(12, 128, 10), acts=(),
                               dtype=DT_F32, task_kind=TASK_SEQ2SEQ, B=128, digits=3),
+    # the multi-agent scheme of Section 3's WaterWorld paragraph: the whole population lives in each of
+    # n_rollouts shared worlds, one agent per member
+    "forage": WorkloadConfig("forage", pop=1024, policy_kind=POLICY_MLP, dims=(8, 32, 32, 2),
+                             acts=(ACT_TANH, ACT_TANH, ACT_TANH), dtype=DT_F32, task_kind=TASK_FORAGE,
+                             n_rollouts=8, steps=500),
 }
