@@ -37,13 +37,14 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg4": 807734117,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4304870251,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
     "seq2seq": 876919192,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
+    "forage": None,        # launch-latency bound: 500 step kernels of a few microseconds, the weights stay in L2
 }
 
 
 # Timed generations per workload when --steps is not given (about a second of GPU time or less) and
 # the population of the oracle's bounded sample (about 10-30 s of CPU time on one core).
-DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20}
-ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32}
+DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20, "forage": 20}
+ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32, "forage": 128}
 ORACLE_SAMPLE_GENERATIONS = {"cfg1": 600}
 
 
@@ -66,6 +67,12 @@ def _build_workload(name, seed, batch=None):
     params = torch.empty(c.pop, c.P, dtype=tdtype, device=dev)
     fitness = torch.empty(c.pop, dtype=torch.float32, device=dev)
     wl = {"cfg": c, "pgpe": pg, "params": params, "fitness": fitness, "evo": evo}
+
+    def with_work_cached(make):      # one workspace, a fresh descriptor per generation
+        if "work" not in wl:
+            n = evo.rollout_workspace_bytes(make(None), wl.get("pd"), c.pop)
+            wl["work"] = torch.empty(max(n, 16), dtype=torch.uint8, device=dev)
+        return make(wl["work"])
 
     def with_work(make):
         td = make(None)
@@ -153,6 +160,22 @@ def _build_workload(name, seed, batch=None):
         wl["desc"] = ("seq2seq: LSTM encoder-decoder H=128 (P=145674) on three-digit addition strings, pop 1024, "
                       "128 strings per member")
         wl["dtype"] = "f32"
+    elif name == "forage":
+        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+        w = wc.world_dict(c.world)
+        cp = tuple(c.world)
+        wl["task"] = lambda t: with_work_cached(lambda work: evo.make_task_desc(
+            evo.EVO_TASK_FORAGE, n_rollouts=c.n_rollouts, reset_seed=seed, generation=t + 1, cp=cp, work=work,
+            generation_dev=wl.get("gen_dev")))
+        # one launch = one step of every world: per agent the scan over the others (2 sub, 2 mul, add, compare per
+        # candidate) and over the items (twice: sensing and touching), and the policy's multiply-adds
+        n_items = w["n_food"] + w["n_poison"]
+        per_agent = 6.0 * c.pop + 2 * 6.0 * n_items + 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(3))
+        wl["roofline"] = ("alu", per_agent * c.pop * c.n_rollouts, PEAK_ALU_F32_TF, "TFLOP/s")
+        wl["launches"] = c.steps      # the stage is `steps` launches of the step kernel (+ reset and finish)
+        wl["desc"] = ("forage: the population as %d agents of each of %d shared worlds, fp32 MLP 8-32-32-2, %d steps "
+                      "(one launch per step)" % (c.pop, c.n_rollouts, c.steps))
+        wl["dtype"] = "f32"
     else:
         raise SystemExit("unknown workload %r" % name)
     wl.setdefault("roofline_stage", "rollout")
@@ -191,6 +214,10 @@ def _cpu_baseline(name, seed):
         q, a = gen.addition_batch(c.data_seed, 1, c.B, c.digits)
         task = {"kind": "seq2seq", "H": c.dims[1], "query": q, "answer": a}
         evals = sample_pop * c.B
+    elif name == "forage":      # a smaller population is a smaller crowd in each world, not a slice of the big one
+        task = {"kind": "forage", "dims": c.dims, "acts": c.acts, "n_worlds": c.n_rollouts, "steps": c.steps,
+                "world": wc.world_dict(c.world)}
+        evals = sample_pop * c.n_rollouts * c.steps
     else:
         task = {"kind": "sphere", "x_star": gen.sphere_target(c.data_seed, c.P)}
         evals = sample_pop
@@ -211,7 +238,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq", "forage"])
     ap.add_argument("--seed", type=int, default=20220509)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=None,
@@ -304,7 +331,7 @@ def main():
     ms_per_step = elapsed * 1e3 / steps
     value = c.evals_per_generation * steps / elapsed
     bound, work, peak, unit = wl["roofline"]
-    dom_ms = stage_ms[wl["roofline_stage"]]
+    dom_ms = stage_ms[wl["roofline_stage"]] / wl.get("launches", 1)      # average duration of one launch
     achieved = work / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
     out = {
         "metric": "member-evals/sec (pop x samples, or env-steps/s, or pop for the sphere) for one whole ES generation",
@@ -317,6 +344,8 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": wl["roofline_stage"], "kernel_ms": dom_ms},
     }
+    if "launches" in wl:
+        out["roofline"]["launches_per_generation"] = wl["launches"]
     if "f16_issued_flops" in wl:      # the same contraction counted as the fp16 matrix instructions that carry it
         out["roofline"]["mfma_f16_issued_tflops"] = wl["f16_issued_flops"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_f16_issued_frac"] = out["roofline"]["mfma_f16_issued_tflops"] / PEAK_MFMA_BF16_TF

@@ -43,8 +43,9 @@ typedef enum {
 enum { EVO_F32 = 0, EVO_BF16 = 1 };                                   /* parameter storage  */
 enum { EVO_ACT_NONE = 0, EVO_ACT_TANH = 1, EVO_ACT_RELU = 2 };
 enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1, EVO_POLICY_LSTM_SEQ2SEQ = 2 };
-enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3, EVO_TASK_SEQ2SEQ = 4 };
-enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1 };                        /* Philox stream tags */
+enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3, EVO_TASK_SEQ2SEQ = 4,
+       EVO_TASK_FORAGE = 5 };
+enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1, EVO_TAG_WORLD_AGENT = 2, EVO_TAG_WORLD_ITEM = 3 }; /* Philox stream tags */
 enum { EVO_OPT_ADAM = 0, EVO_OPT_CLIPUP = 1, EVO_OPT_MOMENTUM = 2 };  /* optimizer of mu    */
 #define EVO_POP_MAX 4096
 #define EVO_MAX_LAYERS 8
@@ -243,23 +244,43 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *   state, counted while alive; the episode dies after a step ending with |x'| > x_limit.
  *   Reset of roll-out r: (x, x_d, th - pi, th_d) = init_scale * the four normals of Philox
  *   counter (0, r, generation, EVO_TAG_RESET) under reset_seed: the same for every member.
+ *   FORAGE    the multi-agent scheme of Section 3's WaterWorld paragraph: the whole population is
+ *             spawned in the same roll-out, member a as agent a of each of n_rollouts worlds, and
+ *             fitness = an agent's summed reward, averaged over the worlds.  The paper gives no
+ *             rules; this world is the library's own definition:
+ *     cp = {dt, thrust, drag, vmax, touch radius, food items F, poison items Q} (F, Q whole numbers,
+ *     F + Q <= 256); policy: fp32 MLP of dims {8, H, H, 2}, H in {16, 32, 64}; pop <= about 1900.
+ *     World r: the unit square; agent a starts at rest at (u(x0), u(x1)) of Philox counter
+ *     (a, r, generation, EVO_TAG_WORLD_AGENT) under reset_seed; item i (i < F food, else poison) that
+ *     has been eaten c times lies at (u(x0), u(x1)) of counter (256 c + i, r, generation,
+ *     EVO_TAG_WORLD_ITEM); u(x) = (2 (x >> 9) + 1) 2^-24.
+ *     Observation: own velocity (2), offset (other - own) to the nearest food, to the nearest poison,
+ *     to the nearest other agent (2 each); nearest by d2 = fl(fl(dx dx) + fl(dy dy)), lowest index
+ *     among equals.  Action = the two policy outputs clipped to [-1, 1].
+ *     Step, per axis, every operation rounded to binary32 on its own:
+ *       v' = clip(fl(fl(drag v) + fl(thrust a)), -vmax, vmax);  p' = fl(p + fl(dt v'));
+ *       p' < 0: p' = 0, v' = 0;  p' > 1: p' = 1, v' = 0.
+ *     Every item (where it lay at the start of the step) with d2(p', item) <= fl(radius radius) is
+ *     touched: +1 (food) or -1 (poison) to every agent that touches it; a touched item has been eaten
+ *     once more from the next step on.  `steps` launches of one kernel (agents of a world depend on
+ *     each other's positions every step); work_dev holds the worlds' state.
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
-  int32_t n_rollouts;          /* CARTPOLE: roll-outs per member (1..64)                     */
+  int32_t n_rollouts;          /* CARTPOLE: roll-outs per member (1..64); FORAGE: worlds     */
   int32_t B;                   /* CLASSIFY / REGRESS: samples per member                     */
   int32_t P;                   /* SPHERE: parameters per member                              */
-  uint64_t reset_seed;         /* CARTPOLE                                                   */
-  uint32_t generation;         /* CARTPOLE: counter word t of the reset stream               */
+  uint64_t reset_seed;         /* CARTPOLE, FORAGE                                           */
+  uint32_t generation;         /* CARTPOLE, FORAGE: counter word t of the reset stream       */
   int32_t seq_in;              /* SEQ2SEQ: tokens per query                                  */
   const float* obs_dev;        /* CLASSIFY / REGRESS: observations, see pop_forward          */
   int64_t obs_member_stride;
   const void* target_dev;      /* labels / targets / x_star, see above                       */
-  float cp[8];                 /* CARTPOLE constants                                         */
+  float cp[8];                 /* CARTPOLE / FORAGE constants                                */
   float init_scale;            /* CARTPOLE: scale of the reset normals                       */
   int32_t seq_out;             /* SEQ2SEQ: tokens per answer                                 */
   void* work_dev;              /* workspace of rollout_workspace_bytes(...) bytes, or NULL if 0 */
-  const uint32_t* generation_dev; /* CARTPOLE: if not NULL, t is read from this device word at run time
+  const uint32_t* generation_dev; /* CARTPOLE, FORAGE: if not NULL, t is read from this device word at run time
                                      (see pgpe_device_generation) instead of `generation`            */
 } task_desc;
 
@@ -288,6 +309,18 @@ int evo_centered_rank(const float* fitness_dev, int32_t pop, uint32_t* rank_dev,
  * pgpe_tell_stored from that fp32 population.  The pending ask stays pending. */
 int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev, float* gsigma_dev,
                        const float* params_dev, void* stream);
+/* One step of every world of a FORAGE task from a given state with given actions (the policy is
+ * bypassed): pos_dev, vel_dev, action_dev [worlds][pop][2] fp32, counts_dev [worlds][F+Q] (times each
+ * item was eaten) -> obs_dev [worlds][pop][8], next_pos_dev, next_vel_dev, reward_dev [worlds][pop]
+ * (int32, this step's reward), hit_dev [worlds][F+Q] (1 = touched in this step).  Reads td->cp,
+ * n_rollouts, reset_seed and generation. */
+int evo_forage_step(const task_desc* td, int32_t pop, const float* pos_dev, const float* vel_dev,
+                    const uint32_t* counts_dev, const float* action_dev, float* obs_dev, float* next_pos_dev,
+                    float* next_vel_dev, int32_t* reward_dev, uint32_t* hit_dev, void* stream);
+/* State of a FORAGE rollout after `steps` steps: positions and velocities [worlds][pop][2], summed
+ * rewards [worlds][pop] (int32), times eaten [worlds][F+Q]; any may be NULL. */
+int evo_forage_state(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
+                     float* pos_dev, float* vel_dev, int32_t* reward_dev, uint32_t* counts_dev, void* stream);
 /* One cart-pole step for n independent (state, action) pairs: state_dev[n][4], action_dev[n]
  * -> next_dev[n][4], reward_dev[n].  Only td->cp is read. */
 int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,

@@ -44,6 +44,9 @@ _SIGNATURES = {
     "pgpe_state_bytes": (C.c_size_t, [C.c_void_p]),
     "pgpe_state_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "pgpe_state_import": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "evo_forage_step": (C.c_int, [C.POINTER(task_desc), C.c_int32] + [C.c_void_p] * 10),
+    "evo_forage_state": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32, C.c_int32]
+                         + [C.c_void_p] * 5),
     "pgpe_device_generation": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p]),
     "pgpe_sync_generation": (C.c_int, [C.c_void_p, C.c_void_p]),
     "pgpe_ask": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),

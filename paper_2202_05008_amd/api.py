@@ -12,8 +12,8 @@ from ._lib import pgpe_config, policy_desc, task_desc
 EVO_F32, EVO_BF16 = 0, 1
 EVO_ACT_NONE, EVO_ACT_TANH, EVO_ACT_RELU = 0, 1, 2
 EVO_POLICY_MLP, EVO_POLICY_CONVNET, EVO_POLICY_LSTM_SEQ2SEQ = 0, 1, 2
-EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE, EVO_TASK_SEQ2SEQ = 0, 1, 2, 3, 4
-EVO_TAG_NOISE, EVO_TAG_RESET = 0, 1
+EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE, EVO_TASK_SEQ2SEQ, EVO_TASK_FORAGE = range(6)
+EVO_TAG_NOISE, EVO_TAG_RESET, EVO_TAG_WORLD_AGENT, EVO_TAG_WORLD_ITEM = 0, 1, 2, 3
 EVO_OPT_ADAM, EVO_OPT_CLIPUP, EVO_OPT_MOMENTUM = 0, 1, 2
 
 
@@ -221,6 +221,21 @@ def evo_seq2seq_logits(td, pd, params, pop, logits):
 def evo_task_step(td, state, action, nxt, reward, n):
     _check(_lib.load().evo_task_step(C.byref(td), _ptr(state, torch.float32), _ptr(action, torch.float32),
                                      _ptr(nxt, torch.float32), _ptr(reward, torch.float32), n, _stream()))
+
+
+def evo_forage_step(td, pop, pos, vel, counts, action, obs, next_pos, next_vel, reward, hit):
+    f32, i32 = torch.float32, torch.int32
+    _check(_lib.load().evo_forage_step(C.byref(td), pop, _ptr(pos, f32), _ptr(vel, f32), _ptr(counts, i32),
+                                       _ptr(action, f32), _ptr(obs, f32), _ptr(next_pos, f32), _ptr(next_vel, f32),
+                                       _ptr(reward, i32), _ptr(hit, i32), _stream()))
+
+
+def evo_forage_state(td, pd, params, pop, steps, pos=None, vel=None, reward=None, counts=None):
+    f32, i32 = torch.float32, torch.int32
+    _check(_lib.load().evo_forage_state(C.byref(td), C.byref(pd), _ptr(params), pop, steps,
+                                        _ptr(pos, f32, allow_none=True), _ptr(vel, f32, allow_none=True),
+                                        _ptr(reward, i32, allow_none=True), _ptr(counts, i32, allow_none=True),
+                                        _stream()))
 
 
 def evo_rollout_details(td, pd, params, pop, steps, ret, final):

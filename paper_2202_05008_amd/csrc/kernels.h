@@ -53,6 +53,18 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
 int launch_cartpole_step(const float* cp, const float* state, const float* action, float* next, float* reward,
                          int n, hipStream_t s);
 
+// The shared-world task: every member is an agent of each of `worlds` worlds; one launch per step.
+// `work` holds forage_workspace_bytes(...) bytes.  The state outputs (positions and velocities
+// [worlds][pop][2], summed rewards [worlds][pop], times eaten [worlds][items]) may be null.
+int forage_supported(const MlpShape& sh, int pop, int worlds, const float* cp);
+size_t forage_workspace_bytes(int pop, int worlds, const float* cp);
+int launch_forage(const MlpShape& sh, const float* params, int pop, int worlds, int steps, const float* cp,
+                  uint64_t seed, uint32_t gen, const uint32_t* gen_dev, void* work, float* fitness, float* pos_out,
+                  float* vel_out, int32_t* reward_out, uint32_t* counts_out, hipStream_t s);
+int launch_forage_step(int pop, int worlds, const float* cp, uint64_t seed, uint32_t gen, const float* pos,
+                       const float* vel, const uint32_t* counts, const float* actions, float* obs_out, float* pos_out,
+                       float* vel_out, int32_t* reward_out, uint32_t* hit_out, hipStream_t s);
+
 // LSTM sequence-to-sequence policy on shared token strings: fitness[pop] = -mean cross-entropy of
 // the answer digits and / or logits[pop][B][La][n_out].
 int lstm_supported(int V, int H, int n_out, int Lq, int La);

@@ -126,7 +126,7 @@ int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
 
 int check_task(const task_desc* td) {
   EVO_REQUIRE(td != nullptr, EVO_ERR_ARG, "task_desc is null");
-  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_SEQ2SEQ, EVO_ERR_ARG, "task: bad kind %d",
+  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_FORAGE, EVO_ERR_ARG, "task: bad kind %d",
               td->kind);
   return EVO_OK;
 }
@@ -136,6 +136,7 @@ int check_task(const task_desc* td) {
 extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop) {
   if (check_task(td) || pop < 1) return 0;
   if (td->kind == EVO_TASK_CARTPOLE || td->kind == EVO_TASK_SEQ2SEQ) return 0;
+  if (td->kind == EVO_TASK_FORAGE) return forage_workspace_bytes(pop, td->n_rollouts, td->cp);
   if (td->kind != EVO_TASK_SPHERE && check_policy(pd)) return 0;
   return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
 }
@@ -159,6 +160,31 @@ static int seq2seq_impl(const task_desc* td, const policy_desc* pd, const void* 
                              fitness_dev, logits_dev, as_stream(stream));
 }
 
+// The shared-world task: fitness and / or the state after the last step.
+static int forage_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
+                       float* fitness_dev, float* pos_dev, float* vel_dev, int32_t* reward_dev, uint32_t* counts_dev,
+                       void* stream) {
+  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_FORAGE, EVO_ERR_ARG, "forage: needs an EVO_TASK_FORAGE task");
+  int rc = check_policy(pd);
+  if (rc) return rc;
+  EVO_REQUIRE(pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
+              "forage: needs an fp32 MLP policy");
+  EVO_REQUIRE(params_dev != nullptr && aligned16(params_dev), EVO_ERR_ARG,
+              "forage: params_dev must be a 16-byte aligned device pointer");
+  EVO_REQUIRE(pop >= 2 && pop <= 65535, EVO_ERR_ARG, "forage: pop must be in [2,65535] (got %d)", pop);
+  EVO_REQUIRE(steps >= 1 && steps <= (1 << 20), EVO_ERR_ARG, "forage: steps must be in [1, 2^20]");
+  EVO_REQUIRE(td->work_dev != nullptr && aligned16(td->work_dev), EVO_ERR_ARG,
+              "forage: work_dev must hold rollout_workspace_bytes() bytes, 16-byte aligned");
+  MlpShape sh;
+  rc = mlp_shape(pd, &sh);
+  if (rc) return rc;
+  rc = forage_supported(sh, pop, td->n_rollouts, td->cp);
+  if (rc) return rc;
+  return launch_forage(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp, td->reset_seed,
+                       td->generation, td->generation_dev, td->work_dev, fitness_dev, pos_dev, vel_dev, reward_dev,
+                       counts_dev, as_stream(stream));
+}
+
 static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                         int32_t steps, float* fitness_dev, float* ret_dev, float* final_dev, void* stream) {
   int rc = check_task(td);
@@ -176,6 +202,10 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     EVO_REQUIRE(td->work_dev != nullptr, EVO_ERR_ARG, "sphere: work_dev is null but rollout_workspace_bytes() > 0");
     return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P,
                          static_cast<float*>(td->work_dev), fitness_dev, s);
+  }
+  if (td->kind == EVO_TASK_FORAGE) {
+    EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
+    return forage_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, nullptr, stream);
   }
   if (td->kind == EVO_TASK_SEQ2SEQ) {
     EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
@@ -268,6 +298,32 @@ extern "C" int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, co
   EVO_REQUIRE(pop >= 1 && pop <= 65535, EVO_ERR_ARG, "evo_seq2seq_logits: pop must be in [1,65535] (got %d)", pop);
   EVO_REQUIRE(aligned16(params_dev), EVO_ERR_ARG, "evo_seq2seq_logits: params_dev must be 16-byte aligned");
   return seq2seq_impl(td, pd, params_dev, pop, nullptr, logits_dev, stream);
+}
+
+extern "C" int evo_forage_state(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                                int32_t steps, float* pos_dev, float* vel_dev, int32_t* reward_dev,
+                                uint32_t* counts_dev, void* stream) {
+  EVO_REQUIRE(pos_dev || vel_dev || reward_dev || counts_dev, EVO_ERR_ARG, "evo_forage_state: no output requested");
+  return forage_impl(td, pd, params_dev, pop, steps, nullptr, pos_dev, vel_dev, reward_dev, counts_dev, stream);
+}
+
+extern "C" int evo_forage_step(const task_desc* td, int32_t pop, const float* pos_dev, const float* vel_dev,
+                               const uint32_t* counts_dev, const float* action_dev, float* obs_dev, float* next_pos_dev,
+                               float* next_vel_dev, int32_t* reward_dev, uint32_t* hit_dev, void* stream) {
+  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_FORAGE, EVO_ERR_ARG, "evo_forage_step: needs an EVO_TASK_FORAGE task");
+  EVO_REQUIRE(pos_dev && vel_dev && counts_dev && action_dev && obs_dev && next_pos_dev && next_vel_dev &&
+                  reward_dev && hit_dev,
+              EVO_ERR_ARG, "evo_forage_step: null device pointer");
+  EVO_REQUIRE(aligned16(obs_dev) && aligned16(pos_dev) && aligned16(vel_dev) && aligned16(action_dev) &&
+                  aligned16(next_pos_dev) && aligned16(next_vel_dev),
+              EVO_ERR_ARG, "evo_forage_step: device pointers must be 16-byte aligned");
+  EVO_REQUIRE(pop >= 2 && pop <= 65535, EVO_ERR_ARG, "evo_forage_step: pop must be in [2,65535] (got %d)", pop);
+  MlpShape any;
+  any.n_layers = 3, any.dims[0] = 8, any.dims[1] = any.dims[2] = 16, any.dims[3] = 2;
+  int rc = forage_supported(any, pop, td->n_rollouts, td->cp);
+  if (rc) return rc;
+  return launch_forage_step(pop, td->n_rollouts, td->cp, td->reset_seed, td->generation, pos_dev, vel_dev, counts_dev,
+                            action_dev, obs_dev, next_pos_dev, next_vel_dev, reward_dev, hit_dev, as_stream(stream));
 }
 
 extern "C" int evo_task_step(const task_desc* td, const float* state_dev, const float* action_dev, float* next_dev,

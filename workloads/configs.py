@@ -24,6 +24,12 @@ def lstm_seq2seq_param_count(V: int = 12, H: int = 128, n_out: int = 10) -> int:
     return 2 * (V * 4 * H + H * 4 * H + 4 * H) + H * n_out + n_out
 
 
+def world_dict(world: Tuple[float, ...]) -> dict:
+    """The shared world's constants by name (the order of WorkloadConfig.world and of task_desc.cp)."""
+    dt, thrust, drag, vmax, radius, n_food, n_poison = world
+    return dict(dt=dt, thrust=thrust, drag=drag, vmax=vmax, radius=radius, n_food=int(n_food), n_poison=int(n_poison))
+
+
 def convnet_param_count(c1: int = 8, c2: int = 16, n_cls: int = 10, hw: int = 28) -> int:
     feat = (hw // 4) * (hw // 4) * c2
     return 9 * 1 * c1 + c1 + 9 * c1 * c2 + c2 + feat * n_cls + n_cls
