@@ -24,8 +24,11 @@ namespace evo {
 constexpr uint32_t kTagAgent = EVO_TAG_WORLD_AGENT;  // Philox streams of the start positions and of the items
 constexpr uint32_t kTagItem = EVO_TAG_WORLD_ITEM;
 constexpr int kObs = 8;
-constexpr int kAgentsPerBlock = 16;
+constexpr int kLanesPerAgent = 8;
+constexpr int kAgentsPerBlock = 64 / kLanesPerAgent;  // a wave; the workgroup's waves are worlds
 constexpr int kWorldsPerBlock = 4;
+
+__host__ __device__ constexpr int pad_to(int n, int m) { return (n + m - 1) / m * m; }
 
 struct WorldConst {
   float dt, thrust, drag, vmax, r2;
@@ -54,6 +57,33 @@ struct StepArgs {
   float* obs_out;              // test hook: [worlds][pop][8]
 };
 
+// Value of the partner lane in the three butterfly stages that cover an agent's eight lanes, as
+// data-parallel-primitive moves (register to register, no trip through LDS): stage 0 swaps
+// neighbours, stage 1 swaps pairs (both quad permutations), stage 2 mirrors the eight lanes, which
+// pairs each lane of one quad with a lane of the other.
+template <int STAGE>
+__device__ __forceinline__ int partner_bits(int x) {
+  constexpr int ctrl = STAGE == 0 ? 0xB1 : STAGE == 1 ? 0x4E : 0x141;  // quad_perm 1,0,3,2 / 2,3,0,1 / row_half_mirror
+  return __builtin_amdgcn_update_dpp(x, x, ctrl, 0xF, 0xF, false);
+}
+template <int STAGE>
+__device__ __forceinline__ float partner(float x) {
+  return __int_as_float(partner_bits<STAGE>(__float_as_int(x)));
+}
+static_assert(kLanesPerAgent == 8, "the butterfly below covers eight lanes");
+
+// Sum over an agent's lanes, left in every one of them.
+__device__ __forceinline__ float agent_sum(float x) {
+  x += partner<0>(x);
+  x += partner<1>(x);
+  return x + partner<2>(x);
+}
+__device__ __forceinline__ int agent_sum(int x) {
+  x += partner_bits<0>(x);
+  x += partner_bits<1>(x);
+  return x + partner_bits<2>(x);
+}
+
 // The task's distance: products and sum rounded one by one.
 __device__ __forceinline__ float dist2(float dx, float dy) {
 #pragma clang fp contract(off)
@@ -62,30 +92,58 @@ __device__ __forceinline__ float dist2(float dx, float dy) {
   return xx + yy;
 }
 
+// Nearest candidate so far: distance and index (the offset is read back from the index at the end).
 struct Nearest {
-  float d2, dx, dy;
+  float d2;
   int idx;
 };
 
-__device__ __forceinline__ void nearest_init(Nearest& n) {
-  n.d2 = __builtin_inff(), n.dx = 0.f, n.dy = 0.f, n.idx = 0x7fffffff;
-}
-
 // Candidates arrive in increasing index within a lane: strict "<" keeps the lowest index.
-__device__ __forceinline__ void nearest_offer(Nearest& n, float2 p, float2 o, int idx) {
-  const float dx = o.x - p.x, dy = o.y - p.y;
-  const float d2 = dist2(dx, dy);
-  if (d2 < n.d2) n.d2 = d2, n.dx = dx, n.dy = dy, n.idx = idx;
+template <bool CHECK>
+__device__ __forceinline__ void nearest_offer(Nearest& n, float2 p, float ox, float oy, int idx, int self) {
+  const float d2 = dist2(ox - p.x, oy - p.y);
+  bool take = d2 < n.d2;
+  if (CHECK) take = take && idx != self;
+  n.d2 = take ? d2 : n.d2;
+  n.idx = take ? idx : n.idx;
 }
 
-// Merge over the four lanes of an agent: smaller distance, then lower index.
-__device__ __forceinline__ void nearest_quad(Nearest& n) {
+// 64 candidates: four chunks of 2 per lane and 8 lanes.
+__device__ __forceinline__ void load_scan64(float4 (&c)[4], const float2* s, int base, int q) {
 #pragma unroll
-  for (int m = 1; m <= 2; m <<= 1) {
-    const float od = __shfl_xor(n.d2, m), ox = __shfl_xor(n.dx, m), oy = __shfl_xor(n.dy, m);
-    const int oi = __shfl_xor(n.idx, m);
-    if (od < n.d2 || (od == n.d2 && oi < n.idx)) n.d2 = od, n.dx = ox, n.dy = oy, n.idx = oi;
+  for (int k = 0; k < 4; ++k) c[k] = *reinterpret_cast<const float4*>(s + base + k * 2 * kLanesPerAgent + 2 * q);
+}
+
+template <bool CHECK>
+__device__ __forceinline__ void nearest_scan64(Nearest& n, float2 p, const float4 (&c)[4], int base, int q, int self) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = base + k * 2 * kLanesPerAgent + 2 * q;
+    nearest_offer<CHECK>(n, p, c[k].x, c[k].y, i, self);
+    nearest_offer<CHECK>(n, p, c[k].z, c[k].w, i + 1, self);
   }
+}
+
+// One chunk of 16 candidates (the item lists are short).
+__device__ __forceinline__ void nearest_scan16(Nearest& n, float2 p, const float2* s, int base, int q) {
+  const float4 c = *reinterpret_cast<const float4*>(s + base + 2 * q);
+  nearest_offer<false>(n, p, c.x, c.y, base + 2 * q, -1);
+  nearest_offer<false>(n, p, c.z, c.w, base + 2 * q + 1, -1);
+}
+
+// Merge over the lanes of an agent (smaller distance, then lower index) and read the offset back.
+__device__ __forceinline__ float2 nearest_finish(Nearest n, float2 p, const float2* s, int limit) {
+  auto merge = [&](float od, int oi) {
+    const bool take = od < n.d2 || (od == n.d2 && oi < n.idx);
+    n.d2 = take ? od : n.d2;
+    n.idx = take ? oi : n.idx;
+  };
+  merge(partner<0>(n.d2), partner_bits<0>(n.idx));
+  merge(partner<1>(n.d2), partner_bits<1>(n.idx));
+  merge(partner<2>(n.d2), partner_bits<2>(n.idx));
+  if (n.idx >= limit) return make_float2(0.f, 0.f);  // nothing comparable (non-finite positions)
+  const float2 o = s[n.idx];
+  return make_float2(o.x - p.x, o.y - p.y);
 }
 
 __device__ __forceinline__ float tanh_hw(float x) {
@@ -99,67 +157,97 @@ __device__ __forceinline__ float activate(float x, int act) {
   return x;
 }
 
-// One dense layer, a quarter of its HO outputs per lane: acc[u] = b[c0 + u] + sum_i in[i] W[i][c0 + u].
-template <int HI, int HO>
-__device__ __forceinline__ void dense_quarter(const float* __restrict__ W, const float* __restrict__ b, int c0,
-                                              const float (&in)[HI], float (&acc)[HO / 4]) {
-  constexpr int HQ = HO / 4;
-#pragma unroll
-  for (int u = 0; u < HQ; u += 2) {
-    const float2 bb = *reinterpret_cast<const float2*>(b + c0 + u);
-    acc[u] = bb.x, acc[u + 1] = bb.y;
-  }
-#pragma unroll 8
-  for (int i = 0; i < HI; ++i) {
-#pragma unroll
-    for (int u = 0; u < HQ; u += 2) {
-      const float2 w = *reinterpret_cast<const float2*>(W + i * HO + c0 + u);
-      acc[u] = fmaf(in[i], w.x, acc[u]);
-      acc[u + 1] = fmaf(in[i], w.y, acc[u + 1]);
-    }
-  }
-}
-
-// All HO activations of a layer to every lane of the agent's four.
-template <int HO>
-__device__ __forceinline__ void gather_quad(const float (&mine)[HO / 4], int lane, float (&full)[HO]) {
-  constexpr int HQ = HO / 4;
-#pragma unroll
-  for (int s = 0; s < 4; ++s)
-#pragma unroll
-    for (int u = 0; u < HQ; ++u) full[s * HQ + u] = __shfl(mine[u], (lane & ~3) | s);
-}
-
-// The policy of dims (8, H, H, 2) for one agent; every lane of the four returns both outputs.
+// A lane's slice of the policy's weights (columns c0 .. c0 + HQ - 1 of every layer, rows c0 .. of the
+// last one), loaded at the start of the kernel so that the round trip to L2 runs under the scans.
 template <int H>
-__device__ __forceinline__ float2 policy_forward(const float* __restrict__ th, const int (&act)[3], int lane,
-                                                 const float (&obs)[kObs]) {
-  constexpr int HQ = H / 4;
-  const int q = lane & 3, c0 = q * HQ;
+struct PolicySlice {
+  static constexpr int HQ = H / kLanesPerAgent;
+  static constexpr int kRows2 = H <= 32 ? H : 32;  // rows of W2 held here; the rest is read when it is used
+  float w1[kObs][HQ], b1[HQ], w2[kRows2][HQ], b2[HQ], w3[HQ][2], b3[2];
+  const float* rest;  // &W2[kRows2][c0]
+};
+
+template <int H>
+__device__ __forceinline__ void policy_load(const float* __restrict__ th, int q, PolicySlice<H>& s) {
+  constexpr int HQ = PolicySlice<H>::HQ;
+  const int c0 = q * HQ;
   const float* W1 = th;
   const float* b1 = W1 + kObs * H;
   const float* W2 = b1 + H;
   const float* b2 = W2 + H * H;
   const float* W3 = b2 + H;
   const float* b3 = W3 + H * 2;
+  auto row = [&](const float* src, float (&dst)[HQ]) {
+#pragma unroll
+    for (int u = 0; u < HQ; u += 2) {
+      const float2 w = *reinterpret_cast<const float2*>(src + c0 + u);
+      dst[u] = w.x, dst[u + 1] = w.y;
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < kObs; ++i) row(W1 + i * H, s.w1[i]);
+  row(b1, s.b1);
+#pragma unroll
+  for (int i = 0; i < PolicySlice<H>::kRows2; ++i) row(W2 + i * H, s.w2[i]);
+  s.rest = W2 + PolicySlice<H>::kRows2 * H + c0;
+  row(b2, s.b2);
+#pragma unroll
+  for (int u = 0; u < HQ; ++u) {
+    const float2 w = *reinterpret_cast<const float2*>(W3 + (c0 + u) * 2);
+    s.w3[u][0] = w.x, s.w3[u][1] = w.y;
+  }
+  s.b3[0] = b3[0], s.b3[1] = b3[1];
+}
+
+// All H activations of a layer to every lane of the agent.
+template <int H>
+__device__ __forceinline__ void gather_agent(const float (&mine)[H / kLanesPerAgent], int lane, float (&full)[H]) {
+  constexpr int HQ = H / kLanesPerAgent;
+#pragma unroll
+  for (int s = 0; s < kLanesPerAgent; ++s)
+#pragma unroll
+    for (int u = 0; u < HQ; ++u) full[s * HQ + u] = __shfl(mine[u], (lane & ~(kLanesPerAgent - 1)) | s);
+}
+
+// The policy of dims (8, H, H, 2) for one agent; every lane of the agent returns both outputs.
+template <int H>
+__device__ __forceinline__ float2 policy_forward(const PolicySlice<H>& s, const int (&act)[3], int lane,
+                                                 const float (&obs)[kObs]) {
+  constexpr int HQ = PolicySlice<H>::HQ;
   float part[HQ], full[H];
-  dense_quarter<kObs, H>(W1, b1, c0, obs, part);
+#pragma unroll
+  for (int u = 0; u < HQ; ++u) part[u] = s.b1[u];
+#pragma unroll
+  for (int i = 0; i < kObs; ++i)
+#pragma unroll
+    for (int u = 0; u < HQ; ++u) part[u] = fmaf(obs[i], s.w1[i][u], part[u]);
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = activate(part[u], act[0]);
-  gather_quad<H>(part, lane, full);
-  dense_quarter<H, H>(W2, b2, c0, full, part);
+  gather_agent<H>(part, lane, full);
+#pragma unroll
+  for (int u = 0; u < HQ; ++u) part[u] = s.b2[u];
+#pragma unroll
+  for (int i = 0; i < PolicySlice<H>::kRows2; ++i)
+#pragma unroll
+    for (int u = 0; u < HQ; ++u) part[u] = fmaf(full[i], s.w2[i][u], part[u]);
+#pragma unroll 16
+  for (int i = PolicySlice<H>::kRows2; i < H; ++i)
+#pragma unroll
+    for (int u = 0; u < HQ; u += 2) {
+      const float2 w = *reinterpret_cast<const float2*>(s.rest + (i - PolicySlice<H>::kRows2) * H + u);
+      part[u] = fmaf(full[i], w.x, part[u]);
+      part[u + 1] = fmaf(full[i], w.y, part[u + 1]);
+    }
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = activate(part[u], act[1]);
   float o0 = 0.f, o1 = 0.f;
 #pragma unroll
   for (int u = 0; u < HQ; ++u) {
-    const float2 w = *reinterpret_cast<const float2*>(W3 + (c0 + u) * 2);
-    o0 = fmaf(part[u], w.x, o0);
-    o1 = fmaf(part[u], w.y, o1);
+    o0 = fmaf(part[u], s.w3[u][0], o0);
+    o1 = fmaf(part[u], s.w3[u][1], o1);
   }
-  o0 += __shfl_xor(o0, 1), o1 += __shfl_xor(o1, 1);
-  o0 += __shfl_xor(o0, 2), o1 += __shfl_xor(o1, 2);
-  return make_float2(activate(o0 + b3[0], act[2]), activate(o1 + b3[1], act[2]));
+  o0 = agent_sum(o0), o1 = agent_sum(o1);
+  return make_float2(activate(o0 + s.b3[0], act[2]), activate(o1 + s.b3[1], act[2]));
 }
 
 // One axis of the motion: new velocity and position, each operation rounded on its own.
@@ -177,36 +265,75 @@ __device__ __forceinline__ void move_axis(const WorldConst& c, float a, float& p
   p = np, v = nv;
 }
 
+// Touches of one list of items (16 slots per chunk); returns how many this lane found.
+__device__ __forceinline__ int touch_scan(const WorldConst& c, float2 p, const float2* s, int padded, int q,
+                                          uint32_t* hits) {
+  int found = 0;
+  for (int base = 0; base < padded; base += 2 * kLanesPerAgent) {
+    const float4 it = *reinterpret_cast<const float4*>(s + base + 2 * q);
+    if (dist2(it.x - p.x, it.y - p.y) <= c.r2) ++found, atomicOr(hits + base + 2 * q, 1u);
+    if (dist2(it.z - p.x, it.w - p.y) <= c.r2) ++found, atomicOr(hits + base + 2 * q + 1, 1u);
+  }
+  return found;
+}
+
 template <int H>
-__global__ __launch_bounds__(kAgentsPerBlock * 4 * kWorldsPerBlock) void world_step_kernel(StepArgs a) {
-  extern __shared__ float2 lds[];
+__global__ __launch_bounds__(64 * kWorldsPerBlock) void world_step_kernel(StepArgs a) {
+  extern __shared__ float4 lds4[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int q = lane & 3;
-  const int agent = blockIdx.x * kAgentsPerBlock + (lane >> 2);
+  const int q = lane & (kLanesPerAgent - 1);
+  const int agent0 = blockIdx.x * kAgentsPerBlock;
+  const int agent = agent0 + lane / kLanesPerAgent;
   const int world = blockIdx.y * kWorldsPerBlock + wave;
   const bool world_live = world < a.worlds;
   const bool live = world_live && agent < a.pop;
-  const int n_items = a.c.n_items;
-  float2* s_pos = lds + wave * a.pop;                               // this wave's world: every agent
-  float2* s_item = lds + kWorldsPerBlock * a.pop + wave * n_items;  // and every item
+  const int n_food = a.c.n_food, n_items = a.c.n_items;
+  const int pop_pad = pad_to(a.pop, 64), food_pad = pad_to(n_food, 16), poison_pad = pad_to(n_items - n_food, 16);
+  // this wave's world: every agent, the food, the poison; unused slots lie infinitely far away
+  float2* s_pos = reinterpret_cast<float2*>(lds4) + wave * (pop_pad + food_pad + poison_pad);
+  float2* s_food = s_pos + pop_pad;
+  float2* s_poison = s_food + food_pad;
   if (a.gen_dev) a.gen = *a.gen_dev;
+  const float inf = __builtin_inff();
+
+  // the policy's weights first: their round trip to L2 runs under everything up to the forward pass
+  PolicySlice<H> weights;
+  if (live && !a.actions_in) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
 
   if (world_live) {
     const float2* pin = a.pos_in + static_cast<size_t>(world) * a.pop;
-    for (int j = lane; j < a.pop; j += 64) s_pos[j] = pin[j];
-    for (int i = lane; i < n_items; i += 64) {
-      const size_t o = static_cast<size_t>(world) * n_items + i;
-      uint32_t cnt = a.counts_in[o];
-      if (a.hits_prev) cnt += a.hits_prev[o];
-      if (blockIdx.x == 0) {  // one workgroup per world keeps the item book
-        if (a.counts_out) a.counts_out[o] = cnt;
-        if (a.hits_clear) a.hits_clear[o] = 0u;
-      }
-      const u32x4 w = philox4x32_10(256u * cnt + static_cast<uint32_t>(i), static_cast<uint32_t>(world), a.gen,
-                                    kTagItem, a.key0, a.key1);
-      s_item[i] = make_float2(unit_open(w.x), unit_open(w.y));
+    float2 t[16];  // the first 1024 positions: sixteen loads in flight per lane, stored after the items
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int j = k * 64 + lane;
+      t[k] = pin[min(j, a.pop - 1)];  // in bounds; slots past the last agent are overwritten below
+      if (j >= a.pop) t[k] = make_float2(inf, inf);
     }
+    for (int slot = lane; slot < food_pad + poison_pad; slot += 64) {
+      const bool is_food = slot < food_pad;
+      const int i = is_food ? slot : n_food + slot - food_pad;
+      float2 where = make_float2(inf, inf);
+      if (i < (is_food ? n_food : n_items)) {
+        const size_t o = static_cast<size_t>(world) * n_items + i;
+        uint32_t cnt = a.counts_in[o];
+        if (a.hits_prev) cnt += a.hits_prev[o];
+        if (blockIdx.x == 0) {  // one workgroup per world keeps the item book
+          if (a.counts_out) a.counts_out[o] = cnt;
+          if (a.hits_clear) a.hits_clear[o] = 0u;
+        }
+        const u32x4 w = philox4x32_10(256u * cnt + static_cast<uint32_t>(i), static_cast<uint32_t>(world), a.gen,
+                                      kTagItem, a.key0, a.key1);
+        where = make_float2(unit_open(w.x), unit_open(w.y));
+      }
+      s_food[slot] = where;  // the poison list follows the food list
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int j = k * 64 + lane;
+      if (j < pop_pad) s_pos[j] = t[k];
+    }
+    for (int j = 1024 + lane; j < pop_pad; j += 64) s_pos[j] = j < a.pop ? pin[j] : make_float2(inf, inf);
   }
   __syncthreads();
   if (!live) return;  // no barrier below this line
@@ -215,39 +342,48 @@ __global__ __launch_bounds__(kAgentsPerBlock * 4 * kWorldsPerBlock) void world_s
   float2 p = s_pos[agent];
   float2 v = a.vel_in[me];
 
-  Nearest food, poison, other;
-  nearest_init(food), nearest_init(poison), nearest_init(other);
-  for (int i = q; i < a.c.n_food; i += 4) nearest_offer(food, p, s_item[i], i);
-  for (int i = a.c.n_food + q; i < n_items; i += 4) nearest_offer(poison, p, s_item[i], i);
-  for (int j = q; j < a.pop; j += 4)
-    if (j != agent) nearest_offer(other, p, s_pos[j], j);
-  nearest_quad(food), nearest_quad(poison), nearest_quad(other);
+  Nearest food{inf, 0x7fffffff}, poison{inf, 0x7fffffff}, other{inf, 0x7fffffff};
+  for (int base = 0; base < food_pad; base += 16) nearest_scan16(food, p, s_food, base, q);
+  for (int base = 0; base < poison_pad; base += 16) nearest_scan16(poison, p, s_poison, base, q);
+  const int own_block = agent0 & ~63;  // the only 64 candidates that hold agents of this wave
+  // two sets of 64 candidates take turns: one is on its way from LDS while the other is judged
+  auto judge = [&](const float4 (&c)[4], int base) {
+    if (base == own_block)
+      nearest_scan64<true>(other, p, c, base, q, agent);
+    else
+      nearest_scan64<false>(other, p, c, base, q, agent);
+  };
+  float4 ping[4], pong[4];
+  load_scan64(ping, s_pos, 0, q);
+  for (int base = 0; base < pop_pad; base += 128) {
+    const bool second = base + 64 < pop_pad;
+    if (second) load_scan64(pong, s_pos, base + 64, q);
+    judge(ping, base);
+    if (base + 128 < pop_pad) load_scan64(ping, s_pos, base + 128, q);
+    if (second) judge(pong, base + 64);
+  }
+  const float2 f = nearest_finish(food, p, s_food, food_pad);
+  const float2 g = nearest_finish(poison, p, s_poison, poison_pad);
+  const float2 o = nearest_finish(other, p, s_pos, pop_pad);
 
-  const float obs[kObs] = {v.x, v.y, food.dx, food.dy, poison.dx, poison.dy, other.dx, other.dy};
+  const float obs[kObs] = {v.x, v.y, f.x, f.y, g.x, g.y, o.x, o.y};
   if (a.obs_out && q == 0) {
-    float4* o = reinterpret_cast<float4*>(a.obs_out + me * kObs);
-    o[0] = make_float4(obs[0], obs[1], obs[2], obs[3]);
-    o[1] = make_float4(obs[4], obs[5], obs[6], obs[7]);
+    float4* dst = reinterpret_cast<float4*>(a.obs_out + me * kObs);
+    dst[0] = make_float4(obs[0], obs[1], obs[2], obs[3]);
+    dst[1] = make_float4(obs[4], obs[5], obs[6], obs[7]);
   }
   float2 action;
   if (a.actions_in)
     action = a.actions_in[me];
   else
-    action = policy_forward<H>(a.params + static_cast<size_t>(agent) * a.P, a.act, lane, obs);
+    action = policy_forward<H>(weights, a.act, lane, obs);
 
   move_axis(a.c, action.x, p.x, v.x);
   move_axis(a.c, action.y, p.y, v.y);
 
-  int reward = 0;
-  for (int i = q; i < n_items; i += 4) {
-    const float2 it = s_item[i];
-    if (dist2(it.x - p.x, it.y - p.y) <= a.c.r2) {
-      reward += i < a.c.n_food ? 1 : -1;
-      atomicOr(a.hits_cur + static_cast<size_t>(world) * n_items + i, 1u);
-    }
-  }
-  reward += __shfl_xor(reward, 1);
-  reward += __shfl_xor(reward, 2);
+  uint32_t* hits = a.hits_cur + static_cast<size_t>(world) * n_items;
+  int reward = touch_scan(a.c, p, s_food, food_pad, q, hits) - touch_scan(a.c, p, s_poison, poison_pad, q, hits + n_food);
+  reward = agent_sum(reward);
   if (q == 0) {
     a.pos_out[me] = p;
     a.vel_out[me] = v;
@@ -317,8 +453,9 @@ static Layout carve(int pop, int worlds, int n_items) {
   return l;
 }
 
-static size_t step_lds_bytes(int pop, int n_items) {
-  return static_cast<size_t>(kWorldsPerBlock) * (pop + n_items) * sizeof(float2);
+static size_t step_lds_bytes(int pop, int n_food, int n_items) {
+  return static_cast<size_t>(kWorldsPerBlock) * (pad_to(pop, 64) + pad_to(n_food, 16) + pad_to(n_items - n_food, 16)) *
+         sizeof(float2);
 }
 
 static int fill_const(const float* cp, WorldConst* c) {
@@ -339,8 +476,8 @@ static int fill_const(const float* cp, WorldConst* c) {
 template <int H>
 static int launch_step(const StepArgs& a, hipStream_t s) {
   const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
-  hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(kAgentsPerBlock * 4 * kWorldsPerBlock),
-                     step_lds_bytes(a.pop, a.c.n_items), s, a);
+  hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(64 * kWorldsPerBlock),
+                     step_lds_bytes(a.pop, a.c.n_food, a.c.n_items), s, a);
   return check_launch("world_step_kernel");
 }
 
@@ -362,9 +499,9 @@ int forage_supported(const MlpShape& sh, int pop, int worlds, const float* cp) {
               EVO_ERR_UNSUPPORTED, "forage: the policy must be an MLP of dims {8, H, H, 2} with H = 16, 32 or 64");
   EVO_REQUIRE(pop >= 2, EVO_ERR_ARG, "forage: a world needs at least two agents (got pop = %d)", pop);
   EVO_REQUIRE(worlds >= 1 && worlds <= 4096, EVO_ERR_ARG, "forage: n_rollouts (worlds) must be in [1, 4096]");
-  EVO_REQUIRE(step_lds_bytes(pop, c.n_items) <= 65536, EVO_ERR_UNSUPPORTED,
-              "forage: at most %d agents per world (positions of four worlds are staged in 64 KB of LDS)",
-              65536 / (kWorldsPerBlock * 8) - c.n_items);
+  EVO_REQUIRE(step_lds_bytes(pop, c.n_food, c.n_items) <= 65536, EVO_ERR_UNSUPPORTED,
+              "forage: at most about %d agents per world (positions of four worlds are staged in 64 KB of LDS)",
+              65536 / (kWorldsPerBlock * 8) - c.n_items - 32);
   return EVO_OK;
 }
 
