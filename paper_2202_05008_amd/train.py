@@ -19,6 +19,9 @@ from . import api as evo
 from .trainer import Trainer
 
 
+FORAGE_TEST_POP = 64      # copies of the centre that share the held-out worlds when it is tested
+
+
 def _tasks(name, c, seed, dev):
     """(policy_desc, train_task(t), test_task(t)) of a named workload; inputs from workloads.generators."""
     from workloads import generators as gen
@@ -75,6 +78,18 @@ def _tasks(name, c, seed, dev):
         tds = [strings(g + 1) for g in range(16)]
         test_td = strings(1000)
         return pd, (lambda t: tds[t % len(tds)]), (lambda t: test_td)
+    if name == "forage":
+        pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+        work = {}
+
+        def world(s, t, pop):      # one workspace per population size, a fresh descriptor per generation
+            make = lambda w: evo.make_task_desc(evo.EVO_TASK_FORAGE, n_rollouts=c.n_rollouts, reset_seed=s, generation=t,
+                                                cp=tuple(c.world), work=w)
+            if pop not in work:
+                work[pop] = torch.empty(evo.rollout_workspace_bytes(make(None), pd, pop), dtype=torch.uint8, device=dev)
+            return make(work[pop])
+
+        return pd, (lambda t: world(seed, t, c.pop)), (lambda t: world(seed + 1, 1, FORAGE_TEST_POP))
     raise SystemExit("unknown workload %r" % name)
 
 
@@ -105,7 +120,8 @@ def main(argv=None):
     pg = evo.PGPE(cfg, mu0)
     pd, train_task, test_task = _tasks(args.workload, c, args.seed, dev)
     tr = Trainer(pg, pd, train_task, c.pop, steps=c.steps, seed=args.seed, test_task=test_task,
-                 test_every=args.test_every, log_path=args.log, ckpt_path=args.ckpt, save_every=args.save_every)
+                 test_every=args.test_every, log_path=args.log, ckpt_path=args.ckpt, save_every=args.save_every,
+                 test_pop=FORAGE_TEST_POP if args.workload == "forage" else 1)
     if args.resume:
         if not args.ckpt:
             raise SystemExit("--resume needs --ckpt")

@@ -30,10 +30,12 @@ class Trainer:
     seed        seed of the noise stream; generation t of a run is a function of (seed, t) alone
     log_path    JSON-lines log (appended), or None
     ckpt_path   checkpoint file written every `save_every` generations (0 = never), atomically
+    test_pop    copies of the centre that are evaluated together (a shared world needs company: the
+                test fitness is then the mean over the copies); 1 for every other task
     """
 
     def __init__(self, pgpe, policy, train_task, pop, steps=1, seed=0, test_task=None, test_every=0, log_path=None,
-                 ckpt_path=None, save_every=0):
+                 ckpt_path=None, save_every=0, test_pop=1):
         self.pgpe, self.policy, self.train_task, self.test_task = pgpe, policy, train_task, test_task
         self.pop, self.steps, self.seed = int(pop), int(steps), int(seed)
         self.test_every, self.save_every = int(test_every), int(save_every)
@@ -43,8 +45,9 @@ class Trainer:
         dev = pgpe.mu.device
         self.params = torch.empty(self.pop, pgpe.cfg.P, dtype=tdtype, device=dev)
         self.fitness = torch.empty(self.pop, dtype=torch.float32, device=dev)
-        self._center = torch.empty(1, pgpe.cfg.P, dtype=tdtype, device=dev)
-        self._center_fit = torch.empty(1, dtype=torch.float32, device=dev)
+        self.test_pop = int(test_pop)
+        self._center = torch.empty(self.test_pop, pgpe.cfg.P, dtype=tdtype, device=dev)
+        self._center_fit = torch.empty(self.test_pop, dtype=torch.float32, device=dev)
         self.history = []
 
     # ---- one generation ---------------------------------------------------------------------
@@ -78,9 +81,9 @@ class Trainer:
         """Fitness of the centre mu (no perturbation) on the test task of the current generation."""
         t = self.pgpe.generation
         td = task if task is not None else self.test_task(t)
-        self.pgpe.center(1, self._center, self.dtype)
-        api.rollout(td, self.policy, self._center, 1, self.steps, self._center_fit)
-        return float(self._center_fit[0])
+        self.pgpe.center(self.test_pop, self._center, self.dtype)
+        api.rollout(td, self.policy, self._center, self.test_pop, self.steps, self._center_fit)
+        return float(self._center_fit.mean())
 
     # ---- checkpoints ----------------------------------------------------------------------------
     def save(self, path):
