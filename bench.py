@@ -37,7 +37,7 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg4": 807734117,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4304870251,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
     "seq2seq": 876919192,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
-    "forage": None,        # launch-latency bound: 500 step kernels of a few microseconds, the weights stay in L2
+    "forage": 6944738,     # profiles/world_step_kernel_forage.md (per step launch: weights 5.8 MB + positions)
 }
 
 
