@@ -27,6 +27,7 @@ constexpr int kObs = 8;
 constexpr int kLanesPerAgent = 8;
 constexpr int kAgentsPerBlock = 64 / kLanesPerAgent;  // a wave; the workgroup's waves are worlds
 constexpr int kWorldsPerBlock = 4;
+constexpr int kStepThreads = 2 * 64 * kWorldsPerBlock;  // per world a main wave and a helper wave
 
 __host__ __device__ constexpr int pad_to(int n, int m) { return (n + m - 1) / m * m; }
 
@@ -162,7 +163,7 @@ __device__ __forceinline__ float activate(float x, int act) {
 template <int H>
 struct PolicySlice {
   static constexpr int HQ = H / kLanesPerAgent;
-  static constexpr int kRows2 = H <= 32 ? H : 32;  // rows of W2 held here; the rest is read when it is used
+  static constexpr int kRows2 = H <= 32 ? H : 8;   // rows of W2 held here; the rest is read when it is used
   float w1[kObs][HQ], b1[HQ], w2[kRows2][HQ], b2[HQ], w3[HQ][2], b3[2];
   const float* rest;  // &W2[kRows2][c0]
 };
@@ -277,93 +278,132 @@ __device__ __forceinline__ int touch_scan(const WorldConst& c, float2 p, const f
   return found;
 }
 
+// Per lane of a helper wave, for the main wave of the same world: its part of the agent scan and the
+// two item offsets, as six words (structure of arrays: word w of lane l at [w][l]).
+constexpr int kExchangeWords = 6;
+
 template <int H>
-__global__ __launch_bounds__(64 * kWorldsPerBlock) void world_step_kernel(StepArgs a) {
+__global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   extern __shared__ float4 lds4[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int slot = wave & (kWorldsPerBlock - 1);  // which of the workgroup's worlds
+  const bool helper = wave >= kWorldsPerBlock;    // waves 4..7 assist waves 0..3
   const int q = lane & (kLanesPerAgent - 1);
   const int agent0 = blockIdx.x * kAgentsPerBlock;
   const int agent = agent0 + lane / kLanesPerAgent;
-  const int world = blockIdx.y * kWorldsPerBlock + wave;
+  const int world = blockIdx.y * kWorldsPerBlock + slot;
   const bool world_live = world < a.worlds;
   const bool live = world_live && agent < a.pop;
   const int n_food = a.c.n_food, n_items = a.c.n_items;
   const int pop_pad = pad_to(a.pop, 64), food_pad = pad_to(n_food, 16), poison_pad = pad_to(n_items - n_food, 16);
-  // this wave's world: every agent, the food, the poison; unused slots lie infinitely far away
-  float2* s_pos = reinterpret_cast<float2*>(lds4) + wave * (pop_pad + food_pad + poison_pad);
+  const int region = pop_pad + food_pad + poison_pad;
+  // a world's region: every agent, the food, the poison; unused slots lie infinitely far away
+  float2* s_pos = reinterpret_cast<float2*>(lds4) + slot * region;
   float2* s_food = s_pos + pop_pad;
   float2* s_poison = s_food + food_pad;
+  float* s_xch = reinterpret_cast<float*>(reinterpret_cast<float2*>(lds4) + kWorldsPerBlock * region) +
+                 slot * kExchangeWords * 64;
   if (a.gen_dev) a.gen = *a.gen_dev;
   const float inf = __builtin_inff();
 
-  // the policy's weights first: their round trip to L2 runs under everything up to the forward pass
+  // main wave: the policy's weights first, their round trip to L2 runs under everything up to the forward pass
   PolicySlice<H> weights;
-  if (live && !a.actions_in) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
+  if (!helper && live && !a.actions_in) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
 
   if (world_live) {
     const float2* pin = a.pos_in + static_cast<size_t>(world) * a.pop;
-    float2 t[16];  // the first 1024 positions: sixteen loads in flight per lane, stored after the items
+    const int role = helper ? 1 : 0;
+    float2 t[8];  // the two waves of a world stage alternate runs of 64 positions: eight loads in flight each
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const int j = k * 64 + lane;
+    for (int k = 0; k < 8; ++k) {
+      const int j = (2 * k + role) * 64 + lane;
       t[k] = pin[min(j, a.pop - 1)];  // in bounds; slots past the last agent are overwritten below
       if (j >= a.pop) t[k] = make_float2(inf, inf);
     }
-    for (int slot = lane; slot < food_pad + poison_pad; slot += 64) {
-      const bool is_food = slot < food_pad;
-      const int i = is_food ? slot : n_food + slot - food_pad;
-      float2 where = make_float2(inf, inf);
-      if (i < (is_food ? n_food : n_items)) {
-        const size_t o = static_cast<size_t>(world) * n_items + i;
-        uint32_t cnt = a.counts_in[o];
-        if (a.hits_prev) cnt += a.hits_prev[o];
-        if (blockIdx.x == 0) {  // one workgroup per world keeps the item book
-          if (a.counts_out) a.counts_out[o] = cnt;
-          if (a.hits_clear) a.hits_clear[o] = 0u;
+    if (helper) {  // the items and their book
+      for (int sl = lane; sl < food_pad + poison_pad; sl += 64) {
+        const bool is_food = sl < food_pad;
+        const int i = is_food ? sl : n_food + sl - food_pad;
+        float2 where = make_float2(inf, inf);
+        if (i < (is_food ? n_food : n_items)) {
+          const size_t o = static_cast<size_t>(world) * n_items + i;
+          uint32_t cnt = a.counts_in[o];
+          if (a.hits_prev) cnt += a.hits_prev[o];
+          if (blockIdx.x == 0) {  // one workgroup per world keeps the item book
+            if (a.counts_out) a.counts_out[o] = cnt;
+            if (a.hits_clear) a.hits_clear[o] = 0u;
+          }
+          const u32x4 w = philox4x32_10(256u * cnt + static_cast<uint32_t>(i), static_cast<uint32_t>(world), a.gen,
+                                        kTagItem, a.key0, a.key1);
+          where = make_float2(unit_open(w.x), unit_open(w.y));
         }
-        const u32x4 w = philox4x32_10(256u * cnt + static_cast<uint32_t>(i), static_cast<uint32_t>(world), a.gen,
-                                      kTagItem, a.key0, a.key1);
-        where = make_float2(unit_open(w.x), unit_open(w.y));
+        s_food[sl] = where;  // the poison list follows the food list
       }
-      s_food[slot] = where;  // the poison list follows the food list
     }
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const int j = k * 64 + lane;
+    for (int k = 0; k < 8; ++k) {
+      const int j = (2 * k + role) * 64 + lane;
       if (j < pop_pad) s_pos[j] = t[k];
     }
-    for (int j = 1024 + lane; j < pop_pad; j += 64) s_pos[j] = j < a.pop ? pin[j] : make_float2(inf, inf);
+    for (int j = 1024 + role * 64 + lane; j < pop_pad; j += 128) s_pos[j] = j < a.pop ? pin[j] : make_float2(inf, inf);
   }
   __syncthreads();
-  if (!live) return;  // no barrier below this line
 
-  const size_t me = static_cast<size_t>(world) * a.pop + agent;
-  float2 p = s_pos[agent];
-  float2 v = a.vel_in[me];
-
-  Nearest food{inf, 0x7fffffff}, poison{inf, 0x7fffffff}, other{inf, 0x7fffffff};
-  for (int base = 0; base < food_pad; base += 16) nearest_scan16(food, p, s_food, base, q);
-  for (int base = 0; base < poison_pad; base += 16) nearest_scan16(poison, p, s_poison, base, q);
-  const int own_block = agent0 & ~63;  // the only 64 candidates that hold agents of this wave
-  // two sets of 64 candidates take turns: one is on its way from LDS while the other is judged
-  auto judge = [&](const float4 (&c)[4], int base) {
-    if (base == own_block)
-      nearest_scan64<true>(other, p, c, base, q, agent);
-    else
-      nearest_scan64<false>(other, p, c, base, q, agent);
-  };
-  float4 ping[4], pong[4];
-  load_scan64(ping, s_pos, 0, q);
-  for (int base = 0; base < pop_pad; base += 128) {
-    const bool second = base + 64 < pop_pad;
-    if (second) load_scan64(pong, s_pos, base + 64, q);
-    judge(ping, base);
-    if (base + 128 < pop_pad) load_scan64(ping, s_pos, base + 128, q);
-    if (second) judge(pong, base + 64);
+  // The agent scan is shared: the main wave takes the first blocks of 64 candidates, the helper the rest
+  // and the two item lists (about two blocks' worth of work).
+  const int blocks = pop_pad / 64;
+  const int main_blocks = min(blocks, (blocks + 2) / 2);
+  const size_t me = static_cast<size_t>(world) * a.pop + min(agent, a.pop - 1);
+  float2 p = make_float2(0.f, 0.f), v = p;
+  Nearest other{inf, 0x7fffffff};
+  float2 f = p, g = p;
+  if (live) {
+    p = s_pos[agent];
+    const int own_block = agent0 & ~63;  // the only 64 candidates that hold agents of this wave
+    // two sets of 64 candidates take turns: one is on its way from LDS while the other is judged
+    auto judge = [&](const float4 (&c)[4], int base) {
+      if (base == own_block)
+        nearest_scan64<true>(other, p, c, base, q, agent);
+      else
+        nearest_scan64<false>(other, p, c, base, q, agent);
+    };
+    const int first = helper ? main_blocks * 64 : 0, last = helper ? pop_pad : main_blocks * 64;
+    float4 ping[4], pong[4];
+    if (first < last) load_scan64(ping, s_pos, first, q);
+    for (int base = first; base < last; base += 128) {
+      const bool second = base + 64 < last;
+      if (second) load_scan64(pong, s_pos, base + 64, q);
+      judge(ping, base);
+      if (base + 128 < last) load_scan64(ping, s_pos, base + 128, q);
+      if (second) judge(pong, base + 64);
+    }
+    if (helper) {
+      Nearest food{inf, 0x7fffffff}, poison{inf, 0x7fffffff};
+      for (int base = 0; base < food_pad; base += 16) nearest_scan16(food, p, s_food, base, q);
+      for (int base = 0; base < poison_pad; base += 16) nearest_scan16(poison, p, s_poison, base, q);
+      f = nearest_finish(food, p, s_food, food_pad);
+      g = nearest_finish(poison, p, s_poison, poison_pad);
+      s_xch[0 * 64 + lane] = other.d2;
+      s_xch[1 * 64 + lane] = __int_as_float(other.idx);
+      s_xch[2 * 64 + lane] = f.x, s_xch[3 * 64 + lane] = f.y;
+      s_xch[4 * 64 + lane] = g.x, s_xch[5 * 64 + lane] = g.y;
+    } else {
+      v = a.vel_in[me];
+    }
   }
-  const float2 f = nearest_finish(food, p, s_food, food_pad);
-  const float2 g = nearest_finish(poison, p, s_poison, poison_pad);
+  __syncthreads();
+  if (helper || !live) return;  // no barrier below this line
+
+  {  // the helper's candidates all have higher indices: they win only when strictly nearer
+    const float hd = s_xch[0 * 64 + lane];
+    const int hi = __float_as_int(s_xch[1 * 64 + lane]);
+    const bool take = hd < other.d2;
+    other.d2 = take ? hd : other.d2;
+    other.idx = take ? hi : other.idx;
+    f = make_float2(s_xch[2 * 64 + lane], s_xch[3 * 64 + lane]);
+    g = make_float2(s_xch[4 * 64 + lane], s_xch[5 * 64 + lane]);
+  }
   const float2 o = nearest_finish(other, p, s_pos, pop_pad);
 
   const float obs[kObs] = {v.x, v.y, f.x, f.y, g.x, g.y, o.x, o.y};
@@ -454,8 +494,9 @@ static Layout carve(int pop, int worlds, int n_items) {
 }
 
 static size_t step_lds_bytes(int pop, int n_food, int n_items) {
-  return static_cast<size_t>(kWorldsPerBlock) * (pad_to(pop, 64) + pad_to(n_food, 16) + pad_to(n_items - n_food, 16)) *
-         sizeof(float2);
+  return static_cast<size_t>(kWorldsPerBlock) *
+         ((pad_to(pop, 64) + pad_to(n_food, 16) + pad_to(n_items - n_food, 16)) * sizeof(float2) +
+          kExchangeWords * 64 * sizeof(float));
 }
 
 static int fill_const(const float* cp, WorldConst* c) {
@@ -476,7 +517,7 @@ static int fill_const(const float* cp, WorldConst* c) {
 template <int H>
 static int launch_step(const StepArgs& a, hipStream_t s) {
   const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
-  hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(64 * kWorldsPerBlock),
+  hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(kStepThreads),
                      step_lds_bytes(a.pop, a.c.n_food, a.c.n_items), s, a);
   return check_launch("world_step_kernel");
 }
@@ -501,7 +542,7 @@ int forage_supported(const MlpShape& sh, int pop, int worlds, const float* cp) {
   EVO_REQUIRE(worlds >= 1 && worlds <= 4096, EVO_ERR_ARG, "forage: n_rollouts (worlds) must be in [1, 4096]");
   EVO_REQUIRE(step_lds_bytes(pop, c.n_food, c.n_items) <= 65536, EVO_ERR_UNSUPPORTED,
               "forage: at most about %d agents per world (positions of four worlds are staged in 64 KB of LDS)",
-              65536 / (kWorldsPerBlock * 8) - c.n_items - 32);
+              (65536 / kWorldsPerBlock - kExchangeWords * 256) / 8 - c.n_items - 32);
   return EVO_OK;
 }
 
