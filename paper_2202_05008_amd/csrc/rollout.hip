@@ -319,7 +319,7 @@ extern "C" int evo_forage_step(const task_desc* td, int32_t pop, const float* po
               EVO_ERR_ARG, "evo_forage_step: device pointers must be 16-byte aligned");
   EVO_REQUIRE(pop >= 2 && pop <= 65535, EVO_ERR_ARG, "evo_forage_step: pop must be in [2,65535] (got %d)", pop);
   MlpShape any;
-  any.n_layers = 3, any.dims[0] = 8, any.dims[1] = any.dims[2] = 16, any.dims[3] = 2;
+  any.n_layers = 3, any.dims[0] = 8, any.dims[1] = any.dims[2] = 16, any.dims[3] = 2, any.P = 450;
   int rc = forage_supported(any, pop, td->n_rollouts, td->cp);
   if (rc) return rc;
   return launch_forage_step(pop, td->n_rollouts, td->cp, td->reset_seed, td->generation, pos_dev, vel_dev, counts_dev,

@@ -7,11 +7,14 @@
 // Agents of one world see each other's positions of the current step, so a step is a grid-wide
 // dependency: one kernel launch per step, positions double-buffered in the task's workspace.
 // A launch is a few microseconds of work spread as widely as its parallelism allows:
-//   workgroup = 16 agents x 4 worlds (wave w = world 4 blockIdx.y + w, so the four waves read the
-//   same policy weights and the second to fourth find them in the vector cache);
-//   four lanes per agent: they split the nearest-neighbour scans (each takes every fourth
-//   candidate from LDS, then a four-lane reduction on (distance, index)) and the hidden units of
-//   the policy (each a quarter of a layer; the layer's activations go round by lane shuffles).
+//   workgroup = 8 agents x 4 worlds, two waves per world (main and helper; the four main waves read
+//   the same policy weights);
+//   eight lanes per agent: they split the nearest-neighbour scans (each judges two candidates per
+//   16-byte LDS read, then a three-stage reduction on (distance, index) by lane moves) and the hidden
+//   units of the policy (each an eighth of a layer; the layer's activations go round by lane shuffles);
+//   the helper wave stages half of the positions, places the items and keeps their book, scans the item
+//   lists and the upper half of the agents, leaves its results in LDS and exits; the main wave scans the
+//   lower half, merges, runs the policy, moves its agents and tests the touches.
 // Everything that decides an integer -- who is nearest, who touches an item -- is computed in
 // binary32 with each operation rounded on its own (no fused multiply-add), as the task defines it.
 #include <algorithm>
@@ -307,10 +310,7 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   if (a.gen_dev) a.gen = *a.gen_dev;
   const float inf = __builtin_inff();
 
-  // main wave: the policy's weights first, their round trip to L2 runs under everything up to the forward pass
   PolicySlice<H> weights;
-  if (!helper && live && !a.actions_in) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
-
   if (world_live) {
     const float2* pin = a.pos_in + static_cast<size_t>(world) * a.pop;
     const int role = helper ? 1 : 0;
@@ -318,9 +318,11 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int j = (2 * k + role) * 64 + lane;
-      t[k] = pin[min(j, a.pop - 1)];  // in bounds; slots past the last agent are overwritten below
-      if (j >= a.pop) t[k] = make_float2(inf, inf);
+      t[k] = pin[min(j, a.pop - 1)];  // in bounds; slots past the last agent are replaced when they are stored
     }
+    // main wave: the policy's weights, requested behind the positions; their round trip to L2 runs under
+    // everything up to the forward pass
+    if (!helper && live && !a.actions_in) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
     if (helper) {  // the items and their book
       for (int sl = lane; sl < food_pad + poison_pad; sl += 64) {
         const bool is_food = sl < food_pad;
@@ -344,7 +346,7 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int j = (2 * k + role) * 64 + lane;
-      if (j < pop_pad) s_pos[j] = t[k];
+      if (j < pop_pad) s_pos[j] = j < a.pop ? t[k] : make_float2(inf, inf);  // the first use of the loaded values
     }
     for (int j = 1024 + role * 64 + lane; j < pop_pad; j += 128) s_pos[j] = j < a.pop ? pin[j] : make_float2(inf, inf);
   }
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   // The agent scan is shared: the main wave takes the first blocks of 64 candidates, the helper the rest
   // and the two item lists (about two blocks' worth of work).
   const int blocks = pop_pad / 64;
-  const int main_blocks = min(blocks, (blocks + 2) / 2);
+  const int main_blocks = min(blocks, (blocks + 3) / 2);
   const size_t me = static_cast<size_t>(world) * a.pop + min(agent, a.pop - 1);
   float2 p = make_float2(0.f, 0.f), v = p;
   Nearest other{inf, 0x7fffffff};
@@ -493,6 +495,8 @@ static Layout carve(int pop, int worlds, int n_items) {
   return l;
 }
 
+constexpr size_t kMaxLdsBytes = 160 * 1024;  // per workgroup on this chip
+
 static size_t step_lds_bytes(int pop, int n_food, int n_items) {
   return static_cast<size_t>(kWorldsPerBlock) *
          ((pad_to(pop, 64) + pad_to(n_food, 16) + pad_to(n_items - n_food, 16)) * sizeof(float2) +
@@ -517,6 +521,17 @@ static int fill_const(const float* cp, WorldConst* c) {
 template <int H>
 static int launch_step(const StepArgs& a, hipStream_t s) {
   const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
+  // more than 64 KB of dynamic LDS has to be asked for, once per kernel and device
+  static bool raised[64] = {};
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_step_kernel<H>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
+    raised[device] = e == hipSuccess;
+  }
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the step kernel failed: %s",
+              hipGetErrorString(e));
   hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(kStepThreads),
                      step_lds_bytes(a.pop, a.c.n_food, a.c.n_items), s, a);
   return check_launch("world_step_kernel");
@@ -540,9 +555,10 @@ int forage_supported(const MlpShape& sh, int pop, int worlds, const float* cp) {
               EVO_ERR_UNSUPPORTED, "forage: the policy must be an MLP of dims {8, H, H, 2} with H = 16, 32 or 64");
   EVO_REQUIRE(pop >= 2, EVO_ERR_ARG, "forage: a world needs at least two agents (got pop = %d)", pop);
   EVO_REQUIRE(worlds >= 1 && worlds <= 4096, EVO_ERR_ARG, "forage: n_rollouts (worlds) must be in [1, 4096]");
-  EVO_REQUIRE(step_lds_bytes(pop, c.n_food, c.n_items) <= 65536, EVO_ERR_UNSUPPORTED,
-              "forage: at most about %d agents per world (positions of four worlds are staged in 64 KB of LDS)",
-              (65536 / kWorldsPerBlock - kExchangeWords * 256) / 8 - c.n_items - 32);
+  const size_t lds = step_lds_bytes(pop, c.n_food, c.n_items);
+  EVO_REQUIRE(lds <= kMaxLdsBytes, EVO_ERR_UNSUPPORTED,
+              "forage: too many agents per world: staging the positions of four worlds takes %zu bytes of LDS, %zu fit",
+              lds, kMaxLdsBytes);
   return EVO_OK;
 }
 

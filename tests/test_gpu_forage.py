@@ -44,7 +44,8 @@ def _bits(a):
 
 
 @pytest.mark.parametrize("pop,worlds,n_food,n_poison,radius", [(130, 3, 5, 7, 0.0625), (1024, 5, 24, 24, 0.03125),
-                                                               (2, 1, 1, 1, 0.25), (77, 8, 100, 156, 0.015625)])
+                                                               (2, 1, 1, 1, 0.25), (77, 8, 100, 156, 0.015625),
+                                                               (2500, 2, 24, 24, 0.03125)])
 def test_one_step_from_a_given_state_is_bit_exact(evo, pop, worlds, n_food, n_poison, radius):
     w = dict(forage.WORLD_DEFAULT, n_food=n_food, n_poison=n_poison, radius=radius)
     n_items = n_food + n_poison
@@ -206,8 +207,8 @@ def test_errors_are_reported(evo):
         evo.rollout(_task(evo, w, 2, 64), good, params, 64, 5, fit)
     with pytest.raises(evo.EvoError):                    # no poison
         evo.rollout(_task(evo, dict(w, n_poison=0), 2, 64), good, params, 64, 5, fit)
-    big = torch.zeros(2048, params.shape[1], dtype=torch.float32, device="cuda")
+    big = torch.zeros(6000, params.shape[1], dtype=torch.float32, device="cuda")
     with pytest.raises(evo.EvoError):                    # more agents than the staging area holds
-        evo.rollout(td, good, big, 2048, 5, torch.empty(2048, dtype=torch.float32, device="cuda"))
+        evo.rollout(_task(evo, w, 2, 6000, good), good, big, 6000, 5, torch.empty(6000, dtype=torch.float32, device="cuda"))
     evo.rollout(td, good, params, 64, 5, fit)            # and the good case still runs
     assert torch.isfinite(fit).all()
