@@ -288,7 +288,9 @@ typedef struct {
 size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop);
 
 /* Evaluate every member: fitness_dev[pop] as defined above.  `steps` is the episode length
- * for CARTPOLE and must be 1 for the single-step tasks.
+ * for CARTPOLE and FORAGE (FORAGE enqueues steps + 2 kernels and keeps the worlds' state in
+ * work_dev, so two roll-outs that share a workspace must not overlap) and must be 1 for the
+ * single-step tasks.
  * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED, EVO_ERR_HIP. */
 int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
             float* fitness_dev, void* stream);
