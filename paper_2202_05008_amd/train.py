@@ -5,8 +5,8 @@
     python -m paper_2202_05008_amd.train --workload cfg1 --generations 100 --ckpt run.ckpt --resume
 
 One JSON line per generation goes to stdout (and to --log): generation, max / mean fitness of the
-population, milliseconds, and every --test-every generations the fitness of the unperturbed centre on
-held-out inputs.  A run resumed from a checkpoint continues bit-for-bit (the noise of generation t
+population, milliseconds (with --profile also the device time of each stage), and every
+--test-every generations the fitness of the unperturbed centre on held-out inputs.  A run resumed from a checkpoint continues bit-for-bit (the noise of generation t
 is a function of (seed, t) alone).
 """
 import argparse
@@ -106,6 +106,7 @@ def main(argv=None):
     ap.add_argument("--ckpt", default=None, help="checkpoint file")
     ap.add_argument("--save-every", type=int, default=0)
     ap.add_argument("--resume", action="store_true", help="continue from --ckpt")
+    ap.add_argument("--profile", action="store_true", help="log the device time of ask, rollout and tell per generation")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         raise SystemExit("paper_2202_05008_amd.train needs a GPU (there is no CPU fallback)")
@@ -121,7 +122,7 @@ def main(argv=None):
     pd, train_task, test_task = _tasks(args.workload, c, args.seed, dev)
     tr = Trainer(pg, pd, train_task, c.pop, steps=c.steps, seed=args.seed, test_task=test_task,
                  test_every=args.test_every, log_path=args.log, ckpt_path=args.ckpt, save_every=args.save_every,
-                 test_pop=FORAGE_TEST_POP if args.workload == "forage" else 1)
+                 test_pop=FORAGE_TEST_POP if args.workload == "forage" else 1, profile=args.profile)
     if args.resume:
         if not args.ckpt:
             raise SystemExit("--resume needs --ckpt")

@@ -30,12 +30,13 @@ class Trainer:
     seed        seed of the noise stream; generation t of a run is a function of (seed, t) alone
     log_path    JSON-lines log (appended), or None
     ckpt_path   checkpoint file written every `save_every` generations (0 = never), atomically
+    profile     also log the device time of each stage (ask, rollout, tell) from events on the stream
     test_pop    copies of the centre that are evaluated together (a shared world needs company: the
                 test fitness is then the mean over the copies); 1 for every other task
     """
 
     def __init__(self, pgpe, policy, train_task, pop, steps=1, seed=0, test_task=None, test_every=0, log_path=None,
-                 ckpt_path=None, save_every=0, test_pop=1):
+                 ckpt_path=None, save_every=0, test_pop=1, profile=False):
         self.pgpe, self.policy, self.train_task, self.test_task = pgpe, policy, train_task, test_task
         self.pop, self.steps, self.seed = int(pop), int(steps), int(seed)
         self.test_every, self.save_every = int(test_every), int(save_every)
@@ -45,6 +46,7 @@ class Trainer:
         dev = pgpe.mu.device
         self.params = torch.empty(self.pop, pgpe.cfg.P, dtype=tdtype, device=dev)
         self.fitness = torch.empty(self.pop, dtype=torch.float32, device=dev)
+        self.profile = bool(profile)
         self.test_pop = int(test_pop)
         self._center = torch.empty(self.test_pop, pgpe.cfg.P, dtype=tdtype, device=dev)
         self._center_fit = torch.empty(self.test_pop, dtype=torch.float32, device=dev)
@@ -55,12 +57,21 @@ class Trainer:
         """ask -> rollout -> tell for the next generation; returns its log record."""
         t = self.pgpe.generation
         t0 = time.perf_counter()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if self.profile else None
+        mark = (lambda i: ev[i].record()) if self.profile else (lambda i: None)
+        mark(0)
         self.pgpe.ask(self.seed, self.pop, self.params, self.dtype)
+        mark(1)
         api.rollout(self.train_task(t), self.policy, self.params, self.pop, self.steps, self.fitness)
+        mark(2)
         self.pgpe.tell(self.fitness)
+        mark(3)
         fmax, fmean = float(self.fitness.max()), float(self.fitness.mean())   # waits for the generation
         rec = {"generation": t, "fitness_max": fmax, "fitness_mean": fmean,
                "ms": (time.perf_counter() - t0) * 1e3}
+        if self.profile:
+            ev[3].synchronize()
+            rec["stage_ms"] = {n: ev[i].elapsed_time(ev[i + 1]) for i, n in enumerate(("ask", "rollout", "tell"))}
         if self.test_task is not None and self.test_every and t % self.test_every == 0:
             rec["test_fitness"] = self.test()
         self.history.append(rec)

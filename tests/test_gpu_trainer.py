@@ -158,8 +158,10 @@ def test_train_command_line(evo, tmp_path, capsys, workload, generations):
     from paper_2202_05008_amd import train
     ck, log = str(tmp_path / "run.ckpt"), str(tmp_path / "run.jsonl")
     assert train.main(["--workload", workload, "--generations", str(generations), "--test-every", "1", "--ckpt", ck,
-                       "--log", log]) == 0
+                       "--log", log, "--profile"]) == 0
     lines = [json.loads(l) for l in capsys.readouterr().out.splitlines()]
+    assert all(set(r["stage_ms"]) == {"ask", "rollout", "tell"} and min(r["stage_ms"].values()) > 0 and
+               sum(r["stage_ms"].values()) <= r["ms"] * 1.05 + 0.05 for r in lines[:-1])
     assert [r["generation"] for r in lines[:-1]] == list(range(1, generations + 1))
     assert all(np.isfinite(r["fitness_mean"]) and np.isfinite(r["test_fitness"]) for r in lines[:-1])
     assert lines[-1]["generation"] == generations + 1 and np.isfinite(lines[-1]["final_test_fitness"])
