@@ -165,6 +165,26 @@ def test_short_horizon_with_the_policy_in_the_loop(evo):
     assert np.abs(total).sum() > 10
 
 
+def test_long_horizon_population_statistics(evo):
+    """300 steps with observation-driven policies: single trajectories part ways (a nearest neighbour that
+    flips is a discontinuity), the population's statistics do not: the two fitness vectors have the same mean
+    within sampling error and are strongly rank-correlated (what an agent collects is mostly its policy's doing)."""
+    from scipy.stats import spearmanr
+    pop, worlds, steps = 128, 4, 300
+    w = dict(forage.WORLD_DEFAULT, radius=0.0625)
+    dims, acts = (8, 32, 32, 2), (1, 1, 1)
+    params = _random_policies(pop, dims, 0.7, 23)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    td = _task(evo, w, worlds, pop, pd)
+    pos, vel, reward, counts, fit = _run_state(evo, td, pd, dev(params), pop, worlds, 48, steps)
+    want = forage.rollout(params, dims, acts, SEED, 3, worlds, steps, w)
+    sem = np.sqrt((want.var() + fit.var()) / pop)
+    assert abs(fit.mean() - want.mean()) < 4 * sem + 0.05, (fit.mean(), want.mean(), sem)
+    assert abs(np.abs(fit).mean() - np.abs(want).mean()) < 0.25 * np.abs(want).mean() + 0.1
+    rho = spearmanr(fit, want).correlation
+    assert rho > 0.5, rho
+
+
 def test_full_size_constant_actions_and_properties(evo):
     """The benchmark's configuration (1024 agents, 8 worlds, H = 32): 40 steps of policies that ignore
     their observations bit for bit against the oracle, then the full 500 steps with random policies:
