@@ -12,6 +12,8 @@
 // Register layouts of v_mfma_f32_32x32x16_bf16 (lane = 32 g + c):
 //   A[row c][k = 8 g + i], B[k = 8 g + i][col c], i = 0..7 (eight bf16 per lane)
 //   D[row 8 b + 4 g + i][col c] in register 4 b + i, b = 0..3, i = 0..3
+#include <type_traits>
+
 #include "bf16.h"
 #include "kernels.h"
 
@@ -472,8 +474,279 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
   if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
 }
 
+// Two floats rounded to bf16 (one conversion instruction) and max(x, 0) taken on both halves at once.
+typedef short short2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t relu_pack_bf16x2(float lo, float hi) {
+  const bf16x2_t r = __builtin_convertvector(float2v{lo, hi}, bf16x2_t);
+  const short2v h = __builtin_elementwise_max(__builtin_bit_cast(short2v, r), short2v{0, 0});
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// ---- register-resident kernel for many observations per member (B >= kResidentMinRows) ------------
+// With hundreds of observations per member the weights are a small part of the traffic and the layer
+// products are real matrix work.  Four waves per member; wave w owns neurons 64 w .. 64 w + 63 of both
+// hidden layers, i.e. two 32-neuron tiles, and builds every matrix operand of its weights once (a
+// prologue: 16-byte loads, the wave-private staging tile and the transposed read of the streaming
+// kernel), 48 operands = 192 registers per lane, the member's 173 KB across the workgroup.  The tile
+// loop over 64 observations then runs with no weight traffic at all.  Products are transposed (rows =
+// neurons, columns = 32 observations): one 16-byte LDS read of activations feeds two matrix
+// instructions (the wave's two neuron tiles), which halves the LDS traffic per instruction against
+// one tile per wave -- with one tile per wave the 1 KB operand per instruction is exactly the CU's
+// LDS bandwidth when all four SIMDs issue back to back.  The observations of the next tile are
+// requested before the current tile's layers run.
+template <int D0, int H, int A, int MT, bool RELU>
+__global__ __launch_bounds__(256) void mlp_bf16_resident_kernel(Bf16Args a) {
+  constexpr int kRows = 32 * MT;  // observations per pass of the tile loop
+  static_assert(H == 256 && D0 % 32 == 0 && A == 16 && (MT == 2 || MT == 4), "shape of the resident kernel");
+  constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
+  constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32;
+  extern __shared__ __attribute__((aligned(16))) uint16_t resident_lds[];  // resident_lds_bytes(MT)
+  uint16_t* x_s = resident_lds;                  // [kRows][LD0]
+  uint16_t* h_s = x_s + kRows * LD0;             // [kRows][LDH]
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 31, g = lane >> 5;
+  const int c16 = lane & 15, g4 = lane >> 4;
+  const int member = blockIdx.x, B = a.B;
+  const uint16_t* theta = a.params + static_cast<size_t>(member) * a.sh.P;
+  const uint16_t* W1 = theta;
+  const uint16_t* B1 = W1 + D0 * H;
+  const uint16_t* W2 = B1 + H;
+  const uint16_t* B2 = W2 + H * H;
+  const uint16_t* W3 = B2 + H;
+  const uint16_t* B3 = W3 + H * A;
+
+  // observations of a tile: 64 x D0 floats, 16-byte pieces, kObsPieces per thread
+  constexpr int kObsPieces = kRows * D0 / 4 / 256;
+  const float* obs_member = a.obs + static_cast<size_t>(member) * a.obs_stride;
+  float4 ov[kObsPieces];
+  auto load_obs = [&](int row0) {
+#pragma unroll
+    for (int j = 0; j < kObsPieces; ++j) {
+      const int i = tid + 256 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      ov[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row0 + r < B) ov[j] = reinterpret_cast<const float4*>(obs_member + static_cast<size_t>(row0 + r) * D0)[d4];
+    }
+  };
+  load_obs(0);
+
+  // ---- prologue: this wave's matrix operands ---------------------------------------------------------
+  // 16-byte loads of W (contiguous along the columns), a wave-private staging tile in LDS, and the
+  // transposed read that hands every lane eight consecutive k of its column.  Four tiles per round trip
+  // through LDS; the staging tiles borrow the wave's quarter of the (still unused) hidden-activation buffer.
+  constexpr int kBatch = 4;
+  uint16_t* stage = h_s + wave * (kRows * LDH / 4);
+  static_assert(kBatch * kStageElems <= kRows * LDH / 4, "staging tiles fit into a quarter of the activation buffer");
+  auto fence_wave = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  // 16 rows x 32 columns of W1 / W2 per tile
+  auto transposed12 = [&](const u32x4v* raw, bf16x8* out) {
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      *reinterpret_cast<u32x4v*>(stage + j * kStageElems + (lane >> 2) * kStageLd + 8 * (lane & 3)) = raw[j];
+    fence_wave();
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const uint16_t* q = stage + j * kStageElems + (8 * g + (c16 >> 2)) * kStageLd + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+      const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd));
+      out[j] = join_bf16(lo, hi);
+    }
+    fence_wave();
+  };
+  // 32 rows x 16 columns of W3 per tile
+  auto transposed3 = [&](const u32x4v* raw, bf16x8* out) {
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      *reinterpret_cast<u32x4v*>(stage + j * kStageElems + (lane >> 1) * kStageLd3 + 8 * (lane & 1)) = raw[j];
+    fence_wave();
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const uint16_t* q = stage + j * kStageElems + (8 * g4 + (c16 >> 2)) * kStageLd3 + 4 * (lane & 3);
+      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+      const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd3));
+      out[j] = join_bf16(lo, hi);
+    }
+    fence_wave();
+  };
+  static_assert(U1 % kBatch == 0 && U2 % kBatch == 0 && U3 % kBatch == 0, "operands come in rounds of four");
+  bf16x8 w1[2][U1], w2[2][U2], w3[U3];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint16_t* p12 = theta + static_cast<size_t>(lane >> 2) * H + 32 * (2 * wave + t) + 8 * (lane & 3);
+    u32x4v raw[U1 + U2];
+#pragma unroll
+    for (int u = 0; u < U1; ++u) raw[u] = *reinterpret_cast<const u32x4v*>(p12 + static_cast<size_t>(16 * u) * H);
+#pragma unroll
+    for (int u = 0; u < U2; ++u)
+      raw[U1 + u] = *reinterpret_cast<const u32x4v*>(p12 + (W2 - theta) + static_cast<size_t>(16 * u) * H);
+#pragma unroll
+    for (int u = 0; u < U1; u += kBatch) transposed12(raw + u, w1[t] + u);
+#pragma unroll
+    for (int u = 0; u < U2; u += kBatch) transposed12(raw + U1 + u, w2[t] + u);
+  }
+  {
+    const uint16_t* p3 = W3 + (lane >> 1) * A + 8 * (lane & 1);
+    u32x4v raw[U3];
+#pragma unroll
+    for (int u = 0; u < U3; ++u) raw[u] = *reinterpret_cast<const u32x4v*>(p3 + 32 * u * A);
+#pragma unroll
+    for (int u = 0; u < U3; u += kBatch) transposed3(raw + u, w3 + u);
+  }
+  // The hidden layers' biases enter as one more product: a weight operand whose k = 0 column is the bias
+  // of the lane's neuron (everything else zero) times an activation operand whose k = 0 row is one.  The
+  // accumulators then start from that product with a zero addend: no bias registers, no initial copies.
+  bf16x8 wb1[2], wb2[2], ones;
+  {
+    Pack8 p;
+    p.v = make_uint4(0u, 0u, 0u, 0u);
+    if (g == 0) p.h[0] = 0x3F80;  // bf16 1.0
+    ones = p.b;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      p.v = make_uint4(0u, 0u, 0u, 0u);
+      if (g == 0) p.h[0] = B1[64 * wave + 32 * t + c];
+      wb1[t] = p.b;
+      p.v = make_uint4(0u, 0u, 0u, 0u);
+      if (g == 0) p.h[0] = B2[64 * wave + 32 * t + c];
+      wb2[t] = p.b;
+    }
+  }
+  float bias3[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) bias3[i] = from_bf16(B3[4 * g4 + i]);
+
+  // activation, two bf16 per word, four consecutive neurons of one observation per 8-byte store.
+  // RELU: rounding keeps the sign, so max(x, 0) is taken after the rounding, on both halves of a word at
+  // once as a signed 16-bit maximum (a negative bf16 is a negative int16).
+  auto store_rows = [&](const floatx16& acc, int t, int mt, int act) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      uint2 pk;
+      if (RELU) {
+        pk.x = relu_pack_bf16x2(acc[4 * rr], acc[4 * rr + 1]);
+        pk.y = relu_pack_bf16x2(acc[4 * rr + 2], acc[4 * rr + 3]);
+      } else {
+        pk.x = pack_bf16x2(act_f(acc[4 * rr], act), act_f(acc[4 * rr + 1], act));
+        pk.y = pack_bf16x2(act_f(acc[4 * rr + 2], act), act_f(acc[4 * rr + 3], act));
+      }
+      *reinterpret_cast<uint2*>(h_s + (mt * 32 + c) * LDH + 64 * wave + 32 * t + 8 * rr + 4 * g) = pk;
+    }
+  };
+  // One layer's products: step s = (k-slice s / 2, observation tile s % 2) reads one activation operand and
+  // feeds the wave's two neuron tiles.  The reads run kAhead steps ahead of the matrix instructions; the
+  // scheduling fences keep that order (left alone, the compiler issues each read right before its use).
+  constexpr int kAhead = 3;
+  auto layer_products = [&](floatx16 (&acc)[2][MT], const uint16_t* in, int ld, const bf16x8 (&wb)[2], auto wt,
+                            auto steps_c) {
+    constexpr int kSteps = decltype(steps_c)::value;
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[0], ones, zero, 0, 0, 0);
+      acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1], ones, zero, 0, 0, 0);
+    }
+    uint4 av[kSteps];
+    auto read = [&](int s) { av[s] = *reinterpret_cast<const uint4*>(in + ((s % MT) * 32 + c) * ld + 16 * (s / MT) + 8 * g); };
+#pragma unroll
+    for (int s = 0; s < kAhead && s < kSteps; ++s) read(s);
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) {
+      if (s + kAhead < kSteps) read(s + kAhead);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[0][s % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wt(0, s / MT), as_bf16x8(av[s]), acc[0][s % MT], 0, 0, 0);
+      acc[1][s % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wt(1, s / MT), as_bf16x8(av[s]), acc[1][s % MT], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  float loss_acc = 0.f;
+#pragma unroll 1
+  for (int row0 = 0; row0 < B; row0 += kRows) {
+    // ---- observations -> bf16 rows (rows beyond B are zero); the next tile's are requested at once ----
+#pragma unroll
+    for (int j = 0; j < kObsPieces; ++j) {
+      const int i = tid + 256 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      uint2 pk;
+      pk.x = pack_bf16x2(ov[j].x, ov[j].y);
+      pk.y = pack_bf16x2(ov[j].z, ov[j].w);
+      *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
+    }
+    if (row0 + kRows < B) load_obs(row0 + kRows);
+    // layer 3: a wave takes MT / 2 groups of 16 observations; lane = observation c16 of a group, outputs 4 g4 ..
+    constexpr int kGroups = MT / 2;
+    float4 tgt[kGroups];
+#pragma unroll
+    for (int gi = 0; gi < kGroups; ++gi) {
+      const int row = row0 + 16 * (kGroups * wave + gi) + c16;
+      tgt[gi] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (a.loss != LOSS_NONE && row < B)
+        tgt[gi] = *reinterpret_cast<const float4*>(a.target + (static_cast<size_t>(member) * B + row) * A + 4 * g4);
+    }
+    __syncthreads();  // x_s is complete; every wave has left layer 3 of the previous tile
+
+    // ---- layer 1 ------------------------------------------------------------------------------------
+    floatx16 acc[2][MT];
+    layer_products(acc, x_s, LD0, wb1, [&](int t, int u) { return w1[t][u]; }, std::integral_constant<int, MT * U1>{});
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) store_rows(acc[t][mt], t, mt, RELU ? EVO_ACT_RELU : a.sh.act[0]);
+    __syncthreads();
+
+    // ---- layer 2 ------------------------------------------------------------------------------------
+    layer_products(acc, h_s, LDH, wb2, [&](int t, int u) { return w2[t][u]; }, std::integral_constant<int, MT * U2>{});
+    __syncthreads();  // every wave has read h1: the buffer can take h2
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) store_rows(acc[t][mt], t, mt, RELU ? EVO_ACT_RELU : a.sh.act[1]);
+    __syncthreads();
+
+    // ---- layer 3: 16x16x32 tiles (lane = 16 g4 + c16), MT / 2 groups of 16 observations per wave ----------
+#pragma unroll
+    for (int gi = 0; gi < kGroups; ++gi) {
+      const int local = 16 * (kGroups * wave + gi) + c16, row = row0 + local;
+      floatx4v o = {bias3[0], bias3[1], bias3[2], bias3[3]};
+#pragma unroll
+      for (int u = 0; u < U3; ++u) {
+        const uint4 av = *reinterpret_cast<const uint4*>(h_s + local * LDH + 32 * u + 8 * g4);
+        o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3[u], as_bf16x8(av), o, 0, 0, 0);
+      }
+      if (row < B) {
+        const int act = RELU ? EVO_ACT_NONE : a.sh.act[2];
+        const float v0 = act_f(o[0], act), v1 = act_f(o[1], act), v2 = act_f(o[2], act), v3 = act_f(o[3], act);
+        if (a.loss == LOSS_NONE) {
+          *reinterpret_cast<float4*>(a.out + (static_cast<size_t>(member) * B + row) * A + 4 * g4) = make_float4(v0, v1, v2, v3);
+        } else {
+          const float d0 = v0 - tgt[gi].x, d1 = v1 - tgt[gi].y, d2 = v2 - tgt[gi].z, d3 = v3 - tgt[gi].w;
+          loss_acc = fmaf(d0, d0, loss_acc);
+          loss_acc = fmaf(d1, d1, loss_acc);
+          loss_acc = fmaf(d2, d2, loss_acc);
+          loss_acc = fmaf(d3, d3, loss_acc);
+        }
+      }
+    }
+  }
+  if (a.loss == LOSS_NONE) return;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
+  if (lane == 0) red[wave] = loss_acc;
+  __syncthreads();
+  if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
+}
+
+template <int D0, int H, int MT>
+constexpr size_t resident_lds_bytes() {
+  return static_cast<size_t>(32 * MT) * (D0 + kRowPad + H + kRowPad) * sizeof(uint16_t);
+}
+
 constexpr int kStreamMaxRows = 4096;  // observations per member of the streaming kernel (tiles of 64)
-constexpr int kKeepMinRows = 448;     // from seven tiles on, keeping the operands in registers pays (measured)
+constexpr int kKeepMinRows = 65;      // more than one tile of 64 rows: the register-resident kernel
 
 static bool stream_shape(const MlpShape& sh, int B) {
   return sh.n_layers == 3 && sh.dims[0] == 64 && sh.dims[1] == 256 && sh.dims[2] == 256 && sh.dims[3] == 16 &&
@@ -507,7 +780,17 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
     } else if (B < kKeepMinRows) {
       if (relu) EVO_STREAM(1, true); else EVO_STREAM(1, false);
     } else {
-      if (relu) EVO_STREAM(2, true); else EVO_STREAM(2, false);
+      constexpr int MT = 2;  // 64 observations per pass (128 measured slower: 2.17 vs 1.64 ms at B = 2048)
+      constexpr size_t lds = resident_lds_bytes<64, 256, MT>();
+      const void* fn = relu ? reinterpret_cast<const void*>(&mlp_bf16_resident_kernel<64, 256, 16, MT, true>)
+                            : reinterpret_cast<const void*>(&mlp_bf16_resident_kernel<64, 256, 16, MT, false>);
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+      if (relu)
+        hipLaunchKernelGGL((mlp_bf16_resident_kernel<64, 256, 16, MT, true>), dim3(pop), dim3(256), lds, s, a);
+      else
+        hipLaunchKernelGGL((mlp_bf16_resident_kernel<64, 256, 16, MT, false>), dim3(pop), dim3(256), lds, s, a);
+      return check_launch("mlp_bf16_resident_kernel");
     }
 #undef EVO_STREAM
     return check_launch("mlp_bf16_stream_kernel");
