@@ -197,19 +197,11 @@ constexpr int kStageLd = 40;   // row stride (elements) of the 16 x 32 staging t
 constexpr int kStageLd3 = 24;  // row stride of the 32 x 16 staging tile of layer 3
 constexpr int kStageElems = 32 * kStageLd3;  // 768 elements >= 16 * kStageLd
 
-// MULTI: more than 64 observations per member: a loop over tiles of 64 rows (two waves per SIMD
-// instead of four).  MULTI == 1 streams the weights again for every tile (from L2, where a member's
-// 173 KB stay resident).  MULTI == 2, for large B: the first tile keeps every matrix operand it
-// builds (28 units = 112 registers per lane: the member's whole 173 KB across the workgroup) and the
-// later tiles run from those registers with no loads, no staging and no transposed reads; the first
-// tile pays for the registers with spills, the later ones cost 0.07 ms instead of 0.12 ms over the
-// population.
+// At most 64 observations per member (one tile); more go to the register-resident kernel below.
 // RELU: the hidden activations are ReLU and the output is linear (the shape's usual policy), which
 // removes the per-value activation switch from the epilogues.
-template <int D0, int H, int A, int MULTI, bool RELU>
-__global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf16Args a) {
-  constexpr bool KEEP = MULTI == 2;  // operands stay in registers after the first tile
-  constexpr bool TR = MULTI != 0;    // transposed products (measured: they pay with several tiles, not with one)
+template <int D0, int H, int A, bool RELU>
+__global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   static_assert(H == 256 && D0 % 32 == 0 && A == 16, "shape of the streaming kernel");
   constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
   constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32, UT = U1 + U2 + U3;
@@ -269,79 +261,41 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
     __builtin_amdgcn_wave_barrier();
     return join_bf16(lo, hi);
   };
-  // TR: the products run transposed (rows = this wave's 32 neurons, columns = 32 observations): a
-  // lane's accumulator registers 4 rr .. 4 rr + 3 are four consecutive neurons 32 wave + 8 rr + 4 g ..
-  // of one observation, which leave as one 8-byte LDS store instead of four 2-byte ones.  Otherwise
-  // rows = observations 8 rr + 4 g + i, columns = the wave's neurons 32 wave + c.
-  // single tile: the two column biases are fetched here, ahead of the tile (a load at the point of use
-  // would sit between two layers); several tiles: the 16 row biases of a layer are fetched where they
-  // are used (registers are scarcer there than latency)
+  // rows = observations 8 rr + 4 g + i, columns = the wave's neurons 32 wave + c; the two column biases are
+  // fetched here, ahead of the tile (a load at the point of use would sit between two layers)
   const float bias_col[2] = {from_bf16(B1[32 * wave + c]), from_bf16(B2[32 * wave + c])};
   auto bias_rows = [&](int layer, floatx16 (&acc)[2]) {
-    if (!TR) {
-      const float b = bias_col[layer];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][r] = b;
-      return;
-    }
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const uint2 pk = *reinterpret_cast<const uint2*>((layer == 0 ? B1 : B2) + 32 * wave + 8 * rr + 4 * g);
-      const float b0 = __uint_as_float(pk.x << 16), b1 = __uint_as_float(pk.x & 0xFFFF0000u);
-      const float b2 = __uint_as_float(pk.y << 16), b3 = __uint_as_float(pk.y & 0xFFFF0000u);
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) acc[mt][4 * rr] = b0, acc[mt][4 * rr + 1] = b1, acc[mt][4 * rr + 2] = b2, acc[mt][4 * rr + 3] = b3;
-    }
-  };
-  auto store_rows = [&](const floatx16 (&acc)[2], int act) {
-    if (!TR) {
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          h_s[row * LDH + 32 * wave + c] = to_bf16(act_f(acc[mt][r], act));
-        }
-      return;
-    }
+    const float b = bias_col[layer];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        uint2 pk;
-        pk.x = pack_bf16x2(act_f(acc[mt][4 * rr], act), act_f(acc[mt][4 * rr + 1], act));
-        pk.y = pack_bf16x2(act_f(acc[mt][4 * rr + 2], act), act_f(acc[mt][4 * rr + 3], act));
-        *reinterpret_cast<uint2*>(h_s + (mt * 32 + c) * LDH + 32 * wave + 8 * rr + 4 * g) = pk;
+      for (int r = 0; r < 16; ++r) acc[mt][r] = b;
+  };
+  auto store_rows = [&](const floatx16 (&acc)[2], int act) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        h_s[row * LDH + 32 * wave + c] = to_bf16(act_f(acc[mt][r], act));
       }
   };
-  float bias3[4];  // layer 3: TR: rows = outputs 4 g4 + i, columns = observations; else column = output c16
-#pragma unroll
-  for (int i = 0; i < 4; ++i) bias3[i] = from_bf16(B3[TR ? 4 * g4 + i : c16]);
+  const float bias3 = from_bf16(B3[c16]);  // layer 3: column = output c16
   float loss_acc = 0.f;
-  bf16x8 wreg[KEEP ? UT : 1];  // the matrix operands of every unit, built during the first tile
-  // Tiles of 64 observations: the weights are read from HBM once per member whatever B is.
-  const int row_end = MULTI ? B : 1;
-#pragma unroll 1
-  for (int row0 = 0; row0 < row_end; row0 += 64) {
-  const bool first = !KEEP || row0 == 0;  // uniform: this tile streams the weights
   // the observation loads go first so that waiting for them does not drain the weight stream
   constexpr int kObsPieces = 64 * D0 / 4 / 512;
   float4 ov[kObsPieces];
   {
-    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride + static_cast<size_t>(row0) * D0;
+    const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
 #pragma unroll
     for (int j = 0; j < kObsPieces; ++j) {
       const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
       ov[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row0 + r < B) ov[j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
+      if (r < B) ov[j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
     }
   }
-  if (first) {
 #pragma unroll
-    for (int u = 0; u < kDepth; ++u) issue(u);
-  }
+  for (int u = 0; u < kDepth; ++u) issue(u);
 
   // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
 #pragma unroll
@@ -352,21 +306,13 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
     pk.y = pack_bf16x2(ov[j].z, ov[j].w);
     *reinterpret_cast<uint2*>(x_s + r * LD0 + 4 * d4) = pk;
   }
-  // targets of this lane's four output rows (layer 3 tile of wave < 4)
-  // TR: outputs 4 g4 .. 4 g4 + 3 of observation 16 wave + c16; else output c16 of observations 16 wave + 4 g4 + i
-  float4 tgt = make_float4(0.f, 0.f, 0.f, 0.f);
+  // targets of this lane's four output rows (layer 3 tile of wave < 4): output c16 of observations 16 wave + 4 g4 + i
+  float tgt[4] = {0.f, 0.f, 0.f, 0.f};
   if (tail && a.loss != LOSS_NONE) {
-    if (TR) {
-      if (row0 + 16 * wave + c16 < B)
-        tgt = *reinterpret_cast<const float4*>(a.target + (static_cast<size_t>(member) * B + row0 + 16 * wave + c16) * A + 4 * g4);
-    } else {
-      float t[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = row0 + 16 * wave + 4 * g4 + i;
-        if (row < B) t[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
-      }
-      tgt = make_float4(t[0], t[1], t[2], t[3]);
+    for (int i = 0; i < 4; ++i) {
+      const int row = 16 * wave + 4 * g4 + i;
+      if (row < B) tgt[i] = a.target[(static_cast<size_t>(member) * B + row) * A + c16];
     }
   }
   __syncthreads();
@@ -376,19 +322,12 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
   bias_rows(0, acc);
 #pragma unroll
   for (int u = 0; u < U1; ++u) {
-    bf16x8 bv;
-    if (first) {
-      bv = operand12(u);
-      issue(u + kDepth);
-      if (KEEP) wreg[u] = bv;
-    } else {
-      bv = wreg[KEEP ? u : 0];
-    }
+    const bf16x8 bv = operand12(u);
+    issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       const uint4 av = *reinterpret_cast<const uint4*>(x_s + (mt * 32 + c) * LD0 + 16 * u + 8 * g);
-      acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, as_bf16x8(av), acc[mt], 0, 0, 0)
-                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
     }
   }
   store_rows(acc, RELU ? EVO_ACT_RELU : a.sh.act[0]);
@@ -398,19 +337,12 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
   bias_rows(1, acc);
 #pragma unroll
   for (int u = U1; u < U1 + U2; ++u) {
-    bf16x8 bv;
-    if (first) {
-      bv = operand12(u);
-      issue(u + kDepth);
-      if (KEEP) wreg[u] = bv;
-    } else {
-      bv = wreg[KEEP ? u : 0];
-    }
+    const bf16x8 bv = operand12(u);
+    issue(u + kDepth);
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       const uint4 av = *reinterpret_cast<const uint4*>(h_s + (mt * 32 + c) * LDH + 16 * (u - U1) + 8 * g);
-      acc[mt] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, as_bf16x8(av), acc[mt], 0, 0, 0)
-                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mt], 0, 0, 0);
     }
   }
   __syncthreads();  // every wave has read h1: the buffer can take h2
@@ -419,53 +351,29 @@ __global__ __launch_bounds__(512, MULTI ? 2 : 4) void mlp_bf16_stream_kernel(Bf1
 
   // ---- layer 3: four waves, one 16-row tile each (16x16x32 tiles: lane = 16 g4 + c16) -------------
   if (tail) {
-    floatx4v o = {bias3[0], bias3[1], bias3[2], bias3[3]};
+    floatx4v o = {bias3, bias3, bias3, bias3};
 #pragma unroll
     for (int u = U1 + U2; u < UT; ++u) {
-      bf16x8 bv;
-      if (first) {
-        bv = operand3(u);
-        issue(u + kDepth);
-        if (KEEP) wreg[u] = bv;
-      } else {
-        bv = wreg[KEEP ? u : 0];
-      }
+      const bf16x8 bv = operand3(u);
+      issue(u + kDepth);
       const uint4 av = *reinterpret_cast<const uint4*>(h_s + (16 * wave + c16) * LDH + 32 * (u - U1 - U2) + 8 * g4);
-      o = TR ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, as_bf16x8(av), o, 0, 0, 0)
-             : __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
     }
     const int act = RELU ? EVO_ACT_NONE : a.sh.act[2];
-    if (!TR) {
-      const float tg[4] = {tgt.x, tgt.y, tgt.z, tgt.w};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = row0 + 16 * wave + 4 * g4 + i;
-        const float v = act_f(o[i], act);
-        if (row < B) {
-          if (a.loss == LOSS_NONE) {
-            a.out[(static_cast<size_t>(member) * B + row) * A + c16] = v;
-          } else {
-            const float d = v - tg[i];
-            loss_acc = fmaf(d, d, loss_acc);
-          }
+    for (int i = 0; i < 4; ++i) {
+      const int row = 16 * wave + 4 * g4 + i;
+      const float v = act_f(o[i], act);
+      if (row < B) {
+        if (a.loss == LOSS_NONE) {
+          a.out[(static_cast<size_t>(member) * B + row) * A + c16] = v;
+        } else {
+          const float d = v - tgt[i];
+          loss_acc = fmaf(d, d, loss_acc);
         }
       }
     }
-    const int row = row0 + 16 * wave + c16;  // TR: this lane's observation; its registers are outputs 4 g4 + i
-    if (TR && row < B) {
-      const float v0 = act_f(o[0], act), v1 = act_f(o[1], act), v2 = act_f(o[2], act), v3 = act_f(o[3], act);
-      if (a.loss == LOSS_NONE) {
-        *reinterpret_cast<float4*>(a.out + (static_cast<size_t>(member) * B + row) * A + 4 * g4) = make_float4(v0, v1, v2, v3);
-      } else {
-        const float d0 = v0 - tgt.x, d1 = v1 - tgt.y, d2 = v2 - tgt.z, d3 = v3 - tgt.w;
-        loss_acc = fmaf(d0, d0, loss_acc);
-        loss_acc = fmaf(d1, d1, loss_acc);
-        loss_acc = fmaf(d2, d2, loss_acc);
-        loss_acc = fmaf(d3, d3, loss_acc);
-      }
-    }
   }
-  }  // row tiles (the first barrier of the next tile comes after every wave's layer 3)
   if (a.loss == LOSS_NONE) return;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
@@ -483,7 +391,7 @@ __device__ __forceinline__ uint32_t relu_pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-// ---- register-resident kernel for many observations per member (B >= kResidentMinRows) ------------
+// ---- register-resident kernel for more than 64 observations per member -----------------------------
 // With hundreds of observations per member the weights are a small part of the traffic and the layer
 // products are real matrix work.  Four waves per member; wave w owns neurons 64 w .. 64 w + 63 of both
 // hidden layers, i.e. two 32-neuron tiles, and builds every matrix operand of its weights once (a
@@ -746,7 +654,6 @@ constexpr size_t resident_lds_bytes() {
 }
 
 constexpr int kStreamMaxRows = 4096;  // observations per member of the streaming kernel (tiles of 64)
-constexpr int kKeepMinRows = 65;      // more than one tile of 64 rows: the register-resident kernel
 
 static bool stream_shape(const MlpShape& sh, int B) {
   return sh.n_layers == 3 && sh.dims[0] == 64 && sh.dims[1] == 256 && sh.dims[2] == 256 && sh.dims[3] == 16 &&
@@ -773,12 +680,11 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
   if (stream_shape(sh, B)) {
     a.buf_elems = 0;
     const bool relu = sh.act[0] == EVO_ACT_RELU && sh.act[1] == EVO_ACT_RELU && sh.act[2] == EVO_ACT_NONE;
-#define EVO_STREAM(MULTIV, RELUV) \
-  hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16, MULTIV, RELUV>), dim3(pop), dim3(512), 0, s, a)
     if (B <= 64) {
-      if (relu) EVO_STREAM(0, true); else EVO_STREAM(0, false);
-    } else if (B < kKeepMinRows) {
-      if (relu) EVO_STREAM(1, true); else EVO_STREAM(1, false);
+      if (relu)
+        hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16, true>), dim3(pop), dim3(512), 0, s, a);
+      else
+        hipLaunchKernelGGL((mlp_bf16_stream_kernel<64, 256, 16, false>), dim3(pop), dim3(512), 0, s, a);
     } else {
       constexpr int MT = 2;  // 64 observations per pass (128 measured slower: 2.17 vs 1.64 ms at B = 2048)
       constexpr size_t lds = resident_lds_bytes<64, 256, MT>();
@@ -792,7 +698,6 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
         hipLaunchKernelGGL((mlp_bf16_resident_kernel<64, 256, 16, MT, false>), dim3(pop), dim3(256), lds, s, a);
       return check_launch("mlp_bf16_resident_kernel");
     }
-#undef EVO_STREAM
     return check_launch("mlp_bf16_stream_kernel");
   }
   const int rows = ((B + 31) / 32) * 32;
