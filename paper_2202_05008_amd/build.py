@@ -27,9 +27,16 @@ FLAGS = [
 ]
 
 
+# Extra flags of single files.  policy_bf16.hip: the matrix accumulators of its kernels are consumed by
+# vector instructions right after the products, so they are kept in the vector half of the register file
+# (otherwise every value costs one move out of the accumulation registers before its epilogue; measured on
+# the register-resident kernel: 1.62 -> 1.47 ms at 2048 observations per member, the streaming kernel unchanged).
+FILE_FLAGS = {"policy_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src):
     obj = os.path.join(BUILD, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
     if src.endswith(".cpp"):
         cmd[1:1] = ["-x", "hip"]
     r = subprocess.run(cmd, capture_output=True, text=True)
