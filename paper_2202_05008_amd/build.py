@@ -27,11 +27,14 @@ FLAGS = [
 ]
 
 
-# Extra flags of single files.  policy_bf16.hip: the matrix accumulators of its kernels are consumed by
-# vector instructions right after the products, so they are kept in the vector half of the register file
-# (otherwise every value costs one move out of the accumulation registers before its epilogue; measured on
-# the register-resident kernel: 1.62 -> 1.47 ms at 2048 observations per member, the streaming kernel unchanged).
-FILE_FLAGS = {"policy_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+# Extra flags of single files.  The matrix accumulators of these kernels are consumed by vector instructions
+# right after the products, so they are kept in the vector half of the register file; otherwise every value
+# costs one move out of the accumulation registers before its epilogue.  Measured on one box: the
+# register-resident bf16 kernel 1.61 -> 1.48 ms at 2048 observations per member (the streaming kernel
+# unchanged), the cart-pole roll-out 1.38 -> 1.30 ms; the LSTM kernel does not change and the ConvNet kernel has
+# no such moves, so they are left alone.
+_VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+FILE_FLAGS = {"policy_bf16.hip": _VGPR_FORM, "task_cartpole.hip": _VGPR_FORM}
 
 
 def _compile(src):
