@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kBf16Threads) void mlp_bf16_kernel(Bf16Args a) {
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][r] = bv;
-#pragma unroll 2
+#pragma unroll 1
       for (int k0 = 0; k0 < K; k0 += 16) {
         Pack8 wv;
         const uint16_t* wp = W + static_cast<size_t>(k0 + 8 * g) * N + col;

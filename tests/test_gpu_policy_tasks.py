@@ -145,6 +145,8 @@ def test_convnet_beyond_the_fp16_range_is_loud(evo):
                                              ((64, 256, 256, 16), (2, 2, 0), 3, 520), ((64, 256, 256, 16), (1, 2, 0), 2, 448),
                                              ((64, 256, 256, 16), (2, 2, 0), 3, 128),       # two tiles of 64 rows
                                              ((64, 256, 256, 16), (2, 2, 0), 2, 200),       # ragged last tile
+                                             ((64, 256, 256, 16), (2, 2, 0), 2, 65),        # one row into the second tile
+                                             ((64, 256, 256, 16), (2, 1, 1), 2, 1000),      # many tiles, tanh epilogues
                                              ((32, 48, 16), (1, 0), 4, 17), ((16, 16), (0,), 2, 64)])
 def test_mlp_bf16(evo, dims, acts, pop, B):
     P = mlp_param_count(dims)
