@@ -249,7 +249,7 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *             fitness = an agent's summed reward, averaged over the worlds.  The paper gives no
  *             rules; this world is the library's own definition:
  *     cp = {dt, thrust, drag, vmax, touch radius, food items F, poison items Q} (F, Q whole numbers,
- *     F + Q <= 256); policy: fp32 MLP of dims {8, H, H, 2}, H in {16, 32, 64}; pop <= about 3400 (H <= 32) or 4800 (H = 64).
+ *     F + Q <= 256); policy: fp32 MLP of dims {8, H, H, 2}, H in {16, 32, 64}; pop <= about 4800.
  *     World r: the unit square; agent a starts at rest at (u(x0), u(x1)) of Philox counter
  *     (a, r, generation, EVO_TAG_WORLD_AGENT) under reset_seed; item i (i < F food, else poison) that
  *     has been eaten c times lies at (u(x0), u(x1)) of counter (256 c + i, r, generation,
