@@ -45,7 +45,8 @@ def _bits(a):
 
 @pytest.mark.parametrize("pop,worlds,n_food,n_poison,radius", [(130, 3, 5, 7, 0.0625), (1024, 5, 24, 24, 0.03125),
                                                                (2, 1, 1, 1, 0.25), (77, 8, 100, 156, 0.015625),
-                                                               (2500, 2, 24, 24, 0.03125)])
+                                                               (2500, 2, 24, 24, 0.03125),
+                                                               (4800, 1, 24, 24, 0.03125)])   # the most that fit
 def test_one_step_from_a_given_state_is_bit_exact(evo, pop, worlds, n_food, n_poison, radius):
     w = dict(forage.WORLD_DEFAULT, n_food=n_food, n_poison=n_poison, radius=radius)
     n_items = n_food + n_poison
