@@ -21,6 +21,12 @@ the world below is this build's own definition (a reading, not the original envi
   agent that touches it; a touched item is eaten once and lies at its next position from the next
   step on.  Agents interact through the items they take from each other and through what they see.
 * Fitness of member a: its summed reward, averaged over the worlds.
+* Single-agent form (the same paragraph's first sentence: one agent collecting food and avoiding
+  poison): every member lives alone in its own copy of each world -- a world with one agent, agent
+  index 0, so all members start at the same place among the same items (identical initial
+  observations, Section 4) and part ways through what they eat.  With nobody else around, the offset
+  to the nearest other agent is (0, 0).  `rollout_solitary` is that definition spelt out: the
+  shared-world roll-out of each member on its own.
 
 Precision: the task fixes the world's arithmetic as IEEE binary32 with every operation rounded on
 its own (no fused multiply-add), because it decides integers (who is nearest, who touches); the
@@ -129,4 +135,19 @@ def rollout(params, dims, acts, seed, generation, n_worlds, steps, w=WORLD_DEFAU
     fit = total.mean(axis=0)
     if return_details:
         return fit, total, details
+    return fit
+
+
+def rollout_solitary(params, dims, acts, seed, generation, n_worlds, steps, w=WORLD_DEFAULT, return_details=False):
+    """fitness[pop] (fp64) when every member lives alone in its own copy of each world."""
+    params = np.asarray(params, dtype=np.float64)
+    fit = np.empty(params.shape[0])
+    totals, details = [], []
+    for m in range(params.shape[0]):
+        f, total, det = rollout(params[m:m + 1], dims, acts, seed, generation, n_worlds, steps, w, return_details=True)
+        fit[m] = f[0]
+        totals.append(total[:, 0])
+        details.append(det)
+    if return_details:
+        return fit, np.stack(totals, axis=1), details      # total[world, member]; details[member][world]
     return fit

@@ -3,7 +3,7 @@
 Strings the pieces together in the order the paper's training loop has them (Section 2,
 Figure 2 and the trainer / simulation-manager paragraph; Section 4's ask / tell):
 ask -> evaluate every member with the global policy on the vectorised task -> tell.
-`task` is a plain dict: kind in {"classify","regress","cartpole","sphere","seq2seq","forage"}, the policy
+`task` is a plain dict: kind in {"classify","regress","cartpole","sphere","seq2seq","forage","forage_solo"}, the policy
 description and the task's input arrays.  parity unpinned as a whole: the paper prints no
 value of any generation; every stage it calls is pinned on its own.
 """
@@ -21,6 +21,9 @@ def evaluate(task, params, seed, generation):
         return tasks.cartpole_rollout(params, task["dims"], task["acts"], seed, generation,
                                       task["n_rollouts"], task["steps"], task.get("cp", tasks.CP_DEFAULT),
                                       task.get("init_scale", 0.2))
+    if kind == "forage_solo":
+        return forage.rollout_solitary(params, task["dims"], task["acts"], seed, generation, task["n_worlds"],
+                                       task["steps"], task.get("world", forage.WORLD_DEFAULT))
     if kind == "forage":
         return forage.rollout(params, task["dims"], task["acts"], seed, generation, task["n_worlds"], task["steps"],
                               task.get("world", forage.WORLD_DEFAULT))
