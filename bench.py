@@ -38,13 +38,14 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg5": 4304870251,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
     "seq2seq": 876919192,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
     "forage": 6944738,     # profiles/world_step_kernel_forage.md (per step launch: weights 5.8 MB + positions)
+    "forage_solo": None,   # one launch per episode: the weights are read once (5.8 MB), everything else stays on chip
 }
 
 
 # Timed generations per workload when --steps is not given (about a second of GPU time or less) and
 # the population of the oracle's bounded sample (about 10-30 s of CPU time on one core).
-DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20, "forage": 20}
-ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32, "forage": 128}
+DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20, "forage": 20, "forage_solo": 50}
+ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32, "forage": 128, "forage_solo": 24}
 ORACLE_SAMPLE_GENERATIONS = {"cfg1": 600}
 
 
@@ -160,21 +161,27 @@ def _build_workload(name, seed, batch=None):
         wl["desc"] = ("seq2seq: LSTM encoder-decoder H=128 (P=145674) on three-digit addition strings, pop 1024, "
                       "128 strings per member")
         wl["dtype"] = "f32"
-    elif name == "forage":
+    elif name in ("forage", "forage_solo"):
+        solo = name == "forage_solo"
         wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
         w = wc.world_dict(c.world)
         cp = tuple(c.world)
         wl["task"] = lambda t: with_work_cached(lambda work: evo.make_task_desc(
-            evo.EVO_TASK_FORAGE, n_rollouts=c.n_rollouts, reset_seed=seed, generation=t + 1, cp=cp, work=work,
+            evo.EVO_TASK_FORAGE_SOLO if solo else evo.EVO_TASK_FORAGE, n_rollouts=c.n_rollouts, reset_seed=seed, generation=t + 1, cp=cp, work=work,
             generation_dev=wl.get("gen_dev")))
         # one launch = one step of every world: per agent the scan over the others (2 sub, 2 mul, add, compare per
         # candidate) and over the items (twice: sensing and touching), and the policy's multiply-adds
         n_items = w["n_food"] + w["n_poison"]
-        per_agent = 6.0 * c.pop + 2 * 6.0 * n_items + 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(3))
-        wl["roofline"] = ("alu", per_agent * c.pop * c.n_rollouts, PEAK_ALU_F32_TF, "TFLOP/s")
-        wl["launches"] = c.steps      # the stage is `steps` launches of the step kernel (+ reset and finish)
-        wl["desc"] = ("forage: the population as %d agents of each of %d shared worlds, fp32 MLP 8-32-32-2, %d steps "
-                      "(one launch per step)" % (c.pop, c.n_rollouts, c.steps))
+        per_agent = (0.0 if solo else 6.0 * c.pop) + 2 * 6.0 * n_items + 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(3))
+        if solo:      # the whole episode is one launch
+            wl["roofline"] = ("alu", per_agent * c.pop * c.n_rollouts * c.steps, PEAK_ALU_F32_TF, "TFLOP/s")
+            wl["desc"] = ("forage_solo: every member alone in its own copy of each of %d worlds, %d members, fp32 MLP "
+                          "8-32-32-2, %d steps (one launch per episode)" % (c.n_rollouts, c.pop, c.steps))
+        else:
+            wl["roofline"] = ("alu", per_agent * c.pop * c.n_rollouts, PEAK_ALU_F32_TF, "TFLOP/s")
+            wl["launches"] = c.steps      # the stage is `steps` launches of the step kernel (+ reset and finish)
+            wl["desc"] = ("forage: the population as %d agents of each of %d shared worlds, fp32 MLP 8-32-32-2, %d "
+                          "steps (one launch per step)" % (c.pop, c.n_rollouts, c.steps))
         wl["dtype"] = "f32"
     else:
         raise SystemExit("unknown workload %r" % name)
@@ -214,8 +221,8 @@ def _cpu_baseline(name, seed):
         q, a = gen.addition_batch(c.data_seed, 1, c.B, c.digits)
         task = {"kind": "seq2seq", "H": c.dims[1], "query": q, "answer": a}
         evals = sample_pop * c.B
-    elif name == "forage":      # a smaller population is a smaller crowd in each world, not a slice of the big one
-        task = {"kind": "forage", "dims": c.dims, "acts": c.acts, "n_worlds": c.n_rollouts, "steps": c.steps,
+    elif name in ("forage", "forage_solo"):      # forage: a smaller population is a smaller crowd in each world
+        task = {"kind": name, "dims": c.dims, "acts": c.acts, "n_worlds": c.n_rollouts, "steps": c.steps,
                 "world": wc.world_dict(c.world)}
         evals = sample_pop * c.n_rollouts * c.steps
     else:
@@ -238,7 +245,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq", "forage"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq", "forage", "forage_solo"])
     ap.add_argument("--seed", type=int, default=20220509)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=None,

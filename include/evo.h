@@ -44,7 +44,7 @@ enum { EVO_F32 = 0, EVO_BF16 = 1 };                                   /* paramet
 enum { EVO_ACT_NONE = 0, EVO_ACT_TANH = 1, EVO_ACT_RELU = 2 };
 enum { EVO_POLICY_MLP = 0, EVO_POLICY_CONVNET = 1, EVO_POLICY_LSTM_SEQ2SEQ = 2 };
 enum { EVO_TASK_CLASSIFY = 0, EVO_TASK_REGRESS = 1, EVO_TASK_CARTPOLE = 2, EVO_TASK_SPHERE = 3, EVO_TASK_SEQ2SEQ = 4,
-       EVO_TASK_FORAGE = 5 };
+       EVO_TASK_FORAGE = 5, EVO_TASK_FORAGE_SOLO = 6 };
 enum { EVO_TAG_NOISE = 0, EVO_TAG_RESET = 1, EVO_TAG_WORLD_AGENT = 2, EVO_TAG_WORLD_ITEM = 3 }; /* Philox stream tags */
 enum { EVO_OPT_ADAM = 0, EVO_OPT_CLIPUP = 1, EVO_OPT_MOMENTUM = 2 };  /* optimizer of mu    */
 #define EVO_POP_MAX 4096
@@ -264,10 +264,15 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *     touched: +1 (food) or -1 (poison) to every agent that touches it; a touched item has been eaten
  *     once more from the next step on.  `steps` launches of one kernel (agents of a world depend on
  *     each other's positions every step); work_dev holds the worlds' state.
+ *   FORAGE_SOLO  the single-agent form of the same world (the paragraph's first sentence): every member lives
+ *             alone in its own copy of each world, i.e. a FORAGE world with one agent (agent index 0): all
+ *             members start at the same place among the same items and part ways through what they eat; the
+ *             offset to the nearest other agent is (0, 0).  Same cp, policy and fitness; pop >= 1; the whole
+ *             episode is one launch (weights in registers, the member's items in LDS).
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
-  int32_t n_rollouts;          /* CARTPOLE: roll-outs per member (1..64); FORAGE: worlds     */
+  int32_t n_rollouts;          /* CARTPOLE: roll-outs per member (1..64); FORAGE(_SOLO): worlds */
   int32_t B;                   /* CLASSIFY / REGRESS: samples per member                     */
   int32_t P;                   /* SPHERE: parameters per member                              */
   uint64_t reset_seed;         /* CARTPOLE, FORAGE                                           */
@@ -319,8 +324,9 @@ int evo_pgpe_gradients(pgpe_state* st, const float* fitness_dev, float* gmu_dev,
 int evo_forage_step(const task_desc* td, int32_t pop, const float* pos_dev, const float* vel_dev,
                     const uint32_t* counts_dev, const float* action_dev, float* obs_dev, float* next_pos_dev,
                     float* next_vel_dev, int32_t* reward_dev, uint32_t* hit_dev, void* stream);
-/* State of a FORAGE rollout after `steps` steps: positions and velocities [worlds][pop][2], summed
- * rewards [worlds][pop] (int32), times eaten [worlds][F+Q]; any may be NULL. */
+/* State of a FORAGE or FORAGE_SOLO rollout after `steps` steps: positions and velocities [worlds][pop][2],
+ * summed rewards [worlds][pop] (int32), times eaten [worlds][F+Q] (FORAGE_SOLO: [worlds][pop][F+Q]); any may
+ * be NULL. */
 int evo_forage_state(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
                      float* pos_dev, float* vel_dev, int32_t* reward_dev, uint32_t* counts_dev, void* stream);
 /* One cart-pole step for n independent (state, action) pairs: state_dev[n][4], action_dev[n]

@@ -12,7 +12,7 @@ from ._lib import pgpe_config, policy_desc, task_desc
 EVO_F32, EVO_BF16 = 0, 1
 EVO_ACT_NONE, EVO_ACT_TANH, EVO_ACT_RELU = 0, 1, 2
 EVO_POLICY_MLP, EVO_POLICY_CONVNET, EVO_POLICY_LSTM_SEQ2SEQ = 0, 1, 2
-EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE, EVO_TASK_SEQ2SEQ, EVO_TASK_FORAGE = range(6)
+EVO_TASK_CLASSIFY, EVO_TASK_REGRESS, EVO_TASK_CARTPOLE, EVO_TASK_SPHERE, EVO_TASK_SEQ2SEQ, EVO_TASK_FORAGE, EVO_TASK_FORAGE_SOLO = range(7)
 EVO_TAG_NOISE, EVO_TAG_RESET, EVO_TAG_WORLD_AGENT, EVO_TAG_WORLD_ITEM = 0, 1, 2, 3
 EVO_OPT_ADAM, EVO_OPT_CLIPUP, EVO_OPT_MOMENTUM = 0, 1, 2
 

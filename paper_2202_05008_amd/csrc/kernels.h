@@ -65,6 +65,14 @@ int launch_forage_step(int pop, int worlds, const float* cp, uint64_t seed, uint
                        const float* vel, const uint32_t* counts, const float* actions, float* obs_out, float* pos_out,
                        float* vel_out, int32_t* reward_out, uint32_t* hit_out, hipStream_t s);
 
+// The single-agent form: every member alone in its own copy of each world, the whole episode in one launch.
+// counts_out is [worlds][pop][items] here.
+int forage_solo_supported(const MlpShape& sh, int pop, int worlds, const float* cp);
+size_t forage_solo_workspace_bytes(int pop, int worlds);
+int launch_forage_solo(const MlpShape& sh, const float* params, int pop, int worlds, int steps, const float* cp,
+                       uint64_t seed, uint32_t gen, const uint32_t* gen_dev, void* work, float* fitness, float* pos_out,
+                       float* vel_out, int32_t* reward_out, uint32_t* counts_out, hipStream_t s);
+
 // LSTM sequence-to-sequence policy on shared token strings: fitness[pop] = -mean cross-entropy of
 // the answer digits and / or logits[pop][B][La][n_out].
 int lstm_supported(int V, int H, int n_out, int Lq, int La);

@@ -126,7 +126,7 @@ int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
 
 int check_task(const task_desc* td) {
   EVO_REQUIRE(td != nullptr, EVO_ERR_ARG, "task_desc is null");
-  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_FORAGE, EVO_ERR_ARG, "task: bad kind %d",
+  EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_FORAGE_SOLO, EVO_ERR_ARG, "task: bad kind %d",
               td->kind);
   return EVO_OK;
 }
@@ -137,6 +137,7 @@ extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc
   if (check_task(td) || pop < 1) return 0;
   if (td->kind == EVO_TASK_CARTPOLE || td->kind == EVO_TASK_SEQ2SEQ) return 0;
   if (td->kind == EVO_TASK_FORAGE) return forage_workspace_bytes(pop, td->n_rollouts, td->cp);
+  if (td->kind == EVO_TASK_FORAGE_SOLO) return forage_solo_workspace_bytes(pop, td->n_rollouts);
   if (td->kind != EVO_TASK_SPHERE && check_policy(pd)) return 0;
   return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
 }
@@ -164,20 +165,30 @@ static int seq2seq_impl(const task_desc* td, const policy_desc* pd, const void* 
 static int forage_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
                        float* fitness_dev, float* pos_dev, float* vel_dev, int32_t* reward_dev, uint32_t* counts_dev,
                        void* stream) {
-  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_FORAGE, EVO_ERR_ARG, "forage: needs an EVO_TASK_FORAGE task");
+  EVO_REQUIRE(td != nullptr && (td->kind == EVO_TASK_FORAGE || td->kind == EVO_TASK_FORAGE_SOLO), EVO_ERR_ARG,
+              "forage: needs an EVO_TASK_FORAGE or EVO_TASK_FORAGE_SOLO task");
+  const bool solo = td->kind == EVO_TASK_FORAGE_SOLO;
   int rc = check_policy(pd);
   if (rc) return rc;
   EVO_REQUIRE(pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
               "forage: needs an fp32 MLP policy");
   EVO_REQUIRE(params_dev != nullptr && aligned16(params_dev), EVO_ERR_ARG,
               "forage: params_dev must be a 16-byte aligned device pointer");
-  EVO_REQUIRE(pop >= 2 && pop <= 65535, EVO_ERR_ARG, "forage: pop must be in [2,65535] (got %d)", pop);
+  EVO_REQUIRE(pop >= (solo ? 1 : 2) && pop <= 65535, EVO_ERR_ARG, "forage: pop must be in [%d,65535] (got %d)",
+              solo ? 1 : 2, pop);
   EVO_REQUIRE(steps >= 1 && steps <= (1 << 20), EVO_ERR_ARG, "forage: steps must be in [1, 2^20]");
   EVO_REQUIRE(td->work_dev != nullptr && aligned16(td->work_dev), EVO_ERR_ARG,
               "forage: work_dev must hold rollout_workspace_bytes() bytes, 16-byte aligned");
   MlpShape sh;
   rc = mlp_shape(pd, &sh);
   if (rc) return rc;
+  if (solo) {
+    rc = forage_solo_supported(sh, pop, td->n_rollouts, td->cp);
+    if (rc) return rc;
+    return launch_forage_solo(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp,
+                              td->reset_seed, td->generation, td->generation_dev, td->work_dev, fitness_dev, pos_dev,
+                              vel_dev, reward_dev, counts_dev, as_stream(stream));
+  }
   rc = forage_supported(sh, pop, td->n_rollouts, td->cp);
   if (rc) return rc;
   return launch_forage(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp, td->reset_seed,
@@ -203,7 +214,7 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P,
                          static_cast<float*>(td->work_dev), fitness_dev, s);
   }
-  if (td->kind == EVO_TASK_FORAGE) {
+  if (td->kind == EVO_TASK_FORAGE || td->kind == EVO_TASK_FORAGE_SOLO) {
     EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
     return forage_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, nullptr, stream);
   }

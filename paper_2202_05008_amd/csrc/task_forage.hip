@@ -433,6 +433,121 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   }
 }
 
+// ---- single-agent form: every member alone in its own copy of each world ---------------------------------
+// Nothing couples the members, so the whole episode runs in one launch (the fused roll-out of the control
+// tasks): wave = 8 members x 8 lanes in one world, the policy's weights in registers for all steps, each
+// member's item lists and item book in LDS.  A touched item is moved at once by the lane that found it
+// (every slot is judged by exactly one lane per step, after the step's sensing), which is "from the next
+// step on".  All members start at agent 0's place among the same items.
+struct SoloArgs {
+  const float* params;  // [pop][P]
+  int P, pop, worlds, steps;
+  int act[3];
+  WorldConst c;
+  uint32_t key0, key1, gen;
+  const uint32_t* gen_dev;
+  int32_t* reward;       // [worlds][pop]: the episode's summed reward
+  float2* pos_out;       // [worlds][pop] or null: state after the last step
+  float2* vel_out;       // [worlds][pop] or null
+  uint32_t* counts_out;  // [worlds][pop][n_items] or null: times each item was eaten
+};
+
+template <int H>
+__global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloArgs a) {
+  extern __shared__ float4 lds4[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int q = lane & (kLanesPerAgent - 1), la = lane / kLanesPerAgent;
+  const int agent = blockIdx.x * kAgentsPerBlock + la;
+  const int world = blockIdx.y * kWorldsPerBlock + wave;
+  const bool live = world < a.worlds && agent < a.pop;
+  const int n_food = a.c.n_food, n_items = a.c.n_items;
+  const int food_pad = pad_to(n_food, 16), poison_pad = pad_to(n_items - n_food, 16), slots = food_pad + poison_pad;
+  // per wave: [8 members][slots] positions, then [8 members][slots] counts
+  float2* s_item = reinterpret_cast<float2*>(lds4) + wave * kAgentsPerBlock * slots;
+  uint32_t* s_count = reinterpret_cast<uint32_t*>(reinterpret_cast<float2*>(lds4) + kWorldsPerBlock * kAgentsPerBlock * slots) +
+                      wave * kAgentsPerBlock * slots;
+  if (a.gen_dev) a.gen = *a.gen_dev;
+  const float inf = __builtin_inff();
+  auto item_of = [&](int slot) {  // item index of a slot of the two padded lists, or -1
+    const bool is_food = slot < food_pad;
+    const int i = is_food ? slot : n_food + slot - food_pad;
+    return i < (is_food ? n_food : n_items) ? i : -1;
+  };
+  auto place = [&](int i, uint32_t cnt) {
+    const u32x4 w = philox4x32_10(256u * cnt + static_cast<uint32_t>(i), static_cast<uint32_t>(world), a.gen, kTagItem,
+                                  a.key0, a.key1);
+    return make_float2(unit_open(w.x), unit_open(w.y));
+  };
+
+  PolicySlice<H> weights;
+  if (live) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
+  if (world < a.worlds) {  // the same fresh items for every member of the wave
+    for (int slot = lane; slot < slots; slot += 64) {
+      const int i = item_of(slot);
+      const float2 where = i >= 0 ? place(i, 0u) : make_float2(inf, inf);
+      for (int m = 0; m < kAgentsPerBlock; ++m) s_item[m * slots + slot] = where, s_count[m * slots + slot] = 0u;
+    }
+  }
+  __syncthreads();
+  if (!live) return;  // no barrier below this line; the lanes of a member stay together
+
+  float2* my_food = s_item + la * slots;
+  float2* my_poison = my_food + food_pad;
+  uint32_t* my_count = s_count + la * slots;
+  float2 p, v = make_float2(0.f, 0.f);
+  {
+    const u32x4 w = philox4x32_10(0u, static_cast<uint32_t>(world), a.gen, kTagAgent, a.key0, a.key1);
+    p = make_float2(unit_open(w.x), unit_open(w.y));
+  }
+  int reward = 0;
+#pragma unroll 1
+  for (int step = 0; step < a.steps; ++step) {
+    Nearest food{inf, 0x7fffffff}, poison{inf, 0x7fffffff};
+    for (int base = 0; base < food_pad; base += 16) nearest_scan16(food, p, my_food, base, q);
+    for (int base = 0; base < poison_pad; base += 16) nearest_scan16(poison, p, my_poison, base, q);
+    const float2 f = nearest_finish(food, p, my_food, food_pad);
+    const float2 g = nearest_finish(poison, p, my_poison, poison_pad);
+    const float obs[kObs] = {v.x, v.y, f.x, f.y, g.x, g.y, 0.f, 0.f};  // nobody else is there
+    const float2 action = policy_forward<H>(weights, a.act, lane, obs);
+    move_axis(a.c, action.x, p.x, v.x);
+    move_axis(a.c, action.y, p.y, v.y);
+    // touches: the lane that judges a slot also moves the item it finds eaten
+    for (int base = 0; base < slots; base += 2 * kLanesPerAgent) {
+      const float4 it = *reinterpret_cast<const float4*>(my_food + base + 2 * q);
+      const bool hit0 = dist2(it.x - p.x, it.y - p.y) <= a.c.r2, hit1 = dist2(it.z - p.x, it.w - p.y) <= a.c.r2;
+      if (hit0 || hit1) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          if (k == 0 ? hit0 : hit1) {
+            const int slot = base + 2 * q + k, i = item_of(slot);
+            reward += slot < food_pad ? 1 : -1;
+            const uint32_t cnt = my_count[slot] + 1u;
+            my_count[slot] = cnt;
+            my_food[slot] = place(i, cnt);
+          }
+        }
+      }
+    }
+    // the next step's sensing reads what this step's touches wrote (same wave: LDS keeps program order)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  reward = agent_sum(reward);
+  const size_t me = static_cast<size_t>(world) * a.pop + agent;
+  if (q == 0) {
+    a.reward[me] = reward;
+    if (a.pos_out) a.pos_out[me] = p;
+    if (a.vel_out) a.vel_out[me] = v;
+  }
+  if (a.counts_out)
+    for (int slot = q; slot < slots; slot += kLanesPerAgent) {
+      const int i = item_of(slot);
+      if (i >= 0) a.counts_out[me * n_items + i] = my_count[slot];
+    }
+}
+
 struct ResetArgs {
   int pop, worlds, n_items;
   uint32_t key0, key1, gen;
@@ -628,6 +743,79 @@ int launch_forage(const MlpShape& sh, const float* params, int pop, int worlds, 
                        counts[steps & 1], hits[(steps - 1) % 3], static_cast<int>(nb), counts_out);
     rc = check_launch("world_counts_kernel");
     if (rc) return rc;
+  }
+  return EVO_OK;
+}
+
+static size_t solo_lds_bytes(int n_food, int n_items) {
+  const size_t slots = pad_to(n_food, 16) + pad_to(n_items - n_food, 16);
+  return static_cast<size_t>(kWorldsPerBlock) * kAgentsPerBlock * slots * (sizeof(float2) + sizeof(uint32_t));
+}
+
+template <int H>
+static int launch_solo(const SoloArgs& a, hipStream_t s) {
+  const size_t lds = solo_lds_bytes(a.c.n_food, a.c.n_items);
+  static bool raised[64] = {};
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
+    raised[device] = e == hipSuccess;
+  }
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the episode kernel failed: %s",
+              hipGetErrorString(e));
+  const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
+  hipLaunchKernelGGL(world_solo_kernel<H>, grid, dim3(64 * kWorldsPerBlock), lds, s, a);
+  return check_launch("world_solo_kernel");
+}
+
+int forage_solo_supported(const MlpShape& sh, int pop, int worlds, const float* cp) {
+  WorldConst c;
+  int rc = fill_const(cp, &c);
+  if (rc) return rc;
+  EVO_REQUIRE(sh.n_layers == 3 && sh.dims[0] == kObs && sh.dims[3] == 2 && sh.dims[1] == sh.dims[2] &&
+                  (sh.dims[1] == 16 || sh.dims[1] == 32 || sh.dims[1] == 64),
+              EVO_ERR_UNSUPPORTED, "forage: the policy must be an MLP of dims {8, H, H, 2} with H = 16, 32 or 64");
+  EVO_REQUIRE(pop >= 1, EVO_ERR_ARG, "forage: pop must be positive (got %d)", pop);
+  EVO_REQUIRE(worlds >= 1 && worlds <= 4096, EVO_ERR_ARG, "forage: n_rollouts (worlds) must be in [1, 4096]");
+  EVO_REQUIRE(solo_lds_bytes(c.n_food, c.n_items) <= kMaxLdsBytes, EVO_ERR_UNSUPPORTED, "forage: too many items");
+  return EVO_OK;
+}
+
+size_t forage_solo_workspace_bytes(int pop, int worlds) {
+  if (pop < 1 || worlds < 1) return 0;
+  return (static_cast<size_t>(pop) * worlds * sizeof(int32_t) + 255) & ~size_t(255);
+}
+
+int launch_forage_solo(const MlpShape& sh, const float* params, int pop, int worlds, int steps, const float* cp,
+                       uint64_t seed, uint32_t gen, const uint32_t* gen_dev, void* work, float* fitness, float* pos_out,
+                       float* vel_out, int32_t* reward_out, uint32_t* counts_out, hipStream_t s) {
+  SoloArgs a;
+  int rc = fill_const(cp, &a.c);
+  if (rc) return rc;
+  a.params = params, a.P = sh.P, a.pop = pop, a.worlds = worlds, a.steps = steps;
+  a.act[0] = sh.act[0], a.act[1] = sh.act[1], a.act[2] = sh.act[2];
+  a.key0 = static_cast<uint32_t>(seed), a.key1 = static_cast<uint32_t>(seed >> 32), a.gen = gen, a.gen_dev = gen_dev;
+  a.reward = static_cast<int32_t*>(work);
+  a.pos_out = reinterpret_cast<float2*>(pos_out), a.vel_out = reinterpret_cast<float2*>(vel_out);
+  a.counts_out = counts_out;
+  switch (sh.dims[1]) {
+    case 16: rc = launch_solo<16>(a, s); break;
+    case 32: rc = launch_solo<32>(a, s); break;
+    case 64: rc = launch_solo<64>(a, s); break;
+    default: return fail(EVO_ERR_UNSUPPORTED, "forage: the hidden width must be 16, 32 or 64");
+  }
+  if (rc) return rc;
+  if (fitness) {
+    hipLaunchKernelGGL(world_finish_kernel, dim3((pop + 255) / 256), dim3(256), 0, s, a.reward, pop, worlds, fitness);
+    rc = check_launch("world_finish_kernel");
+    if (rc) return rc;
+  }
+  if (reward_out) {
+    hipError_t e = hipMemcpyAsync(reward_out, a.reward, static_cast<size_t>(worlds) * pop * sizeof(int32_t),
+                                  hipMemcpyDeviceToDevice, s);
+    EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: copying the rewards failed: %s", hipGetErrorString(e));
   }
   return EVO_OK;
 }

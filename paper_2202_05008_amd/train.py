@@ -78,18 +78,20 @@ def _tasks(name, c, seed, dev):
         tds = [strings(g + 1) for g in range(16)]
         test_td = strings(1000)
         return pd, (lambda t: tds[t % len(tds)]), (lambda t: test_td)
-    if name == "forage":
+    if name in ("forage", "forage_solo"):
+        kind = evo.EVO_TASK_FORAGE if name == "forage" else evo.EVO_TASK_FORAGE_SOLO
         pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
         work = {}
 
         def world(s, t, pop):      # one workspace per population size, a fresh descriptor per generation
-            make = lambda w: evo.make_task_desc(evo.EVO_TASK_FORAGE, n_rollouts=c.n_rollouts, reset_seed=s, generation=t,
+            make = lambda w: evo.make_task_desc(kind, n_rollouts=c.n_rollouts, reset_seed=s, generation=t,
                                                 cp=tuple(c.world), work=w)
             if pop not in work:
                 work[pop] = torch.empty(evo.rollout_workspace_bytes(make(None), pd, pop), dtype=torch.uint8, device=dev)
             return make(work[pop])
 
-        return pd, (lambda t: world(seed, t, c.pop)), (lambda t: world(seed + 1, 1, FORAGE_TEST_POP))
+        test_pop = FORAGE_TEST_POP if name == "forage" else 1
+        return pd, (lambda t: world(seed, t, c.pop)), (lambda t: world(seed + 1, 1, test_pop))
     raise SystemExit("unknown workload %r" % name)
 
 

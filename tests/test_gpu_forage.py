@@ -28,8 +28,9 @@ def _cp(w):
     return (w["dt"], w["thrust"], w["drag"], w["vmax"], w["radius"], float(w["n_food"]), float(w["n_poison"]))
 
 
-def _task(evo, w, worlds, pop, pd=None, generation=3, seed=SEED):
-    make = lambda work: evo.make_task_desc(evo.EVO_TASK_FORAGE, n_rollouts=worlds, reset_seed=seed,
+def _task(evo, w, worlds, pop, pd=None, generation=3, seed=SEED, kind=None):
+    kind = evo.EVO_TASK_FORAGE if kind is None else kind
+    make = lambda work: evo.make_task_desc(kind, n_rollouts=worlds, reset_seed=seed,
                                            generation=generation, cp=_cp(w), work=work)
     if pd is None:
         return make(None)
@@ -98,12 +99,12 @@ def _params_constant_action(pop, dims, rng):
     return params
 
 
-def _run_state(evo, td, pd, params, pop, worlds, n_items, steps):
+def _run_state(evo, td, pd, params, pop, worlds, n_items, steps, solo=False):
     f32, i32 = torch.float32, torch.int32
     pos = torch.empty(worlds, pop, 2, dtype=f32, device="cuda")
     vel = torch.empty(worlds, pop, 2, dtype=f32, device="cuda")
     reward = torch.empty(worlds, pop, dtype=i32, device="cuda")
-    counts = torch.empty(worlds, n_items, dtype=i32, device="cuda")
+    counts = torch.empty((worlds, pop, n_items) if solo else (worlds, n_items), dtype=i32, device="cuda")
     evo.evo_forage_state(td, pd, params, pop, steps, pos, vel, reward, counts)
     fit = torch.empty(pop, dtype=f32, device="cuda")
     evo.rollout(td, pd, params, pop, steps, fit)
@@ -233,3 +234,70 @@ def test_errors_are_reported(evo):
         evo.rollout(_task(evo, w, 2, 6000, good), good, big, 6000, 5, torch.empty(6000, dtype=torch.float32, device="cuda"))
     evo.rollout(td, good, params, 64, 5, fit)            # and the good case still runs
     assert torch.isfinite(fit).all()
+
+
+# ---- the single-agent form: every member alone in its own copy of each world, one launch per episode ----
+
+@pytest.mark.parametrize("pop,worlds,H,steps,n_food,n_poison", [(13, 3, 16, 60, 9, 6), (8, 1, 32, 45, 24, 24),
+                                                                 (5, 6, 64, 35, 3, 40), (1, 1, 32, 30, 1, 1)])
+def test_solo_rollout_with_constant_actions_is_bit_exact(evo, pop, worlds, H, steps, n_food, n_poison):
+    w = dict(forage.WORLD_DEFAULT, n_food=n_food, n_poison=n_poison, radius=0.125)
+    dims, acts = (8, H, H, 2), (evo.EVO_ACT_TANH, evo.EVO_ACT_RELU, evo.EVO_ACT_NONE)
+    params = _params_constant_action(pop, dims, np.random.default_rng(H + pop))
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    td = _task(evo, w, worlds, pop, pd, kind=evo.EVO_TASK_FORAGE_SOLO)
+    n_items = n_food + n_poison
+    pos, vel, reward, counts, fit = _run_state(evo, td, pd, dev(params), pop, worlds, n_items, steps, solo=True)
+    want_fit, total, details = forage.rollout_solitary(params, dims, acts, SEED, 3, worlds, steps, w, return_details=True)
+    for m in range(pop):
+        for r in range(worlds):
+            assert np.array_equal(_bits(pos[r, m]), _bits(details[m][r][0][0])), "position of member %d, world %d" % (m, r)
+            assert np.array_equal(_bits(vel[r, m]), _bits(details[m][r][1][0]))
+            assert np.array_equal(counts[r, m], details[m][r][2]), "item book of member %d, world %d" % (m, r)
+    assert np.array_equal(reward, total)
+    assert counts.sum() > 0 or n_items < 10, "items must be eaten"
+    np.testing.assert_allclose(fit, want_fit, rtol=1e-6, atol=0)
+
+
+def test_solo_policy_in_the_loop(evo):
+    pop, worlds = 24, 2
+    w = dict(forage.WORLD_DEFAULT, radius=0.0625)
+    dims, acts = (8, 32, 32, 2), (1, 1, 1)
+    params = _random_policies(pop, dims, 0.5, 31)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    td = _task(evo, w, worlds, pop, pd, kind=evo.EVO_TASK_FORAGE_SOLO)
+    pos, vel, reward, counts, fit = _run_state(evo, td, pd, dev(params), pop, worlds, 48, 1, solo=True)
+    _, total, details = forage.rollout_solitary(params, dims, acts, SEED, 3, worlds, 1, w, return_details=True)
+    want_pos = np.stack([np.stack([details[m][r][0][0] for m in range(pop)]) for r in range(worlds)])
+    want_vel = np.stack([np.stack([details[m][r][1][0] for m in range(pop)]) for r in range(worlds)])
+    np.testing.assert_allclose(pos, want_pos, rtol=0, atol=1e-7)
+    np.testing.assert_allclose(vel, want_vel, rtol=0, atol=1e-7)
+    assert np.array_equal(reward, total) and np.abs(vel).max() > 1e-3
+    # 25 steps: most members still on the oracle's path (a flipped nearest item is a legitimate discontinuity)
+    pos, vel, reward, counts, fit = _run_state(evo, td, pd, dev(params), pop, worlds, 48, 25, solo=True)
+    _, total, details = forage.rollout_solitary(params, dims, acts, SEED, 3, worlds, 25, w, return_details=True)
+    want_pos = np.stack([np.stack([details[m][r][0][0] for m in range(pop)]) for r in range(worlds)])
+    close = np.abs(pos - want_pos).max(axis=-1) < 1e-5
+    assert close.mean() > 0.9 and (reward == total).mean() > 0.9
+
+
+def test_solo_full_size_properties(evo):
+    """1024 members x 8 worlds x 500 steps in one launch: repeatable bit for bit, inside the square, whole-number
+    rewards; members with the same policy get the same result (their worlds are identical)."""
+    c = CONFIGS["forage"]
+    w = wc.world_dict(c.world)
+    n_items = w["n_food"] + w["n_poison"]
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+    td = _task(evo, w, c.n_rollouts, c.pop, pd, kind=evo.EVO_TASK_FORAGE_SOLO)
+    host_params = _random_policies(c.pop, c.dims, 0.3, 5)
+    host_params[1::2] = host_params[0::2]                  # pairs of identical policies
+    params = dev(host_params)
+    a = _run_state(evo, td, pd, params, c.pop, c.n_rollouts, n_items, c.steps, solo=True)
+    b = _run_state(evo, td, pd, params, c.pop, c.n_rollouts, n_items, c.steps, solo=True)
+    for x, y in zip(a, b):
+        assert np.array_equal(_bits(x), _bits(y)), "two runs of the same roll-out differ"
+    pos, vel, reward, counts, fit = a
+    assert pos.min() >= 0 and pos.max() <= 1 and np.abs(vel).max() <= w["vmax"]
+    np.testing.assert_array_equal(fit * c.n_rollouts, reward.sum(axis=0).astype(np.float32))
+    assert np.array_equal(reward[:, 0::2], reward[:, 1::2]) and np.array_equal(_bits(pos[:, 0::2]), _bits(pos[:, 1::2]))
+    assert counts.sum() > 0 and np.array_equal(counts[:, :, :w["n_food"]].sum(axis=2) - counts[:, :, w["n_food"]:].sum(axis=2), reward)

@@ -151,7 +151,7 @@ def test_seq2seq_training_improves(evo):
 
 
 @pytest.mark.parametrize("workload,generations", [("cfg1", 12), ("cfg2", 2), ("cfg3", 1), ("cfg4", 2), ("cfg5", 2),
-                                                  ("seq2seq", 2), ("forage", 2)])
+                                                  ("seq2seq", 2), ("forage", 2), ("forage_solo", 2)])
 def test_train_command_line(evo, tmp_path, capsys, workload, generations):
     """The command line of the training shell on every named workload: one JSON line per generation,
     finite numbers, and (cfg1) a run resumed from its checkpoint goes on from the right generation."""

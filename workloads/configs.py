@@ -13,6 +13,7 @@ from typing import Tuple
 ACT_NONE, ACT_TANH, ACT_RELU = 0, 1, 2
 POLICY_MLP, POLICY_CONVNET, POLICY_LSTM_SEQ2SEQ = 0, 1, 2
 TASK_CLASSIFY, TASK_REGRESS, TASK_CARTPOLE, TASK_SPHERE, TASK_SEQ2SEQ, TASK_FORAGE = 0, 1, 2, 3, 4, 5
+TASK_FORAGE_SOLO = 6
 DT_F32, DT_BF16 = 0, 1
 
 
@@ -77,7 +78,7 @@ class WorkloadConfig:
     @property
     def evals_per_generation(self) -> int:
         """member-evals: pop x samples, or env-steps, or pop x P parameter samples."""
-        if self.task_kind in (TASK_CARTPOLE, TASK_FORAGE):
+        if self.task_kind in (TASK_CARTPOLE, TASK_FORAGE, TASK_FORAGE_SOLO):
             return self.pop * self.n_rollouts * self.steps
         if self.task_kind == TASK_SPHERE:
             return self.pop
@@ -107,4 +108,8 @@ CONFIGS = {
     "forage": WorkloadConfig("forage", pop=1024, policy_kind=POLICY_MLP, dims=(8, 32, 32, 2),
                              acts=(ACT_TANH, ACT_TANH, ACT_TANH), dtype=DT_F32, task_kind=TASK_FORAGE,
                              n_rollouts=8, steps=500),
+    # the single-agent form of the same world: every member alone in its own copy of each world
+    "forage_solo": WorkloadConfig("forage_solo", pop=1024, policy_kind=POLICY_MLP, dims=(8, 32, 32, 2),
+                                  acts=(ACT_TANH, ACT_TANH, ACT_TANH), dtype=DT_F32, task_kind=TASK_FORAGE_SOLO,
+                                  n_rollouts=8, steps=500),
 }
