@@ -25,10 +25,10 @@ class _Run:
 
     def __init__(self, evo, kind, device_t, optimizer=None):
         self.evo = evo
-        c = CONFIGS[{"classify": "cfg1", "cartpole": "cfg3", "forage": "forage"}[kind]]
+        c = CONFIGS[{"classify": "cfg1", "cartpole": "cfg3", "forage": "forage", "forage_solo": "forage"}[kind]]
         self.c, self.kind = c, kind
         self.pop = c.pop if kind == "classify" else 64
-        self.steps = {"classify": 1, "cartpole": 20, "forage": 12}[kind]
+        self.steps = {"classify": 1, "cartpole": 20, "forage": 12, "forage_solo": 12}[kind]
         kw = {} if optimizer is None else {"optimizer": optimizer}
         self.pg = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=self.pop, **kw), gen.initial_mu(c.data_seed, c.P))
         self.gen_dev = self.pg.device_generation() if device_t else None
@@ -43,9 +43,10 @@ class _Run:
             self.work = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
             self.td = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=self.x, target=self.y, work=self.work)
 
-        if kind == "forage":
+        if kind in ("forage", "forage_solo"):
+            task_kind = evo.EVO_TASK_FORAGE if kind == "forage" else evo.EVO_TASK_FORAGE_SOLO
             cp = tuple(c.world[:4]) + (0.125,) + tuple(c.world[5:])        # a wide touch radius: rewards within 12 steps
-            self.make = lambda t, work: evo.make_task_desc(evo.EVO_TASK_FORAGE, n_rollouts=3, reset_seed=SEED + 1,
+            self.make = lambda t, work: evo.make_task_desc(task_kind, n_rollouts=3, reset_seed=SEED + 1,
                                                            generation=t, cp=cp, work=work, generation_dev=self.gen_dev)
             n = evo.rollout_workspace_bytes(self.make(1, None), self.pd, self.pop)
             self.work = torch.empty(n, dtype=torch.uint8, device="cuda")
@@ -53,7 +54,7 @@ class _Run:
     def task(self, t):
         if self.kind == "classify":
             return self.td
-        if self.kind == "forage":
+        if self.kind in ("forage", "forage_solo"):
             return self.make(t, self.work)
         return self.evo.make_task_desc(self.evo.EVO_TASK_CARTPOLE, n_rollouts=self.c.n_rollouts, reset_seed=SEED + 1,
                                        generation=t, cp=self.c.cartpole, init_scale=self.c.init_scale,
@@ -73,12 +74,12 @@ def _same_bits(a, b, what):
         assert np.array_equal(p.view(np.uint32), q.view(np.uint32)), "%s: %s differs" % (what, name)
 
 
-@pytest.mark.parametrize("kind", ["classify", "cartpole", "forage"])
+@pytest.mark.parametrize("kind", ["classify", "cartpole", "forage", "forage_solo"])
 def test_device_generation_matches_host_generation(evo, kind):
     a, b = _Run(evo, kind, False), _Run(evo, kind, True)
     for t in range(1, 7):
         a.generation(t), b.generation(0)          # in device mode the task's host-side t is not used
-        if kind == "forage":                      # whole-number rewards: the worlds of generation t, or not
+        if kind in ("forage", "forage_solo"):     # whole-number rewards: the worlds of generation t, or not
             assert np.array_equal(host(a.fitness), host(b.fitness)) and np.abs(host(a.fitness)).sum() > 0
             continue
         sa, sb = a.snapshot(), b.snapshot()
@@ -94,7 +95,7 @@ def test_device_generation_matches_host_generation(evo, kind):
 
 
 @pytest.mark.parametrize("kind,optimizer", [("classify", None), ("cartpole", None), ("classify", "clipup"),
-                                            ("forage", None)])
+                                            ("forage", None), ("forage_solo", None)])
 def test_graph_replays_are_successive_generations(evo, kind, optimizer):
     opt = None if optimizer is None else evo.EVO_OPT_CLIPUP
     warm = _Run(evo, kind, True, opt)
