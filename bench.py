@@ -38,7 +38,7 @@ MEASURED_TRAFFIC_BYTES = {
     "cfg5": 4304870251,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
     "seq2seq": 876919192,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
     "forage": 6944738,     # profiles/world_step_kernel_forage.md (per step launch: weights 5.8 MB + positions)
-    "forage_solo": None,   # one launch per episode: the weights are read once (5.8 MB), everything else stays on chip
+    "forage_solo": 5993764,  # profiles/world_solo_kernel_forage_solo.md (the weights, read once; the rest stays on chip)
 }
 
 

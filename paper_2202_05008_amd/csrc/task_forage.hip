@@ -61,31 +61,37 @@ struct StepArgs {
   float* obs_out;              // test hook: [worlds][pop][8]
 };
 
-// Value of the partner lane in the three butterfly stages that cover an agent's eight lanes, as
+// Value of the partner lane in the butterfly stages that cover an agent's eight (or sixteen) lanes, as
 // data-parallel-primitive moves (register to register, no trip through LDS): stage 0 swaps
 // neighbours, stage 1 swaps pairs (both quad permutations), stage 2 mirrors the eight lanes, which
-// pairs each lane of one quad with a lane of the other.
+// pairs each lane of one quad with a lane of the other, stage 3 mirrors a row of sixteen lanes.
 template <int STAGE>
 __device__ __forceinline__ int partner_bits(int x) {
-  constexpr int ctrl = STAGE == 0 ? 0xB1 : STAGE == 1 ? 0x4E : 0x141;  // quad_perm 1,0,3,2 / 2,3,0,1 / row_half_mirror
+  // quad_perm 1,0,3,2 / quad_perm 2,3,0,1 / row_half_mirror / row_mirror
+  constexpr int ctrl = STAGE == 0 ? 0xB1 : STAGE == 1 ? 0x4E : STAGE == 2 ? 0x141 : 0x140;
   return __builtin_amdgcn_update_dpp(x, x, ctrl, 0xF, 0xF, false);
 }
 template <int STAGE>
 __device__ __forceinline__ float partner(float x) {
   return __int_as_float(partner_bits<STAGE>(__float_as_int(x)));
 }
-static_assert(kLanesPerAgent == 8, "the butterfly below covers eight lanes");
-
-// Sum over an agent's lanes, left in every one of them.
+// Sum over an agent's LPA lanes (8 or 16), left in every one of them.
+template <int LPA = kLanesPerAgent>
 __device__ __forceinline__ float agent_sum(float x) {
+  static_assert(LPA == 8 || LPA == 16, "the butterfly covers eight or sixteen lanes");
   x += partner<0>(x);
   x += partner<1>(x);
-  return x + partner<2>(x);
+  x += partner<2>(x);
+  if (LPA == 16) x += partner<3>(x);
+  return x;
 }
+template <int LPA = kLanesPerAgent>
 __device__ __forceinline__ int agent_sum(int x) {
   x += partner_bits<0>(x);
   x += partner_bits<1>(x);
-  return x + partner_bits<2>(x);
+  x += partner_bits<2>(x);
+  if (LPA == 16) x += partner_bits<3>(x);
+  return x;
 }
 
 // The task's distance: products and sum rounded one by one.
@@ -128,7 +134,7 @@ __device__ __forceinline__ void nearest_scan64(Nearest& n, float2 p, const float
   }
 }
 
-// One chunk of 16 candidates (the item lists are short).
+// One chunk of candidates, two per lane of the agent (the item lists are short).
 __device__ __forceinline__ void nearest_scan16(Nearest& n, float2 p, const float2* s, int base, int q) {
   const float4 c = *reinterpret_cast<const float4*>(s + base + 2 * q);
   nearest_offer<false>(n, p, c.x, c.y, base + 2 * q, -1);
@@ -136,6 +142,7 @@ __device__ __forceinline__ void nearest_scan16(Nearest& n, float2 p, const float
 }
 
 // Merge over the lanes of an agent (smaller distance, then lower index) and read the offset back.
+template <int LPA = kLanesPerAgent>
 __device__ __forceinline__ float2 nearest_finish(Nearest n, float2 p, const float2* s, int limit) {
   auto merge = [&](float od, int oi) {
     const bool take = od < n.d2 || (od == n.d2 && oi < n.idx);
@@ -145,6 +152,7 @@ __device__ __forceinline__ float2 nearest_finish(Nearest n, float2 p, const floa
   merge(partner<0>(n.d2), partner_bits<0>(n.idx));
   merge(partner<1>(n.d2), partner_bits<1>(n.idx));
   merge(partner<2>(n.d2), partner_bits<2>(n.idx));
+  if (LPA == 16) merge(partner<3>(n.d2), partner_bits<3>(n.idx));
   if (n.idx >= limit) return make_float2(0.f, 0.f);  // nothing comparable (non-finite positions)
   const float2 o = s[n.idx];
   return make_float2(o.x - p.x, o.y - p.y);
@@ -163,17 +171,18 @@ __device__ __forceinline__ float activate(float x, int act) {
 
 // A lane's slice of the policy's weights (columns c0 .. c0 + HQ - 1 of every layer, rows c0 .. of the
 // last one), loaded at the start of the kernel so that the round trip to L2 runs under the scans.
-template <int H>
+template <int H, int LPA = kLanesPerAgent>
 struct PolicySlice {
-  static constexpr int HQ = H / kLanesPerAgent;
+  static constexpr int HQ = H / LPA;
+  static_assert(HQ >= 2 && HQ % 2 == 0, "a lane's columns are loaded two at a time");
   static constexpr int kRows2 = H <= 32 ? H : 8;   // rows of W2 held here; the rest is read when it is used
   float w1[kObs][HQ], b1[HQ], w2[kRows2][HQ], b2[HQ], w3[HQ][2], b3[2];
   const float* rest;  // &W2[kRows2][c0]
 };
 
-template <int H>
-__device__ __forceinline__ void policy_load(const float* __restrict__ th, int q, PolicySlice<H>& s) {
-  constexpr int HQ = PolicySlice<H>::HQ;
+template <int H, int LPA>
+__device__ __forceinline__ void policy_load(const float* __restrict__ th, int q, PolicySlice<H, LPA>& s) {
+  constexpr int HQ = PolicySlice<H, LPA>::HQ;
   const int c0 = q * HQ;
   const float* W1 = th;
   const float* b1 = W1 + kObs * H;
@@ -192,8 +201,8 @@ __device__ __forceinline__ void policy_load(const float* __restrict__ th, int q,
   for (int i = 0; i < kObs; ++i) row(W1 + i * H, s.w1[i]);
   row(b1, s.b1);
 #pragma unroll
-  for (int i = 0; i < PolicySlice<H>::kRows2; ++i) row(W2 + i * H, s.w2[i]);
-  s.rest = W2 + PolicySlice<H>::kRows2 * H + c0;
+  for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i) row(W2 + i * H, s.w2[i]);
+  s.rest = W2 + PolicySlice<H, LPA>::kRows2 * H + c0;
   row(b2, s.b2);
 #pragma unroll
   for (int u = 0; u < HQ; ++u) {
@@ -204,20 +213,20 @@ __device__ __forceinline__ void policy_load(const float* __restrict__ th, int q,
 }
 
 // All H activations of a layer to every lane of the agent.
-template <int H>
-__device__ __forceinline__ void gather_agent(const float (&mine)[H / kLanesPerAgent], int lane, float (&full)[H]) {
-  constexpr int HQ = H / kLanesPerAgent;
+template <int H, int LPA>
+__device__ __forceinline__ void gather_agent(const float (&mine)[H / LPA], int lane, float (&full)[H]) {
+  constexpr int HQ = H / LPA;
 #pragma unroll
-  for (int s = 0; s < kLanesPerAgent; ++s)
+  for (int s = 0; s < LPA; ++s)
 #pragma unroll
-    for (int u = 0; u < HQ; ++u) full[s * HQ + u] = __shfl(mine[u], (lane & ~(kLanesPerAgent - 1)) | s);
+    for (int u = 0; u < HQ; ++u) full[s * HQ + u] = __shfl(mine[u], (lane & ~(LPA - 1)) | s);
 }
 
 // The policy of dims (8, H, H, 2) for one agent; every lane of the agent returns both outputs.
-template <int H>
-__device__ __forceinline__ float2 policy_forward(const PolicySlice<H>& s, const int (&act)[3], int lane,
+template <int H, int LPA>
+__device__ __forceinline__ float2 policy_forward(const PolicySlice<H, LPA>& s, const int (&act)[3], int lane,
                                                  const float (&obs)[kObs]) {
-  constexpr int HQ = PolicySlice<H>::HQ;
+  constexpr int HQ = PolicySlice<H, LPA>::HQ;
   float part[HQ], full[H];
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = s.b1[u];
@@ -227,18 +236,18 @@ __device__ __forceinline__ float2 policy_forward(const PolicySlice<H>& s, const 
     for (int u = 0; u < HQ; ++u) part[u] = fmaf(obs[i], s.w1[i][u], part[u]);
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = activate(part[u], act[0]);
-  gather_agent<H>(part, lane, full);
+  gather_agent<H, LPA>(part, lane, full);
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = s.b2[u];
 #pragma unroll
-  for (int i = 0; i < PolicySlice<H>::kRows2; ++i)
+  for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i)
 #pragma unroll
     for (int u = 0; u < HQ; ++u) part[u] = fmaf(full[i], s.w2[i][u], part[u]);
 #pragma unroll 16
-  for (int i = PolicySlice<H>::kRows2; i < H; ++i)
+  for (int i = PolicySlice<H, LPA>::kRows2; i < H; ++i)
 #pragma unroll
     for (int u = 0; u < HQ; u += 2) {
-      const float2 w = *reinterpret_cast<const float2*>(s.rest + (i - PolicySlice<H>::kRows2) * H + u);
+      const float2 w = *reinterpret_cast<const float2*>(s.rest + (i - PolicySlice<H, LPA>::kRows2) * H + u);
       part[u] = fmaf(full[i], w.x, part[u]);
       part[u + 1] = fmaf(full[i], w.y, part[u + 1]);
     }
@@ -250,7 +259,7 @@ __device__ __forceinline__ float2 policy_forward(const PolicySlice<H>& s, const 
     o0 = fmaf(part[u], s.w3[u][0], o0);
     o1 = fmaf(part[u], s.w3[u][1], o1);
   }
-  o0 = agent_sum(o0), o1 = agent_sum(o1);
+  o0 = agent_sum<LPA>(o0), o1 = agent_sum<LPA>(o1);
   return make_float2(activate(o0 + s.b3[0], act[2]), activate(o1 + s.b3[1], act[2]));
 }
 
@@ -435,10 +444,11 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
 
 // ---- single-agent form: every member alone in its own copy of each world ---------------------------------
 // Nothing couples the members, so the whole episode runs in one launch (the fused roll-out of the control
-// tasks): wave = 8 members x 8 lanes in one world, the policy's weights in registers for all steps, each
-// member's item lists and item book in LDS.  A touched item is moved at once by the lane that found it
-// (every slot is judged by exactly one lane per step, after the step's sensing), which is "from the next
-// step on".  All members start at agent 0's place among the same items.
+// tasks): wave = 64 / LPA members x LPA lanes in one world (sixteen lanes where the hidden width allows it:
+// twice the waves and half the length of a member's dependent chain), the policy's weights in registers for
+// all steps, each member's item lists and item book in LDS.  A touched item is moved at once by the lane
+// that found it (every slot is judged by exactly one lane per step, after the step's sensing), which is
+// "from the next step on".  All members start at agent 0's place among the same items.
 struct SoloArgs {
   const float* params;  // [pop][P]
   int P, pop, worlds, steps;
@@ -452,21 +462,23 @@ struct SoloArgs {
   uint32_t* counts_out;  // [worlds][pop][n_items] or null: times each item was eaten
 };
 
-template <int H>
+template <int H, int LPA>
 __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloArgs a) {
+  constexpr int kMembers = 64 / LPA;  // members per wave
   extern __shared__ float4 lds4[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int q = lane & (kLanesPerAgent - 1), la = lane / kLanesPerAgent;
-  const int agent = blockIdx.x * kAgentsPerBlock + la;
+  const int q = lane & (LPA - 1), la = lane / LPA;
+  const int agent = blockIdx.x * kMembers + la;
   const int world = blockIdx.y * kWorldsPerBlock + wave;
   const bool live = world < a.worlds && agent < a.pop;
   const int n_food = a.c.n_food, n_items = a.c.n_items;
-  const int food_pad = pad_to(n_food, 16), poison_pad = pad_to(n_items - n_food, 16), slots = food_pad + poison_pad;
-  // per wave: [8 members][slots] positions, then [8 members][slots] counts
-  float2* s_item = reinterpret_cast<float2*>(lds4) + wave * kAgentsPerBlock * slots;
-  uint32_t* s_count = reinterpret_cast<uint32_t*>(reinterpret_cast<float2*>(lds4) + kWorldsPerBlock * kAgentsPerBlock * slots) +
-                      wave * kAgentsPerBlock * slots;
+  const int food_pad = pad_to(n_food, 2 * LPA), poison_pad = pad_to(n_items - n_food, 2 * LPA);
+  const int slots = food_pad + poison_pad;
+  // per wave: [members][slots] positions, then [members][slots] counts
+  float2* s_item = reinterpret_cast<float2*>(lds4) + wave * kMembers * slots;
+  uint32_t* s_count = reinterpret_cast<uint32_t*>(reinterpret_cast<float2*>(lds4) + kWorldsPerBlock * kMembers * slots) +
+                      wave * kMembers * slots;
   if (a.gen_dev) a.gen = *a.gen_dev;
   const float inf = __builtin_inff();
   auto item_of = [&](int slot) {  // item index of a slot of the two padded lists, or -1
@@ -480,13 +492,13 @@ __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloAr
     return make_float2(unit_open(w.x), unit_open(w.y));
   };
 
-  PolicySlice<H> weights;
-  if (live) policy_load<H>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
+  PolicySlice<H, LPA> weights;
+  if (live) policy_load<H, LPA>(a.params + static_cast<size_t>(agent) * a.P, q, weights);
   if (world < a.worlds) {  // the same fresh items for every member of the wave
     for (int slot = lane; slot < slots; slot += 64) {
       const int i = item_of(slot);
       const float2 where = i >= 0 ? place(i, 0u) : make_float2(inf, inf);
-      for (int m = 0; m < kAgentsPerBlock; ++m) s_item[m * slots + slot] = where, s_count[m * slots + slot] = 0u;
+      for (int m = 0; m < kMembers; ++m) s_item[m * slots + slot] = where, s_count[m * slots + slot] = 0u;
     }
   }
   __syncthreads();
@@ -504,16 +516,16 @@ __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloAr
 #pragma unroll 1
   for (int step = 0; step < a.steps; ++step) {
     Nearest food{inf, 0x7fffffff}, poison{inf, 0x7fffffff};
-    for (int base = 0; base < food_pad; base += 16) nearest_scan16(food, p, my_food, base, q);
-    for (int base = 0; base < poison_pad; base += 16) nearest_scan16(poison, p, my_poison, base, q);
-    const float2 f = nearest_finish(food, p, my_food, food_pad);
-    const float2 g = nearest_finish(poison, p, my_poison, poison_pad);
+    for (int base = 0; base < food_pad; base += 2 * LPA) nearest_scan16(food, p, my_food, base, q);
+    for (int base = 0; base < poison_pad; base += 2 * LPA) nearest_scan16(poison, p, my_poison, base, q);
+    const float2 f = nearest_finish<LPA>(food, p, my_food, food_pad);
+    const float2 g = nearest_finish<LPA>(poison, p, my_poison, poison_pad);
     const float obs[kObs] = {v.x, v.y, f.x, f.y, g.x, g.y, 0.f, 0.f};  // nobody else is there
-    const float2 action = policy_forward<H>(weights, a.act, lane, obs);
+    const float2 action = policy_forward<H, LPA>(weights, a.act, lane, obs);
     move_axis(a.c, action.x, p.x, v.x);
     move_axis(a.c, action.y, p.y, v.y);
     // touches: the lane that judges a slot also moves the item it finds eaten
-    for (int base = 0; base < slots; base += 2 * kLanesPerAgent) {
+    for (int base = 0; base < slots; base += 2 * LPA) {
       const float4 it = *reinterpret_cast<const float4*>(my_food + base + 2 * q);
       const bool hit0 = dist2(it.x - p.x, it.y - p.y) <= a.c.r2, hit1 = dist2(it.z - p.x, it.w - p.y) <= a.c.r2;
       if (hit0 || hit1) {
@@ -534,7 +546,7 @@ __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloAr
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
-  reward = agent_sum(reward);
+  reward = agent_sum<LPA>(reward);
   const size_t me = static_cast<size_t>(world) * a.pop + agent;
   if (q == 0) {
     a.reward[me] = reward;
@@ -542,7 +554,7 @@ __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloAr
     if (a.vel_out) a.vel_out[me] = v;
   }
   if (a.counts_out)
-    for (int slot = q; slot < slots; slot += kLanesPerAgent) {
+    for (int slot = q; slot < slots; slot += LPA) {
       const int i = item_of(slot);
       if (i >= 0) a.counts_out[me * n_items + i] = my_count[slot];
     }
@@ -747,26 +759,31 @@ int launch_forage(const MlpShape& sh, const float* params, int pop, int worlds, 
   return EVO_OK;
 }
 
-static size_t solo_lds_bytes(int n_food, int n_items) {
-  const size_t slots = pad_to(n_food, 16) + pad_to(n_items - n_food, 16);
-  return static_cast<size_t>(kWorldsPerBlock) * kAgentsPerBlock * slots * (sizeof(float2) + sizeof(uint32_t));
+// Lanes per member of the episode kernel: sixteen where a lane then still owns two columns of a layer.
+constexpr int solo_lanes(int H) { return H >= 32 ? 16 : 8; }
+
+static size_t solo_lds_bytes(int n_food, int n_items, int lanes) {
+  const size_t slots = pad_to(n_food, 2 * lanes) + pad_to(n_items - n_food, 2 * lanes);
+  return static_cast<size_t>(kWorldsPerBlock) * (64 / lanes) * slots * (sizeof(float2) + sizeof(uint32_t));
 }
 
 template <int H>
 static int launch_solo(const SoloArgs& a, hipStream_t s) {
-  const size_t lds = solo_lds_bytes(a.c.n_food, a.c.n_items);
+  constexpr int LPA = solo_lanes(H);
+  const size_t lds = solo_lds_bytes(a.c.n_food, a.c.n_items, LPA);
   static bool raised[64] = {};
   int device = 0;
   hipError_t e = hipGetDevice(&device);
   if (e == hipSuccess && device >= 0 && device < 64 && !raised[device]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H, LPA>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
     raised[device] = e == hipSuccess;
   }
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the episode kernel failed: %s",
               hipGetErrorString(e));
-  const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
-  hipLaunchKernelGGL(world_solo_kernel<H>, grid, dim3(64 * kWorldsPerBlock), lds, s, a);
+  constexpr int members = 64 / LPA;
+  const dim3 grid((a.pop + members - 1) / members, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
+  hipLaunchKernelGGL((world_solo_kernel<H, LPA>), grid, dim3(64 * kWorldsPerBlock), lds, s, a);
   return check_launch("world_solo_kernel");
 }
 
@@ -779,7 +796,8 @@ int forage_solo_supported(const MlpShape& sh, int pop, int worlds, const float* 
               EVO_ERR_UNSUPPORTED, "forage: the policy must be an MLP of dims {8, H, H, 2} with H = 16, 32 or 64");
   EVO_REQUIRE(pop >= 1, EVO_ERR_ARG, "forage: pop must be positive (got %d)", pop);
   EVO_REQUIRE(worlds >= 1 && worlds <= 4096, EVO_ERR_ARG, "forage: n_rollouts (worlds) must be in [1, 4096]");
-  EVO_REQUIRE(solo_lds_bytes(c.n_food, c.n_items) <= kMaxLdsBytes, EVO_ERR_UNSUPPORTED, "forage: too many items");
+  EVO_REQUIRE(solo_lds_bytes(c.n_food, c.n_items, solo_lanes(sh.dims[1])) <= kMaxLdsBytes, EVO_ERR_UNSUPPORTED,
+              "forage: too many items");
   return EVO_OK;
 }
 
