@@ -338,6 +338,20 @@ int evo_task_step(const task_desc* td, const float* state_dev, const float* acti
 int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                         int32_t steps, float* ret_dev, float* final_dev, void* stream);
 
+/* What every step of a CARTPOLE rollout actually used (Section 3, "Control Tasks": the roll-out loop
+ * itself): trace_dev[pop][n_rollouts][steps][12] fp32, per record
+ *   [0..3] the state (x, x_d, th, th_d) the policy saw at step t,
+ *   [4]    the policy's linear output (before the last activation), [5] the action,
+ *   [6]    the reward of the step (at the new state), [7] alive before the step (1 / 0),
+ *   [8]    the return after the step, [9..11] zero;
+ * final_dev[pop][n_rollouts][4] (may be NULL) the state after the last step.  The records come from the
+ * kernel behind rollout's fitness, compiled with the stores of the records switched on (same source, same
+ * arithmetic: the returns at the end of the trace are bit for bit those of evo_rollout_details), so that
+ * each step can be checked on its own along the device's trajectory.
+ * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED, EVO_ERR_HIP. */
+int evo_rollout_trace(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                      int32_t steps, float* trace_dev, float* final_dev, void* stream);
+
 /* Logits of an EVO_TASK_SEQ2SEQ task: logits_dev[pop][B][seq_out][n_out] (fp32). */
 int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                        float* logits_dev, void* stream);

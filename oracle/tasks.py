@@ -65,6 +65,12 @@ def cartpole_derivs(s, action, cp=CP_DEFAULT):
     return xdd, thdd
 
 
+def cartpole_reward(s):
+    """Reward of arriving at states s[...,4]: cos(theta) exp(-x^2)."""
+    s = np.asarray(s, dtype=np.float64)
+    return np.cos(s[..., 2]) * np.exp(-s[..., 0] ** 2)
+
+
 def cartpole_step(s, action, cp=CP_DEFAULT):
     """One explicit-Euler step; returns (next state, reward at the new state)."""
     s = np.asarray(s, dtype=np.float64)
@@ -73,8 +79,7 @@ def cartpole_step(s, action, cp=CP_DEFAULT):
     xdd, thdd = cartpole_derivs(s, action, cp)
     nxt = np.stack([s[..., 0] + dt * s[..., 1], s[..., 1] + dt * xdd,
                     s[..., 2] + dt * s[..., 3], s[..., 3] + dt * thdd], axis=-1)
-    reward = np.cos(nxt[..., 2]) * np.exp(-nxt[..., 0] ** 2)
-    return nxt, reward
+    return nxt, cartpole_reward(nxt)
 
 
 def cartpole_obs(s):

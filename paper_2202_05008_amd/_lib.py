@@ -70,6 +70,8 @@ _SIGNATURES = {
                                 C.c_void_p]),
     "evo_rollout_details": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "evo_rollout_trace": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
+                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "evo_seq2seq_logits": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_void_p]),
     "evo_last_error": (C.c_char_p, []),

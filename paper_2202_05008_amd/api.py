@@ -244,6 +244,12 @@ def evo_rollout_details(td, pd, params, pop, steps, ret, final):
                                            _ptr(final, torch.float32, allow_none=True), _stream()))
 
 
+def evo_rollout_trace(td, pd, params, pop, steps, trace, final=None):
+    _check(_lib.load().evo_rollout_trace(C.byref(td), C.byref(pd), _ptr(params), pop, steps,
+                                         _ptr(trace, torch.float32),
+                                         _ptr(final, torch.float32, allow_none=True), _stream()))
+
+
 class PGPE:
     """Convenience owner of the device arrays behind one pgpe_state handle."""
 

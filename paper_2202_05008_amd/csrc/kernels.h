@@ -49,7 +49,7 @@ int launch_sphere(const void* params, int dtype, const float* x_star, int pop, i
 int cartpole_supported(const MlpShape& sh, int n_rollouts);
 int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_rollouts, int steps, const float* cp,
                     float init_scale, uint64_t seed, uint32_t gen, const uint32_t* gen_dev, float* fitness, float* ret,
-                    float* final_state, hipStream_t s);
+                    float* final_state, float* trace, hipStream_t s);
 int launch_cartpole_step(const float* cp, const float* state, const float* action, float* next, float* reward,
                          int n, hipStream_t s);
 

@@ -197,7 +197,8 @@ static int forage_impl(const task_desc* td, const policy_desc* pd, const void* p
 }
 
 static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
-                        int32_t steps, float* fitness_dev, float* ret_dev, float* final_dev, void* stream) {
+                        int32_t steps, float* fitness_dev, float* ret_dev, float* final_dev, float* trace_dev,
+                        void* stream) {
   int rc = check_task(td);
   if (rc) return rc;
   EVO_REQUIRE(params_dev != nullptr, EVO_ERR_ARG, "rollout: null device pointer");
@@ -229,7 +230,7 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     EVO_REQUIRE(pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
                 "cartpole: needs an fp32 MLP policy");
     EVO_REQUIRE(steps >= 1 && steps <= (1 << 24), EVO_ERR_ARG, "cartpole: steps out of range");
-    EVO_REQUIRE(fitness_dev || ret_dev || final_dev, EVO_ERR_ARG, "cartpole: no output requested");
+    EVO_REQUIRE(fitness_dev || ret_dev || final_dev || trace_dev, EVO_ERR_ARG, "cartpole: no output requested");
     MlpShape sh;
     rc = mlp_shape(pd, &sh);
     if (rc) return rc;
@@ -237,7 +238,7 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     if (rc) return rc;
     return launch_cartpole(sh, static_cast<const float*>(params_dev), pop, td->n_rollouts, steps, td->cp,
                            td->init_scale, td->reset_seed, td->generation, td->generation_dev, fitness_dev, ret_dev,
-                           final_dev, s);
+                           final_dev, trace_dev, s);
   }
   // supervised single-step tasks
   EVO_REQUIRE(pd->kind != EVO_POLICY_LSTM_SEQ2SEQ, EVO_ERR_UNSUPPORTED,
@@ -290,7 +291,7 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
 extern "C" int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                        int32_t steps, float* fitness_dev, void* stream) {
   EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
-  return rollout_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, stream);
+  return rollout_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, stream);
 }
 
 extern "C" int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
@@ -298,7 +299,16 @@ extern "C" int evo_rollout_details(const task_desc* td, const policy_desc* pd, c
   EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_CARTPOLE, EVO_ERR_ARG,
               "evo_rollout_details: only the cart-pole task has per-roll-out details");
   EVO_REQUIRE(ret_dev || final_dev, EVO_ERR_ARG, "evo_rollout_details: no output requested");
-  return rollout_impl(td, pd, params_dev, pop, steps, nullptr, ret_dev, final_dev, stream);
+  return rollout_impl(td, pd, params_dev, pop, steps, nullptr, ret_dev, final_dev, nullptr, stream);
+}
+
+extern "C" int evo_rollout_trace(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                                 int32_t steps, float* trace_dev, float* final_dev, void* stream) {
+  EVO_REQUIRE(td != nullptr && td->kind == EVO_TASK_CARTPOLE, EVO_ERR_ARG,
+              "evo_rollout_trace: only the cart-pole task records a trace");
+  EVO_REQUIRE(trace_dev != nullptr && aligned16(trace_dev), EVO_ERR_ARG,
+              "evo_rollout_trace: trace_dev must be a 16-byte aligned device pointer");
+  return rollout_impl(td, pd, params_dev, pop, steps, nullptr, nullptr, final_dev, trace_dev, stream);
 }
 
 extern "C" int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,

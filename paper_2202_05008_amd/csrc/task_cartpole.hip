@@ -32,6 +32,11 @@
 #include "philox.h"
 #include "split16.h"
 
+// Every multiply-add below is written out (fmaf where one rounding is meant): with the compiler free to fuse,
+// the roll-out kernel and its build with the per-step records differed in a few last bits, which the
+// chaotic dynamics turn into different returns.  Written out, both builds compute the same numbers.
+#pragma clang fp contract(off)
+
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -41,6 +46,7 @@ constexpr float kSW2 = 256.0f;  // 2^8: scale of the stored layer-2 weights
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
   float inv_2l;  // 1 / (2 l), rounded once on the host
+  float k4, k3, k2ml, k3mg;  // 4 (M + m), 3 m, 2 m l, 3 m g: binary32 products formed on the host
 };
 
 struct CartpoleArgs {
@@ -53,12 +59,13 @@ struct CartpoleArgs {
   float* fitness;
   float* ret;
   float* final_state;
+  float* trace;  // [pop][R][steps][12]: what every step of every roll-out actually used, or null
 };
 
 // tanh(x) = 1 - 2 / (e^{2x} + 1) on the hardware exp2 / reciprocal; saturates cleanly at +-1.
 __device__ __forceinline__ float tanh_fast(float x) {
   const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);  // e^{2x} = 2^{2x log2 e}
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
 }
 
 __device__ __forceinline__ float act_apply(float x, int act) {
@@ -92,23 +99,25 @@ struct CpState {
 // and its sine / cosine (needed for the reward and for the next observation).
 __device__ __forceinline__ CpState cartpole_advance(const CpState& s, float sn, float cs, float a,
                                                     const CartpoleConst& c, float& sn_new, float& cs_new) {
-  const float Fe = c.fscale * a - c.b * s.xd;
-  const float D = 4.0f * (c.M + c.m) - 3.0f * c.m * cs * cs;
+  const float Fe = fmaf(c.fscale, a, -(c.b * s.xd));
+  const float D = fmaf(-cs, c.k3 * cs, c.k4);
   // the hardware reciprocal is within one ulp; D >= 4 M + m > 0
-  const float xdd = (4.0f * Fe + 2.0f * c.m * c.l * s.thd * s.thd * sn - 3.0f * c.m * c.g * sn * cs) *
-                    __builtin_amdgcn_rcpf(D);
-  const float thdd = 3.0f * (c.g * sn - xdd * cs) * c.inv_2l;
+  float num = 4.0f * Fe;
+  num = fmaf(sn, s.thd * (c.k2ml * s.thd), num);
+  num = fmaf(-cs, c.k3mg * sn, num);
+  const float xdd = __builtin_amdgcn_rcpf(D) * num;
+  const float thdd = (3.0f * fmaf(c.g, sn, -(cs * xdd))) * c.inv_2l;
   CpState n;
-  n.x = s.x + c.dt * s.xd;
-  n.xd = s.xd + c.dt * xdd;
-  n.th = s.th + c.dt * s.thd;
-  n.thd = s.thd + c.dt * thdd;
+  n.x = fmaf(c.dt, s.xd, s.x);
+  n.xd = fmaf(c.dt, xdd, s.xd);
+  n.th = fmaf(c.dt, s.thd, s.th);
+  n.thd = fmaf(c.dt, thdd, s.thd);
   sincos_fast(n.th, sn_new, cs_new);
   return n;
 }
 
 __device__ __forceinline__ float step_reward(float x_new, float cs_new) {
-  return cs_new * __builtin_amdgcn_exp2f(-1.4426950408889634f * x_new * x_new);  // cos(th') exp(-x'^2)
+  return cs_new * __builtin_amdgcn_exp2f((-1.4426950408889634f * x_new) * x_new);  // cos(th') exp(-x'^2)
 }
 
 // Sum over the 16 lanes of a row with DPP moves (xor 1, xor 2, half-row mirror, row mirror):
@@ -128,7 +137,9 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 // NT: hidden width 16 NT (NT waves); TWO: two hidden layers of that width; TANH: every activation
 // is tanh (the usual policy), which removes the per-value activation switch from the step loop.
-template <int NT, bool TWO, bool TANH>
+// TRACE: the same kernel with one record per step stored to a.trace (a build of its own, because even
+// a never-taken branch around the stores cost the plain roll-out 10 % of its time).
+template <int NT, bool TWO, bool TANH, bool TRACE>
 __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1_rt, int act2_rt, int act3_rt) {
   const int act1 = TANH ? EVO_ACT_TANH : act1_rt, act2 = TANH ? EVO_ACT_TANH : act2_rt;
   const int act3 = TANH ? EVO_ACT_TANH : act3_rt;
@@ -194,7 +205,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     CpState s;
     s.x = a.init_scale * z[0];
     s.xd = a.init_scale * z[1];
-    s.th = a.init_scale * z[2] + 3.14159265358979323846f;
+    s.th = fmaf(a.init_scale, z[2], 3.14159265358979323846f);
     s.thd = a.init_scale * z[3];
     float sn, cs;
     sincos_fast(s.th, sn, cs);
@@ -263,11 +274,22 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
       float pre = part[0][j];
 #pragma unroll
       for (int w = 1; w < NT; ++w) pre += part[w][j];
-      const float action = act_apply(pre + b3, act3);
+      const float lin = pre + b3;  // the policy's linear output
+      const float action = act_apply(lin, act3);
       // ---- environment step (every wave advances its own copy of the state) -------------------
       float sn_n, cs_n;
       const CpState n = cartpole_advance(s, sn, cs, action, a.c, sn_n, cs_n);
       const float reward = step_reward(n.x, cs_n);
+      if (TRACE) {
+        // the state the policy saw; its linear output, the action, the step's reward, alive before; return after
+        if (valid && q == 0 && wave == 0) {
+          float4* tr = reinterpret_cast<float4*>(
+              a.trace + ((static_cast<size_t>(member) * a.R + r) * a.steps + step) * 12);
+          tr[0] = make_float4(s.x, s.xd, s.th, s.thd);
+          tr[1] = make_float4(lin, action, reward, alive ? 1.f : 0.f);
+          tr[2] = make_float4(alive ? ret + reward : ret, 0.f, 0.f, 0.f);
+        }
+      }
       if (alive) {
         ret += reward;
         s = n;
@@ -317,7 +339,9 @@ __global__ __launch_bounds__(256) void cartpole_step_kernel(CartpoleConst c, con
 }
 
 static CartpoleConst make_const(const float* cp) {
-  return CartpoleConst{cp[0], cp[1], cp[2], cp[3], cp[4], cp[5], cp[6], cp[7], 1.0f / (2.0f * cp[3])};
+  const float g = cp[0], M = cp[1], m = cp[2], l = cp[3];
+  return CartpoleConst{g, M, m, l, cp[4], cp[5], cp[6], cp[7], 1.0f / (2.0f * l),
+                       4.0f * (M + m), 3.0f * m, (2.0f * m) * l, (3.0f * m) * g};
 }
 
 int cartpole_supported(const MlpShape& sh, int n_rollouts) {
@@ -335,7 +359,7 @@ int cartpole_supported(const MlpShape& sh, int n_rollouts) {
 
 int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_rollouts, int steps, const float* cp,
                     float init_scale, uint64_t seed, uint32_t gen, const uint32_t* gen_dev, float* fitness, float* ret,
-                    float* final_state, hipStream_t s) {
+                    float* final_state, float* trace, hipStream_t s) {
   CartpoleArgs a;
   a.params = params, a.P = sh.P, a.R = n_rollouts, a.steps = steps;
   a.c = make_const(cp);
@@ -344,16 +368,22 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
   a.init_scale = init_scale;
   a.key0 = static_cast<uint32_t>(seed), a.key1 = static_cast<uint32_t>(seed >> 32), a.gen = gen;
   a.gen_dev = gen_dev;
-  a.fitness = fitness, a.ret = ret, a.final_state = final_state;
+  a.fitness = fitness, a.ret = ret, a.final_state = final_state, a.trace = trace;
   const int H = sh.dims[1];
   const int a1 = sh.act[0], a2 = sh.n_layers == 3 ? sh.act[1] : 0, a3 = sh.act[sh.n_layers - 1];
   const dim3 grid(pop);
   const bool all_tanh = a1 == EVO_ACT_TANH && a3 == EVO_ACT_TANH && (sh.n_layers == 2 || a2 == EVO_ACT_TANH);
-#define EVO_CP_CASE(NTV, TWOV)                                                                              \
-  if (all_tanh)                                                                                             \
-    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, true>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);     \
-  else                                                                                                      \
-    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, false>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);    \
+#define EVO_CP_LAUNCH(NTV, TWOV, TANHV)                                                                              \
+  if (trace)                                                                                                         \
+    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, TANHV, true>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3);       \
+  else                                                                                                               \
+    hipLaunchKernelGGL((cartpole_kernel<NTV, TWOV, TANHV, false>), grid, dim3(64 * NTV), 0, s, a, a1, a2, a3)
+#define EVO_CP_CASE(NTV, TWOV)                  \
+  if (all_tanh) {                               \
+    EVO_CP_LAUNCH(NTV, TWOV, true);             \
+  } else {                                      \
+    EVO_CP_LAUNCH(NTV, TWOV, false);            \
+  }                                             \
   return check_launch("cartpole_kernel")
   if (sh.n_layers == 3) {
     if (H == 64) { EVO_CP_CASE(4, true); }
@@ -364,6 +394,7 @@ int launch_cartpole(const MlpShape& sh, const float* params, int pop, int n_roll
   if (H == 32) { EVO_CP_CASE(2, false); }
   EVO_CP_CASE(1, false);
 #undef EVO_CP_CASE
+#undef EVO_CP_LAUNCH
 }
 
 int launch_cartpole_step(const float* cp, const float* state, const float* action, float* next, float* reward,
