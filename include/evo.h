@@ -300,6 +300,19 @@ size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32
 int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
             float* fitness_dev, void* stream);
 
+/* rollout for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same evaluation, by the same kernels, as rollout, but the
+ * workspace is a fixed array inside the library's device image (EVO_STATIC_SCRATCH_BYTES per GPU, held until
+ * the process ends) instead of td->work_dev, which is ignored.  Calls no allocating routine.  A task whose
+ * rollout_workspace_bytes() exceeds the array is refused with EVO_ERR_UNSUPPORTED before anything is
+ * launched.  Every call on a GPU shares that GPU's array (each kernel writes what it later reads; nothing has to
+ * start at zero): two calls that overlap on one GPU, on different streams or threads, race.
+ * Errors: as rollout, plus EVO_ERR_UNSUPPORTED (workspace beyond the array), EVO_ERR_HIP (symbol lookup). */
+#define EVO_STATIC_SCRATCH_BYTES (2u << 20)
+size_t rollout_static_scratch_bytes(void);
+int rollout_static_scratch(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                           int32_t steps, float* fitness_dev, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Hooks that expose intermediate results for exact checks.
  * ------------------------------------------------------------------------------------ */

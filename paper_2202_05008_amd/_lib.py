@@ -60,6 +60,9 @@ _SIGNATURES = {
     "rollout_workspace_bytes": (C.c_size_t, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_int32]),
     "rollout": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32, C.c_int32,
                           C.c_void_p, C.c_void_p]),
+    "rollout_static_scratch_bytes": (C.c_size_t, []),
+    "rollout_static_scratch": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
+                                         C.c_int32, C.c_void_p, C.c_void_p]),
     "evo_philox_u32": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                  C.c_void_p, C.c_void_p]),
     "evo_philox_normal": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,

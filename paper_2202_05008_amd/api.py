@@ -194,6 +194,16 @@ def rollout(td, pd, params, pop, steps, fitness):
                                _ptr(fitness, torch.float32), _stream()))
 
 
+def rollout_static_scratch_bytes():
+    return int(_lib.load().rollout_static_scratch_bytes())
+
+
+def rollout_static_scratch(td, pd, params, pop, steps, fitness):
+    """rollout with the workspace inside the library (no allocation anywhere); td.work_dev is ignored."""
+    _check(_lib.load().rollout_static_scratch(C.byref(td), C.byref(pd) if pd is not None else None, _ptr(params),
+                                              pop, steps, _ptr(fitness, torch.float32), _stream()))
+
+
 def evo_philox_u32(seed, gen, pair, block0, nblocks, tag, out):
     _check(_lib.load().evo_philox_u32(seed, gen, pair, block0, nblocks, tag, _ptr(out, torch.int32), _stream()))
 

@@ -4,6 +4,8 @@
 // and population parameters; VectorizedTask reset / step carried over the roll-out steps.
 #include "kernels.h"
 
+#include <mutex>
+
 using namespace evo;
 
 namespace {
@@ -292,6 +294,60 @@ extern "C" int rollout(const task_desc* td, const policy_desc* pd, const void* p
                        int32_t steps, float* fitness_dev, void* stream) {
   EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout: fitness_dev is null");
   return rollout_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, stream);
+}
+
+// ---- rollout for callers that cannot allocate: the workspace lives in the library's image ----------
+// `scratch` is a host-side stand-in for the device array, not an address: kernels are given the address
+// that hipGetSymbolAddress returns for the device that is current, looked up once per device.
+constexpr size_t kStaticScratchBytes = EVO_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // per device: where its copy of `scratch` lives
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "rollout_static_scratch: hipGetDevice failed: %s", hipGetErrorString(e));
+  EVO_REQUIRE(dev >= 0 && dev < kMaxDevices, EVO_ERR_UNSUPPORTED, "rollout_static_scratch: device index %d beyond %d",
+              dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) (void)hipGetLastError();
+    EVO_REQUIRE(e == hipSuccess && p != nullptr, EVO_ERR_HIP, "rollout_static_scratch: hipGetSymbolAddress failed: %s",
+                hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return EVO_OK;
+}
+
+}  // namespace
+
+extern "C" size_t rollout_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int rollout_static_scratch(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
+                                      int32_t steps, float* fitness_dev, void* stream) {
+  EVO_REQUIRE(fitness_dev != nullptr, EVO_ERR_ARG, "rollout_static_scratch: fitness_dev is null");
+  int rc = check_task(td);
+  if (rc) return rc;
+  EVO_REQUIRE(pop >= 1 && pop <= 65535, EVO_ERR_ARG, "rollout_static_scratch: pop must be in [1,65535] (got %d)", pop);
+  const size_t need = rollout_workspace_bytes(td, pd, pop);
+  EVO_REQUIRE(need <= kStaticScratchBytes, EVO_ERR_UNSUPPORTED,
+              "rollout_static_scratch: this task needs %zu bytes of workspace, the built-in scratch holds %zu: "
+              "use rollout with a caller-owned workspace",
+              need, kStaticScratchBytes);
+  task_desc local = *td;
+  void* ptr = nullptr;
+  rc = static_scratch(&ptr);
+  if (rc) return rc;
+  local.work_dev = need ? ptr : nullptr;
+  return rollout_impl(&local, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, stream);
 }
 
 extern "C" int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
