@@ -76,6 +76,12 @@ typedef struct {
   float max_speed;          /* ClipUp: bound on the Euclidean norm of the velocity, > 0     */
 } pgpe_config;
 
+/* The customary values [not in the paper]: sigma_init 0.1, lr_mu 0.01, lr_sigma 0.1, sigma_max_change 0.2,
+ * Adam 0.9 / 0.999 / 1e-8, clipped-ascent sigma rule, centered ranks, Adam on mu, momentum 0.9 and, for
+ * ClipUp, max_speed = pgpe_clipup_default_max_speed(lr_mu) = 2 lr_mu. */
+int pgpe_config_defaults(pgpe_config* cfg, int32_t P, int32_t pop_max);
+float pgpe_clipup_default_max_speed(float lr_mu);
+
 typedef struct pgpe_state pgpe_state; /* host handle: config, t, pending (seed, pop), pointers */
 
 /* Bytes of device workspace a state needs (ranks, shaped fitness, norms, the device copy of t). */
@@ -187,10 +193,10 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      conv3x3 (zero-padded, stride 1) -> ReLU -> maxpool 2x2/2, twice, then a dense layer.
  *      Flat parameters: W1[3][3][1][c1], b1[c1], W2[3][3][c1][c2], b2[c2],
  *      Wd[(H/4)(H/4)c2][n_cls], bd[n_cls]; dense input flattened (h, w, c), c fastest.
- *      fp32 results; the second convolution is evaluated on 16-bit matrix instructions with
- *      two-term operand splits, which needs its weights below 255.9 and its input activations
- *      below 4094 in magnitude: an image for which they are not gets NaN logits (a NaN fitness
- *      ranks lowest).
+ *      fp32 results for any finite weights and pixels (the second convolution is evaluated on 16-bit
+ *      matrix instructions with two-term operand splits whose scales are set at run time); a member
+ *      with a non-finite convolution weight, or an image with an infinite pixel, gets NaN logits (a NaN
+ *      pixel is not detected: ReLU and pooling are maximum operations, which drop it).
  * LSTM sequence-to-sequence (kind EVO_POLICY_LSTM_SEQ2SEQ; Section 3, "Seq2Seq Learning"; the carried
  *      cells are the policy state of Section 4): dims = {V, H, n_out}, H = 64 or 128, n_out <= V <= 16.
  *      Tokens are integers in [0, V).  LSTM cell, gates i, f, g, o in columns g H + u:
@@ -199,8 +205,9 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      encoder's final (h, c) and takes one step per answer position j, its input being token V - 1
  *      for j = 0 and the true answer token j - 1 afterwards; logits_j = h_j Wo + bo.
  *      Flat parameters: enc Wx[V][4H], Wh[H][4H], b[4H]; dec Wx[V][4H], Wh[H][4H], b[4H];
- *      Wo[H][n_out]; bo[n_out].  fp32 results; the recurrent and output weights must stay below
- *      255.9 in magnitude (two-term fp16 operand splits), else the member's outputs are NaN.
+ *      Wo[H][n_out]; bo[n_out].  fp32 results for any finite weights (two-term fp16 operand splits; a
+ *      member with a recurrent weight of 255.9 or more is evaluated by a second, slower build of the kernel
+ *      that is launched behind the first and scales each group of weights by its own largest magnitude).
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int32_t kind;
@@ -232,10 +239,9 @@ int pop_forward(const policy_desc* pd, const void* params_dev, const float* obs_
  *             (passed through the float pointer), target_dev = int32 answer tokens [B][seq_out],
  *             shared by all members (obs_member_stride = 0); seq_in <= 32, seq_out <= 16.
  *   CARTPOLE  mean over n_rollouts of the episode return of the swing-up task below; the whole
- *             episode (policy weights, environment state) stays on chip for all `steps`.  With two
- *             hidden layers the second one has the same limits on its weights (255.9) and, unless a
- *             tanh bounds them, its inputs (4094) as the ConvNet's second convolution: a member
- *             outside them gets a NaN fitness.
+ *             episode (policy weights, environment state) stays on chip for all `steps`.  fp32
+ *             results for any finite weights (the second hidden layer runs as two-term fp16 products
+ *             with run-time scales, like the ConvNet's second convolution).
  * Cart-pole: state (x, x_d, th, th_d), th from upright; cp = {g, m_cart M, m_pole m, length l,
  *   friction b, force scale, dt, x_limit}; F = force_scale * a - b x_d (a = policy output);
  *   D = 4(M+m) - 3 m cos^2 th;  x_dd = [4F + 2 m l th_d^2 sin th - 3 m g sin th cos th] / D;

@@ -34,6 +34,8 @@ class task_desc(C.Structure):
 
 _SIGNATURES = {
     "pgpe_workspace_bytes": (C.c_size_t, [C.POINTER(pgpe_config)]),
+    "pgpe_config_defaults": (C.c_int, [C.POINTER(pgpe_config), C.c_int32, C.c_int32]),
+    "pgpe_clipup_default_max_speed": (C.c_float, [C.c_float]),
     "pgpe_create": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(pgpe_config), C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p, C.c_void_p]),
     "pgpe_destroy": (C.c_int, [C.c_void_p]),

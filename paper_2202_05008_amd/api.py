@@ -48,12 +48,18 @@ def evo_version():
     return _lib.load().evo_version().decode()
 
 
-def make_pgpe_config(P, pop_max, sigma_init=0.1, lr_mu=0.01, lr_sigma=0.1, sigma_max_change=0.2, beta1=0.9,
-                     beta2=0.999, eps=1e-8, sigma_rule=0, shaping=1, optimizer=0, momentum=0.9, max_speed=None):
-    if max_speed is None:
-        max_speed = 2.0 * lr_mu
-    return pgpe_config(P, pop_max, sigma_init, lr_mu, lr_sigma, sigma_max_change, beta1, beta2, eps, sigma_rule,
-                       shaping, optimizer, momentum, max_speed)
+def make_pgpe_config(P, pop_max, **fields):
+    """pgpe_config_defaults, then the fields given by name; an unnamed max_speed follows lr_mu (the library's rule)."""
+    lib = _lib.load()
+    cfg = pgpe_config()
+    _check(lib.pgpe_config_defaults(C.byref(cfg), P, pop_max))
+    max_speed = fields.pop("max_speed", None)
+    for name, value in fields.items():
+        if name not in dict(pgpe_config._fields_):
+            raise TypeError("pgpe_config has no field %r" % name)
+        setattr(cfg, name, value)
+    cfg.max_speed = lib.pgpe_clipup_default_max_speed(cfg.lr_mu) if max_speed is None else max_speed
+    return cfg
 
 
 def make_policy_desc(kind, dims, act=(), dtype=EVO_F32):

@@ -603,6 +603,18 @@ static int check_cfg(const pgpe_config* c) {
   return EVO_OK;
 }
 
+extern "C" float pgpe_clipup_default_max_speed(float lr_mu) { return 2.0f * lr_mu; }
+
+extern "C" int pgpe_config_defaults(pgpe_config* cfg, int32_t P, int32_t pop_max) {
+  EVO_REQUIRE(cfg != nullptr, EVO_ERR_ARG, "pgpe_config_defaults: cfg is null");
+  cfg->P = P, cfg->pop_max = pop_max;
+  cfg->sigma_init = 0.1f, cfg->lr_mu = 0.01f, cfg->lr_sigma = 0.1f, cfg->sigma_max_change = 0.2f;
+  cfg->beta1 = 0.9f, cfg->beta2 = 0.999f, cfg->eps = 1e-8f;
+  cfg->sigma_rule = 0, cfg->shaping = 1, cfg->optimizer = EVO_OPT_ADAM;
+  cfg->momentum = 0.9f, cfg->max_speed = pgpe_clipup_default_max_speed(cfg->lr_mu);
+  return EVO_OK;
+}
+
 static int check_ask_pop(const pgpe_state* st, int32_t pop, const char* who) {
   EVO_REQUIRE(pop >= 2 && (pop & 1) == 0 && pop <= st->cfg.pop_max, EVO_ERR_ARG,
               "%s: pop must be even and in [2, pop_max=%d] (got %d)", who, st->cfg.pop_max, pop);

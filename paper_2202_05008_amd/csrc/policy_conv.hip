@@ -18,13 +18,14 @@
 // for 8192 MACs.  conv2 therefore runs on the fp16 matrix instruction with every fp32 operand
 // split into two half-precision terms (split16.h): three matrix instructions per product, a
 // product within 3 * 2^-22 of the fp32 one, a 72-term sum well inside the 1e-5 gate (measured:
-// 4e-7 of the rms), at 3 / 16 of the issue cycles of the fp32 matrix instruction.  The conv1
-// activations are produced times 2^4 (the factor sits in the conv1 weights and bias), the conv2
-// weights are stored times 2^8, and the 2^12 of the conv2 output is taken out by the staged dense
-// weights.  The fp16 range then allows activations below 4094 and weights below 255.9: the
-// kernel tracks the largest conv1 activation of an image and checks the conv2 weights when it
-// loads them, and where either exceeds the range it returns NaN logits for the image (the
-// member's fitness is then NaN and ranks lowest) instead of a wrong finite value.
+// 4e-7 of the rms), at 3 / 16 of the issue cycles of the fp32 matrix instruction.  Both operands
+// carry a power-of-two scale chosen at run time so that any finite value fits fp16's range: the
+// conv2 weights of a member from their largest magnitude, the conv1 activations of an image from
+// the bound max|pixel| max_c sum_t |W1[t][c]| + max_c |b1[c]| (the conv1 sums start from the bias,
+// so the factor is one multiply before the ReLU; the conv2 bias is added by the multiply-add that
+// takes both factors out again).  A member with a non-finite convolution weight, or an image with
+// an infinite pixel, gets NaN logits (the maximum operations of ReLU and pooling would otherwise
+// swallow what fp32 arithmetic propagates); a NaN pixel is not detected.
 //
 // Band pipeline.  conv2 output row b needs the pooled conv1 rows 2b-1 .. 2b+2 only (rows -1 and
 // H/2 are the zero border), so the conv1 output is never held whole: pass b of conv1 produces the
@@ -47,9 +48,7 @@ namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr float kSA1 = 16.0f;            // 2^4: scale of the stored conv1 activations
-constexpr float kSW2 = 256.0f;           // 2^8: scale of the stored conv2 weights
-constexpr float kSA2 = kSA1 * kSW2;      // 2^12: scale of the conv2 output
+constexpr float kFltMax = 3.402823466e+38f;
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
@@ -142,7 +141,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // ---- once per workgroup: dense weights -> LDS (rows padded to NCS with zeros) ----------------
   for (int i = threadIdx.x; i < n_feat * NCS; i += 64 * kConvWaves) {
     const int f = i / NCS, c = i - f * NCS;
-    wd_s[i] = c < n_cls ? Wd[f * n_cls + c] * (1.0f / kSA2) : 0.f;  // takes the scale of the conv2 output out
+    wd_s[i] = c < n_cls ? Wd[f * n_cls + c] : 0.f;
   }
   // zero the padded buffers once: borders stay zero, interiors are overwritten per image
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
@@ -151,21 +150,31 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // beyond tap 8), element j = input channel j, column n; each weight split into two terms
   const int n = lane & 15, q = lane >> 4;
   f16x8 w2b[2][3];
-  float w2_max = 0.f;
+  float u_w2;           // 1 / (scale of the stored conv2 weights)
+  bool lane_bad = false;  // a non-finite convolution weight seen by this lane
+  {
+    float x[3][8];
+    float w2_max = 0.f;
 #pragma unroll
-  for (int st = 0; st < 3; ++st) {
-    const int tap = 4 * st + q;
-    float x[8];
+    for (int st = 0; st < 3; ++st) {
+      const int tap = 4 * st + q;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      x[j] = tap < 9 ? kSW2 * W2[(tap * kC1 + j) * kC2 + n] : 0.f;
-      w2_max = fmaxf(w2_max, fabsf(x[j]));
+      for (int j = 0; j < 8; ++j) {
+        x[st][j] = tap < 9 ? W2[(tap * kC1 + j) * kC2 + n] : 0.f;
+        w2_max = fmaxf(w2_max, fabsf(x[st][j]));
+        lane_bad |= !(fabsf(x[st][j]) <= kFltMax);
+      }
     }
-    split2_x8(x, w2b[0][st], w2b[1][st]);
+    const float s_w2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w2_max)))));
+    u_w2 = pow2_reciprocal(s_w2);
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[st][j] *= s_w2;
+      split2_x8(x[st], w2b[0][st], w2b[1][st]);
+    }
   }
-  // a weight beyond the fp16 range (or a NaN, which the comparison also rejects) poisons the member
-  const bool w2_bad = __any(!(w2_max <= kSplitMax));
-  const float bias2 = kSA2 * b2[n];
+  const float bias2 = b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
   // conv1 role of this lane: pooled pixel (row select rs, column wx) x four channels 4 cg .. 4 cg + 3
@@ -176,9 +185,27 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) w1v[t][c] = kSA1 * W1[t * kC1 + 4 * c1_cg + c];  // conv1 output times 2^4
+    for (int c = 0; c < 4; ++c) w1v[t][c] = W1[t * kC1 + 4 * c1_cg + c];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) bias1v[c] = kSA1 * b1[4 * c1_cg + c];
+  for (int c = 0; c < 4; ++c) bias1v[c] = b1[4 * c1_cg + c];
+  // bound on the conv1 activations of any image: max|pixel| * bound_w1 + bound_b1 (both channel groups are
+  // present among the lanes of a wave)
+  float bound_w1, bound_b1;
+  {
+    float sw = 0.f, sb = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float t_sum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) t_sum += fabsf(w1v[t][c]);
+      sw = fmaxf(sw, t_sum);
+      sb = fmaxf(sb, fabsf(bias1v[c]));
+      lane_bad |= !(t_sum <= kFltMax) || !(fabsf(bias1v[c]) <= kFltMax) || !(fabsf(bias2) <= kFltMax);
+    }
+    bound_w1 = wave_max(sw);
+    bound_b1 = wave_max(sb);
+  }
+  const bool member_bad = __any(lane_bad);
 
   // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3,
   // shifted by tap 4 step + q (the padding taps 9..11 re-read tap 8 against zero weights)
@@ -223,6 +250,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 
   for (; im < img_end; im += kConvWaves) {
     // ---- image registers -> zero-padded LDS buffer; then prefetch the next image ---------------
+    float px_max = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i = lane + 64 * j;
@@ -230,8 +258,20 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         const int y = i / row4, x4 = i - y * row4;
         float* d = img + (y + 1) * kImgW + 4 * x4 + 1;
         d[0] = pre[j].x, d[1] = pre[j].y, d[2] = pre[j].z, d[3] = pre[j].w;
+        px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
       }
     }
+    // scale of this image's conv1 activations from the bound on them, and the factor that takes it and the
+    // weights' scale out again (all wave-uniform; non-negative floats order like their bit patterns)
+    px_max = row16_max(px_max);
+    const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
+                                     __builtin_amdgcn_readlane(__float_as_uint(px_max), 16)),
+                                 max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 32),
+                                     __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
+    const float a1_bound = fmaf(__uint_as_float(px_bits), bound_w1, bound_b1);
+    const float s_a1 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(a1_bound))));
+    const float u_a2 = pow2_reciprocal(s_a1) * u_w2;
+    const bool image_bad = member_bad || !(a1_bound <= kFltMax);
     if (im + kConvWaves < img_end) {
       const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(im + kConvWaves) * H * H);
 #pragma unroll
@@ -240,7 +280,6 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
     wave_sync();
 
-    float a1_max = 0.f;  // largest conv1 activation of this image seen by this lane
     zero_band_row(bandb, 0);  // band 0, row 0: the border above the image
     int b3 = 0;               // b mod 3: buffer of band b
 #pragma unroll 1
@@ -261,7 +300,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
           }
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            float o00 = 0.f, o01 = 0.f, o10 = 0.f, o11 = 0.f;
+            float o00 = bias1v[c], o01 = o00, o10 = o00, o11 = o00;
 #pragma unroll
             for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
@@ -272,10 +311,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
                 o10 = fmaf(p[dy + 1][dx], wv, o10);
                 o11 = fmaf(p[dy + 1][dx + 1], wv, o11);
               }
-            v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) + bias1v[c], 0.f);
+            v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) * s_a1, 0.f);  // stored times s_a1
           }
-          a1_max = fmaxf(fmaxf(a1_max, v[0]), v[1]);
-          a1_max = fmaxf(fmaxf(a1_max, v[2]), v[3]);
         }
         // two fp16 terms of the four channels: 8 bytes per term
         uint2 term[2];
@@ -322,9 +359,12 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         acc1[i] = fmaf(low1[i], kSplitLowUnscale, acc1[i]);
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n
-      if (q < H4) a2[((b - 1) * H4 + q) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])) + bias2, 0.f);
+      if (q < H4)
+        a2[((b - 1) * H4 + q) * kC2 + n] =
+            fmaxf(fmaf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])), u_a2, bias2), 0.f);
       if (q + 4 < H4)
-        a2[((b - 1) * H4 + q + 4) * kC2 + n] = fmaxf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])) + bias2, 0.f);
+        a2[((b - 1) * H4 + q + 4) * kC2 + n] =
+            fmaxf(fmaf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])), u_a2, bias2), 0.f);
       wave_sync();
     }
 
@@ -354,7 +394,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       logit += __shfl_xor(logit, 32, 64);
       logit += bias_d;
     }
-    if (w2_bad || __any(!(a1_max <= kSplitMax))) logit = __builtin_nanf("");  // outside the range of the split
+    if (image_bad) logit = __builtin_nanf("");  // a non-finite weight or pixel: what fp32 arithmetic would propagate
     wave_sync();
     // both scratch uses sat on zero-padded buffers: restore the zeros (the next image's
     // interior is rewritten anyway, the borders must read as zero again)

@@ -20,10 +20,16 @@
 // of one sample: the cell update is lane-local, c stays in registers, and h' leaves as one 8-byte
 // LDS store per split term.  h is kept in LDS as two half-precision terms (split16.h: 22
 // significand bits, three matrix instructions per product, within a few 1e-7 of fp32 arithmetic).
-// h lies in (-1, 1) and is stored times 2^14, the weights are stored times 2^8, so the gate
-// pre-activations come out times 2^22 and the factor is folded into the exp2 arguments of the
-// sigmoids and tanh; only the weights have to be checked against the fp16 range (|w| < 255.9),
-// and a member outside it gets NaN logits.  The input term needs no product at all: a
+// h lies in (-1, 1) and is stored times 2^14; the recurrent weights of a wave are stored times a power
+// of two s_w, so the gate pre-activations come out times 2^14 s_w and the factor is folded into the
+// exp2 arguments of the sigmoids and tanh.  The kernel is built twice.  The first build takes s_w = 2^8,
+// which holds every weight below 255.9, checks the weights as it loads them, and marks a member that has a
+// larger one (its result is a NaN with a payload of its own).  The second build is launched right behind
+// it over the same grid: a workgroup whose member is not marked exits at once; for a marked member each
+// wave first reads its weights once more to find their largest magnitude and scales them by the power of
+// two that fits it, so any finite weight is representable.  Members in range pay one empty workgroup.
+// (The output layer, being small, always takes its scale from its largest weight.)
+// The input term needs no product at all: a
 // one-hot token selects a row of Wx, which is kept with the bias added in an LDS table.  A step
 // writes h' into a buffer nobody reads, so one workgroup barrier per step suffices.  Samples are
 // processed in chunks of 64 (four column tiles); two chunks are in flight per pass (three h
@@ -45,16 +51,18 @@ namespace {
 constexpr int kChunk = 64;            // samples per pass: four column tiles
 constexpr int kMaxV = 16, kMaxOut = 16, kMaxLq = 32, kMaxLa = 16;
 constexpr float kSH = 16384.0f;                 // 2^14: scale of the stored h
-constexpr float kSW = 256.0f;                   // 2^8: scale of the stored weights
-constexpr float kSA = kSH * kSW;                // 2^22: scale of the accumulators
-constexpr float kUA = 1.0f / kSA;
+constexpr float kSWDefault = 256.0f;            // 2^8: scale of the stored weights unless one of them would overflow
+constexpr float kSplitMax = 65504.0f;           // largest finite fp16
+constexpr uint32_t kMarkBits = 0x7fc5eed5u;     // the quiet NaN that marks a member for the second build
 constexpr float kLog2e = 1.4426950408889634f;
 
-// sigmoid and tanh of a pre-activation that is held times 2^22 (the factor rides in the exp2 argument)
-__device__ __forceinline__ float exp_neg_scaled(float A) { return __builtin_amdgcn_exp2f((-kLog2e * kUA) * A); }
-__device__ __forceinline__ float sigmoid_scaled(float A) { return __builtin_amdgcn_rcpf(1.0f + exp_neg_scaled(A)); }
-__device__ __forceinline__ float tanh_scaled(float A) {
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f((2.0f * kLog2e * kUA) * A) + 1.0f);
+// sigmoid and tanh of a pre-activation that is held times 1 / u (k = log2(e) u rides in the exp2 argument)
+__device__ __forceinline__ float exp_neg_scaled(float A, float k) { return __builtin_amdgcn_exp2f((-k) * A); }
+__device__ __forceinline__ float sigmoid_scaled(float A, float k) {
+  return __builtin_amdgcn_rcpf(1.0f + exp_neg_scaled(A, k));
+}
+__device__ __forceinline__ float tanh_scaled(float A, float k) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f((2.0f * k) * A) + 1.0f);
 }
 
 __device__ __forceinline__ float tanh_fast(float x) {
@@ -75,7 +83,7 @@ struct LstmArgs {
 template <int H, typename TokOf>
 __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], floatx4 (&cst)[4], const float* tab,
                                           const unsigned char* hc, unsigned char* hn, int wave, int j, int q,
-                                          TokOf tok_of) {
+                                          float k_u, TokOf tok_of) {
   constexpr int KS = H / 32, kRowB = (H + 8) * 2, kTermB = kChunk * kRowB, kTabRow = 4 * H + 4;
 #pragma unroll
   for (int st = 0; st < 4; ++st) {
@@ -108,10 +116,10 @@ __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], float
       const float af = fmaf(low[1][i], kSplitLowUnscale, acc[1][i]);
       const float ag = fmaf(low[2][i], kSplitLowUnscale, acc[2][i]);
       const float ao = fmaf(low[3][i], kSplitLowUnscale, acc[3][i]);
-      const float c = fmaf(sigmoid_scaled(af), cst[st][i], sigmoid_scaled(ai) * tanh_scaled(ag));
+      const float c = fmaf(sigmoid_scaled(af, k_u), cst[st][i], sigmoid_scaled(ai, k_u) * tanh_scaled(ag, k_u));
       cst[st][i] = c;
       // 2^14 sigmoid(a_o) = 1 / (2^-14 (1 + e^-a_o))
-      const float so = __builtin_amdgcn_rcpf(fmaf(exp_neg_scaled(ao), 1.0f / kSH, 1.0f / kSH));
+      const float so = __builtin_amdgcn_rcpf(fmaf(exp_neg_scaled(ao, k_u), 1.0f / kSH, 1.0f / kSH));
       hs[i] = so * tanh_fast(c);
     }
     uint2 lead, resid;
@@ -125,7 +133,8 @@ __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], float
 
 }  // namespace
 
-template <int H>
+// DYNAMIC: the second build (see the head of the file).
+template <int H, bool DYNAMIC>
 __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   constexpr int NW = H / 16;            // waves
   constexpr int KS = H / 32;            // matrix-core steps over the hidden units
@@ -141,7 +150,9 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   __shared__ unsigned char tokq[2 * kChunk * kMaxLq];
   __shared__ unsigned char toka[2 * kChunk * kMaxLa];
   __shared__ float wave_loss[NW];
-  __shared__ int out_of_range;
+  __shared__ float wave_scale[NW];  // 2^14 s_w of each wave's columns of the active cell (for the input table)
+  __shared__ float wg_max[NW];
+  __shared__ int refetch;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -152,23 +163,41 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   const int cell_size = V * G4 + H * G4 + G4;
   const float* Wo = theta + 2 * cell_size;
   const float* bo = Wo + H * n_out;
+  // where the mark of this member lives: its fitness, or else its first logit
+  float* const mark = a.fitness ? a.fitness + member
+                                : a.logits + static_cast<size_t>(member) * a.B * La * n_out;
+  if (DYNAMIC) {
+    if (tid == 0) refetch = __float_as_uint(*mark) == kMarkBits;
+    __syncthreads();
+    if (!refetch) return;
+  }
+  float range_max = 0.f;  // first build: largest |weight| this thread has seen
 
-  // ---- once: output layer as A operands (row j = output j, zero beyond n_out), bias of this lane's rows ----
-  float range_max = 0.f;
-  for (int i = tid; i < KS * 64; i += 4 * H) {
-    const int kb = i >> 6, l = i & 63, jj = l & 15, qq = l >> 4;
-    float x[8];
+  // ---- once: output layer as A operands (row j = output j, zero beyond n_out), scaled by the power of two that
+  //      fits its largest weight; bias of this lane's rows ----
+  float u_o;  // 1 / (2^14 s_o)
+  {
+    float m = 0.f;
+    for (int i = tid; i < H * n_out; i += 4 * H) m = fmaxf(m, fabsf(Wo[i]));
+    m = wave_max(m);
+    if (lane == 0) wg_max[wave] = m;
+    __syncthreads();
+    m = wg_max[0];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      x[e] = jj < n_out ? kSW * Wo[(32 * kb + 8 * qq + e) * n_out + jj] : 0.f;
-      range_max = fmaxf(range_max, fabsf(x[e]));
+    for (int w = 1; w < NW; ++w) m = fmaxf(m, wg_max[w]);
+    const float s_o = split_pow2_scale(m);
+    u_o = pow2_reciprocal(s_o) * (1.0f / kSH);
+    for (int i = tid; i < KS * 64; i += 4 * H) {
+      const int kb = i >> 6, l = i & 63, jj = l & 15, qq = l >> 4;
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = jj < n_out ? s_o * Wo[(32 * kb + 8 * qq + e) * n_out + jj] : 0.f;
+      split2_x8(x, wo_s[0][kb][l], wo_s[1][kb][l]);
     }
-    split2_x8(x, wo_s[0][kb][l], wo_s[1][kb][l]);
   }
   float bo4[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) bo4[i] = 4 * q + i < n_out ? kSA * bo[4 * q + i] : 0.f;
-  if (tid == 0) out_of_range = 0;
+  for (int i = 0; i < 4; ++i) bo4[i] = 4 * q + i < n_out ? bo[4 * q + i] : 0.f;
 
   float loss_acc = 0.f;  // sum over this lane's samples and positions (lanes with q == 0 of waves 0..3)
 
@@ -219,6 +248,15 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
       constexpr int kVecPerThread = 4;           // float4 per thread and piece: 16 rows x H float4 over 4 H threads
       constexpr int kBatch = kPieces < 4 ? kPieces : 4;  // pieces fetched together (64 registers of raw weights)
       f16x8 wh[2][4][KS];
+      float s_w = kSWDefault;  // scale of this wave's weights (wave-uniform)
+      if (DYNAMIC) {
+        // the wave's own columns (gate g, unit 16 wave + j), all rows: their largest magnitude sets the scale
+        float w_max = 0.f;
+        for (int k = q; k < H; k += 4)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) w_max = fmaxf(w_max, fabsf(Wh[k * G4 + g * H + 16 * wave + j]));
+        s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
+      }
       float xlo[4][4];  // rows e = 0..3 of the current step, kept until rows 4..7 arrive
 #pragma unroll
       for (int p0 = 0; p0 < kPieces; p0 += kBatch) {
@@ -247,8 +285,8 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
           for (int g = 0; g < 4; ++g)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              x[g][e] = kSW * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
-              range_max = fmaxf(range_max, fabsf(x[g][e]));
+              x[g][e] = s_w * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
+              if (!DYNAMIC) range_max = fmaxf(range_max, fabsf(x[g][e]));
             }
           if ((pc & 1) == 0) {
 #pragma unroll
@@ -265,8 +303,14 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);  // the next batch is fetched only now: its registers are the ones just freed
       }
+      const float k_u = kLog2e * (pow2_reciprocal(s_w) * (1.0f / kSH));  // log2(e) / (2^14 s_w)
+      if (DYNAMIC && lane == 0) wave_scale[wave] = kSH * s_w;
       __syncthreads();  // every wave has read the last piece
-      for (int i = tid; i < V * G4; i += 4 * H) tab[(i / G4) * kTabRow + i % G4] = kSA * (Wx[i] + bg[i % G4]);
+      for (int i = tid; i < V * G4; i += 4 * H) {
+        const int col = i % G4;
+        // in the units of its wave's sums
+        tab[(i / G4) * kTabRow + col] = (DYNAMIC ? wave_scale[(col % H) >> 4] : kSH * kSWDefault) * (Wx[i] + bg[col]);
+      }
       __syncthreads();
 
       const int n_steps = phase == 0 ? Lq : La;
@@ -281,9 +325,9 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
           const unsigned char* hc = hbuf + cur * kBufB;
           unsigned char* hn = hbuf + spare * kBufB;
           if (phase == 0)
-            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q, [&](int s) { return int(tq[s * kMaxLq + t]); });
+            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q, k_u, [&](int s) { return int(tq[s * kMaxLq + t]); });
           else
-            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q,
+            lstm_step<H>(wh, cst[ch], tab, hc, hn, wave, j, q, k_u,
                          [&](int s) { return t == 0 ? V - 1 : int(ta[s * kMaxLa + t - 1]); });
           __syncthreads();  // h' is complete; nobody reads the old h any more
           const int old = cur;
@@ -294,7 +338,7 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
             // ---- logits of answer position t for sample tile `wave`: rows = outputs, columns = samples ----
             const int s = 16 * wave + j;
             const unsigned char* src = hbuf + cur * kBufB + s * kRowB + 16 * q;
-            floatx4 lg = {bo4[0], bo4[1], bo4[2], bo4[3]}, lw = {0.f, 0.f, 0.f, 0.f};
+            floatx4 lg = {0.f, 0.f, 0.f, 0.f}, lw = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kb = 0; kb < KS; ++kb) {
               const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
@@ -306,7 +350,7 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
             }
             float z[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) z[i] = fmaf(lw[i], kSplitLowUnscale, lg[i]) * kUA;
+            for (int i = 0; i < 4; ++i) z[i] = fmaf(fmaf(lw[i], kSplitLowUnscale, lg[i]), u_o, bo4[i]);
             const int gs = c0 + ch * kChunk + s;  // sample index in the batch
             const bool valid = gs < a.B;
             if (a.logits && valid) {
@@ -340,23 +384,22 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
     }
   }
 
-  // ---- a weight outside the fp16 range (or NaN) anywhere in the workgroup poisons the member ----
+  // ---- first build: a weight beyond the default scale's range anywhere in the workgroup marks the member ----
   __syncthreads();
-  if (!(range_max <= kSplitMax)) out_of_range = 1;
+  if (!DYNAMIC) {
+    if (tid == 0) refetch = 0;
+    __syncthreads();
+    if (range_max > kSplitMax) refetch = 1;
+  }
   // ---- fitness: lanes in a fixed order, then waves 0..3 in order ----
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) loss_acc += __shfl_xor(loss_acc, o, 64);
   if (lane == 0) wave_loss[wave] = loss_acc;
   __syncthreads();
-  if (out_of_range && a.logits) {
-    const size_t n = static_cast<size_t>(a.B) * La * n_out;
-    float* out = a.logits + static_cast<size_t>(member) * n;
-    for (size_t i = tid; i < n; i += 4 * H) out[i] = __builtin_nanf("");
-  }
-  if (tid == 0 && a.fitness) {
+  if (tid == 0) {
     const float total = ((wave_loss[0] + wave_loss[1]) + wave_loss[2]) + wave_loss[3];
-    a.fitness[member] =
-        out_of_range ? __builtin_nanf("") : -total / (static_cast<float>(a.B) * static_cast<float>(La));
+    if (a.fitness) a.fitness[member] = -total / (static_cast<float>(a.B) * static_cast<float>(La));
+    if (!DYNAMIC && refetch) *mark = __uint_as_float(kMarkBits);
   }
 }
 
@@ -382,10 +425,13 @@ int launch_lstm_seq2seq(int V, int H, int n_out, const float* params, const int3
   a.params = params, a.query = query, a.answer = answer, a.fitness = fitness, a.logits = logits;
   a.P = static_cast<int>(lstm_param_count(V, H, n_out));
   a.B = B, a.Lq = Lq, a.La = La, a.V = V, a.n_out = n_out;
-  if (H == 128)
-    hipLaunchKernelGGL((lstm_seq2seq_kernel<128>), dim3(pop), dim3(512), 0, s, a);
-  else
-    hipLaunchKernelGGL((lstm_seq2seq_kernel<64>), dim3(pop), dim3(256), 0, s, a);
+  if (H == 128) {
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<128, false>), dim3(pop), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<128, true>), dim3(pop), dim3(512), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<64, false>), dim3(pop), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((lstm_seq2seq_kernel<64, true>), dim3(pop), dim3(256), 0, s, a);
+  }
   return check_launch("lstm_seq2seq_kernel");
 }
 

@@ -39,6 +39,8 @@ int conv_shape(const policy_desc* pd, ConvShape* sh) {
   EVO_REQUIRE(sh->H >= 4 && sh->c1 >= 1 && sh->c2 >= 1 && sh->n_cls >= 1, EVO_ERR_ARG,
               "convnet: dims must be {H, c1, c2, n_cls}, all positive");
   EVO_REQUIRE(sh->H % 4 == 0, EVO_ERR_ARG, "convnet: H must be a multiple of 4 (got %d)", sh->H);
+  const int rc = convnet_supported(*sh);  // bounds every dimension, so the count below cannot overflow
+  if (rc) return rc;
   const int feat = (sh->H / 4) * (sh->H / 4) * sh->c2;
   sh->P = 9 * sh->c1 + sh->c1 + 9 * sh->c1 * sh->c2 + sh->c2 + feat * sh->n_cls + sh->n_cls;
   return EVO_OK;
@@ -214,6 +216,8 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     const int dtype = pd ? pd->dtype : EVO_F32;
     EVO_REQUIRE(dtype == EVO_F32 || dtype == EVO_BF16, EVO_ERR_ARG, "sphere: bad dtype");
     EVO_REQUIRE(td->work_dev != nullptr, EVO_ERR_ARG, "sphere: work_dev is null but rollout_workspace_bytes() > 0");
+    EVO_REQUIRE(aligned16(td->target_dev) && aligned16(td->work_dev), EVO_ERR_ARG,
+                "sphere: x_star and work_dev must be 16-byte aligned");
     return launch_sphere(params_dev, dtype, static_cast<const float*>(td->target_dev), pop, td->P,
                          static_cast<float*>(td->work_dev), fitness_dev, s);
   }

@@ -13,8 +13,11 @@
 // taken against the value that is actually stored, so the pair is converted once and the same
 // register feeds both uses.  A leading term that came out as zero is harmless: the whole value
 // then sits in m (11 bits of it), and the tensor scales keep such values below 2^-14 / s.
-// (2) The leading term overflows beyond 65504 / s: callers check their operands against
-// kSplitMax and poison the result with NaN instead of returning a wrong finite value.
+// (2) The leading term overflows beyond 65504 / s.  Tensors whose magnitude is not bounded by
+// construction (weights; activations behind a ReLU or no activation) therefore get their power of
+// two at run time, from their largest magnitude or from a bound on it (split_pow2_scale): any finite
+// fp32 value is then representable, and a non-finite one propagates as NaN / infinity as it would
+// in fp32 arithmetic.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -27,7 +30,25 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kSplitLowScale = 2048.0f;           // 2^11: the residual term is stored times this
 constexpr float kSplitLowUnscale = 1.0f / 2048.0f;  // factor of the second accumulator
-constexpr float kSplitMax = 65504.0f;               // largest finite fp16: bound on |s x|
+
+// The power of two s that puts a tensor whose magnitudes are bounded by `bound` just below the top of
+// fp16's range: s * bound in [2^14, 2^15).  s is limited to [2^-100, 2^64]: beyond 2^64 the values are
+// below 2^-50 and simply sit lower in the format (they do not matter next to biases of any size that
+// fp32 sums could hold them against); 2^-100 is reached only by bounds near the top of fp32's range.
+__device__ __forceinline__ float split_pow2_scale(float bound) {
+  const int E = (__float_as_int(bound) >> 23) & 0xff;  // biased exponent: bound in [2^(E-127), 2^(E-126))
+  const int e = min(max(268 - E, 27), 191);            // biased exponent of s = 2^(14 - (E - 127))
+  return __int_as_float(e << 23);
+}
+// 1 / s for a power of two s (exact).
+__device__ __forceinline__ float pow2_reciprocal(float s) { return __int_as_float((254 << 23) - __float_as_int(s)); }
+
+// Largest value over the 64 lanes of a wave, in every lane.
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
 
 // Two values -> the packed leading terms and the packed scaled residual terms.
 __device__ __forceinline__ void split2_pair(float x0, float x1, uint32_t& lead, uint32_t& resid) {

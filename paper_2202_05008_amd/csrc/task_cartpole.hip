@@ -22,12 +22,13 @@
 // of one roll-out: after the activation they are split into two half-precision terms
 // (split16.h) and stored with one 8-byte LDS write per term.  Layer 2 (K = H) then runs on the
 // fp16 instruction (16 cycles for 8192 multiply-adds against 32 cycles for 1024 of the fp32 one),
-// three instructions per product, within a few 1e-7 of fp32 arithmetic.  The activations are
-// stored times 2^14 when they come from a tanh (times 2^4 otherwise), the weights times 2^8; the
-// factor of the layer-2 pre-activation rides in the argument of the next activation.  The weights
-// are checked against the fp16 range (|w| < 255.9) when they are loaded, activations other than
-// tanh are tracked, and a member outside the range gets a NaN fitness (it then ranks lowest)
-// instead of a wrong finite one.
+// three instructions per product, within a few 1e-7 of fp32 arithmetic.  Both operands carry a
+// power-of-two scale that keeps them inside fp16's range whatever their magnitude: the weights of a
+// wave's 16 neurons get theirs from their largest magnitude when they are loaded; activations behind
+// a tanh are stored times 2^14; activations behind a ReLU or no activation get a scale per roll-out
+// and step from a bound on them (sum_k max_n |W1[k][n]| |obs_k| + max_n |b1[n]|).  The factor of the
+// layer-2 pre-activation and the layer-2 bias ride in the multiply-add that feeds the next
+// activation.
 #include "kernels.h"
 #include "philox.h"
 #include "split16.h"
@@ -40,8 +41,6 @@
 namespace evo {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-constexpr float kSW2 = 256.0f;  // 2^8: scale of the stored layer-2 weights
 
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
@@ -74,10 +73,15 @@ __device__ __forceinline__ float act_apply(float x, int act) {
   return x;
 }
 
-// scale * tanh(x * inv): a pre-activation that is held times 1 / inv, a result wanted times scale
-__device__ __forceinline__ float tanh_scaled(float x, float inv, float scale) {
-  const float e = __builtin_amdgcn_exp2f((2.885390081777927f * inv) * x);
+// scale * tanh(x): a result wanted times scale
+__device__ __forceinline__ float tanh_times(float x, float scale) {
+  const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);
   return fmaf(-2.0f * scale, __builtin_amdgcn_rcpf(e + 1.0f), scale);
+}
+// tanh(x u + b) with k_u = 2 log2(e) u and k_b = 2 log2(e) b formed once: a pre-activation held times 1 / u
+__device__ __forceinline__ float tanh_affine(float x, float k_u, float k_b) {
+  const float e = __builtin_amdgcn_exp2f(fmaf(x, k_u, k_b));
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
 }
 
 // sin and cos of an angle in radians: two-term reduction by 2 pi (2 pi = hi - lo with hi the fp32
@@ -143,9 +147,7 @@ template <int NT, bool TWO, bool TANH, bool TRACE>
 __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int act1_rt, int act2_rt, int act3_rt) {
   const int act1 = TANH ? EVO_ACT_TANH : act1_rt, act2 = TANH ? EVO_ACT_TANH : act2_rt;
   const int act3 = TANH ? EVO_ACT_TANH : act3_rt;
-  constexpr float kSH1 = TANH ? 16384.0f : 16.0f;  // scale of the stored layer-1 activations: 2^14 behind a tanh
-  constexpr float kSA2 = kSH1 * kSW2;              // scale of the layer-2 accumulators
-  constexpr float kUA2 = 1.0f / kSA2;
+  constexpr float kSTanh = 16384.0f;  // 2^14: scale of stored activations that a tanh bounds
   constexpr int H = 16 * NT;
   constexpr int KP = H < 32 ? 32 : H;      // contraction length of layer 2, padded to the instruction's 32
   constexpr int KS2 = KP / 32;             // matrix-core steps of layer 2 per split term pair
@@ -166,34 +168,64 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding)
   const float bias1 = theta[5 * H + col];
   const float* th2 = theta + 5 * H + H;
-  f16x8 w2b[2][TWO ? KS2 : 1];  // [term][step]: element e is W2[32 step + 8 q + e][col]
-  float range_max = 0.f;         // largest |layer-2 weight| (and, unless tanh bounds them, |activation|) of this lane
+  f16x8 w2b[2][TWO ? KS2 : 1];  // [term][step]: element e is s_w W2[32 step + 8 q + e][col]
   float bias1t[4];               // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
   float bias2 = 0.f, w3, b3;
+  float u_w = 1.0f;              // 1 / s_w, s_w the scale of this wave's layer-2 weights
+  float bound_w[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, bound_b = 0.f;  // !TANH: max_n |W1[k][n]|, max_n |b1[n]|
   if (TWO) {
+    float x[KS2][8];
+    float w_max = 0.f;
 #pragma unroll
-    for (int s = 0; s < KS2; ++s) {
-      float x[8];
+    for (int s = 0; s < KS2; ++s)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int k = 32 * s + 8 * q + e;
-        x[e] = k < H ? kSW2 * th2[k * H + col] : 0.f;
-        range_max = fmaxf(range_max, fabsf(x[e]));
+        x[s][e] = k < H ? th2[k * H + col] : 0.f;
+        w_max = fmaxf(w_max, fabsf(x[s][e]));
       }
-      split2_x8(x, w2b[0][s], w2b[1][s]);
+    const float s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
+    u_w = pow2_reciprocal(s_w);
+#pragma unroll
+    for (int s = 0; s < KS2; ++s) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[s][e] *= s_w;
+      split2_x8(x[s], w2b[0][s], w2b[1][s]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) bias1t[i] = theta[5 * H + 16 * wave + 4 * q + i];
-    bias2 = kSA2 * th2[H * H + col];
+    bias2 = th2[H * H + col];
     w3 = th2[H * H + H + col];
     b3 = th2[H * H + H + H];
     // columns H .. KP - 1 of the activation rows are never written and must read as zero
     for (int i = threadIdx.x; i < 2 * kTermB / 4; i += 64 * NT) reinterpret_cast<uint32_t*>(hb)[i] = 0u;
+    if (!TANH) {
+      // bounds on the layer-1 pre-activations of the whole member: the largest weight per input, the largest bias
+      __shared__ float wg_max[NT][6];
+      float m[6];
+#pragma unroll
+      for (int k = 0; k < 5; ++k) m[k] = wave_max(fabsf(theta[k * H + col]));
+      m[5] = wave_max(fabsf(bias1));
+      if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < 6; ++k) wg_max[wave][k] = m[k];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < 6; ++k) {
+        float v = wg_max[0][k];
+#pragma unroll
+        for (int w = 1; w < NT; ++w) v = fmaxf(v, wg_max[w][k]);
+        if (k < 5) bound_w[k] = v; else bound_b = v;
+      }
+    }
     __syncthreads();
   } else {
     w3 = th2[col];
     b3 = th2[H];
   }
+  // the factor 1 / (2^14 s_w) and the bias of the layer-2 pre-activation inside the tanh's exp2 argument
+  const float k_u2 = 2.885390081777927f * (u_w * (1.0f / kSTanh)), k_b2 = 2.885390081777927f * bias2;
 
   float total = 0.f;  // sum of the returns of this lane's roll-outs over all passes
   for (int r0 = 0; r0 < a.R; r0 += 16) {
@@ -223,12 +255,28 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a, a0, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1b, a1, acc, 0, 0, 0);
         // neurons 16 wave + 4 q .. + 3 of roll-out j: two terms, 8 bytes each
+        float u_row[4];  // !TANH: 1 / (scale of the stored activations) of roll-outs 4 q + i
         {
           float h1[4];
+          if (TANH) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            h1[i] = TANH ? tanh_scaled(acc[i], 1.0f, kSH1) : kSH1 * act_apply(acc[i], act1);
-            if (!TANH) range_max = fmaxf(range_max, fabsf(h1[i]));
+            for (int i = 0; i < 4; ++i) h1[i] = tanh_times(acc[i], kSTanh);
+          } else {
+            // scale of this roll-out's activations at this step, from the bound on the pre-activations
+            // (every wave carries the same state and forms the same number); a tanh bounds them by 1
+            float bound = bound_b;
+            bound = fmaf(bound_w[0], fabsf(s.x), bound);
+            bound = fmaf(bound_w[1], fabsf(s.xd), bound);
+            bound = fmaf(bound_w[2], fabsf(cs), bound);
+            bound = fmaf(bound_w[3], fabsf(sn), bound);
+            bound = fmaf(bound_w[4], fabsf(s.thd), bound);
+            const float s_row = act1 == EVO_ACT_TANH ? kSTanh : split_pow2_scale(bound);
+            const float u_mine = pow2_reciprocal(s_row) * u_w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              h1[i] = s_row * act_apply(acc[i], act1);
+              u_row[i] = __shfl(u_mine, 4 * q + i, 64);  // lane r < 16 holds roll-out r
+            }
           }
           uint2 lead, resid;
           split2_pair(h1[0], h1[1], lead.x, resid.x);
@@ -239,8 +287,8 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         }
         __syncthreads();
         // ---- layer 2: lane (row j, k group q) reads 8 consecutive activations per term and step ----
-        floatx4 acc2 = {bias2, bias2, bias2, bias2};  // bias + h h'
-        floatx4 low2 = {0.f, 0.f, 0.f, 0.f};          // 2^11 (h m' + m h')
+        floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};  // h h'
+        floatx4 low2 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
         const unsigned char* src = hb + j * kRowB + 16 * q;
 #pragma unroll
         for (int s2 = 0; s2 < KS2; ++s2) {
@@ -253,8 +301,8 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float pre = fmaf(low2[i], kSplitLowUnscale, acc2[i]);  // layer-2 pre-activation times kSA2
-          p[i] = (TANH ? tanh_scaled(pre, kUA2, 1.0f) : act_apply(pre * kUA2, act2)) * w3;
+          const float pre = fmaf(low2[i], kSplitLowUnscale, acc2[i]);  // layer-2 product times the two scales
+          p[i] = (TANH ? tanh_affine(pre, k_u2, k_b2) : act_apply(fmaf(pre, u_row[i], bias2), act2)) * w3;
         }
       } else {
         floatx4 acc = {bias1, bias1, bias1, bias1};
@@ -308,15 +356,6 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     }
     total += valid ? ret : 0.f;
     __syncthreads();
-  }
-  // a layer-2 operand outside the fp16 range (or NaN) anywhere in the workgroup poisons the member
-  if (TWO) {
-    __shared__ int out_of_range;
-    if (threadIdx.x == 0) out_of_range = 0;
-    __syncthreads();
-    if (!(range_max <= kSplitMax)) out_of_range = 1;
-    __syncthreads();
-    if (out_of_range) total = __builtin_nanf("");
   }
   // ---- fitness = mean return over the roll-outs (rows j = 0..15, fixed order) -----------------
   total = row16_sum(total);

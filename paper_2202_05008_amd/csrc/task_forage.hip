@@ -20,6 +20,8 @@
 #include <algorithm>
 
 #include "kernels.h"
+
+#include <atomic>
 #include "philox.h"
 
 namespace evo {
@@ -649,13 +651,13 @@ template <int H>
 static int launch_step(const StepArgs& a, hipStream_t s) {
   const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
   // more than 64 KB of dynamic LDS has to be asked for, once per kernel and device
-  static bool raised[64] = {};
+  static std::atomic<bool> raised[64];  // zero-initialised; a second setter does the same harmless call
   int device = 0;
   hipError_t e = hipGetDevice(&device);
-  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device]) {
+  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device].load()) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_step_kernel<H>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
-    raised[device] = e == hipSuccess;
+    raised[device].store(e == hipSuccess);
   }
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the step kernel failed: %s",
               hipGetErrorString(e));
@@ -771,13 +773,13 @@ template <int H>
 static int launch_solo(const SoloArgs& a, hipStream_t s) {
   constexpr int LPA = solo_lanes(H);
   const size_t lds = solo_lds_bytes(a.c.n_food, a.c.n_items, LPA);
-  static bool raised[64] = {};
+  static std::atomic<bool> raised[64];  // zero-initialised; a second setter does the same harmless call
   int device = 0;
   hipError_t e = hipGetDevice(&device);
-  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device]) {
+  if (e == hipSuccess && device >= 0 && device < 64 && !raised[device].load()) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H, LPA>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
-    raised[device] = e == hipSuccess;
+    raised[device].store(e == hipSuccess);
   }
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the episode kernel failed: %s",
               hipGetErrorString(e));

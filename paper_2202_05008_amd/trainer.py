@@ -1,6 +1,6 @@
 """Minimal training shell around the C ABI: the loop, testing of the centre, JSON-lines logging
-and checkpoints with exact resume (the paper's trainer, Section 2: "training loop, logging,
-testing, periodic model saving").
+and checkpoints with exact resume (the trainer of Section 2: loop, log, test of the centre,
+periodic saving).
 
 Host-side orchestration only: every number it logs is produced by the library's kernels
 (ask, rollout, tell, pgpe_center); torch supplies device memory, the stream and the

@@ -150,18 +150,43 @@ CASES = [
     ((5, 32, 32, 1), (2, 0, 1), 3, 20, 200, 0.3, CP),                       # two passes of sixteen roll-outs
     ((5, 16, 1), (1, 0), 3, 16, 300, 0.5, CP),                              # one hidden layer, unbounded action
     ((5, 64, 1), (1, 1), 2, 7, 1000, 1.0, CP),
+    # operands far beyond fp16's own range (the scales of the two-term products are set at run time)
+    ((5, 64, 64, 1), (1, 1, 1), 3, 16, 300, "huge", CP),
+    ((5, 64, 64, 1), (2, 2, 1), 3, 16, 300, "huge", CP),
+    ((5, 32, 32, 1), (0, 2, 1), 3, 16, 300, "huge", CP),
 ]
+
+
+def _params(dims, acts, pop, scale):
+    """Random parameters; "huge": members whose layer-2 operands lie far outside fp16's range, built so that the
+    network stays well conditioned (an fp32 evaluation of sums of thousands that cancel, or of a tanh fed by
+    pre-activations of +-1000 that cross zero, is itself off by more than 1e-5 of its output)."""
+    P = mlp_param_count(dims)
+    if scale != "huge":
+        return gen.random_params(26, pop, P, scale)
+    H = dims[1]
+    params = gen.random_params(26, pop, P, 0.5)
+    l2 = slice(5 * H + H, 5 * H + H + H * H)
+    params[0, 5 * H + H + 70] = -1.0e5               # one weight of the second layer
+    params[2, l2] *= 1.0e-6                          # all of layer 2 tiny next to its ordinary biases
+    if acts[0] != 1:
+        # unbounded layer-1 activations in the thousands; positive weights behind them, so that the sums of
+        # layers 2 and 3 do not cancel; a small output layer brings the action's argument back to order one
+        params[1, :5 * H] *= 2000.0
+        params[1, 5 * H + H:] = np.abs(params[1, 5 * H + H:])
+        params[1, l2.stop + H:l2.stop + 2 * H] *= 1.0e-6
+    return params
 
 
 @pytest.mark.parametrize("dims,acts,pop,R,steps,scale,cp", CASES)
 def test_every_step_against_the_oracle(evo, dims, acts, pop, R, steps, scale, cp):
-    params = gen.random_params(26, pop, mlp_param_count(dims), scale)
+    params = _params(dims, acts, pop, scale)
     if len(dims) == 4 and dims[1] == 16:
         params[3] = 0.0                   # the zero policy: the free system
     seed, t = 31, 2
     trace, fin, ret, fit = run_trace(evo, dims, acts, dev(params), pop, R, steps, seed, t, cp)
     info = check_trace(params, dims, acts, host(trace), host(fin), host(ret), host(fit), seed, t, cp, 0.2,
-                       "dims %s scale %g" % (dims, scale))
+                       "dims %s acts %s scale %s" % (dims, acts, scale))
     print(info)
     if cp[7] < 1.0:
         assert 0.05 < info["dead"] < 0.95, "the case is meant to have episodes that end early and ones that do not"

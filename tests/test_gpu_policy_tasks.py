@@ -122,22 +122,33 @@ def test_convnet_keeps_fp32_accuracy_over_value_ranges(evo, scale):
     assert_close(host(out), opolicy.convnet_forward(params, img, 8, 16, n_cls), 1e-5, "convnet logits, scale %g" % scale)
 
 
-def test_convnet_beyond_the_fp16_range_is_loud(evo):
-    """A conv2 weight of 1e5 is outside the range of the leading fp16 term: that member's logits are
-    non-finite (its fitness then ranks lowest), the other members are untouched."""
-    H, n_cls, pop, B = 28, 10, 2, 5
+def test_convnet_any_finite_magnitude(evo):
+    """The operands of the fp16 matrix products carry run-time powers of two, so nothing finite is out of
+    range: a conv2 weight of 1e5, images whose conv1 activations reach 1e4 and beyond, tiny weights next to
+    ordinary biases all give the oracle's logits; a non-finite weight gives that member NaN logits."""
+    H, n_cls, pop, B = 28, 10, 5, 6
     P = convnet_param_count(8, 16, n_cls, H)
     params = gen.random_params(33, pop, P, 0.2)
     params[1, 88 + 7] = 1.0e5                      # one weight of W2 (W1 and b1 take 80 + 8 entries)
+    params[2, :80] *= 300.0                        # conv1 weights: activations far beyond 4094 on bright images
+    params[3, 88:88 + 1152] *= 1.0e-6              # all of W2 tiny, its biases ordinary
+    params[4, 88 + 100] = np.nan
     img, y = gen.mnist_shaped_batch(34, 1, B, n_cls, H)
+    img[1] *= 400.0                                # a bright image
+    img[2] *= 1.0e-4                               # and a dark one
     pd = evo.make_policy_desc(evo.EVO_POLICY_CONVNET, (H, 8, 16, n_cls))
     out = torch.empty(pop, B, n_cls, dtype=torch.float32, device="cuda")
     evo.pop_forward(pd, dev(params), dev(img), 0, out, pop, B)
     got = host(out)
-    assert_close(got[0], opolicy.convnet_forward(params[:1], img, 8, 16, n_cls)[0], 1e-5, "the in-range member")
-    assert not np.isfinite(got[1]).any()
+    ref = opolicy.convnet_forward(params[:4], img, 8, 16, n_cls)
+    assert np.abs(ref[2, 1]).max() > 1e4
+    for m in range(4):
+        for b in range(B):           # every (member, image) on its own scale
+            assert_close(got[m, b], ref[m, b], 1e-5, "member %d image %d" % (m, b))
+    assert np.isnan(got[4]).all()
     fit = _classify(evo, pd, dev(params), dev(img), dev(y), pop, B)
-    assert np.isfinite(fit[0]) and not np.isfinite(fit[1])
+    assert_scalar_rel(fit[:4], otasks.classify_fitness(ref, y), 1e-5, "fitness")
+    assert np.isnan(fit[4])
 
 
 # ---------------------------------------------------------------- bf16 MLP on the matrix cores
@@ -247,24 +258,25 @@ def test_cartpole_narrow_and_wide_reset(evo, init_scale):
 
 
 def test_cartpole_layer2_range(evo):
-    """Layer 2 runs on the fp16 matrix instruction with two-term operands: small and large weights
-    keep fp32 accuracy, and a weight beyond the fp16 range gives that member a NaN fitness."""
-    dims, acts, R = (5, 64, 64, 1), (1, 1, 1), 16
+    """Layer 2 runs on the fp16 matrix instruction with two-term operands whose scales are set at run time:
+    tiny weights keep fp32 accuracy, and so does a member with a layer-2 weight of 1e5 or with ReLU
+    activations in the thousands.  (Weights of order one and more over whole episodes: the step-by-step
+    gate of test_gpu_cartpole_trace.py.)"""
+    dims, R = (5, 64, 64, 1), 16
     P = mlp_param_count(dims)
-    # (large weights saturate the tanh units and make the closed loop so sensitive that any fp32
-    # evaluation leaves the fp64 trajectory within a few steps: two steps there, twelve for small weights)
-    for scale, steps in ((1e-3, 12), (1.0, 2)):
-        params = gen.random_params(41, 3, P, scale)
-        fit, ret, fin = _cartpole(evo, dims, acts, params, R, steps, 5, 1)
-        rfit, rret, rfin, _ = otasks.cartpole_rollout(params, dims, acts, 5, 1, R, steps, CP, return_details=True)
-        assert_close(fin, rfin, 1e-5, "final states, weight scale %g" % scale)
-        assert_scalar_rel(fit, rfit, 1e-5, "fitness, weight scale %g" % scale)
-    params = gen.random_params(42, 2, P, 0.5)
-    params[1, 5 * 64 + 64 + 70] = -1.0e5             # one weight of the second layer
-    fit, _, _ = _cartpole(evo, dims, acts, params, R, 12, 5, 1)
-    rfit = otasks.cartpole_rollout(params[:1], dims, acts, 5, 1, R, 12, CP)
-    assert_scalar_rel(fit[:1], rfit, 1e-5, "the in-range member")
-    assert np.isnan(fit[1])
+    params = gen.random_params(41, 3, P, 1e-3)
+    fit, ret, fin = _cartpole(evo, dims, (1, 1, 1), params, R, 12, 5, 1)
+    rfit, rret, rfin, _ = otasks.cartpole_rollout(params, dims, (1, 1, 1), 5, 1, R, 12, CP, return_details=True)
+    assert_close(fin, rfin, 1e-5, "final states, tiny weights")
+    assert_scalar_rel(fit, rfit, 1e-5, "fitness, tiny weights")
+    for acts in ((1, 1, 1), (2, 1, 1), (0, 2, 1)):     # one step from the reset: nothing for chaos to amplify
+        params = gen.random_params(42, 3, P, 0.5)
+        params[1, 5 * 64 + 64 + 70] = -1.0e5         # one weight of the second layer
+        params[2, :5 * 64] *= 2000.0                 # layer 1: pre-activations in the thousands
+        fit, ret, fin = _cartpole(evo, dims, acts, params, R, 1, 5, 1)
+        rfit, rret, rfin, _ = otasks.cartpole_rollout(params, dims, acts, 5, 1, R, 1, CP, return_details=True)
+        assert_close(fin, rfin, 1e-5, "final states, acts %s" % (acts,))
+        assert_scalar_rel(fit, rfit, 1e-5, "fitness, acts %s" % (acts,))
 
 
 def test_cartpole_termination_and_zero_policy(evo):

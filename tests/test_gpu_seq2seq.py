@@ -45,19 +45,46 @@ def test_logits_and_fitness_against_oracle(evo, H, pop, B, digits, scale):
     assert_scalar_rel(fit, os2s.fitness(ref, answer), 1e-5, "seq2seq fitness")
 
 
-def test_zero_weights_and_out_of_range(evo):
-    H, B = 64, 20
+@pytest.mark.parametrize("H", [64, 128])
+def test_zero_weights_and_any_finite_magnitude(evo, H):
+    """Zero weights give ln 10; recurrent or output weights beyond what the default scale of the fp16 operands
+    holds (255.9) send the member through the second build of the kernel, which scales each wave's weights
+    by their own largest magnitude: the oracle's logits again."""
+    B = 20
     P = os2s.param_count(H)
-    params = gen.random_params(53, 3, P, 0.3)
+    G4 = 4 * H
+    cell = 12 * G4 + H * G4 + G4
+    params = gen.random_params(53, 5, P, 0.3)
     params[0] = 0.0                                   # logits = 0: cross-entropy ln 10
-    params[2, 2 * (12 * 256) + 5] = 3.0e5             # a recurrent weight beyond the fp16 range
-    params[2, 12 * 256 + 77] = 3.0e5
+    params[2, 12 * G4 + 77] = 3.0e5                   # an encoder recurrent weight
+    params[2, cell + 12 * G4 + 5 * G4 + 9] = -1.0e3   # and a decoder one
+    # forty recurrent weights of both cells between 300 and 3e5, in every wave's columns.  They all sit in the row
+    # of hidden unit 5, which is pinned to h = tanh(1) sigmoid(20) by its biases: the gates they feed are then
+    # saturated one way or the other whatever the rest does.  (Huge weights on a unit whose h passes through
+    # zero, or a whole matrix of them, make the recurrence ill-conditioned beyond what fp32 arithmetic tracks:
+    # the rounding of h alone, 6e-8, times a weight of 300 moves a gate's argument by 2e-5.)
+    rng = np.random.default_rng(7)
+    k0 = 5
+    for c in range(2):
+        base = c * cell
+        for g, b in enumerate((20.0, -20.0, 20.0, 20.0)):
+            col = g * H + k0
+            params[3, base + np.arange(12) * G4 + col] = 0.0                 # Wx[:, col]
+            params[3, base + 12 * G4 + np.arange(H) * G4 + col] = 0.0        # Wh[:, col]
+            params[3, base + 12 * G4 + H * G4 + col] = b
+        for n in range(20):
+            col = int(rng.integers(0, G4))
+            if col % H == k0:
+                continue
+            params[3, base + 12 * G4 + k0 * G4 + col] = (300.0 * 10.0 ** rng.uniform(0, 3)) * rng.choice([-1.0, 1.0])
+    params[4, 2 * cell + 3] = 5.0e4                   # an output weight
     query, answer = gen.addition_batch(54, 2, B, 3)
     logits, fit = _run(evo, H, params, query, answer)
     assert np.all(logits[0] == 0.0) and abs(fit[0] + np.log(10.0)) < 1e-6
-    ref = os2s.forward(params[1:2], query, answer, H)
-    assert_close(logits[1], ref[0], 1e-5, "the in-range member")
-    assert np.isnan(logits[2]).all() and np.isnan(fit[2])
+    ref = os2s.forward(params, query, answer, H)
+    for m in range(1, 5):
+        assert_close(logits[m], ref[m], 1e-5, "member %d" % m)
+    assert_scalar_rel(fit[1:], os2s.fitness(ref, answer)[1:], 1e-5, "fitness")
 
 
 def test_unsupported_shapes_are_refused(evo):
