@@ -5,8 +5,11 @@
 
 A step is one generation of the named synthetic workload with every input already resident
 in device memory.  Prints ONE JSON line: whole-job throughput in member-evals/s, ms per
-generation, the roofline of the dominant kernel (timed with events on the launch stream) and
-the CPU oracle timed on a bounded sample of the same workload.
+generation, the roofline of the dominant kernel (timed with events on the launch stream), the
+CPU oracle timed on a bounded sample of the same workload (one thread, and all cores), and what
+this GPU measures for the quantities the roofline peaks are quoted for.  Without --workload the
+headline is cfg2 and the line also carries `per_config`: the same measurement for each of the five
+configurations.
 """
 import argparse
 import json
@@ -19,17 +22,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-# The ConvNet, cart-pole and LSTM kernels deliver fp32-accurate results (the algorithmic flops below
-# are fp32 flops) and are priced against the fp32 matrix peak, although their contractions are issued
-# as fp16 matrix instructions on two-term scaled operand splits (three instructions per product):
-# `frac` can therefore exceed 1; `mfma_f16_issued_*` prices the same launch as issued.
+# The ConvNet, cart-pole and LSTM kernels deliver fp32-accurate results, but their contractions are issued as
+# fp16 matrix instructions on two-term scaled operand splits (three instructions per product): `frac` prices
+# the launch as issued, against the fp16 matrix peak; `fp32_equivalent` prices the algorithmic fp32 flops
+# against the fp32 matrix peak (it can exceed 1, which says that peak is no bound for these kernels).  By the
+# counters in profiles/ all three are bound by vector-instruction issue, not by the matrix pipe.
 PEAK_MFMA_F32_TF = 157.3       # dense fp32 matrix
 PEAK_MFMA_BF16_TF = 2500.0     # dense bf16 / fp16 matrix
 PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 GHz x 2 flop)
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by what the same counters read for a 1 GiB copy in the same process (on this
-# box FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Sources: the summaries under profiles/.
+# box FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Sources: the summaries under profiles/.  Counters cannot be
+# read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2891893,       # profiles/mlp_f32_kernel_cfg1.md
     "cfg2": 32755287,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
@@ -44,6 +49,19 @@ MEASURED_TRAFFIC_BYTES = {
 
 # Timed generations per workload when --steps is not given (about a second of GPU time or less) and
 # the population of the oracle's bounded sample (about 10-30 s of CPU time on one core).
+# What the rocprofv3 counters in profiles/ say bounds the dominant kernel.
+BOUND_DETAIL = {
+    "cfg1": "launch latency: five launches of a few microseconds each (profiles/mlp_f32_kernel_cfg1.md)",
+    "cfg2": "vector-instruction issue: VALU busy 85 %, MFMA busy 21 % (profiles/convnet_kernel_cfg2.md)",
+    "cfg3": "vector-instruction issue along a 1000-step dependency chain: 42 % of wave time waiting "
+            "(profiles/cartpole_kernel_cfg3.md)",
+    "cfg4": "HBM weight stream: 64 flop per weight byte (profiles/mlp_bf16_stream_kernel_cfg4.md)",
+    "cfg5": "HBM write of the population in ask (profiles/ask_sphere_tell_kernels_cfg5.md)",
+    "seq2seq": "instruction issue: VALU busy 48 % + MFMA busy 37 %, which add up (profiles/lstm_seq2seq_kernel_seq2seq.md)",
+    "forage": "latency of one step launch: vector ALU 20 % busy (profiles/world_step_kernel_forage.md)",
+    "forage_solo": "one dependent chain per step: vector ALU 66 % busy (profiles/world_solo_kernel_forage_solo.md)",
+}
+
 DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20, "forage": 20, "forage_solo": 50}
 ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 96, "seq2seq": 32, "forage": 128, "forage_solo": 24}
 ORACLE_SAMPLE_GENERATIONS = {"cfg1": 600}
@@ -98,9 +116,9 @@ def _build_workload(name, seed, batch=None):
                 batches.append((torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)))
             c1, c2, ncls = c.dims
             per_img = 2.0 * (9 * c1 * 28 * 28 + 9 * c1 * c2 * 14 * 14 + 7 * 7 * c2 * ncls)
-            wl["roofline"] = ("mfma", per_img * c.pop * c.B, PEAK_MFMA_F32_TF, "TFLOP/s")
             # conv2 as issued: k padded from 72 to 96, three fp16 matrix instructions per product
-            wl["f16_issued_flops"] = 3.0 * 2.0 * 96 * c2 * 14 * 14 * c.pop * c.B
+            wl["roofline"] = ("valu-issue", 3.0 * 2.0 * 96 * c2 * 14 * 14 * c.pop * c.B, PEAK_MFMA_BF16_TF, "TFLOP/s")
+            wl["fp32_flops"] = per_img * c.pop * c.B
             wl["desc"] = "cfg2: MNIST-shaped synthetic images, per-member fp32 ConvNet P=9098, pop 256, batch 1024"
         tds = [with_work(lambda w, b=b: evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=b[0], target=b[1], work=w))
                for b in batches]
@@ -114,9 +132,10 @@ def _build_workload(name, seed, batch=None):
                                                   generation=t + 1, cp=c.cartpole, init_scale=c.init_scale,
                                                   generation_dev=wl.get("gen_dev"))
         flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.evals_per_generation
-        wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
         # layer 2 as issued: three fp16 matrix instructions per product (layer 1 runs on the fp32 instruction)
-        wl["f16_issued_flops"] = 3.0 * 2.0 * c.dims[1] * c.dims[2] * c.evals_per_generation
+        wl["roofline"] = ("valu-issue", 3.0 * 2.0 * c.dims[1] * c.dims[2] * c.evals_per_generation, PEAK_MFMA_BF16_TF,
+                          "TFLOP/s")
+        wl["fp32_flops"] = flops
         wl["desc"] = "cfg3: cart-pole swing-up, fp32 MLP 5-64-64-1, pop 1024 x 16 roll-outs x 1000 steps"
         wl["dtype"] = "f32"
     elif name == "cfg4":
@@ -156,8 +175,8 @@ def _build_workload(name, seed, batch=None):
         wl["n_tasks"] = len(tds)
         Lq, La = 2 * c.digits + 2, c.digits + 1
         flops = 2.0 * ((Lq + La) * H * 4 * H + La * H * n_out) * c.pop * c.B
-        wl["roofline"] = ("mfma", flops, PEAK_MFMA_F32_TF, "TFLOP/s")
-        wl["f16_issued_flops"] = 3.0 * flops      # every product is three fp16 matrix instructions
+        wl["roofline"] = ("valu-issue", 3.0 * flops, PEAK_MFMA_BF16_TF, "TFLOP/s")   # three fp16 instructions per product
+        wl["fp32_flops"] = flops
         wl["desc"] = ("seq2seq: LSTM encoder-decoder H=128 (P=145674) on three-digit addition strings, pop 1024, "
                       "128 strings per member")
         wl["dtype"] = "f32"
@@ -189,8 +208,22 @@ def _build_workload(name, seed, batch=None):
     return wl
 
 
+_POOL_TASK = None      # the task dict of the oracle's all-cores leg; worker processes inherit it through fork
+
+
+def _oracle_slice(job):
+    """Worker of the all-cores leg: the oracle's fitness of a slice of the population."""
+    from oracle import generation as ogen
+    params, seed, t = job
+    return ogen.evaluate(_POOL_TASK, params, seed, t)
+
+
 def _cpu_baseline(name, seed):
-    """The oracle, as it stands, on a bounded sample of the workload; one BLAS thread."""
+    """The oracle, as it stands, on a bounded sample of the workload: on one thread, and with the sample's
+    population split over all cores of this machine's share (worker processes, each on one BLAS thread; ask and
+    tell stay on the parent).  Runs before anything touches the GPU, so that the workers can be forked."""
+    global _POOL_TASK
+    import multiprocessing
     import numpy as np
     from threadpoolctl import threadpool_limits
     from oracle import pgpe as opgpe, generation as ogen
@@ -235,44 +268,91 @@ def _cpu_baseline(name, seed):
         for _ in range(gens):
             ogen.run_generation(st, task, seed, sample_pop, dtype)
         dt = time.perf_counter() - t0
-    return {"value": evals * gens / dt, "unit": "member-evals/s", "cores": 1, "kind": "oracle",
-            "sample": "%d generation(s) of %s with pop=%d (all other sizes as configured), %.1f s"
-                      % (gens, name, sample_pop, dt)}
+    out = {"value": evals * gens / dt, "unit": "member-evals/s", "cores": 1, "kind": "oracle",
+           "sample": "%d generation(s) of %s with pop=%d (all other sizes as configured), %.1f s"
+                     % (gens, name, sample_pop, dt)}
+    # ---- all cores: members are independent in every task but the shared worlds; per-member data goes with its slice
+    nproc = os.cpu_count() or 1
+    cores = max(1, min(nproc, 16, sample_pop))      # a one-GPU machine's share of the host is 16 cores
+    if name == "forage" or cores == 1:
+        out["all_cores"] = None
+        return out
+    bounds = np.linspace(0, sample_pop, cores + 1).astype(int)
+    st = opgpe.PGPEState.create(opgpe.PGPEConfig(P=c.P, pop_max=sample_pop), mu0)
+    per_member = [k for k in ("obs", "targets") if name == "cfg4" and k in task]
+    with threadpool_limits(limits=1):
+        if per_member:       # cfg4: every member has its own observations and targets; a worker gets its slice only
+            full = {k: task[k] for k in per_member}
+        _POOL_TASK = task
+        ctx = multiprocessing.get_context("fork")
+        with ctx.Pool(cores) as pool:
+            pool.map(_noop, range(cores))      # workers are up before the clock starts
+            t0 = time.perf_counter()
+            for _ in range(gens):
+                t = st.t
+                params = opgpe.ask(st, seed, sample_pop, dtype)
+                if per_member:
+                    fit = np.concatenate(pool.map(_oracle_slice_own, [(params[lo:hi], seed, t, lo, hi)
+                                                                      for lo, hi in zip(bounds[:-1], bounds[1:])]))
+                else:
+                    fit = np.concatenate(pool.map(_oracle_slice, [(params[lo:hi], seed, t)
+                                                                  for lo, hi in zip(bounds[:-1], bounds[1:])]))
+                opgpe.tell(st, fit.astype(np.float32))
+            dt_all = time.perf_counter() - t0
+    out["all_cores"] = {"value": evals * gens / dt_all, "cores": cores, "nproc": nproc,
+                        "how": "the sample's population split over %d forked worker processes, one BLAS thread each; "
+                               "ask and tell on the parent; %.1f s" % (cores, dt_all)}
+    return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq", "forage", "forage_solo"])
-    ap.add_argument("--seed", type=int, default=20220509)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--batch", type=int, default=None,
-                    help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
-    ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
-                    help="cfg5 only: 'fused' = ask fused with the sphere fitness (no population in memory), "
-                         "'stored' = tell reads the perturbations back from the stored population")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay each generation from a recorded HIP graph (generation index kept on the device); "
-                         "the per-stage times then come from an untimed pass of direct calls before the replays")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
-              % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    import torch
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.batch is not None and args.workload != "cfg4":
-        raise SystemExit("--batch applies to --workload cfg4 only")
-    if args.variant != "materialised" and args.workload != "cfg5":
-        raise SystemExit("--variant applies to --workload cfg5 only")
-    wl = _build_workload(args.workload, args.seed, args.batch)
+def _noop(_):
+    return None
+
+
+def _oracle_slice_own(job):
+    """As _oracle_slice for a task whose members have their own observations and targets."""
+    from oracle import generation as ogen
+    params, seed, t, lo, hi = job
+    task = dict(_POOL_TASK)
+    task["obs"], task["targets"] = _POOL_TASK["obs"][lo:hi], _POOL_TASK["targets"][lo:hi]
+    return ogen.evaluate(task, params, seed, t)
+
+
+def _measure_peaks(evo, torch):
+    """What this GPU delivers for the quantities the roofline peaks are quoted for: a plain 1 GiB device copy
+    and register-only loops of one instruction kind (evo_probe_rate), each timed with events, second run kept."""
+    def timed(fn):
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = fn()
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = (work, ms) if best is None or ms < best[1] else best
+        return best
+
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    work, ms = timed(lambda: (dst.copy_(src), 2.0 * src.numel() * 4)[1])
+    peaks = {"hbm_copy_1GiB_GBs": work / (ms * 1e-3) / 1e9, "hbm_published_GBs": PEAK_HBM_GBS}
+    del src, dst
+    out = torch.zeros(16, dtype=torch.float32, device="cuda:0")
+    for key, kind, iters, published in (("fma_f32_vector_TFs", 0, 100000, PEAK_ALU_F32_TF),
+                                        ("mfma_f16_16x16x32_TFs", 1, 10000, PEAK_MFMA_BF16_TF),
+                                        ("mfma_bf16_32x32x16_TFs", 2, 5000, PEAK_MFMA_BF16_TF),
+                                        ("mfma_f32_16x16x4_TFs", 3, 5000, PEAK_MFMA_F32_TF)):
+        work, ms = timed(lambda: evo.evo_probe_rate(kind, iters, out))
+        peaks[key] = work / (ms * 1e-3) / 1e12
+        peaks[key.replace("_TFs", "_published_TFs")] = published
+    return peaks
+
+
+def _run_workload(name, args, steps, warmup, torch):
+    """Time `steps` whole generations of one workload; returns the fields of its JSON line."""
+    wl = _build_workload(name, args.seed, args.batch)
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
-    steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload]
     stage_names = ("ask", "rollout", "tell")
     events = []
 
@@ -299,20 +379,14 @@ def main():
             ev[3].record()
             events.append(ev)
 
-    if args.calibrate_copy:      # a copy kernel of known size: reads 1 GiB, writes 1 GiB
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
     if args.graph:
         wl["gen_dev"] = pg.device_generation()
-    for t in range(args.warmup):
+    for t in range(warmup):
         generation(t, False)
     torch.cuda.synchronize()
     if args.graph:      # one recorded generation per distinct batch; each replay is the next generation
         for t in range(min(steps, 20)):
-            generation(args.warmup + t, True)
+            generation(warmup + t, True)
         graphs = []
         for k in range(wl.get("n_tasks", 1)):
             g = torch.cuda.CUDAGraph()
@@ -329,7 +403,7 @@ def main():
     else:
         t0 = time.perf_counter()
         for t in range(steps):
-            generation(args.warmup + t, True)
+            generation(warmup + t, True)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
 
@@ -342,20 +416,23 @@ def main():
     achieved = work / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
     out = {
         "metric": "member-evals/sec (pop x samples, or env-steps/s, or pop for the sphere) for one whole ES generation",
-        "value": value, "unit": "member-evals/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "value": value, "unit": "member-evals/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl["dtype"], "data": "synthetic",
         "config": {"workload": wl["desc"], "pop": c.pop, "P": c.P, "generation": "ask -> rollout -> tell"},
         "stage_ms": stage_ms,
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "kernel": wl["roofline_stage"], "kernel_ms": dom_ms},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                     "traffic_source": "rocprofv3 --pmc summary under profiles/ of this command (not read in this run)",
+                     "kernel": wl["roofline_stage"], "kernel_ms": dom_ms, "bound_detail": BOUND_DETAIL.get(name)},
     }
     if "launches" in wl:
         out["roofline"]["launches_per_generation"] = wl["launches"]
-    if "f16_issued_flops" in wl:      # the same contraction counted as the fp16 matrix instructions that carry it
-        out["roofline"]["mfma_f16_issued_tflops"] = wl["f16_issued_flops"] / (dom_ms * 1e-3) / 1e12
-        out["roofline"]["mfma_f16_issued_frac"] = out["roofline"]["mfma_f16_issued_tflops"] / PEAK_MFMA_BF16_TF
+    if "fp32_flops" in wl:      # the same launch priced as the fp32 work it stands for
+        tf = wl["fp32_flops"] / (dom_ms * 1e-3) / 1e12
+        out["roofline"]["priced_as"] = "fp16 matrix instructions as issued (two-term splits of fp32 operands)"
+        out["roofline"]["fp32_equivalent"] = {"achieved": tf, "peak": PEAK_MFMA_F32_TF, "unit": "TFLOP/s",
+                                              "frac": tf / PEAK_MFMA_F32_TF}
     if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
         out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
@@ -373,8 +450,72 @@ def main():
             out["roofline"] = {"bound": "alu", "achieved": normals / (dom_ms * 1e-3) / 1e9, "peak": None,
                                "unit": "Gnormal/s", "frac": None, "traffic": None, "kernel": "ask_sphere",
                                "kernel_ms": dom_ms}
+    pg.close()
+    del wl
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None,
+                    choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "seq2seq", "forage", "forage_solo"],
+                    help="one workload only; default: cfg2 as the headline plus per_config for cfg1..cfg5")
+    ap.add_argument("--seed", type=int, default=20220509)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peak probes")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
+    ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
+                    help="cfg5 only: 'fused' = ask fused with the sphere fitness (no population in memory), "
+                         "'stored' = tell reads the perturbations back from the stored population")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each generation from a recorded HIP graph (generation index kept on the device); "
+                         "the per-stage times then come from an untimed pass of direct calls before the replays")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    headline = args.workload or "cfg2"
+    all_configs = args.workload is None and args.batch is None and args.variant == "materialised" and not args.graph
+    if args.batch is not None and headline != "cfg4":
+        raise SystemExit("--batch applies to --workload cfg4 only")
+    if args.variant != "materialised" and headline != "cfg5":
+        raise SystemExit("--variant applies to --workload cfg5 only")
+    # the oracle first: its all-cores leg forks worker processes, which must happen before the GPU is initialised
+    cpu = None
     if not args.no_cpu_baseline and args.batch is None and args.variant == "materialised":
-        out["cpu_baseline"] = _cpu_baseline(args.workload, args.seed)
+        cpu = _cpu_baseline(headline, args.seed)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    import paper_2202_05008_amd as evo
+    if args.calibrate_copy:      # a copy kernel of known size: reads 1 GiB, writes 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[headline]
+    out = _run_workload(headline, args, steps, args.warmup, torch)
+    if all_configs:
+        per = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            r = out if name == headline else _run_workload(name, args, DEFAULT_STEPS[name], args.warmup, torch)
+            per[name] = {"workload": r["config"]["workload"], "ms_per_generation": r["ms_per_step"], "steps": r["steps"],
+                         "value": r["value"], "unit": r["unit"], "dtype": r["dtype"], "stage_ms": r["stage_ms"],
+                         "roofline": r["roofline"]}
+        out["per_config"] = per
+    if not args.no_peaks:
+        out["measured_peaks"] = _measure_peaks(evo, torch)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

@@ -375,6 +375,13 @@ int evo_rollout_trace(const task_desc* td, const policy_desc* pd, const void* pa
 int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                        float* logits_dev, void* stream);
 
+/* Rate probe for the benchmark's "measured next to published" peaks (no step of the path uses it): one launch
+ * that fills the GPU with waves running `iters` rounds of eight independent instructions of one kind on
+ * registers -- kind 0: fp32 vector multiply-add, 1: v_mfma_f32_16x16x32_f16, 2: v_mfma_f32_32x32x16_bf16,
+ * 3: v_mfma_f32_16x16x4_f32.  *flop_out (host) receives the floating-point operations the launch performs;
+ * the caller times it.  out_dev: one float of device memory (never written in practice). */
+int evo_probe_rate(int32_t kind, int32_t iters, double* flop_out, float* out_dev, void* stream);
+
 const char* evo_last_error(void);
 /* Library version string, e.g. "evo-gfx950 0.1". */
 const char* evo_version(void);

@@ -79,6 +79,7 @@ _SIGNATURES = {
                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "evo_seq2seq_logits": (C.c_int, [C.POINTER(task_desc), C.POINTER(policy_desc), C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_void_p]),
+    "evo_probe_rate": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.c_void_p, C.c_void_p]),
     "evo_last_error": (C.c_char_p, []),
     "evo_version": (C.c_char_p, []),
 }

@@ -266,6 +266,13 @@ def evo_rollout_trace(td, pd, params, pop, steps, trace, final=None):
                                          _ptr(final, torch.float32, allow_none=True), _stream()))
 
 
+def evo_probe_rate(kind, iters, out):
+    """Enqueue one rate probe; returns the floating-point operations it performs (the caller times it)."""
+    flop = C.c_double()
+    _check(_lib.load().evo_probe_rate(kind, iters, C.byref(flop), _ptr(out, torch.float32), _stream()))
+    return flop.value
+
+
 class PGPE:
     """Convenience owner of the device arrays behind one pgpe_state handle."""
 

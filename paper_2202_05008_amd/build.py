@@ -34,7 +34,7 @@ FLAGS = [
 # unchanged), the cart-pole roll-out 1.38 -> 1.30 ms; the LSTM kernel does not change and the ConvNet kernel has
 # no such moves, so they are left alone.
 _VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
-FILE_FLAGS = {"policy_bf16.hip": _VGPR_FORM, "task_cartpole.hip": _VGPR_FORM}
+FILE_FLAGS = {"policy_bf16.hip": _VGPR_FORM, "task_cartpole.hip": _VGPR_FORM, "probe.hip": _VGPR_FORM}
 
 
 def _compile(src):
