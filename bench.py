@@ -362,7 +362,10 @@ def _run_workload(name, args, steps, warmup, torch):
         if timed:
             ev[0].record()
         if args.variant == "fused":      # one call stands for ask + rollout: the rollout stage reads 0
-            pg.ask_sphere(args.seed, c.pop, wl["x_star"], wl["fitness"])
+            if name == "cfg4":
+                pg.ask_rollout(args.seed, c.pop, td, wl["pd"], wl["fitness"])
+            else:
+                pg.ask_sphere(args.seed, c.pop, wl["x_star"], wl["fitness"])
         else:
             pg.ask(args.seed, c.pop, wl["params"], c.dtype)
         if timed:
@@ -412,7 +415,8 @@ def _run_workload(name, args, steps, warmup, torch):
     ms_per_step = elapsed * 1e3 / steps
     value = c.evals_per_generation * steps / elapsed
     bound, work, peak, unit = wl["roofline"]
-    dom_ms = stage_ms[wl["roofline_stage"]] / wl.get("launches", 1)      # average duration of one launch
+    dom_stage = "ask" if args.variant == "fused" else wl["roofline_stage"]      # the fused call is timed as the ask stage
+    dom_ms = stage_ms[dom_stage] / wl.get("launches", 1)      # average duration of one launch
     achieved = work / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
     out = {
         "metric": "member-evals/sec (pop x samples, or env-steps/s, or pop for the sphere) for one whole ES generation",
@@ -442,14 +446,15 @@ def _run_workload(name, args, steps, warmup, torch):
         out["config"]["batch_override"] = args.batch
         out["roofline"]["traffic"] = None
     if args.variant != "materialised":
-        out["config"]["generation"] = {"fused": "ask_sphere (ask + fitness in one kernel, no population) -> tell",
+        out["config"]["generation"] = {"fused": ("ask_rollout" if name == "cfg4" else "ask_sphere") +
+                                                " (ask + fitness in one kernel, no population) -> tell",
                                        "stored": "ask -> rollout -> tell_stored"}[args.variant]
         out["roofline"]["traffic"] = None
         if args.variant == "fused":      # no population is written: the stage is bound by the noise generation
             normals = c.pop / 2 * c.P
             out["roofline"] = {"bound": "alu", "achieved": normals / (dom_ms * 1e-3) / 1e9, "peak": None,
-                               "unit": "Gnormal/s", "frac": None, "traffic": None, "kernel": "ask_sphere",
-                               "kernel_ms": dom_ms}
+                               "unit": "Gnormal/s", "frac": None, "traffic": None,
+                               "kernel": "ask_rollout" if name == "cfg4" else "ask_sphere", "kernel_ms": dom_ms}
     pg.close()
     del wl
     torch.cuda.empty_cache()
@@ -470,8 +475,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None,
                     help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
     ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
-                    help="cfg5 only: 'fused' = ask fused with the sphere fitness (no population in memory), "
-                         "'stored' = tell reads the perturbations back from the stored population")
+                    help="cfg5: 'fused' = ask fused with the sphere fitness (no population in memory), 'stored' = tell "
+                         "reads the perturbations back from the stored population; cfg4: 'fused' = ask fused into the forward")
     ap.add_argument("--graph", action="store_true",
                     help="replay each generation from a recorded HIP graph (generation index kept on the device); "
                          "the per-stage times then come from an untimed pass of direct calls before the replays")
@@ -486,8 +491,8 @@ def main():
     all_configs = args.workload is None and args.batch is None and args.variant == "materialised" and not args.graph
     if args.batch is not None and headline != "cfg4":
         raise SystemExit("--batch applies to --workload cfg4 only")
-    if args.variant != "materialised" and headline != "cfg5":
-        raise SystemExit("--variant applies to --workload cfg5 only")
+    if args.variant != "materialised" and not (headline == "cfg5" or (headline == "cfg4" and args.variant == "fused")):
+        raise SystemExit("--variant applies to --workload cfg5 (fused, stored) and cfg4 (fused) only")
     # the oracle first: its all-cores leg forks worker processes, which must happen before the GPU is initialised
     cpu = None
     if not args.no_cpu_baseline and args.batch is None and args.variant == "materialised":

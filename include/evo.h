@@ -306,6 +306,16 @@ size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32
 int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
             float* fitness_dev, void* stream);
 
+/* ask fused into the evaluation (Section 4's ask feeding Section 2's global policy without the population ever
+ * being stored): fitness_dev[m] = what rollout(td, pd, ...) gives on the bfloat16 population that
+ * pgpe_ask(st, seed, pop, ..., EVO_BF16) would write -- bit for bit -- for the EVO_TASK_REGRESS task of the bfloat16
+ * MLP 64-256-256-16 with at most 64 observations per member.  One workgroup evaluates the two members of an
+ * antithetic pair together from one draw of their noise; mu and sigma are read instead of 2 P bytes per member.
+ * Records the pending ask like pgpe_ask; tell regenerates the noise as usual.
+ * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED (any other task / policy: use pgpe_ask + rollout), EVO_ERR_HIP. */
+int pgpe_ask_rollout(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc* td, const policy_desc* pd,
+                     float* fitness_dev, void* stream);
+
 /* rollout for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): the same evaluation, by the same kernels, as rollout, but the
  * workspace is a fixed array inside the library's device image (EVO_STATIC_SCRATCH_BYTES per GPU, held until
@@ -370,6 +380,11 @@ int evo_rollout_details(const task_desc* td, const policy_desc* pd, const void* 
  * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED, EVO_ERR_HIP. */
 int evo_rollout_trace(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                       int32_t steps, float* trace_dev, float* final_dev, void* stream);
+
+/* The policy outputs behind pgpe_ask_rollout: out_dev[pop][B][A] as pop_forward gives on the population that
+ * pgpe_ask would write for (seed, current generation).  Leaves the state untouched (no pending ask). */
+int evo_ask_forward(pgpe_state* st, uint64_t seed, int32_t pop, const policy_desc* pd, const float* obs_dev,
+                    int64_t obs_member_stride, float* out_dev, int32_t B, void* stream);
 
 /* Logits of an EVO_TASK_SEQ2SEQ task: logits_dev[pop][B][seq_out][n_out] (fp32). */
 int evo_seq2seq_logits(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,

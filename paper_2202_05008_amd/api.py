@@ -175,6 +175,15 @@ def pgpe_ask_sphere(h, seed, pop, x_star, fitness, work):
                                        _ptr(work), _stream()))
 
 
+def pgpe_ask_rollout(h, seed, pop, td, pd, fitness):
+    _check(_lib.load().pgpe_ask_rollout(h, seed, pop, C.byref(td), C.byref(pd), _ptr(fitness, torch.float32), _stream()))
+
+
+def evo_ask_forward(h, seed, pop, pd, obs, obs_member_stride, out, B):
+    _check(_lib.load().evo_ask_forward(h, seed, pop, C.byref(pd), _ptr(obs, torch.float32), obs_member_stride,
+                                       _ptr(out, torch.float32), B, _stream()))
+
+
 def pgpe_tell_stored(h, fitness, params):
     _check(_lib.load().pgpe_tell_stored(h, _ptr(fitness, torch.float32), _ptr(params, torch.float32), _stream()))
 
@@ -302,6 +311,9 @@ class PGPE:
             self._sphere_work = torch.empty(pgpe_ask_sphere_workspace_bytes(self.cfg), dtype=torch.uint8,
                                             device=self.mu.device)
         pgpe_ask_sphere(self.handle, seed, pop, x_star, fitness, self._sphere_work)
+
+    def ask_rollout(self, seed, pop, td, pd, fitness):
+        pgpe_ask_rollout(self.handle, seed, pop, td, pd, fitness)
 
     def tell_stored(self, fitness, params):
         pgpe_tell_stored(self.handle, fitness, params)

@@ -31,6 +31,25 @@ int mlp_bf16_supported(const MlpShape& sh, int B);
 int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs, int64_t obs_stride, int pop, int B,
                     float* out, int loss, const void* target, float* fitness, hipStream_t s);
 
+// ask fused into the bf16 forward: members 2k, 2k+1 of pair k are drawn from (mu, sigma, seed, generation) inside the
+// kernel and evaluated together; the population is never written.  Same outputs as launch_mlp_bf16 on what ask stores.
+int mlp_bf16_pair_supported(const MlpShape& sh, int B);
+int launch_mlp_bf16_pair(const MlpShape& sh, const float* mu, const float* sigma, uint64_t seed, uint32_t gen,
+                         const uint32_t* gen_dev, const float* obs, int64_t obs_stride, int pop, int B, float* out,
+                         int loss, const void* target, float* fitness, hipStream_t s);
+
+// What the fused calls need of a PGPE state (defined beside the state, in pgpe.hip).
+struct PgpeView {
+  const float* mu;
+  const float* sigma;
+  int P;
+  uint32_t t;
+  const uint32_t* gen_dev;  // the device copy of t, or null
+};
+int pgpe_view(const pgpe_state* st, PgpeView* out);
+int pgpe_check_ask(const pgpe_state* st, int32_t pop, const char* who);
+void pgpe_note_ask(pgpe_state* st, uint64_t seed, int32_t pop);
+
 // fp32 ConvNet; images shared by all members.  Partials per (member, chunk).
 int convnet_supported(const ConvShape& sh);
 int convnet_chunks(const ConvShape& sh, int pop, int B);

@@ -7,7 +7,7 @@
 // population; tell regenerates every normal from the counter-based generator, reduces the
 // rank-weighted sums in registers / LDS in a fixed order and applies the optimizer in the
 // same kernel, so mu, sigma and the moments are read and written exactly once.
-#include "common.h"
+#include "kernels.h"
 #include "philox.h"
 #include "bf16.h"
 
@@ -624,6 +624,20 @@ static int check_ask_pop(const pgpe_state* st, int32_t pop, const char* who) {
 // The device copy of t, or null while the state keeps t on the host only.
 static const uint32_t* device_generation(const pgpe_state* st) {
   return st->device_t ? ws_carve(st->work, st->cfg.pop_max).gen : nullptr;
+}
+
+// What the calls that fuse ask into an evaluation (other source files) need of a state.
+int pgpe_view(const pgpe_state* st, PgpeView* out) {
+  EVO_REQUIRE(st != nullptr && out != nullptr, EVO_ERR_ARG, "pgpe state is null");
+  out->mu = st->mu, out->sigma = st->sigma, out->P = st->cfg.P, out->t = st->t;
+  out->gen_dev = device_generation(st);
+  return EVO_OK;
+}
+int pgpe_check_ask(const pgpe_state* st, int32_t pop, const char* who) { return check_ask_pop(st, pop, who); }
+void pgpe_note_ask(pgpe_state* st, uint64_t seed, int32_t pop) {
+  st->pending = true;
+  st->seed = seed;
+  st->pop = pop;
 }
 
 // Host t -> device copy, in stream order.

@@ -16,6 +16,7 @@
 
 #include "bf16.h"
 #include "kernels.h"
+#include "philox.h"
 
 namespace evo {
 
@@ -382,6 +383,279 @@ __global__ __launch_bounds__(512, 4) void mlp_bf16_stream_kernel(Bf16Args a) {
   if (tid == 0) a.fitness[member] = -(red[0] + red[1] + red[2] + red[3]) / (static_cast<float>(B) * A);
 }
 
+// ---- ask fused into the forward: one workgroup per antithetic pair, the population never written -------
+// The streaming kernel above is bound by the weight stream that ask wrote a moment earlier (cfg4: 709 MB
+// written and read straight back).  Here the two members of a pair are evaluated together and their weights
+// are never in memory: where the streaming kernel loads the 16 bytes of unit u that belong to a lane (eight
+// consecutive parameters), this kernel draws them -- mu and sigma of those eight parameters (fp32, shared by
+// every pair, so they come from the L2), the two Philox blocks of the pair's noise, theta+ and theta- formed
+// and rounded exactly as pgpe_ask stores them -- and hands each member's 16 bytes to the same staging tile and
+// transposed read.  One draw serves both members; the matrix products, epilogues and the loss follow the
+// streaming kernel instruction for instruction, so the fitness is bit for bit that of ask followed by rollout.
+// The kernel is bound by the noise generation (the cost of ask alone); the forward rides along.
+// The small output layer's operands are drawn once per workgroup (wave w draws rows 32 w .. 32 w + 31) and left
+// in LDS in operand form for the four waves that run layer 3.
+struct PairArgs {
+  MlpShape sh;
+  const float* mu;
+  const float* sigma;
+  uint32_t key0, key1, gen;
+  const uint32_t* gen_dev;
+  const float* obs;
+  int64_t obs_stride;
+  int B;
+  float* out;
+  const float* target;
+  float* fitness;
+  int loss;
+};
+
+// theta+ and theta- of parameter i as pgpe_ask stores them in bfloat16, widened again.
+__device__ __forceinline__ void theta_pair_at(const PairArgs& a, uint32_t pair, uint32_t gen, int i, float& plus,
+                                              float& minus) {
+  float z[4];
+  philox_normal4(static_cast<uint32_t>(i >> 2), pair, gen, EVO_TAG_NOISE, a.key0, a.key1, z);
+  const int e = i & 3;
+  const float zz = e == 0 ? z[0] : (e == 1 ? z[1] : (e == 2 ? z[2] : z[3]));
+  const float m = a.mu[i], sg = a.sigma[i];
+  plus = from_bf16(to_bf16(fmaf(sg, zz, m)));
+  minus = from_bf16(to_bf16(fmaf(-sg, zz, m)));
+}
+
+template <int D0, int H, int A>
+constexpr size_t pair_lds_bytes() {
+  return (2 * 64 * (D0 + kRowPad) + 2 * 64 * (H + kRowPad) + 8 * kStageElems) * sizeof(uint16_t) +
+         2 * (H / 32) * 64 * 16;
+}
+
+template <int D0, int H, int A, bool RELU>
+__global__ __launch_bounds__(512) void mlp_bf16_pair_kernel(PairArgs a) {
+  static_assert(H == 256 && D0 % 32 == 0 && A == 16, "shape of the pair kernel");
+  constexpr int LD0 = D0 + kRowPad, LDH = H + kRowPad;
+  constexpr int U1 = D0 / 16, U2 = H / 16, U3 = H / 32;
+  constexpr int oB1 = D0 * H, oW2 = oB1 + H, oB2 = oW2 + H * H, oW3 = oB2 + H, oB3 = oW3 + H * A;
+  static_assert(U3 == 8, "one output-layer unit per wave");
+  extern __shared__ __attribute__((aligned(16))) uint16_t pair_lds[];
+  uint16_t* x_s = pair_lds;                         // [2][64][LD0]
+  uint16_t* h_s = x_s + 2 * 64 * LD0;               // [2][64][LDH]
+  uint16_t* stage_s = h_s + 2 * 64 * LDH;           // [8][kStageElems]
+  u32x4v* w3_s = reinterpret_cast<u32x4v*>(stage_s + 8 * kStageElems);  // [2][U3][64] output-layer operands
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 31, g = lane >> 5;
+  const int c16 = lane & 15, g4 = lane >> 4;
+  uint16_t* stage = stage_s + wave * kStageElems;
+  const uint32_t pair = blockIdx.x;
+  const uint32_t gen = a.gen_dev ? *a.gen_dev : a.gen;
+  const int B = a.B;
+  const bool tail = wave < 4;  // waves that also run layer 3
+
+  // ---- the draw of unit u: mu and sigma of the lane's eight parameters, fetched kAhead units early ------
+  constexpr int kAhead = 2;
+  float4 ms[kAhead][4];
+  const int lane12 = (lane >> 2) * H + 32 * wave + 8 * (lane & 3);  // this lane's eight parameters inside a unit
+  auto unit_index = [&](int u) -> int {
+    if (u < U1) return 16 * u * H + lane12;
+    return oW2 + 16 * (u - U1) * H + lane12;
+  };
+  auto fetch = [&](int u) {
+    if (u >= U1 + U2) return;
+    const int i = unit_index(u);
+    float4* r = ms[u % kAhead];
+    r[0] = *reinterpret_cast<const float4*>(a.mu + i);
+    r[1] = *reinterpret_cast<const float4*>(a.mu + i + 4);
+    r[2] = *reinterpret_cast<const float4*>(a.sigma + i);
+    r[3] = *reinterpret_cast<const float4*>(a.sigma + i + 4);
+  };
+  // eight parameters from index i (a multiple of 8): both members' 16 bytes, as pgpe_ask stores them
+  auto draw8 = [&](int i, const float4 (&r)[4], u32x4v& plus, u32x4v& minus) {
+    const float mu8[8] = {r[0].x, r[0].y, r[0].z, r[0].w, r[1].x, r[1].y, r[1].z, r[1].w};
+    const float sg8[8] = {r[2].x, r[2].y, r[2].z, r[2].w, r[3].x, r[3].y, r[3].z, r[3].w};
+    float z[8];
+    philox_normal4(static_cast<uint32_t>(i >> 2), pair, gen, EVO_TAG_NOISE, a.key0, a.key1, z);
+    philox_normal4(static_cast<uint32_t>(i >> 2) + 1u, pair, gen, EVO_TAG_NOISE, a.key0, a.key1, z + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      plus[e] = pack_bf16x2(fmaf(sg8[2 * e], z[2 * e], mu8[2 * e]), fmaf(sg8[2 * e + 1], z[2 * e + 1], mu8[2 * e + 1]));
+      minus[e] = pack_bf16x2(fmaf(-sg8[2 * e], z[2 * e], mu8[2 * e]), fmaf(-sg8[2 * e + 1], z[2 * e + 1], mu8[2 * e + 1]));
+    }
+  };
+  // 16 bytes of a lane -> staging tile -> transposed B operand of this lane (layers 1, 2: 16 rows x 32 columns)
+  auto operand12 = [&](const u32x4v& v) -> bf16x8 {
+    *reinterpret_cast<u32x4v*>(stage + (lane >> 2) * kStageLd + 8 * (lane & 3)) = v;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t* q = stage + (8 * g + (c16 >> 2)) * kStageLd + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return join_bf16(lo, hi);
+  };
+  // layer 3: 32 rows x 16 columns
+  auto operand3 = [&](const u32x4v& v) -> bf16x8 {
+    *reinterpret_cast<u32x4v*>(stage + (lane >> 1) * kStageLd3 + 8 * (lane & 1)) = v;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t* q = stage + (8 * g4 + (c16 >> 2)) * kStageLd3 + 4 * (lane & 3);
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(q + 4 * kStageLd3));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return join_bf16(lo, hi);
+  };
+
+  // ---- observations and targets of both members (requested first: they come from HBM) --------------------
+  constexpr int kObsPieces = 64 * D0 / 4 / 512;
+  float4 ov[2][kObsPieces];
+#pragma unroll
+  for (int mem = 0; mem < 2; ++mem) {
+    const float* obs = a.obs + static_cast<size_t>(2 * pair + mem) * a.obs_stride;
+#pragma unroll
+    for (int j = 0; j < kObsPieces; ++j) {
+      const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      ov[mem][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < B) ov[mem][j] = reinterpret_cast<const float4*>(obs + static_cast<size_t>(r) * D0)[d4];
+    }
+  }
+  fetch(0);
+  fetch(1);
+  float tgt[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  if (tail && a.loss != LOSS_NONE) {
+#pragma unroll
+    for (int mem = 0; mem < 2; ++mem)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * wave + 4 * g4 + i;
+        if (row < B) tgt[mem][i] = a.target[(static_cast<size_t>(2 * pair + mem) * B + row) * A + c16];
+      }
+  }
+  // ---- output layer: wave w draws rows 32 w .. 32 w + 31 of W3 and leaves both members' operands in LDS ----
+  {
+    const int i = oW3 + (32 * wave + (lane >> 1)) * A + 8 * (lane & 1);
+    float4 r[4];
+    r[0] = *reinterpret_cast<const float4*>(a.mu + i);
+    r[1] = *reinterpret_cast<const float4*>(a.mu + i + 4);
+    r[2] = *reinterpret_cast<const float4*>(a.sigma + i);
+    r[3] = *reinterpret_cast<const float4*>(a.sigma + i + 4);
+    u32x4v plus, minus;
+    draw8(i, r, plus, minus);
+    w3_s[(0 * U3 + wave) * 64 + lane] = __builtin_bit_cast(u32x4v, operand3(plus));
+    w3_s[(1 * U3 + wave) * 64 + lane] = __builtin_bit_cast(u32x4v, operand3(minus));
+  }
+  // biases of this lane's columns (layers 1, 2) and output (layer 3), both members
+  float bias_col[2][2], bias3[2];
+  theta_pair_at(a, pair, gen, oB1 + 32 * wave + c, bias_col[0][0], bias_col[1][0]);
+  theta_pair_at(a, pair, gen, oB2 + 32 * wave + c, bias_col[0][1], bias_col[1][1]);
+  theta_pair_at(a, pair, gen, oB3 + c16, bias3[0], bias3[1]);
+
+  // ---- observations -> bf16 rows (rows beyond B are zero) ---------------------------------------
+#pragma unroll
+  for (int mem = 0; mem < 2; ++mem)
+#pragma unroll
+    for (int j = 0; j < kObsPieces; ++j) {
+      const int i = tid + 512 * j, r = i / (D0 / 4), d4 = i - r * (D0 / 4);
+      uint2 pk;
+      pk.x = pack_bf16x2(ov[mem][j].x, ov[mem][j].y);
+      pk.y = pack_bf16x2(ov[mem][j].z, ov[mem][j].w);
+      *reinterpret_cast<uint2*>(x_s + mem * 64 * LD0 + r * LD0 + 4 * d4) = pk;
+    }
+  __syncthreads();
+
+  floatx16 acc[2][2];  // [member][row tile]
+  auto bias_rows = [&](int layer) {
+#pragma unroll
+    for (int mem = 0; mem < 2; ++mem)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mem][mt][r] = bias_col[mem][layer];
+  };
+  auto store_rows = [&](int act) {
+#pragma unroll
+    for (int mem = 0; mem < 2; ++mem)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          h_s[mem * 64 * LDH + row * LDH + 32 * wave + c] = to_bf16(act_f(acc[mem][mt][r], act));
+        }
+  };
+  // one unit of layer 1 or 2: draw, then both members' products
+  auto unit = [&](int u, const uint16_t* in, int ld, int k0) {
+    u32x4v pm[2];
+    draw8(unit_index(u), ms[u % kAhead], pm[0], pm[1]);
+    fetch(u + kAhead);
+#pragma unroll
+    for (int mem = 0; mem < 2; ++mem) {
+      const bf16x8 bv = operand12(pm[mem]);
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const uint4 av = *reinterpret_cast<const uint4*>(in + mem * 64 * ld + (mt * 32 + c) * ld + k0 + 8 * g);
+        acc[mem][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), bv, acc[mem][mt], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- layer 1 ----------------------------------------------------------------------------------
+  bias_rows(0);
+#pragma unroll
+  for (int u = 0; u < U1; ++u) unit(u, x_s, LD0, 16 * u);
+  store_rows(RELU ? EVO_ACT_RELU : a.sh.act[0]);
+  __syncthreads();
+
+  // ---- layer 2 ----------------------------------------------------------------------------------
+  bias_rows(1);
+#pragma unroll
+  for (int u = U1; u < U1 + U2; ++u) unit(u, h_s, LDH, 16 * (u - U1));
+  __syncthreads();  // every wave has read h1: the buffer can take h2
+  store_rows(RELU ? EVO_ACT_RELU : a.sh.act[1]);
+  __syncthreads();
+
+  // ---- layer 3: four waves, one 16-row tile each per member ------------------------------------------
+  float loss_acc[2] = {0.f, 0.f};
+  if (tail) {
+#pragma unroll
+    for (int mem = 0; mem < 2; ++mem) {
+      floatx4v o = {bias3[mem], bias3[mem], bias3[mem], bias3[mem]};
+#pragma unroll
+      for (int u = 0; u < U3; ++u) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, w3_s[(mem * U3 + u) * 64 + lane]);
+        const uint4 av = *reinterpret_cast<const uint4*>(h_s + mem * 64 * LDH + (16 * wave + c16) * LDH + 32 * u + 8 * g4);
+        o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), bv, o, 0, 0, 0);
+      }
+      const int act = RELU ? EVO_ACT_NONE : a.sh.act[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * wave + 4 * g4 + i;
+        const float v = act_f(o[i], act);
+        if (row < B) {
+          if (a.loss == LOSS_NONE) {
+            a.out[(static_cast<size_t>(2 * pair + mem) * B + row) * A + c16] = v;
+          } else {
+            const float d = v - tgt[mem][i];
+            loss_acc[mem] = fmaf(d, d, loss_acc[mem]);
+          }
+        }
+      }
+    }
+  }
+  if (a.loss == LOSS_NONE) return;
+#pragma unroll
+  for (int mem = 0; mem < 2; ++mem) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) loss_acc[mem] += __shfl_xor(loss_acc[mem], o, 64);
+    if (lane == 0 && tail) red[mem][wave] = loss_acc[mem];
+  }
+  __syncthreads();
+  if (tid < 2)
+    a.fitness[2 * pair + tid] = -(red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3]) / (static_cast<float>(B) * A);
+}
+
 // Two floats rounded to bf16 (one conversion instruction) and max(x, 0) taken on both halves at once.
 typedef short short2v __attribute__((ext_vector_type(2)));
 typedef float float2v __attribute__((ext_vector_type(2)));
@@ -710,6 +984,37 @@ int launch_mlp_bf16(const MlpShape& sh, const uint16_t* params, const float* obs
   }
   hipLaunchKernelGGL(mlp_bf16_kernel, dim3(pop), dim3(kBf16Threads), shmem, s, a);
   return check_launch("mlp_bf16_kernel");
+}
+
+int mlp_bf16_pair_supported(const MlpShape& sh, int B) {
+  EVO_REQUIRE(stream_shape(sh, B) && B <= 64, EVO_ERR_UNSUPPORTED,
+              "ask fused with the forward: the policy must be the bfloat16 MLP 64-256-256-16 with at most 64 "
+              "observations per member");
+  return EVO_OK;
+}
+
+int launch_mlp_bf16_pair(const MlpShape& sh, const float* mu, const float* sigma, uint64_t seed, uint32_t gen,
+                         const uint32_t* gen_dev, const float* obs, int64_t obs_stride, int pop, int B, float* out,
+                         int loss, const void* target, float* fitness, hipStream_t s) {
+  EVO_REQUIRE(loss != LOSS_CE, EVO_ERR_UNSUPPORTED, "bf16 MLP: the classification loss is not implemented");
+  PairArgs a;
+  a.sh = sh, a.mu = mu, a.sigma = sigma;
+  a.key0 = static_cast<uint32_t>(seed), a.key1 = static_cast<uint32_t>(seed >> 32), a.gen = gen, a.gen_dev = gen_dev;
+  a.obs = obs, a.obs_stride = obs_stride, a.B = B;
+  a.out = out, a.target = static_cast<const float*>(target), a.fitness = fitness, a.loss = loss;
+  const bool relu = sh.act[0] == EVO_ACT_RELU && sh.act[1] == EVO_ACT_RELU && sh.act[2] == EVO_ACT_NONE;
+  constexpr size_t lds = pair_lds_bytes<64, 256, 16>();
+  static_assert(lds + 64 <= 160 * 1024, "LDS budget of a CU");
+  const void* fn = relu ? reinterpret_cast<const void*>(&mlp_bf16_pair_kernel<64, 256, 16, true>)
+                        : reinterpret_cast<const void*>(&mlp_bf16_pair_kernel<64, 256, 16, false>);
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+  if (e != hipSuccess) (void)hipGetLastError();
+  EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+  if (relu)
+    hipLaunchKernelGGL((mlp_bf16_pair_kernel<64, 256, 16, true>), dim3(pop / 2), dim3(512), lds, s, a);
+  else
+    hipLaunchKernelGGL((mlp_bf16_pair_kernel<64, 256, 16, false>), dim3(pop / 2), dim3(512), lds, s, a);
+  return check_launch("mlp_bf16_pair_kernel");
 }
 
 }  // namespace evo

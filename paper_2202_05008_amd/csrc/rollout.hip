@@ -300,6 +300,57 @@ extern "C" int rollout(const task_desc* td, const policy_desc* pd, const void* p
   return rollout_impl(td, pd, params_dev, pop, steps, fitness_dev, nullptr, nullptr, nullptr, stream);
 }
 
+// ---- ask fused into the evaluation: the population is never written ---------------------------------------
+static int ask_forward_impl(pgpe_state* st, uint64_t seed, int32_t pop, const policy_desc* pd, const float* obs_dev,
+                            int64_t obs_member_stride, int32_t B, float* out_dev, int loss, const void* target_dev,
+                            float* fitness_dev, const char* who, void* stream) {
+  PgpeView v;
+  int rc = pgpe_view(st, &v);
+  if (rc) return rc;
+  rc = pgpe_check_ask(st, pop, who);
+  if (rc) return rc;
+  rc = check_policy(pd);
+  if (rc) return rc;
+  EVO_REQUIRE(pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_BF16, EVO_ERR_UNSUPPORTED,
+              "%s: needs a bfloat16 MLP policy", who);
+  MlpShape sh;
+  rc = mlp_shape(pd, &sh);
+  if (rc) return rc;
+  EVO_REQUIRE(sh.P == v.P, EVO_ERR_ARG, "%s: the policy has %d parameters, the PGPE state %d", who, sh.P, v.P);
+  EVO_REQUIRE(B >= 1 && obs_dev != nullptr && aligned16(obs_dev), EVO_ERR_ARG,
+              "%s: needs B >= 1 and 16-byte aligned observations", who);
+  EVO_REQUIRE(obs_member_stride == 0 || obs_member_stride == static_cast<int64_t>(B) * sh.dims[0], EVO_ERR_ARG,
+              "%s: obs_member_stride must be 0 or B*D", who);
+  rc = mlp_bf16_pair_supported(sh, B);
+  if (rc) return rc;
+  return launch_mlp_bf16_pair(sh, v.mu, v.sigma, seed, v.t, v.gen_dev, obs_dev, obs_member_stride, pop, B, out_dev, loss,
+                              target_dev, fitness_dev, as_stream(stream));
+}
+
+extern "C" int pgpe_ask_rollout(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc* td, const policy_desc* pd,
+                                float* fitness_dev, void* stream) {
+  EVO_REQUIRE(st != nullptr && fitness_dev != nullptr, EVO_ERR_ARG, "pgpe_ask_rollout: null argument");
+  int rc = check_task(td);
+  if (rc) return rc;
+  EVO_REQUIRE(td->kind == EVO_TASK_REGRESS, EVO_ERR_UNSUPPORTED,
+              "pgpe_ask_rollout: only the regression task of a bfloat16 MLP is fused (the sphere: pgpe_ask_sphere)");
+  EVO_REQUIRE(td->target_dev != nullptr && aligned16(td->target_dev), EVO_ERR_ARG,
+              "pgpe_ask_rollout: needs 16-byte aligned targets");
+  rc = ask_forward_impl(st, seed, pop, pd, td->obs_dev, td->obs_member_stride, td->B, nullptr, LOSS_MSE, td->target_dev,
+                        fitness_dev, "pgpe_ask_rollout", stream);
+  if (rc) return rc;
+  pgpe_note_ask(st, seed, pop);
+  return EVO_OK;
+}
+
+extern "C" int evo_ask_forward(pgpe_state* st, uint64_t seed, int32_t pop, const policy_desc* pd, const float* obs_dev,
+                               int64_t obs_member_stride, float* out_dev, int32_t B, void* stream) {
+  EVO_REQUIRE(st != nullptr && out_dev != nullptr && aligned16(out_dev), EVO_ERR_ARG,
+              "evo_ask_forward: needs a state and a 16-byte aligned output");
+  return ask_forward_impl(st, seed, pop, pd, obs_dev, obs_member_stride, B, out_dev, LOSS_NONE, nullptr, nullptr,
+                          "evo_ask_forward", stream);
+}
+
 // ---- rollout for callers that cannot allocate: the workspace lives in the library's image ----------
 // `scratch` is a host-side stand-in for the device array, not an address: kernels are given the address
 // that hipGetSymbolAddress returns for the device that is current, looked up once per device.
