@@ -7,7 +7,14 @@
 // Mapping: workgroup = (member, tile of 64 samples).  Lane = sample, so an activation
 // h[k][sample] is one conflict-free LDS read; the four waves take different groups of four
 // output neurons, whose weights W[k][o..o+3] are contiguous and wave-uniform (scalar loads).
+//
+// Two kernels.  Networks whose layers are all narrow (every fan-in below 64: cfg1's 16-32-4) stay on the
+// vector ALU (mlp_f32_kernel: they are bound by launch latency).  Any other network of widths up to 256 runs
+// its layers as contractions on the matrix cores (mlp_f32_mfma_kernel): fp32 operands as two-term scaled fp16
+// splits (split16.h), three v_mfma_f32_16x16x32_f16 per product, fp32 accumulation, results within a few
+// 1e-7 of fp32 arithmetic.
 #include "kernels.h"
+#include "split16.h"
 
 namespace evo {
 
@@ -127,6 +134,239 @@ __global__ __launch_bounds__(256) void mlp_f32_kernel(MlpArgs a) {
   if (s == 0) a.partial[static_cast<size_t>(member) * a.tiles + blockIdx.x] = loss;
 }
 
+// ---- the matrix-core form ------------------------------------------------------------------------------
+// Workgroup = (member, tile of 64 samples), eight waves (two per SIMD).  A layer is computed
+// transposed: rows of a 16 x 16 tile are neurons (A operand: the member's weights W[k][neuron], read from
+// memory as they are needed and split once per neuron tile), columns are samples (B operand: the layer's input,
+// kept in LDS as two fp16 terms [term][sample][k], one 16-byte read per term and 32 k).  A lane then ends up
+// with four consecutive neurons of one sample: bias, activation, and one 8-byte LDS store per term hand them
+// to the next layer.  Wave w takes neuron tiles w, w + 8, ...; its outputs wait in registers until every wave
+// has finished reading the layer's input, which they then overwrite.
+// Scales (powers of two, so that every finite fp32 value fits fp16's range): the weights of a neuron tile from
+// their largest magnitude; the activations of a SAMPLE from the largest magnitude among that sample's outputs
+// of the layer (in-lane maxima, two lane exchanges, one LDS word per wave and sample).  The factor of a
+// pre-activation, 1 / (sample scale x tile scale), rides in the multiply-add that adds the bias.
+typedef float floatx4m __attribute__((ext_vector_type(4)));
+constexpr int kMfmaMaxWidth = 256;             // fan-in and fan-out of a layer
+constexpr int kMfmaKSteps = kMfmaMaxWidth / 32;
+constexpr int kMfmaWaves = 8;
+constexpr int kMfmaSlots = kMfmaMaxWidth / 16 / kMfmaWaves;  // neuron tiles per wave
+
+template <int LOSS>
+__global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  constexpr int TB = kMlpTile;
+  static_assert(TB == 64, "four column tiles of 16 samples");
+  const int kRowB = (a.ldw + 8) * 2;       // bytes of one sample's row of one term (a.ldw: widest padded fan-in)
+  const int kTermB = TB * kRowB;
+  unsigned char* at = lds_raw;                                    // [2][64][ldw + 8] fp16
+  float* smax = reinterpret_cast<float*>(lds_raw + 2 * kTermB);   // [8][64] per wave: largest |output| of a sample
+  float* us_s = smax + kMfmaWaves * TB;                                    // [64] 1 / scale of the staged observations
+  float* fin = reinterpret_cast<float*>(lds_raw);                 // [A][64] network output (after the last layer)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 15, q = lane >> 4;
+  const int member = blockIdx.y, b0 = blockIdx.x * TB;
+  const float* theta = a.params + static_cast<size_t>(member) * a.sh.P;
+  const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
+
+  // ---- observations -> two fp16 terms per value, scaled per sample (eight threads per sample) --------------
+  {
+    const int D = a.sh.dims[0], KP = (D + 31) & ~31;
+    const int smp = tid >> 3, part = tid & 7;
+    const bool live = b0 + smp < a.B;
+    const float* row = obs + static_cast<size_t>(b0 + smp) * D;
+    float m = 0.f;
+    for (int d = part; d < D; d += 8) m = fmaxf(m, live ? fabsf(row[d]) : 0.f);
+    m = fmaxf(m, __shfl_xor(m, 1, 64));
+    m = fmaxf(m, __shfl_xor(m, 2, 64));
+    m = fmaxf(m, __shfl_xor(m, 4, 64));
+    const float sc = split_pow2_scale(m);
+    for (int d = 2 * part; d < KP; d += 16) {
+      const float x0 = (live && d < D) ? sc * row[d] : 0.f, x1 = (live && d + 1 < D) ? sc * row[d + 1] : 0.f;
+      uint32_t lead, resid;
+      split2_pair(x0, x1, lead, resid);
+      *reinterpret_cast<uint32_t*>(at + smp * kRowB + d * 2) = lead;
+      *reinterpret_cast<uint32_t*>(at + kTermB + smp * kRowB + d * 2) = resid;
+    }
+    if (part == 0) us_s[smp] = pow2_reciprocal(sc);
+  }
+  __syncthreads();
+  float u_s[4];  // 1 / scale of the stored input of sample 16 ct + j
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) u_s[ct] = us_s[16 * ct + j];
+
+  int off = 0;
+  const int n_layers = a.sh.n_layers;
+  for (int l = 0; l < n_layers; ++l) {
+    const int K = a.sh.dims[l], N = a.sh.dims[l + 1], act = a.sh.act[l];
+    const bool last = l == n_layers - 1;
+    const int KS = (K + 31) >> 5;
+    // neuron tiles to produce: enough to fill the next layer's fan-in up to a multiple of 32 (zeros beyond N)
+    const int NT = last ? (N + 15) >> 4 : ((N + 31) & ~31) >> 4;
+    const float* W = theta + off;
+    const float* bias = W + K * N;
+    float held[kMfmaSlots][4][4];  // [slot][sample tile][neuron 4 q + i]: this wave's outputs of the layer
+    float m_s[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int slot = 0; slot < kMfmaSlots; ++slot) {
+      const int nt = wave + kMfmaWaves * slot;
+      if (nt >= NT) continue;
+      // ---- this tile's weights as A operands: A[row j][k = 32 s + 8 q + e] = W[k][16 nt + j] ----
+      const int neuron = 16 * nt + j;
+      const bool ok = neuron < N;
+      // two passes over the tile's weights (the second one hits the cache): their largest magnitude sets the
+      // scale, then they are split; keeping them in registers in between costs 64 registers too many
+      const float* wcol = W + neuron;
+      float w_max = 0.f;
+#pragma unroll
+      for (int st = 0; st < kMfmaKSteps; ++st) {
+        if (st < KS) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int k = 32 * st + 8 * q + e;
+            w_max = fmaxf(w_max, (ok && k < K) ? fabsf(wcol[static_cast<size_t>(k) * N]) : 0.f);
+          }
+        }
+      }
+      const float s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
+      const float u_w = pow2_reciprocal(s_w);
+      f16x8 wa[2][kMfmaKSteps];
+#pragma unroll
+      for (int st = 0; st < kMfmaKSteps; ++st) {
+        if (st < KS) {
+          float raw[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int k = 32 * st + 8 * q + e;
+            raw[e] = (ok && k < K) ? s_w * wcol[static_cast<size_t>(k) * N] : 0.f;
+          }
+          split2_x8(raw, wa[0][st], wa[1][st]);
+        }
+      }
+      float bias4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bias4[i] = 16 * nt + 4 * q + i < N ? bias[16 * nt + 4 * q + i] : 0.f;
+      // ---- four sample tiles ----
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        floatx4m acc = {0.f, 0.f, 0.f, 0.f}, low = {0.f, 0.f, 0.f, 0.f};
+        const unsigned char* src = at + (16 * ct + j) * kRowB + 16 * q;
+#pragma unroll
+        for (int st = 0; st < kMfmaKSteps; ++st) {
+          if (st < KS) {
+            const f16x8 x0 = *reinterpret_cast<const f16x8*>(src + 64 * st);
+            const f16x8 x1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * st);
+            low = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[0][st], x1, low, 0, 0, 0);
+            low = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[1][st], x0, low, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[0][st], x0, acc, 0, 0, 0);
+          }
+        }
+        const float u = u_s[ct] * u_w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float v = activate(fmaf(fmaf(low[i], kSplitLowUnscale, acc[i]), u, bias4[i]), act);
+          held[slot][ct][i] = v;
+          m_s[ct] = fmaxf(m_s[ct], fabsf(v));
+        }
+      }
+    }
+    if (last) {
+      __syncthreads();  // every wave has read the layer's input: the buffer takes the network's output
+#pragma unroll
+      for (int slot = 0; slot < kMfmaSlots; ++slot) {
+        const int nt = wave + kMfmaWaves * slot;
+        if (nt >= NT) continue;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int o = 16 * nt + 4 * q + i;
+            if (o < N) fin[o * TB + 16 * ct + j] = held[slot][ct][i];
+          }
+      }
+      __syncthreads();
+      break;
+    }
+    // ---- per-sample scale of this layer's outputs: the largest magnitude over all neurons ----
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      float m = m_s[ct];
+      m = fmaxf(m, __shfl_xor(m, 16, 64));
+      m = fmaxf(m, __shfl_xor(m, 32, 64));
+      if (q == 0) smax[wave * TB + 16 * ct + j] = m;
+    }
+    __syncthreads();  // every wave has read the layer's input, and the maxima are out
+    float s_new[4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const int smp = 16 * ct + j;
+      float m = smax[smp];
+#pragma unroll
+      for (int w = 1; w < kMfmaWaves; ++w) m = fmaxf(m, smax[w * TB + smp]);
+      s_new[ct] = split_pow2_scale(m);
+      u_s[ct] = pow2_reciprocal(s_new[ct]);
+    }
+#pragma unroll
+    for (int slot = 0; slot < kMfmaSlots; ++slot) {
+      const int nt = wave + kMfmaWaves * slot;
+      if (nt >= NT) continue;
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        uint2 lead, resid;
+        split2_pair(s_new[ct] * held[slot][ct][0], s_new[ct] * held[slot][ct][1], lead.x, resid.x);
+        split2_pair(s_new[ct] * held[slot][ct][2], s_new[ct] * held[slot][ct][3], lead.y, resid.y);
+        unsigned char* dst = at + (16 * ct + j) * kRowB + (16 * nt + 4 * q) * 2;
+        *reinterpret_cast<uint2*>(dst) = lead;
+        *reinterpret_cast<uint2*>(dst + kTermB) = resid;
+      }
+    }
+    __syncthreads();
+    off += K * N + N;
+  }
+
+  // ---- the network output [A][sample] -> memory, or its loss (as in mlp_f32_kernel) -----------------------
+  const int A = a.sh.dims[n_layers];
+  const int s = tid & 63, b = b0 + s;
+  if (LOSS == LOSS_NONE) {
+    float* dst = a.out + (static_cast<size_t>(member) * a.B + b0) * A;
+    const int rows = min(TB, a.B - b0);
+    for (int i = tid; i < rows * A; i += 64 * kMfmaWaves) {
+      const int ss = i / A, o = i - ss * A;
+      dst[i] = fin[o * TB + ss];
+    }
+    return;
+  }
+  if (wave != 0) return;
+  float loss = 0.f;
+  if (b < a.B) {
+    if (LOSS == LOSS_CE) {
+      const int y = min(max(static_cast<const int32_t*>(a.target)[b], 0), A - 1);  // labels outside [0, A) are clamped
+      float mx = fin[s];
+      for (int o = 1; o < A; ++o) mx = fmaxf(mx, fin[o * TB + s]);
+      float se = 0.f;
+      for (int o = 0; o < A; ++o) se += expf(fin[o * TB + s] - mx);
+      loss = (mx + logf(se)) - fin[y * TB + s];
+    } else {
+      const float* tg = static_cast<const float*>(a.target) + (static_cast<size_t>(member) * a.B + b) * A;
+      for (int o = 0; o < A; ++o) {
+        const float d = fin[o * TB + s] - tg[o];
+        loss = fmaf(d, d, loss);
+      }
+    }
+  }
+  loss = wave_sum(loss);
+  if (s == 0) a.partial[static_cast<size_t>(member) * a.tiles + blockIdx.x] = loss;
+}
+
+// The matrix-core kernel takes networks of widths up to 256 with at least one fan-in of 64 or more.
+static bool mfma_shape(const MlpShape& sh) {
+  if (sh.max_width > kMfmaMaxWidth) return false;
+  for (int l = 0; l < sh.n_layers; ++l)
+    if (sh.dims[l] >= 64) return true;
+  return false;
+}
+
 int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, int64_t obs_stride, int pop, int B,
                    float* out, int loss, const void* target, float* partial, hipStream_t s) {
   EVO_REQUIRE(sh.max_width <= 256, EVO_ERR_UNSUPPORTED, "fp32 MLP: layer widths above 256 are not supported (%d)",
@@ -135,9 +375,26 @@ int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, in
   a.sh = sh, a.params = params, a.obs = obs, a.obs_stride = obs_stride, a.B = B;
   a.out = out, a.target = target, a.partial = partial;
   a.tiles = (B + kMlpTile - 1) / kMlpTile;
+  const dim3 grid(a.tiles, pop);
+  if (mfma_shape(sh)) {
+    int kp = 32;      // widest fan-in, padded to the matrix instruction's 32
+    for (int l = 0; l < sh.n_layers; ++l) kp = max(kp, (sh.dims[l] + 31) & ~31);
+    a.ldw = kp;
+    const size_t lds = static_cast<size_t>(2) * kMlpTile * (kp + 8) * 2 + (kMfmaWaves + 1) * kMlpTile * sizeof(float);
+    auto launch_mfma = [&](auto kern) -> int {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) (void)hipGetLastError();
+      EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
+      hipLaunchKernelGGL(kern, grid, dim3(64 * kMfmaWaves), lds, s, a);
+      return check_launch("mlp_f32_mfma_kernel");
+    };
+    if (loss == LOSS_NONE) return launch_mfma(mlp_f32_mfma_kernel<LOSS_NONE>);
+    if (loss == LOSS_CE) return launch_mfma(mlp_f32_mfma_kernel<LOSS_CE>);
+    return launch_mfma(mlp_f32_mfma_kernel<LOSS_MSE>);
+  }
   a.ldw = sh.max_width;
   const size_t shmem = sizeof(float) * 2 * a.ldw * kMlpTile;
-  const dim3 grid(a.tiles, pop);
   auto launch = [&](auto kern) -> int {
     if (shmem > 64 * 1024) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

@@ -49,6 +49,53 @@ def test_pop_forward_mlp_f32(evo, dims, acts, pop, B, shared):
     assert_close(host(out), ref, 1e-5, "mlp forward")
 
 
+# Networks with a fan-in of 64 or more run their layers on the matrix cores (two-term fp16 splits of the fp32
+# operands, scales set at run time): fp32 accuracy over ragged widths, batches and value ranges.
+@pytest.mark.parametrize("dims,acts,pop,B,shared,scale", [
+    ((64, 256, 256, 16), (2, 2, 0), 3, 200, False, 0.1), ((64, 256, 256, 16), (1, 1, 1), 2, 64, True, 0.4),
+    ((70, 100, 3), (2, 0), 3, 65, False, 0.3), ((64, 48, 5), (0, 0), 2, 1, True, 0.5),
+    ((200, 256, 256, 7), (1, 2, 0), 2, 130, False, 0.2), ((256, 17), (1,), 4, 33, True, 0.3),
+    ((64, 256, 256, 16), (2, 2, 0), 2, 70, False, 1e-3), ((64, 256, 256, 16), (2, 0, 0), 2, 70, False, 30.0)])
+def test_pop_forward_mlp_f32_matrix_cores(evo, dims, acts, pop, B, shared, scale):
+    P = mlp_param_count(dims)
+    params = gen.random_params(16, pop, P, scale)
+    r = np.random.default_rng(17)
+    obs = r.standard_normal((B, dims[0]) if shared else (pop, B, dims[0])).astype(np.float32)
+    if not shared and 1 not in acts:
+        # one sample far larger than the others, one far smaller: scales are per sample.  (Not in front of a tanh:
+        # pre-activations of +-1e4 that cancel to order one are off by more than 1e-5 in any fp32 evaluation.)
+        obs[0, 0] *= 1.0e4
+        obs[-1, -1] *= 1.0e-4
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    out = torch.full((pop, B, dims[-1]), np.nan, dtype=torch.float32, device="cuda")
+    evo.pop_forward(pd, dev(params), dev(obs), 0 if shared else B * dims[0], out, pop, B)
+    ref = opolicy.mlp_forward(params, obs, dims, acts)
+    got = host(out)
+    for m in range(pop):
+        for b in range(B):           # every sample on its own scale
+            assert_close(got[m, b], ref[m, b], 1e-5, "member %d sample %d" % (m, b))
+
+
+def test_rollout_losses_mlp_f32_matrix_cores(evo):
+    dims, acts, pop, B = (64, 128, 10), (2, 0), 5, 150
+    P = mlp_param_count(dims)
+    params = gen.random_params(18, pop, P, 0.2)
+    x, y = gen.class_blobs(19, B, dims[0], dims[-1])
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    fit = _classify(evo, pd, dev(params), dev(x), dev(y), pop, B)
+    ref = otasks.classify_fitness(opolicy.mlp_forward(params, x, dims, acts), y)
+    assert_scalar_rel(fit, ref, 1e-5, "classification fitness")
+    obs, tgt = gen.teacher_regression(20, pop, B, dims)
+    od, tdv = dev(obs), dev(tgt)
+    td = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=B, obs=od, obs_member_stride=B * dims[0], target=tdv)
+    work = _work(evo, td, pd, pop)
+    td = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=B, obs=od, obs_member_stride=B * dims[0], target=tdv, work=work)
+    fit = torch.empty(pop, dtype=torch.float32, device="cuda")
+    evo.rollout(td, pd, dev(params), pop, 1, fit)
+    ref = otasks.regress_fitness(opolicy.mlp_forward(params, obs, dims, acts), tgt)
+    assert_scalar_rel(host(fit), ref, 1e-5, "regression fitness")
+
+
 def test_rollout_classify_mlp_cfg1(evo):
     c = CONFIGS["cfg1"]
     x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
