@@ -5,7 +5,9 @@ Figure 2 and the trainer / simulation-manager paragraph; Section 4's ask / tell)
 ask -> evaluate every member with the global policy on the vectorised task -> tell.
 `task` is a plain dict: kind in {"classify","regress","cartpole","sphere","seq2seq","forage","forage_solo"}, the policy
 description and the task's input arrays.  parity unpinned as a whole: the paper prints no
-value of any generation; every stage it calls is pinned on its own.
+value of any generation; every stage it calls is pinned on its own, and the routing done here is
+pinned in tests/test_oracle_generation.py (torch's functional network and losses, closed forms, the
+free cart-pole stepped by hand, ask -> evaluate -> tell spelled out).
 """
 import numpy as np
 
