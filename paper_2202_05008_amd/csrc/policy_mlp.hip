@@ -29,6 +29,7 @@ struct MlpArgs {
   float* partial;
   int tiles;
   int ldw;  // LDS row capacity (max width)
+  int pop;
 };
 
 __device__ __forceinline__ float activate(float x, int act) {
@@ -136,8 +137,8 @@ __global__ __launch_bounds__(256) void mlp_f32_kernel(MlpArgs a) {
 
 // ---- the matrix-core form ------------------------------------------------------------------------------
 // Workgroup = (member, tile of 64 samples), eight waves (two per SIMD).  A layer is computed
-// transposed: rows of a 16 x 16 tile are neurons (A operand: the member's weights W[k][neuron], read from
-// memory as they are needed and split once per neuron tile), columns are samples (B operand: the layer's input,
+// transposed: rows of a 16 x 16 tile are neurons (A operand: the member's weights W[k][neuron], fetched one
+// tile ahead of their use and split once per neuron tile), columns are samples (B operand: the layer's input,
 // kept in LDS as two fp16 terms [term][sample][k], one 16-byte read per term and 32 k).  A lane then ends up
 // with four consecutive neurons of one sample: bias, activation, and one 8-byte LDS store per term hand them
 // to the next layer.  Wave w takes neuron tiles w, w + 8, ...; its outputs wait in registers until every wave
@@ -166,7 +167,11 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = lane & 15, q = lane >> 4;
-  const int member = blockIdx.y, b0 = blockIdx.x * TB;
+  // Workgroup -> (member, tile): consecutive workgroup numbers go to the eight dies in turn, each with a cache
+  // of its own, so a member's tiles, which read the same weights, take numbers that are 8 apart.
+  const int die = blockIdx.x & 7, turn = blockIdx.x >> 3;
+  const int member = 8 * (turn / a.tiles) + die, tile = turn % a.tiles, b0 = tile * TB;
+  if (member >= a.pop) return;
   const float* theta = a.params + static_cast<size_t>(member) * a.sh.P;
   const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
 
@@ -176,18 +181,46 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
     const int smp = tid >> 3, part = tid & 7;
     const bool live = b0 + smp < a.B;
     const float* row = obs + static_cast<size_t>(b0 + smp) * D;
-    float m = 0.f;
-    for (int d = part; d < D; d += 8) m = fmaxf(m, live ? fabsf(row[d]) : 0.f);
-    m = fmaxf(m, __shfl_xor(m, 1, 64));
-    m = fmaxf(m, __shfl_xor(m, 2, 64));
-    m = fmaxf(m, __shfl_xor(m, 4, 64));
-    const float sc = split_pow2_scale(m);
-    for (int d = 2 * part; d < KP; d += 16) {
-      const float x0 = (live && d < D) ? sc * row[d] : 0.f, x1 = (live && d + 1 < D) ? sc * row[d + 1] : 0.f;
-      uint32_t lead, resid;
-      split2_pair(x0, x1, lead, resid);
-      *reinterpret_cast<uint32_t*>(at + smp * kRowB + d * 2) = lead;
-      *reinterpret_cast<uint32_t*>(at + kTermB + smp * kRowB + d * 2) = resid;
+    float sc;
+    if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(obs) & 15u) == 0) {  // then every row starts on 16 bytes
+      // every 16-byte load of the thread's share of the row is in flight at once: one trip to memory
+      float4 v[kMfmaMaxWidth / 32];
+      float m = 0.f;
+#pragma unroll
+      for (int c = 0; c < kMfmaMaxWidth / 32; ++c) {
+        const int d = 4 * (part + 8 * c);
+        v[c] = (live && d < D) ? *reinterpret_cast<const float4*>(row + d) : make_float4(0.f, 0.f, 0.f, 0.f);
+        m = fmaxf(fmaxf(m, fmaxf(fabsf(v[c].x), fabsf(v[c].y))), fmaxf(fabsf(v[c].z), fabsf(v[c].w)));
+      }
+      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      m = fmaxf(m, __shfl_xor(m, 2, 64));
+      m = fmaxf(m, __shfl_xor(m, 4, 64));
+      sc = split_pow2_scale(m);
+#pragma unroll
+      for (int c = 0; c < kMfmaMaxWidth / 32; ++c) {
+        const int d = 4 * (part + 8 * c);
+        if (d < KP) {
+          uint2 lead, resid;
+          split2_pair(sc * v[c].x, sc * v[c].y, lead.x, resid.x);
+          split2_pair(sc * v[c].z, sc * v[c].w, lead.y, resid.y);
+          *reinterpret_cast<uint2*>(at + smp * kRowB + d * 2) = lead;
+          *reinterpret_cast<uint2*>(at + kTermB + smp * kRowB + d * 2) = resid;
+        }
+      }
+    } else {
+      float m = 0.f;
+      for (int d = part; d < D; d += 8) m = fmaxf(m, live ? fabsf(row[d]) : 0.f);
+      m = fmaxf(m, __shfl_xor(m, 1, 64));
+      m = fmaxf(m, __shfl_xor(m, 2, 64));
+      m = fmaxf(m, __shfl_xor(m, 4, 64));
+      sc = split_pow2_scale(m);
+      for (int d = 2 * part; d < KP; d += 16) {
+        const float x0 = (live && d < D) ? sc * row[d] : 0.f, x1 = (live && d + 1 < D) ? sc * row[d + 1] : 0.f;
+        uint32_t lead, resid;
+        split2_pair(x0, x1, lead, resid);
+        *reinterpret_cast<uint32_t*>(at + smp * kRowB + d * 2) = lead;
+        *reinterpret_cast<uint32_t*>(at + kTermB + smp * kRowB + d * 2) = resid;
+      }
     }
     if (part == 0) us_s[smp] = pow2_reciprocal(sc);
   }
@@ -196,37 +229,83 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) u_s[ct] = us_s[16 * ct + j];
 
-  int off = 0;
+  // A neuron tile's weights as A operands, A[row j][k = 32 s + 8 q + e] = W[k][16 nt + j], and its four biases
+  // per lane, are fetched one tile ahead: all 64 loads of the next tile are in flight while the matrix
+  // instructions of this one run.
+  float raw[kMfmaKSteps][8], bias4[4];
   const int n_layers = a.sh.n_layers;
+  auto tiles_of = [&](int l) {  // neuron tiles of layer l: its outputs fill the next fan-in up to a multiple of 32
+    const int N = a.sh.dims[l + 1];
+    return l == n_layers - 1 ? (N + 15) >> 4 : ((N + 31) & ~31) >> 4;
+  };
+  // Fetches this wave's first tile at or after (layer l, slot).  Loads go to clamped addresses, so that none is
+  // predicated or waited for here; what lies beyond the layer's fan-in or fan-out is zeroed where the tile is used.
+  auto fetch_from = [&](int l, int slot, const float* W) {
+    while (l < n_layers && !(slot < kMfmaSlots && wave + kMfmaWaves * slot < tiles_of(l))) {
+      W += a.sh.dims[l] * a.sh.dims[l + 1] + a.sh.dims[l + 1];
+      ++l, slot = 0;
+    }
+    if (l >= n_layers) return;
+    const int K = a.sh.dims[l], N = a.sh.dims[l + 1], nt = wave + kMfmaWaves * slot;
+    const int KS = (K + 31) >> 5;
+    // address = a wave-uniform row pointer + an unsigned per-lane offset (no per-load vector arithmetic); only
+    // a ragged last step clamps its rows per lane
+    const unsigned lane_off = 4u * static_cast<unsigned>(8 * q * N + min(16 * nt + j, N - 1));  // bytes
+#pragma unroll
+    for (int st = 0; st < kMfmaKSteps; ++st) {
+      if (st < KS) {
+        if (32 * st + 32 <= K) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            raw[st][e] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(W + (32 * st + e) * N) + lane_off);
+        } else {
+          const unsigned col = static_cast<unsigned>(min(16 * nt + j, N - 1));
+#pragma unroll
+          for (int e = 0; e < 8; ++e) raw[st][e] = W[static_cast<unsigned>(min(32 * st + 8 * q + e, K - 1) * N) + col];
+        }
+      }
+    }
+    const float* bias = W + K * N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int o = 16 * nt + 4 * q + i;
+      bias4[i] = bias[min(o, N - 1)];
+    }
+  };
+  fetch_from(0, 0, theta);
+
+  int off = 0;
   for (int l = 0; l < n_layers; ++l) {
     const int K = a.sh.dims[l], N = a.sh.dims[l + 1], act = a.sh.act[l];
     const bool last = l == n_layers - 1;
     const int KS = (K + 31) >> 5;
-    // neuron tiles to produce: enough to fill the next layer's fan-in up to a multiple of 32 (zeros beyond N)
-    const int NT = last ? (N + 15) >> 4 : ((N + 31) & ~31) >> 4;
+    const int NT = tiles_of(l);
     const float* W = theta + off;
-    const float* bias = W + K * N;
     float held[kMfmaSlots][4][4];  // [slot][sample tile][neuron 4 q + i]: this wave's outputs of the layer
     float m_s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int slot = 0; slot < kMfmaSlots; ++slot) {
       const int nt = wave + kMfmaWaves * slot;
       if (nt >= NT) continue;
-      // ---- this tile's weights as A operands: A[row j][k = 32 s + 8 q + e] = W[k][16 nt + j] ----
-      const int neuron = 16 * nt + j;
-      const bool ok = neuron < N;
-      // two passes over the tile's weights (the second one hits the cache): their largest magnitude sets the
-      // scale, then they are split; keeping them in registers in between costs 64 registers too many
-      const float* wcol = W + neuron;
+      // ---- zeros beyond a ragged fan-in or fan-out, scale from the tile's largest magnitude, split ----
+      if ((K & 31) != 0 || 16 * nt + 16 > N) {
+        const bool ok = 16 * nt + j < N;
+#pragma unroll
+        for (int st = 0; st < kMfmaKSteps; ++st) {
+          if (st < KS) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) raw[st][e] = (ok && 32 * st + 8 * q + e < K) ? raw[st][e] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bias4[i] = 16 * nt + 4 * q + i < N ? bias4[i] : 0.f;
+      }
       float w_max = 0.f;
 #pragma unroll
       for (int st = 0; st < kMfmaKSteps; ++st) {
         if (st < KS) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int k = 32 * st + 8 * q + e;
-            w_max = fmaxf(w_max, (ok && k < K) ? fabsf(wcol[static_cast<size_t>(k) * N]) : 0.f);
-          }
+          for (int e = 0; e < 8; ++e) w_max = fmaxf(w_max, fabsf(raw[st][e]));
         }
       }
       const float s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
@@ -235,18 +314,16 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
 #pragma unroll
       for (int st = 0; st < kMfmaKSteps; ++st) {
         if (st < KS) {
-          float raw[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int k = 32 * st + 8 * q + e;
-            raw[e] = (ok && k < K) ? s_w * wcol[static_cast<size_t>(k) * N] : 0.f;
-          }
-          split2_x8(raw, wa[0][st], wa[1][st]);
+          for (int e = 0; e < 8; ++e) raw[st][e] *= s_w;
+          split2_x8(raw[st], wa[0][st], wa[1][st]);
         }
       }
-      float bias4[4];
+      float b4[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) bias4[i] = 16 * nt + 4 * q + i < N ? bias[16 * nt + 4 * q + i] : 0.f;
+      for (int i = 0; i < 4; ++i) b4[i] = bias4[i];
+      // ---- this wave's next tile: the layer's second one, else the first of a later layer ----
+      fetch_from(l, slot + 1, W);
       // ---- four sample tiles ----
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
@@ -265,7 +342,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
         const float u = u_s[ct] * u_w;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float v = activate(fmaf(fmaf(low[i], kSplitLowUnscale, acc[i]), u, bias4[i]), act);
+          const float v = activate(fmaf(fmaf(low[i], kSplitLowUnscale, acc[i]), u, b4[i]), act);
           held[slot][ct][i] = v;
           m_s[ct] = fmaxf(m_s[ct], fabsf(v));
         }
@@ -356,7 +433,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
     }
   }
   loss = wave_sum(loss);
-  if (s == 0) a.partial[static_cast<size_t>(member) * a.tiles + blockIdx.x] = loss;
+  if (s == 0) a.partial[static_cast<size_t>(member) * a.tiles + tile] = loss;
 }
 
 // The matrix-core kernel takes networks of widths up to 256 with at least one fan-in of 64 or more.
@@ -375,6 +452,7 @@ int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, in
   a.sh = sh, a.params = params, a.obs = obs, a.obs_stride = obs_stride, a.B = B;
   a.out = out, a.target = target, a.partial = partial;
   a.tiles = (B + kMlpTile - 1) / kMlpTile;
+  a.pop = pop;
   const dim3 grid(a.tiles, pop);
   if (mfma_shape(sh)) {
     int kp = 32;      // widest fan-in, padded to the matrix instruction's 32
@@ -386,7 +464,7 @@ int launch_mlp_f32(const MlpShape& sh, const float* params, const float* obs, in
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
       if (e != hipSuccess) (void)hipGetLastError();
       EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-      hipLaunchKernelGGL(kern, grid, dim3(64 * kMfmaWaves), lds, s, a);
+      hipLaunchKernelGGL(kern, dim3(8 * ((pop + 7) / 8) * a.tiles), dim3(64 * kMfmaWaves), lds, s, a);
       return check_launch("mlp_f32_mfma_kernel");
     };
     if (loss == LOSS_NONE) return launch_mfma(mlp_f32_mfma_kernel<LOSS_NONE>);

@@ -55,7 +55,8 @@ def test_pop_forward_mlp_f32(evo, dims, acts, pop, B, shared):
     ((64, 256, 256, 16), (2, 2, 0), 3, 200, False, 0.1), ((64, 256, 256, 16), (1, 1, 1), 2, 64, True, 0.4),
     ((70, 100, 3), (2, 0), 3, 65, False, 0.3), ((64, 48, 5), (0, 0), 2, 1, True, 0.5),
     ((200, 256, 256, 7), (1, 2, 0), 2, 130, False, 0.2), ((256, 17), (1,), 4, 33, True, 0.3),
-    ((64, 256, 256, 16), (2, 2, 0), 2, 70, False, 1e-3), ((64, 256, 256, 16), (2, 0, 0), 2, 70, False, 30.0)])
+    ((64, 256, 256, 16), (2, 2, 0), 2, 70, False, 1e-3), ((64, 256, 256, 16), (2, 0, 0), 2, 70, False, 30.0),
+    ((64, 96, 16), (2, 0), 11, 130, False, 0.3)])   # members beyond one group of eight, three tiles each
 def test_pop_forward_mlp_f32_matrix_cores(evo, dims, acts, pop, B, shared, scale):
     P = mlp_param_count(dims)
     params = gen.random_params(16, pop, P, scale)
