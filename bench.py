@@ -146,9 +146,15 @@ def _build_workload(name, seed, batch=None):
         td = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=c.B, obs=od, obs_member_stride=c.B * c.dims[0], target=tg)
         wl["task"] = lambda t: td
         nbytes = c.pop * (c.P * 2.0 + c.B * c.dims[0] * 4.0 + c.B * c.dims[-1] * 4.0 + 4.0)
-        wl["roofline"] = ("hbm", nbytes, PEAK_HBM_GBS, "GB/s")
+        flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.pop * c.B
+        # past the ridge (peak flop rate / peak byte rate = 312 flop per byte) the forward is priced as a contraction
+        if flops / nbytes > PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9):
+            wl["roofline"] = ("mfma", flops, PEAK_MFMA_BF16_TF, "TFLOP/s")
+            wl["hbm_bytes_work"] = nbytes
+        else:
+            wl["roofline"] = ("hbm", nbytes, PEAK_HBM_GBS, "GB/s")
+            wl["mfma_tflops_work"] = flops
         wl["desc"] = "cfg4: wide bf16 MLP 64-256-256-16, pop 4096, %d observations per member" % c.B
-        wl["mfma_tflops_work"] = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.pop * c.B
         wl["dtype"] = "bf16"
     elif name == "cfg5":
         wl["pd"] = None
@@ -440,6 +446,11 @@ def _run_workload(name, args, steps, warmup, torch):
     if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
         out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
+    if "hbm_bytes_work" in wl:      # ... and its HBM rate next to its matrix-core rate
+        out["roofline"]["hbm_GBs"] = wl["hbm_bytes_work"] / (dom_ms * 1e-3) / 1e9
+        out["roofline"]["hbm_frac"] = out["roofline"]["hbm_GBs"] / PEAK_HBM_GBS
+        out["roofline"]["bound_detail"] = ("bf16 matrix instructions of the register-resident forward: MFMA busy 42 %, "
+                                           "co-limited by LDS operand reads (DESIGN.md, section 7)")
     if args.graph:
         out["config"]["launch"] = "HIP graph replay of one recorded generation; stage_ms from direct calls before it"
     if args.batch is not None:
@@ -454,7 +465,11 @@ def _run_workload(name, args, steps, warmup, torch):
             normals = c.pop / 2 * c.P
             out["roofline"] = {"bound": "alu", "achieved": normals / (dom_ms * 1e-3) / 1e9, "peak": None,
                                "unit": "Gnormal/s", "frac": None, "traffic": None,
-                               "kernel": "ask_rollout" if name == "cfg4" else "ask_sphere", "kernel_ms": dom_ms}
+                               "kernel": "ask_rollout" if name == "cfg4" else "ask_sphere", "kernel_ms": dom_ms,
+                               "bound_detail": "vector instructions of the noise generation (Philox4x32-10 + Box-Muller "
+                               "per antithetic pair): no published peak applies; VALU busy " +
+                               ("70 % (profiles/mlp_bf16_stream_kernel_cfg4.md)" if name == "cfg4" else
+                                "as in profiles/ask_sphere_tell_kernels_cfg5.md")}
     pg.close()
     del wl
     torch.cuda.empty_cache()
