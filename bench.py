@@ -37,7 +37,7 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2876815,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 33267688,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
+    "cfg2": 33462628,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
     "cfg3": 19117871,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4305387571,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
@@ -52,7 +52,9 @@ MEASURED_TRAFFIC_BYTES = {
 # What the rocprofv3 counters in profiles/ say bounds the dominant kernel.
 BOUND_DETAIL = {
     "cfg1": "launch latency: five launches of a few microseconds each (profiles/mlp_f32_kernel_cfg1.md)",
-    "cfg2": "vector-instruction issue: VALU busy 84 %, MFMA busy 21 % (profiles/convnet_kernel_cfg2.md)",
+    "cfg2": "both convolutions on the matrix cores: MFMA busy 30 %, VALU busy 53 % on the same SIMDs (8 % of the cycles overlap), "
+            "LDS busy 68 % of which a third are bank conflicts, 24 % of wave time waiting, three waves per SIMD "
+            "(profiles/convnet_kernel_cfg2.md)",
     "cfg3": "vector-instruction issue along a 1000-step dependency chain: VALU busy 70 %, MFMA busy 22 %, 39 % of wave "
             "time waiting (profiles/cartpole_kernel_cfg3.md)",
     "cfg4": "HBM weight stream: 64 flop per weight byte (profiles/mlp_bf16_stream_kernel_cfg4.md)",
@@ -116,8 +118,9 @@ def _build_workload(name, seed, batch=None):
                 batches.append((torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)))
             c1, c2, ncls = c.dims
             per_img = 2.0 * (9 * c1 * 28 * 28 + 9 * c1 * c2 * 14 * 14 + 7 * 7 * c2 * ncls)
-            # conv2 as issued: k padded from 72 to 96, three fp16 matrix instructions per product
-            wl["roofline"] = ("valu-issue", 3.0 * 2.0 * 96 * c2 * 14 * 14 * c.pop * c.B, PEAK_MFMA_BF16_TF, "TFLOP/s")
+            # as issued: v_mfma_f32_16x16x32_f16 (16,384 flop each) per image: conv1 7 passes x 2 tiles x 4, conv2 7 bands x
+            # 3 steps of k x 2 tiles x 3 products of split terms
+            wl["roofline"] = ("mfma", 16384.0 * (7 * 2 * 4 + 7 * 3 * 2 * 3) * c.pop * c.B, PEAK_MFMA_BF16_TF, "TFLOP/s")
             wl["fp32_flops"] = per_img * c.pop * c.B
             wl["desc"] = "cfg2: MNIST-shaped synthetic images, per-member fp32 ConvNet P=9098, pop 256, batch 1024"
         tds = [with_work(lambda w, b=b: evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=b[0], target=b[1], work=w))
@@ -531,6 +534,11 @@ def main():
             per[name] = {"workload": r["config"]["workload"], "ms_per_generation": r["ms_per_step"], "steps": r["steps"],
                          "value": r["value"], "unit": r["unit"], "dtype": r["dtype"], "stage_ms": r["stage_ms"],
                          "roofline": r["roofline"]}
+            if name == "cfg4":      # the same generation with ask fused into the forward (no population in memory)
+                fa = argparse.Namespace(**{**vars(args), "variant": "fused"})
+                r = _run_workload(name, fa, DEFAULT_STEPS[name], args.warmup, torch)
+                per[name]["ask_fused_into_forward"] = {"ms_per_generation": r["ms_per_step"], "value": r["value"],
+                                                       "stage_ms": r["stage_ms"], "roofline": r["roofline"]}
         out["per_config"] = per
     if not args.no_peaks:
         out["measured_peaks"] = _measure_peaks(evo, torch)

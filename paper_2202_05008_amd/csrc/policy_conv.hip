@@ -6,33 +6,47 @@
 // conv3x3 -> ReLU -> maxpool2 -> conv3x3 -> ReLU -> maxpool2 -> dense, c1 = 8, c2 = 16.
 //
 // Each wavefront runs whole images end to end out of its private 10 KB slice of LDS, with no
-// workgroup barrier in the loop: conv1 (K = 9) on the vector ALU, conv2 (K = 72, N = 16:
-// 78% of the flops) as implicit GEMM on the matrix cores, the dense layer on the vector ALU
-// against a workgroup-shared LDS copy of its weights.  The next image is prefetched into
+// workgroup barrier in the loop: both convolutions as implicit GEMMs on the matrix cores, the dense layer
+// on the vector ALU against a workgroup-shared LDS copy of its weights, accumulated band by band from the
+// conv2 results while they are still in registers.  The next image is prefetched into
 // registers while the current one is computed.  Activations never leave the chip; per image
 // the kernel reads 3 KB (L2 resident, shared by all members).
 //
-// conv2 arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
+// Arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
 // v_mfma_f32_16x16x4_f32 takes 32 cycles (1024 MACs), and the two do not overlap, so the fp32
 // matrix instruction is only 1.4x the vector rate.  v_mfma_f32_16x16x32_f16 takes 16 cycles
-// for 8192 MACs.  conv2 therefore runs on the fp16 matrix instruction with every fp32 operand
-// split into two half-precision terms (split16.h): three matrix instructions per product, a
-// product within 3 * 2^-22 of the fp32 one, a 72-term sum well inside the 1e-5 gate (measured:
-// 4e-7 of the rms), at 3 / 16 of the issue cycles of the fp32 matrix instruction.  Both operands
-// carry a power-of-two scale chosen at run time so that any finite value fits fp16's range: the
-// conv2 weights of a member from their largest magnitude, the conv1 activations of an image from
-// the bound max|pixel| max_c sum_t |W1[t][c]| + max_c |b1[c]| (the conv1 sums start from the bias,
+// for 8192 MACs.  The convolutions therefore run on the fp16 matrix instruction with every fp32 operand
+// split into two half-precision terms (split16.h): a product within 3 * 2^-22 of the fp32 one, sums of 9 and
+// 72 terms well inside the 1e-5 gate (measured: 2e-7 .. 7e-7 of the rms of the logits).  Every operand
+// carries a power-of-two scale chosen at run time so that any finite value fits fp16's range: the
+// weights of a member from their largest magnitude (conv1: per output channel), the pixels of an image from
+// their largest magnitude, the conv1 activations of an image from
+// the bound max|pixel| max_c sum_t |W1[t][c]| + max_c |b1[c]| (the conv1 sums start from the scaled bias,
 // so the factor is one multiply before the ReLU; the conv2 bias is added by the multiply-add that
 // takes both factors out again).  A member with a non-finite convolution weight, or an image with
 // an infinite pixel, gets NaN logits (the maximum operations of ReLU and pooling would otherwise
 // swallow what fp32 arithmetic propagates); a NaN pixel is not detected.
 //
+// conv1 tiling (K = 9, one input channel).  The image sits in LDS as two planes of fp16 terms.  The 16
+// columns of a matrix tile are 16 pooling windows; the contraction runs over the 4 x 4 pixel patch that holds
+// the 3 x 3 neighbourhoods of the window's four pixels (k = 4 r + c; the lane's eight values are two rows of
+// four consecutive pixels: four 4-byte LDS reads), once against the leading terms of the pixels (lane groups
+// 0, 1) and once against their residual terms (lane groups 2, 3), which fills K = 32.  The 16 rows are
+// (8 output channels) x (the window's two pixel columns); one set of weight operands per pixel row of the
+// window (the stencil shifted inside the patch, zeros elsewhere).  With the residual-side factor 2^-11 folded
+// into the weight operands, h h' + 2^-11 (m' h + h' m) takes two instructions into ONE accumulator:
+// (h | h 2^-11) and (m 2^-11 | 0) against (h' | m').  (fp16 values of h 2^-11 below 2^-14 vanish: weights
+// more than 2^17 below the largest of their channel then carry 11 bits, which is below 2^-28 of the channel's
+// activations.)  Row order (channel pair, column, channel parity) puts a window's two columns of channels
+// 2 q, 2 q + 1 into the four accumulator registers of lane group q: pooling is three maxima per channel on
+// registers, and the pooled pair goes to the band buffers as one 4-byte store per term.
+//
 // Band pipeline.  conv2 output row b needs the pooled conv1 rows 2b-1 .. 2b+2 only (rows -1 and
 // H/2 are the zero border), so the conv1 output is never held whole: pass b of conv1 produces the
 // pooled rows 2b and 2b+1 and stores each twice, as rows 1, 2 of the four-row buffer of band b
 // and as row 3 of band b-1 and row 0 of band b+1 (three buffers in rotation); conv2 of band b-1
-// follows pass b.  H/4 passes do exactly the H/2 rows.  The conv2 output overwrites the part of the
-// image buffer that conv1 has already consumed.
+// follows pass b.  H/4 passes do exactly the H/2 rows.  The conv2 output never goes to memory: its pooled
+// values are the dense layer's features and are consumed from the registers they are computed in.
 //
 // conv2 tiling.  The 16 rows of a matrix tile are 4 pooling windows x their 4 pixels, so
 // that the 4 accumulator registers of a lane (rows 4q..4q+3 of column n) are exactly one
@@ -52,15 +66,16 @@ constexpr float kFltMax = 3.402823466e+38f;
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
-constexpr int kImgW = kHMax + 2;                     // padded image row (30)
-constexpr int kImgFloats = kImgW * kImgW + 4;        // 904: padded image; its consumed part takes the conv2 output
+constexpr int kPlanePitch = 64;                      // bytes of a padded image row of one split term: 30 fp16 pixels in 32 slots
+constexpr int kPlaneBytes = 33 * kPlanePitch;        // 2112: 30 rows + padding that puts the second term 16 banks after the first
+constexpr int kImgBytes = 2 * kPlaneBytes;           // the padded image as two fp16 terms
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
 constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as fp16
 constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 2a+1, interleaved pixel by pixel
 constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
 constexpr int kBandBytes = 2 * kBandTerm;            // 2048 bytes per band buffer
 constexpr int kBandFloats = kBandBytes / 4;          // 512
-constexpr int kWaveFloats = kImgFloats + 3 * kBandFloats;  // 2440 floats = 9,760 bytes per wave
+constexpr int kWaveFloats = kImgBytes / 4 + 3 * kBandFloats;  // 2592 floats = 10,368 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -126,9 +141,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   const int n_cls = a.n_cls;
 
   float* wd_s = lds;                                   // [n_feat][NCS] dense weights, shared by the waves
-  float* img = lds + kMaxFeat * NCS + wave * kWaveFloats;
-  float* band = img + kImgFloats;                      // three band buffers of conv1 output
-  float* a2 = img;                                     // conv2 output reuses the consumed image rows
+  float* img = lds + kMaxFeat * NCS + wave * kWaveFloats;  // the padded image as two fp16 terms
+  float* band = img + kImgBytes / 4;                   // three band buffers of conv1 output
+  char* const planes = reinterpret_cast<char*>(img);
 
   const float* theta = a.params + static_cast<size_t>(member) * a.P;
   const float* W1 = theta;                 // [3][3][1][8]
@@ -177,33 +192,81 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   const float bias2 = b2[n];
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
-  // conv1 role of this lane: pooled pixel (row select rs, column wx) x four channels 4 cg .. 4 cg + 3
-  const int c1_win = lane % (2 * H2), c1_cg = min(lane / (2 * H2), 1);
-  const bool c1_on = lane < 4 * H2;
-  const int c1_rs = c1_win / H2, c1_wx = c1_win - c1_rs * H2;
-  float w1v[9][4], bias1v[4];
-#pragma unroll
-  for (int t = 0; t < 9; ++t)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) w1v[t][c] = W1[t * kC1 + 4 * c1_cg + c];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) bias1v[c] = b1[4 * c1_cg + c];
-  // bound on the conv1 activations of any image: max|pixel| * bound_w1 + bound_b1 (both channel groups are
-  // present among the lanes of a wave)
-  float bound_w1, bound_b1;
+  // conv1 weights as matrix A operands.  Row i of the tile is (channel 2 (i >> 2) + (i & 1), pixel column
+  // s = (i >> 1) & 1 of the pooling window), so that the four accumulator registers of a lane (rows 4 q .. 4 q + 3
+  // of one window) are channels 2 q and 2 q + 1 at both columns.  The contraction runs over the 4 x 4 patch of a
+  // window, k = 4 r + c in lane groups 0, 1 (patch rows 0, 1 and 2, 3) against the leading terms of the pixels
+  // and again in lane groups 2, 3 against their residual terms; w1a[t] holds the weights shifted to the
+  // window's pixel row t (tap (r - t, c - s), zero outside the 3 x 3 stencil).  One instruction with
+  // (h | h 2^-11) and one with (m 2^-11 | 0) give h h' + 2^-11 (m' h + h' m) in a single accumulator.  Each
+  // channel has its own power of two (its weights' largest magnitude), taken out again by the epilogue.
+  f16x8 w1a[2][2];      // [pixel row t][instruction]
+  float sw1_row;        // scale of the channel of this lane's A row
+  float bound_w1, bound_b1;    // bound on the conv1 activations of any image: max|pixel| * bound_w1 + bound_b1
+  float sbound_w1, sbound_b1;  // the same bound on the scaled accumulators (before the pixels' scale)
   {
-    float sw = 0.f, sb = 0.f;
+    const int i = lane & 15, ch = 2 * (i >> 2) + (i & 1), sx = (i >> 1) & 1;
+    const int rblk = q & 1, half = q >> 1;
+    float wt[9], t_sum = 0.f, t_max = 0.f;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      float t_sum = 0.f;
-#pragma unroll
-      for (int t = 0; t < 9; ++t) t_sum += fabsf(w1v[t][c]);
-      sw = fmaxf(sw, t_sum);
-      sb = fmaxf(sb, fabsf(bias1v[c]));
-      lane_bad |= !(t_sum <= kFltMax) || !(fabsf(bias1v[c]) <= kFltMax) || !(fabsf(bias2) <= kFltMax);
+    for (int t = 0; t < 9; ++t) {
+      wt[t] = W1[t * kC1 + ch];
+      t_sum += fabsf(wt[t]);
+      t_max = fmaxf(t_max, fabsf(wt[t]));
     }
-    bound_w1 = wave_max(sw);
-    bound_b1 = wave_max(sb);
+    const float bch = b1[ch];
+    lane_bad |= !(t_sum <= kFltMax) || !(fabsf(bch) <= kFltMax) || !(fabsf(bias2) <= kFltMax);
+    // at most 2^56, so that the product with the pixels' scale (at most 2^56 too) stays finite
+    sw1_row = fminf(split_pow2_scale(t_max), 0x1p56f);
+    bound_w1 = wave_max(t_sum);
+    bound_b1 = wave_max(fabsf(bch));
+    sbound_w1 = wave_max(sw1_row * t_sum);
+    sbound_b1 = wave_max(sw1_row * fabsf(bch));
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      float x1[8], x2[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int dy = 2 * rblk + (j >> 2) - t, dx = (j & 3) - sx;
+        float w = 0.f;
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) w = (3 * dy + dx == tap && dx >= 0 && dx <= 2 && dy >= 0 && dy <= 2) ? wt[tap] : w;
+        w *= sw1_row;
+        const _Float16 h = static_cast<_Float16>(w);
+        const float hf = static_cast<float>(h), mf = (w - hf) * kSplitLowScale;
+        x1[j] = half ? hf * kSplitLowUnscale : hf;
+        x2[j] = half ? 0.f : static_cast<float>(static_cast<_Float16>(mf)) * kSplitLowUnscale;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        w1a[t][0][j] = static_cast<_Float16>(x1[j]);
+        w1a[t][1][j] = static_cast<_Float16>(x2[j]);
+      }
+    }
+  }
+  // conv1 D role: lane (window n, group q) ends with channels 2 q and 2 q + 1 of its window; their scales come
+  // from the lanes whose A rows are those channels (rows 4 q and 4 q + 1)
+  float sw1_d[2], b1_d[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    sw1_d[j] = __shfl(sw1_row, 4 * q + j, 64);
+    b1_d[j] = b1[2 * q + j];
+  }
+  // patch of window 16 m + n in the image planes (pass 0): term q >> 1, patch rows 2 (q & 1), 2 (q & 1) + 1;
+  // where its pooled pair goes in a band buffer: rows 1, 2 of the band of the pass and row 3 of the band
+  // before (upper pooled row) or row 0 of the band after (lower one)
+  const int n_mt = (H + 15) >> 4;   // tiles of 16 windows per pass (2 H2 = H windows)
+  int p_off[2], own_off[2], nbr_off[2];
+  bool c1_valid[2], c1_lower[2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m) {
+    const int w = 16 * m + n, wc = min(w, H - 1);
+    const int rs = wc / H2, wx = wc - rs * H2;
+    p_off[m] = (q >> 1) * kPlaneBytes + (2 * rs + 2 * (q & 1)) * kPlanePitch + 4 * wx;
+    own_off[m] = band_off(1 + rs, wx + 1) + 4 * q;
+    nbr_off[m] = band_off(rs ? 0 : 3, wx + 1) + 4 * q;
+    c1_valid[m] = w < H;
+    c1_lower[m] = rs != 0;
   }
   const bool member_bad = __any(lane_bad);
 
@@ -223,10 +286,6 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
   }
   char* const bandb = reinterpret_cast<char*>(band);
-  // conv1 store targets of this lane inside a band buffer: its row of the pass (2b or 2b+1) is row
-  // 1 or 2 of band b and row 3 of band b-1 or row 0 of band b+1
-  const int c1_dst_own = band_off(1 + c1_rs, c1_wx + 1) + 8 * c1_cg;
-  const int c1_dst_nbr = band_off(c1_rs ? 0 : 3, c1_wx + 1) + 8 * c1_cg;
   // one padded band row (16 pixels of 16 bytes, both terms) set to zero by lanes 0..31
   auto zero_band_row = [&](char* buf, int row) {
     if (lane < 32) *reinterpret_cast<uint4*>(buf + (lane >> 4) * kBandTerm + band_off(row, lane & 15)) = make_uint4(0, 0, 0, 0);
@@ -249,29 +308,58 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   __syncthreads();  // dense weights staged
 
   for (; im < img_end; im += kConvWaves) {
-    // ---- image registers -> zero-padded LDS buffer; then prefetch the next image ---------------
+    // ---- image registers -> two fp16 terms in the zero-padded planes; then prefetch the next image -------
     float px_max = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = lane + 64 * j;
-      if (i < n_vec) {
-        const int y = i / row4, x4 = i - y * row4;
-        float* d = img + (y + 1) * kImgW + 4 * x4 + 1;
-        d[0] = pre[j].x, d[1] = pre[j].y, d[2] = pre[j].z, d[3] = pre[j].w;
+    for (int j = 0; j < 4; ++j)
+      if (lane + 64 * j < n_vec)
         px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
-      }
-    }
-    // scale of this image's conv1 activations from the bound on them, and the factor that takes it and the
-    // weights' scale out again (all wave-uniform; non-negative floats order like their bit patterns)
+    // scales of this image (all wave-uniform; non-negative floats order like their bit patterns): of its
+    // pixels from their largest magnitude, of its conv1 activations from the bound on them
     px_max = row16_max(px_max);
     const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
                                      __builtin_amdgcn_readlane(__float_as_uint(px_max), 16)),
                                  max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 32),
                                      __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
-    const float a1_bound = fmaf(__uint_as_float(px_bits), bound_w1, bound_b1);
+    const float px_bound = __uint_as_float(px_bits);
+    const float a1_bound = fmaf(px_bound, bound_w1, bound_b1);
     const float s_a1 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(a1_bound))));
     const float u_a2 = pow2_reciprocal(s_a1) * u_w2;
     const bool image_bad = member_bad || !(a1_bound <= kFltMax);
+    // The pixels' scale is also limited so that the scaled conv1 sums stay below 2^100: the limit acts only where
+    // a bias is more than 2^70 times the convolution it is added to.
+    float s_px;
+    {
+      const float sb = fmaf(px_bound, sbound_w1, sbound_b1);  // bound on the accumulators before the pixels' scale
+      const int e_cap = 353 - ((__float_as_int(sb) >> 23) & 0xff);
+      const int e_px = min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183);
+      s_px = __int_as_float(__builtin_amdgcn_readfirstlane(min(e_px, e_cap) << 23));
+    }
+    float c1_init[2], c1_out[2];  // accumulators start from the scaled bias; factor from them to the stored activations
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float both = sw1_d[j] * s_px;
+      c1_init[j] = b1_d[j] * both;
+      c1_out[j] = s_a1 * pow2_reciprocal(both);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = lane + 64 * j;
+      if (i < n_vec) {
+        const int y = i / row4, x4 = i - y * row4;
+        // pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: the middle pair is a four-byte store
+        char* d = planes + (y + 1) * kPlanePitch + 8 * x4 + 2;
+        uint32_t lead_o, resid_o, lead_m, resid_m;
+        split2_pair(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
+        split2_pair(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
+        *reinterpret_cast<uint16_t*>(d) = static_cast<uint16_t>(lead_o);
+        *reinterpret_cast<uint32_t*>(d + 2) = lead_m;
+        *reinterpret_cast<uint16_t*>(d + 6) = static_cast<uint16_t>(lead_o >> 16);
+        *reinterpret_cast<uint16_t*>(d + kPlaneBytes) = static_cast<uint16_t>(resid_o);
+        *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 2) = resid_m;
+        *reinterpret_cast<uint16_t*>(d + kPlaneBytes + 6) = static_cast<uint16_t>(resid_o >> 16);
+      }
+    }
     if (im + kConvWaves < img_end) {
       const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(im + kConvWaves) * H * H);
 #pragma unroll
@@ -280,6 +368,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
     wave_sync();
 
+    float acc[NCS];  // the dense layer's partial sums of this lane, per class
+#pragma unroll
+    for (int c = 0; c < NCS; ++c) acc[c] = 0.f;
     zero_band_row(bandb, 0);  // band 0, row 0: the border above the image
     int b3 = 0;               // b mod 3: buffer of band b
 #pragma unroll 1
@@ -287,46 +378,40 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       // ---- conv1 + ReLU + pool, pass b: pooled rows 2b and 2b+1 ----
       if (b == H4) {
         zero_band_row(bandb + (b3 == 0 ? 2 : b3 - 1) * kBandBytes, 3);  // last band, row 3: the border below the image
-      } else if (c1_on) {
-        const int pr = 2 * b + c1_rs;  // pooled row of this lane
-        float v[4] = {0.f, 0.f, 0.f, 0.f};
-        {
-          float p[4][4];
+      } else {
+        const int nxt3 = b3 == 2 ? 0 : b3 + 1, prv3 = b3 == 0 ? 2 : b3 - 1;
+        const floatx4 c_init = {c1_init[0], c1_init[1], c1_init[0], c1_init[1]};
 #pragma unroll
-          for (int dy = 0; dy < 4; ++dy) {
-            const float2* rowp = reinterpret_cast<const float2*>(img + (2 * pr + dy) * kImgW + 2 * c1_wx);
-            const float2 u = rowp[0], w = rowp[1];
-            p[dy][0] = u.x, p[dy][1] = u.y, p[dy][2] = w.x, p[dy][3] = w.y;
-          }
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            float o00 = bias1v[c], o01 = o00, o10 = o00, o11 = o00;
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-              for (int dx = 0; dx < 3; ++dx) {
-                const float wv = w1v[dy * 3 + dx][c];
-                o00 = fmaf(p[dy][dx], wv, o00);
-                o01 = fmaf(p[dy][dx + 1], wv, o01);
-                o10 = fmaf(p[dy + 1][dx], wv, o10);
-                o11 = fmaf(p[dy + 1][dx + 1], wv, o11);
+        for (int m = 0; m < 2; ++m) {
+          if (m < n_mt) {
+            // the lane's eight patch values: two rows of four consecutive fp16 pixels
+            const char* pp = planes + p_off[m] + b * (4 * kPlanePitch);
+            typedef uint32_t u32x4c __attribute__((ext_vector_type(4)));
+            const u32x4c pw = {*reinterpret_cast<const uint32_t*>(pp), *reinterpret_cast<const uint32_t*>(pp + 4),
+                               *reinterpret_cast<const uint32_t*>(pp + kPlanePitch),
+                               *reinterpret_cast<const uint32_t*>(pp + kPlanePitch + 4)};
+            const f16x8 patch = __builtin_bit_cast(f16x8, pw);
+            floatx4 o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][0], patch, c_init, 0, 0, 0);
+            floatx4 o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][0], patch, c_init, 0, 0, 0);
+            o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][1], patch, o0, 0, 0, 0);
+            o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][1], patch, o1, 0, 0, 0);
+            // pooling window of channels 2 q, 2 q + 1: both pixel rows (o0, o1) and both columns (registers i, i + 2)
+            const float v0 = fmaxf(fmaxf(fmaxf(o0[0], o0[2]), fmaxf(o1[0], o1[2])) * c1_out[0], 0.f);  // stored times s_a1
+            const float v1 = fmaxf(fmaxf(fmaxf(o0[1], o0[3]), fmaxf(o1[1], o1[3])) * c1_out[1], 0.f);
+            uint32_t lead, resid;
+            split2_pair(v0, v1, lead, resid);
+            if (c1_valid[m]) {
+              // own band, and the neighbour band that shares the row
+              char* cur = bandb + b3 * kBandBytes + own_off[m];
+              *reinterpret_cast<uint32_t*>(cur) = lead;
+              *reinterpret_cast<uint32_t*>(cur + kBandTerm) = resid;
+              if (c1_lower[m] ? b + 1 < H4 : b >= 1) {
+                char* nxt = bandb + (c1_lower[m] ? nxt3 : prv3) * kBandBytes + nbr_off[m];
+                *reinterpret_cast<uint32_t*>(nxt) = lead;
+                *reinterpret_cast<uint32_t*>(nxt + kBandTerm) = resid;
               }
-            v[c] = fmaxf(fmaxf(fmaxf(o00, o01), fmaxf(o10, o11)) * s_a1, 0.f);  // stored times s_a1
+            }
           }
-        }
-        // two fp16 terms of the four channels: 8 bytes per term
-        uint2 term[2];
-        split2_pair(v[0], v[1], term[0].x, term[1].x);
-        split2_pair(v[2], v[3], term[0].y, term[1].y);
-        // own band, and the neighbour band that shares the row
-        const int nbr3 = c1_rs ? (b3 == 2 ? 0 : b3 + 1) : (b3 == 0 ? 2 : b3 - 1);
-        char* cur = bandb + b3 * kBandBytes + c1_dst_own;
-        char* nxt = bandb + nbr3 * kBandBytes + c1_dst_nbr;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(cur + k * kBandTerm) = term[k];
-        if (c1_rs ? b + 1 < H4 : b >= 1) {
-#pragma unroll
-          for (int k = 0; k < 2; ++k) *reinterpret_cast<uint2*>(nxt + k * kBandTerm) = term[k];
         }
       }
       wave_sync();
@@ -358,26 +443,19 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         acc0[i] = fmaf(low0[i], kSplitLowUnscale, acc0[i]);
         acc1[i] = fmaf(low1[i], kSplitLowUnscale, acc1[i]);
       }
-      // D role: the four registers of lane (q, n) are window q (+4) of channel n
-      if (q < H4)
-        a2[((b - 1) * H4 + q) * kC2 + n] =
-            fmaxf(fmaf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])), u_a2, bias2), 0.f);
-      if (q + 4 < H4)
-        a2[((b - 1) * H4 + q + 4) * kC2 + n] =
-            fmaxf(fmaf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])), u_a2, bias2), 0.f);
+      // D role: the four registers of lane (q, n) are window q (+4) of channel n: two features of the dense
+      // layer, which is accumulated band by band (per lane and class) from the workgroup's copy of its weights
+      {
+        const float x0 = q < H4 ? fmaxf(fmaf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])), u_a2, bias2), 0.f) : 0.f;
+        const float x1 = q + 4 < H4 ? fmaxf(fmaf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])), u_a2, bias2), 0.f) : 0.f;
+        const float* wr0 = wd_s + (((b - 1) * H4 + min(q, H4 - 1)) * kC2 + n) * NCS;
+        const float* wr1 = wd_s + (((b - 1) * H4 + min(q + 4, H4 - 1)) * kC2 + n) * NCS;
+#pragma unroll
+        for (int c = 0; c < NCS; ++c) acc[c] = fmaf(x1, wr1[c], fmaf(x0, wr0[c], acc[c]));
+      }
       wave_sync();
     }
 
-    // ---- dense: lane takes features lane, lane + 64, ... and accumulates every class ---------
-    float acc[NCS];
-#pragma unroll
-    for (int c = 0; c < NCS; ++c) acc[c] = 0.f;
-    for (int f = lane; f < n_feat; f += 64) {
-      const float x = a2[f];
-      const float* wrow = wd_s + f * NCS;
-#pragma unroll
-      for (int c = 0; c < NCS; ++c) acc[c] = fmaf(x, wrow[c], acc[c]);
-    }
     // transpose-reduce through LDS (the band buffers are free now): lane (c, part) adds 16 partials
     float* red = band;
 #pragma unroll
@@ -399,7 +477,6 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     // both scratch uses sat on zero-padded buffers: restore the zeros (the next image's
     // interior is rewritten anyway, the borders must read as zero again)
     for (int i = lane; i < 64 * NCS; i += 64) red[i] = 0.f;
-    for (int i = lane; i < n_feat; i += 64) a2[i] = 0.f;
 
     const int cls = lane & 15;
     if (a.out) {
