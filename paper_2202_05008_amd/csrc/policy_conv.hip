@@ -27,8 +27,9 @@
 // an infinite pixel, gets NaN logits (the maximum operations of ReLU and pooling would otherwise
 // swallow what fp32 arithmetic propagates); a NaN pixel is not detected.
 //
-// conv1 tiling (K = 9, one input channel).  The image sits in LDS as two planes of fp16 terms.  The 16
-// columns of a matrix tile are 16 pooling windows; the contraction runs over the 4 x 4 pixel patch that holds
+// conv1 tiling (K = 9, one input channel).  The image sits in LDS as two planes of fp16 terms (written with
+// aligned 8-byte stores: a lane gets the pixel left of its four from the lane before it).  The 16
+// columns of a matrix tile are 16 pooling windows (8 window columns x the two pooled rows of the pass); the contraction runs over the 4 x 4 pixel patch that holds
 // the 3 x 3 neighbourhoods of the window's four pixels (k = 4 r + c; the lane's eight values are two rows of
 // four consecutive pixels: four 4-byte LDS reads), once against the leading terms of the pixels (lane groups
 // 0, 1) and once against their residual terms (lane groups 2, 3), which fills K = 32.  The 16 rows are
@@ -39,7 +40,10 @@
 // more than 2^17 below the largest of their channel then carry 11 bits, which is below 2^-28 of the channel's
 // activations.)  Row order (channel pair, column, channel parity) puts a window's two columns of channels
 // 2 q, 2 q + 1 into the four accumulator registers of lane group q: pooling is three maxima per channel on
-// registers, and the pooled pair goes to the band buffers as one 4-byte store per term.
+// registers; one swap between neighbouring lane groups and one between the halves of the wave then collect a
+// window's four channel pairs, and the pooled pixel goes to the band buffers as one 16-byte store per term.
+// (LDS counters decided these two layouts: 2-byte stores of the image and 4-byte stores of the channel pairs,
+// at 32 bytes from window to window, cost 14 % and 15 % of the kernel's time in bank and address conflicts.)
 //
 // Band pipeline.  conv2 output row b needs the pooled conv1 rows 2b-1 .. 2b+2 only (rows -1 and
 // H/2 are the zero border), so the conv1 output is never held whole: pass b of conv1 produces the
@@ -66,8 +70,9 @@ constexpr float kFltMax = 3.402823466e+38f;
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
-constexpr int kPlanePitch = 64;                      // bytes of a padded image row of one split term: 30 fp16 pixels in 32 slots
-constexpr int kPlaneBytes = 33 * kPlanePitch;        // 2112: 30 rows + padding that puts the second term 16 banks after the first
+constexpr int kPlanePitch = 80;                      // bytes of a padded image row of one split term (30 fp16 pixels); 20 words, so
+                                                     // that rows 0, 2, 4 of a patch column start 8 of the 32 banks apart
+constexpr int kPlaneBytes = 30 * kPlanePitch;        // 2400
 constexpr int kImgBytes = 2 * kPlaneBytes;           // the padded image as two fp16 terms
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
 constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as fp16
@@ -75,7 +80,7 @@ constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 
 constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
 constexpr int kBandBytes = 2 * kBandTerm;            // 2048 bytes per band buffer
 constexpr int kBandFloats = kBandBytes / 4;          // 512
-constexpr int kWaveFloats = kImgBytes / 4 + 3 * kBandFloats;  // 2592 floats = 10,368 bytes per wave
+constexpr int kWaveFloats = kImgBytes / 4 + 3 * kBandFloats;  // 2736 floats = 10,944 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -252,21 +257,22 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     sw1_d[j] = __shfl(sw1_row, 4 * q + j, 64);
     b1_d[j] = b1[2 * q + j];
   }
-  // patch of window 16 m + n in the image planes (pass 0): term q >> 1, patch rows 2 (q & 1), 2 (q & 1) + 1;
-  // where its pooled pair goes in a band buffer: rows 1, 2 of the band of the pass and row 3 of the band
-  // before (upper pooled row) or row 0 of the band after (lower one)
-  const int n_mt = (H + 15) >> 4;   // tiles of 16 windows per pass (2 H2 = H windows)
+  // Column n of tile m is the window (pooled row 2 b + (n & 1), column 8 m + (n >> 1)): with both pooled rows of the
+  // pass in one tile, the patch reads of 32 lanes and the band stores below fall on different banks.  Patch of
+  // that window in the image planes (pass 0): term q >> 1, patch rows 2 (q & 1), 2 (q & 1) + 1.  Its pooled pixel
+  // goes to a band buffer twice: rows 1, 2 of the band of the pass and row 3 of the band before (upper pooled
+  // row) or row 0 of the band after (lower one); lane groups 0 and 1 store it (leading and residual term).
+  const int n_mt = (H2 + 7) >> 3;   // tiles of 8 window columns x 2 pooled rows per pass
   int p_off[2], own_off[2], nbr_off[2];
-  bool c1_valid[2], c1_lower[2];
+  bool c1_store[2];
+  const bool c1_lower = (n & 1) != 0;
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
-    const int w = 16 * m + n, wc = min(w, H - 1);
-    const int rs = wc / H2, wx = wc - rs * H2;
-    p_off[m] = (q >> 1) * kPlaneBytes + (2 * rs + 2 * (q & 1)) * kPlanePitch + 4 * wx;
-    own_off[m] = band_off(1 + rs, wx + 1) + 4 * q;
-    nbr_off[m] = band_off(rs ? 0 : 3, wx + 1) + 4 * q;
-    c1_valid[m] = w < H;
-    c1_lower[m] = rs != 0;
+    const int wx = 8 * m + (n >> 1), wxc = min(wx, H2 - 1), rs = n & 1;
+    p_off[m] = (q >> 1) * kPlaneBytes + (2 * rs + 2 * (q & 1)) * kPlanePitch + 4 * wxc;
+    own_off[m] = band_off(1 + rs, wxc + 1) + (q & 1) * kBandTerm;
+    nbr_off[m] = band_off(rs ? 0 : 3, wxc + 1) + (q & 1) * kBandTerm;
+    c1_store[m] = wx < H2 && q < 2;
   }
   const bool member_bad = __any(lane_bad);
 
@@ -297,7 +303,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   float loss_sum = 0.f;
 
   // prefetch of the first image: lane takes pieces lane, lane + 64, ...
-  float4 pre[4];
+  float4 pre[4] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f),
+                   make_float4(0.f, 0.f, 0.f, 0.f)};  // pieces beyond the image stay zero
   int im = img_begin + wave;
   if (im < img_end) {
     const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(im) * H * H);
@@ -342,22 +349,30 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       c1_init[j] = b1_d[j] * both;
       c1_out[j] = s_a1 * pow2_reciprocal(both);
     }
+    // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
+    // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
+    // lane 0 the last lane of the previous round), and the last piece of a row adds the row's last pixel.
+    uint32_t last_lead = 0, last_resid = 0;  // lane 63's outer pair of the previous round
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i = lane + 64 * j;
+      const int y = i / row4, x4 = i - y * row4;
+      uint32_t lead_o, resid_o, lead_m, resid_m;
+      split2_pair(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
+      split2_pair(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
+      uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead_o, 0x138, 0xf, 0xf, false);    // wave_shr:1
+      uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid_o, 0x138, 0xf, 0xf, false);
+      last_lead = __builtin_amdgcn_readlane(lead_o, 63);
+      last_resid = __builtin_amdgcn_readlane(resid_o, 63);
+      if (x4 == 0) left_lead = 0, left_resid = 0;  // the border left of the row
       if (i < n_vec) {
-        const int y = i / row4, x4 = i - y * row4;
-        // pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: the middle pair is a four-byte store
-        char* d = planes + (y + 1) * kPlanePitch + 8 * x4 + 2;
-        uint32_t lead_o, resid_o, lead_m, resid_m;
-        split2_pair(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
-        split2_pair(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
-        *reinterpret_cast<uint16_t*>(d) = static_cast<uint16_t>(lead_o);
-        *reinterpret_cast<uint32_t*>(d + 2) = lead_m;
-        *reinterpret_cast<uint16_t*>(d + 6) = static_cast<uint16_t>(lead_o >> 16);
-        *reinterpret_cast<uint16_t*>(d + kPlaneBytes) = static_cast<uint16_t>(resid_o);
-        *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 2) = resid_m;
-        *reinterpret_cast<uint16_t*>(d + kPlaneBytes + 6) = static_cast<uint16_t>(resid_o >> 16);
+        char* d = planes + (y + 1) * kPlanePitch + 8 * x4;
+        *reinterpret_cast<uint2*>(d) = make_uint2((left_lead >> 16) | (lead_o << 16), lead_m);
+        *reinterpret_cast<uint2*>(d + kPlaneBytes) = make_uint2((left_resid >> 16) | (resid_o << 16), resid_m);
+        if (x4 == row4 - 1) {
+          *reinterpret_cast<uint32_t*>(d + 8) = lead_o >> 16;
+          *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 8) = resid_o >> 16;
+        }
       }
     }
     if (im + kConvWaves < img_end) {
@@ -400,16 +415,18 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             const float v1 = fmaxf(fmaxf(fmaxf(o0[1], o0[3]), fmaxf(o1[1], o1[3])) * c1_out[1], 0.f);
             uint32_t lead, resid;
             split2_pair(v0, v1, lead, resid);
-            if (c1_valid[m]) {
+            // the four channel pairs of a window (lane groups 0..3) -> the 16 bytes of its pixel, leading term in
+            // lane group 0 and residual term in lane group 1: one swap between neighbouring groups, then the
+            // upper half of the wave moves down
+            const auto sw = __builtin_amdgcn_permlane16_swap(lead, resid, false, false);   // (L0 R0 L2 R2), (L1 R1 L3 R3)
+            const uint32_t t2 = __builtin_amdgcn_permlane32_swap(sw[0], sw[0], false, false)[1];  // groups 0, 1: L2, R2
+            const uint32_t t3 = __builtin_amdgcn_permlane32_swap(sw[1], sw[1], false, false)[1];  // groups 0, 1: L3, R3
+            if (c1_store[m]) {
+              const uint4 pixel = make_uint4(sw[0], sw[1], t2, t3);
               // own band, and the neighbour band that shares the row
-              char* cur = bandb + b3 * kBandBytes + own_off[m];
-              *reinterpret_cast<uint32_t*>(cur) = lead;
-              *reinterpret_cast<uint32_t*>(cur + kBandTerm) = resid;
-              if (c1_lower[m] ? b + 1 < H4 : b >= 1) {
-                char* nxt = bandb + (c1_lower[m] ? nxt3 : prv3) * kBandBytes + nbr_off[m];
-                *reinterpret_cast<uint32_t*>(nxt) = lead;
-                *reinterpret_cast<uint32_t*>(nxt + kBandTerm) = resid;
-              }
+              *reinterpret_cast<uint4*>(bandb + b3 * kBandBytes + own_off[m]) = pixel;
+              if (c1_lower ? b + 1 < H4 : b >= 1)
+                *reinterpret_cast<uint4*>(bandb + (c1_lower ? nxt3 : prv3) * kBandBytes + nbr_off[m]) = pixel;
             }
           }
         }
