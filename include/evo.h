@@ -193,7 +193,7 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      conv3x3 (zero-padded, stride 1) -> ReLU -> maxpool 2x2/2, twice, then a dense layer.
  *      Flat parameters: W1[3][3][1][c1], b1[c1], W2[3][3][c1][c2], b2[c2],
  *      Wd[(H/4)(H/4)c2][n_cls], bd[n_cls]; dense input flattened (h, w, c), c fastest.
- *      fp32 results for any finite weights and pixels (the second convolution is evaluated on 16-bit
+ *      fp32 results for any finite weights and pixels (the convolutions are evaluated on 16-bit
  *      matrix instructions with two-term operand splits whose scales are set at run time); a member
  *      with a non-finite convolution weight, or an image with an infinite pixel, gets NaN logits (a NaN
  *      pixel is not detected: ReLU and pooling are maximum operations, which drop it).

@@ -37,11 +37,14 @@ _VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
 FILE_FLAGS = {"policy_bf16.hip": _VGPR_FORM, "task_cartpole.hip": _VGPR_FORM, "probe.hip": _VGPR_FORM}
 
 
-def _compile(src):
-    obj = os.path.join(BUILD, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
+def _compile(src, build_dir=BUILD, extra_flags=()):
+    obj = os.path.join(build_dir, os.path.basename(src) + ".o")
+    cmd = [HIPCC, *FLAGS, *extra_flags, *FILE_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
     if src.endswith(".cpp"):
         cmd[1:1] = ["-x", "hip"]
+    if src.endswith(".c"):      # a plain C caller of the C ABI: host compiler only
+        cmd = [HIPCC, "-x", "c", "-O1", "-g", *extra_flags, "-I", os.path.join(os.path.dirname(HERE), "include"),
+               "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s\n%s" % (src, r.stdout, r.stderr))
@@ -70,6 +73,28 @@ def build(verbose=True, jobs=8):
     if verbose:
         print("built %s from %d sources" % (LIB, len(srcs)))
     return LIB
+
+
+# Host-side sanitizers (the device code is compiled as always): every -fsanitize= goes to the host pass only.
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_checked_executable(driver_c, out, build_dir, jobs=8):
+    """The library's sources plus one C driver, host code under AddressSanitizer and UndefinedBehaviorSanitizer,
+    linked into the executable `out` (used by the CPU tests; no GPU needed to build or to run the host paths)."""
+    os.makedirs(build_dir, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = [o for o, _ in ex.map(lambda s: _compile(s, build_dir, HOST_SANITIZE), srcs)]
+    drv, _ = _compile(driver_c, build_dir, ["-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+                                            "-fno-sanitize-recover=undefined"])
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+                        "-o", out, drv, *objs],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return out
 
 
 if __name__ == "__main__":
