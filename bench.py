@@ -36,7 +36,7 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # box FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Sources: the summaries under profiles/.  Counters cannot be
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1": 2876815,       # profiles/mlp_f32_kernel_cfg1.md
+    "cfg1": 2924945,       # profiles/mlp_f32_kernel_cfg1.md
     "cfg2": 33418606,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
     "cfg3": 19117871,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md
@@ -369,6 +369,13 @@ def _run_workload(name, args, steps, warmup, torch):
         td = wl["task"](t)
         if timed:
             ev[0].record()
+        if args.variant == "fused" and name == "cfg1":      # the whole generation in one launch: timed as the ask stage
+            pg.generation_step(args.seed, c.pop, td, wl["pd"], wl["fitness"])
+            if timed:
+                for e in ev[1:]:
+                    e.record()
+                events.append(ev)
+            return
         if args.variant == "fused":      # one call stands for ask + rollout: the rollout stage reads 0
             if name == "cfg4":
                 pg.ask_rollout(args.seed, c.pop, td, wl["pd"], wl["fitness"])
@@ -459,11 +466,16 @@ def _run_workload(name, args, steps, warmup, torch):
         out["config"]["batch_override"] = args.batch
         out["roofline"]["traffic"] = None
     if args.variant != "materialised":
-        out["config"]["generation"] = {"fused": ("ask_rollout" if name == "cfg4" else "ask_sphere") +
+        out["config"]["generation"] = {"fused": "pgpe_generation: ask, evaluation, ranks and tell in one launch" if name == "cfg1" else
+                                                ("ask_rollout" if name == "cfg4" else "ask_sphere") +
                                                 " (ask + fitness in one kernel, no population) -> tell",
                                        "stored": "ask -> rollout -> tell_stored"}[args.variant]
         out["roofline"]["traffic"] = None
-        if args.variant == "fused":      # no population is written: the stage is bound by the noise generation
+        if args.variant == "fused" and name == "cfg1":
+            out["roofline"]["kernel"] = "generation_small_kernel"
+            out["roofline"]["kernel_ms"] = dom_ms
+            out["roofline"]["bound_detail"] = "launch latency: one launch whose update workgroups wait for the evaluation"
+        elif args.variant == "fused":      # no population is written: the stage is bound by the noise generation
             normals = c.pop / 2 * c.P
             out["roofline"] = {"bound": "alu", "achieved": normals / (dom_ms * 1e-3) / 1e9, "peak": None,
                                "unit": "Gnormal/s", "frac": None, "traffic": None,
@@ -493,7 +505,7 @@ def main():
                     help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
     ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
                     help="cfg5: 'fused' = ask fused with the sphere fitness (no population in memory), 'stored' = tell "
-                         "reads the perturbations back from the stored population; cfg4: 'fused' = ask fused into the forward")
+                         "reads the perturbations back from the stored population; cfg4: 'fused' = ask fused into the forward; cfg1: 'fused' = the whole generation in one launch")
     ap.add_argument("--graph", action="store_true",
                     help="replay each generation from a recorded HIP graph (generation index kept on the device); "
                          "the per-stage times then come from an untimed pass of direct calls before the replays")
@@ -508,8 +520,8 @@ def main():
     all_configs = args.workload is None and args.batch is None and args.variant == "materialised" and not args.graph
     if args.batch is not None and headline != "cfg4":
         raise SystemExit("--batch applies to --workload cfg4 only")
-    if args.variant != "materialised" and not (headline == "cfg5" or (headline == "cfg4" and args.variant == "fused")):
-        raise SystemExit("--variant applies to --workload cfg5 (fused, stored) and cfg4 (fused) only")
+    if args.variant != "materialised" and not (headline == "cfg5" or (headline in ("cfg1", "cfg4") and args.variant == "fused")):
+        raise SystemExit("--variant applies to --workload cfg5 (fused, stored) and cfg1, cfg4 (fused) only")
     # the oracle first: its all-cores leg forks worker processes, which must happen before the GPU is initialised
     cpu = None
     if not args.no_cpu_baseline and args.batch is None and args.variant == "materialised":
@@ -533,6 +545,11 @@ def main():
             per[name] = {"workload": r["config"]["workload"], "ms_per_generation": r["ms_per_step"], "steps": r["steps"],
                          "value": r["value"], "unit": r["unit"], "dtype": r["dtype"], "stage_ms": r["stage_ms"],
                          "roofline": r["roofline"]}
+            if name == "cfg1":      # the same generation as one launch
+                fa = argparse.Namespace(**{**vars(args), "variant": "fused"})
+                r = _run_workload(name, fa, DEFAULT_STEPS[name], args.warmup, torch)
+                per[name]["one_launch"] = {"ms_per_generation": r["ms_per_step"], "value": r["value"],
+                                           "generation": r["config"]["generation"]}
             if name == "cfg4":      # the same generation with ask fused into the forward (no population in memory)
                 fa = argparse.Namespace(**{**vars(args), "variant": "fused"})
                 r = _run_workload(name, fa, DEFAULT_STEPS[name], args.warmup, torch)

@@ -316,6 +316,20 @@ int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, 
 int pgpe_ask_rollout(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc* td, const policy_desc* pd,
                      float* fitness_dev, void* stream);
 
+/* One whole generation -- ask, evaluation, ranks, tell (Section 4's ask / tell around Section 2's evaluation of the
+ * population) -- in ONE launch, for problems so small that five launches of a few microseconds each are what a
+ * generation costs: the supervised tasks EVO_TASK_CLASSIFY / EVO_TASK_REGRESS of an fp32 MLP whose fan-ins are all
+ * below 64, at most 8192 parameters, optimizer Adam or momentum.  fitness_dev[pop] and the state (mu, sigma, moments,
+ * t) end up bit for bit as pgpe_ask, rollout(td, pd, ...) and pgpe_tell would leave them; the population itself is
+ * never stored (each workgroup draws its member's parameters into LDS).  td->work_dev is not used (the loss sums
+ * go through the state's workspace; at most 4096 (member, tile of 64 samples) pairs).  Inside the kernel the
+ * workgroups that update mu and sigma wait, with a bounded spin, until every workgroup has handed over its loss
+ * sum; all others exit, so the wait always ends.
+ * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED (any other task, policy, optimizer or size: use the three calls),
+ * EVO_ERR_HIP. */
+int pgpe_generation(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc* td, const policy_desc* pd,
+                    float* fitness_dev, void* stream);
+
 /* rollout for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): the same evaluation, by the same kernels, as rollout, but the
  * workspace is a fixed array inside the library's device image (EVO_STATIC_SCRATCH_BYTES per GPU, held until

@@ -57,6 +57,8 @@ _SIGNATURES = {
     "pgpe_ask_sphere": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "pgpe_ask_rollout": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.POINTER(task_desc), C.POINTER(policy_desc),
                                    C.c_void_p, C.c_void_p]),
+    "pgpe_generation": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.POINTER(task_desc), C.POINTER(policy_desc),
+                                  C.c_void_p, C.c_void_p]),
     "evo_ask_forward": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int32, C.POINTER(policy_desc), C.c_void_p, C.c_int64,
                                   C.c_void_p, C.c_int32, C.c_void_p]),
     "pgpe_tell_stored": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),

@@ -179,6 +179,10 @@ def pgpe_ask_rollout(h, seed, pop, td, pd, fitness):
     _check(_lib.load().pgpe_ask_rollout(h, seed, pop, C.byref(td), C.byref(pd), _ptr(fitness, torch.float32), _stream()))
 
 
+def pgpe_generation(h, seed, pop, td, pd, fitness):
+    _check(_lib.load().pgpe_generation(h, seed, pop, C.byref(td), C.byref(pd), _ptr(fitness, torch.float32), _stream()))
+
+
 def evo_ask_forward(h, seed, pop, pd, obs, obs_member_stride, out, B):
     _check(_lib.load().evo_ask_forward(h, seed, pop, C.byref(pd), _ptr(obs, torch.float32), obs_member_stride,
                                        _ptr(out, torch.float32), B, _stream()))
@@ -314,6 +318,10 @@ class PGPE:
 
     def ask_rollout(self, seed, pop, td, pd, fitness):
         pgpe_ask_rollout(self.handle, seed, pop, td, pd, fitness)
+
+    def generation_step(self, seed, pop, td, pd, fitness):
+        """ask, evaluation and tell in one launch (small supervised problems; EvoError otherwise)."""
+        pgpe_generation(self.handle, seed, pop, td, pd, fitness)
 
     def tell_stored(self, fitness, params):
         pgpe_tell_stored(self.handle, fitness, params)

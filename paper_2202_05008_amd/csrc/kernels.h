@@ -50,6 +50,12 @@ int pgpe_view(const pgpe_state* st, PgpeView* out);
 int pgpe_check_ask(const pgpe_state* st, int32_t pop, const char* who);
 void pgpe_note_ask(pgpe_state* st, uint64_t seed, int32_t pop);
 
+// ask -> forward + loss -> ranks -> tell of an fp32 MLP on a supervised task in one launch (small problems only:
+// EVO_ERR_UNSUPPORTED otherwise); the loss sums go through the state's own workspace.
+int pgpe_generation_small(pgpe_state* st, uint64_t seed, int32_t pop, const MlpShape& sh, const float* obs,
+                          int64_t obs_stride, int B, int loss, const void* target, float scale, float* fitness,
+                          hipStream_t s);
+
 // fp32 ConvNet; images shared by all members.  Partials per (member, chunk).
 int convnet_supported(const ConvShape& sh);
 int convnet_chunks(const ConvShape& sh, int pop, int B);

@@ -8,6 +8,7 @@
 // rank-weighted sums in registers / LDS in a fixed order and applies the optimizer in the
 // same kernel, so mu, sigma and the moments are read and written exactly once.
 #include "kernels.h"
+#include "mlp_f32_body.h"
 #include "philox.h"
 #include "bf16.h"
 
@@ -28,6 +29,7 @@ struct pgpe_state {
   bool pending;
   uint64_t seed;
   int32_t pop;
+  bool tickets_ready;  // the two counters of the one-launch generation have been cleared
 };
 
 namespace evo {
@@ -45,7 +47,8 @@ struct Workspace {
 static inline size_t ws_arrays_bytes(int pop_max) {
   return ((static_cast<size_t>(pop_max) * 2 + 2 * kNormBlocks) * 4 + 255) & ~size_t(255);
 }
-static inline size_t ws_bytes(int pop_max) { return ws_arrays_bytes(pop_max) + 256; }
+constexpr int kSmallSumWords = 2 * 4096;  // the two arrays of loss sums of the one-launch generation
+static inline size_t ws_bytes(int pop_max) { return ws_arrays_bytes(pop_max) + 256 + 4 * kSmallSumWords; }
 
 static inline Workspace ws_carve(void* base, int pop_max) {
   Workspace w;
@@ -266,15 +269,12 @@ __device__ __forceinline__ uint32_t orderable(float f) {
 constexpr int kRankThreads = 256;
 constexpr int kRankMembers = 16;
 
-__global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int shaping,
-                                                            uint32_t* __restrict__ rank_out,
-                                                            float* __restrict__ shaped_out) {
-  __shared__ uint32_t ord[EVO_POP_MAX];
+// The members of one block of sixteen: ord holds the orderable words of the whole population (LDS).
+__device__ __forceinline__ void rank_members(const uint32_t* ord, const float* fitness, int pop, int shaping, int block,
+                                             uint32_t* rank_out, float* shaped_out) {
   const int tid = threadIdx.x;
-  for (int i = tid; i < pop; i += kRankThreads) ord[i] = orderable(fitness[i]);
-  __syncthreads();
   const int part = tid & 15;
-  const int m = blockIdx.x * kRankMembers + (tid >> 4);
+  const int m = block * kRankMembers + (tid >> 4);
   const int mc = min(m, pop - 1);
   const uint64_t key_m = (static_cast<uint64_t>(ord[mc]) << 32) | static_cast<uint32_t>(mc);
   uint32_t count = 0;
@@ -296,6 +296,16 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restr
       shaped_out[m] = shaping ? c : fitness[m];
     }
   }
+}
+
+__global__ __launch_bounds__(kRankThreads) void rank_kernel(const float* __restrict__ fitness, int pop, int shaping,
+                                                            uint32_t* __restrict__ rank_out,
+                                                            float* __restrict__ shaped_out) {
+  __shared__ uint32_t ord[EVO_POP_MAX];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < pop; i += kRankThreads) ord[i] = orderable(fitness[i]);
+  __syncthreads();
+  rank_members(ord, fitness, pop, shaping, blockIdx.x, rank_out, shaped_out);
 }
 
 // ---- tell --------------------------------------------------------------------------------
@@ -331,8 +341,7 @@ __device__ __forceinline__ float adam_step(float x, float g, float& m, float& v,
 // (sums of w eps and u (eps^2 - sigma^2)) instead of being regenerated (sums of w z and u (z^2 - 1)).
 enum { OPT_ADAM = 0, OPT_CLIPUP_GRAD = 1, OPT_MOMENTUM = 2, OPT_GRAD = 3 };
 template <int OPT, int SRULE, bool STORED>
-__global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void tell_block(TellArgs a, int block, float* smem) {
   float* w_s = smem;
   float* u_s = smem + a.N;
   float* part = smem + 2 * a.N;  // [KS][QPB][8] when KS > 1
@@ -346,7 +355,7 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
   const int QPB = 256 / a.KS;
   const int ql = tid % QPB;
   const int ks = tid / QPB;
-  const int q = blockIdx.x * QPB + ql;
+  const int q = block * QPB + ql;
   // pair weights from the utilities: b = mean(c) in fp64 with a fixed tree (every workgroup
   // computes the same bits), w_k = (c[2k] - c[2k+1]) / 2, u_k = (c[2k] + c[2k+1]) / 2 - b
   {
@@ -465,6 +474,163 @@ __global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
       a.sigma[c] = fmaxf(adam_step(sg, g_sg, ms, vs, a.lr_sigma, a), 1e-8f);
       a.ms[c] = ms;
       a.vs[c] = vs;
+    }
+  }
+}
+
+template <int OPT, int SRULE, bool STORED>
+__global__ __launch_bounds__(256) void tell_kernel(TellArgs a) {
+  extern __shared__ float smem[];
+  tell_block<OPT, SRULE, STORED>(a, blockIdx.x, smem);
+}
+
+// ---- one whole generation in one launch (small problems) ----------------------------------------------------
+// ask -> forward + loss -> fitness -> ranks -> tell for problems whose five launches are bound by launch latency
+// (Section 2's loop of ask, evaluate, tell at cfg1's size).  Workgroup (tile, member): draws the member's parameters
+// into LDS exactly as ask_kernel would store them, runs mlp_f32_body on its tile of samples and hands the tile's
+// loss sum over.  The first n_tell workgroups then wait for every tile's sum (every other workgroup exits, so those
+// that wait cannot keep anyone from arriving; the wait is bounded), form every member's fitness and utility in LDS
+// with the arithmetic of finalize_kernel and rank_kernel and run tell_block for their block of parameters: the
+// same bits as the five launches give.  mu and sigma are first written after every workgroup has read them.
+//
+// The hand-over has no counter and no fence: on this chip a release at device scope writes a die's cache back
+// (measured: 5 us from the end of the forward to the counted arrival, 13 us until 512 arrivals had been seen).
+// The sums themselves are the flags.  There are two arrays of them, used by even and odd generations; a word
+// holds kNotYet until its workgroup stores its sum with one device-scope store, the waiting workgroups poll the
+// words with device-scope loads, and every workgroup re-arms its word of the OTHER array, which the previous
+// launch has finished with and the next one will use.  (A sum that happened to have kNotYet's bits, one pattern
+// among the NaNs, is stored as the default NaN.)
+struct GenSmallArgs {
+  MlpArgs mlp;       // params and partial unused: the parameters are drawn here, the sums go through `sums`
+  TellArgs tell;     // shaped unused: the utilities are formed here
+  float* fitness;    // [pop] out
+  float scale;       // fitness = scale * sum of the member's loss sums
+  uint32_t* sums;    // [2][kSmallMaxTiles] loss sums of (member, tile) as bit patterns, by parity of the generation
+  uint32_t* done;    // waiting workgroups that have finished (the last one clears it and advances gen_rw)
+  uint32_t* gen_rw;  // the device copy of t, or null
+  int pop, shaping, n_tell, total;
+};
+constexpr int kSmallMaxTiles = 4096;       // (member, tile) pairs of one launch
+constexpr uint32_t kNotYet = 0x7fc5a5a5u;  // a quiet NaN that no arithmetic produces
+constexpr int kSmallSpinLimit = 1 << 21;   // polls of about a microsecond: a sum that has not come by then never will
+typedef __attribute__((address_space(3))) const float* lds_cfloat_ptr;
+
+template <int LOSS, int OPT, int SRULE>
+__global__ __launch_bounds__(256) void generation_small_kernel(GenSmallArgs g) {
+  extern __shared__ __attribute__((aligned(16))) float gs_smem[];
+  __shared__ int missing;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int member = blockIdx.y, tile = blockIdx.x;
+  const int wg = member * gridDim.x + tile;
+  const int P = g.tell.P, nquads = g.tell.nquads;
+  const uint32_t gen = g.tell.gen_dev ? *g.tell.gen_dev : g.tell.gen;
+  uint32_t* mine = g.sums + (gen & 1u) * kSmallMaxTiles;
+  if (tid == 0) {
+    missing = 0;
+    __hip_atomic_store(g.sums + ((gen & 1u) ^ 1u) * kSmallMaxTiles + wg, kNotYet, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // ---- ask: this member's row, as ask_kernel forms it ----
+  {
+    const float sign = (member & 1) ? -1.0f : 1.0f;
+    for (int q = tid; q < nquads; q += 256) {
+      const int col = q * 4;
+      float mu4[4], sg4[4];
+      if (col + 3 < P) {
+        const float4 a = *reinterpret_cast<const float4*>(g.tell.mu + col);
+        const float4 b = *reinterpret_cast<const float4*>(g.tell.sigma + col);
+        mu4[0] = a.x, mu4[1] = a.y, mu4[2] = a.z, mu4[3] = a.w;
+        sg4[0] = b.x, sg4[1] = b.y, sg4[2] = b.z, sg4[3] = b.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          mu4[i] = col + i < P ? g.tell.mu[col + i] : 0.f;
+          sg4[i] = col + i < P ? g.tell.sigma[col + i] : 0.f;
+        }
+      }
+      float z[4];
+      philox_normal4(static_cast<uint32_t>(q), static_cast<uint32_t>(member >> 1), gen, EVO_TAG_NOISE, g.tell.key0,
+                     g.tell.key1, z);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) gs_smem[col + i] = fmaf(sign * sg4[i], z[i], mu4[i]);
+    }
+  }
+  __syncthreads();
+  // ---- forward and loss of this tile; thread 0 holds the tile's sum and hands it over ----
+  float* mlp_lds = gs_smem + 4 * nquads;
+  const float tile_loss = mlp_f32_body<LOSS>(g.mlp, (lds_cfloat_ptr)gs_smem, member, tile, mlp_lds);
+  if (tid == 0) {
+    uint32_t bits = __float_as_uint(tile_loss);
+    if (bits == kNotYet) bits = 0x7fc00000u;
+    __hip_atomic_store(mine + wg, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (wg >= g.n_tell) return;
+  __syncthreads();  // the tile's LDS is free
+  // ---- every tile's sum, polled into LDS ----
+  float* fit_s = gs_smem;
+  float* shaped_s = fit_s + g.pop;
+  uint32_t* ord_s = reinterpret_cast<uint32_t*>(shaped_s + g.pop);
+  float* part_s = reinterpret_cast<float*>(ord_s + g.pop);
+  float* tell_smem = part_s + g.total;
+  for (int i = tid; i < g.total; i += 256) {
+    uint32_t bits = __hip_atomic_load(mine + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int polls = 0; bits == kNotYet && polls < kSmallSpinLimit; ++polls) {
+      __builtin_amdgcn_s_sleep(2);
+      bits = __hip_atomic_load(mine + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (bits == kNotYet) missing = 1;
+    part_s[i] = __uint_as_float(bits);
+  }
+  __syncthreads();
+  if (missing) {  // never seen; the fitness says so rather than a silent wrong update
+    if (wg == 0 && tid == 0) g.fitness[0] = __builtin_nanf("");
+    return;
+  }
+  // ---- fitness, orderable words and utilities of every member, in LDS ----
+  // finalize_kernel's sum per member: lane j takes tiles j, j + 64, ..., then the fixed butterfly over the 64 lanes.
+  // With at most 16 tiles the butterfly's first two levels add the zeros of lanes 16..63 (x + 0 = x, and a sum of
+  // per-sample losses is never -0), so four members share a wave, sixteen lanes each, and take the last four levels.
+  const int tiles = g.mlp.tiles;
+  if (tiles <= 16) {
+    const int sub = lane >> 4, j = lane & 15;
+    for (int m0 = 4 * wave; m0 < g.pop; m0 += 16) {
+      const int m = m0 + sub;
+      float acc = (m < g.pop && j < tiles) ? part_s[m * tiles + j] : 0.f;
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (j == 0 && m < g.pop) {
+        const float f = g.scale * acc;
+        fit_s[m] = f;
+        if (wg == 0) g.fitness[m] = f;
+      }
+    }
+  } else {
+    for (int m = wave; m < g.pop; m += 4) {
+      float acc = 0.f;
+      for (int j = lane; j < tiles; j += 64) acc += part_s[m * tiles + j];
+      acc = wave_sum(acc);
+      if (lane == 0) {
+        const float f = g.scale * acc;
+        fit_s[m] = f;
+        if (wg == 0) g.fitness[m] = f;
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < g.pop; i += 256) ord_s[i] = orderable(fit_s[i]);
+  __syncthreads();
+  for (int blk = 0; blk * kRankMembers < g.pop; ++blk) rank_members(ord_s, fit_s, g.pop, g.shaping, blk, nullptr, shaped_s);
+  __syncthreads();
+  // ---- tell for this workgroup's block of parameters ----
+  TellArgs a = g.tell;
+  a.shaped = shaped_s;
+  tell_block<OPT, SRULE, false>(a, wg, tell_smem);
+  if (g.gen_rw == nullptr) return;
+  __syncthreads();
+  if (tid == 0) {  // t on the device: the last of the waiting workgroups to finish advances it
+    if (atomicAdd(g.done, 1u) == static_cast<uint32_t>(g.n_tell - 1)) {
+      *g.done = 0u;
+      *g.gen_rw += 1u;
     }
   }
 }
@@ -665,14 +831,13 @@ static int advance_generation(pgpe_state* st, hipStream_t s) {
   return check_launch("generation_kernel");
 }
 
-// Shared by pgpe_tell, pgpe_tell_stored and the gradient hook (theta: stored population or null).
-static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, const float* theta,
-                    hipStream_t s) {
+// The arguments of the tell kernels for the pending ask (theta: stored population or null), the number of
+// workgroups and their dynamic LDS.
+static TellArgs tell_args(const pgpe_state* st, float* gmu, float* gsg, const float* theta, unsigned* blocks_out,
+                          size_t* shmem_out) {
   const pgpe_config& c = st->cfg;
-  const int pop = st->pop, N = pop / 2, P = c.P;
+  const int N = st->pop / 2, P = c.P;
   Workspace ws = ws_carve(st->work, c.pop_max);
-  int rc = launch_rank(fitness, pop, c.shaping, ws.rank, ws.shaped, s);
-  if (rc) return rc;
   TellArgs a;
   a.mu = st->mu, a.sigma = st->sigma, a.m = st->m, a.v = st->v;
   a.ms = st->aux, a.vs = st->aux ? st->aux + P : nullptr;
@@ -695,8 +860,22 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   a.bc1 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta1), static_cast<double>(st->t))));
   a.bc2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(c.beta2), static_cast<double>(st->t))));
   const int QPB = 256 / KS;
-  const unsigned blocks = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
-  const size_t shmem = sizeof(float) * (2 * static_cast<size_t>(N) + 256 * 8);  // w, u, partial sums / mean tree
+  *blocks_out = static_cast<unsigned>((a.nquads + QPB - 1) / QPB);
+  *shmem_out = sizeof(float) * (2 * static_cast<size_t>(N) + 256 * 8);  // w, u, partial sums / mean tree
+  return a;
+}
+
+// Shared by pgpe_tell, pgpe_tell_stored and the gradient hook (theta: stored population or null).
+static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg, const float* theta,
+                    hipStream_t s) {
+  const pgpe_config& c = st->cfg;
+  const int pop = st->pop, P = c.P;
+  Workspace ws = ws_carve(st->work, c.pop_max);
+  int rc = launch_rank(fitness, pop, c.shaping, ws.rank, ws.shaped, s);
+  if (rc) return rc;
+  unsigned blocks;
+  size_t shmem;
+  const TellArgs a = tell_args(st, gmu, gsg, theta, &blocks, &shmem);
 #define EVO_TELL(OPTV, SRV)                                                                          \
   do {                                                                                               \
     if (theta) hipLaunchKernelGGL((tell_kernel<OPTV, SRV, true>), dim3(blocks), dim3(256), shmem, s, a); \
@@ -726,6 +905,89 @@ static int run_tell(pgpe_state* st, const float* fitness, float* gmu, float* gsg
   return check_launch("clipup kernels");
 }
 
+// One generation in one launch (see generation_small_kernel).  The caller has validated the task; this checks what
+// the kernel itself needs and leaves the state as pgpe_ask followed by pgpe_tell would.
+int pgpe_generation_small(pgpe_state* st, uint64_t seed, int32_t pop, const MlpShape& sh, const float* obs,
+                          int64_t obs_stride, int B, int loss, const void* target, float scale, float* fitness,
+                          hipStream_t s) {
+  EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_generation: state is null");
+  int rc = check_ask_pop(st, pop, "pgpe_generation");
+  if (rc) return rc;
+  const pgpe_config& c = st->cfg;
+  EVO_REQUIRE(sh.P == c.P, EVO_ERR_ARG, "pgpe_generation: the policy has %d parameters, the state %d", sh.P, c.P);
+  EVO_REQUIRE(c.optimizer != EVO_OPT_CLIPUP, EVO_ERR_UNSUPPORTED,
+              "pgpe_generation: ClipUp needs norms over all parameters between its steps (use ask, rollout, tell)");
+  EVO_REQUIRE(c.P <= 8192 && sh.max_width <= 256, EVO_ERR_UNSUPPORTED,
+              "pgpe_generation: at most 8192 parameters and widths up to 256 (got P = %d, width %d)", c.P, sh.max_width);
+  const uint64_t seed_before = st->seed;
+  const int32_t pop_before = st->pop;
+  st->seed = seed, st->pop = pop;  // what tell_args reads
+  GenSmallArgs g;
+  unsigned n_tell;
+  size_t tell_shmem;
+  g.tell = tell_args(st, nullptr, nullptr, nullptr, &n_tell, &tell_shmem);
+  g.mlp.sh = sh, g.mlp.params = nullptr, g.mlp.obs = obs, g.mlp.obs_stride = obs_stride, g.mlp.B = B;
+  g.mlp.out = nullptr, g.mlp.target = target, g.mlp.partial = nullptr;
+  g.mlp.tiles = (B + kMlpTile - 1) / kMlpTile, g.mlp.ldw = sh.max_width, g.mlp.pop = pop;
+  const long total = static_cast<long>(pop) * g.mlp.tiles;
+  const size_t lds_a = sizeof(float) * (4 * static_cast<size_t>(g.tell.nquads) + 2 * static_cast<size_t>(g.mlp.ldw) * kMlpTile);
+  const size_t lds_c = sizeof(float) * (3 * static_cast<size_t>(pop) + static_cast<size_t>(total)) + tell_shmem;
+  const size_t lds = lds_a > lds_c ? lds_a : lds_c;
+  if (!(n_tell <= 128 && static_cast<long>(n_tell) <= total && total <= kSmallMaxTiles && lds <= 160 * 1024 - 64)) {
+    st->seed = seed_before, st->pop = pop_before;
+    EVO_REQUIRE(false, EVO_ERR_UNSUPPORTED,
+                "pgpe_generation: %u update workgroups for %ld evaluation workgroups, %zu bytes of LDS: not a small problem",
+                n_tell, total, lds);
+  }
+  static_assert(kSmallSumWords == 2 * kSmallMaxTiles, "two arrays of sums");
+  Workspace ws = ws_carve(st->work, c.pop_max);
+  g.done = ws.gen + 16;  // inside the 256 bytes kept for the generation word
+  g.sums = ws.gen + 64;  // behind them
+  if (!st->tickets_ready) {  // once per state: nothing has arrived, nobody has finished
+    rc = fill(reinterpret_cast<float*>(g.done), 1, 0.f, s);
+    float not_yet;  // the bit pattern as a float (moved, never computed with)
+    const uint32_t not_yet_bits = kNotYet;
+    memcpy(&not_yet, &not_yet_bits, sizeof(not_yet));
+    if (!rc) rc = fill(reinterpret_cast<float*>(g.sums), kSmallSumWords, not_yet, s);
+    if (rc) return rc;
+    st->tickets_ready = true;
+  }
+  g.fitness = fitness, g.scale = scale;
+  g.gen_rw = st->device_t ? ws.gen : nullptr;
+  g.pop = pop, g.shaping = c.shaping, g.n_tell = static_cast<int>(n_tell), g.total = static_cast<int>(total);
+  const dim3 grid(g.mlp.tiles, pop);
+#define EVO_GEN(LOSSV, OPTV, SRV)                                                                               \
+  do {                                                                                                          \
+    auto kern = generation_small_kernel<LOSSV, OPTV, SRV>;                                                      \
+    if (lds > 64 * 1024) {                                                                                      \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));    \
+      if (e != hipSuccess) (void)hipGetLastError();                                                             \
+      EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));        \
+    }                                                                                                           \
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, g);                                                       \
+  } while (0)
+#define EVO_GEN_OPT(LOSSV)                                                                 \
+  do {                                                                                     \
+    if (c.optimizer == EVO_OPT_ADAM) {                                                     \
+      if (c.sigma_rule == 0) EVO_GEN(LOSSV, OPT_ADAM, 0);                                  \
+      else EVO_GEN(LOSSV, OPT_ADAM, 1);                                                    \
+    } else {                                                                               \
+      if (c.sigma_rule == 0) EVO_GEN(LOSSV, OPT_MOMENTUM, 0);                              \
+      else EVO_GEN(LOSSV, OPT_MOMENTUM, 1);                                                \
+    }                                                                                      \
+  } while (0)
+  if (loss == LOSS_CE) EVO_GEN_OPT(LOSS_CE);
+  else EVO_GEN_OPT(LOSS_MSE);
+#undef EVO_GEN_OPT
+#undef EVO_GEN
+  rc = check_launch("generation_small_kernel");
+  if (rc) return rc;
+  st->pending = false;  // asked and told
+  st->t += 1;           // the device copy, if any, was advanced by the kernel
+  return EVO_OK;
+}
+
 }  // namespace evo
 
 using namespace evo;
@@ -752,7 +1014,7 @@ extern "C" int pgpe_create(pgpe_state** out, const pgpe_config* cfg, float* mu_d
   EVO_REQUIRE(st != nullptr, EVO_ERR_ARG, "pgpe_create: out of host memory");
   st->cfg = *cfg;
   st->mu = mu_dev, st->sigma = sigma_dev, st->m = m_dev, st->v = v_dev, st->aux = aux_dev, st->work = work_dev;
-  st->t = 1, st->device_t = false, st->pending = false, st->seed = 0, st->pop = 0;
+  st->t = 1, st->device_t = false, st->pending = false, st->seed = 0, st->pop = 0, st->tickets_ready = false;
   *out = st;
   return EVO_OK;
 }

@@ -14,125 +14,15 @@
 // splits (split16.h), three v_mfma_f32_16x16x32_f16 per product, fp32 accumulation, results within a few
 // 1e-7 of fp32 arithmetic.
 #include "kernels.h"
+#include "mlp_f32_body.h"
 #include "split16.h"
 
 namespace evo {
 
-struct MlpArgs {
-  MlpShape sh;
-  const float* params;
-  const float* obs;
-  int64_t obs_stride;
-  int B;
-  float* out;
-  const void* target;
-  float* partial;
-  int tiles;
-  int ldw;  // LDS row capacity (max width)
-  int pop;
-};
-
-__device__ __forceinline__ float activate(float x, int act) {
-  if (act == EVO_ACT_TANH) return tanhf(x);
-  if (act == EVO_ACT_RELU) return fmaxf(x, 0.f);
-  return x;
-}
-
-// Sum over the 64 lanes of a wave in a fixed butterfly order (every lane gets the result).
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
 template <int LOSS>
 __global__ __launch_bounds__(256) void mlp_f32_kernel(MlpArgs a) {
   extern __shared__ float lds[];
-  constexpr int TB = kMlpTile;
-  float* hin = lds;
-  float* hout = lds + a.ldw * TB;
-  const int tid = threadIdx.x;
-  const int s = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int member = blockIdx.y;
-  const int b0 = blockIdx.x * TB;
-  const int b = b0 + s;
-  const bool live = b < a.B;
-  const float* theta = a.params + static_cast<size_t>(member) * a.sh.P;
-  const float* obs = a.obs + static_cast<size_t>(member) * a.obs_stride;
-  const int D = a.sh.dims[0];
-  // stage the observation tile transposed: hin[d][sample]
-  for (int i = tid; i < D * TB; i += 256) {
-    const int ss = i / D, d = i - ss * D;
-    hin[d * TB + ss] = (b0 + ss < a.B) ? obs[static_cast<size_t>(b0 + ss) * D + d] : 0.f;
-  }
-  __syncthreads();
-  int off = 0;
-  for (int l = 0; l < a.sh.n_layers; ++l) {
-    const int n_in = a.sh.dims[l], n_out = a.sh.dims[l + 1], act = a.sh.act[l];
-    const float* W = theta + off;
-    const float* bias = W + n_in * n_out;
-    for (int o0 = wave * 4; o0 < n_out; o0 += 16) {
-      float acc[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[j] = (o0 + j < n_out) ? bias[o0 + j] : 0.f;
-      if (o0 + 3 < n_out) {
-        for (int k = 0; k < n_in; ++k) {
-          const float hk = hin[k * TB + s];
-          const float* wr = W + k * n_out + o0;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc[j] = fmaf(hk, wr[j], acc[j]);
-        }
-      } else {
-        for (int k = 0; k < n_in; ++k) {
-          const float hk = hin[k * TB + s];
-          const float* wr = W + k * n_out + o0;
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (o0 + j < n_out) acc[j] = fmaf(hk, wr[j], acc[j]);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (o0 + j < n_out) hout[(o0 + j) * TB + s] = activate(acc[j], act);
-    }
-    __syncthreads();
-    float* t = hin;
-    hin = hout;
-    hout = t;
-    off += n_in * n_out + n_out;
-  }
-  // hin now holds the network output [A][sample]
-  const int A = a.sh.dims[a.sh.n_layers];
-  if (LOSS == LOSS_NONE) {
-    float* dst = a.out + (static_cast<size_t>(member) * a.B + b0) * A;
-    const int rows = min(TB, a.B - b0);
-    for (int i = tid; i < rows * A; i += 256) {
-      const int ss = i / A, o = i - ss * A;
-      dst[i] = hin[o * TB + ss];
-    }
-    return;
-  }
-  if (wave != 0) return;
-  float loss = 0.f;
-  if (live) {
-    if (LOSS == LOSS_CE) {
-      const int y = min(max(static_cast<const int32_t*>(a.target)[b], 0), A - 1);  // labels outside [0, A) are clamped
-      float mx = hin[s];
-      for (int o = 1; o < A; ++o) mx = fmaxf(mx, hin[o * TB + s]);
-      float se = 0.f;
-      for (int o = 0; o < A; ++o) se += expf(hin[o * TB + s] - mx);
-      loss = (mx + logf(se)) - hin[y * TB + s];
-    } else {
-      const float* tg = static_cast<const float*>(a.target) + (static_cast<size_t>(member) * a.B + b) * A;
-      for (int o = 0; o < A; ++o) {
-        const float d = hin[o * TB + s] - tg[o];
-        loss = fmaf(d, d, loss);
-      }
-    }
-  }
-  loss = wave_sum(loss);
-  if (s == 0) a.partial[static_cast<size_t>(member) * a.tiles + blockIdx.x] = loss;
+  mlp_f32_body<LOSS>(a, a.params + static_cast<size_t>(blockIdx.y) * a.sh.P, blockIdx.y, blockIdx.x, lds);
 }
 
 // ---- the matrix-core form ------------------------------------------------------------------------------

@@ -343,6 +343,36 @@ extern "C" int pgpe_ask_rollout(pgpe_state* st, uint64_t seed, int32_t pop, cons
   return EVO_OK;
 }
 
+extern "C" int pgpe_generation(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc* td, const policy_desc* pd,
+                               float* fitness_dev, void* stream) {
+  EVO_REQUIRE(st != nullptr && fitness_dev != nullptr, EVO_ERR_ARG, "pgpe_generation: null argument");
+  int rc = check_task(td);
+  if (rc) return rc;
+  EVO_REQUIRE(td->kind == EVO_TASK_CLASSIFY || td->kind == EVO_TASK_REGRESS, EVO_ERR_UNSUPPORTED,
+              "pgpe_generation: only the supervised tasks of an fp32 MLP run as one launch");
+  EVO_REQUIRE(pd != nullptr && pd->kind == EVO_POLICY_MLP && pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED,
+              "pgpe_generation: only the supervised tasks of an fp32 MLP run as one launch");
+  EVO_REQUIRE(td->B >= 1 && td->obs_dev != nullptr && td->target_dev != nullptr, EVO_ERR_ARG,
+              "pgpe_generation: B >= 1, obs_dev and target_dev required");
+  EVO_REQUIRE(td->obs_member_stride >= 0, EVO_ERR_ARG, "pgpe_generation: negative obs_member_stride");
+  EVO_REQUIRE(aligned16(td->obs_dev) && aligned16(td->target_dev), EVO_ERR_ARG,
+              "pgpe_generation: obs and target must be 16-byte aligned");
+  MlpShape sh;
+  rc = mlp_shape(pd, &sh);
+  if (rc) return rc;
+  EVO_REQUIRE(td->obs_member_stride == 0 || td->obs_member_stride == static_cast<int64_t>(td->B) * sh.dims[0],
+              EVO_ERR_ARG, "pgpe_generation: obs_member_stride must be 0 or B*D");
+  bool narrow = true;  // the vector-ALU forward: every fan-in below 64
+  for (int l = 0; l < sh.n_layers; ++l) narrow = narrow && sh.dims[l] < 64;
+  EVO_REQUIRE(narrow, EVO_ERR_UNSUPPORTED, "pgpe_generation: networks with a fan-in of 64 or more take ask, rollout, tell");
+  const int loss = td->kind == EVO_TASK_CLASSIFY ? LOSS_CE : LOSS_MSE;
+  const int A = sh.dims[sh.n_layers];
+  const float scale = loss == LOSS_CE ? -1.0f / static_cast<float>(td->B)
+                                      : -1.0f / (static_cast<float>(td->B) * static_cast<float>(A));
+  return pgpe_generation_small(st, seed, pop, sh, td->obs_dev, td->obs_member_stride, td->B, loss, td->target_dev, scale,
+                               fitness_dev, as_stream(stream));
+}
+
 extern "C" int evo_ask_forward(pgpe_state* st, uint64_t seed, int32_t pop, const policy_desc* pd, const float* obs_dev,
                                int64_t obs_member_stride, float* out_dev, int32_t B, void* stream) {
   EVO_REQUIRE(st != nullptr && out_dev != nullptr && aligned16(out_dev), EVO_ERR_ARG,

@@ -1,0 +1,149 @@
+"""pgpe_generation: ask, evaluation, ranks and tell of a small supervised problem in ONE launch (Section 4's
+ask / tell around Section 2's evaluation of the population).
+
+Gate: against the calls it replaces -- pgpe_ask, rollout, pgpe_tell of the same library, each of which has its own
+parity tests against the oracle -- the fitness and the whole state (mu, sigma, both moments, t) must be bit-identical
+after every generation: the kernel draws what ask stores, runs the same forward, and updates with the same block
+function.  One case also runs the oracle beside it over three free-running generations."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import generation as ogen, pgpe as opgpe
+from workloads import CONFIGS, generators as gen, mlp_param_count
+
+from util import assert_close, assert_scalar_rel, adam_ill_conditioned, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def evo():
+    import paper_2202_05008_amd as evo
+    return evo
+
+
+def _work(evo, td, pd, pop):
+    n = evo.rollout_workspace_bytes(td, pd, pop)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+
+
+def _state(g):
+    return [host(x).copy() for x in (g.mu, g.sigma, g.m, g.v)] + ([host(g.aux).copy()] if g.aux is not None else [])
+
+
+CASES = [
+    # task, dims, acts, pop, B, config overrides, generations, device-side t
+    ("classify", (16, 32, 4), (1, 0), 64, 512, {}, 4, False),                      # cfg1
+    ("classify", (16, 32, 4), (1, 0), 64, 512, {}, 3, True),
+    ("classify", (16, 32, 4), (1, 0), 32, 100, {"sigma_rule": 1}, 3, False),       # ragged last tile, Adam on sigma
+    ("regress", (8, 24, 24, 3), (2, 1, 0), 16, 130, {"optimizer": 2, "momentum": 0.8}, 3, False),   # per-member observations
+    ("regress", (5, 7, 2), (1, 0), 8, 64, {"shaping": 0}, 2, True),                # raw fitness as utilities
+    ("classify", (63, 40, 10), (2, 0), 24, 70, {}, 2, False),                      # P = 2970: several update workgroups per slice
+]
+
+
+@pytest.mark.parametrize("task,dims,acts,pop,B,over,generations,device_t", CASES)
+def test_one_launch_equals_ask_rollout_tell(evo, task, dims, acts, pop, B, over, generations, device_t):
+    P = mlp_param_count(dims)
+    mu0 = gen.initial_mu(7, P, 0.3)
+    cfg = evo.make_pgpe_config(P=P, pop_max=pop, **over)
+    one, three = evo.PGPE(cfg, mu0), evo.PGPE(cfg, mu0)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    if task == "classify":
+        x, y = gen.class_blobs(8, B, dims[0], dims[-1])
+        xd, yd = dev(x), dev(y)
+        make = lambda w: evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=B, obs=xd, target=yd, work=w)
+    else:
+        obs, tgt = gen.teacher_regression(9, pop, B, dims)
+        xd, yd = dev(obs), dev(tgt)
+        make = lambda w: evo.make_task_desc(evo.EVO_TASK_REGRESS, B=B, obs=xd, obs_member_stride=B * dims[0], target=yd, work=w)
+    w1, w3 = _work(evo, make(None), pd, pop), _work(evo, make(None), pd, pop)
+    td1, td3 = make(w1), make(w3)
+    if device_t:
+        one.device_generation()
+        three.device_generation()
+    params = torch.empty(pop, P, dtype=torch.float32, device="cuda")
+    for t in range(generations):
+        seed = 1000 + 17 * t
+        fit1 = torch.full((pop,), np.nan, dtype=torch.float32, device="cuda")
+        fit3 = torch.full((pop,), np.nan, dtype=torch.float32, device="cuda")
+        one.generation_step(seed, pop, td1, pd, fit1)
+        three.ask(seed, pop, params)
+        evo.rollout(td3, pd, params, pop, 1, fit3)
+        three.tell(fit3)
+        torch.cuda.synchronize()
+        assert torch.equal(fit1, fit3), "generation %d: fitness differs" % (t + 1)
+        for name, a, b in zip(("mu", "sigma", "m", "v", "aux"), _state(one), _state(three)):
+            assert np.array_equal(a, b), "generation %d: %s differs from ask + rollout + tell" % (t + 1, name)
+    assert one.generation == three.generation == generations + 1
+    # a tell without an ask is still refused: the call left no pending ask behind
+    with pytest.raises(evo.EvoError):
+        one.tell(torch.zeros(pop, device="cuda"))
+
+
+def test_one_launch_against_the_oracle(evo):
+    """Both sides run their own three generations of cfg1 (as the free-running test of the three calls does)."""
+    c = CONFIGS["cfg1"]
+    seed = 20220509
+    mu0 = gen.initial_mu(c.data_seed, c.P)
+    g = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop), mu0)
+    o = opgpe.PGPEState.create(opgpe.PGPEConfig(P=c.P, pop_max=c.pop), mu0)
+    x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
+    xd, yd = dev(x), dev(y)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+    td0 = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=xd, target=yd)
+    td = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=xd, target=yd, work=_work(evo, td0, pd, c.pop))
+    task = {"kind": "classify", "dims": c.dims, "acts": c.acts, "obs": x, "labels": y}
+    ill = np.zeros(c.P, dtype=bool)
+    for t in range(c.generations):
+        fit = torch.empty(c.pop, dtype=torch.float32, device="cuda")
+        g.generation_step(seed, c.pop, td, pd, fit)
+        probe = opgpe.PGPEState(o.cfg, o.mu.copy(), o.sigma.copy(), o.m.copy(), o.v.copy(), o.m_sigma.copy(),
+                                o.v_sigma.copy(), o.t)
+        _, ref_fit = ogen.run_generation(o, task, seed, c.pop)
+        opgpe.ask(probe, seed, c.pop)
+        g_mu, _ = opgpe.tell(probe, ref_fit, return_grads=True)
+        ill |= adam_ill_conditioned(g_mu, o.cfg.eps)
+        assert_scalar_rel(host(fit), ref_fit, 1e-5, "fitness, generation %d" % (t + 1))
+        keep = ~ill
+        assert keep.mean() > 0.99
+        assert_close(host(g.mu)[keep], o.mu[keep], 1e-5, "mu, generation %d" % (t + 1))
+        assert_close(host(g.sigma), o.sigma, 1e-5, "sigma, generation %d" % (t + 1))
+    assert g.generation == o.t == c.generations + 1
+
+
+def test_what_is_not_small_is_refused(evo):
+    dims, acts, pop, B = (64, 256, 256, 16), (2, 2, 0), 8, 64
+    P = mlp_param_count(dims)
+    g = evo.PGPE(evo.make_pgpe_config(P=P, pop_max=pop), gen.initial_mu(1, P, 0.1))
+    obs, tgt = gen.teacher_regression(3, pop, B, dims)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, dims, acts)
+    td0 = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=B, obs=dev(obs), obs_member_stride=B * dims[0], target=dev(tgt))
+    fit = torch.empty(pop, dtype=torch.float32, device="cuda")
+    with pytest.raises(evo.EvoError):      # a fan-in of 64 or more: the matrix-core forward is a launch of its own
+        g.generation_step(1, pop, td0, pd, fit)
+    small = (16, 32, 4)
+    Ps = mlp_param_count(small)
+    gc = evo.PGPE(evo.make_pgpe_config(P=Ps, pop_max=64, optimizer=1), gen.initial_mu(1, Ps, 0.1))
+    x, y = gen.class_blobs(8, 64, 16, 4)
+    pds = evo.make_policy_desc(evo.EVO_POLICY_MLP, small, (1, 0))
+    xd, yd = dev(x), dev(y)
+    tdc0 = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=64, obs=xd, target=yd)
+    tdc = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=64, obs=xd, target=yd, work=_work(evo, tdc0, pds, 64))
+    fit = torch.empty(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(evo.EvoError):      # ClipUp: norms over all parameters between its steps
+        gc.generation_step(1, 64, tdc, pds, fit)
+    wide = (63, 40, 10)
+    Pw = mlp_param_count(wide)
+    g2 = evo.PGPE(evo.make_pgpe_config(P=Pw, pop_max=2), gen.initial_mu(1, Pw, 0.1))
+    xw, yw = gen.class_blobs(8, 64, 63, 10)
+    xwd, ywd = dev(xw), dev(yw)
+    pdw = evo.make_policy_desc(evo.EVO_POLICY_MLP, wide, (2, 0))
+    tdw0 = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=64, obs=xwd, target=ywd)
+    tdw = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=64, obs=xwd, target=ywd, work=_work(evo, tdw0, pdw, 2))
+    fit = torch.empty(2, dtype=torch.float32, device="cuda")
+    with pytest.raises(evo.EvoError):      # two evaluation workgroups cannot carry the update of 2970 parameters
+        g2.generation_step(1, 2, tdw, pdw, fit)
+    # none of the refusals left anything behind
+    assert g.generation == gc.generation == g2.generation == 1
