@@ -147,3 +147,45 @@ def test_what_is_not_small_is_refused(evo):
         g2.generation_step(1, 2, tdw, pdw, fit)
     # none of the refusals left anything behind
     assert g.generation == gc.generation == g2.generation == 1
+
+
+def test_one_launch_generation_replayed_from_a_graph(evo):
+    """One recorded launch replays as successive generations (t and the parity of the hand-over arrays live on the
+    device): six replays, with eager work and waits between them, against six generations of the three calls."""
+    c = CONFIGS["cfg1"]
+    seed = 20220509
+    mu0 = gen.initial_mu(c.data_seed, c.P)
+    one = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop), mu0)
+    three = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop), mu0)
+    one.device_generation()
+    x, y = gen.class_blobs(c.data_seed, c.B, c.dims[0], c.dims[-1])
+    xd, yd = dev(x), dev(y)
+    pd = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts)
+    td0 = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=xd, target=yd)
+    td = evo.make_task_desc(evo.EVO_TASK_CLASSIFY, B=c.B, obs=xd, target=yd, work=_work(evo, td0, pd, c.pop))
+    fit1 = torch.empty(c.pop, dtype=torch.float32, device="cuda")
+    fit3 = torch.empty(c.pop, dtype=torch.float32, device="cuda")
+    params = torch.empty(c.pop, c.P, dtype=torch.float32, device="cuda")
+
+    def three_calls():
+        three.ask(seed, c.pop, params)
+        evo.rollout(td, pd, params, c.pop, 1, fit3)
+        three.tell(fit3)
+
+    one.generation_step(seed, c.pop, td, pd, fit1)      # generation 1 directly: the first call also arms the arrays
+    three_calls()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        one.generation_step(seed, c.pop, td, pd, fit1)
+    _ = one.generation      # recording moved the host copy of the index, not the device's: bring it back
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for t in range(6):
+        g.replay()
+        scratch.add_(1.0)                               # eager work between the replays
+        three_calls()
+        torch.cuda.synchronize()
+        assert torch.equal(fit1, fit3), "replay %d: fitness differs" % (t + 1)
+        for name, a, b in zip(("mu", "sigma", "m", "v"), _state(one), _state(three)):
+            assert np.array_equal(a, b), "replay %d: %s differs from ask + rollout + tell" % (t + 1, name)
+    assert one.generation == three.generation == 8
