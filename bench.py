@@ -68,7 +68,7 @@ ORACLE_SAMPLE_POP = {"cfg1": 64, "cfg2": 96, "cfg3": 512, "cfg4": 1024, "cfg5": 
 ORACLE_SAMPLE_GENERATIONS = {"cfg1": 600}
 
 
-def _build_workload(name, seed, batch=None):
+def _build_workload(name, seed, batch=None, f32=False):
     import dataclasses
     import numpy as np
     import torch
@@ -79,6 +79,8 @@ def _build_workload(name, seed, batch=None):
     c = CONFIGS[name]
     if batch is not None:      # cfg4 only: observations per member, for the sweep of arithmetic intensity
         c = dataclasses.replace(c, B=batch)
+    if f32:                    # cfg4 only: the same shape with fp32 parameters (the fp32 matrix-core MLP kernel)
+        c = dataclasses.replace(c, dtype=wc.DT_F32)
     dev = torch.device("cuda:0")
     mu0 = None if name == "cfg5" else gen.initial_mu(c.data_seed, c.P)
     pg = evo.PGPE(evo.make_pgpe_config(P=c.P, pop_max=c.pop, sigma_init=c.sigma_init, lr_mu=c.lr_mu,
@@ -141,13 +143,14 @@ def _build_workload(name, seed, batch=None):
         wl["desc"] = "cfg3: cart-pole swing-up, fp32 MLP 5-64-64-1, pop 1024 x 16 roll-outs x 1000 steps"
         wl["dtype"] = "f32"
     elif name == "cfg4":
-        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts, evo.EVO_BF16)
+        wl["pd"] = evo.make_policy_desc(evo.EVO_POLICY_MLP, c.dims, c.acts, evo.EVO_F32 if f32 else evo.EVO_BF16)
         obs, tgt = gen.teacher_regression(c.data_seed, c.pop, c.B, c.dims)
         od, tg = torch.from_numpy(obs).to(dev), torch.from_numpy(tgt).to(dev)
         wl["keep"] = [od, tg]
-        td = evo.make_task_desc(evo.EVO_TASK_REGRESS, B=c.B, obs=od, obs_member_stride=c.B * c.dims[0], target=tg)
+        td = with_work(lambda w: evo.make_task_desc(evo.EVO_TASK_REGRESS, B=c.B, obs=od, obs_member_stride=c.B * c.dims[0],
+                                                    target=tg, work=w))
         wl["task"] = lambda t: td
-        nbytes = c.pop * (c.P * 2.0 + c.B * c.dims[0] * 4.0 + c.B * c.dims[-1] * 4.0 + 4.0)
+        nbytes = c.pop * (c.P * (4.0 if f32 else 2.0) + c.B * c.dims[0] * 4.0 + c.B * c.dims[-1] * 4.0 + 4.0)
         flops = 2.0 * sum(c.dims[i] * c.dims[i + 1] for i in range(len(c.dims) - 1)) * c.pop * c.B
         # past the ridge (peak flop rate / peak byte rate = 312 flop per byte) the forward is priced as a contraction
         if flops / nbytes > PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9):
@@ -156,8 +159,10 @@ def _build_workload(name, seed, batch=None):
         else:
             wl["roofline"] = ("hbm", nbytes, PEAK_HBM_GBS, "GB/s")
             wl["mfma_tflops_work"] = flops
-        wl["desc"] = "cfg4: wide bf16 MLP 64-256-256-16, pop 4096, %d observations per member" % c.B
-        wl["dtype"] = "bf16"
+        wl["desc"] = "cfg4: wide %s MLP 64-256-256-16, pop 4096, %d observations per member" % ("fp32" if f32 else "bf16", c.B)
+        wl["dtype"] = "f32" if f32 else "bf16"
+        if f32:      # two-term fp16 splits: three matrix instructions per product
+            wl["mfma_f16_issued_work"] = 3.0 * flops
     elif name == "cfg5":
         wl["pd"] = None
         xs = torch.from_numpy(gen.sphere_target(c.data_seed, c.P)).to(dev)
@@ -359,7 +364,7 @@ def _measure_peaks(evo, torch):
 
 def _run_workload(name, args, steps, warmup, torch):
     """Time `steps` whole generations of one workload; returns the fields of its JSON line."""
-    wl = _build_workload(name, args.seed, args.batch)
+    wl = _build_workload(name, args.seed, args.batch, args.variant == "f32")
     c, pg, evo = wl["cfg"], wl["pgpe"], wl["evo"]
     stage_names = ("ask", "rollout", "tell")
     events = []
@@ -452,6 +457,11 @@ def _run_workload(name, args, steps, warmup, torch):
         out["roofline"]["priced_as"] = "fp16 matrix instructions as issued (two-term splits of fp32 operands)"
         out["roofline"]["fp32_equivalent"] = {"achieved": tf, "peak": PEAK_MFMA_F32_TF, "unit": "TFLOP/s",
                                               "frac": tf / PEAK_MFMA_F32_TF}
+    if "mfma_f16_issued_work" in wl:
+        out["roofline"]["mfma_f16_issued_tflops"] = wl["mfma_f16_issued_work"] / (dom_ms * 1e-3) / 1e12
+        out["roofline"]["bound_detail"] = ("fp32 MLP on the matrix cores (mlp_f32_mfma_kernel): one workgroup per CU, a chain of "
+                                           "weight-fetch, split and product phases per neuron tile")
+        out["roofline"]["traffic"] = None
     if "mfma_tflops_work" in wl:      # the forward's matrix-core rate next to its HBM rate
         out["roofline"]["mfma_bf16_tflops"] = wl["mfma_tflops_work"] / (dom_ms * 1e-3) / 1e12
         out["roofline"]["mfma_bf16_frac"] = out["roofline"]["mfma_bf16_tflops"] / PEAK_MFMA_BF16_TF
@@ -459,7 +469,7 @@ def _run_workload(name, args, steps, warmup, torch):
         out["roofline"]["hbm_GBs"] = wl["hbm_bytes_work"] / (dom_ms * 1e-3) / 1e9
         out["roofline"]["hbm_frac"] = out["roofline"]["hbm_GBs"] / PEAK_HBM_GBS
         out["roofline"]["bound_detail"] = ("bf16 matrix instructions of the register-resident forward: MFMA busy 42 %, "
-                                           "co-limited by LDS operand reads (DESIGN.md, section 7)")
+                                           "co-limited by LDS operand reads (profiles/mlp_bf16_resident_kernel_cfg4_b2048.md)")
     if args.graph:
         out["config"]["launch"] = "HIP graph replay of one recorded generation; stage_ms from direct calls before it"
     if args.batch is not None:
@@ -469,7 +479,8 @@ def _run_workload(name, args, steps, warmup, torch):
         out["config"]["generation"] = {"fused": "pgpe_generation: ask, evaluation, ranks and tell in one launch" if name == "cfg1" else
                                                 ("ask_rollout" if name == "cfg4" else "ask_sphere") +
                                                 " (ask + fitness in one kernel, no population) -> tell",
-                                       "stored": "ask -> rollout -> tell_stored"}[args.variant]
+                                       "stored": "ask -> rollout -> tell_stored",
+                                       "f32": "ask -> rollout -> tell with fp32 parameters"}[args.variant]
         out["roofline"]["traffic"] = None
         if args.variant == "fused" and name == "cfg1":
             out["roofline"]["kernel"] = "generation_small_kernel"
@@ -503,9 +514,9 @@ def main():
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured-peak probes")
     ap.add_argument("--batch", type=int, default=None,
                     help="cfg4 only: observations per member (default 64); sweeps the arithmetic intensity of the forward")
-    ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored"],
+    ap.add_argument("--variant", default="materialised", choices=["materialised", "fused", "stored", "f32"],
                     help="cfg5: 'fused' = ask fused with the sphere fitness (no population in memory), 'stored' = tell "
-                         "reads the perturbations back from the stored population; cfg4: 'fused' = ask fused into the forward; cfg1: 'fused' = the whole generation in one launch")
+                         "reads the perturbations back from the stored population; cfg4: 'fused' = ask fused into the forward; cfg1: 'fused' = the whole generation in one launch; cfg4: 'f32' = the same shape with fp32 parameters")
     ap.add_argument("--graph", action="store_true",
                     help="replay each generation from a recorded HIP graph (generation index kept on the device); "
                          "the per-stage times then come from an untimed pass of direct calls before the replays")
@@ -520,8 +531,10 @@ def main():
     all_configs = args.workload is None and args.batch is None and args.variant == "materialised" and not args.graph
     if args.batch is not None and headline != "cfg4":
         raise SystemExit("--batch applies to --workload cfg4 only")
-    if args.variant != "materialised" and not (headline == "cfg5" or (headline in ("cfg1", "cfg4") and args.variant == "fused")):
-        raise SystemExit("--variant applies to --workload cfg5 (fused, stored) and cfg1, cfg4 (fused) only")
+    if args.variant != "materialised" and not ((headline == "cfg5" and args.variant != "f32") or
+                                               (headline in ("cfg1", "cfg4") and args.variant == "fused") or
+                                               (headline == "cfg4" and args.variant == "f32")):
+        raise SystemExit("--variant applies to --workload cfg5 (fused, stored), cfg1 (fused) and cfg4 (fused, f32) only")
     # the oracle first: its all-cores leg forks worker processes, which must happen before the GPU is initialised
     cpu = None
     if not args.no_cpu_baseline and args.batch is None and args.variant == "materialised":
