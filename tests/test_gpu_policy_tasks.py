@@ -127,7 +127,9 @@ def test_rollout_regress_mlp_f32(evo):
 
 
 # ---------------------------------------------------------------- ConvNet
-@pytest.mark.parametrize("H,n_cls,pop,B", [(28, 10, 3, 37), (28, 10, 2, 1), (12, 4, 5, 9), (28, 16, 2, 8)])
+@pytest.mark.parametrize("H,n_cls,pop,B", [(28, 10, 3, 37), (28, 10, 2, 1), (12, 4, 5, 9), (28, 16, 2, 8),
+                                           # image sizes around the tiling of conv1 (8 window columns per matrix tile)
+                                           (4, 3, 2, 5), (8, 10, 2, 14), (16, 10, 3, 13), (20, 7, 2, 25), (24, 10, 2, 12)])
 def test_convnet_forward_and_fitness(evo, H, n_cls, pop, B):
     P = convnet_param_count(8, 16, n_cls, H)
     params = gen.random_params(16, pop, P, 0.25)
@@ -197,6 +199,34 @@ def test_convnet_any_finite_magnitude(evo):
     fit = _classify(evo, pd, dev(params), dev(img), dev(y), pop, B)
     assert_scalar_rel(fit[:4], otasks.classify_fitness(ref, y), 1e-5, "fitness")
     assert np.isnan(fit[4])
+
+
+def test_convnet_conv1_operand_ranges(evo):
+    """conv1 runs on the fp16 matrix instruction with a scale per output channel and per image: one tap far above
+    its channel's other taps, a channel ruled by its bias, channels of very different size, a black image, an image
+    with a single bright pixel and one with pixels of both signs all give the oracle's logits."""
+    H, n_cls, pop, B = 28, 10, 5, 7
+    P = convnet_param_count(8, 16, n_cls, H)
+    params = gen.random_params(35, pop, P, 0.2)
+    params[1, 4 * 8 + 3] = 2.0e3                   # W1[tap 4][channel 3]: the centre tap 10^4 times its neighbours
+    params[2, 72 + 5] = 1.0e6                      # b1[5]: that channel is its bias
+    params[3, 0:72:8] *= 1.0e-5                    # channel 0 of conv1 tiny, the others ordinary
+    params[3, 1:72:8] *= 1.0e3                     # and channel 1 large
+    params[4, :72] = 0.0                           # conv1 weights all zero: activations = relu(bias)
+    img, y = gen.mnist_shaped_batch(36, 1, B, n_cls, H)
+    img[1] = 0.0
+    img[2] = 0.0
+    img[2, 0, 13, 17] = 250.0
+    img[3] = img[3] - 0.5                          # pixels of both signs
+    img[4] *= 1.0e-6
+    pd = evo.make_policy_desc(evo.EVO_POLICY_CONVNET, (H, 8, 16, n_cls))
+    out = torch.empty(pop, B, n_cls, dtype=torch.float32, device="cuda")
+    evo.pop_forward(pd, dev(params), dev(img), 0, out, pop, B)
+    got = host(out)
+    ref = opolicy.convnet_forward(params, img, 8, 16, n_cls)
+    for m in range(pop):
+        for b in range(B):           # every (member, image) on its own scale
+            assert_close(got[m, b], ref[m, b], 1e-5, "member %d image %d" % (m, b))
 
 
 # ---------------------------------------------------------------- bf16 MLP on the matrix cores
