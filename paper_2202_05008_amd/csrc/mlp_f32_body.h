@@ -20,8 +20,22 @@ struct MlpArgs {
   int pop;
 };
 
+// tanh without branches: 1 - 2 / (e^{2|x|} + 1) through the hardware's exp2 and reciprocal (absolute error about
+// 1e-7, so 5e-7 relative from |x| = 0.25 on) and, below 0.25, the odd series up to x^9 (next term 9e-3 x^11: 2e-9
+// relative); saturates to 1 for large |x| (e^{2|x|} = inf), propagates NaN.
+__device__ __forceinline__ float tanh_fast_accurate(float x) {
+  const float ax = fabsf(x);
+  const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(2.885390081777927f * ax) + 1.0f), 1.0f);
+  const float x2 = ax * ax;
+  float p = fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
+  p = fmaf(x2, p, 2.0f / 15.0f);
+  p = fmaf(x2, p, -1.0f / 3.0f);
+  p = fmaf(x2 * ax, p, ax);
+  return copysignf(ax < 0.25f ? p : big, x);
+}
+
 __device__ __forceinline__ float activate(float x, int act) {
-  if (act == EVO_ACT_TANH) return tanhf(x);
+  if (act == EVO_ACT_TANH) return tanh_fast_accurate(x);
   if (act == EVO_ACT_RELU) return fmaxf(x, 0.f);
   return x;
 }
