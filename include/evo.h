@@ -319,7 +319,7 @@ int pgpe_ask_rollout(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc
 /* One whole generation -- ask, evaluation, ranks, tell (Section 4's ask / tell around Section 2's evaluation of the
  * population) -- in ONE launch, for problems so small that five launches of a few microseconds each are what a
  * generation costs: the supervised tasks EVO_TASK_CLASSIFY / EVO_TASK_REGRESS of an fp32 MLP whose fan-ins are all
- * below 64, at most 8192 parameters, optimizer Adam or momentum.  fitness_dev[pop] and the state (mu, sigma, moments,
+ * below 64, at most 8192 parameters and 512 members, optimizer Adam or momentum.  fitness_dev[pop] and the state (mu, sigma, moments,
  * t) end up bit for bit as pgpe_ask, rollout(td, pd, ...) and pgpe_tell would leave them; the population itself is
  * never stored (each workgroup draws its member's parameters into LDS).  td->work_dev is not used (the loss sums
  * go through the state's workspace; at most 4096 (member, tile of 64 samples) pairs).  Inside the kernel the

@@ -919,6 +919,9 @@ int pgpe_generation_small(pgpe_state* st, uint64_t seed, int32_t pop, const MlpS
               "pgpe_generation: ClipUp needs norms over all parameters between its steps (use ask, rollout, tell)");
   EVO_REQUIRE(c.P <= 8192 && sh.max_width <= 256, EVO_ERR_UNSUPPORTED,
               "pgpe_generation: at most 8192 parameters and widths up to 256 (got P = %d, width %d)", c.P, sh.max_width);
+  // every waiting workgroup ranks the whole population by itself: beyond a few hundred members that tail is
+  // longer than the launches it saves
+  EVO_REQUIRE(pop <= 512, EVO_ERR_UNSUPPORTED, "pgpe_generation: at most 512 members (got %d)", pop);
   const uint64_t seed_before = st->seed;
   const int32_t pop_before = st->pop;
   st->seed = seed, st->pop = pop;  // what tell_args reads
