@@ -109,6 +109,8 @@ def main(argv=None):
     ap.add_argument("--save-every", type=int, default=0)
     ap.add_argument("--resume", action="store_true", help="continue from --ckpt")
     ap.add_argument("--profile", action="store_true", help="log the device time of ask, rollout and tell per generation")
+    ap.add_argument("--one-launch", action="store_true",
+                    help="small supervised problems (cfg1): ask, evaluation and tell of a generation as one launch, same results")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         raise SystemExit("paper_2202_05008_amd.train needs a GPU (there is no CPU fallback)")
@@ -124,7 +126,7 @@ def main(argv=None):
     pd, train_task, test_task = _tasks(args.workload, c, args.seed, dev)
     tr = Trainer(pg, pd, train_task, c.pop, steps=c.steps, seed=args.seed, test_task=test_task,
                  test_every=args.test_every, log_path=args.log, ckpt_path=args.ckpt, save_every=args.save_every,
-                 test_pop=FORAGE_TEST_POP if args.workload == "forage" else 1, profile=args.profile)
+                 test_pop=FORAGE_TEST_POP if args.workload == "forage" else 1, profile=args.profile, one_launch=args.one_launch)
     if args.resume:
         if not args.ckpt:
             raise SystemExit("--resume needs --ckpt")

@@ -36,7 +36,7 @@ class Trainer:
     """
 
     def __init__(self, pgpe, policy, train_task, pop, steps=1, seed=0, test_task=None, test_every=0, log_path=None,
-                 ckpt_path=None, save_every=0, test_pop=1, profile=False):
+                 ckpt_path=None, save_every=0, test_pop=1, profile=False, one_launch=False):
         self.pgpe, self.policy, self.train_task, self.test_task = pgpe, policy, train_task, test_task
         self.pop, self.steps, self.seed = int(pop), int(steps), int(seed)
         self.test_every, self.save_every = int(test_every), int(save_every)
@@ -47,6 +47,7 @@ class Trainer:
         self.params = torch.empty(self.pop, pgpe.cfg.P, dtype=tdtype, device=dev)
         self.fitness = torch.empty(self.pop, dtype=torch.float32, device=dev)
         self.profile = bool(profile)
+        self.one_launch = bool(one_launch)      # small supervised problems: the whole generation as one launch (same bits)
         self.test_pop = int(test_pop)
         self._center = torch.empty(self.test_pop, pgpe.cfg.P, dtype=tdtype, device=dev)
         self._center_fit = torch.empty(self.test_pop, dtype=torch.float32, device=dev)
@@ -60,11 +61,15 @@ class Trainer:
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if self.profile else None
         mark = (lambda i: ev[i].record()) if self.profile else (lambda i: None)
         mark(0)
-        self.pgpe.ask(self.seed, self.pop, self.params, self.dtype)
-        mark(1)
-        api.rollout(self.train_task(t), self.policy, self.params, self.pop, self.steps, self.fitness)
-        mark(2)
-        self.pgpe.tell(self.fitness)
+        if self.one_launch:
+            self.pgpe.generation_step(self.seed, self.pop, self.train_task(t), self.policy, self.fitness)
+            mark(1), mark(2)
+        else:
+            self.pgpe.ask(self.seed, self.pop, self.params, self.dtype)
+            mark(1)
+            api.rollout(self.train_task(t), self.policy, self.params, self.pop, self.steps, self.fitness)
+            mark(2)
+            self.pgpe.tell(self.fitness)
         mark(3)
         fmax, fmean = float(self.fitness.max()), float(self.fitness.mean())   # waits for the generation
         rec = {"generation": t, "fitness_max": fmax, "fitness_mean": fmean,

@@ -56,6 +56,18 @@ def test_center_is_evaluated_like_the_oracle_and_training_improves(evo, tmp_path
     assert lines[9]["test_fitness"] > first
 
 
+def test_one_launch_training_is_the_same_run(evo):
+    """The trainer with every generation as one launch (pgpe_generation) logs the same numbers and ends in the same
+    state as with ask, rollout, tell."""
+    a, _ = _cfg1_trainer(evo)
+    b, _ = _cfg1_trainer(evo, one_launch=True)
+    ha, hb = a.run(12), b.run(12)
+    for ra, rb in zip(ha, hb):
+        assert (ra["generation"], ra["fitness_max"], ra["fitness_mean"]) == (rb["generation"], rb["fitness_max"], rb["fitness_mean"])
+    assert torch.equal(a.pgpe.mu, b.pgpe.mu) and torch.equal(a.pgpe.sigma, b.pgpe.sigma)
+    assert a.test() == b.test()
+
+
 def test_bf16_center_rounds_to_nearest_even(evo):
     P = 1003
     mu0 = gen.initial_mu(3, P, scale=1.0)
@@ -167,7 +179,7 @@ def test_train_command_line(evo, tmp_path, capsys, workload, generations):
     assert lines[-1]["generation"] == generations + 1 and np.isfinite(lines[-1]["final_test_fitness"])
     assert len(open(log).readlines()) == generations
     if workload == "cfg1":
-        assert train.main(["--workload", workload, "--generations", "3", "--ckpt", ck, "--resume"]) == 0
+        assert train.main(["--workload", workload, "--generations", "3", "--ckpt", ck, "--resume", "--one-launch"]) == 0
         more = [json.loads(l) for l in capsys.readouterr().out.splitlines()]
         assert more[0] == {"resumed_at_generation": generations + 1}
         assert [r["generation"] for r in more[1:-1]] == [generations + 1, generations + 2, generations + 3]
