@@ -17,12 +17,16 @@
 //   v_mfma_f32_16x16x32_f16   A[row j][k = 8 q + e], B[k = 8 q + e][col j], e = 0..7: eight fp16 each
 //   both                      D[row 4 q + i][col j], i = 0..3: four floats
 //
-// With two hidden layers, layer 1 (K = 5) is computed transposed on the fp32 instruction
-// (rows = neurons, columns = roll-outs), so that a lane ends up with four consecutive neurons
-// of one roll-out: after the activation they are split into two half-precision terms
-// (split16.h) and stored with one 8-byte LDS write per term.  Layer 2 (K = H) then runs on the
-// fp16 instruction (16 cycles for 8192 multiply-adds against 32 cycles for 1024 of the fp32 one),
-// three instructions per product, within a few 1e-7 of fp32 arithmetic.  Both operands carry a
+// With two hidden layers, layer 1 is computed transposed (rows = neurons, columns = roll-outs): four of
+// its inputs on the fp32 instruction, the fifth (th_d, the lane's own state) by four multiply-adds that
+// also bring the bias, so that a lane ends up with four consecutive neurons of one roll-out: after the
+// activation they are split into two half-precision terms (split16.h) and stored with one 8-byte LDS
+// write per term.  Layer 2 (K = H) then runs on the fp16 instruction (16 cycles for 8192 multiply-adds
+// against 32 cycles for 1024 of the fp32 one), three instructions per product, within a few 1e-7 of
+// fp32 arithmetic, transposed as well: the lane again holds four neurons of its own roll-out, so the
+// output layer is four multiply-adds, three additions and two exchanges between the k groups.  The
+// step loop is bound by the number of vector instructions a wave issues, which is what the forms
+// below are chosen by (constants folded into the operands, tanh layers kept as 1 - t).  Both operands carry a
 // power-of-two scale that keeps them inside fp16's range whatever their magnitude: the weights of a
 // wave's 16 neurons get theirs from their largest magnitude when they are loaded; activations behind
 // a tanh are stored times 2^14; activations behind a ReLU or no activation get a scale per roll-out
@@ -137,6 +141,34 @@ __device__ __forceinline__ float row16_sum(float v) {
   v = dpp_add<0x140>(v);  // row_mirror
   return v;
 }
+// Four such sums at once: lane j of a row ends with the row's total of p[j % 4].  The first two exchanges
+// halve the number of live values (a lane keeps one of a pair and hands the other to its partner), so the
+// whole reduction is 11 instructions instead of 16; the order of the additions is fixed.
+__device__ __forceinline__ float row16_sum4(const float (&p)[4], int j) {
+  const bool odd = (j & 1) != 0, upper = (j & 2) != 0;
+  const float t01 = (odd ? p[1] : p[0]) +
+                    __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(odd ? p[0] : p[1]), 0xB1, 0xf, 0xf, false));
+  const float t23 = (odd ? p[3] : p[2]) +
+                    __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(odd ? p[2] : p[3]), 0xB1, 0xf, 0xf, false));
+  float u = (upper ? t23 : t01) +
+            __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(upper ? t01 : t23), 0x4E, 0xf, 0xf, false));
+  u = dpp_add<0x124>(u);  // row_ror:4
+  u = dpp_add<0x128>(u);  // row_ror:8
+  return u;
+}
+
+// Two values that are also at hand times 2^11 -> the packed leading terms and the packed scaled residual
+// terms: the same numbers as split2_pair (x - h is exact, and so is its multiple), two instructions fewer.
+__device__ __forceinline__ void split2_pair_scaled(float x0, float x1, float xs0, float xs1, uint32_t& lead,
+                                                   uint32_t& resid) {
+  uint32_t hb = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x0, x1}, f16x2));
+  asm volatile("" : "+v"(hb));  // one conversion: what is stored is what the residual is taken against
+  const f16x2 h = __builtin_bit_cast(f16x2, hb);
+  const f32x2 r = {fmaf(static_cast<float>(h[0]), -kSplitLowScale, xs0),
+                   fmaf(static_cast<float>(h[1]), -kSplitLowScale, xs1)};
+  lead = hb;
+  resid = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2));
+}
 
 
 // NT: hidden width 16 NT (NT waves); TWO: two hidden layers of that width; TANH: every activation
@@ -164,13 +196,19 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   const int col = 16 * wave + j;  // this lane's hidden neuron
 
   // ---- weights -> registers (B operands of this wave's column tile) ----------------------------
-  const float w1a = theta[q * H + col];                      // k = q      (x, x_d, cos, sin)
-  const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding)
+  // With two tanh layers the first layer's weights and biases carry the factor 2 log2(e) of the tanh's
+  // exp2 argument, so the pre-activations leave the product ready for the exponential.
+  constexpr float kLog2e2 = 2.885390081777927f;
+  const float kk = (TWO && TANH) ? kLog2e2 : 1.0f;
+  const float w1a = kk * theta[q * H + col];                 // k = q      (x, x_d, cos, sin)
+  const float w1b = (q == 0) ? theta[4 * H + col] : 0.f;     // k = 4 + q  (th_d, then padding): one hidden layer only
   const float bias1 = theta[5 * H + col];
   const float* th2 = theta + 5 * H + H;
   f16x8 w2b[2][TWO ? KS2 : 1];  // [term][step]: element e is s_w W2[32 step + 8 q + e][col]
-  float bias1t[4];               // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
-  float bias2 = 0.f, w3, b3;
+  float bias1t[4], w_thd[4];     // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
+  float w3 = 0.f, b3;            // one hidden layer: output weight of this lane's column
+  float bias2t[4], w3t[4];       // two: layer-2 bias and output weight of this lane's rows (neurons 16 wave + 4 q + i)
+  float colsum = 0.f;            // sum over k of W2[k][col]
   float u_w = 1.0f;              // 1 / s_w, s_w the scale of this wave's layer-2 weights
   float bound_w[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, bound_b = 0.f;  // !TANH: max_n |W1[k][n]|, max_n |b1[n]|
   if (TWO) {
@@ -183,7 +221,10 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         const int k = 32 * s + 8 * q + e;
         x[s][e] = k < H ? th2[k * H + col] : 0.f;
         w_max = fmaxf(w_max, fabsf(x[s][e]));
+        colsum += x[s][e];
       }
+    colsum += __shfl_xor(colsum, 16, 64);
+    colsum += __shfl_xor(colsum, 32, 64);
     const float s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
     u_w = pow2_reciprocal(s_w);
 #pragma unroll
@@ -193,9 +234,15 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
       split2_x8(x[s], w2b[0][s], w2b[1][s]);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) bias1t[i] = theta[5 * H + 16 * wave + 4 * q + i];
-    bias2 = th2[H * H + col];
-    w3 = th2[H * H + H + col];
+    for (int i = 0; i < 4; ++i) {
+      bias1t[i] = kk * theta[5 * H + 16 * wave + 4 * q + i];
+      w_thd[i] = kk * theta[4 * H + 16 * wave + 4 * q + i];  // the fifth input (th_d) is added by the vector ALU
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bias2t[i] = th2[H * H + 16 * wave + 4 * q + i];
+      w3t[i] = th2[H * H + H + 16 * wave + 4 * q + i];
+    }
     b3 = th2[H * H + H + H];
     // columns H .. KP - 1 of the activation rows are never written and must read as zero
     for (int i = threadIdx.x; i < 2 * kTermB / 4; i += 64 * NT) reinterpret_cast<uint32_t*>(hb)[i] = 0u;
@@ -224,8 +271,20 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     w3 = th2[col];
     b3 = th2[H];
   }
-  // the factor 1 / (2^14 s_w) and the bias of the layer-2 pre-activation inside the tanh's exp2 argument
-  const float k_u2 = 2.885390081777927f * (u_w * (1.0f / kSTanh)), k_b2 = 2.885390081777927f * bias2;
+  // With two tanh layers the first layer's activations travel as their distance from one, tanh(x) = 1 - 2 /
+  // (e^{2x} + 1) = 1 - t / 2^14 with t = 2^15 / (e^{2x} + 1) = 1 / (2^-15 e^{2x} + 2^-15), which is one multiply-add
+  // and one reciprocal; the ones are a constant of layer 2, which sees bias2 + sum_k W2[k][n] and the negated
+  // product.  (The same form for the output layer would leave the policy's output as the difference of two sums
+  // sixty times its size when the weights are small, which the 1e-5 parity does not survive.)
+  const float k_u2 = -kLog2e2 * (u_w * (1.0f / kSTanh));
+  float k_b2t[4], m2w3t[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    k_b2t[i] = TWO ? kLog2e2 * (bias2t[i] + __shfl(colsum, 4 * q + i, 64)) : 0.f;  // lane n < 16 holds column n
+    m2w3t[i] = TWO ? -2.0f * w3t[i] : 0.f;  // w3 tanh(x) = w3 - 2 w3 / (e^{2x} + 1): one multiply-add
+    asm volatile("" : "+v"(m2w3t[i]));      // kept in its register (the compiler would form it again every step)
+  }
+  const float k_b3 = kLog2e2 * b3;    // the output tanh's argument is 2 log2(e) (sum) + this
 
   float total = 0.f;  // sum of the returns of this lane's roll-outs over all passes
   for (int r0 = 0; r0 < a.R; r0 += 16) {
@@ -247,20 +306,28 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     for (int step = 0; step < a.steps; ++step) {
       // ---- layer 1: observation (x, x_d, cos, sin, th_d) is the A operand directly -------------
       const float a0 = q == 0 ? s.x : (q == 1 ? s.xd : (q == 2 ? cs : sn));
-      const float a1 = q == 0 ? s.thd : 0.f;
       float p[4];
       if (TWO) {
-        // transposed: rows = this wave's neurons, columns = roll-outs
-        floatx4 acc = {bias1t[0], bias1t[1], bias1t[2], bias1t[3]};
+        // transposed: rows = this wave's neurons, columns = roll-outs; the column of th_d is this lane's own state
+        floatx4 acc;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = fmaf(w_thd[i], s.thd, bias1t[i]);
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1a, a0, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1b, a1, acc, 0, 0, 0);
         // neurons 16 wave + 4 q .. + 3 of roll-out j: two terms, 8 bytes each
-        float u_row[4];  // !TANH: 1 / (scale of the stored activations) of roll-outs 4 q + i
+        float u_mine = 0.f;  // !TANH: 1 / (scale of the stored activations of this lane's roll-out times s_w)
         {
           float h1[4];
+          uint2 lead, resid;
           if (TANH) {
+            // t = 2^14 (1 - tanh) and, for the residual terms, 2^11 t
+            float h1s[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h1[i] = tanh_times(acc[i], kSTanh);
+            for (int i = 0; i < 4; ++i) {
+              h1[i] = __builtin_amdgcn_rcpf(fmaf(__builtin_amdgcn_exp2f(acc[i]), 0.5f / kSTanh, 0.5f / kSTanh));
+              h1s[i] = h1[i] * kSplitLowScale;
+            }
+            split2_pair_scaled(h1[0], h1[1], h1s[0], h1s[1], lead.x, resid.x);
+            split2_pair_scaled(h1[2], h1[3], h1s[2], h1s[3], lead.y, resid.y);
           } else {
             // scale of this roll-out's activations at this step, from the bound on the pre-activations
             // (every wave carries the same state and forms the same number); a tanh bounds them by 1
@@ -271,22 +338,19 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
             bound = fmaf(bound_w[3], fabsf(sn), bound);
             bound = fmaf(bound_w[4], fabsf(s.thd), bound);
             const float s_row = act1 == EVO_ACT_TANH ? kSTanh : split_pow2_scale(bound);
-            const float u_mine = pow2_reciprocal(s_row) * u_w;
+            u_mine = pow2_reciprocal(s_row) * u_w;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              h1[i] = s_row * act_apply(acc[i], act1);
-              u_row[i] = __shfl(u_mine, 4 * q + i, 64);  // lane r < 16 holds roll-out r
-            }
+            for (int i = 0; i < 4; ++i) h1[i] = s_row * act_apply(acc[i], act1);
+            split2_pair(h1[0], h1[1], lead.x, resid.x);
+            split2_pair(h1[2], h1[3], lead.y, resid.y);
           }
-          uint2 lead, resid;
-          split2_pair(h1[0], h1[1], lead.x, resid.x);
-          split2_pair(h1[2], h1[3], lead.y, resid.y);
           unsigned char* dst = hb + j * kRowB + (16 * wave + 4 * q) * 2;
           *reinterpret_cast<uint2*>(dst) = lead;
           *reinterpret_cast<uint2*>(dst + kTermB) = resid;
         }
         __syncthreads();
-        // ---- layer 2: lane (row j, k group q) reads 8 consecutive activations per term and step ----
+        // ---- layer 2, transposed as well (the weights are the row operand): lane (column j, k group q) reads 8
+        //      consecutive activations of its roll-out per term and step and ends with neurons 16 wave + 4 q + i ----
         floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};  // h h'
         floatx4 low2 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
         const unsigned char* src = hb + j * kRowB + 16 * q;
@@ -295,35 +359,42 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
           f16x8 at[2];
 #pragma unroll
           for (int k = 0; k < 2; ++k) at[k] = *reinterpret_cast<const f16x8*>(src + k * kTermB + 64 * s2);
-          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[1], w2b[0][s2], low2, 0, 0, 0);
-          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0], w2b[1][s2], low2, 0, 0, 0);
-          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0], w2b[0][s2], acc2, 0, 0, 0);
+          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[1], low2, 0, 0, 0);
+          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[1][s2], at[0], low2, 0, 0, 0);
+          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[0], acc2, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float pre = fmaf(low2[i], kSplitLowUnscale, acc2[i]);  // layer-2 product times the two scales
-          p[i] = (TANH ? tanh_affine(pre, k_u2, k_b2) : act_apply(fmaf(pre, u_row[i], bias2), act2)) * w3;
+          if (TANH)
+            p[i] = fmaf(m2w3t[i], __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(fmaf(pre, k_u2, k_b2t[i])) + 1.0f),
+                        w3t[i]);
+          else
+            p[i] = act_apply(fmaf(pre, u_mine, bias2t[i]), act2) * w3t[i];
         }
+        // ---- output layer: this lane's four neurons, the other twelve of the wave from the other k groups ----
+        float p_wave = (p[0] + p[1]) + (p[2] + p[3]);
+        p_wave += __shfl_xor(p_wave, 16, 64);
+        p_wave += __shfl_xor(p_wave, 32, 64);
+        if (q == 0) part[wave][j] = p_wave;
       } else {
         floatx4 acc = {bias1, bias1, bias1, bias1};
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, w1a, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, w1b, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(q == 0 ? s.thd : 0.f, w1b, acc, 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = act_apply(acc[i], act1) * w3;
+        // ---- output layer: this wave's 16 columns ----
+        const float p_row = row16_sum4(p, j);  // lane j < 4: roll-out 4 q + j
+        if (j < 4) part[wave][4 * q + j] = p_row;
       }
-      // ---- output layer: this wave's 16 columns, then the waves' partial sums in wave order ----
-#pragma unroll
-      for (int i = 0; i < 4; ++i) p[i] = row16_sum(p[i]);
-      if (j == 0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) part[wave][4 * q + i] = p[i];
-      }
-      __syncthreads();
+      __syncthreads();  // then the waves' partial sums in wave order
       float pre = part[0][j];
 #pragma unroll
       for (int w = 1; w < NT; ++w) pre += part[w][j];
       const float lin = pre + b3;  // the policy's linear output
-      const float action = act_apply(lin, act3);
+      const float action =
+          TANH ? fmaf(-2.0f, __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(fmaf(pre, kLog2e2, k_b3)) + 1.0f), 1.0f)
+               : act_apply(lin, act3);
       // ---- environment step (every wave advances its own copy of the state) -------------------
       float sn_n, cs_n;
       const CpState n = cartpole_advance(s, sn, cs, action, a.c, sn_n, cs_n);
