@@ -24,9 +24,9 @@
 // write per term.  Layer 2 (K = H) then runs on the fp16 instruction (16 cycles for 8192 multiply-adds
 // against 32 cycles for 1024 of the fp32 one), three instructions per product, within a few 1e-7 of
 // fp32 arithmetic, transposed as well: the lane again holds four neurons of its own roll-out, so the
-// output layer is four multiply-adds, three additions and two exchanges between the k groups.  The
+// output layer is four multiply-adds, three additions and two lane swaps between the k groups.  The
 // step loop is bound by the number of vector instructions a wave issues, which is what the forms
-// below are chosen by (constants folded into the operands, tanh layers kept as 1 - t).  Both operands carry a
+// below are chosen by (constants folded into the operands, one reciprocal serving both split terms).  Both operands carry a
 // power-of-two scale that keeps them inside fp16's range whatever their magnitude: the weights of a
 // wave's 16 neurons get theirs from their largest magnitude when they are loaded; activations behind
 // a tanh are stored times 2^14; activations behind a ReLU or no activation get a scale per roll-out
@@ -48,8 +48,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 struct CartpoleConst {
   float g, M, m, l, b, fscale, dt, xlim;
-  float inv_2l;  // 1 / (2 l), rounded once on the host
+  float k3_2l;   // 3 / (2 l), rounded once on the host
   float k4, k3, k2ml, k3mg;  // 4 (M + m), 3 m, 2 m l, 3 m g: binary32 products formed on the host
+  float fscale4, b4;         // 4 fscale, 4 b (exact): the force enters the equations times four
 };
 
 struct CartpoleArgs {
@@ -107,14 +108,13 @@ struct CpState {
 // and its sine / cosine (needed for the reward and for the next observation).
 __device__ __forceinline__ CpState cartpole_advance(const CpState& s, float sn, float cs, float a,
                                                     const CartpoleConst& c, float& sn_new, float& cs_new) {
-  const float Fe = fmaf(c.fscale, a, -(c.b * s.xd));
   const float D = fmaf(-cs, c.k3 * cs, c.k4);
   // the hardware reciprocal is within one ulp; D >= 4 M + m > 0
-  float num = 4.0f * Fe;
+  float num = fmaf(c.fscale4, a, -(c.b4 * s.xd));  // 4 (fscale a - b x_d)
   num = fmaf(sn, s.thd * (c.k2ml * s.thd), num);
   num = fmaf(-cs, c.k3mg * sn, num);
   const float xdd = __builtin_amdgcn_rcpf(D) * num;
-  const float thdd = (3.0f * fmaf(c.g, sn, -(cs * xdd))) * c.inv_2l;
+  const float thdd = c.k3_2l * fmaf(c.g, sn, -(cs * xdd));
   CpState n;
   n.x = fmaf(c.dt, s.xd, s.x);
   n.xd = fmaf(c.dt, xdd, s.xd);
@@ -208,7 +208,6 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
   float bias1t[4], w_thd[4];     // transposed layer 1: this lane's rows are neurons 16 wave + 4 q + i
   float w3 = 0.f, b3;            // one hidden layer: output weight of this lane's column
   float bias2t[4], w3t[4];       // two: layer-2 bias and output weight of this lane's rows (neurons 16 wave + 4 q + i)
-  float colsum = 0.f;            // sum over k of W2[k][col]
   float u_w = 1.0f;              // 1 / s_w, s_w the scale of this wave's layer-2 weights
   float bound_w[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, bound_b = 0.f;  // !TANH: max_n |W1[k][n]|, max_n |b1[n]|
   if (TWO) {
@@ -221,10 +220,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         const int k = 32 * s + 8 * q + e;
         x[s][e] = k < H ? th2[k * H + col] : 0.f;
         w_max = fmaxf(w_max, fabsf(x[s][e]));
-        colsum += x[s][e];
       }
-    colsum += __shfl_xor(colsum, 16, 64);
-    colsum += __shfl_xor(colsum, 32, 64);
     const float s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
     u_w = pow2_reciprocal(s_w);
 #pragma unroll
@@ -271,16 +267,12 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     w3 = th2[col];
     b3 = th2[H];
   }
-  // With two tanh layers the first layer's activations travel as their distance from one, tanh(x) = 1 - 2 /
-  // (e^{2x} + 1) = 1 - t / 2^14 with t = 2^15 / (e^{2x} + 1) = 1 / (2^-15 e^{2x} + 2^-15), which is one multiply-add
-  // and one reciprocal; the ones are a constant of layer 2, which sees bias2 + sum_k W2[k][n] and the negated
-  // product.  (The same form for the output layer would leave the policy's output as the difference of two sums
-  // sixty times its size when the weights are small, which the 1e-5 parity does not survive.)
-  const float k_u2 = -kLog2e2 * (u_w * (1.0f / kSTanh));
+  // the factor 1 / (2^14 s_w) and the bias of the layer-2 pre-activation inside the tanh's exp2 argument
+  const float k_u2 = kLog2e2 * (u_w * (1.0f / kSTanh));
   float k_b2t[4], m2w3t[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    k_b2t[i] = TWO ? kLog2e2 * (bias2t[i] + __shfl(colsum, 4 * q + i, 64)) : 0.f;  // lane n < 16 holds column n
+    k_b2t[i] = TWO ? kLog2e2 * bias2t[i] : 0.f;
     m2w3t[i] = TWO ? -2.0f * w3t[i] : 0.f;  // w3 tanh(x) = w3 - 2 w3 / (e^{2x} + 1): one multiply-add
     asm volatile("" : "+v"(m2w3t[i]));      // kept in its register (the compiler would form it again every step)
   }
@@ -319,12 +311,13 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
           float h1[4];
           uint2 lead, resid;
           if (TANH) {
-            // t = 2^14 (1 - tanh) and, for the residual terms, 2^11 t
+            // 2^14 tanh and, from the same reciprocal, 2^25 tanh for the residual terms
             float h1s[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              h1[i] = __builtin_amdgcn_rcpf(fmaf(__builtin_amdgcn_exp2f(acc[i]), 0.5f / kSTanh, 0.5f / kSTanh));
-              h1s[i] = h1[i] * kSplitLowScale;
+              const float rc = __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(acc[i]) + 1.0f);
+              h1[i] = fmaf(-2.0f * kSTanh, rc, kSTanh);
+              h1s[i] = fmaf(-2.0f * kSTanh * kSplitLowScale, rc, kSTanh * kSplitLowScale);
             }
             split2_pair_scaled(h1[0], h1[1], h1s[0], h1s[1], lead.x, resid.x);
             split2_pair_scaled(h1[2], h1[3], h1s[2], h1s[3], lead.y, resid.y);
@@ -374,8 +367,15 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         }
         // ---- output layer: this lane's four neurons, the other twelve of the wave from the other k groups ----
         float p_wave = (p[0] + p[1]) + (p[2] + p[3]);
-        p_wave += __shfl_xor(p_wave, 16, 64);
-        p_wave += __shfl_xor(p_wave, 32, 64);
+        {
+          // register-to-register lane swaps (an exchange through LDS would put two more round trips on the step's
+          // chain): lanes l and l + 32, then the 16-lane groups pairwise; every lane ends with the wave's total
+          const uint32_t pb = __float_as_uint(p_wave);
+          const auto h = __builtin_amdgcn_permlane32_swap(pb, pb, false, false);  // (lower, lower), (upper, upper)
+          const uint32_t ph = __float_as_uint(__uint_as_float(h[0]) + __uint_as_float(h[1]));
+          const auto g = __builtin_amdgcn_permlane16_swap(ph, ph, false, false);  // groups (0 0 2 2), (1 1 3 3)
+          p_wave = __uint_as_float(g[0]) + __uint_as_float(g[1]);
+        }
         if (q == 0) part[wave][j] = p_wave;
       } else {
         floatx4 acc = {bias1, bias1, bias1, bias1};
@@ -450,8 +450,8 @@ __global__ __launch_bounds__(256) void cartpole_step_kernel(CartpoleConst c, con
 
 static CartpoleConst make_const(const float* cp) {
   const float g = cp[0], M = cp[1], m = cp[2], l = cp[3];
-  return CartpoleConst{g, M, m, l, cp[4], cp[5], cp[6], cp[7], 1.0f / (2.0f * l),
-                       4.0f * (M + m), 3.0f * m, (2.0f * m) * l, (3.0f * m) * g};
+  return CartpoleConst{g, M, m, l, cp[4], cp[5], cp[6], cp[7], static_cast<float>(3.0 / (2.0 * static_cast<double>(l))),
+                       4.0f * (M + m), 3.0f * m, (2.0f * m) * l, (3.0f * m) * g, 4.0f * cp[5], 4.0f * cp[4]};
 }
 
 int cartpole_supported(const MlpShape& sh, int n_rollouts) {
