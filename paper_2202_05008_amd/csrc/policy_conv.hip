@@ -342,12 +342,14 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       const int e_px = min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183);
       s_px = __int_as_float(__builtin_amdgcn_readfirstlane(min(e_px, e_cap) << 23));
     }
-    float c1_init[2], c1_out[2];  // accumulators start from the scaled bias; factor from them to the stored activations
+    // accumulators start from the scaled bias; factor from them to the stored activations, and 2^11 times it
+    float c1_init[2], c1_out[2], c1_out_s[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const float both = sw1_d[j] * s_px;
       c1_init[j] = b1_d[j] * both;
       c1_out[j] = s_a1 * pow2_reciprocal(both);
+      c1_out_s[j] = c1_out[j] * kSplitLowScale;
     }
     // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
     // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
@@ -410,19 +412,25 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             floatx4 o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][0], patch, c_init, 0, 0, 0);
             o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][1], patch, o0, 0, 0, 0);
             o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][1], patch, o1, 0, 0, 0);
-            // pooling window of channels 2 q, 2 q + 1: both pixel rows (o0, o1) and both columns (registers i, i + 2)
-            const float v0 = fmaxf(fmaxf(fmaxf(o0[0], o0[2]), fmaxf(o1[0], o1[2])) * c1_out[0], 0.f);  // stored times s_a1
-            const float v1 = fmaxf(fmaxf(fmaxf(o0[1], o0[3]), fmaxf(o1[1], o1[3])) * c1_out[1], 0.f);
+            // pooling window of channels 2 q, 2 q + 1: both pixel rows (o0, o1) and both columns (registers i, i + 2).
+            // ReLU of the largest of four = the largest of the four and zero, taken on the bit patterns as signed
+            // integers: among non-negative floats they order like the floats, and every negative float (and -0) is a
+            // negative integer, which the zero beats.  The factor to the stored units (a power of two) comes after.
+            const float r0 = __int_as_float(max(max(max(__float_as_int(o0[0]), __float_as_int(o0[2])),
+                                                    max(__float_as_int(o1[0]), __float_as_int(o1[2]))), 0));
+            const float r1 = __int_as_float(max(max(max(__float_as_int(o0[1]), __float_as_int(o0[3])),
+                                                    max(__float_as_int(o1[1]), __float_as_int(o1[3]))), 0));
             uint32_t lead, resid;
-            split2_pair(v0, v1, lead, resid);
+            split2_pair_scaled(r0 * c1_out[0], r1 * c1_out[1], r0 * c1_out_s[0], r1 * c1_out_s[1], lead, resid);
             // the four channel pairs of a window (lane groups 0..3) -> the 16 bytes of its pixel, leading term in
             // lane group 0 and residual term in lane group 1: one swap between neighbouring groups, then the
-            // upper half of the wave moves down
+            // upper half of the wave moves down (what the swaps leave in the upper half is not stored; their second
+            // operands are values that are dead by now, so no copies are made to preserve them)
             const auto sw = __builtin_amdgcn_permlane16_swap(lead, resid, false, false);   // (L0 R0 L2 R2), (L1 R1 L3 R3)
-            const uint32_t t2 = __builtin_amdgcn_permlane32_swap(sw[0], sw[0], false, false)[1];  // groups 0, 1: L2, R2
-            const uint32_t t3 = __builtin_amdgcn_permlane32_swap(sw[1], sw[1], false, false)[1];  // groups 0, 1: L3, R3
+            const auto s2 = __builtin_amdgcn_permlane32_swap(sw[0], __float_as_uint(o0[0]), false, false);  // groups 0, 1: own, then L2, R2
+            const auto s3 = __builtin_amdgcn_permlane32_swap(sw[1], __float_as_uint(o1[0]), false, false);  // groups 0, 1: own, then L3, R3
             if (c1_store[m]) {
-              const uint4 pixel = make_uint4(sw[0], sw[1], t2, t3);
+              const uint4 pixel = make_uint4(s2[0], s3[0], s2[1], s3[1]);
               // own band, and the neighbour band that shares the row
               *reinterpret_cast<uint4*>(bandb + b3 * kBandBytes + own_off[m]) = pixel;
               if (c1_lower ? b + 1 < H4 : b >= 1)
