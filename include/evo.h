@@ -206,7 +206,7 @@ int pgpe_tell_stored(pgpe_state* st, const float* fitness_dev, const float* para
  *      for j = 0 and the true answer token j - 1 afterwards; logits_j = h_j Wo + bo.
  *      Flat parameters: enc Wx[V][4H], Wh[H][4H], b[4H]; dec Wx[V][4H], Wh[H][4H], b[4H];
  *      Wo[H][n_out]; bo[n_out].  fp32 results for any finite weights (two-term fp16 operand splits; a
- *      member with a recurrent weight of 255.9 or more is evaluated by a second, slower build of the kernel
+ *      member with a recurrent weight of 15.99 or more is evaluated by a second, slower build of the kernel
  *      that is launched behind the first and scales each group of weights by its own largest magnitude).
  * ------------------------------------------------------------------------------------ */
 typedef struct {

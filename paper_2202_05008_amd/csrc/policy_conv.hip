@@ -191,7 +191,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     for (int st = 0; st < 3; ++st) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) x[st][j] *= s_w2;
-      split2_x8(x[st], w2b[0][st], w2b[1][st]);
+      split2_x8_true<true>(x[st], w2b[0][st], w2b[1][st]);
     }
   }
   const float bias2 = b2[n];
@@ -342,14 +342,12 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       const int e_px = min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183);
       s_px = __int_as_float(__builtin_amdgcn_readfirstlane(min(e_px, e_cap) << 23));
     }
-    // accumulators start from the scaled bias; factor from them to the stored activations, and 2^11 times it
-    float c1_init[2], c1_out[2], c1_out_s[2];
+    float c1_init[2], c1_out[2];  // accumulators start from the scaled bias; factor from them to the stored activations
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const float both = sw1_d[j] * s_px;
       c1_init[j] = b1_d[j] * both;
       c1_out[j] = s_a1 * pow2_reciprocal(both);
-      c1_out_s[j] = c1_out[j] * kSplitLowScale;
     }
     // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
     // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
@@ -421,7 +419,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             const float r1 = __int_as_float(max(max(max(__float_as_int(o0[1]), __float_as_int(o0[3])),
                                                     max(__float_as_int(o1[1]), __float_as_int(o1[3]))), 0));
             uint32_t lead, resid;
-            split2_pair_scaled(r0 * c1_out[0], r1 * c1_out[1], r0 * c1_out_s[0], r1 * c1_out_s[1], lead, resid);
+            split2_pair_true(r0 * c1_out[0], r1 * c1_out[1], lead, resid);
             // the four channel pairs of a window (lane groups 0..3) -> the 16 bytes of its pixel, leading term in
             // lane group 0 and residual term in lane group 1: one swap between neighbouring groups, then the
             // upper half of the wave moves down (what the swaps leave in the upper half is not stored; their second
@@ -446,8 +444,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 
       // ---- conv2 + ReLU + pool, band b-1: two independent tiles (windows 0..3 and 4..7 of the row) --
       const char* bb = bandb + prev3 * kBandBytes;
-      floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h'
-      floatx4 low0 = {0.f, 0.f, 0.f, 0.f}, low1 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
+      floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h' + h m' + m h' (residual terms unscaled)
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
         f16x8 a0[2], a1[2];  // [term] of tile 0 and tile 1
@@ -456,23 +453,23 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
           a0[k] = *reinterpret_cast<const f16x8*>(bb + a_off[0][st] + k * kBandTerm);
           a1[k] = *reinterpret_cast<const f16x8*>(bb + a_off[1][st] + k * kBandTerm);
         }
-        low0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[1], w2b[0][st], low0, 0, 0, 0);
-        low1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[1], w2b[0][st], low1, 0, 0, 0);
-        low0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[1][st], low0, 0, 0, 0);
-        low1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[1][st], low1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[1], w2b[0][st], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[1], w2b[0][st], acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[1][st], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[1][st], acc1, 0, 0, 0);
         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[0][st], acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[0][st], acc1, 0, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc0[i] = fmaf(low0[i], kSplitLowUnscale, acc0[i]);
-        acc1[i] = fmaf(low1[i], kSplitLowUnscale, acc1[i]);
       }
       // D role: the four registers of lane (q, n) are window q (+4) of channel n: two features of the dense
       // layer, which is accumulated band by band (per lane and class) from the workgroup's copy of its weights
       {
-        const float x0 = q < H4 ? fmaxf(fmaf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])), u_a2, bias2), 0.f) : 0.f;
-        const float x1 = q + 4 < H4 ? fmaxf(fmaf(fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])), u_a2, bias2), 0.f) : 0.f;
+        // bias and factor first (monotone, so the same number as after the maximum): the maxima then work on
+        // results of vector instructions and need no canonicalising moves
+        float f0[4], f1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f0[i] = fmaf(acc0[i], u_a2, bias2), f1[i] = fmaf(acc1[i], u_a2, bias2);
+        const float x0 = q < H4 ? fmaxf(fmaxf(fmaxf(f0[0], f0[1]), f0[2]), fmaxf(f0[3], 0.f)) : 0.f;
+        const float x1 = q + 4 < H4 ? fmaxf(fmaxf(fmaxf(f1[0], f1[1]), f1[2]), fmaxf(f1[3], 0.f)) : 0.f;
         const float* wr0 = wd_s + (((b - 1) * H4 + min(q, H4 - 1)) * kC2 + n) * NCS;
         const float* wr1 = wd_s + (((b - 1) * H4 + min(q + 4, H4 - 1)) * kC2 + n) * NCS;
 #pragma unroll

@@ -19,11 +19,12 @@
 // gate, columns = 16 samples, so that a lane ends up with the four gates of four consecutive units
 // of one sample: the cell update is lane-local, c stays in registers, and h' leaves as one 8-byte
 // LDS store per split term.  h is kept in LDS as two half-precision terms (split16.h: 22
-// significand bits, three matrix instructions per product, within a few 1e-7 of fp32 arithmetic).
+// significand bits, three matrix instructions per product into one accumulator, within a few 1e-7 of
+// fp32 arithmetic).
 // h lies in (-1, 1) and is stored times 2^14; the recurrent weights of a wave are stored times a power
 // of two s_w, so the gate pre-activations come out times 2^14 s_w and the factor is folded into the
-// exp2 arguments of the sigmoids and tanh.  The kernel is built twice.  The first build takes s_w = 2^8,
-// which holds every weight below 255.9, checks the weights as it loads them, and marks a member that has a
+// exp2 arguments of the sigmoids and tanh.  The kernel is built twice.  The first build takes s_w = 2^12,
+// which holds every weight below 15.99 (and keeps the residual term of every weight above 2^-15 a normal number), checks the weights as it loads them, and marks a member that has a
 // larger one (its result is a NaN with a payload of its own).  The second build is launched right behind
 // it over the same grid: a workgroup whose member is not marked exits at once; for a marked member each
 // wave first reads its weights once more to find their largest magnitude and scales them by the power of
@@ -51,7 +52,7 @@ namespace {
 constexpr int kChunk = 64;            // samples per pass: four column tiles
 constexpr int kMaxV = 16, kMaxOut = 16, kMaxLq = 32, kMaxLa = 16;
 constexpr float kSH = 16384.0f;                 // 2^14: scale of the stored h
-constexpr float kSWDefault = 256.0f;            // 2^8: scale of the stored weights unless one of them would overflow
+constexpr float kSWDefault = 4096.0f;           // 2^12: scale of the stored weights unless one of them would overflow
 constexpr float kSplitMax = 65504.0f;           // largest finite fp16
 constexpr uint32_t kMarkBits = 0x7fc5eed5u;     // the quiet NaN that marks a member for the second build
 constexpr float kLog2e = 1.4426950408889634f;
@@ -89,33 +90,29 @@ __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], float
   for (int st = 0; st < 4; ++st) {
     const int s = 16 * st + j;  // this lane's sample (column)
     const int tok = tok_of(s);
-    floatx4 acc[4], low[4];
+    floatx4 acc[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
+    for (int g = 0; g < 4; ++g)
       acc[g] = *reinterpret_cast<const floatx4*>(tab + tok * kTabRow + g * H + 16 * wave + 4 * q);
-      low[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
     const unsigned char* src = hc + s * kRowB + 16 * q;
 #pragma unroll
     for (int kb = 0; kb < KS; ++kb) {
       const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
       const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
-      // three rounds over the gates: four independent instructions between two that share an accumulator
+      // three rounds over the gates (four independent instructions between two that share an accumulator), the
+      // small partial products first
 #pragma unroll
-      for (int g = 0; g < 4; ++g) low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b1, low[g], 0, 0, 0);
+      for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b1, acc[g], 0, 0, 0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[1][g][kb], b0, acc[g], 0, 0, 0);
 #pragma unroll
       for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[0][g][kb], b0, acc[g], 0, 0, 0);
-#pragma unroll
-      for (int g = 0; g < 4; ++g) low[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wh[1][g][kb], b0, low[g], 0, 0, 0);
     }
     // ---- cell update of units 16 wave + 4 q + i for sample s; h' (times 2^14) -> the free buffer ----
     float hs[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float ai = fmaf(low[0][i], kSplitLowUnscale, acc[0][i]);
-      const float af = fmaf(low[1][i], kSplitLowUnscale, acc[1][i]);
-      const float ag = fmaf(low[2][i], kSplitLowUnscale, acc[2][i]);
-      const float ao = fmaf(low[3][i], kSplitLowUnscale, acc[3][i]);
+      const float ai = acc[0][i], af = acc[1][i], ag = acc[2][i], ao = acc[3][i];
       const float c = fmaf(sigmoid_scaled(af, k_u), cst[st][i], sigmoid_scaled(ai, k_u) * tanh_scaled(ag, k_u));
       cst[st][i] = c;
       // 2^14 sigmoid(a_o) = 1 / (2^-14 (1 + e^-a_o))
@@ -123,8 +120,8 @@ __device__ __forceinline__ void lstm_step(const f16x8 (&wh)[2][4][H / 32], float
       hs[i] = so * tanh_fast(c);
     }
     uint2 lead, resid;
-    split2_pair(hs[0], hs[1], lead.x, resid.x);
-    split2_pair(hs[2], hs[3], lead.y, resid.y);
+    split2_pair_true(hs[0], hs[1], lead.x, resid.x);
+    split2_pair_true(hs[2], hs[3], lead.y, resid.y);
     unsigned char* dst = hn + s * kRowB + (16 * wave + 4 * q) * 2;
     *reinterpret_cast<uint2*>(dst) = lead;
     *reinterpret_cast<uint2*>(dst + kTermB) = resid;
@@ -145,7 +142,7 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
   constexpr int kTabRow = G4 + 4;       // floats per token row: 16 bytes of padding spread the tokens over the banks
   // three h buffers: the current h of each of the two chunks in flight and the one the next step writes
   __shared__ __attribute__((aligned(16))) unsigned char hbuf[3 * kBufB];
-  __shared__ __attribute__((aligned(16))) float tab[kMaxV * kTabRow];     // 2^22 (Wx[token] + b) of the active cell
+  __shared__ __attribute__((aligned(16))) float tab[kMaxV * kTabRow];     // 2^14 s_w (Wx[token] + b) of the active cell
   __shared__ __attribute__((aligned(16))) f16x8 wo_s[2][KS][64];          // Wo^T as A operands, two terms
   __shared__ unsigned char tokq[2 * kChunk * kMaxLq];
   __shared__ unsigned char toka[2 * kChunk * kMaxLa];
@@ -192,7 +189,7 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
       float x[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = jj < n_out ? s_o * Wo[(32 * kb + 8 * qq + e) * n_out + jj] : 0.f;
-      split2_x8(x, wo_s[0][kb][l], wo_s[1][kb][l]);
+      split2_x8_true<true>(x, wo_s[0][kb][l], wo_s[1][kb][l]);
     }
   }
   float bo4[4];
@@ -239,7 +236,7 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
       const float* Wh = Wx + V * G4;
       const float* bg = Wh + H * G4;
       // ---- recurrent weights of this cell -> registers: wh[term][gate][step], element e is
-      //      2^8 Wh[32 step + 8 q + e][gate H + 16 wave + j].  The whole matrix is fetched with 16-byte
+      //      s_w Wh[32 step + 8 q + e][gate H + 16 wave + j].  The whole matrix is fetched with 16-byte
       //      loads that are all in flight at once (one round trip to memory per cell), then handed
       //      through LDS in pieces of 16 rows (the area of the token table, free between two cells):
       //      piece (step, half) holds rows 32 step + 8 q' + 4 half + e', q' = 0..3, e' = 0..3. ----
@@ -297,7 +294,8 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
               const float x8[8] = {xlo[g][0], xlo[g][1], xlo[g][2], xlo[g][3], x[g][0], x[g][1], x[g][2], x[g][3]};
-              split2_x8(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
+              // the second build's weights may lie far below their wave's largest one: their residuals are kept
+              split2_x8_true<DYNAMIC>(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
             }
           }
         }
@@ -338,19 +336,19 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
             // ---- logits of answer position t for sample tile `wave`: rows = outputs, columns = samples ----
             const int s = 16 * wave + j;
             const unsigned char* src = hbuf + cur * kBufB + s * kRowB + 16 * q;
-            floatx4 lg = {0.f, 0.f, 0.f, 0.f}, lw = {0.f, 0.f, 0.f, 0.f};
+            floatx4 lg = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kb = 0; kb < KS; ++kb) {
               const f16x8 b0 = *reinterpret_cast<const f16x8*>(src + 64 * kb);
               const f16x8 b1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * kb);
               const f16x8 w0 = wo_s[0][kb][lane], w1 = wo_s[1][kb][lane];
-              lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b1, lw, 0, 0, 0);
-              lw = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1, b0, lw, 0, 0, 0);
+              lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b1, lg, 0, 0, 0);
+              lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1, b0, lg, 0, 0, 0);
               lg = __builtin_amdgcn_mfma_f32_16x16x32_f16(w0, b0, lg, 0, 0, 0);
             }
             float z[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) z[i] = fmaf(fmaf(lw[i], kSplitLowUnscale, lg[i]), u_o, bo4[i]);
+            for (int i = 0; i < 4; ++i) z[i] = fmaf(lg[i], u_o, bo4[i]);
             const int gs = c0 + ch * kChunk + s;  // sample index in the batch
             const bool valid = gs < a.B;
             if (a.logits && valid) {

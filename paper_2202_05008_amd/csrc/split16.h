@@ -7,6 +7,9 @@
 // |x - h - 2^-11 m| <= 2^-22 |x|.  A product of two such values is accumulated in fp32 as
 //     h h'  (one accumulator)   and   h m' + m h'  (a second one, added with the factor 2^-11);
 // every fp16 x fp16 product is exact in fp32 and the dropped m m' is below 2^-22 of the product.
+// The second form below (split2_pair_true) stores the residual x - h itself: all three partial products then
+// share one accumulator, at the price of the residuals of values far below the tensor's bound (see there);
+// the contractions over many terms (conv2, cart-pole layer 2, the LSTM's gates) use it.
 //
 // Two hardware facts shape the code.  (1) v_cvt_pk_f16_f32, which the compiler picks for a pair of
 // conversions, returns zero where the single conversion returns a subnormal: the residual must be
@@ -71,6 +74,50 @@ __device__ __forceinline__ void split2_pair_scaled(float x0, float x1, float xs0
                    fmaf(static_cast<float>(h[1]), -kSplitLowScale, xs1)};
   lead = hb;
   resid = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2));
+}
+
+// Two values -> the packed leading terms and the packed residual terms x - h themselves (no factor): with them
+// all three partial products of a product run into ONE accumulator and nothing is left to add afterwards.  The
+// matrix instruction takes half-precision subnormals as they are (measured: 2^-24 x 1024 = 2^-14), but the packed
+// conversion returns zero for them, so a residual below 2^-14, which is that of a value below 2^-3, is dropped,
+// and a value below 2^-14 altogether: the absolute error of a term is then at most 2^-14, against
+// a tensor whose power of two puts its bound at 2^14 or above, i.e. 2^-28 of the bound (and 2^-22 of the
+// value wherever the value is above 2^-3).
+__device__ __forceinline__ void split2_pair_true(float x0, float x1, uint32_t& lead, uint32_t& resid) {
+  uint32_t hb = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x0, x1}, f16x2));
+  asm volatile("" : "+v"(hb));  // one conversion: what is stored is what the residual is taken against
+  const f16x2 h = __builtin_bit_cast(f16x2, hb);
+  const f32x2 r = {fmaf(static_cast<float>(h[0]), -1.0f, x0), fmaf(static_cast<float>(h[1]), -1.0f, x1)};
+  lead = hb;
+  resid = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2));
+}
+// The same with the residuals converted one by one, which keeps the subnormal ones (two instructions more per
+// pair): for tensors that are split once and used for a whole launch (weights), where a value far below the
+// tensor's bound must still keep (almost) its own 22 bits.
+__device__ __forceinline__ void split2_pair_true_kept(float x0, float x1, uint32_t& lead, uint32_t& resid) {
+  uint32_t hb = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x0, x1}, f16x2));
+  asm volatile("" : "+v"(hb));
+  const f16x2 h = __builtin_bit_cast(f16x2, hb);
+  const float r0 = x0 - static_cast<float>(h[0]), r1 = x1 - static_cast<float>(h[1]);
+  // (an empty statement between the two conversions keeps the compiler from pairing them)
+  uint32_t lo = __builtin_bit_cast(uint16_t, static_cast<_Float16>(r0));
+  asm volatile("" : "+v"(lo));
+  const uint32_t hi = __builtin_bit_cast(uint16_t, static_cast<_Float16>(r1));
+  lead = hb;
+  resid = lo | (hi << 16);
+}
+// Eight values -> the two matrix operands (leading, residual itself); KEPT: subnormal residuals are kept.
+template <bool KEPT>
+__device__ __forceinline__ void split2_x8_true(const float x[8], f16x8& lead, f16x8& resid) {
+  uint32_t l[4], r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (KEPT) split2_pair_true_kept(x[2 * i], x[2 * i + 1], l[i], r[i]);
+    else split2_pair_true(x[2 * i], x[2 * i + 1], l[i], r[i]);
+  }
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  lead = __builtin_bit_cast(f16x8, u32x4{l[0], l[1], l[2], l[3]});
+  resid = __builtin_bit_cast(f16x8, u32x4{r[0], r[1], r[2], r[3]});
 }
 
 // Eight values -> the two matrix operands (leading, residual).

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
     for (int s = 0; s < KS2; ++s) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[s][e] *= s_w;
-      split2_x8(x[s], w2b[0][s], w2b[1][s]);
+      split2_x8_true<true>(x[s], w2b[0][s], w2b[1][s]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -297,16 +297,11 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
           float h1[4];
           uint2 lead, resid;
           if (TANH) {
-            // 2^14 tanh and, from the same reciprocal, 2^25 tanh for the residual terms
-            float h1s[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const float rc = __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(acc[i]) + 1.0f);
-              h1[i] = fmaf(-2.0f * kSTanh, rc, kSTanh);
-              h1s[i] = fmaf(-2.0f * kSTanh * kSplitLowScale, rc, kSTanh * kSplitLowScale);
-            }
-            split2_pair_scaled(h1[0], h1[1], h1s[0], h1s[1], lead.x, resid.x);
-            split2_pair_scaled(h1[2], h1[3], h1s[2], h1s[3], lead.y, resid.y);
+            for (int i = 0; i < 4; ++i)  // 2^14 tanh
+              h1[i] = fmaf(-2.0f * kSTanh, __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(acc[i]) + 1.0f), kSTanh);
+            split2_pair_true(h1[0], h1[1], lead.x, resid.x);
+            split2_pair_true(h1[2], h1[3], lead.y, resid.y);
           } else {
             // scale of this roll-out's activations at this step, from the bound on the pre-activations
             // (every wave carries the same state and forms the same number); a tanh bounds them by 1
@@ -320,8 +315,8 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
             u_mine = pow2_reciprocal(s_row) * u_w;
 #pragma unroll
             for (int i = 0; i < 4; ++i) h1[i] = s_row * act_apply(acc[i], act1);
-            split2_pair(h1[0], h1[1], lead.x, resid.x);
-            split2_pair(h1[2], h1[3], lead.y, resid.y);
+            split2_pair_true(h1[0], h1[1], lead.x, resid.x);
+            split2_pair_true(h1[2], h1[3], lead.y, resid.y);
           }
           unsigned char* dst = hb + j * kRowB + (16 * wave + 4 * q) * 2;
           *reinterpret_cast<uint2*>(dst) = lead;
@@ -330,21 +325,24 @@ __global__ __launch_bounds__(64 * NT) void cartpole_kernel(CartpoleArgs a, int a
         __syncthreads();
         // ---- layer 2, transposed as well (the weights are the row operand): lane (column j, k group q) reads 8
         //      consecutive activations of its roll-out per term and step and ends with neurons 16 wave + 4 q + i ----
-        floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};  // h h'
-        floatx4 low2 = {0.f, 0.f, 0.f, 0.f};  // 2^11 (h m' + m h')
+        floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};  // h h' + h m' + m h', the small partial products first
         const unsigned char* src = hb + j * kRowB + 16 * q;
+        f16x8 at[KS2][2];
+#pragma unroll
+        for (int s2 = 0; s2 < KS2; ++s2)
+#pragma unroll
+          for (int k = 0; k < 2; ++k) at[s2][k] = *reinterpret_cast<const f16x8*>(src + k * kTermB + 64 * s2);
 #pragma unroll
         for (int s2 = 0; s2 < KS2; ++s2) {
-          f16x8 at[2];
-#pragma unroll
-          for (int k = 0; k < 2; ++k) at[k] = *reinterpret_cast<const f16x8*>(src + k * kTermB + 64 * s2);
-          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[1], low2, 0, 0, 0);
-          low2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[1][s2], at[0], low2, 0, 0, 0);
-          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[0], acc2, 0, 0, 0);
+          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[s2][1], acc2, 0, 0, 0);
+          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[1][s2], at[s2][0], acc2, 0, 0, 0);
         }
 #pragma unroll
+        for (int s2 = 0; s2 < KS2; ++s2)
+          acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w2b[0][s2], at[s2][0], acc2, 0, 0, 0);
+#pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float pre = fmaf(low2[i], kSplitLowUnscale, acc2[i]);  // layer-2 product times the two scales
+          const float pre = acc2[i];  // layer-2 product times the two scales
           if (TANH)
             p[i] = fmaf(m2w3t[i], __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(fmaf(pre, k_u2, k_b2t[i])) + 1.0f),
                         w3t[i]);

@@ -48,7 +48,7 @@ def test_logits_and_fitness_against_oracle(evo, H, pop, B, digits, scale):
 @pytest.mark.parametrize("H", [64, 128])
 def test_zero_weights_and_any_finite_magnitude(evo, H):
     """Zero weights give ln 10; recurrent or output weights beyond what the default scale of the fp16 operands
-    holds (255.9) send the member through the second build of the kernel, which scales each wave's weights
+    holds (15.99) send the member through the second build of the kernel, which scales each wave's weights
     by their own largest magnitude: the oracle's logits again."""
     B = 20
     P = os2s.param_count(H)
