@@ -34,11 +34,9 @@
 // four consecutive pixels: four 4-byte LDS reads), once against the leading terms of the pixels (lane groups
 // 0, 1) and once against their residual terms (lane groups 2, 3), which fills K = 32.  The 16 rows are
 // (8 output channels) x (the window's two pixel columns); one set of weight operands per pixel row of the
-// window (the stencil shifted inside the patch, zeros elsewhere).  With the residual-side factor 2^-11 folded
-// into the weight operands, h h' + 2^-11 (m' h + h' m) takes two instructions into ONE accumulator:
-// (h | h 2^-11) and (m 2^-11 | 0) against (h' | m').  (fp16 values of h 2^-11 below 2^-14 vanish: weights
-// more than 2^17 below the largest of their channel then carry 11 bits, which is below 2^-28 of the channel's
-// activations.)  Row order (channel pair, column, channel parity) puts a window's two columns of channels
+// window (the stencil shifted inside the patch, zeros elsewhere).  With the residual terms stored as they are
+// (split16.h: the matrix instruction keeps half-precision subnormals), h h' + m' h + h' m takes two
+// instructions into ONE accumulator: (h | h) and (m | 0) against (h' | m').  Row order (channel pair, column, channel parity) puts a window's two columns of channels
 // 2 q, 2 q + 1 into the four accumulator registers of lane group q: pooling is three maxima per channel on
 // registers; one swap between neighbouring lane groups and one between the halves of the wave then collect a
 // window's four channel pairs, and the pooled pixel goes to the band buffers as one 16-byte store per term.
@@ -203,7 +201,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // window, k = 4 r + c in lane groups 0, 1 (patch rows 0, 1 and 2, 3) against the leading terms of the pixels
   // and again in lane groups 2, 3 against their residual terms; w1a[t] holds the weights shifted to the
   // window's pixel row t (tap (r - t, c - s), zero outside the 3 x 3 stencil).  One instruction with
-  // (h | h 2^-11) and one with (m 2^-11 | 0) give h h' + 2^-11 (m' h + h' m) in a single accumulator.  Each
+  // (h | h) and one with (m | 0), m and m' being the residuals themselves, give h h' + m' h + h' m in a single
+  // accumulator.  Each
   // channel has its own power of two (its weights' largest magnitude), taken out again by the epilogue.
   f16x8 w1a[2][2];      // [pixel row t][instruction]
   float sw1_row;        // scale of the channel of this lane's A row
@@ -239,7 +238,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         w *= sw1_row;
         const _Float16 h = static_cast<_Float16>(w);
         const float hf = static_cast<float>(h), mf = (w - hf) * kSplitLowScale;
-        x1[j] = half ? hf * kSplitLowUnscale : hf;
+        x1[j] = hf;
         x2[j] = half ? 0.f : static_cast<float>(static_cast<_Float16>(mf)) * kSplitLowUnscale;
       }
 #pragma unroll
@@ -358,8 +357,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       const int i = lane + 64 * j;
       const int y = i / row4, x4 = i - y * row4;
       uint32_t lead_o, resid_o, lead_m, resid_m;
-      split2_pair(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
-      split2_pair(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
+      split2_pair_true(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
+      split2_pair_true(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
       uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead_o, 0x138, 0xf, 0xf, false);    // wave_shr:1
       uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid_o, 0x138, 0xf, 0xf, false);
       last_lead = __builtin_amdgcn_readlane(lead_o, 63);
