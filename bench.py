@@ -37,11 +37,11 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2924945,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 33468888,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
-    "cfg3": 19117076,      # profiles/cartpole_kernel_cfg3.md
+    "cfg2": 33456128,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
+    "cfg3": 19116032,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4305387571,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
-    "seq2seq": 903251968,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
+    "seq2seq": 890661888,  # profiles/lstm_seq2seq_kernel_seq2seq.md (algorithmic 598 MB: the rest is register spill traffic)
     "forage": 6944738,     # profiles/world_step_kernel_forage.md (per step launch: weights 5.8 MB + positions)
     "forage_solo": 5993764,  # profiles/world_solo_kernel_forage_solo.md (the weights, read once; the rest stays on chip)
 }
@@ -52,13 +52,13 @@ MEASURED_TRAFFIC_BYTES = {
 # What the rocprofv3 counters in profiles/ say bounds the dominant kernel.
 BOUND_DETAIL = {
     "cfg1": "launch latency: five launches of a few microseconds each (profiles/mlp_f32_kernel_cfg1.md)",
-    "cfg2": "both convolutions on the matrix cores: MFMA busy 32 % + VALU busy 60 % on the same SIMDs (9 % of the cycles overlap), LDS busy 76 %, "
-            "21 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
-    "cfg3": "vector-instruction issue along a 1000-step dependency chain: VALU busy 67 %, MFMA busy 20 %, 35 % of wave "
+    "cfg2": "both convolutions on the matrix cores: MFMA busy 33 % + VALU busy 58 % on the same SIMDs (9 % of the cycles overlap), LDS busy 78 %, "
+            "22 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
+    "cfg3": "vector-instruction issue along a 1000-step dependency chain: VALU busy 66 %, MFMA busy 21 %, 36 % of wave "
             "time waiting (profiles/cartpole_kernel_cfg3.md)",
     "cfg4": "HBM weight stream: 64 flop per weight byte (profiles/mlp_bf16_stream_kernel_cfg4.md)",
     "cfg5": "HBM write of the population in ask (profiles/ask_sphere_tell_kernels_cfg5.md)",
-    "seq2seq": "instruction issue: VALU busy 48 % + MFMA busy 37 %, which add up (profiles/lstm_seq2seq_kernel_seq2seq.md)",
+    "seq2seq": "instruction issue: VALU busy 44 % + MFMA busy 37 %, 29 % of wave time waiting (profiles/lstm_seq2seq_kernel_seq2seq.md)",
     "forage": "latency of one step launch: vector ALU 20 % busy (profiles/world_step_kernel_forage.md)",
     "forage_solo": "one dependent chain per step: vector ALU 66 % busy (profiles/world_solo_kernel_forage_solo.md)",
 }
