@@ -254,7 +254,6 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
           for (int g = 0; g < 4; ++g) w_max = fmaxf(w_max, fabsf(Wh[k * G4 + g * H + 16 * wave + j]));
         s_w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w_max)))));
       }
-      float xlo[4][4];  // rows e = 0..3 of the current step, kept until rows 4..7 arrive
 #pragma unroll
       for (int p0 = 0; p0 < kPieces; p0 += kBatch) {
         f32x4 raw[kBatch][kVecPerThread];
@@ -285,18 +284,22 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
               x[g][e] = s_w * tab[(4 * q + e) * kTabRow + g * H + 16 * wave + j];
               if (!DYNAMIC) range_max = fmaxf(range_max, fabsf(x[g][e]));
             }
-          if ((pc & 1) == 0) {
+          // rows e = 0..3 (4..7) of the step are the first (second) two words of the operands: split as they arrive.
+          // The second build's weights may lie far below their wave's largest one: their residuals are kept.
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
+          for (int g = 0; g < 4; ++g) {
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 l = __builtin_bit_cast(u32x4, wh[0][g][pc >> 1]), r = __builtin_bit_cast(u32x4, wh[1][g][pc >> 1]);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) xlo[g][e] = x[g][e];
-          } else {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const float x8[8] = {xlo[g][0], xlo[g][1], xlo[g][2], xlo[g][3], x[g][0], x[g][1], x[g][2], x[g][3]};
-              // the second build's weights may lie far below their wave's largest one: their residuals are kept
-              split2_x8_true<DYNAMIC>(x8, wh[0][g][pc >> 1], wh[1][g][pc >> 1]);
+            for (int w = 0; w < 2; ++w) {
+              uint32_t lw, rw;
+              if (DYNAMIC) split2_pair_true_kept(x[g][2 * w], x[g][2 * w + 1], lw, rw);
+              else split2_pair_true(x[g][2 * w], x[g][2 * w + 1], lw, rw);
+              l[2 * (pc & 1) + w] = lw;
+              r[2 * (pc & 1) + w] = rw;
             }
+            wh[0][g][pc >> 1] = __builtin_bit_cast(f16x8, l);
+            wh[1][g][pc >> 1] = __builtin_bit_cast(f16x8, r);
           }
         }
         __builtin_amdgcn_sched_barrier(0);  // the next batch is fetched only now: its registers are the ones just freed
