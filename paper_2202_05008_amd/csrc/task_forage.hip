@@ -71,12 +71,26 @@ template <int STAGE>
 __device__ __forceinline__ int partner_bits(int x) {
   // quad_perm 1,0,3,2 / quad_perm 2,3,0,1 / row_half_mirror / row_mirror
   constexpr int ctrl = STAGE == 0 ? 0xB1 : STAGE == 1 ? 0x4E : STAGE == 2 ? 0x141 : 0x140;
-  return __builtin_amdgcn_update_dpp(x, x, ctrl, 0xF, 0xF, false);
+  // every lane has a partner in these patterns, so the value for lanes without one is never used
+  return __builtin_amdgcn_update_dpp(0, x, ctrl, 0xF, 0xF, true);
 }
 template <int STAGE>
 __device__ __forceinline__ float partner(float x) {
   return __int_as_float(partner_bits<STAGE>(__float_as_int(x)));
 }
+// Value of the lane N places away in the rotation of a row of sixteen lanes (the lanes of one agent when it has
+// sixteen), again register to register.  Which way the hardware rotates does not matter to the callers: they
+// apply the same move to the lane number to learn whose value they receive.
+template <int N>
+__device__ __forceinline__ int rotated_bits(int x) {
+  static_assert(N >= 1 && N <= 15, "a rotation inside a row");
+  return __builtin_amdgcn_update_dpp(0, x, 0x120 + N, 0xF, 0xF, true);  // row_ror:N
+}
+template <int N>
+__device__ __forceinline__ float rotated(float x) {
+  return __int_as_float(rotated_bits<N>(__float_as_int(x)));
+}
+
 // Sum over an agent's LPA lanes (8 or 16), left in every one of them.
 template <int LPA = kLanesPerAgent>
 __device__ __forceinline__ float agent_sum(float x) {
@@ -146,8 +160,12 @@ __device__ __forceinline__ void nearest_scan16(Nearest& n, float2 p, const float
 // Merge over the lanes of an agent (smaller distance, then lower index) and read the offset back.
 template <int LPA = kLanesPerAgent>
 __device__ __forceinline__ float2 nearest_finish(Nearest n, float2 p, const float2* s, int limit) {
+  // smaller distance, then lower index = smaller 64-bit key (distance bits, index): a distance is a sum of
+  // squares or the initial infinity, and non-negative floats order like their bit patterns
   auto merge = [&](float od, int oi) {
-    const bool take = od < n.d2 || (od == n.d2 && oi < n.idx);
+    const uint64_t mine = (static_cast<uint64_t>(__float_as_uint(n.d2)) << 32) | static_cast<uint32_t>(n.idx);
+    const uint64_t other = (static_cast<uint64_t>(__float_as_uint(od)) << 32) | static_cast<uint32_t>(oi);
+    const bool take = other < mine;
     n.d2 = take ? od : n.d2;
     n.idx = take ? oi : n.idx;
   };
@@ -178,9 +196,48 @@ struct PolicySlice {
   static constexpr int HQ = H / LPA;
   static_assert(HQ >= 2 && HQ % 2 == 0, "a lane's columns are loaded two at a time");
   static constexpr int kRows2 = H <= 32 ? H : 8;   // rows of W2 held here; the rest is read when it is used
+  // With sixteen lanes per agent and the whole of W2 held here, the rows sit in the order in which the hidden
+  // activations reach the lane by rotations of its row: w2[n HQ + v] is the row of activation v of the lane whose
+  // value rotation n delivers (n = 0: the lane's own), so layer 2 needs no gather at all.
+  static constexpr bool kRotated = LPA == 16 && kRows2 == H;
   float w1[kObs][HQ], b1[HQ], w2[kRows2][HQ], b2[HQ], w3[HQ][2], b3[2];
   const float* rest;  // &W2[kRows2][c0]
 };
+
+// Rows of W2 in rotation order (see PolicySlice): rotation N delivers the value of lane `from`.
+template <int H, int LPA, int N>
+__device__ __forceinline__ void rotated_rows(const float* __restrict__ W2, int q, int c0, PolicySlice<H, LPA>& s) {
+  constexpr int HQ = PolicySlice<H, LPA>::HQ;
+  if constexpr (N < 16) {
+    int from = q;
+    if constexpr (N > 0) from = rotated_bits<N>(q);
+#pragma unroll
+    for (int v = 0; v < HQ; ++v)
+#pragma unroll
+      for (int u = 0; u < HQ; u += 2) {
+        const float2 w = *reinterpret_cast<const float2*>(W2 + (from * HQ + v) * H + c0 + u);
+        s.w2[N * HQ + v][u] = w.x, s.w2[N * HQ + v][u + 1] = w.y;
+      }
+    rotated_rows<H, LPA, N + 1>(W2, q, c0, s);
+  }
+}
+// Layer 2 on activations that arrive by rotation: part[u] += h[from][v] W2[from HQ + v][c0 + u] for every lane of
+// the agent in turn.
+template <int H, int LPA, int N>
+__device__ __forceinline__ void rotated_layer(const PolicySlice<H, LPA>& s, const float (&mine)[H / LPA],
+                                              float (&part)[H / LPA]) {
+  constexpr int HQ = H / LPA;
+  if constexpr (N < 16) {
+#pragma unroll
+    for (int v = 0; v < HQ; ++v) {
+      float x = mine[v];
+      if constexpr (N > 0) x = rotated<N>(mine[v]);
+#pragma unroll
+      for (int u = 0; u < HQ; ++u) part[u] = fmaf(x, s.w2[N * HQ + v][u], part[u]);
+    }
+    rotated_layer<H, LPA, N + 1>(s, mine, part);
+  }
+}
 
 template <int H, int LPA>
 __device__ __forceinline__ void policy_load(const float* __restrict__ th, int q, PolicySlice<H, LPA>& s) {
@@ -202,8 +259,12 @@ __device__ __forceinline__ void policy_load(const float* __restrict__ th, int q,
 #pragma unroll
   for (int i = 0; i < kObs; ++i) row(W1 + i * H, s.w1[i]);
   row(b1, s.b1);
+  if constexpr (PolicySlice<H, LPA>::kRotated) {
+    rotated_rows<H, LPA, 0>(W2, q, c0, s);
+  } else {
 #pragma unroll
-  for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i) row(W2 + i * H, s.w2[i]);
+    for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i) row(W2 + i * H, s.w2[i]);
+  }
   s.rest = W2 + PolicySlice<H, LPA>::kRows2 * H + c0;
   row(b2, s.b2);
 #pragma unroll
@@ -238,21 +299,28 @@ __device__ __forceinline__ float2 policy_forward(const PolicySlice<H, LPA>& s, c
     for (int u = 0; u < HQ; ++u) part[u] = fmaf(obs[i], s.w1[i][u], part[u]);
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = activate(part[u], act[0]);
-  gather_agent<H, LPA>(part, lane, full);
+  if constexpr (PolicySlice<H, LPA>::kRotated) {
+    float h1[HQ];
 #pragma unroll
-  for (int u = 0; u < HQ; ++u) part[u] = s.b2[u];
+    for (int u = 0; u < HQ; ++u) h1[u] = part[u], part[u] = s.b2[u];
+    rotated_layer<H, LPA, 0>(s, h1, part);
+  } else {
+    gather_agent<H, LPA>(part, lane, full);
 #pragma unroll
-  for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i)
+    for (int u = 0; u < HQ; ++u) part[u] = s.b2[u];
 #pragma unroll
-    for (int u = 0; u < HQ; ++u) part[u] = fmaf(full[i], s.w2[i][u], part[u]);
+    for (int i = 0; i < PolicySlice<H, LPA>::kRows2; ++i)
+#pragma unroll
+      for (int u = 0; u < HQ; ++u) part[u] = fmaf(full[i], s.w2[i][u], part[u]);
 #pragma unroll 16
-  for (int i = PolicySlice<H, LPA>::kRows2; i < H; ++i)
+    for (int i = PolicySlice<H, LPA>::kRows2; i < H; ++i)
 #pragma unroll
-    for (int u = 0; u < HQ; u += 2) {
-      const float2 w = *reinterpret_cast<const float2*>(s.rest + (i - PolicySlice<H, LPA>::kRows2) * H + u);
-      part[u] = fmaf(full[i], w.x, part[u]);
-      part[u + 1] = fmaf(full[i], w.y, part[u + 1]);
-    }
+      for (int u = 0; u < HQ; u += 2) {
+        const float2 w = *reinterpret_cast<const float2*>(s.rest + (i - PolicySlice<H, LPA>::kRows2) * H + u);
+        part[u] = fmaf(full[i], w.x, part[u]);
+        part[u + 1] = fmaf(full[i], w.y, part[u + 1]);
+      }
+  }
 #pragma unroll
   for (int u = 0; u < HQ; ++u) part[u] = activate(part[u], act[1]);
   float o0 = 0.f, o1 = 0.f;
