@@ -286,9 +286,12 @@ __device__ __forceinline__ void gather_agent(const float (&mine)[H / LPA], int l
 }
 
 // The policy of dims (8, H, H, 2) for one agent; every lane of the agent returns both outputs.
-template <int H, int LPA>
-__device__ __forceinline__ float2 policy_forward(const PolicySlice<H, LPA>& s, const int (&act)[3], int lane,
+// TANH: all three activations are tanh (the usual policy), known when the kernel is built: no switch per value.
+template <int H, int LPA, bool TANH = false>
+__device__ __forceinline__ float2 policy_forward(const PolicySlice<H, LPA>& s, const int (&act_rt)[3], int lane,
                                                  const float (&obs)[kObs]) {
+  const int act[3] = {TANH ? EVO_ACT_TANH : act_rt[0], TANH ? EVO_ACT_TANH : act_rt[1],
+                      TANH ? EVO_ACT_TANH : act_rt[2]};
   constexpr int HQ = PolicySlice<H, LPA>::HQ;
   float part[HQ], full[H];
 #pragma unroll
@@ -364,7 +367,7 @@ __device__ __forceinline__ int touch_scan(const WorldConst& c, float2 p, const f
 // two item offsets, as six words (structure of arrays: word w of lane l at [w][l]).
 constexpr int kExchangeWords = 6;
 
-template <int H>
+template <int H, bool TANH>
 __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   extern __shared__ float4 lds4[];
   const int lane = threadIdx.x & 63;
@@ -497,7 +500,7 @@ __global__ __launch_bounds__(kStepThreads) void world_step_kernel(StepArgs a) {
   if (a.actions_in)
     action = a.actions_in[me];
   else
-    action = policy_forward<H>(weights, a.act, lane, obs);
+    action = policy_forward<H, kLanesPerAgent, TANH>(weights, a.act, lane, obs);
 
   move_axis(a.c, action.x, p.x, v.x);
   move_axis(a.c, action.y, p.y, v.y);
@@ -532,7 +535,7 @@ struct SoloArgs {
   uint32_t* counts_out;  // [worlds][pop][n_items] or null: times each item was eaten
 };
 
-template <int H, int LPA>
+template <int H, int LPA, bool TANH>
 __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloArgs a) {
   constexpr int kMembers = 64 / LPA;  // members per wave
   extern __shared__ float4 lds4[];
@@ -591,7 +594,7 @@ __global__ __launch_bounds__(64 * kWorldsPerBlock) void world_solo_kernel(SoloAr
     const float2 f = nearest_finish<LPA>(food, p, my_food, food_pad);
     const float2 g = nearest_finish<LPA>(poison, p, my_poison, poison_pad);
     const float obs[kObs] = {v.x, v.y, f.x, f.y, g.x, g.y, 0.f, 0.f};  // nobody else is there
-    const float2 action = policy_forward<H, LPA>(weights, a.act, lane, obs);
+    const float2 action = policy_forward<H, LPA, TANH>(weights, a.act, lane, obs);
     move_axis(a.c, action.x, p.x, v.x);
     move_axis(a.c, action.y, p.y, v.y);
     // touches: the lane that judges a slot also moves the item it finds eaten
@@ -715,23 +718,28 @@ static int fill_const(const float* cp, WorldConst* c) {
   return EVO_OK;
 }
 
-template <int H>
-static int launch_step(const StepArgs& a, hipStream_t s) {
+template <int H, bool TANH>
+static int launch_step_built(const StepArgs& a, hipStream_t s) {
   const dim3 grid((a.pop + kAgentsPerBlock - 1) / kAgentsPerBlock, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
   // more than 64 KB of dynamic LDS has to be asked for, once per kernel and device
   static std::atomic<bool> raised[64];  // zero-initialised; a second setter does the same harmless call
   int device = 0;
   hipError_t e = hipGetDevice(&device);
   if (e == hipSuccess && device >= 0 && device < 64 && !raised[device].load()) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_step_kernel<H>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_step_kernel<H, TANH>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
     raised[device].store(e == hipSuccess);
   }
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "forage: raising the LDS limit of the step kernel failed: %s",
               hipGetErrorString(e));
-  hipLaunchKernelGGL(world_step_kernel<H>, grid, dim3(kStepThreads),
+  hipLaunchKernelGGL((world_step_kernel<H, TANH>), grid, dim3(kStepThreads),
                      step_lds_bytes(a.pop, a.c.n_food, a.c.n_items), s, a);
   return check_launch("world_step_kernel");
+}
+template <int H>
+static int launch_step(const StepArgs& a, hipStream_t s) {
+  const bool all_tanh = a.act[0] == EVO_ACT_TANH && a.act[1] == EVO_ACT_TANH && a.act[2] == EVO_ACT_TANH;
+  return all_tanh ? launch_step_built<H, true>(a, s) : launch_step_built<H, false>(a, s);
 }
 
 static int launch_step_for(int H, const StepArgs& a, hipStream_t s) {
@@ -837,15 +845,15 @@ static size_t solo_lds_bytes(int n_food, int n_items, int lanes) {
   return static_cast<size_t>(kWorldsPerBlock) * (64 / lanes) * slots * (sizeof(float2) + sizeof(uint32_t));
 }
 
-template <int H>
-static int launch_solo(const SoloArgs& a, hipStream_t s) {
+template <int H, bool TANH>
+static int launch_solo_built(const SoloArgs& a, hipStream_t s) {
   constexpr int LPA = solo_lanes(H);
   const size_t lds = solo_lds_bytes(a.c.n_food, a.c.n_items, LPA);
   static std::atomic<bool> raised[64];  // zero-initialised; a second setter does the same harmless call
   int device = 0;
   hipError_t e = hipGetDevice(&device);
   if (e == hipSuccess && device >= 0 && device < 64 && !raised[device].load()) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H, LPA>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&world_solo_kernel<H, LPA, TANH>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kMaxLdsBytes));
     raised[device].store(e == hipSuccess);
   }
@@ -853,8 +861,13 @@ static int launch_solo(const SoloArgs& a, hipStream_t s) {
               hipGetErrorString(e));
   constexpr int members = 64 / LPA;
   const dim3 grid((a.pop + members - 1) / members, (a.worlds + kWorldsPerBlock - 1) / kWorldsPerBlock);
-  hipLaunchKernelGGL((world_solo_kernel<H, LPA>), grid, dim3(64 * kWorldsPerBlock), lds, s, a);
+  hipLaunchKernelGGL((world_solo_kernel<H, LPA, TANH>), grid, dim3(64 * kWorldsPerBlock), lds, s, a);
   return check_launch("world_solo_kernel");
+}
+template <int H>
+static int launch_solo(const SoloArgs& a, hipStream_t s) {
+  const bool all_tanh = a.act[0] == EVO_ACT_TANH && a.act[1] == EVO_ACT_TANH && a.act[2] == EVO_ACT_TANH;
+  return all_tanh ? launch_solo_built<H, true>(a, s) : launch_solo_built<H, false>(a, s);
 }
 
 int forage_solo_supported(const MlpShape& sh, int pop, int worlds, const float* cp) {
