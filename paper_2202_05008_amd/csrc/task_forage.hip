@@ -230,10 +230,24 @@ __device__ __forceinline__ void rotated_layer(const PolicySlice<H, LPA>& s, cons
   if constexpr (N < 16) {
 #pragma unroll
     for (int v = 0; v < HQ; ++v) {
-      float x = mine[v];
-      if constexpr (N > 0) x = rotated<N>(mine[v]);
 #pragma unroll
-      for (int u = 0; u < HQ; ++u) part[u] = fmaf(x, s.w2[N * HQ + v][u], part[u]);
+      for (int u = 0; u < HQ; ++u) {
+        if constexpr (N == 0) {
+          part[u] = fmaf(mine[v], s.w2[v][u], part[u]);
+        } else {
+          // the rotation rides in the multiply-add itself (the compiler keeps it as a move of its own).  A lane
+          // move may not read a register in the two instructions after it is written: the first of these
+          // statements brings its own wait, the others read registers written long before
+          if constexpr (N == 1)
+            asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_ror:%3 row_mask:0xf bank_mask:0xf bound_ctrl:0"
+                : "+v"(part[u])
+                : "v"(mine[v]), "v"(s.w2[N * HQ + v][u]), "n"(N));
+          else
+            asm("v_fmac_f32_dpp %0, %1, %2 row_ror:%3 row_mask:0xf bank_mask:0xf bound_ctrl:0"
+                : "+v"(part[u])
+                : "v"(mine[v]), "v"(s.w2[N * HQ + v][u]), "n"(N));
+        }
+      }
     }
     rotated_layer<H, LPA, N + 1>(s, mine, part);
   }
