@@ -60,7 +60,7 @@ BOUND_DETAIL = {
     "cfg5": "HBM write of the population in ask (profiles/ask_sphere_tell_kernels_cfg5.md)",
     "seq2seq": "instruction issue: VALU busy 44 % + MFMA busy 37 %, 29 % of wave time waiting (profiles/lstm_seq2seq_kernel_seq2seq.md)",
     "forage": "latency of one step launch: vector ALU 20 % busy (profiles/world_step_kernel_forage.md)",
-    "forage_solo": "vector-instruction issue along the step chain: vector ALU 88 % busy (profiles/world_solo_kernel_forage_solo.md)",
+    "forage_solo": "vector-instruction issue along the step chain: vector ALU 82 % busy (profiles/world_solo_kernel_forage_solo.md)",
 }
 
 DEFAULT_STEPS = {"cfg1": 200, "cfg2": 50, "cfg3": 20, "cfg4": 50, "cfg5": 20, "seq2seq": 20, "forage": 20, "forage_solo": 50}
