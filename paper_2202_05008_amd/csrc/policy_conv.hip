@@ -237,9 +237,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         for (int tap = 0; tap < 9; ++tap) w = (3 * dy + dx == tap && dx >= 0 && dx <= 2 && dy >= 0 && dy <= 2) ? wt[tap] : w;
         w *= sw1_row;
         const _Float16 h = static_cast<_Float16>(w);
-        const float hf = static_cast<float>(h), mf = (w - hf) * kSplitLowScale;
+        const float hf = static_cast<float>(h);
         x1[j] = hf;
-        x2[j] = half ? 0.f : static_cast<float>(static_cast<_Float16>(mf)) * kSplitLowUnscale;
+        x2[j] = half ? 0.f : w - hf;  // the residual, exact in fp32; converted singly below (subnormals kept)
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {

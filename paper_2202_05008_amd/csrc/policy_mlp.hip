@@ -91,8 +91,8 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
         const int d = 4 * (part + 8 * c);
         if (d < KP) {
           uint2 lead, resid;
-          split2_pair(sc * v[c].x, sc * v[c].y, lead.x, resid.x);
-          split2_pair(sc * v[c].z, sc * v[c].w, lead.y, resid.y);
+          split2_pair_true(sc * v[c].x, sc * v[c].y, lead.x, resid.x);
+          split2_pair_true(sc * v[c].z, sc * v[c].w, lead.y, resid.y);
           *reinterpret_cast<uint2*>(at + smp * kRowB + d * 2) = lead;
           *reinterpret_cast<uint2*>(at + kTermB + smp * kRowB + d * 2) = resid;
         }
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
       for (int d = 2 * part; d < KP; d += 16) {
         const float x0 = (live && d < D) ? sc * row[d] : 0.f, x1 = (live && d + 1 < D) ? sc * row[d + 1] : 0.f;
         uint32_t lead, resid;
-        split2_pair(x0, x1, lead, resid);
+        split2_pair_true(x0, x1, lead, resid);
         *reinterpret_cast<uint32_t*>(at + smp * kRowB + d * 2) = lead;
         *reinterpret_cast<uint32_t*>(at + kTermB + smp * kRowB + d * 2) = resid;
       }
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
         if (st < KS) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) raw[st][e] *= s_w;
-          split2_x8(raw[st], wa[0][st], wa[1][st]);
+          split2_x8_true<false>(raw[st], wa[0][st], wa[1][st]);
         }
       }
       float b4[4];
@@ -217,22 +217,22 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
       // ---- four sample tiles ----
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        floatx4m acc = {0.f, 0.f, 0.f, 0.f}, low = {0.f, 0.f, 0.f, 0.f};
+        floatx4m acc = {0.f, 0.f, 0.f, 0.f};  // all three partial products (residual terms unscaled)
         const unsigned char* src = at + (16 * ct + j) * kRowB + 16 * q;
 #pragma unroll
         for (int st = 0; st < kMfmaKSteps; ++st) {
           if (st < KS) {
             const f16x8 x0 = *reinterpret_cast<const f16x8*>(src + 64 * st);
             const f16x8 x1 = *reinterpret_cast<const f16x8*>(src + kTermB + 64 * st);
-            low = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[0][st], x1, low, 0, 0, 0);
-            low = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[1][st], x0, low, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[0][st], x1, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[1][st], x0, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[0][st], x0, acc, 0, 0, 0);
           }
         }
         const float u = u_s[ct] * u_w;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float v = activate(fmaf(fmaf(low[i], kSplitLowUnscale, acc[i]), u, b4[i]), act);
+          const float v = activate(fmaf(acc[i], u, b4[i]), act);
           held[slot][ct][i] = v;
           m_s[ct] = fmaxf(m_s[ct], fabsf(v));
         }
@@ -281,8 +281,8 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
         uint2 lead, resid;
-        split2_pair(s_new[ct] * held[slot][ct][0], s_new[ct] * held[slot][ct][1], lead.x, resid.x);
-        split2_pair(s_new[ct] * held[slot][ct][2], s_new[ct] * held[slot][ct][3], lead.y, resid.y);
+        split2_pair_true(s_new[ct] * held[slot][ct][0], s_new[ct] * held[slot][ct][1], lead.x, resid.x);
+        split2_pair_true(s_new[ct] * held[slot][ct][2], s_new[ct] * held[slot][ct][3], lead.y, resid.y);
         unsigned char* dst = at + (16 * ct + j) * kRowB + (16 * nt + 4 * q) * 2;
         *reinterpret_cast<uint2*>(dst) = lead;
         *reinterpret_cast<uint2*>(dst + kTermB) = resid;
