@@ -231,12 +231,22 @@ __global__ __launch_bounds__(64 * kMfmaWaves, 2) void mlp_f32_mfma_kernel(MlpArg
         }
         const float u = u_s[ct] * u_w;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float v = activate(fmaf(acc[i], u, b4[i]), act);
-          held[slot][ct][i] = v;
-          m_s[ct] = fmaxf(m_s[ct], fabsf(v));
-        }
+        for (int i = 0; i < 4; ++i) held[slot][ct][i] = fmaf(acc[i], u, b4[i]);
       }
+      // the activation of the tile's sixteen values per lane, switched once and not per value
+      auto apply = [&](auto f) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float v = f(held[slot][ct][i]);
+            held[slot][ct][i] = v;
+            m_s[ct] = fmaxf(m_s[ct], fabsf(v));
+          }
+      };
+      if (act == EVO_ACT_TANH) apply([](float x) { return tanh_fast_accurate(x); });
+      else if (act == EVO_ACT_RELU) apply([](float x) { return fmaxf(x, 0.f); });
+      else apply([](float x) { return x; });
     }
     if (last) {
       __syncthreads();  // every wave has read the layer's input: the buffer takes the network's output
