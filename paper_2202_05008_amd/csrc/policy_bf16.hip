@@ -185,7 +185,10 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
 
 __device__ __forceinline__ float act_f(float v, int act) {
   if (act == EVO_ACT_TANH) return tanhf(v);
-  if (act == EVO_ACT_RELU) return fmaxf(v, 0.f);
+  // max(v, 0) on the bit pattern as a signed integer: every negative float (and -0) is a negative integer, the
+  // others order like themselves; one instruction where the floating-point maximum of a matrix result needs a
+  // canonicalising move first, and a NaN stays a NaN
+  if (act == EVO_ACT_RELU) return __int_as_float(max(__float_as_int(v), 0));
   return v;
 }
 
