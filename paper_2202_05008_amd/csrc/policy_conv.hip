@@ -111,7 +111,8 @@ __device__ __forceinline__ void wave_sync() {
 // no LDS round trip, every lane of the row ends with the result, the order is fixed.
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+  // every lane has a source in these patterns: no value has to be prepared for lanes without one
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 __device__ __forceinline__ float row16_sum(float v) {
   v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
@@ -126,6 +127,16 @@ __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, dpp_mov<0x141>(v));
   v = fmaxf(v, dpp_mov<0x140>(v));
   return v;
+}
+// The same for magnitudes (non-negative floats order like their bit patterns): integer maxima, which take the
+// moved value as an operand and need no canonicalising moves.
+__device__ __forceinline__ float row16_max_magnitude(float v) {
+  int b = __float_as_int(v);
+  b = max(b, __float_as_int(dpp_mov<0xB1>(__int_as_float(b))));
+  b = max(b, __float_as_int(dpp_mov<0x4E>(__int_as_float(b))));
+  b = max(b, __float_as_int(dpp_mov<0x141>(__int_as_float(b))));
+  b = max(b, __float_as_int(dpp_mov<0x140>(__int_as_float(b))));
+  return __int_as_float(b);
 }
 
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
@@ -322,7 +333,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
     // scales of this image (all wave-uniform; non-negative floats order like their bit patterns): of its
     // pixels from their largest magnitude, of its conv1 activations from the bound on them
-    px_max = row16_max(px_max);
+    px_max = row16_max_magnitude(px_max);
     const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
                                      __builtin_amdgcn_readlane(__float_as_uint(px_max), 16)),
                                  max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 32),
