@@ -518,9 +518,10 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       const int y = a.labels[im];  // a label outside [0, n_cls) contributes logit 0
       const float lv = cls < n_cls ? logit : -INFINITY;
       const float mx = row16_max(lv);
-      const float se = row16_sum(cls < n_cls ? expf(lv - mx) : 0.f);
+      // the hardware's exp2 and log2 (one ulp each): the terms are at most one and their sum lies in [1, 16]
+      const float se = row16_sum(cls < n_cls ? __builtin_amdgcn_exp2f(1.4426950408889634f * (lv - mx)) : 0.f);
       const float picked = row16_sum(cls == y ? lv : 0.f);
-      loss_sum += (mx + logf(se)) - picked;
+      loss_sum += (mx + 0.6931471805599453f * __builtin_amdgcn_logf(se)) - picked;
     }
     wave_sync();
   }
