@@ -373,12 +373,12 @@ __global__ __launch_bounds__(4 * H) void lstm_seq2seq_kernel(LstmArgs a) {
             float se = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (4 * q + i < n_out) se += expf(z[i] - mx);
+              if (4 * q + i < n_out) se += __builtin_amdgcn_exp2f(kLog2e * (z[i] - mx));  // one ulp; the terms are at most one
             se += __shfl_xor(se, 16, 64);
             se += __shfl_xor(se, 32, 64);
             picked += __shfl_xor(picked, 16, 64);
             picked += __shfl_xor(picked, 32, 64);
-            if (valid && q == 0) loss_acc += (mx + logf(se)) - picked;
+            if (valid && q == 0) loss_acc += (mx + 0.6931471805599453f * __builtin_amdgcn_logf(se)) - picked;  // se in [1, 16]
           }
         }
       }
