@@ -75,10 +75,15 @@ constexpr int kImgBytes = 2 * kPlaneBytes;           // the padded image as two 
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
 constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as fp16
 constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 2a+1, interleaved pixel by pixel
-constexpr int kBandTerm = 2 * kBandRowPair;          // 1024 bytes: four rows of one split term
-constexpr int kBandBytes = 2 * kBandTerm;            // 2048 bytes per band buffer
-constexpr int kBandFloats = kBandBytes / 4;          // 512
-constexpr int kWaveFloats = kImgBytes / 4 + 3 * kBandFloats;  // 2736 floats = 10,944 bytes per wave
+// The pooled conv1 rows live in a ring of eight rows per split term (row (r + 1) mod 8 for pooled row r, so the
+// border above the image is row 0), followed by copies of rows 0 and 1 as rows 8 and 9: the four rows of a conv2
+// band then always lie at consecutive addresses, starting two rows further with every band and back at row 0
+// every fourth one.
+constexpr int kRingRows = 10;
+constexpr int kBandTerm = (kRingRows / 2) * kBandRowPair;   // 2560 bytes: the ring of one split term
+constexpr int kBandBytes = 2 * kBandTerm;            // 5120 bytes
+constexpr int kBandFloats = kBandBytes / 4;          // 1280
+constexpr int kWaveFloats = kImgBytes / 4 + kBandFloats;  // 2480 floats = 9,920 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -270,25 +275,24 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // Column n of tile m is the window (pooled row 2 b + (n & 1), column 8 m + (n >> 1)): with both pooled rows of the
   // pass in one tile, the patch reads of 32 lanes and the band stores below fall on different banks.  Patch of
   // that window in the image planes (pass 0): term q >> 1, patch rows 2 (q & 1), 2 (q & 1) + 1.  Its pooled pixel
-  // goes to a band buffer twice: rows 1, 2 of the band of the pass and row 3 of the band before (upper pooled
-  // row) or row 0 of the band after (lower one); lane groups 0 and 1 store it (leading and residual term).
+  // goes to ring row 2 u + 1 + (n & 1) in pass b = 4 k + u (and to the copy of that row where it has one);
+  // lane groups 0 and 1 store it (leading and residual term).
   const int n_mt = (H2 + 7) >> 3;   // tiles of 8 window columns x 2 pooled rows per pass
-  int p_off[2], own_off[2], nbr_off[2];
+  int p_off[2], own_off[2];
   bool c1_store[2];
   const bool c1_lower = (n & 1) != 0;
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const int wx = 8 * m + (n >> 1), wxc = min(wx, H2 - 1), rs = n & 1;
     p_off[m] = (q >> 1) * kPlaneBytes + (2 * rs + 2 * (q & 1)) * kPlanePitch + 4 * wxc;
-    own_off[m] = band_off(1 + rs, wxc + 1) + (q & 1) * kBandTerm;
-    nbr_off[m] = band_off(rs ? 0 : 3, wxc + 1) + (q & 1) * kBandTerm;
+    own_off[m] = band_off(1 + rs, wxc + 1) + (q & 1) * kBandTerm;  // for u = 0; two rows = one row pair further per u
     c1_store[m] = wx < H2 && q < 2;
   }
   const bool member_bad = __any(lane_bad);
 
   // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3,
   // shifted by tap 4 step + q (the padding taps 9..11 re-read tap 8 against zero weights)
-  int a_off[2][3];  // bytes from the start of a band buffer
+  int a_off[2][3];  // bytes from the first of the band's four ring rows
   {
     const int r = lane & 15, i = r & 3;
 #pragma unroll
@@ -396,15 +400,20 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     float acc[NCS];  // the dense layer's partial sums of this lane, per class
 #pragma unroll
     for (int c = 0; c < NCS; ++c) acc[c] = 0.f;
-    zero_band_row(bandb, 0);  // band 0, row 0: the border above the image
-    int b3 = 0;               // b mod 3: buffer of band b
+    zero_band_row(bandb, 0);  // ring row 0: the border above the image
+    // Four passes per round of the ring, written out so that every ring address is a lane constant plus an
+    // immediate: pass b = b0 + u stores to ring rows 2 u + 1, 2 u + 2, the conv2 band behind it starts at row
+    // 2 ((u + 3) & 3).
 #pragma unroll 1
-    for (int b = 0; b <= H4; ++b) {
+    for (int b0 = 0; b0 <= H4; b0 += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = b0 + u;
+      if (b > H4) break;
       // ---- conv1 + ReLU + pool, pass b: pooled rows 2b and 2b+1 ----
       if (b == H4) {
-        zero_band_row(bandb + (b3 == 0 ? 2 : b3 - 1) * kBandBytes, 3);  // last band, row 3: the border below the image
+        zero_band_row(bandb, 2 * ((H4 - 1) & 3) + 3);  // the border below the image: last row of the last band
       } else {
-        const int nxt3 = b3 == 2 ? 0 : b3 + 1, prv3 = b3 == 0 ? 2 : b3 - 1;
         const floatx4 c_init = {c1_init[0], c1_init[1], c1_init[0], c1_init[1]};
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
@@ -439,21 +448,19 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             const auto s3 = __builtin_amdgcn_permlane32_swap(sw[1], __float_as_uint(o1[0]), false, false);  // groups 0, 1: own, then L3, R3
             if (c1_store[m]) {
               const uint4 pixel = make_uint4(s2[0], s3[0], s2[1], s3[1]);
-              // own band, and the neighbour band that shares the row
-              *reinterpret_cast<uint4*>(bandb + b3 * kBandBytes + own_off[m]) = pixel;
-              if (c1_lower ? b + 1 < H4 : b >= 1)
-                *reinterpret_cast<uint4*>(bandb + (c1_lower ? nxt3 : prv3) * kBandBytes + nbr_off[m]) = pixel;
+              *reinterpret_cast<uint4*>(bandb + u * kBandRowPair + own_off[m]) = pixel;
+              // ring rows 1 and 8 have a copy (rows 9 and 0)
+              if (u == 0 && !c1_lower) *reinterpret_cast<uint4*>(bandb + 4 * kBandRowPair + own_off[m]) = pixel;
+              if (u == 3 && c1_lower) *reinterpret_cast<uint4*>(bandb - kBandRowPair + own_off[m]) = pixel;
             }
           }
         }
       }
       wave_sync();
-      const int prev3 = b3 == 0 ? 2 : b3 - 1;  // buffer of band b - 1
-      b3 = b3 == 2 ? 0 : b3 + 1;
       if (b == 0) continue;
 
       // ---- conv2 + ReLU + pool, band b-1: two independent tiles (windows 0..3 and 4..7 of the row) --
-      const char* bb = bandb + prev3 * kBandBytes;
+      const char* bb = bandb + ((u + 3) & 3) * kBandRowPair;
       floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h' + h m' + m h' (residual terms unscaled)
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
@@ -486,6 +493,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         for (int c = 0; c < NCS; ++c) acc[c] = fmaf(x1, wr1[c], fmaf(x0, wr0[c], acc[c]));
       }
       wave_sync();
+    }
     }
 
     // transpose-reduce through LDS (the band buffers are free now): lane (c, part) adds 16 partials
