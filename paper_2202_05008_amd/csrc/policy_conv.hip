@@ -306,6 +306,25 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
   }
   char* const bandb = reinterpret_cast<char*>(band);
+  // the same as LDS addresses (32-bit), pinned in one register each (the compiler would rather keep the addends
+  // apart and add them before every access): what is added per band or per step below is an immediate of the
+  // LDS instruction
+  typedef __attribute__((address_space(3))) char lds_char;
+  auto lds_address = [](const char* p) { return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_char*)p)); };
+  auto lds_at = [](uint32_t address, int imm) { return reinterpret_cast<lds_char*>(static_cast<uintptr_t>(address)) + imm; };
+  uint32_t a_abs[2][3], own_abs[2], p_abs[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    own_abs[h] = lds_address(bandb + own_off[h]);
+    p_abs[h] = lds_address(planes + p_off[h]);
+    asm volatile("" : "+v"(own_abs[h]));
+    asm volatile("" : "+v"(p_abs[h]));
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+      a_abs[h][st] = lds_address(bandb + a_off[h][st]);
+      asm volatile("" : "+v"(a_abs[h][st]));
+    }
+  }
   // one padded band row (16 pixels of 16 bytes, both terms) set to zero by lanes 0..31
   auto zero_band_row = [&](char* buf, int row) {
     if (lane < 32) *reinterpret_cast<uint4*>(buf + (lane >> 4) * kBandTerm + band_off(row, lane & 15)) = make_uint4(0, 0, 0, 0);
@@ -419,11 +438,12 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
         for (int m = 0; m < 2; ++m) {
           if (m < n_mt) {
             // the lane's eight patch values: two rows of four consecutive fp16 pixels
-            const char* pp = planes + p_off[m] + b * (4 * kPlanePitch);
+            typedef __attribute__((address_space(3))) const uint32_t lds_u32;
+            const lds_char* pp = lds_at(p_abs[m] + b0 * (4 * kPlanePitch), u * (4 * kPlanePitch));
             typedef uint32_t u32x4c __attribute__((ext_vector_type(4)));
-            const u32x4c pw = {*reinterpret_cast<const uint32_t*>(pp), *reinterpret_cast<const uint32_t*>(pp + 4),
-                               *reinterpret_cast<const uint32_t*>(pp + kPlanePitch),
-                               *reinterpret_cast<const uint32_t*>(pp + kPlanePitch + 4)};
+            const u32x4c pw = {*reinterpret_cast<lds_u32*>(pp), *reinterpret_cast<lds_u32*>(pp + 4),
+                               *reinterpret_cast<lds_u32*>(pp + kPlanePitch),
+                               *reinterpret_cast<lds_u32*>(pp + kPlanePitch + 4)};
             const f16x8 patch = __builtin_bit_cast(f16x8, pw);
             floatx4 o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][0], patch, c_init, 0, 0, 0);
             floatx4 o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][0], patch, c_init, 0, 0, 0);
@@ -447,11 +467,13 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             const auto s2 = __builtin_amdgcn_permlane32_swap(sw[0], __float_as_uint(o0[0]), false, false);  // groups 0, 1: own, then L2, R2
             const auto s3 = __builtin_amdgcn_permlane32_swap(sw[1], __float_as_uint(o1[0]), false, false);  // groups 0, 1: own, then L3, R3
             if (c1_store[m]) {
-              const uint4 pixel = make_uint4(s2[0], s3[0], s2[1], s3[1]);
-              *reinterpret_cast<uint4*>(bandb + u * kBandRowPair + own_off[m]) = pixel;
+              typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
+              const u32x4p pixel = {s2[0], s3[0], s2[1], s3[1]};
+              typedef __attribute__((address_space(3))) u32x4p lds_u4;
+              *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], u * kBandRowPair)) = pixel;
               // ring rows 1 and 8 have a copy (rows 9 and 0)
-              if (u == 0 && !c1_lower) *reinterpret_cast<uint4*>(bandb + 4 * kBandRowPair + own_off[m]) = pixel;
-              if (u == 3 && c1_lower) *reinterpret_cast<uint4*>(bandb - kBandRowPair + own_off[m]) = pixel;
+              if (u == 0 && !c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], 4 * kBandRowPair)) = pixel;
+              if (u == 3 && c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], -kBandRowPair)) = pixel;
             }
           }
         }
@@ -460,15 +482,16 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       if (b == 0) continue;
 
       // ---- conv2 + ReLU + pool, band b-1: two independent tiles (windows 0..3 and 4..7 of the row) --
-      const char* bb = bandb + ((u + 3) & 3) * kBandRowPair;
+      const int bb = ((u + 3) & 3) * kBandRowPair;  // bytes from ring row 0 to the band's first row
       floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h' + h m' + m h' (residual terms unscaled)
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
         f16x8 a0[2], a1[2];  // [term] of tile 0 and tile 1
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-          a0[k] = *reinterpret_cast<const f16x8*>(bb + a_off[0][st] + k * kBandTerm);
-          a1[k] = *reinterpret_cast<const f16x8*>(bb + a_off[1][st] + k * kBandTerm);
+          typedef __attribute__((address_space(3))) const f16x8 lds_f16x8;
+          a0[k] = *reinterpret_cast<lds_f16x8*>(lds_at(a_abs[0][st], bb + k * kBandTerm));
+          a1[k] = *reinterpret_cast<lds_f16x8*>(lds_at(a_abs[1][st], bb + k * kBandTerm));
         }
         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[1], w2b[0][st], acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[1], w2b[0][st], acc1, 0, 0, 0);
