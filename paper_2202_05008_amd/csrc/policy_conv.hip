@@ -5,7 +5,7 @@
 //
 // conv3x3 -> ReLU -> maxpool2 -> conv3x3 -> ReLU -> maxpool2 -> dense, c1 = 8, c2 = 16.
 //
-// Each wavefront runs whole images end to end out of its private 10 KB slice of LDS, with no
+// Each wavefront runs whole images end to end out of its private 9.7 KB slice of LDS, with no
 // workgroup barrier in the loop: both convolutions as implicit GEMMs on the matrix cores, the dense layer
 // on the vector ALU against a workgroup-shared LDS copy of its weights, accumulated band by band from the
 // conv2 results while they are still in registers.  The next image is prefetched into
@@ -21,9 +21,9 @@
 // carries a power-of-two scale chosen at run time so that any finite value fits fp16's range: the
 // weights of a member from their largest magnitude (conv1: per output channel), the pixels of an image from
 // their largest magnitude, the conv1 activations of an image from
-// the bound max|pixel| max_c sum_t |W1[t][c]| + max_c |b1[c]| (the conv1 sums start from the scaled bias,
-// so the factor is one multiply before the ReLU; the conv2 bias is added by the multiply-add that
-// takes both factors out again).  A member with a non-finite convolution weight, or an image with
+// the bound max|pixel| max_c sum_t |W1[t][c]| + max_c |b1[c]| (the sums of both convolutions start from the bias in
+// their own units, so the factor back is one multiply after ReLU and pooling; the scales are limited where a bias is
+// more than 2^70 times the convolution it is added to, so that this start value stays finite).  A member with a non-finite convolution weight, or an image with
 // an infinite pixel, gets NaN logits (the maximum operations of ReLU and pooling would otherwise
 // swallow what fp32 arithmetic propagates); a NaN pixel is not detected.
 //
@@ -45,20 +45,27 @@
 //
 // Band pipeline.  conv2 output row b needs the pooled conv1 rows 2b-1 .. 2b+2 only (rows -1 and
 // H/2 are the zero border), so the conv1 output is never held whole: pass b of conv1 produces the
-// pooled rows 2b and 2b+1 and stores each twice, as rows 1, 2 of the four-row buffer of band b
-// and as row 3 of band b-1 and row 0 of band b+1 (three buffers in rotation); conv2 of band b-1
-// follows pass b.  H/4 passes do exactly the H/2 rows.  The conv2 output never goes to memory: its pooled
+// pooled rows 2b and 2b+1 and stores them into a ring of eight rows (plus copies of two of them, so that the four
+// rows of a band always lie at consecutive addresses); conv2 of band b-1 follows pass b.  The loop is written out
+// four passes at a time, which makes every ring address a lane constant plus an immediate of the LDS
+// instruction.  H/4 passes do exactly the H/2 rows.  The conv2 output never goes to memory: its pooled
 // values are the dense layer's features and are consumed from the registers they are computed in.
 //
-// conv2 tiling.  The 16 rows of a matrix tile are 4 pooling windows x their 4 pixels, so
-// that the 4 accumulator registers of a lane (rows 4q..4q+3 of column n) are exactly one
-// pooling window of output channel n: max-pooling is three v_max on registers.  The
-// contraction index k = tap * 8 + channel, padded from 72 to 96 = 3 steps of 32 with zero
-// weights; lane group q supplies the 8 channels of tap 4 step + q: one 16-byte LDS read per
-// split term from the band buffer, which holds [term][row pair][column][row parity][channel]
-// half-precision values.
+// conv2 tiling.  One matrix tile covers a whole band: its 16 rows are the 16 pixel columns of the (padded)
+// conv2 output row pair, i.e. 8 pooling windows x their two columns, and the two pixel rows of the windows
+// are two accumulators that share the A operands.  The contraction of one step is (4 band rows) x (8 input
+// channels) for one tap column kx: lane group q supplies band row q, and the weights of output row py sit in lane
+// group q as tap row ky = q - py (zero where that falls outside the stencil: a quarter of each operand), so the
+// second output row costs a second set of weight registers and no LDS traffic.  Lane (q, r) therefore reads the
+// pixel (band row q, column r + kx): ONE 16-byte read per split term gives tap column 0, conflict-free (the 64
+// lanes read 1 KB end to end), and tap columns 1 and 2 are the values of the lanes one and two further
+// (row_shl moves).  Two reads per band instead of the twelve of an im2col read per tap (measured: LDS busy
+// 78 % -> 66 %).  The 4 accumulator registers of lane (q, n) are the two columns of windows 2 q and 2 q + 1 of
+// output channel n: with the second accumulator, max-pooling is in-lane.  The sums start from the bias in their
+// own units, so ReLU and pooling are integer maxima on the bit patterns, as for conv1.
 #include "kernels.h"
 #include "split16.h"
+#include <type_traits>
 
 namespace evo {
 
@@ -180,35 +187,46 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // zero the padded buffers once: borders stay zero, interiors are overwritten per image
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
 
-  // conv2 weights as matrix B operands, w2b[term][step]: lane group q holds tap 4 step + q (zero
-  // beyond tap 8), element j = input channel j, column n; each weight split into two terms
+  // conv2 weights as matrix B operands, w2b[output row of the window][term][step]: the step is the tap's column kx,
+  // lane group q holds the 8 input channels of band row q, which output row py of the pooling window meets with
+  // tap row ky = q - py (zero where that is outside the stencil); column n; each weight split into two terms
   const int n = lane & 15, q = lane >> 4;
-  f16x8 w2b[2][3];
-  float u_w2;           // 1 / (scale of the stored conv2 weights)
+  f16x8 w2b[2][2][3];
+  float s_w2, u_w2;     // scale of the stored conv2 weights and its reciprocal
   bool lane_bad = false;  // a non-finite convolution weight seen by this lane
   {
-    float x[3][8];
+    float x[2][3][8];
     float w2_max = 0.f;
 #pragma unroll
-    for (int st = 0; st < 3; ++st) {
-      const int tap = 4 * st + q;
+    for (int py = 0; py < 2; ++py) {
+      const int ky = q - py;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        x[st][j] = tap < 9 ? W2[(tap * kC1 + j) * kC2 + n] : 0.f;
-        w2_max = fmaxf(w2_max, fabsf(x[st][j]));
-        lane_bad |= !(fabsf(x[st][j]) <= kFltMax);
+      for (int st = 0; st < 3; ++st) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          x[py][st][j] = (ky >= 0 && ky < 3) ? W2[((3 * ky + st) * kC1 + j) * kC2 + n] : 0.f;
+          w2_max = fmaxf(w2_max, fabsf(x[py][st][j]));
+          lane_bad |= !(fabsf(x[py][st][j]) <= kFltMax);
+        }
       }
     }
-    const float s_w2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w2_max)))));
+    const float s_w2_ = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(wave_max(w2_max)))));
+    s_w2 = s_w2_;
     u_w2 = pow2_reciprocal(s_w2);
 #pragma unroll
-    for (int st = 0; st < 3; ++st) {
+    for (int py = 0; py < 2; ++py) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) x[st][j] *= s_w2;
-      split2_x8_true<true>(x[st], w2b[0][st], w2b[1][st]);
+      for (int st = 0; st < 3; ++st) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[py][st][j] *= s_w2_;
+        split2_x8_true<true>(x[py][st], w2b[py][0][st], w2b[py][1][st]);
+      }
     }
   }
   const float bias2 = b2[n];
+  // largest biased exponent of the conv1 activations' scale that keeps |bias2| s_a1 s_w2 below 2^100
+  const int e_cap_a1 = __builtin_amdgcn_readfirstlane(
+      480 - ((__float_as_int(wave_max(fabsf(bias2))) >> 23) & 0xff) - ((__float_as_int(s_w2) >> 23) & 0xff));
   const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
 
   // conv1 weights as matrix A operands.  Row i of the tile is (channel 2 (i >> 2) + (i & 1), pixel column
@@ -290,21 +308,10 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   }
   const bool member_bad = __any(lane_bad);
 
-  // conv2 A role of this lane: row r = lane & 15 -> window 4 h + (r >> 2) of the band, pixel r & 3,
-  // shifted by tap 4 step + q (the padding taps 9..11 re-read tap 8 against zero weights)
-  int a_off[2][3];  // bytes from the first of the band's four ring rows
-  {
-    const int r = lane & 15, i = r & 3;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int wxA = min(4 * h + (r >> 2), H4 - 1);
-#pragma unroll
-      for (int st = 0; st < 3; ++st) {
-        const int tap = min(4 * st + q, 8), dy = tap / 3, dx = tap - 3 * dy;
-        a_off[h][st] = band_off((i >> 1) + dy, 2 * wxA + (i & 1) + dx);
-      }
-    }
-  }
+  // conv2 A role of this lane: row r = lane & 15 is the pixel column r of the band (window r >> 1, its column r & 1),
+  // lane group q the band's row q: tap column kx reads the pixel kx columns further (the last two rows of the tile
+  // belong to a window that no supported image has; their columns are held inside the padded row)
+  const int a_off = band_off(q, lane & 15);  // bytes from the first of the band's four ring rows
   char* const bandb = reinterpret_cast<char*>(band);
   // the same as LDS addresses (32-bit), pinned in one register each (the compiler would rather keep the addends
   // apart and add them before every access): what is added per band or per step below is an immediate of the
@@ -312,18 +319,21 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   typedef __attribute__((address_space(3))) char lds_char;
   auto lds_address = [](const char* p) { return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_char*)p)); };
   auto lds_at = [](uint32_t address, int imm) { return reinterpret_cast<lds_char*>(static_cast<uintptr_t>(address)) + imm; };
-  uint32_t a_abs[2][3], own_abs[2], p_abs[2];
+  uint32_t a_abs = lds_address(bandb + a_off), own_abs[2], p_abs[2];
+  asm volatile("" : "+v"(a_abs));
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     own_abs[h] = lds_address(bandb + own_off[h]);
     p_abs[h] = lds_address(planes + p_off[h]);
     asm volatile("" : "+v"(own_abs[h]));
     asm volatile("" : "+v"(p_abs[h]));
+  }
+  // the lane's two rows of dense weights in band 0 (windows 2 q and 2 q + 1, channel n)
+  uint32_t wr_abs[2];
 #pragma unroll
-    for (int st = 0; st < 3; ++st) {
-      a_abs[h][st] = lds_address(bandb + a_off[h][st]);
-      asm volatile("" : "+v"(a_abs[h][st]));
-    }
+  for (int k = 0; k < 2; ++k) {
+    wr_abs[k] = lds_address(reinterpret_cast<const char*>(wd_s + (min(2 * q + k, H4 - 1) * kC2 + n) * NCS));
+    asm volatile("" : "+v"(wr_abs[k]));
   }
   // one padded band row (16 pixels of 16 bytes, both terms) set to zero by lanes 0..31
   auto zero_band_row = [&](char* buf, int row) {
@@ -363,8 +373,13 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
                                      __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
     const float px_bound = __uint_as_float(px_bits);
     const float a1_bound = fmaf(px_bound, bound_w1, bound_b1);
-    const float s_a1 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(split_pow2_scale(a1_bound))));
+    // (limited so that the conv2 sums, which start from the scaled bias, stay below 2^100: the limit acts only where a
+    // conv2 bias is more than 2^70 times the convolution it is added to)
+    const float s_a1 = __int_as_float(__builtin_amdgcn_readfirstlane(
+        min(__float_as_int(split_pow2_scale(a1_bound)) >> 23, e_cap_a1) << 23));
     const float u_a2 = pow2_reciprocal(s_a1) * u_w2;
+    // the conv2 bias in the units of the conv2 sums (the smaller factor first: no intermediate overflow)
+    const float bias2_init = (bias2 * fminf(s_a1, s_w2)) * fmaxf(s_a1, s_w2);
     const bool image_bad = member_bad || !(a1_bound <= kFltMax);
     // The pixels' scale is also limited so that the scaled conv1 sums stay below 2^100: the limit acts only where
     // a bias is more than 2^70 times the convolution it is added to.
@@ -419,6 +434,30 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     float acc[NCS];  // the dense layer's partial sums of this lane, per class
 #pragma unroll
     for (int c = 0; c < NCS; ++c) acc[c] = 0.f;
+    // conv2 D role: the registers of lane (q, n) are the two pixel columns of windows 2 q and 2 q + 1 of channel n,
+    // one accumulator per pixel row: two features of the dense layer, which is accumulated band by band (per lane
+    // and class) from the workgroup's copy of its weights.
+    const float u_win[2] = {2 * q < H4 ? u_a2 : 0.f, 2 * q + 1 < H4 ? u_a2 : 0.f};  // zero: a window beyond the image
+    const int dense_band_bytes = H4 * kC2 * NCS * 4;  // dense weights of one band of features
+    auto dense_of_band = [&](const floatx4 (&sums)[2], int bd) {
+      // ReLU of the largest of four, on the bit patterns as for conv1 (the sums carry the bias already); the factor
+      // to true units, a power of two, comes after
+      const int m0 = max(max(max(__float_as_int(sums[0][0]), __float_as_int(sums[0][1])),
+                             max(__float_as_int(sums[1][0]), __float_as_int(sums[1][1]))), 0);
+      const int m1 = max(max(max(__float_as_int(sums[0][2]), __float_as_int(sums[0][3])),
+                             max(__float_as_int(sums[1][2]), __float_as_int(sums[1][3]))), 0);
+      const float x0 = __int_as_float(m0) * u_win[0], x1 = __int_as_float(m1) * u_win[1];
+      typedef __attribute__((address_space(3))) const f32x2 lds_f32x2;  // rows of NCS floats: 8-byte aligned
+      const uint32_t band_bytes = static_cast<uint32_t>(bd * dense_band_bytes);
+      const uint32_t wr0 = wr_abs[0] + band_bytes, wr1 = wr_abs[1] + band_bytes;
+#pragma unroll
+      for (int c = 0; c < NCS; c += 2) {
+        const f32x2 w0 = *reinterpret_cast<lds_f32x2*>(lds_at(wr0, 4 * c));
+        const f32x2 w1 = *reinterpret_cast<lds_f32x2*>(lds_at(wr1, 4 * c));
+        acc[c] = fmaf(x1, w1[0], fmaf(x0, w0[0], acc[c]));
+        acc[c + 1] = fmaf(x1, w1[1], fmaf(x0, w0[1], acc[c + 1]));
+      }
+    };
     zero_band_row(bandb, 0);  // ring row 0: the border above the image
     // Four passes per round of the ring, written out so that every ring address is a lane constant plus an
     // immediate: pass b = b0 + u stores to ring rows 2 u + 1, 2 u + 2, the conv2 band behind it starts at row
@@ -433,30 +472,45 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       if (b == H4) {
         zero_band_row(bandb, 2 * ((H4 - 1) & 3) + 3);  // the border below the image: last row of the last band
       } else {
-        const floatx4 c_init = {c1_init[0], c1_init[1], c1_init[0], c1_init[1]};
+        // the tiles of the pass side by side, stage by stage (reads, matrix instructions, pooling, stores), so that
+        // the dependent chain of one tile runs in the gaps of the other's
+        auto conv1_pass = [&](auto tiles) {
+          constexpr int NM = decltype(tiles)::value;
+          const floatx4 c_init = {c1_init[0], c1_init[1], c1_init[0], c1_init[1]};
+          typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
+          f16x8 patch[NM];
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-          if (m < n_mt) {
+          for (int m = 0; m < NM; ++m) {
             // the lane's eight patch values: two rows of four consecutive fp16 pixels
             typedef __attribute__((address_space(3))) const uint32_t lds_u32;
             const lds_char* pp = lds_at(p_abs[m] + b0 * (4 * kPlanePitch), u * (4 * kPlanePitch));
-            typedef uint32_t u32x4c __attribute__((ext_vector_type(4)));
-            const u32x4c pw = {*reinterpret_cast<lds_u32*>(pp), *reinterpret_cast<lds_u32*>(pp + 4),
+            const u32x4p pw = {*reinterpret_cast<lds_u32*>(pp), *reinterpret_cast<lds_u32*>(pp + 4),
                                *reinterpret_cast<lds_u32*>(pp + kPlanePitch),
                                *reinterpret_cast<lds_u32*>(pp + kPlanePitch + 4)};
-            const f16x8 patch = __builtin_bit_cast(f16x8, pw);
-            floatx4 o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][0], patch, c_init, 0, 0, 0);
-            floatx4 o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][0], patch, c_init, 0, 0, 0);
-            o0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][1], patch, o0, 0, 0, 0);
-            o1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][1], patch, o1, 0, 0, 0);
+            patch[m] = __builtin_bit_cast(f16x8, pw);
+          }
+          floatx4 o0[NM], o1[NM];
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
+            o0[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][0], patch[m], c_init, 0, 0, 0);
+            o1[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][0], patch[m], c_init, 0, 0, 0);
+          }
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
+            o0[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[0][1], patch[m], o0[m], 0, 0, 0);
+            o1[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w1a[1][1], patch[m], o1[m], 0, 0, 0);
+          }
+          u32x4p pixel[NM];
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
             // pooling window of channels 2 q, 2 q + 1: both pixel rows (o0, o1) and both columns (registers i, i + 2).
             // ReLU of the largest of four = the largest of the four and zero, taken on the bit patterns as signed
             // integers: among non-negative floats they order like the floats, and every negative float (and -0) is a
             // negative integer, which the zero beats.  The factor to the stored units (a power of two) comes after.
-            const float r0 = __int_as_float(max(max(max(__float_as_int(o0[0]), __float_as_int(o0[2])),
-                                                    max(__float_as_int(o1[0]), __float_as_int(o1[2]))), 0));
-            const float r1 = __int_as_float(max(max(max(__float_as_int(o0[1]), __float_as_int(o0[3])),
-                                                    max(__float_as_int(o1[1]), __float_as_int(o1[3]))), 0));
+            const float r0 = __int_as_float(max(max(max(__float_as_int(o0[m][0]), __float_as_int(o0[m][2])),
+                                                    max(__float_as_int(o1[m][0]), __float_as_int(o1[m][2]))), 0));
+            const float r1 = __int_as_float(max(max(max(__float_as_int(o0[m][1]), __float_as_int(o0[m][3])),
+                                                    max(__float_as_int(o1[m][1]), __float_as_int(o1[m][3]))), 0));
             uint32_t lead, resid;
             split2_pair_true(r0 * c1_out[0], r1 * c1_out[1], lead, resid);
             // the four channel pairs of a window (lane groups 0..3) -> the 16 bytes of its pixel, leading term in
@@ -464,60 +518,66 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
             // upper half of the wave moves down (what the swaps leave in the upper half is not stored; their second
             // operands are values that are dead by now, so no copies are made to preserve them)
             const auto sw = __builtin_amdgcn_permlane16_swap(lead, resid, false, false);   // (L0 R0 L2 R2), (L1 R1 L3 R3)
-            const auto s2 = __builtin_amdgcn_permlane32_swap(sw[0], __float_as_uint(o0[0]), false, false);  // groups 0, 1: own, then L2, R2
-            const auto s3 = __builtin_amdgcn_permlane32_swap(sw[1], __float_as_uint(o1[0]), false, false);  // groups 0, 1: own, then L3, R3
+            const auto s2 = __builtin_amdgcn_permlane32_swap(sw[0], __float_as_uint(o0[m][0]), false, false);  // groups 0, 1: own, then L2, R2
+            const auto s3 = __builtin_amdgcn_permlane32_swap(sw[1], __float_as_uint(o1[m][0]), false, false);  // groups 0, 1: own, then L3, R3
+            pixel[m] = u32x4p{s2[0], s3[0], s2[1], s3[1]};
+          }
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
             if (c1_store[m]) {
-              typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
-              const u32x4p pixel = {s2[0], s3[0], s2[1], s3[1]};
               typedef __attribute__((address_space(3))) u32x4p lds_u4;
-              *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], u * kBandRowPair)) = pixel;
+              *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], u * kBandRowPair)) = pixel[m];
               // ring rows 1 and 8 have a copy (rows 9 and 0)
-              if (u == 0 && !c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], 4 * kBandRowPair)) = pixel;
-              if (u == 3 && c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], -kBandRowPair)) = pixel;
+              if (u == 0 && !c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], 4 * kBandRowPair)) = pixel[m];
+              if (u == 3 && c1_lower) *reinterpret_cast<lds_u4*>(lds_at(own_abs[m], -kBandRowPair)) = pixel[m];
             }
           }
-        }
+        };
+        if (n_mt == 2) conv1_pass(std::integral_constant<int, 2>());
+        else conv1_pass(std::integral_constant<int, 1>());
       }
       wave_sync();
       if (b == 0) continue;
 
-      // ---- conv2 + ReLU + pool, band b-1: two independent tiles (windows 0..3 and 4..7 of the row) --
+      // ---- conv2 + ReLU + pool, band b-1: one tile of all its pixel columns, one accumulator per output row ----
       const int bb = ((u + 3) & 3) * kBandRowPair;  // bytes from ring row 0 to the band's first row
-      floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};  // h h' + h m' + m h' (residual terms unscaled)
+      const floatx4 c2_init = {bias2_init, bias2_init, bias2_init, bias2_init};
+      floatx4 accp[2] = {c2_init, c2_init};  // bias + h h' + h m' + m h' (residual terms unscaled)
+      // One 16-byte read per split term: the lane's pixel (band row q, column r).  Tap columns 1 and 2 are the pixels
+      // of the lanes one and two columns further in the same lane group (row_shl moves; the last lanes of a group,
+      // which get zeros, belong to the window that does not exist).
+      f16x8 at[2][3];  // [term][tap column]
+      typedef __attribute__((address_space(3))) const f16x8 lds_f16x8;
+      typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        at[k][0] = *reinterpret_cast<lds_f16x8*>(lds_at(a_abs, bb + k * kBandTerm));
+        const u32x4s w = __builtin_bit_cast(u32x4s, at[k][0]);
+        u32x4s w1, w2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          w1[i] = __builtin_amdgcn_update_dpp(0, w[i], 0x101, 0xf, 0xf, true);  // row_shl:1
+          w2[i] = __builtin_amdgcn_update_dpp(0, w[i], 0x102, 0xf, 0xf, true);  // row_shl:2
+        }
+        at[k][1] = __builtin_bit_cast(f16x8, w1);
+        at[k][2] = __builtin_bit_cast(f16x8, w2);
+      }
 #pragma unroll
       for (int st = 0; st < 3; ++st) {
-        f16x8 a0[2], a1[2];  // [term] of tile 0 and tile 1
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          typedef __attribute__((address_space(3))) const f16x8 lds_f16x8;
-          a0[k] = *reinterpret_cast<lds_f16x8*>(lds_at(a_abs[0][st], bb + k * kBandTerm));
-          a1[k] = *reinterpret_cast<lds_f16x8*>(lds_at(a_abs[1][st], bb + k * kBandTerm));
-        }
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[1], w2b[0][st], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[1], w2b[0][st], acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[1][st], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[1][st], acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0[0], w2b[0][st], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1[0], w2b[0][st], acc1, 0, 0, 0);
+        for (int py = 0; py < 2; ++py) accp[py] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[1][st], w2b[py][0][st], accp[py], 0, 0, 0);
+#pragma unroll
+        for (int py = 0; py < 2; ++py) accp[py] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0][st], w2b[py][1][st], accp[py], 0, 0, 0);
+#pragma unroll
+        for (int py = 0; py < 2; ++py) accp[py] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at[0][st], w2b[py][0][st], accp[py], 0, 0, 0);
       }
-      // D role: the four registers of lane (q, n) are window q (+4) of channel n: two features of the dense
-      // layer, which is accumulated band by band (per lane and class) from the workgroup's copy of its weights
-      {
-        // bias and factor first (monotone, so the same number as after the maximum): the maxima then work on
-        // results of vector instructions and need no canonicalising moves
-        float f0[4], f1[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f0[i] = fmaf(acc0[i], u_a2, bias2), f1[i] = fmaf(acc1[i], u_a2, bias2);
-        const float x0 = q < H4 ? fmaxf(fmaxf(fmaxf(f0[0], f0[1]), f0[2]), fmaxf(f0[3], 0.f)) : 0.f;
-        const float x1 = q + 4 < H4 ? fmaxf(fmaxf(fmaxf(f1[0], f1[1]), f1[2]), fmaxf(f1[3], 0.f)) : 0.f;
-        const float* wr0 = wd_s + (((b - 1) * H4 + min(q, H4 - 1)) * kC2 + n) * NCS;
-        const float* wr1 = wd_s + (((b - 1) * H4 + min(q + 4, H4 - 1)) * kC2 + n) * NCS;
-#pragma unroll
-        for (int c = 0; c < NCS; ++c) acc[c] = fmaf(x1, wr1[c], fmaf(x0, wr0[c], acc[c]));
-      }
+      // the band before this one, whose sums were carried over: independent of the matrix instructions above,
+      // so its vector work can be issued between them
+      dense_of_band(accp, b - 1);
       wave_sync();
     }
     }
+
 
     // transpose-reduce through LDS (the band buffers are free now): lane (c, part) adds 16 partials
     float* red = band;
