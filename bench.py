@@ -37,7 +37,8 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2924945,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 33456128,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2)
+    "cfg2": 54298053,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: shared images re-fetched per L2; 21 MB
+                           # of it is scratch: ten per-image lane constants kept outside the registers)
     "cfg3": 19116032,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4305387571,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
@@ -52,8 +53,8 @@ MEASURED_TRAFFIC_BYTES = {
 # What the rocprofv3 counters in profiles/ say bounds the dominant kernel.
 BOUND_DETAIL = {
     "cfg1": "launch latency: five launches of a few microseconds each (profiles/mlp_f32_kernel_cfg1.md)",
-    "cfg2": "both convolutions on the matrix cores: MFMA busy 33 % + VALU busy 58 % on the same SIMDs (9 % of the cycles overlap), LDS busy 78 %, "
-            "22 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
+    "cfg2": "both convolutions on the matrix cores: MFMA busy 39 %, VALU issue 60 % on the same SIMDs (13 % of the cycles overlap), LDS busy 68 %, "
+            "27 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
     "cfg3": "vector-instruction issue along a 1000-step dependency chain: VALU busy 66 %, MFMA busy 21 %, 36 % of wave "
             "time waiting (profiles/cartpole_kernel_cfg3.md)",
     "cfg4": "HBM weight stream: 64 flop per weight byte (profiles/mlp_bf16_stream_kernel_cfg4.md)",
@@ -120,7 +121,7 @@ def _build_workload(name, seed, batch=None, f32=False):
             c1, c2, ncls = c.dims
             per_img = 2.0 * (9 * c1 * 28 * 28 + 9 * c1 * c2 * 14 * 14 + 7 * 7 * c2 * ncls)
             # as issued: v_mfma_f32_16x16x32_f16 (16,384 flop each) per image: conv1 7 passes x 2 tiles x 4, conv2 7 bands x
-            # 3 steps of k x 2 tiles x 3 products of split terms
+            # 3 tap columns x 2 output rows x 3 products of split terms
             wl["roofline"] = ("mfma", 16384.0 * (7 * 2 * 4 + 7 * 3 * 2 * 3) * c.pop * c.B, PEAK_MFMA_BF16_TF, "TFLOP/s")
             wl["fp32_flops"] = per_img * c.pop * c.B
             wl["desc"] = "cfg2: MNIST-shaped synthetic images, per-member fp32 ConvNet P=9098, pop 256, batch 1024"
