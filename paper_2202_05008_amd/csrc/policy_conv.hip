@@ -119,29 +119,34 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Reductions over the 16 lanes of a row with DPP moves (xor 1, xor 2, half-row mirror, row mirror):
-// no LDS round trip, every lane of the row ends with the result, the order is fixed.
+// A value moved between the lanes of a row (DPP control CTRL): no LDS round trip.
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
   // every lane has a source in these patterns: no value has to be prepared for lanes without one
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
-  v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
-  v += dpp_mov<0x141>(v);  // row_half_mirror
-  v += dpp_mov<0x140>(v);  // row_mirror
+// Reductions over one quad of every row (lanes 1 and 2 apart) and then down the four rows: lane 63 ends with the
+// result over the last quads of the rows (row_bcast:15 hands a row's last lane to the next row, row_bcast:31 the
+// second row's to the third and fourth).
+__device__ __forceinline__ float quads_sum(float v) {
+  v += dpp_mov<0xB1>(v);  // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);  // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xa, 0xf, false));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xc, 0xf, false));
   return v;
 }
-__device__ __forceinline__ float row16_max(float v) {
+__device__ __forceinline__ float quads_max(float v) {
   v = fmaxf(v, dpp_mov<0xB1>(v));
   v = fmaxf(v, dpp_mov<0x4E>(v));
-  v = fmaxf(v, dpp_mov<0x141>(v));
-  v = fmaxf(v, dpp_mov<0x140>(v));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x142, 0xa, 0xf, false)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x143, 0xc, 0xf, false)));
   return v;
 }
-// The same for magnitudes (non-negative floats order like their bit patterns): integer maxima, which take the
-// moved value as an operand and need no canonicalising moves.
+__device__ __forceinline__ float last_lane(float v) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Largest magnitude over the 16 lanes of a row, in every lane of it (non-negative floats order like their bit
+// patterns): integer maxima, which take the moved value as an operand and need no canonicalising moves.
 __device__ __forceinline__ float row16_max_magnitude(float v) {
   int b = __float_as_int(v);
   b = max(b, __float_as_int(dpp_mov<0xB1>(__int_as_float(b))));
@@ -227,7 +232,9 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   // largest biased exponent of the conv1 activations' scale that keeps |bias2| s_a1 s_w2 below 2^100
   const int e_cap_a1 = __builtin_amdgcn_readfirstlane(
       480 - ((__float_as_int(wave_max(fabsf(bias2))) >> 23) & 0xff) - ((__float_as_int(s_w2) >> 23) & 0xff));
-  const float bias_d = (lane & 15) < n_cls ? bd[lane & 15] : 0.f;
+  // the class whose logit this lane ends with (see the reduction after the band loop)
+  const int my_cls = 8 * ((lane >> 1) & 1) + 4 * (lane & 1) + 2 * ((lane >> 4) & 1) + ((lane >> 5) & 1);
+  const float bias_d = my_cls < n_cls ? bd[my_cls] : 0.f;
 
   // conv1 weights as matrix A operands.  Row i of the tile is (channel 2 (i >> 2) + (i & 1), pixel column
   // s = (i >> 1) & 1 of the pooling window), so that the four accumulator registers of a lane (rows 4 q .. 4 q + 3
@@ -579,39 +586,62 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
 
 
-    // transpose-reduce through LDS (the band buffers are free now): lane (c, part) adds 16 partials
-    float* red = band;
-#pragma unroll
-    for (int c = 0; c < NCS; ++c) red[lane * NCS + c] = acc[c];
-    wave_sync();
-    float logit = 0.f;
+    // Sum over the 64 lanes, per class, in registers: every step adds the two halves of a lane pairing and halves
+    // the number of live classes, the lanes of one half keeping the even and the others the odd ones.  Halves of
+    // the wave and neighbouring rows first (a swap and an add per pair of classes), then lanes 1 and 2 apart; the
+    // quads of a row then hold copies, which one rotation by four and one by eight add up.  Lane l ends with the
+    // class 8 b1 + 4 b0 + 2 b4 + b5 of its bits (my_cls).
+    float logit;
     {
-      const int c = lane & 15, part = lane >> 4;
-      if (c < NCS) {
+      constexpr int N1 = (NCS + 1) / 2, N2 = (N1 + 1) / 2, N3 = (N2 + 1) / 2;
+      static_assert(NCS % 2 == 0 && NCS <= 16 && NCS > 8, "class counts this reduction is written for");
+      float w[N1], x[N2], y[N3];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) logit += red[(16 * part + i) * NCS + c];
+      for (int j = 0; j < N1; ++j) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[2 * j]), __float_as_uint(acc[2 * j + 1]), false, false);
+        w[j] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
       }
-      logit += __shfl_xor(logit, 16, 64);
-      logit += __shfl_xor(logit, 32, 64);
+#pragma unroll
+      for (int k = 0; k < N2; ++k) {
+        const uint32_t other = 2 * k + 1 < N1 ? __float_as_uint(w[2 * k + 1 < N1 ? 2 * k + 1 : 0]) : 0u;
+        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(w[2 * k]), other, false, false);
+        x[k] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+      }
+      const bool odd1 = (lane & 1) != 0, odd2 = (lane & 2) != 0;
+#pragma unroll
+      for (int m = 0; m < N3; ++m) {
+        if (2 * m + 1 < N2) {
+          const float keep = odd1 ? x[2 * m + 1 < N2 ? 2 * m + 1 : 0] : x[2 * m];
+          const float send = odd1 ? x[2 * m] : x[2 * m + 1 < N2 ? 2 * m + 1 : 0];
+          y[m] = keep + dpp_mov<0xB1>(send);
+        } else {
+          const float both = x[2 * m] + dpp_mov<0xB1>(x[2 * m]);
+          y[m] = odd1 ? 0.f : both;
+        }
+      }
+      static_assert(N3 == 2, "two registers left before the last halving");
+      {
+        const float keep = odd2 ? y[1] : y[0], send = odd2 ? y[0] : y[1];
+        logit = keep + dpp_mov<0x4E>(send);
+      }
+      logit += dpp_mov<0x124>(logit);  // row_ror:4
+      logit += dpp_mov<0x128>(logit);  // row_ror:8
       logit += bias_d;
     }
     if (image_bad) logit = __builtin_nanf("");  // a non-finite weight or pixel: what fp32 arithmetic would propagate
-    wave_sync();
-    // both scratch uses sat on zero-padded buffers: restore the zeros (the next image's
-    // interior is rewritten anyway, the borders must read as zero again)
-    for (int i = lane; i < 64 * NCS; i += 64) red[i] = 0.f;
 
-    const int cls = lane & 15;
     if (a.out) {
-      if (lane < n_cls) a.out[(static_cast<size_t>(member) * a.B + im) * n_cls + lane] = logit;
+      if ((lane & 12) == 0 && my_cls < n_cls)
+        a.out[(static_cast<size_t>(member) * a.B + im) * n_cls + my_cls] = logit;
     } else {
-      // cross-entropy over the 16 lanes of a row (classes beyond n_cls count as -inf)
+      // cross-entropy over the classes (those beyond n_cls count as -inf): the last quad of every row holds four
+      // of them, so a reduction runs over the quad and then down the rows into lane 63
       const int y = a.labels[im];  // a label outside [0, n_cls) contributes logit 0
-      const float lv = cls < n_cls ? logit : -INFINITY;
-      const float mx = row16_max(lv);
+      const float lv = my_cls < n_cls ? logit : -INFINITY;
+      const float mx = last_lane(quads_max(lv));
       // the hardware's exp2 and log2 (one ulp each): the terms are at most one and their sum lies in [1, 16]
-      const float se = row16_sum(cls < n_cls ? __builtin_amdgcn_exp2f(1.4426950408889634f * (lv - mx)) : 0.f);
-      const float picked = row16_sum(cls == y ? lv : 0.f);
+      const float se = last_lane(quads_sum(my_cls < n_cls ? __builtin_amdgcn_exp2f(1.4426950408889634f * (lv - mx)) : 0.f));
+      const float picked = last_lane(quads_sum(my_cls == y ? lv : 0.f));
       loss_sum += (mx + 0.6931471805599453f * __builtin_amdgcn_logf(se)) - picked;
     }
     wave_sync();
