@@ -295,13 +295,14 @@ typedef struct {
                                      (see pgpe_device_generation) instead of `generation`            */
 } task_desc;
 
-/* Bytes of device workspace `rollout` needs for this task / policy / pop (may be 0). */
+/* Bytes of device workspace `rollout` needs for this task / policy / pop (may be 0): partial sums of the
+ * members' losses and, for the ConvNet, the shared batch converted once for all members (5 KB per image). */
 size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop);
 
 /* Evaluate every member: fitness_dev[pop] as defined above.  `steps` is the episode length
  * for CARTPOLE and FORAGE (FORAGE enqueues steps + 2 kernels and keeps the worlds' state in
- * work_dev, so two roll-outs that share a workspace must not overlap) and must be 1 for the
- * single-step tasks.
+ * work_dev, so two roll-outs that share a workspace must not overlap; the same holds for the
+ * ConvNet, whose converted batch sits there) and must be 1 for the single-step tasks.
  * Errors: EVO_ERR_ARG, EVO_ERR_UNSUPPORTED, EVO_ERR_HIP. */
 int rollout(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop, int32_t steps,
             float* fitness_dev, void* stream);
@@ -338,7 +339,7 @@ int pgpe_generation(pgpe_state* st, uint64_t seed, int32_t pop, const task_desc*
  * launched.  Every call on a GPU shares that GPU's array (each kernel writes what it later reads; nothing has to
  * start at zero): two calls that overlap on one GPU, on different streams or threads, race.
  * Errors: as rollout, plus EVO_ERR_UNSUPPORTED (workspace beyond the array), EVO_ERR_HIP (symbol lookup). */
-#define EVO_STATIC_SCRATCH_BYTES (2u << 20)
+#define EVO_STATIC_SCRATCH_BYTES (8u << 20)
 size_t rollout_static_scratch_bytes(void);
 int rollout_static_scratch(const task_desc* td, const policy_desc* pd, const void* params_dev, int32_t pop,
                            int32_t steps, float* fitness_dev, void* stream);

@@ -56,11 +56,14 @@ int pgpe_generation_small(pgpe_state* st, uint64_t seed, int32_t pop, const MlpS
                           int64_t obs_stride, int B, int loss, const void* target, float scale, float* fitness,
                           hipStream_t s);
 
-// fp32 ConvNet; images shared by all members.  Partials per (member, chunk).
+// fp32 ConvNet; images shared by all members.  Partials per (member, chunk).  planes_work: convnet_planes_bytes(B)
+// bytes of device memory, 16-byte aligned, into which the batch is split into fp16 terms once for all members
+// (a small kernel ahead of the members' one); null: every member's workgroups split the images themselves.
 int convnet_supported(const ConvShape& sh);
 int convnet_chunks(const ConvShape& sh, int pop, int B);
+size_t convnet_planes_bytes(int B);
 int launch_convnet_f32(const ConvShape& sh, const float* params, const float* images, int pop, int B, float* out,
-                       const int32_t* labels, float* partial, int chunks, hipStream_t s);
+                       const int32_t* labels, float* partial, int chunks, void* planes_work, hipStream_t s);
 
 // fitness[m] = scale * sum_j partial[m][j], j in increasing order.
 int launch_finalize(const float* partial, int pop, int n, float scale, float* fitness, hipStream_t s);

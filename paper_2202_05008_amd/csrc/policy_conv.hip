@@ -9,8 +9,10 @@
 // workgroup barrier in the loop: both convolutions as implicit GEMMs on the matrix cores, the dense layer
 // on the vector ALU against a workgroup-shared LDS copy of its weights, accumulated band by band from the
 // conv2 results while they are still in registers.  The next image is prefetched into
-// registers while the current one is computed.  Activations never leave the chip; per image
-// the kernel reads 3 KB (L2 resident, shared by all members).
+// registers while the current one is computed.  Activations never leave the chip.  The conversion of the images into
+// the two fp16 planes conv1 reads is the same for every member: for roll-outs a small kernel does it once per batch
+// into the caller's workspace (5 KB per image, L2 resident, read by all members; 8 % of the ConvNet kernel's time
+// when every member's workgroups did it again), pop_forward, which has no workspace, converts in the kernel.
 //
 // Arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
 // v_mfma_f32_16x16x4_f32 takes 32 cycles (1024 MACs), and the two do not overlap, so the fp32
@@ -99,6 +101,10 @@ __device__ __forceinline__ constexpr int band_off(int row, int col) {
   return (row >> 1) * kBandRowPair + col * 2 * kPixBytes + (row & 1) * kPixBytes;
 }
 constexpr int kConvWavesMax = 12;
+// The batch split once for all members (convnet_split_kernel): per image the two padded planes exactly as they sit
+// in LDS, then the largest pixel magnitude as a float.
+constexpr int kImgStride = 5120;
+constexpr int kSplitWaves = 4;
 constexpr int kMaxCls = 16;
 constexpr int kMaxFeat = (kHMax / 4) * (kHMax / 4) * kC2;  // 784
 
@@ -106,6 +112,7 @@ struct ConvArgs {
   const float* params;
   const float* images;
   const int32_t* labels;
+  const unsigned char* planes;  // the batch already split into fp16 terms (kImgStride bytes per image), or null
   float* out;
   float* partial;
   int P, H, n_cls, B, chunks, imgs_per_chunk;
@@ -159,7 +166,82 @@ __device__ __forceinline__ float row16_max_magnitude(float v) {
 // NCS: row stride of the staged dense weights and number of per-lane class accumulators
 // (10 for the ten-class case, 16 for any n_cls <= 16 with zero padding).
 // kConvWaves: waves per workgroup (12 with ten classes, 10 when the padded dense weights take 49 KB).
-template <int NCS, int kConvWaves>
+// The pixels of one image (lane's float4 pieces lane, lane + 64, ... of its rows) -> two fp16 terms in the
+// zero-padded planes; returns the largest pixel magnitude (wave-uniform).  The pixels' power of two depends on the image alone.
+__device__ __forceinline__ float pixel_scale(float px_bound) {
+  return __int_as_float(__builtin_amdgcn_readfirstlane(min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183) << 23));
+}
+__device__ __forceinline__ float stage_pixels(const float4 (&pre)[4], char* planes, int lane, int row4, int n_vec) {
+  float px_max = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (lane + 64 * j < n_vec)
+      px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
+  // (non-negative floats order like their bit patterns)
+  px_max = row16_max_magnitude(px_max);
+  const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
+                                   __builtin_amdgcn_readlane(__float_as_uint(px_max), 16)),
+                               max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 32),
+                                   __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
+  const float px_bound = __uint_as_float(px_bits);
+  const float s_px = pixel_scale(px_bound);
+  // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
+  // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
+  // lane 0 the last lane of the previous round), and the last piece of a row adds the row's last pixel.
+  uint32_t last_lead = 0, last_resid = 0;  // lane 63's outer pair of the previous round
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = lane + 64 * j;
+    const int y = i / row4, x4 = i - y * row4;
+    uint32_t lead_o, resid_o, lead_m, resid_m;
+    split2_pair_true(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
+    split2_pair_true(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
+    uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead_o, 0x138, 0xf, 0xf, false);    // wave_shr:1
+    uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid_o, 0x138, 0xf, 0xf, false);
+    last_lead = __builtin_amdgcn_readlane(lead_o, 63);
+    last_resid = __builtin_amdgcn_readlane(resid_o, 63);
+    if (x4 == 0) left_lead = 0, left_resid = 0;  // the border left of the row
+    if (i < n_vec) {
+      char* d = planes + (y + 1) * kPlanePitch + 8 * x4;
+      *reinterpret_cast<uint2*>(d) = make_uint2((left_lead >> 16) | (lead_o << 16), lead_m);
+      *reinterpret_cast<uint2*>(d + kPlaneBytes) = make_uint2((left_resid >> 16) | (resid_o << 16), resid_m);
+      if (x4 == row4 - 1) {
+        *reinterpret_cast<uint32_t*>(d + 8) = lead_o >> 16;
+        *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 8) = resid_o >> 16;
+      }
+    }
+  }
+  return px_bound;
+}
+
+// Once per batch, for all members: every image as its two padded fp16 planes plus its largest pixel magnitude.
+// One wave per image at a time, through the same LDS staging as the ConvNet kernel's own.
+__global__ __launch_bounds__(64 * kSplitWaves) void convnet_split_kernel(const float* __restrict__ images, int B, int H,
+                                                                         unsigned char* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) char planes_s[kSplitWaves][kImgBytes];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* planes = planes_s[wave];
+  for (int i = lane; i < kImgBytes / 16; i += 64) reinterpret_cast<uint4*>(planes)[i] = make_uint4(0, 0, 0, 0);
+  wave_sync();
+  const int row4 = H / 4, n_vec = H * row4;
+  for (int im = blockIdx.x * kSplitWaves + wave; im < B; im += gridDim.x * kSplitWaves) {
+    float4 pre[4];
+    const float4* src = reinterpret_cast<const float4*>(images + static_cast<size_t>(im) * H * H);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      pre[j] = lane + 64 * j < n_vec ? src[lane + 64 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float px_bound = stage_pixels(pre, planes, lane, row4, n_vec);
+    wave_sync();
+    unsigned char* dst = out + static_cast<size_t>(im) * kImgStride;
+    for (int i = lane; i < kImgBytes / 16; i += 64)
+      reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(planes)[i];
+    if (lane == 0) *reinterpret_cast<float*>(dst + kImgBytes) = px_bound;
+    wave_sync();
+  }
+}
+
+template <int NCS, int kConvWaves, bool PRESPLIT>
 __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ float wave_loss[kConvWavesMax];
@@ -248,7 +330,6 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   f16x8 w1a[2][2];      // [pixel row t][instruction]
   float sw1_row;        // scale of the channel of this lane's A row
   float bound_w1, bound_b1;    // bound on the conv1 activations of any image: max|pixel| * bound_w1 + bound_b1
-  float sbound_w1, sbound_b1;  // the same bound on the scaled accumulators (before the pixels' scale)
   {
     const int i = lane & 15, ch = 2 * (i >> 2) + (i & 1), sx = (i >> 1) & 1;
     const int rblk = q & 1, half = q >> 1;
@@ -261,12 +342,13 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     }
     const float bch = b1[ch];
     lane_bad |= !(t_sum <= kFltMax) || !(fabsf(bch) <= kFltMax) || !(fabsf(bias2) <= kFltMax);
-    // at most 2^56, so that the product with the pixels' scale (at most 2^56 too) stays finite
-    sw1_row = fminf(split_pow2_scale(t_max), 0x1p56f);
+    // at most 2^56, and at most 2^44 / |bias|: with the pixels' scale (at most 2^56, a matter of the image alone) the
+    // sums, which start from the scaled bias, then stay below 2^100.  The second limit acts only where a bias is more
+    // than 2^29 times its channel's weights.
+    sw1_row = __int_as_float(min(min(__float_as_int(split_pow2_scale(t_max)) >> 23, 127 + 56),
+                                 297 - ((__float_as_int(bch) >> 23) & 0xff)) << 23);
     bound_w1 = wave_max(t_sum);
     bound_b1 = wave_max(fabsf(bch));
-    sbound_w1 = wave_max(sw1_row * t_sum);
-    sbound_b1 = wave_max(sw1_row * fabsf(bch));
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       float x1[8], x2[8];
@@ -352,33 +434,42 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   const int row4 = H / 4, n_vec = H * row4;  // float4 pieces of one image (<= 196)
   float loss_sum = 0.f;
 
-  // prefetch of the first image: lane takes pieces lane, lane + 64, ...
+  // prefetch of the first image: lane takes pieces lane, lane + 64, ... (of its pixels, or of its split planes)
   float4 pre[4] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f),
                    make_float4(0.f, 0.f, 0.f, 0.f)};  // pieces beyond the image stay zero
-  int im = img_begin + wave;
-  if (im < img_end) {
-    const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(im) * H * H);
+  uint4 pre_split[5] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0),
+                        make_uint4(0, 0, 0, 0)};
+  auto prefetch = [&](int image) {
+    if (PRESPLIT) {
+      const uint4* src = reinterpret_cast<const uint4*>(a.planes + static_cast<size_t>(image) * kImgStride);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (lane + 64 * j < n_vec) pre[j] = src[lane + 64 * j];
-  }
+      for (int j = 0; j < 5; ++j) pre_split[j] = src[lane + 64 * j];  // kImgStride = 5 x 64 x 16 bytes
+    } else {
+      const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(image) * H * H);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (lane + 64 * j < n_vec) pre[j] = src[lane + 64 * j];
+    }
+  };
+  int im = img_begin + wave;
+  if (im < img_end) prefetch(im);
   __syncthreads();  // dense weights staged
 
   for (; im < img_end; im += kConvWaves) {
-    // ---- image registers -> two fp16 terms in the zero-padded planes; then prefetch the next image -------
-    float px_max = 0.f;
+    // ---- the image as two fp16 terms in the zero-padded planes (split here, or copied from the batch split once
+    //      for all members); then prefetch the next image -------
+    float px_bound;
+    if (PRESPLIT) {
+      static_assert(kImgBytes == 4 * 1024 + 44 * 16, "four full rounds of 16 bytes a lane and 44 lanes of a fifth");
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (lane + 64 * j < n_vec)
-        px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
-    // scales of this image (all wave-uniform; non-negative floats order like their bit patterns): of its
-    // pixels from their largest magnitude, of its conv1 activations from the bound on them
-    px_max = row16_max_magnitude(px_max);
-    const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
-                                     __builtin_amdgcn_readlane(__float_as_uint(px_max), 16)),
-                                 max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 32),
-                                     __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
-    const float px_bound = __uint_as_float(px_bits);
+      for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4*>(planes + 16 * (lane + 64 * j)) = pre_split[j];
+      if (lane < 44) *reinterpret_cast<uint4*>(planes + 16 * (lane + 256)) = pre_split[4];
+      px_bound = __uint_as_float(__builtin_amdgcn_readlane(pre_split[4].x, 44));  // the float behind the planes
+    } else {
+      px_bound = stage_pixels(pre, planes, lane, row4, n_vec);
+    }
+    // scales of this image (all wave-uniform): of its pixels from their largest magnitude, of its conv1 activations
+    // from the bound on them
     const float a1_bound = fmaf(px_bound, bound_w1, bound_b1);
     // (limited so that the conv2 sums, which start from the scaled bias, stay below 2^100: the limit acts only where a
     // conv2 bias is more than 2^70 times the convolution it is added to)
@@ -388,15 +479,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     // the conv2 bias in the units of the conv2 sums (the smaller factor first: no intermediate overflow)
     const float bias2_init = (bias2 * fminf(s_a1, s_w2)) * fmaxf(s_a1, s_w2);
     const bool image_bad = member_bad || !(a1_bound <= kFltMax);
-    // The pixels' scale is also limited so that the scaled conv1 sums stay below 2^100: the limit acts only where
-    // a bias is more than 2^70 times the convolution it is added to.
-    float s_px;
-    {
-      const float sb = fmaf(px_bound, sbound_w1, sbound_b1);  // bound on the accumulators before the pixels' scale
-      const int e_cap = 353 - ((__float_as_int(sb) >> 23) & 0xff);
-      const int e_px = min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183);
-      s_px = __int_as_float(__builtin_amdgcn_readfirstlane(min(e_px, e_cap) << 23));
-    }
+    const float s_px = pixel_scale(px_bound);
     float c1_init[2], c1_out[2];  // accumulators start from the scaled bias; factor from them to the stored activations
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -404,38 +487,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       c1_init[j] = b1_d[j] * both;
       c1_out[j] = s_a1 * pow2_reciprocal(both);
     }
-    // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
-    // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
-    // lane 0 the last lane of the previous round), and the last piece of a row adds the row's last pixel.
-    uint32_t last_lead = 0, last_resid = 0;  // lane 63's outer pair of the previous round
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = lane + 64 * j;
-      const int y = i / row4, x4 = i - y * row4;
-      uint32_t lead_o, resid_o, lead_m, resid_m;
-      split2_pair_true(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
-      split2_pair_true(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
-      uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead_o, 0x138, 0xf, 0xf, false);    // wave_shr:1
-      uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid_o, 0x138, 0xf, 0xf, false);
-      last_lead = __builtin_amdgcn_readlane(lead_o, 63);
-      last_resid = __builtin_amdgcn_readlane(resid_o, 63);
-      if (x4 == 0) left_lead = 0, left_resid = 0;  // the border left of the row
-      if (i < n_vec) {
-        char* d = planes + (y + 1) * kPlanePitch + 8 * x4;
-        *reinterpret_cast<uint2*>(d) = make_uint2((left_lead >> 16) | (lead_o << 16), lead_m);
-        *reinterpret_cast<uint2*>(d + kPlaneBytes) = make_uint2((left_resid >> 16) | (resid_o << 16), resid_m);
-        if (x4 == row4 - 1) {
-          *reinterpret_cast<uint32_t*>(d + 8) = lead_o >> 16;
-          *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 8) = resid_o >> 16;
-        }
-      }
-    }
-    if (im + kConvWaves < img_end) {
-      const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(im + kConvWaves) * H * H);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (lane + 64 * j < n_vec) pre[j] = src[lane + 64 * j];
-    }
+    if (im + kConvWaves < img_end) prefetch(im + kConvWaves);
     wave_sync();
 
     float acc[NCS];  // the dense layer's partial sums of this lane, per class
@@ -676,27 +728,40 @@ int convnet_chunks(const ConvShape&, int pop, int B) {
   return chunks;
 }
 
-template <int NCS, int WAVES>
+template <int NCS, int WAVES, bool PRESPLIT>
 static int launch_conv(const ConvArgs& a, int pop, hipStream_t s) {
   const size_t shmem = sizeof(float) * (static_cast<size_t>(kMaxFeat) * NCS + WAVES * kWaveFloats);
   static_assert(sizeof(float) * (kMaxFeat * NCS + WAVES * kWaveFloats) + 256 <= 160 * 1024, "LDS budget of a CU");
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(convnet_kernel<NCS, WAVES>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(convnet_kernel<NCS, WAVES, PRESPLIT>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shmem));
   if (e != hipSuccess) (void)hipGetLastError();  // do not leave the error sticky for the caller's next HIP call
   EVO_REQUIRE(e == hipSuccess, EVO_ERR_HIP, "hipFuncSetAttribute failed: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL((convnet_kernel<NCS, WAVES>), dim3(a.chunks, pop), dim3(64 * WAVES), shmem, s, a);
+  hipLaunchKernelGGL((convnet_kernel<NCS, WAVES, PRESPLIT>), dim3(a.chunks, pop), dim3(64 * WAVES), shmem, s, a);
   return check_launch("convnet_kernel");
 }
 
+// Bytes of workspace for the batch split once for all members.
+size_t convnet_planes_bytes(int B) { return static_cast<size_t>(B) * kImgStride; }
+
 int launch_convnet_f32(const ConvShape& sh, const float* params, const float* images, int pop, int B, float* out,
-                       const int32_t* labels, float* partial, int chunks, hipStream_t s) {
+                       const int32_t* labels, float* partial, int chunks, void* planes_work, hipStream_t s) {
   ConvArgs a;
   a.params = params, a.images = images, a.labels = labels, a.out = out, a.partial = partial;
+  a.planes = static_cast<const unsigned char*>(planes_work);
   a.P = sh.P, a.H = sh.H, a.n_cls = sh.n_cls, a.B = B;
   if (chunks <= 0) chunks = convnet_chunks(sh, pop, B);
   a.chunks = chunks;
   a.imgs_per_chunk = (B + chunks - 1) / chunks;
-  return sh.n_cls == 10 ? launch_conv<10, 12>(a, pop, s) : launch_conv<16, 10>(a, pop, s);
+  if (planes_work) {
+    // the split of the batch into fp16 terms is the same for every member: done once, ahead of the members' kernel
+    const int blocks = min((B + kSplitWaves - 1) / kSplitWaves, 1024);
+    hipLaunchKernelGGL(convnet_split_kernel, dim3(blocks), dim3(64 * kSplitWaves), 0, s, images, B, sh.H,
+                       static_cast<unsigned char*>(planes_work));
+    const int rc = check_launch("convnet_split_kernel");
+    if (rc) return rc;
+    return sh.n_cls == 10 ? launch_conv<10, 12, true>(a, pop, s) : launch_conv<16, 10, true>(a, pop, s);
+  }
+  return sh.n_cls == 10 ? launch_conv<10, 12, false>(a, pop, s) : launch_conv<16, 10, false>(a, pop, s);
 }
 
 }  // namespace evo

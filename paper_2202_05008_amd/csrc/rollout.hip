@@ -109,7 +109,7 @@ extern "C" int pop_forward(const policy_desc* pd, const void* params_dev, const 
   rc = convnet_supported(cs);
   if (rc) return rc;
   return launch_convnet_f32(cs, static_cast<const float*>(params_dev), obs_dev, pop, B, out_dev, nullptr, nullptr, 0,
-                            s);
+                            nullptr, s);
 }
 
 namespace {
@@ -128,6 +128,16 @@ int partials_per_member(const task_desc* td, const policy_desc* pd, int pop) {
   return (td->B + kMlpTile - 1) / kMlpTile;
 }
 
+// Bytes of the partial sums in the workspace (a multiple of 256), and of what follows them: the ConvNet's batch
+// split into fp16 terms once for all members.
+size_t partials_bytes(const task_desc* td, const policy_desc* pd, int pop) {
+  return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
+}
+size_t planes_bytes(const task_desc* td, const policy_desc* pd) {
+  if (td->kind != EVO_TASK_CLASSIFY || pd == nullptr || pd->kind != EVO_POLICY_CONVNET || td->B < 1) return 0;
+  return convnet_planes_bytes(td->B);
+}
+
 int check_task(const task_desc* td) {
   EVO_REQUIRE(td != nullptr, EVO_ERR_ARG, "task_desc is null");
   EVO_REQUIRE(td->kind >= EVO_TASK_CLASSIFY && td->kind <= EVO_TASK_FORAGE_SOLO, EVO_ERR_ARG, "task: bad kind %d",
@@ -143,7 +153,7 @@ extern "C" size_t rollout_workspace_bytes(const task_desc* td, const policy_desc
   if (td->kind == EVO_TASK_FORAGE) return forage_workspace_bytes(pop, td->n_rollouts, td->cp);
   if (td->kind == EVO_TASK_FORAGE_SOLO) return forage_solo_workspace_bytes(pop, td->n_rollouts);
   if (td->kind != EVO_TASK_SPHERE && check_policy(pd)) return 0;
-  return (static_cast<size_t>(partials_per_member(td, pd, pop)) * pop * sizeof(float) + 255) & ~size_t(255);
+  return partials_bytes(td, pd, pop) + planes_bytes(td, pd);
 }
 
 // The sequence-to-sequence task: fitness and / or logits of every member.
@@ -264,13 +274,15 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     EVO_REQUIRE(loss == LOSS_CE, EVO_ERR_UNSUPPORTED, "convnet: only the classification task is supported");
     EVO_REQUIRE(pd->dtype == EVO_F32, EVO_ERR_UNSUPPORTED, "convnet: only fp32 parameters are supported");
     EVO_REQUIRE(td->obs_member_stride == 0, EVO_ERR_UNSUPPORTED, "convnet: images must be shared");
+    EVO_REQUIRE(aligned16(td->work_dev), EVO_ERR_ARG, "convnet: work_dev must be 16-byte aligned");
     ConvShape cs;
     rc = conv_shape(pd, &cs);
     if (rc) return rc;
     rc = convnet_supported(cs);
     if (rc) return rc;
     rc = launch_convnet_f32(cs, static_cast<const float*>(params_dev), td->obs_dev, pop, td->B, nullptr,
-                            static_cast<const int32_t*>(td->target_dev), partial, n_part, s);
+                            static_cast<const int32_t*>(td->target_dev), partial, n_part,
+                            static_cast<unsigned char*>(td->work_dev) + partials_bytes(td, pd, pop), s);
     if (rc) return rc;
     return launch_finalize(partial, pop, n_part, -1.0f / static_cast<float>(td->B), fitness_dev, s);
   }

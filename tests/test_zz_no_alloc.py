@@ -64,7 +64,7 @@ def test_static_scratch_matches_rollout_on_calls_in_a_row(evo):
 
 
 def test_static_scratch_refuses_what_does_not_fit(evo):
-    P, pop = 1 << 20, 4096
+    P, pop = 1 << 20, 16384
     td = evo.make_task_desc(evo.EVO_TASK_SPHERE, P=P, target=torch.zeros(16, device="cuda"))
     assert evo.rollout_workspace_bytes(td, None, pop) > evo.rollout_static_scratch_bytes()
     fake = torch.zeros(16, device="cuda")
