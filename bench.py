@@ -37,7 +37,7 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2924945,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 57515892,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: the batch, as 5 KB of fp16 planes per
+    "cfg2": 57515892,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: the batch, as 4 KB of fp16 planes per
                            # image, is re-fetched per L2; 8 MB of it is scratch: four per-image lane constants)
     "cfg3": 19116032,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md

@@ -296,7 +296,7 @@ typedef struct {
 } task_desc;
 
 /* Bytes of device workspace `rollout` needs for this task / policy / pop (may be 0): partial sums of the
- * members' losses and, for the ConvNet, the shared batch converted once for all members (5 KB per image). */
+ * members' losses and, for the ConvNet, the shared batch converted once for all members (4 KB per image). */
 size_t rollout_workspace_bytes(const task_desc* td, const policy_desc* pd, int32_t pop);
 
 /* Evaluate every member: fitness_dev[pop] as defined above.  `steps` is the episode length

@@ -5,13 +5,13 @@
 //
 // conv3x3 -> ReLU -> maxpool2 -> conv3x3 -> ReLU -> maxpool2 -> dense, c1 = 8, c2 = 16.
 //
-// Each wavefront runs whole images end to end out of its private 9.7 KB slice of LDS, with no
+// Each wavefront runs whole images end to end out of its private 8.75 KB slice of LDS, with no
 // workgroup barrier in the loop: both convolutions as implicit GEMMs on the matrix cores, the dense layer
 // on the vector ALU against a workgroup-shared LDS copy of its weights, accumulated band by band from the
 // conv2 results while they are still in registers.  The next image is prefetched into
 // registers while the current one is computed.  Activations never leave the chip.  The conversion of the images into
 // the two fp16 planes conv1 reads is the same for every member: for roll-outs a small kernel does it once per batch
-// into the caller's workspace (5 KB per image, L2 resident, read by all members; 8 % of the ConvNet kernel's time
+// into the caller's workspace (4 KB per image, L2 resident, read by all members; 8 % of the ConvNet kernel's time
 // when every member's workgroups did it again), pop_forward, which has no workspace, converts in the kernel.
 //
 // Arithmetic.  On gfx950 a wave64 fp32 FMA issues every ~2.7 cycles (64 MACs) and
@@ -29,11 +29,12 @@
 // an infinite pixel, gets NaN logits (the maximum operations of ReLU and pooling would otherwise
 // swallow what fp32 arithmetic propagates); a NaN pixel is not detected.
 //
-// conv1 tiling (K = 9, one input channel).  The image sits in LDS as two planes of fp16 terms (written with
-// aligned 8-byte stores: a lane gets the pixel left of its four from the lane before it).  The 16
+// conv1 tiling (K = 9, one input channel).  The image sits in LDS as two planes of fp16 terms, the padded rows 2 k
+// and 2 k + 1 interleaved pixel by pixel (written with aligned 16-byte stores: a lane gets the column left of its
+// four from the lane before it), so that the eight values a lane contributes to a patch are 16 consecutive bytes.  The 16
 // columns of a matrix tile are 16 pooling windows (8 window columns x the two pooled rows of the pass); the contraction runs over the 4 x 4 pixel patch that holds
-// the 3 x 3 neighbourhoods of the window's four pixels (k = 4 r + c; the lane's eight values are two rows of
-// four consecutive pixels: four 4-byte LDS reads), once against the leading terms of the pixels (lane groups
+// the 3 x 3 neighbourhoods of the window's four pixels (the lane's eight values are four consecutive columns of a
+// row pair: one LDS instruction of two 8-byte reads), once against the leading terms of the pixels (lane groups
 // 0, 1) and once against their residual terms (lane groups 2, 3), which fills K = 32.  The 16 rows are
 // (8 output channels) x (the window's two pixel columns); one set of weight operands per pixel row of the
 // window (the stencil shifted inside the patch, zeros elsewhere).  With the residual terms stored as they are
@@ -77,10 +78,11 @@ constexpr float kFltMax = 3.402823466e+38f;
 
 constexpr int kC1 = 8, kC2 = 16;
 constexpr int kHMax = 28;
-constexpr int kPlanePitch = 80;                      // bytes of a padded image row of one split term (30 fp16 pixels); 20 words, so
-                                                     // that rows 0, 2, 4 of a patch column start 8 of the 32 banks apart
-constexpr int kPlaneBytes = 30 * kPlanePitch;        // 2400
-constexpr int kImgBytes = 2 * kPlaneBytes;           // the padded image as two fp16 terms
+// A split term of the padded image: padded rows 2 k and 2 k + 1 interleaved pixel by pixel (4 bytes per column),
+// so that the two rows x four columns of a conv1 patch operand are 16 consecutive bytes.
+constexpr int kPairPitch = 128;                      // bytes of a row pair: 30 columns x 2 rows x 2 bytes, 8 spare
+constexpr int kPlaneBytes = (kHMax / 2 + 1) * kPairPitch;  // 1920
+constexpr int kImgBytes = 2 * kPlaneBytes;           // the padded image as two fp16 terms (3840)
 constexpr int kBandW = kHMax / 2 + 2;                // padded conv1-output row (16 pixels)
 constexpr int kPixBytes = 2 * kC1;                   // 16: the 8 channels of a pixel as fp16
 constexpr int kBandRowPair = 2 * kBandW * kPixBytes;  // 512 bytes: rows 2a and 2a+1, interleaved pixel by pixel
@@ -92,7 +94,7 @@ constexpr int kRingRows = 10;
 constexpr int kBandTerm = (kRingRows / 2) * kBandRowPair;   // 2560 bytes: the ring of one split term
 constexpr int kBandBytes = 2 * kBandTerm;            // 5120 bytes
 constexpr int kBandFloats = kBandBytes / 4;          // 1280
-constexpr int kWaveFloats = kImgBytes / 4 + kBandFloats;  // 2480 floats = 9,920 bytes per wave
+constexpr int kWaveFloats = kImgBytes / 4 + kBandFloats;  // 2240 floats = 8,960 bytes per wave
 
 // Byte offset of pixel (row, col) inside one term of a band buffer.  The pixels of an even row and
 // of the odd row below it alternate (32 bytes per column), so that the sixteen 16-byte reads of
@@ -103,7 +105,7 @@ __device__ __forceinline__ constexpr int band_off(int row, int col) {
 constexpr int kConvWavesMax = 12;
 // The batch split once for all members (convnet_split_kernel): per image the two padded planes exactly as they sit
 // in LDS, then the largest pixel magnitude as a float.
-constexpr int kImgStride = 5120;
+constexpr int kImgStride = 4096;
 constexpr int kSplitWaves = 4;
 constexpr int kMaxCls = 16;
 constexpr int kMaxFeat = (kHMax / 4) * (kHMax / 4) * kC2;  // 784
@@ -171,12 +173,25 @@ __device__ __forceinline__ float row16_max_magnitude(float v) {
 __device__ __forceinline__ float pixel_scale(float px_bound) {
   return __int_as_float(__builtin_amdgcn_readfirstlane(min(__float_as_int(split_pow2_scale(px_bound)) >> 23, 183) << 23));
 }
-__device__ __forceinline__ float stage_pixels(const float4 (&pre)[4], char* planes, int lane, int row4, int n_vec) {
+// The lane's pieces of an image: task t = lane + 64 round (round 0, 1) is the row pair k = t / row4 (padded rows
+// 2 k and 2 k + 1, i.e. image rows 2 k - 1 and 2 k) and the float4 piece x4 = t % row4 of both rows; pre[2 round]
+// and pre[2 round + 1] hold them (zeros for the border rows and for tasks beyond the image).
+__device__ __forceinline__ void load_pixels(const float* __restrict__ image, int H, int lane, int row4, float4 (&pre)[4]) {
+  const int n_task = (H / 2 + 1) * row4;  // at most 105
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const int t = lane + 64 * round, k = t / row4, x4 = t - k * row4;
+    const float4* row_b = reinterpret_cast<const float4*>(image + static_cast<size_t>(2 * k) * H) + x4;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    pre[2 * round] = (t < n_task && k > 0) ? *(row_b - row4) : zero;
+    pre[2 * round + 1] = (t < n_task && 2 * k < H) ? *row_b : zero;
+  }
+}
+__device__ __forceinline__ float stage_pixels(const float4 (&pre)[4], char* planes, int lane, int row4, int n_task) {
   float px_max = 0.f;
 #pragma unroll
   for (int j = 0; j < 4; ++j)
-    if (lane + 64 * j < n_vec)
-      px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
+    px_max = fmaxf(fmaxf(fmaxf(px_max, fabsf(pre[j].x)), fabsf(pre[j].y)), fmaxf(fabsf(pre[j].z), fabsf(pre[j].w)));
   // (non-negative floats order like their bit patterns)
   px_max = row16_max_magnitude(px_max);
   const uint32_t px_bits = max(max(__builtin_amdgcn_readlane(__float_as_uint(px_max), 0),
@@ -185,29 +200,32 @@ __device__ __forceinline__ float stage_pixels(const float4 (&pre)[4], char* plan
                                    __builtin_amdgcn_readlane(__float_as_uint(px_max), 48)));
   const float px_bound = __uint_as_float(px_bits);
   const float s_px = pixel_scale(px_bound);
-  // Pixels 4 x4 .. 4 x4 + 3 of row y sit at padded columns 4 x4 + 1 ..: a lane stores the aligned eight bytes of
-  // columns 4 x4 .. 4 x4 + 3, whose first pixel is the last one of the piece to its left (the lane before it; for
-  // lane 0 the last lane of the previous round), and the last piece of a row adds the row's last pixel.
-  uint32_t last_lead = 0, last_resid = 0;  // lane 63's outer pair of the previous round
+  // Pixels 4 x4 .. 4 x4 + 3 of a row sit at padded columns 4 x4 + 1 ..: a task stores the aligned 16 bytes of
+  // columns 4 x4 .. 4 x4 + 3 of its row pair (a column = the two rows' pixels), whose first column is the last one
+  // of the piece to its left (the lane before it; for lane 0 the last lane of the previous round), and the last
+  // piece of a row pair adds the pair's last column.
+  uint32_t last_lead = 0, last_resid = 0;  // lane 63's last column of the previous round
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int i = lane + 64 * j;
-    const int y = i / row4, x4 = i - y * row4;
-    uint32_t lead_o, resid_o, lead_m, resid_m;
-    split2_pair_true(pre[j].x * s_px, pre[j].w * s_px, lead_o, resid_o);
-    split2_pair_true(pre[j].y * s_px, pre[j].z * s_px, lead_m, resid_m);
-    uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead_o, 0x138, 0xf, 0xf, false);    // wave_shr:1
-    uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid_o, 0x138, 0xf, 0xf, false);
-    last_lead = __builtin_amdgcn_readlane(lead_o, 63);
-    last_resid = __builtin_amdgcn_readlane(resid_o, 63);
-    if (x4 == 0) left_lead = 0, left_resid = 0;  // the border left of the row
-    if (i < n_vec) {
-      char* d = planes + (y + 1) * kPlanePitch + 8 * x4;
-      *reinterpret_cast<uint2*>(d) = make_uint2((left_lead >> 16) | (lead_o << 16), lead_m);
-      *reinterpret_cast<uint2*>(d + kPlaneBytes) = make_uint2((left_resid >> 16) | (resid_o << 16), resid_m);
+  for (int round = 0; round < 2; ++round) {
+    const int t = lane + 64 * round, k = t / row4, x4 = t - k * row4;
+    const float4 ra = pre[2 * round], rb = pre[2 * round + 1];
+    uint32_t lead[4], resid[4];  // columns x, y, z, w of the piece: (upper row, lower row) as a pair of fp16
+    split2_pair_true(ra.x * s_px, rb.x * s_px, lead[0], resid[0]);
+    split2_pair_true(ra.y * s_px, rb.y * s_px, lead[1], resid[1]);
+    split2_pair_true(ra.z * s_px, rb.z * s_px, lead[2], resid[2]);
+    split2_pair_true(ra.w * s_px, rb.w * s_px, lead[3], resid[3]);
+    uint32_t left_lead = __builtin_amdgcn_update_dpp(last_lead, lead[3], 0x138, 0xf, 0xf, false);    // wave_shr:1
+    uint32_t left_resid = __builtin_amdgcn_update_dpp(last_resid, resid[3], 0x138, 0xf, 0xf, false);
+    last_lead = __builtin_amdgcn_readlane(lead[3], 63);
+    last_resid = __builtin_amdgcn_readlane(resid[3], 63);
+    if (x4 == 0) left_lead = 0, left_resid = 0;  // the border left of the rows
+    if (t < n_task) {
+      char* d = planes + k * kPairPitch + 16 * x4;
+      *reinterpret_cast<uint4*>(d) = make_uint4(left_lead, lead[0], lead[1], lead[2]);
+      *reinterpret_cast<uint4*>(d + kPlaneBytes) = make_uint4(left_resid, resid[0], resid[1], resid[2]);
       if (x4 == row4 - 1) {
-        *reinterpret_cast<uint32_t*>(d + 8) = lead_o >> 16;
-        *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 8) = resid_o >> 16;
+        *reinterpret_cast<uint32_t*>(d + 16) = lead[3];
+        *reinterpret_cast<uint32_t*>(d + kPlaneBytes + 16) = resid[3];
       }
     }
   }
@@ -224,14 +242,11 @@ __global__ __launch_bounds__(64 * kSplitWaves) void convnet_split_kernel(const f
   char* planes = planes_s[wave];
   for (int i = lane; i < kImgBytes / 16; i += 64) reinterpret_cast<uint4*>(planes)[i] = make_uint4(0, 0, 0, 0);
   wave_sync();
-  const int row4 = H / 4, n_vec = H * row4;
+  const int row4 = H / 4, n_task = (H / 2 + 1) * row4;
   for (int im = blockIdx.x * kSplitWaves + wave; im < B; im += gridDim.x * kSplitWaves) {
     float4 pre[4];
-    const float4* src = reinterpret_cast<const float4*>(images + static_cast<size_t>(im) * H * H);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      pre[j] = lane + 64 * j < n_vec ? src[lane + 64 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
-    const float px_bound = stage_pixels(pre, planes, lane, row4, n_vec);
+    load_pixels(images + static_cast<size_t>(im) * H * H, H, lane, row4, pre);
+    const float px_bound = stage_pixels(pre, planes, lane, row4, n_task);
     wave_sync();
     unsigned char* dst = out + static_cast<size_t>(im) * kImgStride;
     for (int i = lane; i < kImgBytes / 16; i += 64)
@@ -354,7 +369,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
       float x1[8], x2[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int dy = 2 * rblk + (j >> 2) - t, dx = (j & 3) - sx;
+        const int dy = 2 * rblk + (j & 1) - t, dx = (j >> 1) - sx;  // element j: column j >> 1, row j & 1 of the patch rows
         float w = 0.f;
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) w = (3 * dy + dx == tap && dx >= 0 && dx <= 2 && dy >= 0 && dy <= 2) ? wt[tap] : w;
@@ -391,7 +406,7 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const int wx = 8 * m + (n >> 1), wxc = min(wx, H2 - 1), rs = n & 1;
-    p_off[m] = (q >> 1) * kPlaneBytes + (2 * rs + 2 * (q & 1)) * kPlanePitch + 4 * wxc;
+    p_off[m] = (q >> 1) * kPlaneBytes + (rs + (q & 1)) * kPairPitch + 8 * wxc;
     own_off[m] = band_off(1 + rs, wxc + 1) + (q & 1) * kBandTerm;  // for u = 0; two rows = one row pair further per u
     c1_store[m] = wx < H2 && q < 2;
   }
@@ -431,24 +446,20 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
 
   const int img_begin = blockIdx.x * a.imgs_per_chunk;
   const int img_end = min(a.B, img_begin + a.imgs_per_chunk);
-  const int row4 = H / 4, n_vec = H * row4;  // float4 pieces of one image (<= 196)
+  const int row4 = H / 4, n_task = (H / 2 + 1) * row4;  // float4 pieces of a row; (row pair, piece) tasks of an image
   float loss_sum = 0.f;
 
   // prefetch of the first image: lane takes pieces lane, lane + 64, ... (of its pixels, or of its split planes)
   float4 pre[4] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f),
                    make_float4(0.f, 0.f, 0.f, 0.f)};  // pieces beyond the image stay zero
-  uint4 pre_split[5] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0),
-                        make_uint4(0, 0, 0, 0)};
+  uint4 pre_split[4] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
   auto prefetch = [&](int image) {
     if (PRESPLIT) {
       const uint4* src = reinterpret_cast<const uint4*>(a.planes + static_cast<size_t>(image) * kImgStride);
 #pragma unroll
-      for (int j = 0; j < 5; ++j) pre_split[j] = src[lane + 64 * j];  // kImgStride = 5 x 64 x 16 bytes
+      for (int j = 0; j < 4; ++j) pre_split[j] = src[lane + 64 * j];  // kImgStride = 4 x 64 x 16 bytes
     } else {
-      const float4* src = reinterpret_cast<const float4*>(a.images + static_cast<size_t>(image) * H * H);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (lane + 64 * j < n_vec) pre[j] = src[lane + 64 * j];
+      load_pixels(a.images + static_cast<size_t>(image) * H * H, H, lane, row4, pre);
     }
   };
   int im = img_begin + wave;
@@ -460,13 +471,13 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     //      for all members); then prefetch the next image -------
     float px_bound;
     if (PRESPLIT) {
-      static_assert(kImgBytes == 4 * 1024 + 44 * 16, "four full rounds of 16 bytes a lane and 44 lanes of a fifth");
+      static_assert(kImgBytes == 3 * 1024 + 48 * 16 && kImgStride == 4096, "three full rounds of 16 bytes a lane and 48 lanes of a fourth");
 #pragma unroll
-      for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4*>(planes + 16 * (lane + 64 * j)) = pre_split[j];
-      if (lane < 44) *reinterpret_cast<uint4*>(planes + 16 * (lane + 256)) = pre_split[4];
-      px_bound = __uint_as_float(__builtin_amdgcn_readlane(pre_split[4].x, 44));  // the float behind the planes
+      for (int j = 0; j < 3; ++j) *reinterpret_cast<uint4*>(planes + 16 * (lane + 64 * j)) = pre_split[j];
+      if (lane < 48) *reinterpret_cast<uint4*>(planes + 16 * (lane + 192)) = pre_split[3];
+      px_bound = __uint_as_float(__builtin_amdgcn_readlane(pre_split[3].x, 48));  // the float behind the planes
     } else {
-      px_bound = stage_pixels(pre, planes, lane, row4, n_vec);
+      px_bound = stage_pixels(pre, planes, lane, row4, n_task);
     }
     // scales of this image (all wave-uniform): of its pixels from their largest magnitude, of its conv1 activations
     // from the bound on them
@@ -540,12 +551,12 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
           f16x8 patch[NM];
 #pragma unroll
           for (int m = 0; m < NM; ++m) {
-            // the lane's eight patch values: two rows of four consecutive fp16 pixels
-            typedef __attribute__((address_space(3))) const uint32_t lds_u32;
-            const lds_char* pp = lds_at(p_abs[m] + b0 * (4 * kPlanePitch), u * (4 * kPlanePitch));
-            const u32x4p pw = {*reinterpret_cast<lds_u32*>(pp), *reinterpret_cast<lds_u32*>(pp + 4),
-                               *reinterpret_cast<lds_u32*>(pp + kPlanePitch),
-                               *reinterpret_cast<lds_u32*>(pp + kPlanePitch + 4)};
+            // the lane's eight patch values: four consecutive columns of a row pair
+            typedef uint32_t u32x2p __attribute__((ext_vector_type(2)));
+            typedef __attribute__((address_space(3))) const u32x2p lds_u2;  // 8-byte aligned: one ds_read2_b64
+            const lds_char* pp = lds_at(p_abs[m] + b0 * (2 * kPairPitch), u * (2 * kPairPitch));
+            const u32x2p lo = *reinterpret_cast<lds_u2*>(pp), hi = *reinterpret_cast<lds_u2*>(pp + 8);
+            const u32x4p pw = {lo[0], lo[1], hi[0], hi[1]};
             patch[m] = __builtin_bit_cast(f16x8, pw);
           }
           floatx4 o0[NM], o1[NM];
