@@ -37,8 +37,8 @@ PEAK_ALU_F32_TF = 157.3        # fp32 vector (256 CU x 4 SIMD x 32 lanes x 2.4 G
 # read from inside the run, so `traffic` is what the profile of this same command measured, not this run.
 MEASURED_TRAFFIC_BYTES = {
     "cfg1": 2924945,       # profiles/mlp_f32_kernel_cfg1.md
-    "cfg2": 57515892,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: the batch, as 4 KB of fp16 planes per
-                           # image, is re-fetched per L2; 8 MB of it is scratch: four per-image lane constants)
+    "cfg2": 37831063,      # profiles/convnet_kernel_cfg2.md (algorithmic 12.5 MB: the batch, as 4 KB of fp16 planes per
+                           # image, is re-fetched per L2)
     "cfg3": 19116032,      # profiles/cartpole_kernel_cfg3.md
     "cfg4": 807197617,     # profiles/mlp_bf16_stream_kernel_cfg4.md
     "cfg5": 4305387571,    # profiles/ask_sphere_tell_kernels_cfg5.md (ask)
@@ -53,8 +53,8 @@ MEASURED_TRAFFIC_BYTES = {
 # What the rocprofv3 counters in profiles/ say bounds the dominant kernel.
 BOUND_DETAIL = {
     "cfg1": "launch latency: five launches of a few microseconds each (profiles/mlp_f32_kernel_cfg1.md)",
-    "cfg2": "both convolutions on the matrix cores: MFMA busy 46 %, VALU issue 61 % on the same SIMDs (16 % of the cycles overlap), LDS busy 67 %, "
-            "32 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
+    "cfg2": "both convolutions on the matrix cores: MFMA busy 47 %, VALU issue 63 % on the same SIMDs (16 % of the cycles overlap), LDS busy 64 %, "
+            "31 % of wave time waiting at three waves per SIMD (profiles/convnet_kernel_cfg2.md)",
     "cfg3": "vector-instruction issue along a 1000-step dependency chain: VALU busy 66 %, MFMA busy 21 %, 36 % of wave "
             "time waiting (profiles/cartpole_kernel_cfg3.md)",
     "cfg4": "HBM weight stream: 64 flop per weight byte (profiles/mlp_bf16_stream_kernel_cfg4.md)",
