@@ -282,9 +282,28 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
   const float* bd = Wd + n_feat * n_cls;   // [n_cls]
 
   // ---- once per workgroup: dense weights -> LDS (rows padded to NCS with zeros) ----------------
-  for (int i = threadIdx.x; i < n_feat * NCS; i += 64 * kConvWaves) {
-    const int f = i / NCS, c = i - f * NCS;
-    wd_s[i] = c < n_cls ? Wd[f * n_cls + c] : 0.f;
+  if (n_cls == NCS && (a.P & 1) == 0) {
+    // rows of exactly NCS classes: a plain copy, 8 bytes a thread and round, all loads of a thread in flight together
+    // (a member's parameter vector is 8-byte aligned when P is even, and Wd starts a multiple of 16 bytes into it);
+    // one load per round and iteration took 20 us per workgroup
+    constexpr int kRounds = (kMaxFeat * NCS / 2 + 64 * kConvWaves - 1) / (64 * kConvWaves);
+    const int n2 = n_feat * NCS / 2;
+    float2 v[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const int i = threadIdx.x + r * 64 * kConvWaves;
+      if (i < n2) v[r] = reinterpret_cast<const float2*>(Wd)[i];
+    }
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const int i = threadIdx.x + r * 64 * kConvWaves;
+      if (i < n2) reinterpret_cast<float2*>(wd_s)[i] = v[r];
+    }
+  } else {
+    for (int i = threadIdx.x; i < n_feat * NCS; i += 64 * kConvWaves) {
+      const int f = i / NCS, c = i - f * NCS;
+      wd_s[i] = c < n_cls ? Wd[f * n_cls + c] : 0.f;
+    }
   }
   // zero the padded buffers once: borders stay zero, interiors are overwritten per image
   for (int i = lane; i < kWaveFloats; i += 64) img[i] = 0.f;
@@ -729,14 +748,22 @@ int convnet_supported(const ConvShape& sh) {
   return EVO_OK;
 }
 
-// Workgroups per member: two per compute unit over the whole grid (one resident, one queued, so
-// that the per-workgroup staging of the weights is paid rarely), but no fewer than one image per wave.
+// Workgroups per member: the count that minimises (rounds of the grid over the chip's 256 compute units, one
+// workgroup each) x (a workgroup's set-up, measured at about 25 images' worth, + its images, in rounds of one image
+// per wave); no fewer than one image per wave.  cfg2 (256 members, 1024 images): one workgroup per member.
 int convnet_chunks(const ConvShape&, int pop, int B) {
-  int chunks = (512 + pop - 1) / pop;
-  const int max_chunks = (B + kConvWavesMax - 1) / kConvWavesMax;
-  if (chunks > max_chunks) chunks = max_chunks;
-  if (chunks < 1) chunks = 1;
-  return chunks;
+  constexpr int kCUs = 256, kSetupImages = 25;
+  const int max_chunks = max(1, min((B + kConvWavesMax - 1) / kConvWavesMax, 64));
+  int best = 1;
+  long best_cost = -1;
+  for (int c = 1; c <= max_chunks; ++c) {
+    const long rounds = (static_cast<long>(pop) * c + kCUs - 1) / kCUs;
+    const int images = (B + c - 1) / c;
+    const long per_group = kSetupImages + kConvWavesMax * ((images + kConvWavesMax - 1) / kConvWavesMax);
+    const long cost = rounds * per_group;
+    if (best_cost < 0 || cost < best_cost) best = c, best_cost = cost;
+  }
+  return best;
 }
 
 template <int NCS, int WAVES, bool PRESPLIT>
