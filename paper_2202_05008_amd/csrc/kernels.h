@@ -62,8 +62,11 @@ int pgpe_generation_small(pgpe_state* st, uint64_t seed, int32_t pop, const MlpS
 int convnet_supported(const ConvShape& sh);
 int convnet_chunks(const ConvShape& sh, int pop, int B);
 size_t convnet_planes_bytes(int B);
+// fitness, scale: with one workgroup per member (chunks == 1) the kernel writes fitness[member] = scale * loss sum itself
+// and no partial sums (the caller then skips launch_finalize); ignored otherwise, may be null.
 int launch_convnet_f32(const ConvShape& sh, const float* params, const float* images, int pop, int B, float* out,
-                       const int32_t* labels, float* partial, int chunks, void* planes_work, hipStream_t s);
+                       const int32_t* labels, float* partial, int chunks, void* planes_work, float* fitness, float scale,
+                       hipStream_t s);
 
 // fitness[m] = scale * sum_j partial[m][j], j in increasing order.
 int launch_finalize(const float* partial, int pop, int n, float scale, float* fitness, hipStream_t s);

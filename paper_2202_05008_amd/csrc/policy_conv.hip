@@ -117,6 +117,8 @@ struct ConvArgs {
   const unsigned char* planes;  // the batch already split into fp16 terms (kImgStride bytes per image), or null
   float* out;
   float* partial;
+  float* fitness;  // with one workgroup per member: fitness[member] = scale * (the member's loss sum), no partial sums
+  float scale;
   int P, H, n_cls, B, chunks, imgs_per_chunk;
 };
 
@@ -735,7 +737,8 @@ __global__ __launch_bounds__(64 * kConvWaves) void convnet_kernel(ConvArgs a) {
     if (threadIdx.x == 0) {
       float t = 0.f;
       for (int w = 0; w < kConvWaves; ++w) t += wave_loss[w];
-      a.partial[static_cast<size_t>(member) * a.chunks + blockIdx.x] = t;
+      if (a.fitness) a.fitness[member] = a.scale * t;
+      else a.partial[static_cast<size_t>(member) * a.chunks + blockIdx.x] = t;
     }
   }
 }
@@ -782,7 +785,8 @@ static int launch_conv(const ConvArgs& a, int pop, hipStream_t s) {
 size_t convnet_planes_bytes(int B) { return static_cast<size_t>(B) * kImgStride; }
 
 int launch_convnet_f32(const ConvShape& sh, const float* params, const float* images, int pop, int B, float* out,
-                       const int32_t* labels, float* partial, int chunks, void* planes_work, hipStream_t s) {
+                       const int32_t* labels, float* partial, int chunks, void* planes_work, float* fitness, float scale,
+                       hipStream_t s) {
   ConvArgs a;
   a.params = params, a.images = images, a.labels = labels, a.out = out, a.partial = partial;
   a.planes = static_cast<const unsigned char*>(planes_work);
@@ -790,6 +794,7 @@ int launch_convnet_f32(const ConvShape& sh, const float* params, const float* im
   if (chunks <= 0) chunks = convnet_chunks(sh, pop, B);
   a.chunks = chunks;
   a.imgs_per_chunk = (B + chunks - 1) / chunks;
+  a.fitness = chunks == 1 ? fitness : nullptr, a.scale = scale;
   if (planes_work) {
     // the split of the batch into fp16 terms is the same for every member: done once, ahead of the members' kernel
     const int blocks = min((B + kSplitWaves - 1) / kSplitWaves, 1024);

@@ -109,7 +109,7 @@ extern "C" int pop_forward(const policy_desc* pd, const void* params_dev, const 
   rc = convnet_supported(cs);
   if (rc) return rc;
   return launch_convnet_f32(cs, static_cast<const float*>(params_dev), obs_dev, pop, B, out_dev, nullptr, nullptr, 0,
-                            nullptr, s);
+                            nullptr, nullptr, 0.f, s);
 }
 
 namespace {
@@ -282,8 +282,9 @@ static int rollout_impl(const task_desc* td, const policy_desc* pd, const void* 
     if (rc) return rc;
     rc = launch_convnet_f32(cs, static_cast<const float*>(params_dev), td->obs_dev, pop, td->B, nullptr,
                             static_cast<const int32_t*>(td->target_dev), partial, n_part,
-                            static_cast<unsigned char*>(td->work_dev) + partials_bytes(td, pd, pop), s);
-    if (rc) return rc;
+                            static_cast<unsigned char*>(td->work_dev) + partials_bytes(td, pd, pop), fitness_dev,
+                            -1.0f / static_cast<float>(td->B), s);
+    if (rc || n_part == 1) return rc;  // one workgroup per member: the kernel has written the fitness itself
     return launch_finalize(partial, pop, n_part, -1.0f / static_cast<float>(td->B), fitness_dev, s);
   }
   MlpShape sh;
