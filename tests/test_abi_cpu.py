@@ -76,6 +76,11 @@ def test_policy_and_task_descriptions():
     assert api.rollout_workspace_bytes(td, pd1, 64) >= 64 * 8 * 4
     assert api.rollout_workspace_bytes(api.make_task_desc(api.EVO_TASK_SPHERE, P=8), None, 4) >= 16
     assert api.rollout_workspace_bytes(api.make_task_desc(api.EVO_TASK_CARTPOLE), pd1, 4) == 0
+    # the ConvNet's workspace also holds the shared batch converted once for all members (4 KB per image)
+    pdc = api.make_policy_desc(api.EVO_POLICY_CONVNET, (28, 8, 16, 10))
+    tdc = api.make_task_desc(api.EVO_TASK_CLASSIFY, B=1024)
+    need = api.rollout_workspace_bytes(tdc, pdc, 256)
+    assert need >= 1024 * 4096 + 256 * 4 and need % 256 == 0 and need <= api.rollout_static_scratch_bytes()
 
 
 def test_missing_library_fails_loudly(monkeypatch):
